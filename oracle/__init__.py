@@ -1,0 +1,147 @@
+"""ctypes front end of the CPU oracle (oracle/pvo.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests, by the smoke check and by the
+benchmark's cpu_baseline leg.  The product package never imports this module
+and this module never imports the product package.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from pathlib import Path
+
+import numpy as np
+
+_HERE = Path(__file__).resolve().parent
+_SRC = _HERE / "pvo.c"
+_LIB = _HERE / "libpvo.so"
+
+_lib = None
+
+
+def build(force: bool = False) -> Path:
+    """Compile pvo.c with gcc (no contraction, OpenMP over groups)."""
+    if force or not _LIB.exists() or _LIB.stat().st_mtime < _SRC.stat().st_mtime:
+        tmp = _LIB.with_suffix(f".tmp{os.getpid()}.so")
+        cmd = ["gcc", "-O2", "-std=c11", "-ffp-contract=off", "-fopenmp", "-fPIC",
+               "-shared", "-Wall", "-Wextra", "-o", str(tmp), str(_SRC), "-lm"]
+        subprocess.run(cmd, check=True)
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build()
+        lib = ctypes.CDLL(str(_LIB))
+        i64, i32, f32 = ctypes.c_int64, ctypes.c_int, ctypes.c_float
+        p = ctypes.c_void_p
+        lib.pvo_encode_targets.argtypes = [i64, i64, p, p, f32, p]
+        lib.pvo_select_topk_groups.argtypes = [i64, i64, i32, p, p, i64, p, p]
+        lib.pvo_reencode_groups.argtypes = [i64, i64, i32, i32, i32, p, p, p, p, i64, i32, i32,
+                                            p, p, p, p, p]
+        lib.pvo_group_objective.argtypes = [i64, i64, i32, i32, i32, p, p, p, p, i64, p, p]
+        lib.pvo_dequantize.argtypes = [i64, i64, i32, i32, i32, p, p, p, p]
+        for f in (lib.pvo_encode_targets, lib.pvo_select_topk_groups, lib.pvo_reencode_groups,
+                  lib.pvo_group_objective, lib.pvo_dequantize, lib.pvo_num_threads):
+            f.restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def _ptr(a):
+    return None if a is None else a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _f32(a):
+    a = np.ascontiguousarray(a, dtype=np.float32)
+    return a
+
+
+def num_threads() -> int:
+    return int(_load().pvo_num_threads())
+
+
+def encode_targets(W, G, alpha: float) -> np.ndarray:
+    W, G = _f32(W), _f32(G)
+    assert W.shape == G.shape and W.ndim == 2
+    T = np.empty_like(W)
+    rc = _load().pvo_encode_targets(W.shape[0], W.shape[1], _ptr(W), _ptr(G), float(alpha), _ptr(T))
+    if rc:
+        raise ValueError("pvo_encode_targets failed")
+    return T
+
+
+def select_topk_groups(T, W, group_size: int, k: int, return_scores: bool = False):
+    T, W = _f32(T), _f32(W)
+    out_f, in_f = T.shape
+    N = out_f * (in_f // group_size)
+    idx = np.empty(max(k, 0), dtype=np.int32)
+    scores = np.empty(N, dtype=np.float32) if return_scores else None
+    rc = _load().pvo_select_topk_groups(out_f, in_f, group_size, _ptr(T), _ptr(W), k, _ptr(idx),
+                                        _ptr(scores))
+    if rc:
+        raise ValueError("pvo_select_topk_groups failed")
+    return (idx, scores) if return_scores else idx
+
+
+def reencode_groups(T, codebooks, scales, group_idx, codes, beam_width: int = 1,
+                    use_beam: bool = False):
+    """Returns (new_codes, info) and leaves `codes` untouched."""
+    T = _f32(T)
+    cb = _f32(codebooks)
+    sc = _f32(scales)
+    M, csize, g = cb.shape
+    B = int(csize).bit_length() - 1
+    assert (1 << B) == csize
+    out_f, in_f = T.shape
+    idx = np.ascontiguousarray(group_idx, dtype=np.int32)
+    k = idx.shape[0]
+    new = np.ascontiguousarray(codes, dtype=np.uint16).copy()
+    assert new.shape == (out_f, in_f // g, M), new.shape
+    changed = ctypes.c_int64(0)
+    near = np.zeros(k, dtype=np.uint8)
+    obj_new = np.zeros(k, dtype=np.float64)
+    obj_prev = np.zeros(k, dtype=np.float64)
+    rc = _load().pvo_reencode_groups(out_f, in_f, g, M, B, _ptr(T), _ptr(cb), _ptr(sc), _ptr(idx),
+                                     k, int(beam_width), int(bool(use_beam)), _ptr(new),
+                                     ctypes.addressof(changed), _ptr(near), _ptr(obj_new),
+                                     _ptr(obj_prev))
+    if rc:
+        raise ValueError("pvo_reencode_groups failed")
+    return new, {"num_changed": int(changed.value), "near_tie": near.astype(bool),
+                 "obj_new": obj_new, "obj_prev": obj_prev}
+
+
+def group_objective(T, codebooks, scales, group_idx, tuples) -> np.ndarray:
+    T = _f32(T)
+    cb = _f32(codebooks)
+    sc = _f32(scales)
+    M, csize, g = cb.shape
+    B = int(csize).bit_length() - 1
+    out_f, in_f = T.shape
+    idx = np.ascontiguousarray(group_idx, dtype=np.int32)
+    tup = np.ascontiguousarray(tuples, dtype=np.uint16).reshape(idx.shape[0], M)
+    obj = np.empty(idx.shape[0], dtype=np.float64)
+    rc = _load().pvo_group_objective(out_f, in_f, g, M, B, _ptr(T), _ptr(cb), _ptr(sc), _ptr(idx),
+                                     idx.shape[0], _ptr(tup), _ptr(obj))
+    if rc:
+        raise ValueError("pvo_group_objective failed")
+    return obj
+
+
+def dequantize(codes, codebooks, scales) -> np.ndarray:
+    cb = _f32(codebooks)
+    sc = _f32(scales)
+    M, csize, g = cb.shape
+    B = int(csize).bit_length() - 1
+    codes = np.ascontiguousarray(codes, dtype=np.uint16)
+    out_f, gpr, M2 = codes.shape
+    assert M2 == M
+    W = np.empty((out_f, gpr * g), dtype=np.float32)
+    rc = _load().pvo_dequantize(out_f, gpr * g, g, M, B, _ptr(codes), _ptr(cb), _ptr(sc), _ptr(W))
+    if rc:
+        raise ValueError("pvo_dequantize failed")
+    return W

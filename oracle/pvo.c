@@ -1,0 +1,358 @@
+/*
+ * CPU oracle for the V-step re-encoding path of PV-Tuning (arXiv 2405.14852).
+ *
+ * TEST INFRASTRUCTURE ONLY.  This file is the plain, slow, obviously-correct
+ * statement of what the GPU path must compute.  It shares no code with the
+ * HIP library and must never be called from the product path: only tests,
+ * the smoke check and the benchmark's cpu_baseline leg may load it.
+ *
+ * What follows the paper exactly, and what is a stated reading of it:
+ *   pvo_encode_targets      Eq. 7 (linearised subspace V step): the target is
+ *                           y - (1/L) * grad, with alpha = 1/L; Alg. 3 V step.
+ *   pvo_select_topk_groups  Alg. 2 "arg top tau" + Sec. 3.4: largest update
+ *                           norm, greedily per weight matrix.  Reading: the
+ *                           unit is a weight group (one code covers it).
+ *   pvo_reencode_groups     M = 1: the argmin of Eq. 7 restricted to one group,
+ *                           i.e. "try every code, keep the minimiser" (App. K,
+ *                           VQ) -- a plain definition (pinned by brute force,
+ *                           the App. P worked example, nearest-neighbour
+ *                           library routines, Lemma 3.1).
+ *                           M >= 2: beam search over the codebooks (Sec. 4.2,
+ *                           App. K "beam size 8", App. D local search extended
+ *                           to beam search) -- a heuristic; the paper gives no
+ *                           listing, so the reading is: seed the beam with the
+ *                           current codes, visit codebooks in index order once,
+ *                           score every replacement with the full objective,
+ *                           keep the best `beam_width`.  Pinned only by: equals
+ *                           brute force when the beam is wide enough, never
+ *                           worse than the previous code (Lemma 3.2), reduces
+ *                           to the M = 1 definition, beam 1 = one pass of greedy
+ *                           single-index descent (App. D).  Beyond those bounds
+ *                           the beam result is PARITY UNPINNED.
+ *   pvo_dequantize          Alg. 3 line 1: W = scale_row * sum_m codeword_m.
+ *
+ * Arithmetic: objectives in IEEE double on the fp32 inputs, evaluated in index
+ * order without contraction (compile with -ffp-contract=off).  The selection
+ * score and the dequantised weights are fixed fp32 chains so that they are
+ * reproducible bit for bit.
+ */
+#include <math.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define PVO_OK 0
+#define PVO_ERR 1
+
+#define PVO_NEAR_TIE_REL 1e-6
+
+/* ------------------------------------------------------------------ targets */
+
+/* T = W - alpha * G, one rounding per element (Eq. 7 with 1/L_S = alpha). */
+int pvo_encode_targets(int64_t out_features, int64_t in_features, const float *W,
+                       const float *G, float alpha, float *T)
+{
+    if (!W || !G || !T || out_features < 0 || in_features < 0) return PVO_ERR;
+    int64_t n = out_features * in_features;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n; ++i) T[i] = fmaf(-alpha, G[i], W[i]);
+    return PVO_OK;
+}
+
+/* ---------------------------------------------------------------- selection */
+
+/* Squared norm of one group's update, as an fp32 chain in index order. */
+static float group_score(const float *t, const float *w, int g)
+{
+    float s = 0.0f;
+    for (int i = 0; i < g; ++i) {
+        float d = t[i] - w[i];
+        s = fmaf(d, d, s);
+    }
+    return s;
+}
+
+typedef struct { float score; int32_t id; } scored_t;
+
+/* larger score first; equal scores: lower id first */
+static int cmp_scored(const void *a, const void *b)
+{
+    const scored_t *x = (const scored_t *)a, *y = (const scored_t *)b;
+    if (x->score > y->score) return -1;
+    if (x->score < y->score) return 1;
+    return (x->id > y->id) - (x->id < y->id);
+}
+
+static int cmp_i32(const void *a, const void *b)
+{
+    int32_t x = *(const int32_t *)a, y = *(const int32_t *)b;
+    return (x > y) - (x < y);
+}
+
+/* The k groups with the largest update norm (Alg. 2 line 5, per matrix as in
+ * Sec. 3.4), returned as ascending flat group ids.  Full sort, no shortcuts. */
+int pvo_select_topk_groups(int64_t out_features, int64_t in_features, int g,
+                           const float *T, const float *W, int64_t k,
+                           int32_t *out_idx, float *out_scores /* [N] or NULL */)
+{
+    if (!T || !W || g < 1 || in_features % g) return PVO_ERR;
+    int64_t N = out_features * (in_features / g);
+    if (k < 0 || k > N || N >= INT32_MAX) return PVO_ERR;
+    if (k > 0 && !out_idx) return PVO_ERR;
+    scored_t *all = (scored_t *)malloc(sizeof(scored_t) * (size_t)(N > 0 ? N : 1));
+    if (!all) return PVO_ERR;
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n) {
+        all[n].score = group_score(T + n * g, W + n * g, g);
+        all[n].id = (int32_t)n;
+        if (out_scores) out_scores[n] = all[n].score;
+    }
+    qsort(all, (size_t)N, sizeof(scored_t), cmp_scored);
+    for (int64_t i = 0; i < k; ++i) out_idx[i] = all[i].id;
+    qsort(out_idx, (size_t)k, sizeof(int32_t), cmp_i32);
+    free(all);
+    return PVO_OK;
+}
+
+/* ---------------------------------------------------------------- re-encode */
+
+/* || s * sum_m C_m[b_m] - t ||^2 in double; codewords summed over m ascending. */
+static double tuple_objective(const float *codebooks, int M, int64_t csize, int g,
+                              const uint16_t *b, float s, const float *t)
+{
+    double obj = 0.0;
+    for (int i = 0; i < g; ++i) {
+        double acc = (double)codebooks[((int64_t)0 * csize + b[0]) * g + i];
+        for (int m = 1; m < M; ++m)
+            acc = acc + (double)codebooks[((int64_t)m * csize + b[m]) * g + i];
+        double r = (double)s * acc - (double)t[i];
+        obj = obj + r * r;
+    }
+    return obj;
+}
+
+static int near_tie(double lo, double hi)
+{
+    /* lo <= hi are the two objectives being separated */
+    return (hi - lo) < PVO_NEAR_TIE_REL * hi || hi == lo;
+}
+
+/* M = 1: exact nearest codeword (argmin of Eq. 7 over one group's code).
+ * Ties: the previous code if it is a minimiser, else the lowest index. */
+static void reencode_one_m1(const float *codebook, int64_t csize, int g, float s,
+                            const float *t, uint16_t *code, int *flag_near,
+                            double *obj_new, double *obj_prev)
+{
+    uint16_t prev = *code;
+    double best = INFINITY, second = INFINITY;
+    int64_t best_c = -1;
+    for (int64_t c = 0; c < csize; ++c) {
+        uint16_t cc = (uint16_t)c;
+        double o = tuple_objective(codebook, 1, csize, g, &cc, s, t);
+        if (o < best) { second = best; best = o; best_c = c; }
+        else if (o < second) second = o;
+    }
+    double o_prev = tuple_objective(codebook, 1, csize, g, &prev, s, t);
+    if (o_prev == best) best_c = prev;      /* previous code wins exact ties */
+    if (!(best_c >= 0)) best_c = prev;      /* every objective is NaN: keep   */
+    *code = (uint16_t)best_c;
+    if (flag_near) *flag_near = (csize > 1) ? near_tie(best, second) : 0;
+    if (obj_new) *obj_new = best;
+    if (obj_prev) *obj_prev = o_prev;
+}
+
+#define PVO_MAX_M 8
+
+typedef struct { double obj; uint16_t b[PVO_MAX_M]; } beam_t;
+
+static int g_cmp_M; /* qsort has no context argument; set per thread below */
+#pragma omp threadprivate(g_cmp_M)
+
+/* objective ascending; equal objectives: tuples in lexicographic order */
+static int cmp_beam(const void *a, const void *b)
+{
+    const beam_t *x = (const beam_t *)a, *y = (const beam_t *)b;
+    if (x->obj < y->obj) return -1;
+    if (x->obj > y->obj) return 1;
+    for (int m = 0; m < g_cmp_M; ++m) {
+        if (x->b[m] < y->b[m]) return -1;
+        if (x->b[m] > y->b[m]) return 1;
+    }
+    return 0;
+}
+
+/* M >= 1: beam search seeded with the current tuple, one sweep over the
+ * codebooks in index order.  At codebook m every beam entry spawns 2^B
+ * candidates (its m-th code replaced by each codeword, the others held); all
+ * candidates are ranked by the full objective and the best beam_width kept.
+ * The winner replaces the previous tuple only if it is strictly better. */
+static void reencode_one_beam(const float *codebooks, int M, int64_t csize, int g,
+                              float s, const float *t, int beam_width,
+                              uint16_t *code, beam_t *cand, int *flag_near,
+                              double *obj_new, double *obj_prev)
+{
+    beam_t *cur = cand;                            /* first beam_width slots  */
+    beam_t *pool = cand + beam_width;              /* beam_width * csize slots */
+    int ncur = 1, near = 0;
+    memset(&cur[0], 0, sizeof(beam_t));
+    for (int m = 0; m < M; ++m) cur[0].b[m] = code[m];
+    double o_prev = tuple_objective(codebooks, M, csize, g, cur[0].b, s, t);
+    cur[0].obj = o_prev;
+    g_cmp_M = M;
+    for (int m = 0; m < M; ++m) {
+        int64_t np = 0;
+        for (int e = 0; e < ncur; ++e)
+            for (int64_t c = 0; c < csize; ++c) {
+                beam_t *q = &pool[np++];
+                *q = cur[e];
+                q->b[m] = (uint16_t)c;
+                q->obj = tuple_objective(codebooks, M, csize, g, q->b, s, t);
+            }
+        qsort(pool, (size_t)np, sizeof(beam_t), cmp_beam);
+        int keep = (int)(np < beam_width ? np : beam_width);
+        if (np > keep && near_tie(pool[keep - 1].obj, pool[keep].obj)) near = 1;
+        memcpy(cur, pool, sizeof(beam_t) * (size_t)keep);
+        ncur = keep;
+        if (m == M - 1 && np > 1 && near_tie(pool[0].obj, pool[1].obj)) near = 1;
+    }
+    /* the keep-or-replace decision against the previous tuple is a boundary too */
+    {
+        int same = 1;
+        for (int m = 0; m < M; ++m) same &= (cur[0].b[m] == code[m]);
+        if (!same && near_tie(cur[0].obj < o_prev ? cur[0].obj : o_prev,
+                              cur[0].obj < o_prev ? o_prev : cur[0].obj)) near = 1;
+    }
+    if (cur[0].obj < o_prev)
+        for (int m = 0; m < M; ++m) code[m] = cur[0].b[m];
+    if (flag_near) *flag_near = near;
+    if (obj_new) *obj_new = (cur[0].obj < o_prev) ? cur[0].obj : o_prev;
+    if (obj_prev) *obj_prev = o_prev;
+}
+
+/* Re-assign the codes of the listed groups (ascending flat ids); every other
+ * code is left untouched (Eq. 7: entries outside the subspace keep y's value).
+ * use_beam = 0 forces the M = 1 definition; use_beam = 1 runs the beam routine
+ * for any M (used to pin that it reduces to the definition at M = 1).
+ * Optional per-selected-group outputs: near-tie flag, new / previous objective. */
+int pvo_reencode_groups(int64_t out_features, int64_t in_features, int g, int M, int B,
+                        const float *T, const float *codebooks, const float *scales,
+                        const int32_t *group_idx, int64_t k, int beam_width, int use_beam,
+                        uint16_t *codes, int64_t *num_changed, uint8_t *near_tie_flags,
+                        double *obj_new, double *obj_prev)
+{
+    if (!T || !codebooks || !scales || !codes) return PVO_ERR;
+    if (g < 1 || in_features % g || M < 1 || M > PVO_MAX_M || B < 1 || B > 16) return PVO_ERR;
+    if (beam_width < 1 || k < 0) return PVO_ERR;
+    if (k > 0 && !group_idx) return PVO_ERR;
+    int64_t gpr = in_features / g, N = out_features * gpr, csize = (int64_t)1 << B;
+    for (int64_t j = 0; j < k; ++j)
+        if (group_idx[j] < 0 || group_idx[j] >= N) return PVO_ERR;
+    int beam_path = use_beam || M > 1;
+    int64_t changed = 0;
+    int failed = 0;
+#pragma omp parallel reduction(+ : changed)
+    {
+        beam_t *cand = NULL;
+        if (beam_path) {
+            cand = (beam_t *)malloc(sizeof(beam_t) * (size_t)(beam_width + beam_width * csize));
+            if (!cand) {
+#pragma omp atomic write
+                failed = 1;
+            }
+        }
+#pragma omp for schedule(dynamic, 16)
+        for (int64_t j = 0; j < k; ++j) {
+            if (beam_path && !cand) continue;
+            int64_t n = group_idx[j];
+            int64_t o = n / gpr;
+            const float *t = T + n * g;
+            uint16_t *code = codes + n * M;
+            uint16_t before[PVO_MAX_M];
+            for (int m = 0; m < M; ++m) before[m] = code[m];
+            int flag = 0;
+            double on = 0.0, op = 0.0;
+            if (beam_path)
+                reencode_one_beam(codebooks, M, csize, g, scales[o], t, beam_width, code,
+                                  cand, &flag, &on, &op);
+            else
+                reencode_one_m1(codebooks, csize, g, scales[o], t, code, &flag, &on, &op);
+            int diff = 0;
+            for (int m = 0; m < M; ++m) diff |= (before[m] != code[m]);
+            changed += diff;
+            if (near_tie_flags) near_tie_flags[j] = (uint8_t)flag;
+            if (obj_new) obj_new[j] = on;
+            if (obj_prev) obj_prev[j] = op;
+        }
+        free(cand);
+    }
+    if (failed) return PVO_ERR;
+    if (num_changed) *num_changed = changed;
+    return PVO_OK;
+}
+
+/* Objective of arbitrary code tuples for the listed groups, in the oracle's
+ * arithmetic (used to judge a differing choice on a near-tie group). */
+int pvo_group_objective(int64_t out_features, int64_t in_features, int g, int M, int B,
+                        const float *T, const float *codebooks, const float *scales,
+                        const int32_t *group_idx, int64_t k,
+                        const uint16_t *tuples /* [k, M] */, double *obj /* [k] */)
+{
+    if (!T || !codebooks || !scales || !tuples || !obj || g < 1 || in_features % g) return PVO_ERR;
+    if (M < 1 || M > PVO_MAX_M || B < 1 || B > 16) return PVO_ERR;
+    int64_t gpr = in_features / g, csize = (int64_t)1 << B;
+    (void)out_features;
+#pragma omp parallel for schedule(static)
+    for (int64_t j = 0; j < k; ++j) {
+        int64_t n = group_idx[j];
+        obj[j] = tuple_objective(codebooks, M, csize, g, tuples + j * M, scales[n / gpr],
+                                 T + n * g);
+    }
+    return PVO_OK;
+}
+
+/* --------------------------------------------------------------- dequantize */
+
+/* W[o, j*g + i] = scales[o] * (C_0[b_0, i] + C_1[b_1, i] + ...), fp32 adds in
+ * codebook order then one fp32 multiply (Alg. 3 line 1). */
+int pvo_dequantize(int64_t out_features, int64_t in_features, int g, int M, int B,
+                   const uint16_t *codes, const float *codebooks, const float *scales,
+                   float *W_out)
+{
+    if (!codes || !codebooks || !scales || !W_out || g < 1 || in_features % g) return PVO_ERR;
+    if (M < 1 || B < 1 || B > 16) return PVO_ERR;
+    int64_t gpr = in_features / g, N = out_features * gpr, csize = (int64_t)1 << B;
+    int bad = 0;
+#pragma omp parallel for schedule(static)
+    for (int64_t n = 0; n < N; ++n) {
+        float s = scales[n / gpr];
+        for (int m = 0; m < M; ++m)
+            if (codes[n * M + m] >= csize) {
+#pragma omp atomic write
+                bad = 1;
+            }
+        if (bad) continue;
+        for (int i = 0; i < g; ++i) {
+            float acc = codebooks[((int64_t)0 * csize + codes[n * M]) * g + i];
+            for (int m = 1; m < M; ++m)
+                acc = acc + codebooks[((int64_t)m * csize + codes[n * M + m]) * g + i];
+            W_out[n * g + i] = s * acc;
+        }
+    }
+    return bad ? PVO_ERR : PVO_OK;
+}
+
+int pvo_num_threads(void)
+{
+    int n = 1;
+#ifdef _OPENMP
+#pragma omp parallel
+    {
+#pragma omp master
+        n = omp_get_num_threads();
+    }
+#endif
+    return n;
+}

@@ -1,0 +1,446 @@
+"""Pins for the CPU oracle: every routine is checked against something other
+than itself -- the paper's worked example, closed forms in exact rational
+arithmetic, brute force over all code tuples, library nearest-neighbour
+routines, and the invariants the paper proves.  None of these needs a GPU.
+"""
+from fractions import Fraction
+from itertools import product
+from pathlib import Path
+
+import numpy as np
+import pytest
+from scipy.spatial.distance import cdist
+
+import oracle
+import workloads
+
+GOLDEN = Path(__file__).resolve().parent / "golden"
+
+
+# ----------------------------------------------------------------- helpers
+
+def f32_round(fr: Fraction) -> np.float32:
+    """Correctly rounded (nearest, ties to even) fp32 value of a rational."""
+    if fr == 0:
+        return np.float32(0.0)
+    c = np.float32(float(fr))          # at most one ulp off after double rounding
+    cands = {c, np.nextafter(c, np.float32(np.inf)), np.nextafter(c, np.float32(-np.inf))}
+    best = None
+    for v in cands:
+        if not np.isfinite(v):
+            continue
+        err = abs(Fraction(float(v)) - fr)
+        even = (np.array(v, dtype=np.float32).view(np.uint32) & 1) == 0
+        key = (err, 0 if even else 1)
+        if best is None or key < best[0]:
+            best = (key, v)
+    return best[1]
+
+
+def fr(x) -> Fraction:
+    return Fraction(float(x))
+
+
+def exact_objective(cbs, tup, s, t) -> Fraction:
+    """|| s * sum_m C_m[b_m] - t ||^2 in exact rational arithmetic."""
+    tot = Fraction(0)
+    for i in range(len(t)):
+        acc = sum(fr(cbs[m][tup[m]][i]) for m in range(len(tup)))
+        r = fr(s) * acc - fr(t[i])
+        tot += r * r
+    return tot
+
+
+def tiny_problem(seed, out_f, in_f, g, M, B, scales="uniform"):
+    wl = workloads.make(out_f, in_f, g, M, B, sigma_g=5e-3, scales=scales, seed=seed,
+                        tau=1.0, beam_width=1)
+    T = oracle.encode_targets(wl.W, wl.G, wl.alpha)
+    return wl, T
+
+
+# ------------------------------------------------------------- O1: targets
+
+def test_targets_exact_single_rounding():
+    rng = np.random.default_rng(1)
+    W = rng.standard_normal((7, 24)).astype(np.float32) * np.float32(0.02)
+    G = rng.standard_normal((7, 24)).astype(np.float32) * np.float32(1e-3)
+    for alpha in (1.0, 0.3, 3e-3, -0.75):
+        T = oracle.encode_targets(W, G, alpha)
+        a = np.float32(alpha)
+        for w, g_, t in zip(W.ravel(), G.ravel(), T.ravel()):
+            assert t == f32_round(fr(w) - fr(a) * fr(g_))
+
+
+def test_targets_special_cases():
+    rng = np.random.default_rng(2)
+    W = rng.standard_normal((16, 64)).astype(np.float32)
+    G = rng.standard_normal((16, 64)).astype(np.float32)
+    assert np.array_equal(oracle.encode_targets(W, G, 0.0).view(np.uint32), W.view(np.uint32))
+    assert np.array_equal(oracle.encode_targets(W, np.zeros_like(G), 0.7).view(np.uint32),
+                          W.view(np.uint32))
+    assert np.array_equal(oracle.encode_targets(W, G, 1.0), W - G)
+    assert np.array_equal(oracle.encode_targets(W, G, -1.0), W + G)
+
+
+# ----------------------------------------------------------- O2: selection
+
+def test_selection_scores_exact_chain():
+    rng = np.random.default_rng(3)
+    g = 8
+    W = rng.standard_normal((4, 32)).astype(np.float32) * np.float32(0.02)
+    T = W + rng.standard_normal((4, 32)).astype(np.float32) * np.float32(1e-3)
+    _, scores = oracle.select_topk_groups(T, W, g, 3, return_scores=True)
+    Tg, Wg = T.reshape(-1, g), W.reshape(-1, g)
+    for n in range(Tg.shape[0]):
+        s = np.float32(0)
+        for i in range(g):
+            d = np.float32(Tg[n, i] - Wg[n, i])
+            s = f32_round(fr(d) * fr(d) + fr(s))
+        assert scores[n] == s
+    # and it is the squared update norm up to fp32 rounding
+    ref = ((Tg.astype(np.float64) - Wg.astype(np.float64)) ** 2).sum(1)
+    assert np.allclose(scores, ref, rtol=1e-5)
+
+
+@pytest.mark.parametrize("k", [0, 1, 5, 37, 96])
+def test_selection_matches_full_sort(k):
+    rng = np.random.default_rng(4)
+    g = 4
+    W = rng.standard_normal((8, 48)).astype(np.float32)
+    T = W + rng.standard_normal((8, 48)).astype(np.float32)
+    # plant exact score ties, some straddling the cut
+    T.reshape(-1, g)[10] = W.reshape(-1, g)[10] + (T.reshape(-1, g)[3] - W.reshape(-1, g)[3])
+    idx, scores = oracle.select_topk_groups(T, W, g, k, return_scores=True)
+    N = scores.shape[0]
+    order = np.lexsort((np.arange(N), -scores.astype(np.float64)))   # score desc, id asc
+    assert np.array_equal(idx, np.sort(order[:k]).astype(np.int32))
+    if 0 < k < N:
+        sel = np.zeros(N, bool)
+        sel[idx] = True
+        assert scores[sel].min() >= scores[~sel].max()
+
+
+def test_selection_special_cases():
+    rng = np.random.default_rng(5)
+    g = 8
+    W = rng.standard_normal((8, 64)).astype(np.float32)
+    T = W + rng.standard_normal((8, 64)).astype(np.float32)
+    N = 64
+    assert np.array_equal(oracle.select_topk_groups(T, W, g, N), np.arange(N, dtype=np.int32))
+    sc = ((T - W).astype(np.float64) ** 2).reshape(N, g).sum(1)
+    assert oracle.select_topk_groups(T, W, g, 1)[0] == int(np.argmax(sc))
+    # all scores equal: the first k ids
+    W2 = np.zeros_like(W)
+    T2 = W2 + np.float32(0.5)
+    assert np.array_equal(oracle.select_topk_groups(T2, W2, g, 9), np.arange(9, dtype=np.int32))
+    # two equal maxima: lowest id wins at k = 1
+    T3 = W.copy()
+    T3.reshape(N, g)[[20, 41], 0] += np.float32(2.0)
+    W3 = W.copy()
+    W3.reshape(N, g)[[20, 41], 0] = 0
+    T3.reshape(N, g)[[20, 41], 0] = 2.0
+    assert oracle.select_topk_groups(T3, W3, g, 1)[0] == 20
+    with pytest.raises(ValueError):
+        oracle.select_topk_groups(T, W, g, N + 1)
+
+
+# ------------------------------------------- O3: nearest codeword (M = 1)
+
+def _read_golden():
+    vals = {}
+    for line in (GOLDEN / "app_p_vstep_example.txt").read_text().splitlines():
+        if line.startswith("#") or not line.strip():
+            continue
+        key, *rest = line.split()
+        vals[key] = [float(v) for v in rest]
+    return vals
+
+
+def test_paper_worked_vstep_example():
+    """App. P: xstar={2,10,0,11}, y0={2,5,5,11} -> x1={2,11,2,11}."""
+    gold = _read_golden()
+    xstar = np.array(gold["xstar"], np.float32)[None, :]
+    y0 = np.array(gold["y0"], np.float32)[None, :]
+    values = gold["values"]
+    cb = np.array(values + [1.0e6], np.float32).reshape(1, 4, 1)     # pad to 2^2 codewords
+    scales = np.ones(1, np.float32)
+    codes0 = np.array([values.index(v) for v in gold["y0"]], np.uint16).reshape(1, 4, 1)
+    assert np.array_equal(oracle.dequantize(codes0, cb, scales), y0)
+    grad = 2.0 * (y0 - xstar)                    # gradient of sum (x - xstar)^2 at y0
+    T = oracle.encode_targets(y0, grad, 0.5)     # 1/L with L = 2
+    assert np.array_equal(T, xstar)
+    idx = oracle.select_topk_groups(T, y0, 1, 4)
+    new, info = oracle.reencode_groups(T, cb, scales, idx, codes0)
+    x1 = oracle.dequantize(new, cb, scales)
+    assert x1.ravel().tolist() == gold["x1"]
+    assert info["num_changed"] == 2
+    # restricted to the two coordinates with the largest update only those may move
+    idx2 = oracle.select_topk_groups(T, y0, 1, 2)
+    assert idx2.tolist() == [1, 2]
+    new2, _ = oracle.reencode_groups(T, cb, scales, idx2, codes0)
+    assert np.array_equal(new2, new)
+
+
+def test_scalar_case_is_binary_search_in_sorted_values():
+    """g = 1: nearest value of a sorted codebook (Sec. 3.2, scalar case; Alg. 6)."""
+    rng = np.random.default_rng(6)
+    B = 5
+    vals = np.sort(rng.standard_normal(1 << B).astype(np.float32))
+    cb = vals.reshape(1, -1, 1)
+    T = rng.standard_normal((6, 40)).astype(np.float32) * np.float32(1.5)
+    scales = np.ones(6, np.float32)
+    codes0 = rng.integers(0, 1 << B, size=(6, 40, 1)).astype(np.uint16)
+    new, _ = oracle.reencode_groups(T, cb, scales, np.arange(240), codes0)
+    t = T.ravel().astype(np.float64)
+    v = vals.astype(np.float64)
+    hi = np.clip(np.searchsorted(v, t), 1, len(v) - 1)
+    lo = hi - 1
+    ref = np.where(np.abs(t - v[lo]) <= np.abs(v[hi] - t), lo, hi)
+    assert np.array_equal(new.ravel(), ref.astype(np.uint16))
+
+
+@pytest.mark.parametrize("g,B", [(8, 6), (16, 5), (4, 8), (2, 3)])
+def test_m1_equals_library_nearest_neighbour(g, B):
+    wl, T = tiny_problem(7 + g, 12, 8 * g, g, 1, B, scales="ones")
+    idx = np.arange(wl.layout.num_groups)
+    new, info = oracle.reencode_groups(T, wl.codebooks, wl.scales, idx, wl.codes)
+    D = cdist(T.reshape(-1, g).astype(np.float64), wl.codebooks[0].astype(np.float64),
+              "sqeuclidean")
+    assert np.array_equal(new.ravel(), D.argmin(1).astype(np.uint16))
+    assert np.allclose(info["obj_new"], D.min(1), rtol=1e-9, atol=0)
+
+
+def test_m1_with_scales_exact_rational_argmin():
+    wl, T = tiny_problem(11, 6, 16, 4, 1, 4)
+    wl.scales[2] = np.float32(-0.8)            # a negative scale is legal
+    idx = np.arange(wl.layout.num_groups)
+    new, info = oracle.reencode_groups(T, wl.codebooks, wl.scales, idx, wl.codes)
+    gpr = wl.layout.groups_per_row
+    for n in idx:
+        t = T.reshape(-1, 4)[n]
+        s = wl.scales[n // gpr]
+        objs = [exact_objective(wl.codebooks, (c,), s, t) for c in range(16)]
+        assert new.reshape(-1)[n] == int(np.argmin(objs))
+        assert abs(info["obj_new"][n] - float(min(objs))) <= 1e-12 * float(min(objs))
+
+
+def test_m1_tie_rule_previous_code_then_lowest_index():
+    g = 2
+    cb = np.array([[[1, 0], [0, 1], [1, 0], [0, 1], [5, 5], [5, 5], [-3, 2], [1, 0]]], np.float32)
+    scales = np.ones(1, np.float32)
+    T = np.array([[1, 0, 1, 0, 0, 1, 5, 5]], np.float32)     # four groups
+    codes0 = np.array([2, 4, 6, 5], np.uint16).reshape(1, 4, 1)
+    new, info = oracle.reencode_groups(T, cb, scales, np.arange(4), codes0)
+    # group0: minimisers {0,2,7}, previous 2 kept; group1: minimisers {0,2,7}, previous 4 not
+    # one -> lowest (0); group2: minimisers {1,3} -> 1; group3: minimisers {4,5}, previous 5 kept
+    assert new.ravel().tolist() == [2, 0, 1, 5]
+    assert info["near_tie"].all()
+    assert info["num_changed"] == 2
+
+
+def test_lemma_3_1_quadratic_model_brute_force():
+    """argmin over all code tuples of <grad, x-y> + L/2 ||x-y||^2 equals the
+    nearest representable point to y - grad/L (Lemma 3.1)."""
+    rng = np.random.default_rng(8)
+    g, B, ngroups, L = 2, 2, 4, 3.0
+    cb = rng.standard_normal((1, 1 << B, g)).astype(np.float32)
+    scales = np.ones(1, np.float32)
+    codes0 = rng.integers(0, 1 << B, size=(1, ngroups, 1)).astype(np.uint16)
+    y = oracle.dequantize(codes0, cb, scales)
+    grad = rng.standard_normal(y.shape).astype(np.float32)
+    best, best_tup = None, None
+    for tup in product(range(1 << B), repeat=ngroups):
+        x = cb[0][list(tup)].reshape(1, -1).astype(np.float64)
+        val = float((grad * (x - y)).sum() + 0.5 * L * ((x - y) ** 2).sum())
+        if best is None or val < best:
+            best, best_tup = val, tup
+    T = oracle.encode_targets(y, grad, 1.0 / L)
+    new, _ = oracle.reencode_groups(T, cb, scales, np.arange(ngroups), codes0)
+    assert tuple(int(c) for c in new.ravel()) == best_tup
+
+
+def test_app_d_identity_argmin_without_target_norm():
+    """||c - x||^2 = ||c||^2 - 2<c,x> + ||x||^2: dropping ||x||^2 keeps the argmin (App. D)."""
+    wl, T = tiny_problem(13, 8, 64, 8, 1, 7, scales="ones")
+    new, _ = oracle.reencode_groups(T, wl.codebooks, wl.scales,
+                                    np.arange(wl.layout.num_groups), wl.codes)
+    C = wl.codebooks[0].astype(np.float64)
+    X = T.reshape(-1, 8).astype(np.float64)
+    score = (C * C).sum(1)[None, :] - 2.0 * X @ C.T
+    assert np.array_equal(new.ravel(), score.argmin(1).astype(np.uint16))
+
+
+# --------------------------------------------------- O4: beam search (M >= 2)
+
+def brute_force_tuples(cbs, s, t):
+    M, csize, _ = cbs.shape
+    best = None
+    for tup in product(range(csize), repeat=M):
+        o = exact_objective(cbs, tup, s, t)
+        if best is None or o < best[0]:
+            best = (o, tup)
+    return best
+
+
+@pytest.mark.parametrize("M,B,beam", [(2, 3, 8), (2, 4, 16), (2, 2, 64), (3, 2, 16)])
+def test_wide_beam_equals_brute_force(M, B, beam):
+    """A beam at least as wide as everything it can hold is exhaustive."""
+    wl, T = tiny_problem(17 + M + B, 3, 16, 4, M, B)
+    idx = np.arange(wl.layout.num_groups)
+    new, info = oracle.reencode_groups(T, wl.codebooks, wl.scales, idx, wl.codes, beam_width=beam)
+    gpr = wl.layout.groups_per_row
+    need = (1 << B) ** (M - 1)
+    assert beam >= need
+    for n in idx:
+        t = T.reshape(-1, 4)[n]
+        s = wl.scales[n // gpr]
+        o, tup = brute_force_tuples(wl.codebooks, s, t)
+        got = tuple(int(c) for c in new.reshape(-1, M)[n])
+        assert exact_objective(wl.codebooks, got, s, t) == o
+        assert abs(info["obj_new"][n] - float(o)) <= 1e-12 * float(o)
+
+
+@pytest.mark.parametrize("beam", [1, 2, 8])
+def test_beam_bounds_optimum_and_previous(beam):
+    """brute-force optimum <= obj(result) <= obj(previous) (Lemma 3.2: y is feasible)."""
+    wl, T = tiny_problem(23, 4, 32, 8, 2, 4)
+    idx = np.arange(wl.layout.num_groups)
+    new, info = oracle.reencode_groups(T, wl.codebooks, wl.scales, idx, wl.codes, beam_width=beam)
+    gpr = wl.layout.groups_per_row
+    for n in idx:
+        t = T.reshape(-1, 8)[n]
+        s = wl.scales[n // gpr]
+        o_best, _ = brute_force_tuples(wl.codebooks, s, t)
+        o_new = exact_objective(wl.codebooks, tuple(new.reshape(-1, 2)[n]), s, t)
+        o_old = exact_objective(wl.codebooks, tuple(wl.codes.reshape(-1, 2)[n]), s, t)
+        assert o_best <= o_new <= o_old
+    assert (info["obj_new"] <= info["obj_prev"]).all()
+
+
+def test_beam_with_one_codebook_is_the_definition():
+    wl, T = tiny_problem(29, 8, 64, 8, 1, 6)
+    idx = np.arange(wl.layout.num_groups)
+    a, ia = oracle.reencode_groups(T, wl.codebooks, wl.scales, idx, wl.codes)
+    for beam in (1, 3, 8):
+        b, ib = oracle.reencode_groups(T, wl.codebooks, wl.scales, idx, wl.codes,
+                                       beam_width=beam, use_beam=True)
+        assert np.array_equal(a, b)
+        assert np.array_equal(ia["obj_new"], ib["obj_new"])
+
+
+def test_beam_one_is_greedy_single_index_descent():
+    """beam 1 = one pass of App. D's local search: fix all codes but one, take the best."""
+    wl, T = tiny_problem(31, 4, 32, 4, 3, 3)
+    idx = np.arange(wl.layout.num_groups)
+    new, _ = oracle.reencode_groups(T, wl.codebooks, wl.scales, idx, wl.codes, beam_width=1)
+    gpr = wl.layout.groups_per_row
+    for n in idx:
+        t = T.reshape(-1, 4)[n]
+        s = wl.scales[n // gpr]
+        prev = [int(c) for c in wl.codes.reshape(-1, 3)[n]]
+        cur = list(prev)
+        for m in range(3):
+            objs = []
+            for c in range(8):
+                trial = list(cur)
+                trial[m] = c
+                objs.append(exact_objective(wl.codebooks, trial, s, t))
+            # ties: the lexicographically first tuple = lowest code at this position
+            cur[m] = int(np.argmin(objs))
+        if not exact_objective(wl.codebooks, cur, s, t) < exact_objective(wl.codebooks, prev, s, t):
+            cur = prev
+        assert [int(c) for c in new.reshape(-1, 3)[n]] == cur
+
+
+def _python_beam(cbs, s, t, prev, beam):
+    """Independent restatement of the beam reading in exact arithmetic (a cross-check against
+    slips in the C code; the reading itself is only pinned by the bounds above)."""
+    M, csize, _ = cbs.shape
+    cur = [(exact_objective(cbs, prev, s, t), tuple(prev))]
+    for m in range(M):
+        pool = []
+        for _, tup in cur:
+            for c in range(csize):
+                q = list(tup)
+                q[m] = c
+                pool.append((exact_objective(cbs, q, s, t), tuple(q)))
+        pool.sort()
+        cur = pool[:beam]
+    o_prev = exact_objective(cbs, prev, s, t)
+    return list(cur[0][1]) if cur[0][0] < o_prev else list(prev)
+
+
+@pytest.mark.parametrize("beam", [2, 3, 8])
+def test_beam_cross_check_exact_arithmetic(beam):
+    wl, T = tiny_problem(37, 3, 32, 8, 2, 4)
+    idx = np.arange(wl.layout.num_groups)
+    new, info = oracle.reencode_groups(T, wl.codebooks, wl.scales, idx, wl.codes, beam_width=beam)
+    gpr = wl.layout.groups_per_row
+    for n in idx:
+        if info["near_tie"][n]:
+            continue
+        ref = _python_beam(wl.codebooks, wl.scales[n // gpr], T.reshape(-1, 8)[n],
+                           [int(c) for c in wl.codes.reshape(-1, 2)[n]], beam)
+        assert [int(c) for c in new.reshape(-1, 2)[n]] == ref
+
+
+# -------------------------------------------------------- O5: dequantize
+
+@pytest.mark.parametrize("M", [1, 2, 3])
+def test_dequantize_definition(M):
+    wl = workloads.make(10, 48, 8, M, 5, seed=41)
+    W = oracle.dequantize(wl.codes, wl.codebooks, wl.scales)
+    acc = wl.codebooks[0][wl.codes[..., 0]]
+    for m in range(1, M):
+        acc = acc + wl.codebooks[m][wl.codes[..., m]]
+    ref = (wl.scales[:, None, None] * acc).reshape(10, 48)
+    assert W.dtype == np.float32 and np.array_equal(W, ref)
+    # one hand-computed entry
+    o, j, i = 3, 2, 5
+    v = sum(float(wl.codebooks[m][wl.codes[o, j, m]][i]) for m in range(M)) * float(wl.scales[o])
+    assert abs(W[o, j * 8 + i] - v) <= 1e-6 * abs(v)
+
+
+def test_dequantize_rejects_out_of_range_code():
+    wl = workloads.make(2, 16, 8, 1, 3, seed=43)
+    wl.codes[1, 1, 0] = 9
+    with pytest.raises(ValueError):
+        oracle.dequantize(wl.codes, wl.codebooks, wl.scales)
+
+
+# ---------------------------------------------------------- whole path
+
+@pytest.mark.parametrize("M,B,beam", [(1, 8, 1), (2, 4, 4)])
+def test_round_trip_is_a_fixed_point(M, B, beam):
+    """If the target is the current point (zero update), no code changes (Sec. 3.2,
+    'the optimal solution is often y itself')."""
+    wl = workloads.make(16, 64, 8, M, B, seed=47, beam_width=beam)
+    W = oracle.dequantize(wl.codes, wl.codebooks, wl.scales)
+    T = oracle.encode_targets(W, wl.G, 0.0)
+    idx = np.arange(wl.layout.num_groups)
+    new, info = oracle.reencode_groups(T, wl.codebooks, wl.scales, idx, wl.codes, beam_width=beam)
+    assert np.array_equal(new, wl.codes) and info["num_changed"] == 0
+
+
+@pytest.mark.parametrize("name,shape", [("c1_256x256_1x8", (64, 128)),
+                                        ("c3_11008x4096_2x8", (32, 64))])
+def test_path_invariants(name, shape):
+    wl = workloads.make_config(name, seed=3, out_features=shape[0], in_features=shape[1], tau=0.1)
+    g = wl.layout.group_size
+    T = oracle.encode_targets(wl.W, wl.G, wl.alpha)
+    idx = oracle.select_topk_groups(T, wl.W, g, wl.k)
+    assert len(idx) == wl.k and (np.diff(idx) > 0).all()
+    new, info = oracle.reencode_groups(T, wl.codebooks, wl.scales, idx, wl.codes,
+                                       beam_width=wl.beam_width)
+    M = wl.layout.num_codebooks
+    mask = np.ones(wl.layout.num_groups, bool)
+    mask[idx] = False
+    # codes outside the chosen subspace are untouched (Eq. 7)
+    assert np.array_equal(new.reshape(-1, M)[mask], wl.codes.reshape(-1, M)[mask])
+    # the re-encoded point is never worse than the previous one (Lemma 3.2)
+    assert (info["obj_new"] <= info["obj_prev"]).all()
+    obj = oracle.group_objective(T, wl.codebooks, wl.scales, idx, new.reshape(-1, M)[idx])
+    assert np.array_equal(obj, info["obj_new"])
+    W2 = oracle.dequantize(new, wl.codebooks, wl.scales)
+    err_new = ((W2 - T).astype(np.float64) ** 2).reshape(-1, g).sum(1)[idx]
+    assert np.allclose(err_new, info["obj_new"], rtol=1e-4)
