@@ -1,0 +1,144 @@
+/*
+ * pv.h -- C ABI of the MI355X (gfx950) library for the discrete-code update of
+ * PV-Tuning (arXiv 2405.14852): the linearised subspace V step.
+ *
+ * One V step on one weight matrix is
+ *     W  = pv_dequantize(codes)                       Alg. 3, line 1
+ *     T  = pv_encode_targets(W, G, alpha)             Eq. 7; Alg. 3, V step
+ *     S  = pv_select_topk_groups(T, W, k)             Alg. 2, line 5; Sec. 3.4
+ *     codes[S] = pv_reencode_groups(T, S)             Eq. 7 argmin; Sec. 4.2; App. D, K
+ *
+ * Conventions for every call
+ *   - All tensor pointers are DEVICE pointers on the context's GPU, owned by the
+ *     caller, 16-byte aligned, row-major, dense.  The library neither allocates
+ *     nor frees caller-visible memory.  The context owns its scratch memory,
+ *     grown on demand and released by pv_destroy.
+ *   - A weight matrix is [out_features, in_features].  A group is group_size
+ *     consecutive weights of one row (along the input dimension, App. K).  Groups
+ *     are numbered row by row: n = o * (in_features / group_size) + j;
+ *     N = number of groups must be < 2^31.
+ *   - Calls enqueue work on the context's HIP stream and return without waiting;
+ *     results are ordered by that stream.  One context per host thread.
+ *   - Errors are reported by the return code only; on an error nothing has been
+ *     enqueued or written.  pv_last_error gives a short text for the last error
+ *     of a context.
+ */
+#ifndef PV_H
+#define PV_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct pv_ctx pv_ctx; /* opaque */
+
+typedef enum {
+    PV_OK = 0,
+    PV_ERR_INVALID_ARG = 1, /* NULL pointer, k out of range, beam_width < 1, ...     */
+    PV_ERR_SHAPE = 2,       /* in_features % group_size != 0, N >= 2^31, B not in 1..16 */
+    PV_ERR_UNSUPPORTED = 3, /* a legal shape this build has no kernel for           */
+    PV_ERR_ALLOC = 4,       /* scratch allocation failed                            */
+    PV_ERR_DEVICE = 5       /* a HIP call failed                                    */
+} pv_status;
+
+typedef struct {
+    int64_t out_features;  /* rows of W                                        */
+    int64_t in_features;   /* columns of W; multiple of group_size             */
+    int32_t group_size;    /* g >= 1                                           */
+    int32_t num_codebooks; /* M in 1..8 (additive codebooks)                   */
+    int32_t nbits;         /* B in 1..16; each codebook holds 2^B codewords    */
+} pv_layout;
+
+/* Create a context bound to HIP device `device`; work is enqueued on
+ * `hip_stream` (a hipStream_t; NULL = the device's default stream). */
+pv_status pv_create(pv_ctx **out, int device, void *hip_stream);
+void pv_destroy(pv_ctx *ctx);
+const char *pv_last_error(const pv_ctx *ctx);
+
+/* Eq. 7 / Alg. 3 V step: the target of the linearised subspace V step,
+ * T = W - alpha * G elementwise (alpha plays 1/L_S; G is the gradient or the
+ * Adam direction, the caller's choice), one fp32 rounding per element.
+ * W, G, T: f32 [out_features, in_features].  T may alias W or G exactly
+ * (same pointer) but must not partially overlap them. */
+pv_status pv_encode_targets(pv_ctx *ctx, const pv_layout *layout, const float *W,
+                            const float *G, float alpha, float *T);
+
+/* Alg. 2 line 5 ("arg top tau") with Sec. 3.4's rule (largest update norm, per
+ * weight matrix), applied to weight groups: score_n = sum_i (T[n,i] - W[n,i])^2
+ * accumulated in fp32 in index order with fused multiply-adds; the k groups with
+ * the largest score are returned as ASCENDING flat group ids in out_idx[k]
+ * (i32).  Equal scores: the lower id is preferred.  0 <= k <= N; k == 0 writes
+ * nothing.  group_scores: optional f32 [N], receives every group's score. */
+pv_status pv_select_topk_groups(pv_ctx *ctx, const pv_layout *layout, const float *T,
+                                const float *W, int64_t k, int32_t *out_idx,
+                                float *group_scores /* NULL ok */);
+
+/* Eq. 7 argmin restricted to the listed groups (Alg. 3 last line, "find_nearest"):
+ * for each listed group with target t (g values of T), row scale s and current
+ * code tuple p, minimise  obj(b) = || s * sum_m codebooks[m, b_m, :] - t ||^2
+ * (double precision on the fp32 inputs).
+ *   M == 1: exact nearest codeword over all 2^B codewords ("try every code",
+ *           App. K).  Exact ties: p if p is a minimiser, else the lowest index.
+ *           beam_width is ignored.
+ *   M >= 2: beam search (Sec. 4.2, App. D, App. K): the beam starts as {p}; for
+ *           m = 0..M-1 every beam entry spawns 2^B candidates (its m-th code
+ *           replaced), candidates are ranked by (obj, tuple lexicographic) and
+ *           the best beam_width kept; the final best replaces p only if it is
+ *           strictly better.
+ * codes: u16 [out_features, in_features/g, M], updated in place for the listed
+ * groups only; all other codes are left untouched.  group_idx: i32 [k],
+ * ascending, unique, each in [0, N) (ids outside the range are skipped).
+ * scales: f32 [out_features]; a zero scale keeps the previous code.
+ * num_changed: optional device int64, receives the number of groups whose code
+ * tuple changed. */
+pv_status pv_reencode_groups(pv_ctx *ctx, const pv_layout *layout, const float *T,
+                             const float *codebooks /* f32 [M, 2^B, g] */,
+                             const float *scales /* f32 [out_features] */,
+                             const int32_t *group_idx, int64_t k, int32_t beam_width,
+                             uint16_t *codes, int64_t *num_changed /* NULL ok */);
+
+/* Alg. 3 line 1: W_out[o, j*g + i] = scales[o] * sum_m codebooks[m, codes[o,j,m], i]
+ * with fp32 additions in codebook order and one fp32 multiply.  Codes are
+ * masked to B bits. */
+pv_status pv_dequantize(pv_ctx *ctx, const pv_layout *layout, const uint16_t *codes,
+                        const float *codebooks, const float *scales, float *W_out);
+
+/* ---- instrumentation (does not change results) ------------------------- */
+
+/* Search strategy for M == 1: 0 = automatic (matrix-core filter + exact
+ * re-rank where the shape allows, else exact scan), 1 = exact scan only. */
+pv_status pv_set_search_mode(pv_ctx *ctx, int mode);
+
+typedef enum {
+    PV_K_ENCODE_TARGETS = 0,
+    PV_K_GROUP_SCORES = 1,
+    PV_K_SELECT = 2,      /* all kernels of the radix select + compaction   */
+    PV_K_PREP = 3,        /* codebook + target preparation for the filter   */
+    PV_K_SCORE_MFMA = 4,  /* the distance contraction                       */
+    PV_K_RERANK = 5,      /* exact re-rank + write-back                     */
+    PV_K_EXACT_SCAN = 6,  /* exact scan (fallback list or whole call)       */
+    PV_K_BEAM = 7,
+    PV_K_DEQUANTIZE = 8,
+    PV_K_COUNT = 9
+} pv_kernel_id;
+
+/* With timing on, each kernel (group) above is bracketed by HIP events on the
+ * context's stream; pv_timing_read waits for the stream and returns the sum of
+ * durations in milliseconds and the number of launches since the last reset. */
+pv_status pv_timing_enable(pv_ctx *ctx, int on);
+pv_status pv_timing_reset(pv_ctx *ctx);
+pv_status pv_timing_read(pv_ctx *ctx, int kernel_id, double *total_ms, int64_t *launches);
+
+/* Counters of the last pv_reencode_groups call (waits for the stream):
+ * stats[0] = groups handled by the matrix-core filter, stats[1] = groups the
+ * filter could not certify and that were re-done by the exact scan,
+ * stats[2] = candidate codewords evaluated exactly in the re-rank,
+ * stats[3] = groups handled by exact scan / beam search from the start. */
+pv_status pv_reencode_stats(pv_ctx *ctx, int64_t stats[4]);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PV_H */

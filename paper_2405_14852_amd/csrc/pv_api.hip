@@ -1,0 +1,310 @@
+// C-ABI entry points of libpv: context handling, argument validation, dispatch.
+// Every step of the path runs in the kernels of the other translation units.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+
+#include "pv_internal.h"
+
+// ---------------------------------------------------------------- helpers
+
+pv_status pv_fail(pv_ctx *ctx, pv_status st, const char *fmt, ...)
+{
+    if (ctx) {
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(ctx->err, sizeof(ctx->err), fmt, ap);
+        va_end(ap);
+    }
+    return st;
+}
+
+pv_status pv_ensure(pv_ctx *ctx, pv_buffer &buf, size_t bytes, bool zero_new)
+{
+    if (buf.bytes >= bytes && buf.ptr) return PV_OK;
+    size_t want = bytes < 256 ? 256 : bytes;
+    if (buf.ptr) {
+        // queued kernels may still read the old block
+        PV_HIP(ctx, hipStreamSynchronize(ctx->stream));
+        PV_HIP(ctx, hipFree(buf.ptr));
+        buf.ptr = nullptr;
+        buf.bytes = 0;
+        want += want / 4;
+    }
+    void *p = nullptr;
+    if (hipMalloc(&p, want) != hipSuccess) {
+        (void)hipGetLastError();
+        return pv_fail(ctx, PV_ERR_ALLOC, "scratch allocation of %zu bytes failed", want);
+    }
+    buf.ptr = p;
+    buf.bytes = want;
+    if (zero_new) PV_HIP(ctx, hipMemsetAsync(p, 0, want, ctx->stream));
+    return PV_OK;
+}
+
+static hipEvent_t take_event(pv_ctx *c)
+{
+    if (!c->event_pool.empty()) {
+        hipEvent_t e = c->event_pool.back();
+        c->event_pool.pop_back();
+        return e;
+    }
+    hipEvent_t e = nullptr;
+    if (hipEventCreate(&e) != hipSuccess) return nullptr;
+    return e;
+}
+
+pv_timed::pv_timed(pv_ctx *ctx, int kernel_id) : c(ctx), id(kernel_id)
+{
+    if (!c->timing) return;
+    start = take_event(c);
+    if (start) (void)hipEventRecord(start, c->stream);
+}
+
+pv_timed::~pv_timed()
+{
+    if (!start) return;
+    hipEvent_t stop = take_event(c);
+    if (!stop) {
+        c->event_pool.push_back(start);
+        return;
+    }
+    (void)hipEventRecord(stop, c->stream);
+    c->timers[id].pending.push_back(start);
+    c->timers[id].pending.push_back(stop);
+}
+
+static pv_status check_layout(pv_ctx *ctx, const pv_layout *l)
+{
+    if (!l) return pv_fail(ctx, PV_ERR_INVALID_ARG, "layout is NULL");
+    if (l->out_features < 0 || l->in_features < 0)
+        return pv_fail(ctx, PV_ERR_SHAPE, "negative matrix shape");
+    if (l->group_size < 1 || l->in_features % l->group_size != 0)
+        return pv_fail(ctx, PV_ERR_SHAPE, "in_features %lld is not a multiple of group_size %d",
+                       (long long)l->in_features, l->group_size);
+    if (l->num_codebooks < 1 || l->num_codebooks > 8)
+        return pv_fail(ctx, PV_ERR_SHAPE, "num_codebooks %d not in 1..8", l->num_codebooks);
+    if (l->nbits < 1 || l->nbits > 16)
+        return pv_fail(ctx, PV_ERR_SHAPE, "nbits %d not in 1..16", l->nbits);
+    int64_t gpr = l->in_features / l->group_size;
+    if (l->out_features > 0 && gpr > 0 && gpr > (INT64_C(0x7fffffff) - 1) / l->out_features)
+        return pv_fail(ctx, PV_ERR_SHAPE, "number of groups must be below 2^31");
+    return PV_OK;
+}
+
+static bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+// ---------------------------------------------------------------- context
+
+extern "C" pv_status pv_create(pv_ctx **out, int device, void *hip_stream)
+{
+    if (!out) return PV_ERR_INVALID_ARG;
+    *out = nullptr;
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || device < 0 || device >= ndev) {
+        (void)hipGetLastError();
+        return PV_ERR_DEVICE;
+    }
+    if (hipSetDevice(device) != hipSuccess) return PV_ERR_DEVICE;
+    pv_ctx *c = new (std::nothrow) pv_ctx();
+    if (!c) return PV_ERR_ALLOC;
+    c->device = device;
+    c->stream = static_cast<hipStream_t>(hip_stream);
+    *out = c;
+    return PV_OK;
+}
+
+extern "C" void pv_destroy(pv_ctx *c)
+{
+    if (!c) return;
+    (void)hipSetDevice(c->device);
+    (void)hipStreamSynchronize(c->stream);
+    pv_buffer *bufs[] = {&c->sel_scores, &c->sel_hist, &c->sel_blocks, &c->sel_state, &c->stats,
+                         &c->cb_f16,     &c->cb_meta,  &c->x_f16,      &c->x_meta,    &c->partials,
+                         &c->fb_list};
+    for (pv_buffer *b : bufs)
+        if (b->ptr) (void)hipFree(b->ptr);
+    for (auto &t : c->timers)
+        for (hipEvent_t e : t.pending) (void)hipEventDestroy(e);
+    for (hipEvent_t e : c->event_pool) (void)hipEventDestroy(e);
+    delete c;
+}
+
+extern "C" const char *pv_last_error(const pv_ctx *c) { return c ? c->err : "context is NULL"; }
+
+// ---------------------------------------------------------------- the path
+
+extern "C" pv_status pv_encode_targets(pv_ctx *ctx, const pv_layout *l, const float *W,
+                                       const float *G, float alpha, float *T)
+{
+    if (!ctx) return PV_ERR_INVALID_ARG;
+    pv_status st = check_layout(ctx, l);
+    if (st != PV_OK) return st;
+    if (!W || !G || !T) return pv_fail(ctx, PV_ERR_INVALID_ARG, "NULL tensor pointer");
+    if (misaligned(W) || misaligned(G) || misaligned(T))
+        return pv_fail(ctx, PV_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
+    int64_t n = l->out_features * l->in_features;
+    if (n == 0) return PV_OK;
+    PV_HIP(ctx, hipSetDevice(ctx->device));
+    return pv_launch_encode_targets(ctx, W, G, alpha, T, n);
+}
+
+extern "C" pv_status pv_select_topk_groups(pv_ctx *ctx, const pv_layout *l, const float *T,
+                                           const float *W, int64_t k, int32_t *out_idx,
+                                           float *group_scores)
+{
+    if (!ctx) return PV_ERR_INVALID_ARG;
+    pv_status st = check_layout(ctx, l);
+    if (st != PV_OK) return st;
+    int64_t N = pv_num_groups(l);
+    if (k < 0 || k > N)
+        return pv_fail(ctx, PV_ERR_INVALID_ARG, "k = %lld outside [0, %lld]", (long long)k,
+                       (long long)N);
+    if (!T || !W) return pv_fail(ctx, PV_ERR_INVALID_ARG, "NULL tensor pointer");
+    if (k > 0 && !out_idx) return pv_fail(ctx, PV_ERR_INVALID_ARG, "out_idx is NULL");
+    if (misaligned(T) || misaligned(W) || misaligned(group_scores))
+        return pv_fail(ctx, PV_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
+    if (N == 0 || (k == 0 && !group_scores)) return PV_OK;
+    PV_HIP(ctx, hipSetDevice(ctx->device));
+    return pv_launch_select(ctx, l, T, W, k, out_idx, group_scores);
+}
+
+extern "C" pv_status pv_reencode_groups(pv_ctx *ctx, const pv_layout *l, const float *T,
+                                        const float *codebooks, const float *scales,
+                                        const int32_t *group_idx, int64_t k, int32_t beam_width,
+                                        uint16_t *codes, int64_t *num_changed)
+{
+    if (!ctx) return PV_ERR_INVALID_ARG;
+    pv_status st = check_layout(ctx, l);
+    if (st != PV_OK) return st;
+    int64_t N = pv_num_groups(l);
+    if (k < 0 || k > N)
+        return pv_fail(ctx, PV_ERR_INVALID_ARG, "k = %lld outside [0, %lld]", (long long)k,
+                       (long long)N);
+    if (beam_width < 1) return pv_fail(ctx, PV_ERR_INVALID_ARG, "beam_width must be >= 1");
+    if (!T || !codebooks || !scales || !codes)
+        return pv_fail(ctx, PV_ERR_INVALID_ARG, "NULL tensor pointer");
+    if (k > 0 && !group_idx) return pv_fail(ctx, PV_ERR_INVALID_ARG, "group_idx is NULL");
+    if (misaligned(T) || misaligned(codebooks))
+        return pv_fail(ctx, PV_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
+    const int M = l->num_codebooks;
+    if (M > 1) {
+        int64_t pool = (int64_t)beam_width << l->nbits;
+        if (beam_width > 64 || pool > 4096)
+            return pv_fail(ctx, PV_ERR_UNSUPPORTED,
+                           "beam search supports beam_width <= 64 and beam_width * 2^B <= 4096");
+        if (l->group_size > 64)
+            return pv_fail(ctx, PV_ERR_UNSUPPORTED, "beam search supports group_size <= 64");
+    } else if (l->group_size > 64) {
+        return pv_fail(ctx, PV_ERR_UNSUPPORTED, "nearest-codeword search supports group_size <= 64");
+    }
+    PV_HIP(ctx, hipSetDevice(ctx->device));
+    st = pv_ensure(ctx, ctx->stats, 8 * sizeof(int64_t));
+    if (st != PV_OK) return st;
+    int64_t *stats = static_cast<int64_t *>(ctx->stats.ptr);
+    st = pv_launch_fill_i64(ctx, stats, 8, 0);
+    if (st != PV_OK) return st;
+    if (num_changed) {
+        st = pv_launch_fill_i64(ctx, num_changed, 1, 0);
+        if (st != PV_OK) return st;
+    }
+    if (k == 0) return PV_OK;
+    if (M > 1) return pv_launch_beam(ctx, l, T, codebooks, scales, group_idx, k, beam_width, codes,
+                                     num_changed);
+    if (ctx->search_mode == 0 && pv_mfma_supported(l))
+        return pv_launch_mfma_search(ctx, l, T, codebooks, scales, group_idx, k, codes,
+                                     num_changed);
+    return pv_launch_exact_scan(ctx, l, T, codebooks, scales, group_idx, nullptr, k, codes,
+                                num_changed, stats + 3);
+}
+
+extern "C" pv_status pv_dequantize(pv_ctx *ctx, const pv_layout *l, const uint16_t *codes,
+                                   const float *codebooks, const float *scales, float *W_out)
+{
+    if (!ctx) return PV_ERR_INVALID_ARG;
+    pv_status st = check_layout(ctx, l);
+    if (st != PV_OK) return st;
+    if (!codes || !codebooks || !scales || !W_out)
+        return pv_fail(ctx, PV_ERR_INVALID_ARG, "NULL tensor pointer");
+    if (misaligned(codebooks) || misaligned(W_out))
+        return pv_fail(ctx, PV_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
+    if (pv_num_groups(l) == 0) return PV_OK;
+    PV_HIP(ctx, hipSetDevice(ctx->device));
+    return pv_launch_dequantize(ctx, l, codes, codebooks, scales, W_out);
+}
+
+// ---------------------------------------------------------------- instrumentation
+
+extern "C" pv_status pv_set_search_mode(pv_ctx *ctx, int mode)
+{
+    if (!ctx) return PV_ERR_INVALID_ARG;
+    if (mode != 0 && mode != 1) return pv_fail(ctx, PV_ERR_INVALID_ARG, "search mode must be 0 or 1");
+    ctx->search_mode = mode;
+    return PV_OK;
+}
+
+extern "C" pv_status pv_timing_enable(pv_ctx *ctx, int on)
+{
+    if (!ctx) return PV_ERR_INVALID_ARG;
+    ctx->timing = on != 0;
+    return PV_OK;
+}
+
+static pv_status drain_timers(pv_ctx *ctx)
+{
+    PV_HIP(ctx, hipSetDevice(ctx->device));
+    PV_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    for (auto &t : ctx->timers) {
+        for (size_t i = 0; i + 1 < t.pending.size(); i += 2) {
+            float ms = 0.f;
+            if (hipEventElapsedTime(&ms, t.pending[i], t.pending[i + 1]) == hipSuccess) {
+                t.total_ms += ms;
+                t.launches += 1;
+            } else {
+                (void)hipGetLastError();
+            }
+            ctx->event_pool.push_back(t.pending[i]);
+            ctx->event_pool.push_back(t.pending[i + 1]);
+        }
+        t.pending.clear();
+    }
+    return PV_OK;
+}
+
+extern "C" pv_status pv_timing_reset(pv_ctx *ctx)
+{
+    if (!ctx) return PV_ERR_INVALID_ARG;
+    pv_status st = drain_timers(ctx);
+    for (auto &t : ctx->timers) {
+        t.total_ms = 0.0;
+        t.launches = 0;
+    }
+    return st;
+}
+
+extern "C" pv_status pv_timing_read(pv_ctx *ctx, int kernel_id, double *total_ms, int64_t *launches)
+{
+    if (!ctx) return PV_ERR_INVALID_ARG;
+    if (kernel_id < 0 || kernel_id >= PV_K_COUNT || !total_ms || !launches)
+        return pv_fail(ctx, PV_ERR_INVALID_ARG, "bad timing query");
+    pv_status st = drain_timers(ctx);
+    if (st != PV_OK) return st;
+    *total_ms = ctx->timers[kernel_id].total_ms;
+    *launches = ctx->timers[kernel_id].launches;
+    return PV_OK;
+}
+
+extern "C" pv_status pv_reencode_stats(pv_ctx *ctx, int64_t stats[4])
+{
+    if (!ctx || !stats) return PV_ERR_INVALID_ARG;
+    for (int i = 0; i < 4; ++i) stats[i] = 0;
+    if (!ctx->stats.ptr) return PV_OK;
+    PV_HIP(ctx, hipSetDevice(ctx->device));
+    PV_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    int64_t host[8];
+    PV_HIP(ctx, hipMemcpy(host, ctx->stats.ptr, sizeof(host), hipMemcpyDeviceToHost));
+    for (int i = 0; i < 4; ++i) stats[i] = host[i];
+    return PV_OK;
+}

@@ -1,0 +1,321 @@
+// Exact searches in double precision: the full nearest-codeword scan for one
+// codebook ("try every code", App. K) and the beam search over several
+// codebooks (Sec. 4.2, App. D, App. K).  Objectives are evaluated exactly as
+//     acc = C_0[b_0,i] (+ C_1[b_1,i] + ...)        in double, codebook order
+//     r   = s * acc - t_i ;  obj = obj + r * r      in double, index order
+// with no contraction, so that the decision is taken in one fixed arithmetic.
+//
+// The scan serves two callers: whole calls for shapes the matrix-core filter
+// does not cover, and the (short) list of groups that filter could not certify.
+#include "pv_internal.h"
+
+namespace {
+
+constexpr int kBlock = 256;
+constexpr int kMaxG = 64;
+constexpr double kInf = __builtin_huge_val();
+
+struct best_t {
+    double obj;
+    int idx;
+};
+
+__device__ __forceinline__ bool better(double o1, int i1, double o2, int i2)
+{
+    return o1 < o2 || (o1 == o2 && i1 < i2);
+}
+
+__device__ __forceinline__ best_t wave_min(best_t b)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        double o = __shfl_down(b.obj, off);
+        int i = __shfl_down(b.idx, off);
+        if (better(o, i, b.obj, b.idx)) {
+            b.obj = o;
+            b.idx = i;
+        }
+    }
+    return b;
+}
+
+// Block-wide lexicographic minimum of (obj, idx); valid in thread 0.
+__device__ __forceinline__ best_t block_min(best_t b, double *s_obj, int *s_idx)
+{
+    b = wave_min(b);
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    __syncthreads();
+    if (lane == 0) {
+        s_obj[wave] = b.obj;
+        s_idx[wave] = b.idx;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < kBlock / 64; ++w)
+            if (better(s_obj[w], s_idx[w], b.obj, b.idx)) {
+                b.obj = s_obj[w];
+                b.idx = s_idx[w];
+            }
+    }
+    return b;
+}
+
+// ------------------------------------------------------------------ M = 1 scan
+//
+// One block takes GPB groups of the list at a time; thread t scores codewords
+// t, t + 256, ... against all GPB targets (a codeword is read once for GPB
+// groups).  Ascending scan + strict '<' keeps the lowest index among equal
+// objectives; the previous code wins an exact tie with the minimum.
+constexpr int GPB = 4;
+
+__global__ __launch_bounds__(kBlock) void k_exact_scan(
+    const float *__restrict__ T, const float *__restrict__ codebook,
+    const float *__restrict__ scales, const int32_t *__restrict__ list,
+    const uint32_t *__restrict__ d_count, int64_t max_count, uint16_t *__restrict__ codes,
+    unsigned long long *__restrict__ num_changed, unsigned long long *__restrict__ stat_counter,
+    int g, int nbits, int gpr, int N)
+{
+    __shared__ float s_t[GPB][kMaxG];
+    __shared__ float s_scale[GPB];
+    __shared__ int s_group[GPB];
+    __shared__ double s_obj[kBlock / 64];
+    __shared__ int s_idx[kBlock / 64];
+    const int64_t count = d_count ? (int64_t)*d_count : max_count;
+    const int csize = 1 << nbits;
+    for (int64_t base = (int64_t)blockIdx.x * GPB; base < count; base += (int64_t)gridDim.x * GPB) {
+        __syncthreads();
+        if (threadIdx.x < GPB) {
+            int64_t j = base + threadIdx.x;
+            int n = j < count ? list[j] : -1;
+            if (n < 0 || n >= N) n = -1;
+            s_group[threadIdx.x] = n;
+            s_scale[threadIdx.x] = n >= 0 ? scales[n / gpr] : 0.0f;
+        }
+        __syncthreads();
+        for (int e = threadIdx.x; e < GPB * g; e += kBlock) {
+            int q = e / g, i = e - q * g;
+            int n = s_group[q];
+            s_t[q][i] = n >= 0 ? T[(int64_t)n * g + i] : 0.0f;
+        }
+        __syncthreads();
+        best_t best[GPB];
+#pragma unroll
+        for (int q = 0; q < GPB; ++q) {
+            best[q].obj = kInf;
+            best[q].idx = 0x7fffffff;
+        }
+        for (int c = threadIdx.x; c < csize; c += kBlock) {
+            const float *cw = codebook + (int64_t)c * g;
+            double obj[GPB];
+#pragma unroll
+            for (int q = 0; q < GPB; ++q) obj[q] = 0.0;
+            for (int i = 0; i < g; ++i) {
+                double acc = (double)cw[i];
+#pragma unroll
+                for (int q = 0; q < GPB; ++q) {
+                    double r = (double)s_scale[q] * acc - (double)s_t[q][i];
+                    obj[q] = obj[q] + r * r;
+                }
+            }
+#pragma unroll
+            for (int q = 0; q < GPB; ++q)
+                if (obj[q] < best[q].obj) {
+                    best[q].obj = obj[q];
+                    best[q].idx = c;
+                }
+        }
+#pragma unroll
+        for (int q = 0; q < GPB; ++q) {
+            best_t b = block_min(best[q], s_obj, s_idx);
+            if (threadIdx.x == 0 && s_group[q] >= 0) {
+                const int n = s_group[q];
+                const int prev = codes[n] & (csize - 1);
+                double o_prev = 0.0;
+                for (int i = 0; i < g; ++i) {
+                    double acc = (double)codebook[(int64_t)prev * g + i];
+                    double r = (double)s_scale[q] * acc - (double)s_t[q][i];
+                    o_prev = o_prev + r * r;
+                }
+                int pick = b.idx;
+                if (o_prev == b.obj || pick == 0x7fffffff) pick = prev;
+                if (pick != prev) {
+                    codes[n] = (uint16_t)pick;
+                    if (num_changed) atomicAdd(num_changed, 1ull);
+                }
+                if (stat_counter) atomicAdd(stat_counter, 1ull);
+            }
+        }
+    }
+}
+
+// ------------------------------------------------------------------ beam search
+//
+// One block per listed group.  The beam (tuples + objectives) and the pool of
+// candidate objectives live in LDS.  At codebook m, candidate (e, c) is beam
+// entry e with its m-th code replaced by c.  Candidates are ranked by
+// (objective, tuple in lexicographic order); since all candidates of one step
+// agree on positions > m, the tuple order is (rank of entry e's prefix, c).
+// The best `keep` candidates are extracted one block-wide argmin at a time.
+constexpr int kMaxM = 8;
+constexpr int kMaxBeam = 64;
+constexpr int kMaxPool = 4096;
+
+__device__ __forceinline__ double beam_objective(const float *__restrict__ codebooks, int M,
+                                                 int csize, int g, const uint16_t *tuple,
+                                                 int replace_m, int replace_c, float s,
+                                                 const float *t)
+{
+    double obj = 0.0;
+    for (int i = 0; i < g; ++i) {
+        int c0 = replace_m == 0 ? replace_c : tuple[0];
+        double acc = (double)codebooks[((int64_t)c0) * g + i];
+        for (int m = 1; m < M; ++m) {
+            int cm = replace_m == m ? replace_c : tuple[m];
+            acc = acc + (double)codebooks[((int64_t)m * csize + cm) * g + i];
+        }
+        double r = (double)s * acc - (double)t[i];
+        obj = obj + r * r;
+    }
+    return obj;
+}
+
+__global__ __launch_bounds__(kBlock) void k_beam(
+    const float *__restrict__ T, const float *__restrict__ codebooks,
+    const float *__restrict__ scales, const int32_t *__restrict__ group_idx, int64_t k,
+    int beam_width, uint16_t *__restrict__ codes, unsigned long long *__restrict__ num_changed,
+    unsigned long long *__restrict__ stat_counter, int g, int M, int nbits, int gpr, int N)
+{
+    __shared__ double s_pool[kMaxPool];
+    __shared__ unsigned char s_taken[kMaxPool];
+    __shared__ double s_beam_obj[2][kMaxBeam];
+    __shared__ uint16_t s_beam[2][kMaxBeam][kMaxM];
+    __shared__ int s_rank[kMaxBeam], s_inv[kMaxBeam];
+    __shared__ float s_t[kMaxG];
+    __shared__ double s_obj[kBlock / 64];
+    __shared__ int s_idx[kBlock / 64];
+    __shared__ int s_pick;
+    const int csize = 1 << nbits;
+    for (int64_t j = blockIdx.x; j < k; j += gridDim.x) {
+        const int n = group_idx[j];
+        if (n < 0 || n >= N) continue;  // uniform over the block
+        __syncthreads();
+        const float s = scales[n / gpr];
+        if ((int)threadIdx.x < g) s_t[threadIdx.x] = T[(int64_t)n * g + threadIdx.x];
+        if ((int)threadIdx.x < M)
+            s_beam[0][0][threadIdx.x] = codes[(int64_t)n * M + threadIdx.x] & (csize - 1);
+        __syncthreads();
+        if (threadIdx.x == 0)
+            s_beam_obj[0][0] = beam_objective(codebooks, M, csize, g, s_beam[0][0], -1, 0, s, s_t);
+        __syncthreads();
+        const double o_prev = s_beam_obj[0][0];
+        int ncur = 1, cur = 0;
+        for (int m = 0; m < M && ncur > 0; ++m) {
+            // rank of each beam entry's prefix [0, m) in lexicographic order, and its inverse
+            if ((int)threadIdx.x < ncur) {
+                int r = 0;
+                for (int e = 0; e < ncur; ++e) {
+                    bool less = false;
+                    for (int p = 0; p < m; ++p) {
+                        uint16_t a = s_beam[cur][e][p], b = s_beam[cur][threadIdx.x][p];
+                        if (a != b) {
+                            less = a < b;
+                            break;
+                        }
+                    }
+                    r += less;
+                }
+                s_rank[threadIdx.x] = r;
+                s_inv[r] = threadIdx.x;
+            }
+            const int npool = ncur * csize;
+            for (int q = threadIdx.x; q < npool; q += kBlock) {
+                int e = q / csize, c = q - e * csize;
+                s_pool[q] = beam_objective(codebooks, M, csize, g, s_beam[cur][e], m, c, s, s_t);
+                s_taken[q] = 0;
+            }
+            __syncthreads();
+            const int keep = (m == M - 1) ? 1 : (npool < beam_width ? npool : beam_width);
+            int got = 0;
+            for (int r = 0; r < keep; ++r) {
+                best_t b;
+                b.obj = kInf;
+                b.idx = 0x7fffffff;
+                for (int q = threadIdx.x; q < npool; q += kBlock) {
+                    if (s_taken[q]) continue;
+                    int e = q / csize, c = q - e * csize;
+                    int tie = s_rank[e] * csize + c;
+                    double o = s_pool[q];
+                    if (better(o, tie, b.obj, b.idx)) {  // false for NaN objectives
+                        b.obj = o;
+                        b.idx = tie;
+                    }
+                }
+                b = block_min(b, s_obj, s_idx);
+                if (threadIdx.x == 0) {
+                    s_pick = b.idx;
+                    if (b.idx != 0x7fffffff) {
+                        int e = s_inv[b.idx / csize], c = b.idx % csize;
+                        for (int p = 0; p < M; ++p)
+                            s_beam[cur ^ 1][r][p] = (p == m) ? (uint16_t)c : s_beam[cur][e][p];
+                        s_beam_obj[cur ^ 1][r] = b.obj;
+                        s_taken[e * csize + c] = 1;
+                    }
+                }
+                __syncthreads();
+                if (s_pick == 0x7fffffff) break;  // nothing comparable left (uniform)
+                got = r + 1;
+            }
+            __syncthreads();
+            ncur = got;
+            cur ^= 1;
+        }
+        if (threadIdx.x == 0) {
+            if (ncur > 0 && s_beam_obj[cur][0] < o_prev) {
+                for (int p = 0; p < M; ++p) codes[(int64_t)n * M + p] = s_beam[cur][0][p];
+                if (num_changed) atomicAdd(num_changed, 1ull);
+            }
+            if (stat_counter) atomicAdd(stat_counter, 1ull);
+        }
+    }
+}
+
+}  // namespace
+
+pv_status pv_launch_exact_scan(pv_ctx *ctx, const pv_layout *l, const float *T,
+                               const float *codebooks, const float *scales, const int32_t *list,
+                               const uint32_t *d_count, int64_t max_count, uint16_t *codes,
+                               int64_t *num_changed, int64_t *d_stat_counter)
+{
+    pv_timed t(ctx, PV_K_EXACT_SCAN);
+    const int g = l->group_size;
+    const int gpr = (int)(l->in_features / g);
+    const int N = (int)pv_num_groups(l);
+    int64_t blocks = (max_count + GPB - 1) / GPB;
+    if (blocks > 4096) blocks = 4096;
+    if (blocks < 1) blocks = 1;
+    hipLaunchKernelGGL(k_exact_scan, dim3((unsigned)blocks), dim3(kBlock), 0, ctx->stream, T,
+                       codebooks, scales, list, d_count, max_count, codes,
+                       reinterpret_cast<unsigned long long *>(num_changed),
+                       reinterpret_cast<unsigned long long *>(d_stat_counter), g, l->nbits, gpr, N);
+    PV_HIP(ctx, hipGetLastError());
+    return PV_OK;
+}
+
+pv_status pv_launch_beam(pv_ctx *ctx, const pv_layout *l, const float *T, const float *codebooks,
+                         const float *scales, const int32_t *group_idx, int64_t k,
+                         int32_t beam_width, uint16_t *codes, int64_t *num_changed)
+{
+    pv_timed t(ctx, PV_K_BEAM);
+    const int g = l->group_size;
+    const int gpr = (int)(l->in_features / g);
+    const int N = (int)pv_num_groups(l);
+    int64_t blocks = k < 16384 ? k : 16384;
+    int64_t *stat = static_cast<int64_t *>(ctx->stats.ptr) + 3;
+    hipLaunchKernelGGL(k_beam, dim3((unsigned)blocks), dim3(kBlock), 0, ctx->stream, T, codebooks,
+                       scales, group_idx, k, beam_width, codes,
+                       reinterpret_cast<unsigned long long *>(num_changed),
+                       reinterpret_cast<unsigned long long *>(stat), g, l->num_codebooks, l->nbits,
+                       gpr, N);
+    PV_HIP(ctx, hipGetLastError());
+    return PV_OK;
+}

@@ -1,0 +1,95 @@
+// Internal declarations shared by the translation units of libpv (not installed).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <vector>
+
+#include "pv.h"
+
+// native 16-byte vector (the nontemporal builtins do not take HIP's float4 struct)
+typedef float pv_f4 __attribute__((ext_vector_type(4)));
+
+// ---------------------------------------------------------------- context
+
+struct pv_buffer {
+    void *ptr = nullptr;
+    size_t bytes = 0;
+};
+
+struct pv_timer {
+    std::vector<hipEvent_t> pending;  // start/stop pairs not yet read back
+    double total_ms = 0.0;
+    int64_t launches = 0;
+};
+
+struct pv_ctx {
+    int device = 0;
+    hipStream_t stream = nullptr;
+    char err[256] = {0};
+    int search_mode = 0;
+    bool timing = false;
+    pv_timer timers[PV_K_COUNT];
+    std::vector<hipEvent_t> event_pool;
+
+    // scratch, grown on demand (never shrunk)
+    pv_buffer sel_scores;   // f32 [N]            group scores when the caller passes none
+    pv_buffer sel_hist;     // u32 [3][2048]      radix-select histograms (kept zero between calls)
+    pv_buffer sel_blocks;   // u32 [nblocks][2]   per-block (greater, equal) counts
+    pv_buffer sel_state;    // u32 [4]            threshold key, ties to take
+    pv_buffer stats;        // i64 [8]            counters of the last re-encode
+    pv_buffer cb_f16;       // prepared codebook operand for the matrix-core filter
+    pv_buffer cb_meta;      // f32/u32 [16]       scale exponent, max norms, rounding bounds
+    pv_buffer x_f16;        // prepared target operand [k_pad][16*NK] halves
+    pv_buffer x_meta;       // f32 [k_pad][4]     per-group bounds and flags
+    pv_buffer partials;     // u32 [k_pad][P][2]  best / runner-up keys per partition
+    pv_buffer fb_list;      // i32 [k] + counter  groups handed to the exact scan
+};
+
+// RAII bracket that records HIP events around a group of launches when timing is on.
+struct pv_timed {
+    pv_ctx *c;
+    int id;
+    hipEvent_t start = nullptr;
+    pv_timed(pv_ctx *ctx, int kernel_id);
+    ~pv_timed();
+};
+
+pv_status pv_fail(pv_ctx *ctx, pv_status st, const char *fmt, ...);
+pv_status pv_ensure(pv_ctx *ctx, pv_buffer &buf, size_t bytes, bool zero_new = false);
+
+#define PV_HIP(ctx, call)                                                              \
+    do {                                                                               \
+        hipError_t e_ = (call);                                                        \
+        if (e_ != hipSuccess)                                                          \
+            return pv_fail(ctx, PV_ERR_DEVICE, "%s: %s", #call, hipGetErrorString(e_)); \
+    } while (0)
+
+static inline int64_t pv_num_groups(const pv_layout *l)
+{
+    return l->out_features * (l->in_features / l->group_size);
+}
+
+// ---------------------------------------------------------------- launchers
+// (each enqueues on ctx->stream; arguments were validated by the caller)
+
+pv_status pv_launch_encode_targets(pv_ctx *ctx, const float *W, const float *G, float alpha,
+                                   float *T, int64_t n);
+pv_status pv_launch_dequantize(pv_ctx *ctx, const pv_layout *l, const uint16_t *codes,
+                               const float *codebooks, const float *scales, float *W_out);
+pv_status pv_launch_select(pv_ctx *ctx, const pv_layout *l, const float *T, const float *W,
+                           int64_t k, int32_t *out_idx, float *scores);
+pv_status pv_launch_exact_scan(pv_ctx *ctx, const pv_layout *l, const float *T,
+                               const float *codebooks, const float *scales,
+                               const int32_t *list, const uint32_t *d_count, int64_t max_count,
+                               uint16_t *codes, int64_t *num_changed, int64_t *d_stat_counter);
+pv_status pv_launch_beam(pv_ctx *ctx, const pv_layout *l, const float *T, const float *codebooks,
+                         const float *scales, const int32_t *group_idx, int64_t k,
+                         int32_t beam_width, uint16_t *codes, int64_t *num_changed);
+bool pv_mfma_supported(const pv_layout *l);
+pv_status pv_launch_mfma_search(pv_ctx *ctx, const pv_layout *l, const float *T,
+                                const float *codebooks, const float *scales,
+                                const int32_t *group_idx, int64_t k, uint16_t *codes,
+                                int64_t *num_changed);
+pv_status pv_launch_fill_i64(pv_ctx *ctx, int64_t *p, int64_t n, int64_t value);

@@ -1,0 +1,144 @@
+// HBM-bound streaming kernels: target formation (Eq. 7) and dequantisation
+// (Alg. 3 line 1).  One pass over memory each, 16-byte accesses per lane,
+// consecutive lanes on consecutive addresses.
+#include "pv_internal.h"
+
+namespace {
+
+constexpr int kBlock = 256;
+
+// T = W - alpha * G with a single rounding per element.
+// Each block covers kUnroll * kBlock consecutive pv_f4; the (< 4) tail floats
+// are handled by the last thread that has no full vector.
+constexpr int kUnroll = 4;
+
+__global__ __launch_bounds__(kBlock) void k_encode_targets(const float *W,
+                                                           const float *G,
+                                                           float *T, int64_t n,
+                                                           float alpha)
+{
+    const int64_t n4 = n >> 2;
+    const pv_f4 *W4 = reinterpret_cast<const pv_f4 *>(W);
+    const pv_f4 *G4 = reinterpret_cast<const pv_f4 *>(G);
+    pv_f4 *T4 = reinterpret_cast<pv_f4 *>(T);
+    const int64_t base = (int64_t)blockIdx.x * (kUnroll * kBlock) + threadIdx.x;
+    pv_f4 w[kUnroll], g[kUnroll];
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+        int64_t i = base + (int64_t)u * kBlock;
+        if (i < n4) {
+            w[u] = __builtin_nontemporal_load(&W4[i]);
+            g[u] = __builtin_nontemporal_load(&G4[i]);
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < kUnroll; ++u) {
+        int64_t i = base + (int64_t)u * kBlock;
+        if (i < n4) {
+            pv_f4 t;
+            t.x = fmaf(-alpha, g[u].x, w[u].x);
+            t.y = fmaf(-alpha, g[u].y, w[u].y);
+            t.z = fmaf(-alpha, g[u].z, w[u].z);
+            t.w = fmaf(-alpha, g[u].w, w[u].w);
+            T4[i] = t;
+        }
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0)
+        for (int64_t i = n4 << 2; i < n; ++i) T[i] = fmaf(-alpha, G[i], W[i]);
+}
+
+// One thread per VEC consecutive weights of a group: reads the group's code(s),
+// gathers VEC floats of each codeword (the codebook stays in L2), adds them in
+// codebook order, multiplies by the row scale, writes VEC floats.
+template <int VEC>
+__global__ __launch_bounds__(kBlock) void k_dequantize(const uint16_t *__restrict__ codes,
+                                                       const float *__restrict__ codebooks,
+                                                       const float *__restrict__ scales,
+                                                       float *__restrict__ W_out, int64_t total,
+                                                       int g, int M, int nbits, int gpr)
+{
+    const int64_t idx = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (idx >= total) return;
+    const int parts = g / VEC;
+    const int n = (int)(idx / parts);
+    const int q = (int)(idx - (int64_t)n * parts);
+    const int o = n / gpr;
+    const unsigned mask = (1u << nbits) - 1u;
+    const int64_t csize = (int64_t)1 << nbits;
+    const float s = scales[o];
+    const uint16_t *cp = codes + (int64_t)n * M;
+    if constexpr (VEC == 4) {
+        const pv_f4 *cb4 = reinterpret_cast<const pv_f4 *>(codebooks);
+        pv_f4 acc = cb4[((int64_t)(cp[0] & mask) * g) / 4 + q];
+        for (int m = 1; m < M; ++m) {
+            pv_f4 c = cb4[((m * csize + (cp[m] & mask)) * g) / 4 + q];
+            acc.x = acc.x + c.x;
+            acc.y = acc.y + c.y;
+            acc.z = acc.z + c.z;
+            acc.w = acc.w + c.w;
+        }
+        pv_f4 out;
+        out.x = s * acc.x;
+        out.y = s * acc.y;
+        out.z = s * acc.z;
+        out.w = s * acc.w;
+        __builtin_nontemporal_store(out, &reinterpret_cast<pv_f4 *>(W_out)[idx]);
+    } else {
+        float acc = codebooks[(int64_t)(cp[0] & mask) * g + q];
+        for (int m = 1; m < M; ++m) acc = acc + codebooks[(m * csize + (cp[m] & mask)) * g + q];
+        W_out[idx] = s * acc;
+    }
+}
+
+__global__ void k_fill_i64(int64_t *p, int64_t n, int64_t v)
+{
+    int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+}  // namespace
+
+pv_status pv_launch_encode_targets(pv_ctx *ctx, const float *W, const float *G, float alpha,
+                                   float *T, int64_t n)
+{
+    pv_timed t(ctx, PV_K_ENCODE_TARGETS);
+    int64_t n4 = n >> 2;
+    int64_t blocks = (n4 + kUnroll * kBlock - 1) / (kUnroll * kBlock);
+    if (blocks < 1) blocks = 1;
+    hipLaunchKernelGGL(k_encode_targets, dim3((unsigned)blocks), dim3(kBlock), 0, ctx->stream, W, G,
+                       T, n, alpha);
+    PV_HIP(ctx, hipGetLastError());
+    return PV_OK;
+}
+
+pv_status pv_launch_dequantize(pv_ctx *ctx, const pv_layout *l, const uint16_t *codes,
+                               const float *codebooks, const float *scales, float *W_out)
+{
+    pv_timed t(ctx, PV_K_DEQUANTIZE);
+    const int g = l->group_size;
+    const int64_t N = pv_num_groups(l);
+    const int gpr = (int)(l->in_features / g);
+    if (g % 4 == 0) {
+        int64_t total = N * (g / 4);
+        int64_t blocks = (total + kBlock - 1) / kBlock;
+        hipLaunchKernelGGL(k_dequantize<4>, dim3((unsigned)blocks), dim3(kBlock), 0, ctx->stream,
+                           codes, codebooks, scales, W_out, total, g, l->num_codebooks, l->nbits,
+                           gpr);
+    } else {
+        int64_t total = N * g;
+        int64_t blocks = (total + kBlock - 1) / kBlock;
+        hipLaunchKernelGGL(k_dequantize<1>, dim3((unsigned)blocks), dim3(kBlock), 0, ctx->stream,
+                           codes, codebooks, scales, W_out, total, g, l->num_codebooks, l->nbits,
+                           gpr);
+    }
+    PV_HIP(ctx, hipGetLastError());
+    return PV_OK;
+}
+
+pv_status pv_launch_fill_i64(pv_ctx *ctx, int64_t *p, int64_t n, int64_t value)
+{
+    hipLaunchKernelGGL(k_fill_i64, dim3((unsigned)((n + 63) / 64)), dim3(64), 0, ctx->stream, p, n,
+                       value);
+    PV_HIP(ctx, hipGetLastError());
+    return PV_OK;
+}

@@ -1,0 +1,76 @@
+"""Shared plumbing of the GPU parity tests: move a workload to the device, run
+the library calls through the C ABI binding, bring results back as numpy."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from paper_2405_14852_amd import Layout, PVContext
+
+DEV = torch.device("cuda:0")
+
+
+def lay_of(wl) -> Layout:
+    l = wl.layout
+    return Layout(l.out_features, l.in_features, l.group_size, l.num_codebooks, l.nbits)
+
+
+def dev_f32(a):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(DEV)
+
+
+def dev_u16(a):
+    a = np.ascontiguousarray(a, dtype=np.uint16)
+    return torch.from_numpy(a.view(np.int16)).to(DEV).view(torch.uint16)
+
+
+def dev_i32(a):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(DEV)
+
+
+def host_u16(t):
+    return t.view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+class GpuRun:
+    """Device copies of one workload plus the four calls."""
+
+    def __init__(self, wl, ctx: PVContext | None = None):
+        self.wl = wl
+        self.lay = lay_of(wl)
+        self.ctx = ctx or PVContext(0)
+        self.W = dev_f32(wl.W)
+        self.G = dev_f32(wl.G)
+        self.cb = dev_f32(wl.codebooks)
+        self.sc = dev_f32(wl.scales)
+        self.codes = dev_u16(wl.codes)
+
+    def targets(self, alpha=None):
+        T = torch.empty_like(self.W)
+        self.ctx.pv_encode_targets(self.lay, self.W, self.G,
+                                   self.wl.alpha if alpha is None else alpha, T)
+        return T
+
+    def select(self, T, k, want_scores=False, W=None):
+        idx = torch.empty(max(k, 1), dtype=torch.int32, device=DEV)
+        sc = torch.empty(self.lay.num_groups, dtype=torch.float32, device=DEV) if want_scores else None
+        self.ctx.pv_select_topk_groups(self.lay, T, self.W if W is None else W, k, idx, sc)
+        torch.cuda.synchronize()
+        idx = idx[:k].cpu().numpy()
+        return (idx, sc.cpu().numpy()) if want_scores else idx
+
+    def reencode(self, T, idx_np, beam_width=None, codes=None):
+        idx = dev_i32(idx_np)
+        codes = self.codes.clone() if codes is None else codes
+        nch = torch.full((1,), -7, dtype=torch.int64, device=DEV)
+        self.ctx.pv_reencode_groups(self.lay, T, self.cb, self.sc, idx, len(idx_np),
+                                    self.wl.beam_width if beam_width is None else beam_width,
+                                    codes, nch)
+        torch.cuda.synchronize()
+        return host_u16(codes), int(nch.item())
+
+    def dequantize(self, codes_np):
+        W = torch.empty_like(self.W)
+        self.ctx.pv_dequantize(self.lay, dev_u16(codes_np), self.cb, self.sc, W)
+        torch.cuda.synchronize()
+        return W.cpu().numpy()

@@ -1,0 +1,255 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element
+by element on the same seeded inputs.
+
+Bars: targets, group scores, selected ids, dequantised weights: bit-exact.
+Codes: bit-exact, except on groups the oracle flags as near-ties (best two
+objectives closer than 1e-6 relative), where the GPU's choice must be within
+1e-6 relative of the oracle's objective when evaluated in oracle arithmetic.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads
+from gpu_util import DEV, GpuRun, dev_f32, dev_u16, host_u16
+
+pytestmark = pytest.mark.gpu
+
+NEAR_TIE_REL = 1e-6   # spec tolerance for differing codes
+RECON_REL = 1e-5      # spec tolerance for reconstructed weights (relative L2)
+
+
+def check_codes(wl, T_np, idx, got, want, info):
+    M = wl.layout.num_codebooks
+    g2, w2 = got.reshape(-1, M), want.reshape(-1, M)
+    mask = np.ones(len(g2), bool)
+    mask[idx] = False
+    assert np.array_equal(g2[mask], wl.codes.reshape(-1, M)[mask]), "unselected codes changed"
+    diff = np.nonzero((g2[idx] != w2[idx]).any(1))[0]
+    if len(diff) == 0:
+        return 0
+    assert info["near_tie"][diff].all(), f"{len(diff)} differing groups, not all near-ties"
+    obj = oracle.group_objective(T_np, wl.codebooks, wl.scales, idx[diff], g2[idx[diff]])
+    ref = info["obj_new"][diff]
+    assert (np.abs(obj - ref) <= NEAR_TIE_REL * np.maximum(ref, 1e-300)).all()
+    return len(diff)
+
+
+# ------------------------------------------------------------------ targets
+
+@pytest.mark.parametrize("shape,g", [((3, 6), 2), ((256, 256), 8), ((37, 1048), 8), ((1, 4), 1),
+                                     ((129, 4100), 4)])
+@pytest.mark.parametrize("alpha", [1.0, 0.37, 0.0])
+def test_encode_targets_bit_exact(shape, g, alpha):
+    wl = workloads.make(shape[0], shape[1], g, 1, 4, seed=1)
+    run = GpuRun(wl)
+    T = run.targets(alpha).cpu().numpy()
+    ref = oracle.encode_targets(wl.W, wl.G, alpha)
+    assert np.array_equal(T.view(np.uint32), ref.view(np.uint32))
+
+
+def test_encode_targets_in_place():
+    wl = workloads.make(64, 512, 8, 1, 4, seed=2)
+    run = GpuRun(wl)
+    ref = oracle.encode_targets(wl.W, wl.G, 0.5)
+    W = run.W.clone()
+    run.ctx.pv_encode_targets(run.lay, W, run.G, 0.5, W)
+    assert np.array_equal(W.cpu().numpy(), ref)
+
+
+# --------------------------------------------------------------- dequantize
+
+@pytest.mark.parametrize("g,M,B", [(8, 1, 8), (8, 2, 8), (16, 1, 12), (8, 1, 16), (2, 1, 3),
+                                   (6, 3, 4), (1, 1, 2), (4, 2, 5)])
+def test_dequantize_bit_exact(g, M, B):
+    wl = workloads.make(67, 24 * g, g, M, B, seed=3)
+    run = GpuRun(wl)
+    W = run.dequantize(wl.codes)
+    ref = oracle.dequantize(wl.codes, wl.codebooks, wl.scales)
+    assert np.array_equal(W.view(np.uint32), ref.view(np.uint32))
+
+
+# ---------------------------------------------------------------- selection
+
+@pytest.mark.parametrize("shape,g", [((256, 256), 8), ((61, 1000), 8), ((33, 4096), 16),
+                                     ((5, 12), 1), ((100, 36), 6)])
+@pytest.mark.parametrize("frac", [0.0, 0.01, 0.3, 1.0])
+def test_select_matches_oracle(shape, g, frac):
+    wl = workloads.make(shape[0], shape[1], g, 1, 4, seed=4, sigma_g=1e-3)
+    run = GpuRun(wl)
+    T = run.targets()
+    N = wl.layout.num_groups
+    k = int(frac * N)
+    idx, scores = run.select(T, k, want_scores=True)
+    T_ref = oracle.encode_targets(wl.W, wl.G, wl.alpha)
+    idx_ref, sc_ref = oracle.select_topk_groups(T_ref, wl.W, g, k, return_scores=True)
+    assert np.array_equal(scores.view(np.uint32), sc_ref.view(np.uint32))
+    assert np.array_equal(idx, idx_ref)
+    # a second call on the same context (histograms must have been left clean)
+    idx2 = run.select(T, max(1, k // 2))
+    assert np.array_equal(idx2, oracle.select_topk_groups(T_ref, wl.W, g, max(1, k // 2)))
+
+
+def test_select_ties_lowest_id_first():
+    wl = workloads.make(64, 512, 8, 1, 4, seed=5)
+    N = wl.layout.num_groups
+    W = np.zeros_like(wl.W)
+    T = np.zeros_like(wl.W)
+    Tg = T.reshape(N, 8)
+    Tg[:, 0] = 1.0                       # all scores equal ...
+    Tg[np.arange(0, N, 7), 1] = 2.0      # ... except a higher tier
+    run = GpuRun(wl)
+    Td, Wd = dev_f32(T), dev_f32(W)
+    for k in (1, 5, N // 7 + 1, N // 7 + 2, N // 2, N - 1, N):
+        idx = run.select(Td, k, W=Wd)
+        assert np.array_equal(idx, oracle.select_topk_groups(T, W, 8, k)), k
+
+
+def test_select_all_zero_scores():
+    wl = workloads.make(16, 256, 8, 1, 4, seed=6)
+    run = GpuRun(wl)
+    idx = run.select(run.W, 10)          # T == W: every score is +0
+    assert np.array_equal(idx, np.arange(10, dtype=np.int32))
+
+
+# ---------------------------------------------------------- re-encode, M = 1
+
+def reencode_case(wl, mode, idx=None, T_np=None):
+    run = GpuRun(wl)
+    run.ctx.pv_set_search_mode(mode)
+    if T_np is None:
+        T_np = oracle.encode_targets(wl.W, wl.G, wl.alpha)
+    if idx is None:
+        idx = oracle.select_topk_groups(T_np, wl.W, wl.layout.group_size, wl.k)
+    got, nch = run.reencode(dev_f32(T_np), idx)
+    want, info = oracle.reencode_groups(T_np, wl.codebooks, wl.scales, idx, wl.codes,
+                                        beam_width=wl.beam_width)
+    ndiff = check_codes(wl, T_np, idx, got, want, info)
+    if ndiff == 0:
+        assert nch == info["num_changed"]
+    return run, got, want, info
+
+
+@pytest.mark.parametrize("mode", [1, 0])
+@pytest.mark.parametrize("g,B,shape,tau", [
+    (8, 8, (256, 256), 1.0),        # config 1 as stated
+    (8, 16, (64, 1024), 0.3),       # 1x16, several tiles + ragged tail of selected groups
+    (16, 16, (48, 1024), 0.4),      # 1-bit config shape
+    (8, 12, (32, 264), 1.0),
+    (16, 5, (16, 256), 1.0),
+    (4, 3, (8, 64), 1.0),
+    (1, 2, (4, 16), 1.0),
+    (8, 1, (4, 64), 1.0),
+])
+def test_reencode_m1_matches_oracle(mode, g, B, shape, tau):
+    wl = workloads.make(shape[0], shape[1], g, 1, B, seed=7, sigma_g=2e-3, tau=tau)
+    reencode_case(wl, mode)
+
+
+@pytest.mark.parametrize("mode", [1, 0])
+def test_reencode_m1_scale_edge_cases(mode):
+    wl = workloads.make(32, 512, 8, 1, 10, seed=8, sigma_g=2e-3, tau=1.0)
+    wl.scales[3] = 0.0          # every code ties: previous code kept
+    wl.scales[5] = -0.9         # negative scale
+    wl.scales[7] = 1e-6         # targets far outside the codebook's range after normalisation
+    wl.scales[9] = 300.0
+    _, got, want, _ = reencode_case(wl, mode)
+    gpr = wl.layout.groups_per_row
+    assert np.array_equal(got.reshape(-1)[3 * gpr:4 * gpr], wl.codes.reshape(-1)[3 * gpr:4 * gpr])
+
+
+@pytest.mark.parametrize("mode", [1, 0])
+def test_reencode_m1_duplicate_codewords_tie_rule(mode):
+    wl = workloads.make(16, 256, 8, 1, 8, seed=9, sigma_g=2e-3, tau=1.0)
+    wl.codebooks[0, 128:] = wl.codebooks[0, :128]       # every codeword exists twice
+    _, got, want, info = reencode_case(wl, mode)
+    assert np.array_equal(got, want)                     # exact ties resolve identically
+
+
+@pytest.mark.parametrize("mode", [1, 0])
+def test_reencode_fixed_point_when_update_is_zero(mode):
+    wl = workloads.make(32, 512, 8, 1, 12, seed=10, tau=1.0)
+    W = oracle.dequantize(wl.codes, wl.codebooks, wl.scales)
+    wl.W[:] = W
+    run = GpuRun(wl)
+    run.ctx.pv_set_search_mode(mode)
+    T = run.targets(0.0)
+    got, nch = run.reencode(T, np.arange(wl.layout.num_groups, dtype=np.int32))
+    assert nch == 0 and np.array_equal(got, wl.codes)
+
+
+def test_reencode_empty_selection_and_errors():
+    from paper_2405_14852_amd import PVError
+    wl = workloads.make(8, 64, 8, 1, 4, seed=11)
+    run = GpuRun(wl)
+    T = run.targets()
+    got, nch = run.reencode(T, np.zeros(0, np.int32))
+    assert nch == 0 and np.array_equal(got, wl.codes)
+    with pytest.raises(PVError):
+        run.ctx.pv_reencode_groups(run.lay, T, run.cb, run.sc,
+                                   torch.zeros(4, dtype=torch.int32, device=DEV),
+                                   wl.layout.num_groups + 1, 1, run.codes)
+    with pytest.raises(PVError):
+        run.ctx.pv_reencode_groups(run.lay, T, run.cb, run.sc, None, 0, 0, run.codes)
+    bad = type(run.lay)(8, 60, 8, 1, 4)
+    with pytest.raises(PVError):
+        run.ctx.pv_encode_targets(bad, run.W, run.G, 1.0, T)
+    with pytest.raises(PVError):
+        run.ctx.pv_select_topk_groups(run.lay, T, run.W, -1,
+                                      torch.zeros(4, dtype=torch.int32, device=DEV))
+    bad = type(run.lay)(8, 64, 8, 1, 17)
+    with pytest.raises(PVError):
+        run.ctx.pv_dequantize(bad, run.codes, run.cb, run.sc, T)
+
+
+# ------------------------------------------------------- re-encode, beam search
+
+@pytest.mark.parametrize("M,B,g,beam,shape", [
+    (2, 8, 8, 8, (64, 256)),     # the 2x8 configuration, beam 8
+    (2, 8, 8, 1, (16, 256)),
+    (2, 8, 8, 3, (16, 256)),
+    (3, 4, 8, 8, (16, 128)),
+    (2, 5, 16, 16, (8, 256)),
+    (4, 3, 4, 4, (8, 64)),
+    (2, 2, 2, 64, (4, 32)),
+])
+def test_reencode_beam_matches_oracle(M, B, g, beam, shape):
+    wl = workloads.make(shape[0], shape[1], g, M, B, seed=12, sigma_g=2e-3, tau=0.5,
+                        beam_width=beam)
+    reencode_case(wl, 0)
+
+
+def test_reencode_beam_duplicate_codewords():
+    wl = workloads.make(8, 256, 8, 2, 6, seed=13, sigma_g=2e-3, tau=1.0, beam_width=4)
+    wl.codebooks[:, 32:] = wl.codebooks[:, :32]
+    _, got, want, _ = reencode_case(wl, 0)
+    assert np.array_equal(got, want)
+
+
+# ------------------------------------------------------------- whole path
+
+@pytest.mark.parametrize("name,shape", [("c1_256x256_1x8", None),
+                                        ("c2_4096x4096_1x16", (128, 1024)),
+                                        ("c3_11008x4096_2x8", (96, 512)),
+                                        ("c5a_14336x4096_1x16g16", (64, 2048))])
+def test_whole_path_small(name, shape):
+    kw = {} if shape is None else dict(out_features=shape[0], in_features=shape[1], tau=0.2)
+    wl = workloads.make_config(name, seed=0, **kw)
+    run = GpuRun(wl)
+    g = wl.layout.group_size
+    T = run.targets()
+    T_ref = oracle.encode_targets(wl.W, wl.G, wl.alpha)
+    assert np.array_equal(T.cpu().numpy(), T_ref)
+    idx = run.select(T, wl.k)
+    idx_ref = oracle.select_topk_groups(T_ref, wl.W, g, wl.k)
+    assert np.array_equal(idx, idx_ref)
+    got, _ = run.reencode(T, idx)
+    want, info = oracle.reencode_groups(T_ref, wl.codebooks, wl.scales, idx_ref, wl.codes,
+                                        beam_width=wl.beam_width)
+    check_codes(wl, T_ref, idx_ref, got, want, info)
+    assert (info["obj_new"] <= info["obj_prev"]).all()
+    W2 = run.dequantize(want)
+    W2_ref = oracle.dequantize(want, wl.codebooks, wl.scales)
+    rel = np.linalg.norm((W2 - W2_ref).astype(np.float64)) / np.linalg.norm(W2_ref.astype(np.float64))
+    assert rel <= RECON_REL and np.array_equal(W2, W2_ref)
