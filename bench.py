@@ -1,0 +1,188 @@
+#!/usr/bin/env python3
+"""Benchmark of the V-step re-encoding path on one MI355X.
+
+One "step" is one pass of the whole hot path over one weight matrix:
+    dequantize(codes) -> T = W - alpha*G -> select top-k groups -> re-encode
+    the selected groups -> dequantize(updated codes)
+on the 1x16 configuration (Llama-2-7B q_proj shape, 4096 x 4096, group 8, one
+codebook of 2^16 codewords, tau = 0.01 -> 20 971 groups re-encoded).
+
+All inputs are resident in HBM before the timed region.  Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+from pathlib import Path
+
+ROOT = Path(__file__).resolve().parent
+if str(ROOT) not in sys.path:
+    sys.path.insert(0, str(ROOT))
+
+PEAK_MFMA_F16 = 2500.0   # TFLOP/s dense fp16/bf16 matrix-core peak of MI355X
+PEAK_HBM = 8000.0        # GB/s
+PEAK_F64 = 78.6          # TFLOP/s fp64 vector (256 CU x 4 SIMD x 16 lanes x 2 (fma) x 2.4 GHz)
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="c2_4096x4096_1x16")
+    ap.add_argument("--search-mode", type=int, default=0,
+                    help="0 = matrix-core filter + exact re-rank, 1 = exact scan only")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on exactly one GPU (--gpus 1); the path shards by "
+              "matrix or by rows with no exchange inside the V step, see DESIGN.md", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+
+    import workloads
+    from paper_2405_14852_amd import Layout, PVContext
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    dev = torch.device("cuda:0")
+    wl = workloads.make_config(args.workload, seed=0)
+    L = wl.layout
+    lay = Layout(L.out_features, L.in_features, L.group_size, L.num_codebooks, L.nbits)
+    k = wl.k
+    ctx = PVContext(0)
+    ctx.pv_set_search_mode(args.search_mode)
+
+    W = torch.from_numpy(wl.W).to(dev)
+    G = torch.from_numpy(wl.G).to(dev)
+    cb = torch.from_numpy(wl.codebooks).to(dev)
+    sc = torch.from_numpy(wl.scales).to(dev)
+    codes0 = torch.from_numpy(wl.codes.view(np.int16)).to(dev).view(torch.uint16)
+    codes = codes0.clone()
+    T = torch.empty_like(W)
+    Wq = torch.empty_like(W)
+    idx = torch.empty(k, dtype=torch.int32, device=dev)
+    nch = torch.zeros(1, dtype=torch.int64, device=dev)
+
+    def step():
+        codes.view(torch.int16).copy_(codes0.view(torch.int16))   # same work every step
+        ctx.pv_dequantize(lay, codes, cb, sc, Wq)
+        ctx.pv_encode_targets(lay, W, G, wl.alpha, T)
+        ctx.pv_select_topk_groups(lay, T, W, k, idx)
+        ctx.pv_reencode_groups(lay, T, cb, sc, idx, k, wl.beam_width, codes, nch)
+        ctx.pv_dequantize(lay, codes, cb, sc, Wq)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = 1e3 * dt / args.steps
+    changed = int(nch.item())
+    stats = ctx.pv_reencode_stats()
+
+    # second timed region with HIP events around every kernel group (per-kernel durations)
+    ctx.pv_timing_enable(True)
+    ctx.pv_timing_reset()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    kern = {}
+    for name in ("dequantize", "encode_targets", "group_scores", "select", "prep", "score_mfma",
+                 "rerank", "exact_scan", "beam"):
+        ms, n = ctx.pv_timing_read(name)
+        if n:
+            kern[name] = {"ms_per_step": ms / args.steps, "launches_per_step": n / args.steps,
+                          "avg_ms": ms / n}
+    ctx.pv_timing_enable(False)
+
+    g, B, M = L.group_size, L.nbits, L.num_codebooks
+    params = L.out_features * L.in_features
+    reenc_ms = sum(kern[n]["ms_per_step"] for n in ("prep", "score_mfma", "rerank", "exact_scan", "beam")
+                   if n in kern)
+    dominant = max(kern, key=lambda n: kern[n]["ms_per_step"])
+    flops_contraction = 2.0 * k * (1 << B) * g * M            # algorithmic: 2*g*2^B per group
+    roofline = None
+    if dominant == "score_mfma":
+        a = flops_contraction / (kern[dominant]["avg_ms"] * 1e-3) / 1e12
+        roofline = {"kernel": "k_score_mfma", "bound": "mfma", "achieved": a, "peak": PEAK_MFMA_F16,
+                    "unit": "TFLOP/s", "frac": a / PEAK_MFMA_F16, "traffic": None}
+    elif dominant in ("exact_scan", "beam"):
+        # double-precision ALU work per scored tuple: g * (mul, sub, mul, add) (+ g adds per extra codebook)
+        tuples = k * ((1 << B) if M == 1 else (1 << B) * (1 + (M - 1) * wl.beam_width))
+        fl = tuples * g * (4.0 + (M - 1))
+        a = fl / (kern[dominant]["avg_ms"] * 1e-3) / 1e12
+        roofline = {"kernel": "k_" + dominant, "bound": "alu", "achieved": a, "peak": PEAK_F64,
+                    "unit": "TFLOP/s", "frac": a / PEAK_F64, "traffic": None}
+    else:
+        per_param = {"encode_targets": 12.0, "group_scores": 8.0 + 4.0 / g,
+                     "dequantize": 4.0 + 2.0 * M / g}.get(dominant, 0.0)
+        a = per_param * params / (kern[dominant]["avg_ms"] * 1e-3) / 1e9
+        roofline = {"kernel": "k_" + dominant, "bound": "hbm", "achieved": a, "peak": PEAK_HBM,
+                    "unit": "GB/s", "frac": a / PEAK_HBM, "traffic": None}
+
+    hbm = {}
+    for name, per_param in (("encode_targets", 12.0), ("group_scores", 8.0 + 4.0 / g),
+                            ("dequantize", 4.0 + 2.0 * M / g)):
+        if name in kern:
+            hbm[name + "_GBps"] = per_param * params / (kern[name]["avg_ms"] * 1e-3) / 1e9
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        import oracle
+        t1 = time.perf_counter()
+        Wq_ref = oracle.dequantize(wl.codes, wl.codebooks, wl.scales)
+        T_ref = oracle.encode_targets(wl.W, wl.G, wl.alpha)
+        idx_ref = oracle.select_topk_groups(T_ref, wl.W, g, k)
+        # bounded sample of the search: cost per group is data-independent
+        sample = idx_ref if M == 1 and k * (1 << B) * g <= 3e10 else idx_ref[:: max(1, len(idx_ref) // 4096)]
+        t2 = time.perf_counter()
+        new_ref, info = oracle.reencode_groups(T_ref, wl.codebooks, wl.scales, sample, wl.codes,
+                                               beam_width=wl.beam_width)
+        t3 = time.perf_counter()
+        oracle.dequantize(new_ref, wl.codebooks, wl.scales)
+        t4 = time.perf_counter()
+        stream_s = (t2 - t1) + (t4 - t3)
+        search_s = (t3 - t2) * (k / len(sample))
+        cpu = {"value": k / (stream_s + search_s), "unit": "groups/s", "cores": oracle.num_threads(),
+               "kind": "oracle",
+               "sample": f"one whole step of {args.workload}; search timed on {len(sample)} of {k} "
+                         f"selected groups and scaled ({t3 - t2:.2f} s measured), streaming parts "
+                         f"in full ({stream_s:.2f} s)"}
+        if len(sample) == k:
+            got = codes.view(torch.int16).cpu().numpy().view(np.uint16)
+            cpu["codes_equal_oracle"] = bool(np.array_equal(got, new_ref))
+
+    out = {
+        "metric": "groups_reencoded_per_s", "value": k / (ms_per_step * 1e-3), "unit": "groups/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16" if "score_mfma" in kern else "f64", "data": "synthetic",
+        "config": {"workload": args.workload, "out_features": L.out_features,
+                   "in_features": L.in_features, "group_size": g, "num_codebooks": M, "nbits": B,
+                   "tau": wl.tau, "k_selected": k, "beam_width": wl.beam_width,
+                   "search_mode": args.search_mode},
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "reencode_only_groups_per_s": k / (reenc_ms * 1e-3) if reenc_ms else None,
+        "scoring_algorithmic_TFLOPs": (flops_contraction / (kern["score_mfma"]["avg_ms"] * 1e-3) / 1e12
+                                       if "score_mfma" in kern else None),
+        "scoring_frac_of_mfma_peak": (flops_contraction / (kern["score_mfma"]["avg_ms"] * 1e-3) / 1e12
+                                      / PEAK_MFMA_F16 if "score_mfma" in kern else None),
+        "hbm": hbm, "kernels": kern, "groups_changed": changed, "reencode_stats": stats,
+    }
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

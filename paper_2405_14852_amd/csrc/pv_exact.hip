@@ -20,6 +20,12 @@ struct best_t {
     int idx;
 };
 
+struct part_t {
+    double obj;
+    int idx;
+    int pad;
+};
+
 __device__ __forceinline__ bool better(double o1, int i1, double o2, int i2)
 {
     return o1 < o2 || (o1 == o2 && i1 < i2);
@@ -73,7 +79,7 @@ __global__ __launch_bounds__(kBlock) void k_exact_scan(
     const float *__restrict__ scales, const int32_t *__restrict__ list,
     const uint32_t *__restrict__ d_count, int64_t max_count, uint16_t *__restrict__ codes,
     unsigned long long *__restrict__ num_changed, unsigned long long *__restrict__ stat_counter,
-    int g, int nbits, int gpr, int N)
+    int g, int nbits, int gpr, int N, int nsplit, part_t *__restrict__ partial)
 {
     __shared__ float s_t[GPB][kMaxG];
     __shared__ float s_scale[GPB];
@@ -82,7 +88,12 @@ __global__ __launch_bounds__(kBlock) void k_exact_scan(
     __shared__ int s_idx[kBlock / 64];
     const int64_t count = d_count ? (int64_t)*d_count : max_count;
     const int csize = 1 << nbits;
-    for (int64_t base = (int64_t)blockIdx.x * GPB; base < count; base += (int64_t)gridDim.x * GPB) {
+    const int64_t quads = (count + GPB - 1) / GPB;
+    for (int64_t w = blockIdx.x; w < quads * nsplit; w += gridDim.x) {
+        const int64_t base = (w / nsplit) * GPB;
+        const int piece = (int)(w % nsplit);
+        const int c_begin = (int)((int64_t)piece * csize / nsplit);
+        const int c_end = (int)((int64_t)(piece + 1) * csize / nsplit);
         __syncthreads();
         if (threadIdx.x < GPB) {
             int64_t j = base + threadIdx.x;
@@ -104,7 +115,7 @@ __global__ __launch_bounds__(kBlock) void k_exact_scan(
             best[q].obj = kInf;
             best[q].idx = 0x7fffffff;
         }
-        for (int c = threadIdx.x; c < csize; c += kBlock) {
+        for (int c = c_begin + threadIdx.x; c < c_end; c += kBlock) {
             const float *cw = codebook + (int64_t)c * g;
             double obj[GPB];
 #pragma unroll
@@ -127,6 +138,16 @@ __global__ __launch_bounds__(kBlock) void k_exact_scan(
 #pragma unroll
         for (int q = 0; q < GPB; ++q) {
             best_t b = block_min(best[q], s_obj, s_idx);
+            if (nsplit > 1) {
+                if (threadIdx.x == 0 && s_group[q] >= 0) {
+                    part_t pt;
+                    pt.obj = b.obj;
+                    pt.idx = b.idx;
+                    pt.pad = 0;
+                    partial[(base + q) * nsplit + piece] = pt;
+                }
+                continue;
+            }
             if (threadIdx.x == 0 && s_group[q] >= 0) {
                 const int n = s_group[q];
                 const int prev = codes[n] & (csize - 1);
@@ -145,6 +166,50 @@ __global__ __launch_bounds__(kBlock) void k_exact_scan(
                 if (stat_counter) atomicAdd(stat_counter, 1ull);
             }
         }
+    }
+}
+
+// Combine the per-piece minima of the split scan (pieces are ascending codeword
+// ranges, so lexicographic (obj, idx) order keeps the lowest index) and apply
+// the tie rule against the previous code.
+__global__ __launch_bounds__(kBlock) void k_exact_finalize(
+    const float *__restrict__ T, const float *__restrict__ codebook,
+    const float *__restrict__ scales, const int32_t *__restrict__ list,
+    const uint32_t *__restrict__ d_count, int64_t max_count, uint16_t *__restrict__ codes,
+    unsigned long long *__restrict__ num_changed, unsigned long long *__restrict__ stat_counter,
+    int g, int nbits, int gpr, int N, int nsplit, const part_t *__restrict__ partial)
+{
+    const int64_t count = d_count ? (int64_t)*d_count : max_count;
+    const int csize = 1 << nbits;
+    for (int64_t j = (int64_t)blockIdx.x * kBlock + threadIdx.x; j < count;
+         j += (int64_t)gridDim.x * kBlock) {
+        const int n = list[j];
+        if (n < 0 || n >= N) continue;
+        best_t b;
+        b.obj = kInf;
+        b.idx = 0x7fffffff;
+        for (int p = 0; p < nsplit; ++p) {
+            part_t pt = partial[j * nsplit + p];
+            if (better(pt.obj, pt.idx, b.obj, b.idx)) {
+                b.obj = pt.obj;
+                b.idx = pt.idx;
+            }
+        }
+        const float s = scales[n / gpr];
+        const int prev = codes[n] & (csize - 1);
+        double o_prev = 0.0;
+        for (int i = 0; i < g; ++i) {
+            double acc = (double)codebook[(int64_t)prev * g + i];
+            double r = (double)s * acc - (double)T[(int64_t)n * g + i];
+            o_prev = o_prev + r * r;
+        }
+        int pick = b.idx;
+        if (o_prev == b.obj || pick == 0x7fffffff) pick = prev;
+        if (pick != prev) {
+            codes[n] = (uint16_t)pick;
+            if (num_changed) atomicAdd(num_changed, 1ull);
+        }
+        if (stat_counter) atomicAdd(stat_counter, 1ull);
     }
 }
 
@@ -296,7 +361,45 @@ pv_status pv_launch_exact_scan(pv_ctx *ctx, const pv_layout *l, const float *T,
     hipLaunchKernelGGL(k_exact_scan, dim3((unsigned)blocks), dim3(kBlock), 0, ctx->stream, T,
                        codebooks, scales, list, d_count, max_count, codes,
                        reinterpret_cast<unsigned long long *>(num_changed),
-                       reinterpret_cast<unsigned long long *>(d_stat_counter), g, l->nbits, gpr, N);
+                       reinterpret_cast<unsigned long long *>(d_stat_counter), g, l->nbits, gpr, N, 1,
+                       static_cast<part_t *>(nullptr));
+    PV_HIP(ctx, hipGetLastError());
+    return PV_OK;
+}
+
+pv_status pv_launch_exact_scan_split(pv_ctx *ctx, const pv_layout *l, const float *T,
+                                     const float *codebooks, const float *scales,
+                                     const int32_t *list, const uint32_t *d_count,
+                                     int64_t max_count, uint16_t *codes, int64_t *num_changed,
+                                     int64_t *d_stat_counter)
+{
+    const int g = l->group_size;
+    const int gpr = (int)(l->in_features / g);
+    const int N = (int)pv_num_groups(l);
+    const int csize = 1 << l->nbits;
+    int nsplit = csize / 2048;          // at least 8 passes of 256 codewords per piece
+    if (nsplit > 16) nsplit = 16;
+    if (nsplit < 2)
+        return pv_launch_exact_scan(ctx, l, T, codebooks, scales, list, d_count, max_count, codes,
+                                    num_changed, d_stat_counter);
+    pv_status st = pv_ensure(ctx, ctx->fb_partial, (size_t)(max_count + GPB) * nsplit * sizeof(part_t));
+    if (st != PV_OK) return st;
+    part_t *partial = static_cast<part_t *>(ctx->fb_partial.ptr);
+    pv_timed t(ctx, PV_K_EXACT_SCAN);
+    int64_t blocks = ((max_count + GPB - 1) / GPB) * nsplit;
+    if (blocks > 2048) blocks = 2048;
+    hipLaunchKernelGGL(k_exact_scan, dim3((unsigned)blocks), dim3(kBlock), 0, ctx->stream, T,
+                       codebooks, scales, list, d_count, max_count, codes,
+                       reinterpret_cast<unsigned long long *>(num_changed),
+                       reinterpret_cast<unsigned long long *>(d_stat_counter), g, l->nbits, gpr, N,
+                       nsplit, partial);
+    int64_t fblocks = (max_count + kBlock - 1) / kBlock;
+    if (fblocks > 256) fblocks = 256;
+    hipLaunchKernelGGL(k_exact_finalize, dim3((unsigned)fblocks), dim3(kBlock), 0, ctx->stream, T,
+                       codebooks, scales, list, d_count, max_count, codes,
+                       reinterpret_cast<unsigned long long *>(num_changed),
+                       reinterpret_cast<unsigned long long *>(d_stat_counter), g, l->nbits, gpr, N,
+                       nsplit, partial);
     PV_HIP(ctx, hipGetLastError());
     return PV_OK;
 }

@@ -1,10 +1,642 @@
-// Matrix-core nearest-codeword search (placeholder until the filter lands).
+// Nearest-codeword search for one codebook (M = 1) on the matrix cores.
+//
+// The decision "which codeword minimises || s * C[c] - t ||^2" (Eq. 7 argmin,
+// App. K "try every code") is taken in double precision, exactly as the plain
+// definition does.  The matrix cores only FILTER: by App. D's identity
+//     || c - x ||^2 = ||c||^2 - 2 <c, x> + ||x||^2 ,   x = t / s ,
+// the distance of every codeword to every selected group is one dense
+// contraction.  It is evaluated on fp16 MFMA (fp32 accumulate) for fp16-rounded
+// copies c_hi, x_hi of the operands, scaled by a power of two P so that the
+// largest codebook entry lies in [16, 32).  The spare K slots of the
+// 32x32x16 instruction carry ||c_hi||^2 and ||x_hi||^2 (each split into three
+// fp16 pieces, times 1), so an accumulator IS the approximate squared distance
+//     D~(c) = || c_hi - x_hi ||^2 + off        (+- E1 of fp32 accumulation),
+// a positive float whose bit pattern orders like an unsigned integer.
+//
+// Running minimum (per lane, in registers): the 16 accumulators of a lane
+// belong to one group (column) and to 16 consecutive codewords (a "half
+// tile"); they are reduced with v_min3_u32, the low 11 bits of the minimum are
+// replaced by the tile number, and the lane keeps the smallest and the second
+// smallest such key per partition.  A partition is (codeword range of the
+// workgroup) x (half wave) x (tile residue class).
+//
+// Exact re-rank + certificate (k_rerank): the 16 codewords of the best half
+// tile and the previous code are evaluated in double -> E*.  A codeword that
+// was not evaluated lies in a half tile whose key is at least the partition's
+// runner-up key (or the best key of a partition that was not evaluated), and
+//     | ||P C[c] - P x|| - ||c_hi - x_hi|| | <= dC + dx        (triangle inequality)
+// with dC = max_c ||P C[c] - c_hi|| and dx = ||P x - x_hi|| (+ division
+// rounding), so any codeword that could still reach E* has
+//     key value < Vcut = (P sqrt(E*)/|s| + dC + dx)^2 + off + E1 .
+// Every best-key half tile below Vcut is evaluated as well; if a runner-up key
+// lies below Vcut the group cannot be certified and goes to the exact scan.
+// Hence the chosen code is the double-precision argmin with the tie rule of
+// the definition, whatever the fp16 rounding did.
 #include "pv_internal.h"
 
-bool pv_mfma_supported(const pv_layout *) { return false; }
+namespace {
 
-pv_status pv_launch_mfma_search(pv_ctx *ctx, const pv_layout *, const float *, const float *,
-                                const float *, const int32_t *, int64_t, uint16_t *, int64_t *)
+typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+typedef float f16v __attribute__((ext_vector_type(16)));
+
+constexpr int kBlock = 256;
+constexpr int kStageTiles = 8;       // codeword tiles (of 32) per LDS stage
+constexpr int kResidues = 4;         // tile residue classes tracked separately per lane
+constexpr unsigned kTileMask = 0x7FFu;
+constexpr float kHalfMinNormal = 6.103515625e-05f;  // 2^-14
+constexpr float kGamma = 7.62939453125e-06f;        // 2^-17: fp32 accumulation bound per unit of sum|terms|
+
+// cb_meta layout (unsigned[8]): [0] bits of max|C|, [1] bits of max ||c_hi||^2,
+// [2] bits of max ||P c - c_hi||^2, [3] bad-codebook flag
+// x_meta layout (float[4] per selected group): off, E1, dx, flag (1 = skip the filter)
+
+__device__ __forceinline__ float scale_from_maxabs(unsigned maxbits, bool *ok)
 {
-    return pv_fail(ctx, PV_ERR_UNSUPPORTED, "matrix-core search not built");
+    float m = __uint_as_float(maxbits);
+    *ok = (m > 0.0f) && (m < 3.0e38f) && (m >= 1.0e-30f);
+    if (!*ok) return 1.0f;
+    int ex;
+    (void)frexpf(m, &ex);          // m = f * 2^ex, f in [0.5, 1)
+    return ldexpf(1.0f, 5 - ex);   // m * P in [16, 32)
+}
+
+__device__ __forceinline__ _Float16 to_half_flush(float v)
+{
+    return fabsf(v) < kHalfMinNormal ? (_Float16)0.0f : (_Float16)v;
+}
+
+// value -> three fp16 pieces p1 + p2 + p3 ~= v (pieces below the normal range dropped)
+__device__ __forceinline__ void split3(float v, _Float16 *p)
+{
+    p[0] = to_half_flush(v);
+    float r = v - (float)p[0];
+    p[1] = to_half_flush(r);
+    r = r - (float)p[1];
+    p[2] = to_half_flush(r);
+}
+
+__global__ __launch_bounds__(kBlock) void k_cb_absmax(const float *__restrict__ cb, int64_t n,
+                                                      unsigned *__restrict__ meta)
+{
+    float m = 0.0f;
+    bool bad = false;
+    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += (int64_t)gridDim.x * kBlock) {
+        float v = fabsf(cb[i]);
+        bad |= !(v <= 3.0e38f);
+        m = fmaxf(m, v);
+    }
+    for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_down(m, off));
+    if ((threadIdx.x & 63) == 0) atomicMax(&meta[0], __float_as_uint(m));
+    if (bad) atomicMax(&meta[3], 1u);
+}
+
+// One thread per codeword: fp16 operand rows in MFMA order + rounding bounds.
+// Operand A of tile t (32 codewords), k-step j, k-half h, row r is the 16-byte
+// chunk  A[((t * NK + j) * 2 + h) * 32 + r].  Codeword c sits in tile c / 32 at
+// row 8*(q/4) + 4*hw + q%4 with hw = (c/16)%2, q = c%16, so that accumulator q
+// of half wave hw is codeword 32*t + 16*hw + q.
+template <int NK>
+__global__ __launch_bounds__(kBlock) void k_cb_prep(const float *__restrict__ cb, int csize, int g,
+                                                    unsigned *__restrict__ meta,
+                                                    h8 *__restrict__ A)
+{
+    const int c = blockIdx.x * kBlock + threadIdx.x;
+    bool ok;
+    const float P = scale_from_maxabs(meta[0], &ok);
+    float n2 = 0.0f, d2 = 0.0f;
+    if (c < csize) {
+        const int tile = c >> 5, hw = (c >> 4) & 1, q = c & 15;
+        const int row = 8 * (q >> 2) + 4 * hw + (q & 3);
+        h8 chunk[2 * NK];
+#pragma unroll
+        for (int u = 0; u < 2 * NK; ++u)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) chunk[u][e] = (_Float16)0.0f;
+        for (int i = 0; i < g; ++i) {
+            float v = ok ? P * cb[(int64_t)c * g + i] : 0.0f;
+            _Float16 hv = to_half_flush(v);
+            float hf = (float)hv;
+            n2 = fmaf(hf, hf, n2);
+            float d = v - hf;
+            d2 = fmaf(d, d, d2);
+            chunk[i >> 3][i & 7] = (_Float16)(-2.0f * hf);
+        }
+        _Float16 pieces[3];
+        split3(n2, pieces);
+        const int u = g / 8;  // first chunk after the coordinates
+        chunk[u][0] = pieces[0];
+        chunk[u][1] = pieces[1];
+        chunk[u][2] = pieces[2];
+        chunk[u][3] = (_Float16)1.0f;
+        chunk[u][4] = (_Float16)1.0f;
+        chunk[u][5] = (_Float16)1.0f;
+#pragma unroll
+        for (int u2 = 0; u2 < 2 * NK; ++u2) A[((int64_t)tile * NK * 2 + u2) * 32 + row] = chunk[u2];
+    }
+    for (int off = 32; off > 0; off >>= 1) {
+        n2 = fmaxf(n2, __shfl_down(n2, off));
+        d2 = fmaxf(d2, __shfl_down(d2, off));
+    }
+    if ((threadIdx.x & 63) == 0) {
+        atomicMax(&meta[1], __float_as_uint(n2));
+        atomicMax(&meta[2], __float_as_uint(d2));
+    }
+}
+
+// One thread per selected group (position j in the list): x = t / s, fp16 copy
+// in MFMA operand order, per-group bounds.  Operand B of group tile gt, k-step
+// j, k-half h, column col is the chunk X[((gt * NK + j) * 2 + h) * 32 + col].
+template <int NK>
+__global__ __launch_bounds__(kBlock) void k_x_prep(const float *__restrict__ T,
+                                                   const float *__restrict__ scales,
+                                                   const int32_t *__restrict__ group_idx, int k,
+                                                   int k_pad, int g, int gpr, int N,
+                                                   const unsigned *__restrict__ meta,
+                                                   h8 *__restrict__ X, float *__restrict__ x_meta)
+{
+    const int j = blockIdx.x * kBlock + threadIdx.x;
+    if (j >= k_pad) return;
+    bool ok;
+    const float P = scale_from_maxabs(meta[0], &ok);
+    ok = ok && meta[3] == 0u;
+    const float cmax = sqrtf(__uint_as_float(meta[1])) * 1.0001f;
+    h8 chunk[2 * NK];
+#pragma unroll
+    for (int u = 0; u < 2 * NK; ++u)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) chunk[u][e] = (_Float16)0.0f;
+    float off = 0.0f, e1 = 0.0f, dx = 0.0f, flag = 1.0f;
+    const int n = j < k ? group_idx[j] : -1;
+    if (n >= 0 && n < N && ok) {
+        const float s = scales[n / gpr];
+        const float inv_ok = (s != 0.0f && fabsf(s) < 3.0e38f) ? 1.0f : 0.0f;
+        float xx = 0.0f, d2 = 0.0f, u2 = 0.0f;
+        bool fits = inv_ok != 0.0f;
+        for (int i = 0; i < g; ++i) {
+            float x = T[(int64_t)n * g + i] / (fits ? s : 1.0f);
+            float u = P * x;
+            if (!(fabsf(u) < 240.0f)) fits = false;   // also catches NaN / inf
+            _Float16 hv = to_half_flush(fits ? u : 0.0f);
+            float hf = (float)hv;
+            xx = fmaf(hf, hf, xx);
+            float d = u - hf;
+            d2 = fmaf(d, d, d2);
+            u2 = fmaf(u, u, u2);
+            chunk[i >> 3][i & 7] = hv;
+        }
+        if (fits && xx < 57000.0f) {
+            const float xn = sqrtf(xx) * 1.0001f;
+            const float e1p = kGamma * (cmax + xn) * (cmax + xn) * 1.01f + 2.5e-4f;
+            off = 4.0f * e1p;
+            e1 = 1.01f * e1p;
+            // rounding of x to fp16, plus the fp32 division and scaling roundings (2^-22 ||u||)
+            dx = sqrtf(d2) * 1.0001f + 2.4e-7f * sqrtf(u2) + 1.0e-30f;
+            flag = 0.0f;
+            _Float16 pieces[3];
+            split3(xx + off, pieces);
+            const int u = g / 8;
+            chunk[u][0] = (_Float16)1.0f;
+            chunk[u][1] = (_Float16)1.0f;
+            chunk[u][2] = (_Float16)1.0f;
+            chunk[u][3] = pieces[0];
+            chunk[u][4] = pieces[1];
+            chunk[u][5] = pieces[2];
+        } else {
+#pragma unroll
+            for (int u = 0; u < 2 * NK; ++u)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) chunk[u][e] = (_Float16)0.0f;
+        }
+    }
+    const int gt = j >> 5, col = j & 31;
+#pragma unroll
+    for (int u = 0; u < 2 * NK; ++u) X[((int64_t)gt * NK * 2 + u) * 32 + col] = chunk[u];
+    float4 m;
+    m.x = off;
+    m.y = e1;
+    m.z = dx;
+    m.w = flag;
+    reinterpret_cast<float4 *>(x_meta)[j] = m;
+}
+
+// Plain C so that the compiler sees the reads of MFMA results and inserts the
+// wait states the hardware requires between a matrix instruction and a vector
+// read of its destination (it does not look inside inline assembly).  It folds
+// the pair of mins into one v_min3_u32.
+__device__ __forceinline__ unsigned umin3(unsigned a, unsigned b, unsigned c)
+{
+    return min(min(a, b), c);
+}
+
+// (m & mask) | tile in one instruction; operands are ordinary vector results.
+__device__ __forceinline__ unsigned and_or(unsigned m, unsigned vmask, unsigned tile)
+{
+    unsigned r;
+    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(m), "v"(vmask), "s"(tile));
+    return r;
+}
+
+__device__ __forceinline__ unsigned umed3(unsigned a, unsigned b, unsigned c)
+{
+    unsigned r;
+    asm("v_med3_u32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+
+// Smallest of the 16 accumulators (positive floats compared as integers).
+__device__ __forceinline__ unsigned acc_min(const f16v &acc)
+{
+    unsigned m = umin3(__float_as_uint(acc[0]), __float_as_uint(acc[1]), __float_as_uint(acc[2]));
+    m = umin3(m, __float_as_uint(acc[3]), __float_as_uint(acc[4]));
+    m = umin3(m, __float_as_uint(acc[5]), __float_as_uint(acc[6]));
+    m = umin3(m, __float_as_uint(acc[7]), __float_as_uint(acc[8]));
+    m = umin3(m, __float_as_uint(acc[9]), __float_as_uint(acc[10]));
+    m = umin3(m, __float_as_uint(acc[11]), __float_as_uint(acc[12]));
+    m = umin3(m, __float_as_uint(acc[13]), __float_as_uint(acc[14]));
+    return min(m, __float_as_uint(acc[15]));
+}
+
+// The distance contraction.  Block = 4 waves; wave w owns NB group tiles (32
+// groups each) whose B operands stay in registers; the block streams the
+// codeword tiles [t_begin, t_end) of its split through a double-buffered LDS
+// stage shared by the 4 waves.  Output: for every group and partition the
+// smallest and second smallest key.
+template <int NK, int NB>
+__global__ __launch_bounds__(kBlock, 2) void k_score_mfma(const h8 *__restrict__ A,
+                                                          const h8 *__restrict__ X,
+                                                          uint2 *__restrict__ partials, int ntiles,
+                                                          int nsplit, int P, int merge)
+{
+    constexpr int kStageChunks = kStageTiles * NK * 64;            // 16-byte chunks per stage
+    constexpr int kLoads = kStageChunks / kBlock;                  // per thread per stage
+    __shared__ h8 lds[2][kStageChunks];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int gtile0 = (blockIdx.x * (kBlock / 64) + wave) * NB;
+    const int split = blockIdx.y;
+    const int t_begin = (int)((int64_t)split * ntiles / nsplit);
+    const int t_end = (int)((int64_t)(split + 1) * ntiles / nsplit);
+
+    h8 b[NB][NK];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int j = 0; j < NK; ++j) b[nb][j] = X[((int64_t)(gtile0 + nb) * NK + j) * 64 + lane];
+
+    unsigned best[NB][kResidues], second[NB][kResidues];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb)
+#pragma unroll
+        for (int r = 0; r < kResidues; ++r) best[nb][r] = second[nb][r] = 0xFFFFFFFFu;
+
+    const h8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
+    unsigned vmask = ~kTileMask;
+    asm volatile("" : "+v"(vmask));   // keep the mask in a vector register
+    h8 pre[kLoads];
+    auto fetch = [&](int t0) {
+        const int valid = (t_end - t0 < kStageTiles ? t_end - t0 : kStageTiles) * NK * 64;
+        const h8 *src = A + (int64_t)t0 * NK * 64;
+#pragma unroll
+        for (int u = 0; u < kLoads; ++u) {
+            int i = u * kBlock + threadIdx.x;
+            pre[u] = i < valid ? src[i] : zero8;
+        }
+    };
+    auto stash = [&](int buf) {
+#pragma unroll
+        for (int u = 0; u < kLoads; ++u) lds[buf][u * kBlock + threadIdx.x] = pre[u];
+    };
+
+    if (t_begin < t_end) {
+        fetch(t_begin);
+        stash(0);
+    }
+    __syncthreads();
+    int buf = 0;
+    for (int t0 = t_begin; t0 < t_end; t0 += kStageTiles) {
+        const bool more = t0 + kStageTiles < t_end;
+        if (more) fetch(t0 + kStageTiles);
+#pragma unroll
+        for (int ts = 0; ts < kStageTiles; ++ts) {
+            if (t0 + ts < t_end) {   // uniform
+                h8 a[NK];
+#pragma unroll
+                for (int j = 0; j < NK; ++j) a[j] = lds[buf][(ts * NK + j) * 64 + lane];
+                const unsigned tile = (unsigned)(t0 + ts);
+#pragma unroll
+                for (int nb = 0; nb < NB; ++nb) {
+                    f16v acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+                    for (int j = 0; j < NK; ++j)
+                        acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[j], b[nb][j], acc, 0, 0, 0);
+                    const unsigned key = and_or(acc_min(acc), vmask, tile);
+                    second[nb][ts % kResidues] =
+                        umed3(best[nb][ts % kResidues], second[nb][ts % kResidues], key);
+                    best[nb][ts % kResidues] = min(best[nb][ts % kResidues], key);
+                }
+            }
+        }
+        if (more) stash(buf ^ 1);
+        __syncthreads();
+        buf ^= 1;
+    }
+
+    const int col = lane & 31, hw = lane >> 5;
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) {
+        const int64_t jpos = (int64_t)(gtile0 + nb) * 32 + col;
+        if (merge) {
+            unsigned b1 = best[nb][0], b2 = second[nb][0];
+#pragma unroll
+            for (int r = 1; r < kResidues; ++r) {
+                // two smallest of {b1, b2, best[r], second[r]} (b1 <= b2, best <= second)
+                unsigned lo = min(b1, best[nb][r]);
+                unsigned hi = max(b1, best[nb][r]);
+                b2 = min(min(b2, second[nb][r]), hi);
+                b1 = lo;
+            }
+            partials[jpos * P + (split * 2 + hw)] = make_uint2(b1, b2);
+        } else {
+#pragma unroll
+            for (int r = 0; r < kResidues; ++r)
+                partials[jpos * P + (split * 2 + hw) * kResidues + r] =
+                    make_uint2(best[nb][r], second[nb][r]);
+        }
+    }
+}
+
+// ---------------------------------------------------------------- exact re-rank
+
+struct cand_t {
+    double obj;
+    int idx;
+};
+
+__device__ __forceinline__ bool cand_better(double o1, int i1, double o2, int i2)
+{
+    return o1 < o2 || (o1 == o2 && i1 < i2);
+}
+
+__device__ __forceinline__ double exact_obj(const float *__restrict__ cw, float s,
+                                            const float *t, int g)
+{
+    double obj = 0.0;
+    for (int i = 0; i < g; ++i) {
+        double acc = (double)cw[i];
+        double r = (double)s * acc - (double)t[i];
+        obj = obj + r * r;
+    }
+    return obj;
+}
+
+constexpr int kMaxG = 16;
+
+// 16 lanes per selected group.
+__global__ __launch_bounds__(kBlock) void k_rerank(
+    const float *__restrict__ T, const float *__restrict__ codebook,
+    const float *__restrict__ scales, const int32_t *__restrict__ group_idx, int k,
+    const uint2 *__restrict__ partials, int P, int per_half, const float *__restrict__ x_meta,
+    const unsigned *__restrict__ cb_meta, uint16_t *__restrict__ codes,
+    unsigned long long *__restrict__ num_changed, int32_t *__restrict__ fb_list,
+    unsigned *__restrict__ fb_count, unsigned long long *__restrict__ stats, int g, int gpr, int N,
+    int nbits)
+{
+    const int gid = blockIdx.x * kBlock + threadIdx.x;
+    const int j = gid >> 4, q = gid & 15;
+    if (j >= k) return;                      // whole 16-lane teams leave together
+    const int n = group_idx[j];
+    if (n < 0 || n >= N) return;
+    const float4 meta = reinterpret_cast<const float4 *>(x_meta)[j];
+    if (meta.w != 0.0f) {                    // the filter was skipped for this group
+        if (q == 0) fb_list[atomicAdd(fb_count, 1u)] = n;
+        return;
+    }
+    const int csize = 1 << nbits;
+    const float s = scales[n / gpr];
+    float t[kMaxG];
+    for (int i = 0; i < g; ++i) t[i] = T[(int64_t)n * g + i];
+
+    // best key over all partitions, with its partition
+    constexpr int kMaxRec = 4;               // P <= 64
+    uint2 rec[kMaxRec];
+    unsigned long long bk = ~0ull;
+#pragma unroll
+    for (int u = 0; u < kMaxRec; ++u) {
+        int p = q + 16 * u;
+        rec[u] = p < P ? partials[(int64_t)j * P + p] : make_uint2(0xFFFFFFFFu, 0xFFFFFFFFu);
+        unsigned long long v = ((unsigned long long)rec[u].x << 32) | (unsigned)p;
+        bk = v < bk ? v : bk;
+    }
+#pragma unroll
+    for (int m = 8; m > 0; m >>= 1) {
+        unsigned long long o = __shfl_xor(bk, m, 16);
+        bk = o < bk ? o : bk;
+    }
+    const unsigned best_key = (unsigned)(bk >> 32);
+    const int best_p = (int)(bk & 0xFFFFFFFFu);
+
+    auto eval_half_tile = [&](unsigned key, int p, cand_t &c) {
+        const int tile = (int)(key & kTileMask);
+        const int hw = (p / per_half) & 1;
+        const int cw = tile * 32 + hw * 16 + q;
+        double o = exact_obj(codebook + (int64_t)cw * g, s, t, g);
+        if (cand_better(o, cw, c.obj, c.idx)) {
+            c.obj = o;
+            c.idx = cw;
+        }
+    };
+    auto team_min = [&](cand_t c) {
+#pragma unroll
+        for (int m = 8; m > 0; m >>= 1) {
+            double o = __shfl_xor(c.obj, m, 16);
+            int i = __shfl_xor(c.idx, m, 16);
+            if (cand_better(o, i, c.obj, c.idx)) {
+                c.obj = o;
+                c.idx = i;
+            }
+        }
+        return c;
+    };
+
+    cand_t mine;
+    mine.obj = __builtin_huge_val();
+    mine.idx = 0x7fffffff;
+    eval_half_tile(best_key, best_p, mine);
+    cand_t first = team_min(mine);
+    const int prev = codes[n] & (csize - 1);
+    const double o_prev = exact_obj(codebook + (int64_t)prev * g, s, t, g);
+    if (o_prev < first.obj) first.obj = o_prev;   // the previous code is a candidate too
+
+    // every codeword that was not evaluated and could still reach E* has a key value below vcut
+    const float Pscale = [&] {
+        bool ok;
+        return scale_from_maxabs(cb_meta[0], &ok);
+    }();
+    const double dC = sqrt((double)__uint_as_float(cb_meta[2])) * 1.0001 + 1e-30;
+    const double dstar = sqrt(first.obj) * (double)Pscale / fabs((double)s) * (1.0 + 1e-9);
+    const double reach = dstar + dC + (double)meta.z;
+    const double vcut_d = (reach * reach + (double)meta.x + (double)meta.y) * (1.0 + 1e-6);
+    const float vcut = __double2float_ru(vcut_d);
+    const bool finite_cut = vcut_d < 3.0e38 && vcut_d == vcut_d;
+
+    bool uncertain = !finite_cut;
+    unsigned pending = 0;                     // bit u: rec[u].x needs evaluation
+#pragma unroll
+    for (int u = 0; u < kMaxRec; ++u) {
+        int p = q + 16 * u;
+        if (p < P) {
+            if (__uint_as_float(rec[u].y & ~kTileMask) < vcut) uncertain = true;
+            if (p != best_p && __uint_as_float(rec[u].x & ~kTileMask) < vcut) pending |= 1u << u;
+        }
+    }
+    const int team_shift = (threadIdx.x & 63) & ~15;
+    unsigned long long unc = __ballot(uncertain);
+    if ((unc >> team_shift) & 0xFFFFull) {
+        if (q == 0) fb_list[atomicAdd(fb_count, 1u)] = n;
+        return;
+    }
+    unsigned extra = 0;
+    for (;;) {
+        unsigned long long pb = __ballot(pending != 0);
+        unsigned team = (unsigned)((pb >> team_shift) & 0xFFFFull);
+        if (!team) break;
+        const int src = __ffs(team) - 1;                      // lane of the team with work
+        const unsigned their = __shfl(pending, src, 16);
+        const int u = __ffs(their) - 1;
+        unsigned key = 0;
+#pragma unroll
+        for (int uu = 0; uu < kMaxRec; ++uu)
+            if (uu == u) key = rec[uu].x;
+        key = __shfl(key, src, 16);
+        eval_half_tile(key, src + 16 * u, mine);
+        if (q == src) pending &= ~(1u << u);
+        ++extra;
+    }
+    cand_t win = team_min(mine);
+    if (q == 0) {
+        int pick = win.idx;
+        if (o_prev <= win.obj || pick == 0x7fffffff) pick = prev;
+        if (pick != prev) {
+            codes[n] = (uint16_t)pick;
+            if (num_changed) atomicAdd(num_changed, 1ull);
+        }
+        atomicAdd(&stats[0], 1ull);
+        atomicAdd(&stats[2], (unsigned long long)(16 * (1 + extra) + 1));
+    }
+}
+
+__global__ void k_fill_u32(unsigned *p, int n, unsigned v)
+{
+    int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+struct plan_t {
+    int NK, NB, k_pad, gblocks, nsplit, P, per_half, merge, ntiles;
+};
+
+plan_t make_plan(const pv_layout *l, int64_t k)
+{
+    plan_t p;
+    p.NK = l->group_size / 8;
+    p.ntiles = (1 << l->nbits) / 32;
+    p.NB = k >= 8192 ? 4 : (k >= 2048 ? 2 : 1);
+    const int per_block = (kBlock / 64) * p.NB * 32;
+    p.gblocks = (int)((k + per_block - 1) / per_block);
+    p.k_pad = p.gblocks * per_block;
+    // about two blocks per compute unit in flight; a split needs at least one stage of tiles
+    int want = (512 + p.gblocks - 1) / p.gblocks;
+    int max_split = p.ntiles / kStageTiles;
+    if (max_split < 1) max_split = 1;
+    if (want > max_split) want = max_split;
+    if (want > 32) want = 32;
+    if (want < 1) want = 1;
+    p.nsplit = want;
+    // keep all residue classes apart while the record count per group stays small
+    p.merge = (p.nsplit * 2 * kResidues > 32) ? 1 : 0;
+    p.per_half = p.merge ? 1 : kResidues;
+    p.P = p.nsplit * 2 * p.per_half;
+    return p;
+}
+
+}  // namespace
+
+bool pv_mfma_supported(const pv_layout *l)
+{
+    return l->num_codebooks == 1 && (l->group_size == 8 || l->group_size == 16) && l->nbits >= 5;
+}
+
+pv_status pv_launch_mfma_search(pv_ctx *ctx, const pv_layout *l, const float *T,
+                                const float *codebooks, const float *scales,
+                                const int32_t *group_idx, int64_t k, uint16_t *codes,
+                                int64_t *num_changed)
+{
+    const plan_t p = make_plan(l, k);
+    const int g = l->group_size;
+    const int csize = 1 << l->nbits;
+    const int gpr = (int)(l->in_features / g);
+    const int N = (int)pv_num_groups(l);
+    pv_status st;
+    if ((st = pv_ensure(ctx, ctx->cb_f16, (size_t)csize * p.NK * 32)) != PV_OK) return st;
+    if ((st = pv_ensure(ctx, ctx->cb_meta, 8 * sizeof(unsigned))) != PV_OK) return st;
+    if ((st = pv_ensure(ctx, ctx->x_f16, (size_t)p.k_pad * p.NK * 32)) != PV_OK) return st;
+    if ((st = pv_ensure(ctx, ctx->x_meta, (size_t)p.k_pad * 4 * sizeof(float))) != PV_OK) return st;
+    if ((st = pv_ensure(ctx, ctx->partials, (size_t)p.k_pad * p.P * sizeof(uint2))) != PV_OK) return st;
+    if ((st = pv_ensure(ctx, ctx->fb_list, ((size_t)k + 4) * sizeof(int32_t))) != PV_OK) return st;
+    h8 *A = static_cast<h8 *>(ctx->cb_f16.ptr);
+    h8 *X = static_cast<h8 *>(ctx->x_f16.ptr);
+    unsigned *cb_meta = static_cast<unsigned *>(ctx->cb_meta.ptr);
+    float *x_meta = static_cast<float *>(ctx->x_meta.ptr);
+    uint2 *partials = static_cast<uint2 *>(ctx->partials.ptr);
+    int32_t *fb_list = static_cast<int32_t *>(ctx->fb_list.ptr) + 4;
+    unsigned *fb_count = reinterpret_cast<unsigned *>(ctx->fb_list.ptr);
+    unsigned long long *stats = static_cast<unsigned long long *>(ctx->stats.ptr);
+    hipStream_t sm = ctx->stream;
+    {
+        pv_timed t(ctx, PV_K_PREP);
+        hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(64), 0, sm, cb_meta, 8, 0u);
+        hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(64), 0, sm, fb_count, 4, 0u);
+        const int64_t ncb = (int64_t)csize * g;
+        int blocks = (int)((ncb + kBlock * 8 - 1) / (kBlock * 8));
+        hipLaunchKernelGGL(k_cb_absmax, dim3(blocks), dim3(kBlock), 0, sm, codebooks, ncb, cb_meta);
+        if (p.NK == 1) {
+            hipLaunchKernelGGL(k_cb_prep<1>, dim3((csize + kBlock - 1) / kBlock), dim3(kBlock), 0, sm,
+                               codebooks, csize, g, cb_meta, A);
+            hipLaunchKernelGGL(k_x_prep<1>, dim3((p.k_pad + kBlock - 1) / kBlock), dim3(kBlock), 0, sm, T, scales,
+                               group_idx, (int)k, p.k_pad, g, gpr, N, cb_meta, X, x_meta);
+        } else {
+            hipLaunchKernelGGL(k_cb_prep<2>, dim3((csize + kBlock - 1) / kBlock), dim3(kBlock), 0, sm,
+                               codebooks, csize, g, cb_meta, A);
+            hipLaunchKernelGGL(k_x_prep<2>, dim3((p.k_pad + kBlock - 1) / kBlock), dim3(kBlock), 0, sm, T, scales,
+                               group_idx, (int)k, p.k_pad, g, gpr, N, cb_meta, X, x_meta);
+        }
+    }
+    {
+        pv_timed t(ctx, PV_K_SCORE_MFMA);
+        dim3 grid(p.gblocks, p.nsplit);
+#define PV_SCORE(NK_, NB_)                                                                     \
+    hipLaunchKernelGGL((k_score_mfma<NK_, NB_>), grid, dim3(kBlock), 0, sm, A, X, partials,    \
+                       p.ntiles, p.nsplit, p.P, p.merge)
+        if (p.NK == 1) {
+            if (p.NB == 4) PV_SCORE(1, 4);
+            else if (p.NB == 2) PV_SCORE(1, 2);
+            else PV_SCORE(1, 1);
+        } else {
+            if (p.NB == 4) PV_SCORE(2, 4);
+            else if (p.NB == 2) PV_SCORE(2, 2);
+            else PV_SCORE(2, 1);
+        }
+#undef PV_SCORE
+    }
+    {
+        pv_timed t(ctx, PV_K_RERANK);
+        const int64_t threads = k * 16;
+        hipLaunchKernelGGL(k_rerank, dim3((unsigned)((threads + kBlock - 1) / kBlock)), dim3(kBlock), 0,
+                           sm, T, codebooks, scales, group_idx, (int)k, partials, p.P, p.per_half,
+                           x_meta, cb_meta, codes,
+                           reinterpret_cast<unsigned long long *>(num_changed), fb_list, fb_count,
+                           stats, g, gpr, N, l->nbits);
+    }
+    PV_HIP(ctx, hipGetLastError());
+    return pv_launch_exact_scan_split(ctx, l, T, codebooks, scales, fb_list, fb_count, k, codes,
+                                      num_changed, reinterpret_cast<int64_t *>(stats + 1));
 }
