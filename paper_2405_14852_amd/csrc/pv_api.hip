@@ -123,7 +123,7 @@ extern "C" void pv_destroy(pv_ctx *c)
     (void)hipStreamSynchronize(c->stream);
     pv_buffer *bufs[] = {&c->sel_scores, &c->sel_hist, &c->sel_blocks, &c->sel_state, &c->stats,
                          &c->cb_f16,     &c->cb_meta,  &c->x_f16,      &c->x_meta,    &c->partials,
-                         &c->fb_list,   &c->fb_partial};
+                         &c->fb_list,   &c->fb_partial, &c->fb_arrivals, &c->rr_counts};
     for (pv_buffer *b : bufs)
         if (b->ptr) (void)hipFree(b->ptr);
     for (auto &t : c->timers)
@@ -204,6 +204,9 @@ extern "C" pv_status pv_reencode_groups(pv_ctx *ctx, const pv_layout *l, const f
     st = pv_ensure(ctx, ctx->stats, 8 * sizeof(int64_t));
     if (st != PV_OK) return st;
     int64_t *stats = static_cast<int64_t *>(ctx->stats.ptr);
+    const bool filter = M == 1 && k > 0 && ctx->search_mode == 0 && pv_mfma_supported(l);
+    if (filter)   // its first kernel clears the counters
+        return pv_launch_mfma_search(ctx, l, T, codebooks, scales, group_idx, k, codes, num_changed);
     st = pv_launch_fill_i64(ctx, stats, 8, 0);
     if (st != PV_OK) return st;
     if (num_changed) {
@@ -212,9 +215,6 @@ extern "C" pv_status pv_reencode_groups(pv_ctx *ctx, const pv_layout *l, const f
     }
     if (k == 0) return PV_OK;
     if (M > 1) return pv_launch_beam(ctx, l, T, codebooks, scales, group_idx, k, beam_width, codes,
-                                     num_changed);
-    if (ctx->search_mode == 0 && pv_mfma_supported(l))
-        return pv_launch_mfma_search(ctx, l, T, codebooks, scales, group_idx, k, codes,
                                      num_changed);
     return pv_launch_exact_scan(ctx, l, T, codebooks, scales, group_idx, nullptr, k, codes,
                                 num_changed, stats + 3);

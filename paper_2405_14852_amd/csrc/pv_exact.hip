@@ -68,29 +68,43 @@ __device__ __forceinline__ best_t block_min(best_t b, double *s_obj, int *s_idx)
 
 // ------------------------------------------------------------------ M = 1 scan
 //
-// One block takes GPB groups of the list at a time; thread t scores codewords
-// t, t + 256, ... against all GPB targets (a codeword is read once for GPB
-// groups).  Ascending scan + strict '<' keeps the lowest index among equal
-// objectives; the previous code wins an exact tie with the minimum.
+// Work item = (GPB consecutive list entries, one piece of the codeword range).
+// Thread t scores codewords t, t + 256, ... of the piece against the GPB
+// targets (a codeword is read once for GPB groups).  Ascending scan + strict
+// '<' keeps the lowest index among equal objectives.  The block that finishes
+// the last piece of an item combines the pieces (ascending ranges, so the
+// lexicographic (obj, idx) minimum is the lowest index), lets the previous
+// code win an exact tie with the minimum, and writes the code.
+// G > 0: group size known at compile time (vector loads, targets in
+// registers); G == 0: any group size up to kMaxG.
 constexpr int GPB = 4;
 
+template <int G>
 __global__ __launch_bounds__(kBlock) void k_exact_scan(
     const float *__restrict__ T, const float *__restrict__ codebook,
     const float *__restrict__ scales, const int32_t *__restrict__ list,
     const uint32_t *__restrict__ d_count, int64_t max_count, uint16_t *__restrict__ codes,
     unsigned long long *__restrict__ num_changed, unsigned long long *__restrict__ stat_counter,
-    int g, int nbits, int gpr, int N, int nsplit, part_t *__restrict__ partial)
+    int g_rt, int nbits, int gpr, int N, int nsplit, part_t *partial, unsigned *arrivals,
+    unsigned *__restrict__ reset_meta, const unsigned *__restrict__ rr_counts, int rr_blocks,
+    unsigned long long *__restrict__ rr_stats)
 {
-    __shared__ float s_t[GPB][kMaxG];
+    constexpr int GS = G > 0 ? G : kMaxG;
+    const int g = G > 0 ? G : g_rt;
+    __shared__ float s_t[GPB][GS];
     __shared__ float s_scale[GPB];
     __shared__ int s_group[GPB];
     __shared__ double s_obj[kBlock / 64];
     __shared__ int s_idx[kBlock / 64];
+    __shared__ unsigned s_last;
+    __shared__ double s_fin_obj[GPB];
+    __shared__ int s_fin_idx[GPB];
     const int64_t count = d_count ? (int64_t)*d_count : max_count;
     const int csize = 1 << nbits;
-    const int64_t quads = (count + GPB - 1) / GPB;
-    for (int64_t w = blockIdx.x; w < quads * nsplit; w += gridDim.x) {
-        const int64_t base = (w / nsplit) * GPB;
+    const int64_t items = (count + GPB - 1) / GPB;
+    for (int64_t w = blockIdx.x; w < items * nsplit; w += gridDim.x) {
+        const int64_t item = w / nsplit;
+        const int64_t base = item * GPB;
         const int piece = (int)(w % nsplit);
         const int c_begin = (int)((int64_t)piece * csize / nsplit);
         const int c_end = (int)((int64_t)(piece + 1) * csize / nsplit);
@@ -115,40 +129,122 @@ __global__ __launch_bounds__(kBlock) void k_exact_scan(
             best[q].obj = kInf;
             best[q].idx = 0x7fffffff;
         }
-        for (int c = c_begin + threadIdx.x; c < c_end; c += kBlock) {
-            const float *cw = codebook + (int64_t)c * g;
-            double obj[GPB];
+        if constexpr (G > 0) {
+            double sc[GPB], tt[GPB][GS];
 #pragma unroll
-            for (int q = 0; q < GPB; ++q) obj[q] = 0.0;
-            for (int i = 0; i < g; ++i) {
-                double acc = (double)cw[i];
+            for (int q = 0; q < GPB; ++q) {
+                sc[q] = (double)s_scale[q];
+#pragma unroll
+                for (int i = 0; i < GS; ++i) tt[q][i] = (double)s_t[q][i];
+            }
+            for (int c = c_begin + threadIdx.x; c < c_end; c += kBlock) {
+                const pv_f4 *cw4 = reinterpret_cast<const pv_f4 *>(codebook + (int64_t)c * GS);
+                double obj[GPB];
+#pragma unroll
+                for (int q = 0; q < GPB; ++q) obj[q] = 0.0;
+#pragma unroll
+                for (int v4 = 0; v4 < GS / 4; ++v4) {
+                    pv_f4 cv = cw4[v4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        double acc = (double)cv[e];
+#pragma unroll
+                        for (int q = 0; q < GPB; ++q) {
+                            double r = sc[q] * acc - tt[q][v4 * 4 + e];
+                            obj[q] = obj[q] + r * r;
+                        }
+                    }
+                }
+#pragma unroll
+                for (int q = 0; q < GPB; ++q)
+                    if (obj[q] < best[q].obj) {
+                        best[q].obj = obj[q];
+                        best[q].idx = c;
+                    }
+            }
+        } else {
+            for (int c = c_begin + threadIdx.x; c < c_end; c += kBlock) {
+                const float *cw = codebook + (int64_t)c * g;
+                double obj[GPB];
+#pragma unroll
+                for (int q = 0; q < GPB; ++q) obj[q] = 0.0;
+                for (int i = 0; i < g; ++i) {
+                    double acc = (double)cw[i];
+#pragma unroll
+                    for (int q = 0; q < GPB; ++q) {
+                        double r = (double)s_scale[q] * acc - (double)s_t[q][i];
+                        obj[q] = obj[q] + r * r;
+                    }
+                }
+#pragma unroll
+                for (int q = 0; q < GPB; ++q)
+                    if (obj[q] < best[q].obj) {
+                        best[q].obj = obj[q];
+                        best[q].idx = c;
+                    }
+            }
+        }
+        best_t mine[GPB];
+#pragma unroll
+        for (int q = 0; q < GPB; ++q) mine[q] = block_min(best[q], s_obj, s_idx);  // valid in thread 0
+        if (nsplit > 1) {
+            if (threadIdx.x == 0) {
 #pragma unroll
                 for (int q = 0; q < GPB; ++q) {
-                    double r = (double)s_scale[q] * acc - (double)s_t[q][i];
-                    obj[q] = obj[q] + r * r;
-                }
-            }
-#pragma unroll
-            for (int q = 0; q < GPB; ++q)
-                if (obj[q] < best[q].obj) {
-                    best[q].obj = obj[q];
-                    best[q].idx = c;
-                }
-        }
-#pragma unroll
-        for (int q = 0; q < GPB; ++q) {
-            best_t b = block_min(best[q], s_obj, s_idx);
-            if (nsplit > 1) {
-                if (threadIdx.x == 0 && s_group[q] >= 0) {
                     part_t pt;
-                    pt.obj = b.obj;
-                    pt.idx = b.idx;
+                    pt.obj = mine[q].obj;
+                    pt.idx = mine[q].idx;
                     pt.pad = 0;
                     partial[(base + q) * nsplit + piece] = pt;
                 }
-                continue;
+                __threadfence();
+                s_last = atomicAdd(&arrivals[item], 1u) == (unsigned)(nsplit - 1) ? 1u : 0u;
             }
-            if (threadIdx.x == 0 && s_group[q] >= 0) {
+            __syncthreads();
+            if (!s_last) continue;                // uniform over the block
+            // all pieces of this item are in memory: combine them, 32 lanes per group
+            __threadfence();
+            {
+                const int q = threadIdx.x >> 5, p = threadIdx.x & 31;
+                best_t b;
+                b.obj = kInf;
+                b.idx = 0x7fffffff;
+                if (q < GPB && p < nsplit) {
+                    const part_t *pp = &partial[(base + q) * nsplit + p];
+                    unsigned long long ob = __hip_atomic_load(
+                        reinterpret_cast<const unsigned long long *>(&pp->obj), __ATOMIC_RELAXED,
+                        __HIP_MEMORY_SCOPE_AGENT);
+                    b.idx = __hip_atomic_load(&pp->idx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    b.obj = __longlong_as_double((long long)ob);
+                }
+#pragma unroll
+                for (int off = 16; off > 0; off >>= 1) {
+                    double o = __shfl_xor(b.obj, off, 32);
+                    int i = __shfl_xor(b.idx, off, 32);
+                    if (better(o, i, b.obj, b.idx)) {
+                        b.obj = o;
+                        b.idx = i;
+                    }
+                }
+                if (q < GPB && p == 0) {
+                    s_fin_obj[q] = b.obj;
+                    s_fin_idx[q] = b.idx;
+                }
+            }
+            __syncthreads();
+            if (threadIdx.x == 0) {
+                arrivals[item] = 0;               // ready for the next call
+#pragma unroll
+                for (int q = 0; q < GPB; ++q) {
+                    mine[q].obj = s_fin_obj[q];
+                    mine[q].idx = s_fin_idx[q];
+                }
+            }
+        }
+        if (threadIdx.x == 0) {
+#pragma unroll
+            for (int q = 0; q < GPB; ++q) {
+                if (s_group[q] < 0) continue;
                 const int n = s_group[q];
                 const int prev = codes[n] & (csize - 1);
                 double o_prev = 0.0;
@@ -157,8 +253,8 @@ __global__ __launch_bounds__(kBlock) void k_exact_scan(
                     double r = (double)s_scale[q] * acc - (double)s_t[q][i];
                     o_prev = o_prev + r * r;
                 }
-                int pick = b.idx;
-                if (o_prev == b.obj || pick == 0x7fffffff) pick = prev;
+                int pick = mine[q].idx;
+                if (o_prev == mine[q].obj || pick == 0x7fffffff) pick = prev;
                 if (pick != prev) {
                     codes[n] = (uint16_t)pick;
                     if (num_changed) atomicAdd(num_changed, 1ull);
@@ -167,49 +263,26 @@ __global__ __launch_bounds__(kBlock) void k_exact_scan(
             }
         }
     }
-}
-
-// Combine the per-piece minima of the split scan (pieces are ascending codeword
-// ranges, so lexicographic (obj, idx) order keeps the lowest index) and apply
-// the tie rule against the previous code.
-__global__ __launch_bounds__(kBlock) void k_exact_finalize(
-    const float *__restrict__ T, const float *__restrict__ codebook,
-    const float *__restrict__ scales, const int32_t *__restrict__ list,
-    const uint32_t *__restrict__ d_count, int64_t max_count, uint16_t *__restrict__ codes,
-    unsigned long long *__restrict__ num_changed, unsigned long long *__restrict__ stat_counter,
-    int g, int nbits, int gpr, int N, int nsplit, const part_t *__restrict__ partial)
-{
-    const int64_t count = d_count ? (int64_t)*d_count : max_count;
-    const int csize = 1 << nbits;
-    for (int64_t j = (int64_t)blockIdx.x * kBlock + threadIdx.x; j < count;
-         j += (int64_t)gridDim.x * kBlock) {
-        const int n = list[j];
-        if (n < 0 || n >= N) continue;
-        best_t b;
-        b.obj = kInf;
-        b.idx = 0x7fffffff;
-        for (int p = 0; p < nsplit; ++p) {
-            part_t pt = partial[j * nsplit + p];
-            if (better(pt.obj, pt.idx, b.obj, b.idx)) {
-                b.obj = pt.obj;
-                b.idx = pt.idx;
-            }
+    // the filter's codebook statistics are dead once this (last) kernel of a call runs
+    if (reset_meta && blockIdx.x == 0 && threadIdx.x < 8) reset_meta[threadIdx.x] = 0u;
+    // fold the re-rank kernel's per-block counters (decided, changed, candidates) into the totals
+    if (rr_counts && blockIdx.x == 0) {
+        unsigned long long c0 = 0, c1 = 0, c2 = 0;
+        for (int b = threadIdx.x; b < rr_blocks; b += kBlock) {
+            c0 += rr_counts[3 * b];
+            c1 += rr_counts[3 * b + 1];
+            c2 += rr_counts[3 * b + 2];
         }
-        const float s = scales[n / gpr];
-        const int prev = codes[n] & (csize - 1);
-        double o_prev = 0.0;
-        for (int i = 0; i < g; ++i) {
-            double acc = (double)codebook[(int64_t)prev * g + i];
-            double r = (double)s * acc - (double)T[(int64_t)n * g + i];
-            o_prev = o_prev + r * r;
+        for (int off = 32; off > 0; off >>= 1) {
+            c0 += __shfl_down(c0, off);
+            c1 += __shfl_down(c1, off);
+            c2 += __shfl_down(c2, off);
         }
-        int pick = b.idx;
-        if (o_prev == b.obj || pick == 0x7fffffff) pick = prev;
-        if (pick != prev) {
-            codes[n] = (uint16_t)pick;
-            if (num_changed) atomicAdd(num_changed, 1ull);
+        if ((threadIdx.x & 63) == 0) {
+            if (c0) atomicAdd(&rr_stats[0], c0);
+            if (c2) atomicAdd(&rr_stats[2], c2);
+            if (c1 && num_changed) atomicAdd(num_changed, c1);
         }
-        if (stat_counter) atomicAdd(stat_counter, 1ull);
     }
 }
 
@@ -346,6 +419,26 @@ __global__ __launch_bounds__(kBlock) void k_beam(
 
 }  // namespace
 
+static void launch_scan(pv_ctx *ctx, int g, unsigned blocks, const float *T, const float *codebooks,
+                        const float *scales, const int32_t *list, const uint32_t *d_count,
+                        int64_t max_count, uint16_t *codes, int64_t *num_changed,
+                        int64_t *d_stat_counter, int nbits, int gpr, int N, int nsplit,
+                        part_t *partial, unsigned *arrivals, unsigned *reset_meta,
+                        const unsigned *rr_counts = nullptr, int rr_blocks = 0,
+                        unsigned long long *rr_stats = nullptr)
+{
+    auto nc = reinterpret_cast<unsigned long long *>(num_changed);
+    auto sc = reinterpret_cast<unsigned long long *>(d_stat_counter);
+#define PV_SCAN(G_)                                                                              \
+    hipLaunchKernelGGL(k_exact_scan<G_>, dim3(blocks), dim3(kBlock), 0, ctx->stream, T, codebooks, \
+                       scales, list, d_count, max_count, codes, nc, sc, g, nbits, gpr, N, nsplit,  \
+                       partial, arrivals, reset_meta, rr_counts, rr_blocks, rr_stats)
+    if (g == 8) PV_SCAN(8);
+    else if (g == 16) PV_SCAN(16);
+    else PV_SCAN(0);
+#undef PV_SCAN
+}
+
 pv_status pv_launch_exact_scan(pv_ctx *ctx, const pv_layout *l, const float *T,
                                const float *codebooks, const float *scales, const int32_t *list,
                                const uint32_t *d_count, int64_t max_count, uint16_t *codes,
@@ -358,11 +451,8 @@ pv_status pv_launch_exact_scan(pv_ctx *ctx, const pv_layout *l, const float *T,
     int64_t blocks = (max_count + GPB - 1) / GPB;
     if (blocks > 4096) blocks = 4096;
     if (blocks < 1) blocks = 1;
-    hipLaunchKernelGGL(k_exact_scan, dim3((unsigned)blocks), dim3(kBlock), 0, ctx->stream, T,
-                       codebooks, scales, list, d_count, max_count, codes,
-                       reinterpret_cast<unsigned long long *>(num_changed),
-                       reinterpret_cast<unsigned long long *>(d_stat_counter), g, l->nbits, gpr, N, 1,
-                       static_cast<part_t *>(nullptr));
+    launch_scan(ctx, g, (unsigned)blocks, T, codebooks, scales, list, d_count, max_count, codes,
+                num_changed, d_stat_counter, l->nbits, gpr, N, 1, nullptr, nullptr, nullptr);
     PV_HIP(ctx, hipGetLastError());
     return PV_OK;
 }
@@ -371,35 +461,29 @@ pv_status pv_launch_exact_scan_split(pv_ctx *ctx, const pv_layout *l, const floa
                                      const float *codebooks, const float *scales,
                                      const int32_t *list, const uint32_t *d_count,
                                      int64_t max_count, uint16_t *codes, int64_t *num_changed,
-                                     int64_t *d_stat_counter)
+                                     int64_t *d_stat_counter, unsigned *reset_meta,
+                                     const unsigned *rr_counts, int rr_blocks, int64_t *rr_stats)
 {
     const int g = l->group_size;
     const int gpr = (int)(l->in_features / g);
     const int N = (int)pv_num_groups(l);
     const int csize = 1 << l->nbits;
-    int nsplit = csize / 2048;          // at least 8 passes of 256 codewords per piece
-    if (nsplit > 16) nsplit = 16;
-    if (nsplit < 2)
-        return pv_launch_exact_scan(ctx, l, T, codebooks, scales, list, d_count, max_count, codes,
-                                    num_changed, d_stat_counter);
-    pv_status st = pv_ensure(ctx, ctx->fb_partial, (size_t)(max_count + GPB) * nsplit * sizeof(part_t));
+    int nsplit = csize / 1024;          // at least 4 passes of 256 codewords per piece
+    if (nsplit > 32) nsplit = 32;
+    if (nsplit < 1) nsplit = 1;
+    const int64_t items = (max_count + GPB - 1) / GPB;
+    pv_status st = pv_ensure(ctx, ctx->fb_partial, (size_t)(items * GPB) * nsplit * sizeof(part_t));
     if (st != PV_OK) return st;
-    part_t *partial = static_cast<part_t *>(ctx->fb_partial.ptr);
+    st = pv_ensure(ctx, ctx->fb_arrivals, (size_t)items * sizeof(unsigned), /*zero_new=*/true);
+    if (st != PV_OK) return st;
     pv_timed t(ctx, PV_K_EXACT_SCAN);
-    int64_t blocks = ((max_count + GPB - 1) / GPB) * nsplit;
+    int64_t blocks = items * nsplit;
     if (blocks > 2048) blocks = 2048;
-    hipLaunchKernelGGL(k_exact_scan, dim3((unsigned)blocks), dim3(kBlock), 0, ctx->stream, T,
-                       codebooks, scales, list, d_count, max_count, codes,
-                       reinterpret_cast<unsigned long long *>(num_changed),
-                       reinterpret_cast<unsigned long long *>(d_stat_counter), g, l->nbits, gpr, N,
-                       nsplit, partial);
-    int64_t fblocks = (max_count + kBlock - 1) / kBlock;
-    if (fblocks > 256) fblocks = 256;
-    hipLaunchKernelGGL(k_exact_finalize, dim3((unsigned)fblocks), dim3(kBlock), 0, ctx->stream, T,
-                       codebooks, scales, list, d_count, max_count, codes,
-                       reinterpret_cast<unsigned long long *>(num_changed),
-                       reinterpret_cast<unsigned long long *>(d_stat_counter), g, l->nbits, gpr, N,
-                       nsplit, partial);
+    launch_scan(ctx, g, (unsigned)blocks, T, codebooks, scales, list, d_count, max_count, codes,
+                num_changed, d_stat_counter, l->nbits, gpr, N, nsplit,
+                static_cast<part_t *>(ctx->fb_partial.ptr),
+                static_cast<unsigned *>(ctx->fb_arrivals.ptr), reset_meta, rr_counts, rr_blocks,
+                reinterpret_cast<unsigned long long *>(rr_stats));
     PV_HIP(ctx, hipGetLastError());
     return PV_OK;
 }

@@ -29,6 +29,7 @@ struct pv_ctx {
     hipStream_t stream = nullptr;
     char err[256] = {0};
     int search_mode = 0;
+    bool meta_dirty = false;   // cb_meta was not reset by the last kernel of a call
     bool timing = false;
     pv_timer timers[PV_K_COUNT];
     std::vector<hipEvent_t> event_pool;
@@ -46,6 +47,8 @@ struct pv_ctx {
     pv_buffer partials;     // u32 [k_pad][P][2]  best / runner-up keys per partition
     pv_buffer fb_list;      // i32 [k] + counter  groups handed to the exact scan
     pv_buffer fb_partial;   // (f64, i32) [k][pieces]  per-piece minima of the split exact scan
+    pv_buffer rr_counts;    // u32 [blocks][3]    per-block counters of the re-rank kernel
+    pv_buffer fb_arrivals;  // u32 [k/4]          pieces finished per work item (kept zero between calls)
 };
 
 // RAII bracket that records HIP events around a group of launches when timing is on.
@@ -91,7 +94,8 @@ pv_status pv_launch_exact_scan_split(pv_ctx *ctx, const pv_layout *l, const floa
                                      const float *codebooks, const float *scales,
                                      const int32_t *list, const uint32_t *d_count,
                                      int64_t max_count, uint16_t *codes, int64_t *num_changed,
-                                     int64_t *d_stat_counter);
+                                     int64_t *d_stat_counter, unsigned *reset_meta,
+                                     const unsigned *rr_counts, int rr_blocks, int64_t *rr_stats);
 pv_status pv_launch_beam(pv_ctx *ctx, const pv_layout *l, const float *T, const float *codebooks,
                          const float *scales, const int32_t *group_idx, int64_t k,
                          int32_t beam_width, uint16_t *codes, int64_t *num_changed);

@@ -75,117 +75,138 @@ __device__ __forceinline__ void split3(float v, _Float16 *p)
     p[2] = to_half_flush(r);
 }
 
+// Largest |entry| of the codebook (fixes the common scale P).  Block 0 also
+// clears the per-call counters, which only later launches touch.
 __global__ __launch_bounds__(kBlock) void k_cb_absmax(const float *__restrict__ cb, int64_t n,
-                                                      unsigned *__restrict__ meta)
+                                                      unsigned *__restrict__ meta,
+                                                      unsigned long long *__restrict__ stats,
+                                                      unsigned *__restrict__ fb_count,
+                                                      unsigned long long *__restrict__ num_changed)
 {
+    if (blockIdx.x == 0) {
+        if (threadIdx.x < 8) stats[threadIdx.x] = 0ull;
+        if (threadIdx.x < 4) fb_count[threadIdx.x] = 0u;
+        if (threadIdx.x == 0 && num_changed) *num_changed = 0ull;
+    }
     float m = 0.0f;
     bool bad = false;
-    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += (int64_t)gridDim.x * kBlock) {
-        float v = fabsf(cb[i]);
-        bad |= !(v <= 3.0e38f);
-        m = fmaxf(m, v);
+    const pv_f4 *cb4 = reinterpret_cast<const pv_f4 *>(cb);
+    const int64_t n4 = n >> 2;   // the codebook holds 2^B * g floats with g a multiple of 8
+    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < n4; i += (int64_t)gridDim.x * kBlock) {
+        pv_f4 v = cb4[i];
+        float a = fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w)));
+        bad |= !(fabsf(v.x) <= 3.0e38f) || !(fabsf(v.y) <= 3.0e38f) || !(fabsf(v.z) <= 3.0e38f) ||
+               !(fabsf(v.w) <= 3.0e38f);
+        m = fmaxf(m, a);
     }
     for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_down(m, off));
     if ((threadIdx.x & 63) == 0) atomicMax(&meta[0], __float_as_uint(m));
     if (bad) atomicMax(&meta[3], 1u);
 }
 
-// One thread per codeword: fp16 operand rows in MFMA order + rounding bounds.
-// Operand A of tile t (32 codewords), k-step j, k-half h, row r is the 16-byte
-// chunk  A[((t * NK + j) * 2 + h) * 32 + r].  Codeword c sits in tile c / 32 at
-// row 8*(q/4) + 4*hw + q%4 with hw = (c/16)%2, q = c%16, so that accumulator q
-// of half wave hw is codeword 32*t + 16*hw + q.
-template <int NK>
-__global__ __launch_bounds__(kBlock) void k_cb_prep(const float *__restrict__ cb, int csize, int g,
-                                                    unsigned *__restrict__ meta,
-                                                    h8 *__restrict__ A)
+// Operand preparation, one launch for both sides.
+//
+// Blocks [0, cb_blocks): one thread per codeword -> fp16 operand rows in MFMA
+// order + the rounding bound dC.  Operand A of tile t (32 codewords), k-step j,
+// k-half h, row r is the 16-byte chunk A[((t * NK + j) * 2 + h) * 32 + r].
+// Codeword c sits in tile c / 32 at row 8*(q/4) + 4*hw + q%4 with
+// hw = (c/16)%2, q = c%16, so that accumulator q of half wave hw is codeword
+// 32*t + 16*hw + q.
+//
+// Remaining blocks: one thread per selected group (position j in the list):
+// x = t / s, its fp16 copy in MFMA operand order, per-group bounds.  Operand B
+// of group tile gt, k-step j, k-half h, column col is the chunk
+// X[((gt * NK + j) * 2 + h) * 32 + col].
+template <int G>
+__global__ __launch_bounds__(kBlock) void k_prep(const float *__restrict__ cb, int csize,
+                                                 int cb_blocks, unsigned *__restrict__ meta,
+                                                 h8 *__restrict__ A, const float *__restrict__ T,
+                                                 const float *__restrict__ scales,
+                                                 const int32_t *__restrict__ group_idx, int k,
+                                                 int k_pad, int gpr, int N, h8 *__restrict__ X,
+                                                 float *__restrict__ x_meta)
 {
-    const int c = blockIdx.x * kBlock + threadIdx.x;
+    constexpr int NK = G / 8;
     bool ok;
     const float P = scale_from_maxabs(meta[0], &ok);
-    float n2 = 0.0f, d2 = 0.0f;
-    if (c < csize) {
-        const int tile = c >> 5, hw = (c >> 4) & 1, q = c & 15;
-        const int row = 8 * (q >> 2) + 4 * hw + (q & 3);
-        h8 chunk[2 * NK];
-#pragma unroll
-        for (int u = 0; u < 2 * NK; ++u)
-#pragma unroll
-            for (int e = 0; e < 8; ++e) chunk[u][e] = (_Float16)0.0f;
-        for (int i = 0; i < g; ++i) {
-            float v = ok ? P * cb[(int64_t)c * g + i] : 0.0f;
-            _Float16 hv = to_half_flush(v);
-            float hf = (float)hv;
-            n2 = fmaf(hf, hf, n2);
-            float d = v - hf;
-            d2 = fmaf(d, d, d2);
-            chunk[i >> 3][i & 7] = (_Float16)(-2.0f * hf);
-        }
-        _Float16 pieces[3];
-        split3(n2, pieces);
-        const int u = g / 8;  // first chunk after the coordinates
-        chunk[u][0] = pieces[0];
-        chunk[u][1] = pieces[1];
-        chunk[u][2] = pieces[2];
-        chunk[u][3] = (_Float16)1.0f;
-        chunk[u][4] = (_Float16)1.0f;
-        chunk[u][5] = (_Float16)1.0f;
-#pragma unroll
-        for (int u2 = 0; u2 < 2 * NK; ++u2) A[((int64_t)tile * NK * 2 + u2) * 32 + row] = chunk[u2];
-    }
-    for (int off = 32; off > 0; off >>= 1) {
-        n2 = fmaxf(n2, __shfl_down(n2, off));
-        d2 = fmaxf(d2, __shfl_down(d2, off));
-    }
-    if ((threadIdx.x & 63) == 0) {
-        atomicMax(&meta[1], __float_as_uint(n2));
-        atomicMax(&meta[2], __float_as_uint(d2));
-    }
-}
-
-// One thread per selected group (position j in the list): x = t / s, fp16 copy
-// in MFMA operand order, per-group bounds.  Operand B of group tile gt, k-step
-// j, k-half h, column col is the chunk X[((gt * NK + j) * 2 + h) * 32 + col].
-template <int NK>
-__global__ __launch_bounds__(kBlock) void k_x_prep(const float *__restrict__ T,
-                                                   const float *__restrict__ scales,
-                                                   const int32_t *__restrict__ group_idx, int k,
-                                                   int k_pad, int g, int gpr, int N,
-                                                   const unsigned *__restrict__ meta,
-                                                   h8 *__restrict__ X, float *__restrict__ x_meta)
-{
-    const int j = blockIdx.x * kBlock + threadIdx.x;
-    if (j >= k_pad) return;
-    bool ok;
-    const float P = scale_from_maxabs(meta[0], &ok);
-    ok = ok && meta[3] == 0u;
-    const float cmax = sqrtf(__uint_as_float(meta[1])) * 1.0001f;
     h8 chunk[2 * NK];
 #pragma unroll
     for (int u = 0; u < 2 * NK; ++u)
 #pragma unroll
         for (int e = 0; e < 8; ++e) chunk[u][e] = (_Float16)0.0f;
+
+    if ((int)blockIdx.x < cb_blocks) {
+        const int c = blockIdx.x * kBlock + threadIdx.x;
+        float d2 = 0.0f;
+        if (c < csize) {
+            float n2 = 0.0f;
+            const pv_f4 *src = reinterpret_cast<const pv_f4 *>(cb + (int64_t)c * G);
+#pragma unroll
+            for (int v4 = 0; v4 < G / 4; ++v4) {
+                pv_f4 raw = src[v4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int i = v4 * 4 + e;
+                    float v = ok ? P * raw[e] : 0.0f;
+                    _Float16 hv = to_half_flush(v);
+                    float hf = (float)hv;
+                    n2 = fmaf(hf, hf, n2);
+                    float d = v - hf;
+                    d2 = fmaf(d, d, d2);
+                    chunk[i >> 3][i & 7] = (_Float16)(-2.0f * hf);
+                }
+            }
+            _Float16 pieces[3];
+            split3(n2, pieces);
+            chunk[NK][0] = pieces[0];
+            chunk[NK][1] = pieces[1];
+            chunk[NK][2] = pieces[2];
+            chunk[NK][3] = (_Float16)1.0f;
+            chunk[NK][4] = (_Float16)1.0f;
+            chunk[NK][5] = (_Float16)1.0f;
+            const int tile = c >> 5, hw = (c >> 4) & 1, q = c & 15;
+            const int row = 8 * (q >> 2) + 4 * hw + (q & 3);
+#pragma unroll
+            for (int u = 0; u < 2 * NK; ++u) A[((int64_t)tile * NK * 2 + u) * 32 + row] = chunk[u];
+        }
+        for (int off = 32; off > 0; off >>= 1) d2 = fmaxf(d2, __shfl_down(d2, off));
+        if ((threadIdx.x & 63) == 0) atomicMax(&meta[2], __float_as_uint(d2));
+        return;
+    }
+
+    const int j = ((int)blockIdx.x - cb_blocks) * kBlock + threadIdx.x;
+    if (j >= k_pad) return;
+    ok = ok && meta[3] == 0u;
+    // ||c_hi|| <= sqrt(G) * 32 because every scaled codebook entry is below 32 in magnitude
+    const float cmax = 32.0f * (G == 8 ? 2.8285f : 4.0004f);
     float off = 0.0f, e1 = 0.0f, dx = 0.0f, flag = 1.0f;
     const int n = j < k ? group_idx[j] : -1;
     if (n >= 0 && n < N && ok) {
         const float s = scales[n / gpr];
-        const float inv_ok = (s != 0.0f && fabsf(s) < 3.0e38f) ? 1.0f : 0.0f;
+        bool fits = (s != 0.0f) && (fabsf(s) < 3.0e38f);
+        const float div = fits ? s : 1.0f;
         float xx = 0.0f, d2 = 0.0f, u2 = 0.0f;
-        bool fits = inv_ok != 0.0f;
-        for (int i = 0; i < g; ++i) {
-            float x = T[(int64_t)n * g + i] / (fits ? s : 1.0f);
-            float u = P * x;
-            if (!(fabsf(u) < 240.0f)) fits = false;   // also catches NaN / inf
-            _Float16 hv = to_half_flush(fits ? u : 0.0f);
-            float hf = (float)hv;
-            xx = fmaf(hf, hf, xx);
-            float d = u - hf;
-            d2 = fmaf(d, d, d2);
-            u2 = fmaf(u, u, u2);
-            chunk[i >> 3][i & 7] = hv;
+        const pv_f4 *src = reinterpret_cast<const pv_f4 *>(T + (int64_t)n * G);
+#pragma unroll
+        for (int v4 = 0; v4 < G / 4; ++v4) {
+            pv_f4 raw = src[v4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const int i = v4 * 4 + e;
+                float u = P * (raw[e] / div);
+                if (!(fabsf(u) < 240.0f)) fits = false;   // also catches NaN / inf
+                _Float16 hv = to_half_flush(fits ? u : 0.0f);
+                float hf = (float)hv;
+                xx = fmaf(hf, hf, xx);
+                float d = u - hf;
+                d2 = fmaf(d, d, d2);
+                u2 = fmaf(u, u, u2);
+                chunk[i >> 3][i & 7] = hv;
+            }
         }
         if (fits && xx < 57000.0f) {
             const float xn = sqrtf(xx) * 1.0001f;
+            // bound of the fp32 accumulation error of one accumulator, plus dropped fp16 pieces
             const float e1p = kGamma * (cmax + xn) * (cmax + xn) * 1.01f + 2.5e-4f;
             off = 4.0f * e1p;
             e1 = 1.01f * e1p;
@@ -194,13 +215,12 @@ __global__ __launch_bounds__(kBlock) void k_x_prep(const float *__restrict__ T,
             flag = 0.0f;
             _Float16 pieces[3];
             split3(xx + off, pieces);
-            const int u = g / 8;
-            chunk[u][0] = (_Float16)1.0f;
-            chunk[u][1] = (_Float16)1.0f;
-            chunk[u][2] = (_Float16)1.0f;
-            chunk[u][3] = pieces[0];
-            chunk[u][4] = pieces[1];
-            chunk[u][5] = pieces[2];
+            chunk[NK][0] = (_Float16)1.0f;
+            chunk[NK][1] = (_Float16)1.0f;
+            chunk[NK][2] = (_Float16)1.0f;
+            chunk[NK][3] = pieces[0];
+            chunk[NK][4] = pieces[1];
+            chunk[NK][5] = pieces[2];
         } else {
 #pragma unroll
             for (int u = 0; u < 2 * NK; ++u)
@@ -211,12 +231,12 @@ __global__ __launch_bounds__(kBlock) void k_x_prep(const float *__restrict__ T,
     const int gt = j >> 5, col = j & 31;
 #pragma unroll
     for (int u = 0; u < 2 * NK; ++u) X[((int64_t)gt * NK * 2 + u) * 32 + col] = chunk[u];
-    float4 m;
+    pv_f4 m;
     m.x = off;
     m.y = e1;
     m.z = dx;
     m.w = flag;
-    reinterpret_cast<float4 *>(x_meta)[j] = m;
+    reinterpret_cast<pv_f4 *>(x_meta)[j] = m;
 }
 
 // Plain C so that the compiler sees the reads of MFMA results and inserts the
@@ -376,152 +396,169 @@ __device__ __forceinline__ bool cand_better(double o1, int i1, double o2, int i2
     return o1 < o2 || (o1 == o2 && i1 < i2);
 }
 
-__device__ __forceinline__ double exact_obj(const float *__restrict__ cw, float s,
-                                            const float *t, int g)
+template <int G>
+__device__ __forceinline__ double exact_obj(const float *__restrict__ cw, float s, const float *t)
 {
+    const pv_f4 *c4 = reinterpret_cast<const pv_f4 *>(cw);
     double obj = 0.0;
-    for (int i = 0; i < g; ++i) {
-        double acc = (double)cw[i];
-        double r = (double)s * acc - (double)t[i];
-        obj = obj + r * r;
+#pragma unroll
+    for (int v4 = 0; v4 < G / 4; ++v4) {
+        pv_f4 c = c4[v4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            double acc = (double)c[e];
+            double r = (double)s * acc - (double)t[v4 * 4 + e];
+            obj = obj + r * r;
+        }
     }
     return obj;
 }
 
-constexpr int kMaxG = 16;
-
-// 16 lanes per selected group.
+// 16 lanes ("team") per selected group; lane q scores codeword q of a half tile.
+template <int G>
 __global__ __launch_bounds__(kBlock) void k_rerank(
     const float *__restrict__ T, const float *__restrict__ codebook,
     const float *__restrict__ scales, const int32_t *__restrict__ group_idx, int k,
     const uint2 *__restrict__ partials, int P, int per_half, const float *__restrict__ x_meta,
     const unsigned *__restrict__ cb_meta, uint16_t *__restrict__ codes,
-    unsigned long long *__restrict__ num_changed, int32_t *__restrict__ fb_list,
-    unsigned *__restrict__ fb_count, unsigned long long *__restrict__ stats, int g, int gpr, int N,
-    int nbits)
+    unsigned *__restrict__ block_counts, int32_t *__restrict__ fb_list,
+    unsigned *__restrict__ fb_count, int gpr, int N, int nbits)
 {
+    __shared__ unsigned s_cnt[3];   // groups decided here, codes changed, candidates evaluated
+    if (threadIdx.x < 3) s_cnt[threadIdx.x] = 0;
+    __syncthreads();
     const int gid = blockIdx.x * kBlock + threadIdx.x;
     const int j = gid >> 4, q = gid & 15;
-    if (j >= k) return;                      // whole 16-lane teams leave together
-    const int n = group_idx[j];
-    if (n < 0 || n >= N) return;
-    const float4 meta = reinterpret_cast<const float4 *>(x_meta)[j];
-    if (meta.w != 0.0f) {                    // the filter was skipped for this group
+    const int n = j < k ? group_idx[j] : -1;
+    bool live = n >= 0 && n < N;             // whole 16-lane teams agree on every branch below
+    pv_f4 meta = {0.f, 0.f, 0.f, 1.f};
+    if (live) meta = reinterpret_cast<const pv_f4 *>(x_meta)[j];
+    if (live && meta.w != 0.0f) {            // the filter was skipped for this group
         if (q == 0) fb_list[atomicAdd(fb_count, 1u)] = n;
-        return;
+        live = false;
     }
-    const int csize = 1 << nbits;
-    const float s = scales[n / gpr];
-    float t[kMaxG];
-    for (int i = 0; i < g; ++i) t[i] = T[(int64_t)n * g + i];
-
-    // best key over all partitions, with its partition
-    constexpr int kMaxRec = 4;               // P <= 64
-    uint2 rec[kMaxRec];
-    unsigned long long bk = ~0ull;
+    if (live) {
+        const int csize = 1 << nbits;
+        const float s = scales[n / gpr];
+        float t[G];
+        {
+            const pv_f4 *t4 = reinterpret_cast<const pv_f4 *>(T + (int64_t)n * G);
 #pragma unroll
-    for (int u = 0; u < kMaxRec; ++u) {
-        int p = q + 16 * u;
-        rec[u] = p < P ? partials[(int64_t)j * P + p] : make_uint2(0xFFFFFFFFu, 0xFFFFFFFFu);
-        unsigned long long v = ((unsigned long long)rec[u].x << 32) | (unsigned)p;
-        bk = v < bk ? v : bk;
-    }
-#pragma unroll
-    for (int m = 8; m > 0; m >>= 1) {
-        unsigned long long o = __shfl_xor(bk, m, 16);
-        bk = o < bk ? o : bk;
-    }
-    const unsigned best_key = (unsigned)(bk >> 32);
-    const int best_p = (int)(bk & 0xFFFFFFFFu);
-
-    auto eval_half_tile = [&](unsigned key, int p, cand_t &c) {
-        const int tile = (int)(key & kTileMask);
-        const int hw = (p / per_half) & 1;
-        const int cw = tile * 32 + hw * 16 + q;
-        double o = exact_obj(codebook + (int64_t)cw * g, s, t, g);
-        if (cand_better(o, cw, c.obj, c.idx)) {
-            c.obj = o;
-            c.idx = cw;
-        }
-    };
-    auto team_min = [&](cand_t c) {
-#pragma unroll
-        for (int m = 8; m > 0; m >>= 1) {
-            double o = __shfl_xor(c.obj, m, 16);
-            int i = __shfl_xor(c.idx, m, 16);
-            if (cand_better(o, i, c.obj, c.idx)) {
-                c.obj = o;
-                c.idx = i;
+            for (int v4 = 0; v4 < G / 4; ++v4) {
+                pv_f4 v = t4[v4];
+                t[v4 * 4 + 0] = v.x;
+                t[v4 * 4 + 1] = v.y;
+                t[v4 * 4 + 2] = v.z;
+                t[v4 * 4 + 3] = v.w;
             }
         }
-        return c;
-    };
-
-    cand_t mine;
-    mine.obj = __builtin_huge_val();
-    mine.idx = 0x7fffffff;
-    eval_half_tile(best_key, best_p, mine);
-    cand_t first = team_min(mine);
-    const int prev = codes[n] & (csize - 1);
-    const double o_prev = exact_obj(codebook + (int64_t)prev * g, s, t, g);
-    if (o_prev < first.obj) first.obj = o_prev;   // the previous code is a candidate too
-
-    // every codeword that was not evaluated and could still reach E* has a key value below vcut
-    const float Pscale = [&] {
-        bool ok;
-        return scale_from_maxabs(cb_meta[0], &ok);
-    }();
-    const double dC = sqrt((double)__uint_as_float(cb_meta[2])) * 1.0001 + 1e-30;
-    const double dstar = sqrt(first.obj) * (double)Pscale / fabs((double)s) * (1.0 + 1e-9);
-    const double reach = dstar + dC + (double)meta.z;
-    const double vcut_d = (reach * reach + (double)meta.x + (double)meta.y) * (1.0 + 1e-6);
-    const float vcut = __double2float_ru(vcut_d);
-    const bool finite_cut = vcut_d < 3.0e38 && vcut_d == vcut_d;
-
-    bool uncertain = !finite_cut;
-    unsigned pending = 0;                     // bit u: rec[u].x needs evaluation
+        // best key over all partitions, with its partition
+        constexpr int kMaxRec = 4;           // P <= 64
+        uint2 rec[kMaxRec];
+        unsigned long long bk = ~0ull;
 #pragma unroll
-    for (int u = 0; u < kMaxRec; ++u) {
-        int p = q + 16 * u;
-        if (p < P) {
-            if (__uint_as_float(rec[u].y & ~kTileMask) < vcut) uncertain = true;
-            if (p != best_p && __uint_as_float(rec[u].x & ~kTileMask) < vcut) pending |= 1u << u;
+        for (int u = 0; u < kMaxRec; ++u) {
+            int p = q + 16 * u;
+            rec[u] = p < P ? partials[(int64_t)j * P + p] : make_uint2(0xFFFFFFFFu, 0xFFFFFFFFu);
+            unsigned long long v = ((unsigned long long)rec[u].x << 32) | (unsigned)p;
+            bk = v < bk ? v : bk;
+        }
+#pragma unroll
+        for (int m = 8; m > 0; m >>= 1) {
+            unsigned long long o = __shfl_xor(bk, m, 16);
+            bk = o < bk ? o : bk;
+        }
+        const unsigned best_key = (unsigned)(bk >> 32);
+        const int best_p = (int)(bk & 0xFFFFFFFFu);
+
+        auto eval_half_tile = [&](unsigned key, int p, cand_t &c) {
+            const int tile = (int)(key & kTileMask);
+            const int hw = (p / per_half) & 1;
+            const int cw = tile * 32 + hw * 16 + q;
+            double o = exact_obj<G>(codebook + (int64_t)cw * G, s, t);
+            if (cand_better(o, cw, c.obj, c.idx)) {
+                c.obj = o;
+                c.idx = cw;
+            }
+        };
+        auto team_min = [&](cand_t c) {
+#pragma unroll
+            for (int m = 8; m > 0; m >>= 1) {
+                double o = __shfl_xor(c.obj, m, 16);
+                int i = __shfl_xor(c.idx, m, 16);
+                if (cand_better(o, i, c.obj, c.idx)) {
+                    c.obj = o;
+                    c.idx = i;
+                }
+            }
+            return c;
+        };
+
+        cand_t mine;
+        mine.obj = __builtin_huge_val();
+        mine.idx = 0x7fffffff;
+        eval_half_tile(best_key, best_p, mine);
+        cand_t first = team_min(mine);
+        const int prev = codes[n] & (csize - 1);
+        const double o_prev = exact_obj<G>(codebook + (int64_t)prev * G, s, t);
+        if (o_prev < first.obj) first.obj = o_prev;   // the previous code is a candidate too
+
+        // every codeword that was not evaluated and could still reach E* has a key value below vcut
+        bool okP;
+        const float Pscale = scale_from_maxabs(cb_meta[0], &okP);
+        const double dC = sqrt((double)__uint_as_float(cb_meta[2])) * 1.0001 + 1e-30;
+        const double dstar = sqrt(first.obj) * (double)Pscale / fabs((double)s) * (1.0 + 1e-9);
+        const double reach = dstar + dC + (double)meta.z;
+        const double vcut_d = (reach * reach + (double)meta.x + (double)meta.y) * (1.0 + 1e-6);
+        const float vcut = __double2float_ru(vcut_d);
+        bool uncertain = !(vcut_d < 3.0e38);          // also true for NaN
+        unsigned pending = 0;                         // bit u: rec[u].x needs evaluation
+#pragma unroll
+        for (int u = 0; u < kMaxRec; ++u) {
+            int p = q + 16 * u;
+            if (p < P) {
+                if (__uint_as_float(rec[u].y & ~kTileMask) < vcut) uncertain = true;
+                if (p != best_p && __uint_as_float(rec[u].x & ~kTileMask) < vcut) pending |= 1u << u;
+            }
+        }
+        const int team_shift = (threadIdx.x & 63) & ~15;
+        const unsigned long long unc = __ballot(uncertain);
+        if ((unc >> team_shift) & 0xFFFFull) {
+            if (q == 0) fb_list[atomicAdd(fb_count, 1u)] = n;
+        } else {
+            unsigned extra = 0;
+            for (;;) {
+                const unsigned long long pb = __ballot(pending != 0);
+                const unsigned team = (unsigned)((pb >> team_shift) & 0xFFFFull);
+                if (!team) break;
+                const int src = __ffs(team) - 1;      // lane of the team with work
+                const unsigned their = __shfl(pending, src, 16);
+                const int u = __ffs(their) - 1;
+                unsigned key = 0;
+#pragma unroll
+                for (int uu = 0; uu < kMaxRec; ++uu)
+                    if (uu == u) key = rec[uu].x;
+                key = __shfl(key, src, 16);
+                eval_half_tile(key, src + 16 * u, mine);
+                if (q == src) pending &= ~(1u << u);
+                ++extra;
+            }
+            const cand_t win = team_min(mine);
+            if (q == 0) {
+                int pick = win.idx;
+                if (o_prev <= win.obj || pick == 0x7fffffff) pick = prev;
+                if (pick != prev) {
+                    codes[n] = (uint16_t)pick;
+                    atomicAdd(&s_cnt[1], 1u);
+                }
+                atomicAdd(&s_cnt[0], 1u);
+                atomicAdd(&s_cnt[2], 16u * (1u + extra) + 1u);
+            }
         }
     }
-    const int team_shift = (threadIdx.x & 63) & ~15;
-    unsigned long long unc = __ballot(uncertain);
-    if ((unc >> team_shift) & 0xFFFFull) {
-        if (q == 0) fb_list[atomicAdd(fb_count, 1u)] = n;
-        return;
-    }
-    unsigned extra = 0;
-    for (;;) {
-        unsigned long long pb = __ballot(pending != 0);
-        unsigned team = (unsigned)((pb >> team_shift) & 0xFFFFull);
-        if (!team) break;
-        const int src = __ffs(team) - 1;                      // lane of the team with work
-        const unsigned their = __shfl(pending, src, 16);
-        const int u = __ffs(their) - 1;
-        unsigned key = 0;
-#pragma unroll
-        for (int uu = 0; uu < kMaxRec; ++uu)
-            if (uu == u) key = rec[uu].x;
-        key = __shfl(key, src, 16);
-        eval_half_tile(key, src + 16 * u, mine);
-        if (q == src) pending &= ~(1u << u);
-        ++extra;
-    }
-    cand_t win = team_min(mine);
-    if (q == 0) {
-        int pick = win.idx;
-        if (o_prev <= win.obj || pick == 0x7fffffff) pick = prev;
-        if (pick != prev) {
-            codes[n] = (uint16_t)pick;
-            if (num_changed) atomicAdd(num_changed, 1ull);
-        }
-        atomicAdd(&stats[0], 1ull);
-        atomicAdd(&stats[2], (unsigned long long)(16 * (1 + extra) + 1));
-    }
+    __syncthreads();
+    // per-block totals; the last kernel of the call adds them up (no same-address atomics here)
+    if (threadIdx.x < 3) block_counts[3 * blockIdx.x + threadIdx.x] = s_cnt[threadIdx.x];
 }
 
 __global__ void k_fill_u32(unsigned *p, int n, unsigned v)
@@ -577,11 +614,14 @@ pv_status pv_launch_mfma_search(pv_ctx *ctx, const pv_layout *l, const float *T,
     const int N = (int)pv_num_groups(l);
     pv_status st;
     if ((st = pv_ensure(ctx, ctx->cb_f16, (size_t)csize * p.NK * 32)) != PV_OK) return st;
-    if ((st = pv_ensure(ctx, ctx->cb_meta, 8 * sizeof(unsigned))) != PV_OK) return st;
+    if ((st = pv_ensure(ctx, ctx->cb_meta, 8 * sizeof(unsigned), /*zero_new=*/true)) != PV_OK) return st;
     if ((st = pv_ensure(ctx, ctx->x_f16, (size_t)p.k_pad * p.NK * 32)) != PV_OK) return st;
     if ((st = pv_ensure(ctx, ctx->x_meta, (size_t)p.k_pad * 4 * sizeof(float))) != PV_OK) return st;
     if ((st = pv_ensure(ctx, ctx->partials, (size_t)p.k_pad * p.P * sizeof(uint2))) != PV_OK) return st;
     if ((st = pv_ensure(ctx, ctx->fb_list, ((size_t)k + 4) * sizeof(int32_t))) != PV_OK) return st;
+    const int rr_blocks = (int)((k * 16 + kBlock - 1) / kBlock);
+    if ((st = pv_ensure(ctx, ctx->rr_counts, (size_t)rr_blocks * 3 * sizeof(unsigned))) != PV_OK) return st;
+    unsigned *rr_counts = static_cast<unsigned *>(ctx->rr_counts.ptr);
     h8 *A = static_cast<h8 *>(ctx->cb_f16.ptr);
     h8 *X = static_cast<h8 *>(ctx->x_f16.ptr);
     unsigned *cb_meta = static_cast<unsigned *>(ctx->cb_meta.ptr);
@@ -591,24 +631,27 @@ pv_status pv_launch_mfma_search(pv_ctx *ctx, const pv_layout *l, const float *T,
     unsigned *fb_count = reinterpret_cast<unsigned *>(ctx->fb_list.ptr);
     unsigned long long *stats = static_cast<unsigned long long *>(ctx->stats.ptr);
     hipStream_t sm = ctx->stream;
+    if (ctx->meta_dirty) {   // a previous call did not run to its last kernel
+        hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(64), 0, sm, cb_meta, 8, 0u);
+    }
+    ctx->meta_dirty = true;
     {
         pv_timed t(ctx, PV_K_PREP);
-        hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(64), 0, sm, cb_meta, 8, 0u);
-        hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(64), 0, sm, fb_count, 4, 0u);
         const int64_t ncb = (int64_t)csize * g;
-        int blocks = (int)((ncb + kBlock * 8 - 1) / (kBlock * 8));
-        hipLaunchKernelGGL(k_cb_absmax, dim3(blocks), dim3(kBlock), 0, sm, codebooks, ncb, cb_meta);
-        if (p.NK == 1) {
-            hipLaunchKernelGGL(k_cb_prep<1>, dim3((csize + kBlock - 1) / kBlock), dim3(kBlock), 0, sm,
-                               codebooks, csize, g, cb_meta, A);
-            hipLaunchKernelGGL(k_x_prep<1>, dim3((p.k_pad + kBlock - 1) / kBlock), dim3(kBlock), 0, sm, T, scales,
-                               group_idx, (int)k, p.k_pad, g, gpr, N, cb_meta, X, x_meta);
-        } else {
-            hipLaunchKernelGGL(k_cb_prep<2>, dim3((csize + kBlock - 1) / kBlock), dim3(kBlock), 0, sm,
-                               codebooks, csize, g, cb_meta, A);
-            hipLaunchKernelGGL(k_x_prep<2>, dim3((p.k_pad + kBlock - 1) / kBlock), dim3(kBlock), 0, sm, T, scales,
-                               group_idx, (int)k, p.k_pad, g, gpr, N, cb_meta, X, x_meta);
-        }
+        int blocks = (int)((ncb / 4 + kBlock * 4 - 1) / (kBlock * 4));
+        if (blocks > 256) blocks = 256;
+        hipLaunchKernelGGL(k_cb_absmax, dim3(blocks), dim3(kBlock), 0, sm, codebooks, ncb, cb_meta,
+                           stats, fb_count, reinterpret_cast<unsigned long long *>(num_changed));
+        const int cb_blocks = (csize + kBlock - 1) / kBlock;
+        const int x_blocks = (p.k_pad + kBlock - 1) / kBlock;
+        if (g == 8)
+            hipLaunchKernelGGL(k_prep<8>, dim3(cb_blocks + x_blocks), dim3(kBlock), 0, sm, codebooks,
+                               csize, cb_blocks, cb_meta, A, T, scales, group_idx, (int)k, p.k_pad,
+                               gpr, N, X, x_meta);
+        else
+            hipLaunchKernelGGL(k_prep<16>, dim3(cb_blocks + x_blocks), dim3(kBlock), 0, sm,
+                               codebooks, csize, cb_blocks, cb_meta, A, T, scales, group_idx, (int)k,
+                               p.k_pad, gpr, N, X, x_meta);
     }
     {
         pv_timed t(ctx, PV_K_SCORE_MFMA);
@@ -629,14 +672,22 @@ pv_status pv_launch_mfma_search(pv_ctx *ctx, const pv_layout *l, const float *T,
     }
     {
         pv_timed t(ctx, PV_K_RERANK);
-        const int64_t threads = k * 16;
-        hipLaunchKernelGGL(k_rerank, dim3((unsigned)((threads + kBlock - 1) / kBlock)), dim3(kBlock), 0,
-                           sm, T, codebooks, scales, group_idx, (int)k, partials, p.P, p.per_half,
-                           x_meta, cb_meta, codes,
-                           reinterpret_cast<unsigned long long *>(num_changed), fb_list, fb_count,
-                           stats, g, gpr, N, l->nbits);
+        const dim3 rgrid((unsigned)rr_blocks);
+        if (g == 8)
+            hipLaunchKernelGGL(k_rerank<8>, rgrid, dim3(kBlock), 0, sm, T, codebooks, scales,
+                               group_idx, (int)k, partials, p.P, p.per_half, x_meta, cb_meta, codes,
+                               rr_counts, fb_list, fb_count, gpr, N, l->nbits);
+        else
+            hipLaunchKernelGGL(k_rerank<16>, rgrid, dim3(kBlock), 0, sm, T, codebooks, scales,
+                               group_idx, (int)k, partials, p.P, p.per_half, x_meta, cb_meta, codes,
+                               rr_counts, fb_list, fb_count, gpr, N, l->nbits);
     }
     PV_HIP(ctx, hipGetLastError());
-    return pv_launch_exact_scan_split(ctx, l, T, codebooks, scales, fb_list, fb_count, k, codes,
-                                      num_changed, reinterpret_cast<int64_t *>(stats + 1));
+    pv_status fin = pv_launch_exact_scan_split(ctx, l, T, codebooks, scales, fb_list, fb_count, k,
+                                               codes, num_changed,
+                                               reinterpret_cast<int64_t *>(stats + 1), cb_meta,
+                                               rr_counts, rr_blocks,
+                                               reinterpret_cast<int64_t *>(stats));
+    if (fin == PV_OK) ctx->meta_dirty = false;
+    return fin;
 }

@@ -3,43 +3,50 @@
 // score_n = sum_i (T[n,i] - W[n,i])^2 as an fp32 fused-multiply-add chain in
 // index order, so that every implementation of this rule gives the same bits.
 // Scores are non-negative floats, so their bit patterns order like unsigned
-// integers.  The k-th largest key is found by a 3-digit radix select (11+11+10
-// bits, most significant first); groups above the threshold are taken, groups
+// integers.  The k-th largest key is found by a 3-digit radix select (13 + 13 +
+// 6 bits, most significant first); groups above the threshold are taken, groups
 // equal to it are taken lowest id first, and the ids are written in ascending
 // order through a two-level prefix sum.  Nothing returns to the host.
 //
 // Launches: [scores + digit-0 histogram] [digit-1 histogram] [digit-2 histogram]
-// [per-block counts] [ordered write].  Every block re-derives the digits chosen
-// so far from the (tiny) histograms instead of waiting for a separate kernel.
+// [per-chunk counts] [ordered write].  Every block re-derives the digits chosen
+// so far from the (small) histograms instead of waiting for a separate kernel.
+// Blocks are persistent (a few per compute unit, grid-stride over the input) so
+// that clearing and flushing the LDS histogram is paid once per block.
 #include "pv_internal.h"
 
 namespace {
 
 constexpr int kBlock = 256;
-constexpr int kBins = 2048;
+constexpr int kBins = 8192;                    // 13-bit digits
+constexpr int kLastBins = 64;                  // the last digit has 6 bits
 constexpr int kItems = 8;                      // groups per thread in the compaction kernels
-constexpr int kChunk = kBlock * kItems;        // groups per block there
+constexpr int kChunk = kBlock * kItems;        // groups per chunk there
+constexpr int kMaxBlocks = 1024;               // persistent grid: 4 blocks per compute unit
 
 __device__ __forceinline__ int digit_of(unsigned key, int pass)
 {
-    return pass == 0 ? (int)(key >> 21) : pass == 1 ? (int)((key >> 10) & 2047u) : (int)(key & 1023u);
+    return pass == 0 ? (int)(key >> 19) : pass == 1 ? (int)((key >> 6) & 8191u) : (int)(key & 63u);
 }
 
 // Add one count per valid lane to an LDS histogram.  Lanes of a wave that hit
-// the same bin are merged first (two rounds catch the dominant bins of a
-// narrow score distribution); the rest fall back to one atomic each.
+// the same bin as the first pending lane are merged first (catches the
+// dominant bins of a narrow score distribution); the rest use one atomic each.
+template <int ROUNDS>
 __device__ __forceinline__ void hist_add(unsigned *hist, int bin, bool valid)
 {
     const int lane = threadIdx.x & 63;
-    unsigned long long todo = __ballot(valid);
+    if (ROUNDS > 0) {
+        unsigned long long todo = __ballot(valid);
 #pragma unroll 1
-    for (int round = 0; round < 2 && todo; ++round) {
-        int leader = __ffsll((long long)todo) - 1;
-        int lb = __shfl(bin, leader);
-        unsigned long long same = __ballot(valid && bin == lb);
-        if (lane == leader) atomicAdd(&hist[lb], (unsigned)__popcll(same));
-        if (valid && bin == lb) valid = false;
-        todo &= ~same;
+        for (int round = 0; round < ROUNDS && todo; ++round) {
+            int leader = __ffsll((long long)todo) - 1;
+            int lb = __shfl(bin, leader);
+            unsigned long long same = __ballot(valid && bin == lb);
+            if (lane == leader) atomicAdd(&hist[lb], (unsigned)__popcll(same));
+            if (valid && bin == lb) valid = false;
+            todo &= ~same;
+        }
     }
     if (valid) atomicAdd(&hist[bin], 1u);
 }
@@ -70,6 +77,16 @@ __device__ __forceinline__ unsigned block_excl_scan(unsigned v, unsigned *tmp, u
     return before + inc - v;
 }
 
+// Global histograms are stored so that the scan below reads them coalesced:
+// digit d of a `bins`-digit histogram has rank r = bins - 1 - d from the top and
+// lives at slot (r % 32) * 256 + r / 32; thread t of the scan owns ranks
+// [32 t, 32 t + 32), i.e. slots t, t + 256, ...  Every histogram occupies kBins slots.
+__device__ __forceinline__ int hist_slot(int digit, int bins)
+{
+    const int r = bins - 1 - digit;
+    return (r & 31) * kBlock + (r >> 5);
+}
+
 // Given a histogram of `bins` digits and the rank `kk` (1-based, counted from the
 // largest digit), find the digit d with  count(> d) < kk <= count(>= d)  and
 // return kk - count(> d).  All threads of the block call this; the result goes
@@ -77,31 +94,55 @@ __device__ __forceinline__ unsigned block_excl_scan(unsigned v, unsigned *tmp, u
 __device__ void pick_digit(const unsigned *__restrict__ ghist, int bins, unsigned kk,
                            unsigned *tmp, int *digit, unsigned *kk_rem)
 {
-    constexpr int per = kBins / kBlock;  // 8 bins per thread; thread 0 owns the TOP bins
+    constexpr int per = kBins / kBlock;  // 32 ranks per thread; thread 0 owns the TOP digits
     const int tid = threadIdx.x;
-    unsigned local[per];
+    unsigned cnt[per];
     unsigned sum = 0;
 #pragma unroll
     for (int j = 0; j < per; ++j) {
-        int bin = bins - 1 - (tid * per + j);
-        local[j] = bin >= 0 ? ghist[bin] : 0u;
-        sum += local[j];
+        cnt[j] = (tid * per + j) < bins ? ghist[j * kBlock + tid] : 0u;
+        sum += cnt[j];
     }
     unsigned total;
     unsigned above = block_excl_scan(sum, tmp, &total);
 #pragma unroll
     for (int j = 0; j < per; ++j) {
-        int bin = bins - 1 - (tid * per + j);
-        if (bin >= 0 && above < kk && kk <= above + local[j]) {
-            tmp[kBlock] = (unsigned)bin;
+        if (above < kk && kk <= above + cnt[j]) {
+            tmp[kBlock] = (unsigned)(bins - 1 - (tid * per + j));
             tmp[kBlock + 1] = kk - above;
         }
-        above += local[j];
+        above += cnt[j];
     }
     __syncthreads();
     *digit = (int)tmp[kBlock];
     *kk_rem = tmp[kBlock + 1];
     __syncthreads();
+}
+
+__device__ __forceinline__ void flush_hist(const unsigned *lh, unsigned *__restrict__ gh, int bins)
+{
+    for (int b = threadIdx.x; b < bins; b += kBlock) {
+        unsigned v = lh[b];
+        if (v) atomicAdd(&gh[hist_slot(b, bins)], v);
+    }
+}
+
+// One count per valid lane straight into a global histogram (few candidates
+// reach the later digits).  One merge round keeps a degenerate input (all keys
+// equal) from serialising on a single address.
+__device__ __forceinline__ void global_hist_add(unsigned *__restrict__ gh, int bin, int bins,
+                                                bool valid)
+{
+    const int lane = threadIdx.x & 63;
+    unsigned long long todo = __ballot(valid);
+    if (todo) {
+        int leader = __ffsll((long long)todo) - 1;
+        int lb = __shfl(bin, leader);
+        unsigned long long same = __ballot(valid && bin == lb);
+        if (lane == leader) atomicAdd(&gh[hist_slot(lb, bins)], (unsigned)__popcll(same));
+        if (valid && bin == lb) valid = false;
+    }
+    if (valid) atomicAdd(&gh[hist_slot(bin, bins)], 1u);
 }
 
 __device__ __forceinline__ float score_group(const float *__restrict__ t,
@@ -129,59 +170,143 @@ __device__ __forceinline__ float score_group(const float *__restrict__ t,
     return s;
 }
 
-// Pass 0: one thread per group: score, store, histogram of the top 11 key bits.
+// Pass 0, any group size: one thread per group.
 __global__ __launch_bounds__(kBlock) void k_scores_hist0(const float *__restrict__ T,
                                                          const float *__restrict__ W,
                                                          float *__restrict__ scores,
-                                                         unsigned *__restrict__ hist0, int N, int g)
+                                                         unsigned *__restrict__ hist0, int N, int g,
+                                                         int want_hist)
 {
     __shared__ unsigned lh[kBins];
-    for (int b = threadIdx.x; b < kBins; b += kBlock) lh[b] = 0;
+    if (want_hist)
+        for (int b = threadIdx.x; b < kBins; b += kBlock) lh[b] = 0;
     __syncthreads();
-    const int64_t n = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-    const bool valid = n < N;
-    unsigned key = 0;
-    if (valid) {
-        float s = score_group(T + n * g, W + n * g, g);
-        scores[n] = s;
-        key = __float_as_uint(s);
+    for (int64_t base = (int64_t)blockIdx.x * kBlock; base < N; base += (int64_t)gridDim.x * kBlock) {
+        const int64_t n = base + threadIdx.x;
+        const bool valid = n < N;
+        unsigned key = 0;
+        if (valid) {
+            float s = score_group(T + n * g, W + n * g, g);
+            scores[n] = s;
+            key = __float_as_uint(s);
+        }
+        if (want_hist) hist_add<1>(lh, digit_of(key, 0), valid);
     }
-    hist_add(lh, digit_of(key, 0), valid);
     __syncthreads();
-    for (int b = threadIdx.x; b < kBins; b += kBlock) {
-        unsigned v = lh[b];
-        if (v) atomicAdd(&hist0[b], v);
+    if (want_hist) flush_hist(lh, hist0, kBins);
+}
+
+// Pass 0 for g = 4 * PARTS (PARTS a power of two): every lane loads one 16-byte
+// vector of T and of W, so a wave reads two contiguous 1 KiB runs per step.
+// The fused-multiply-add chain of a group runs over PARTS neighbouring lanes in
+// index order: each lane folds its four differences onto the partial sum of
+// the lane before it; the last lane of the group holds the score.
+constexpr int kVecUnroll = 4;
+
+template <int PARTS>
+__global__ __launch_bounds__(kBlock) void k_scores_hist0_vec(const float *__restrict__ T,
+                                                             const float *__restrict__ W,
+                                                             float *__restrict__ scores,
+                                                             unsigned *__restrict__ hist0,
+                                                             int64_t nvec, int want_hist)
+{
+    __shared__ unsigned lh[kBins];
+    if (want_hist)
+        for (int b = threadIdx.x; b < kBins; b += kBlock) lh[b] = 0;
+    __syncthreads();
+    const pv_f4 *T4 = reinterpret_cast<const pv_f4 *>(T);
+    const pv_f4 *W4 = reinterpret_cast<const pv_f4 *>(W);
+    const int part = threadIdx.x & (PARTS - 1);   // kBlock and every stride are multiples of PARTS
+    for (int64_t cbase = (int64_t)blockIdx.x * (kBlock * kVecUnroll); cbase < nvec;
+         cbase += (int64_t)gridDim.x * (kBlock * kVecUnroll)) {
+        const int64_t base = cbase + threadIdx.x;
+        pv_f4 a[kVecUnroll], b[kVecUnroll];
+#pragma unroll
+        for (int u = 0; u < kVecUnroll; ++u) {
+            const int64_t i = base + (int64_t)u * kBlock;
+            if (i < nvec) {
+                a[u] = __builtin_nontemporal_load(&T4[i]);
+                b[u] = __builtin_nontemporal_load(&W4[i]);
+            } else {
+                a[u] = pv_f4{0.f, 0.f, 0.f, 0.f};
+                b[u] = a[u];
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kVecUnroll; ++u) {
+            const int64_t i = base + (int64_t)u * kBlock;
+            const float d0 = a[u].x - b[u].x, d1 = a[u].y - b[u].y;
+            const float d2 = a[u].z - b[u].z, d3 = a[u].w - b[u].w;
+            float s = 0.0f;
+#pragma unroll
+            for (int r = 0; r < PARTS; ++r) {
+                // after round r the lanes with part <= r hold their final prefix
+                float in = r == 0 ? 0.0f : __shfl_up(s, 1);
+                if (part >= r) {
+                    float c = part == 0 ? 0.0f : in;
+                    c = fmaf(d0, d0, c);
+                    c = fmaf(d1, d1, c);
+                    c = fmaf(d2, d2, c);
+                    c = fmaf(d3, d3, c);
+                    if (part == r) s = c;
+                }
+            }
+            const bool valid = i < nvec && part == PARTS - 1;
+            if (valid) scores[i / PARTS] = s;
+            if (want_hist) hist_add<1>(lh, digit_of(__float_as_uint(s), 0), valid);
+        }
     }
+    __syncthreads();
+    if (want_hist) flush_hist(lh, hist0, kBins);
 }
 
 // Passes 1 and 2: histogram of the next digit among keys that match the digits
-// chosen so far.
+// chosen so far.  Each launch resolves the digit of the previous histogram and
+// block 0 publishes it in `state` for the launches that follow:
+// state[4] = digit 0, state[5] = digit 1, state[6] = rank left after digit 0,
+// state[7] = rank left after digit 1.
 __global__ __launch_bounds__(kBlock) void k_hist_next(const float *__restrict__ scores,
                                                       const unsigned *__restrict__ hist_all,
-                                                      unsigned *__restrict__ hist_out, int N,
+                                                      unsigned *__restrict__ hist_out,
+                                                      unsigned *__restrict__ state, int N,
                                                       unsigned k, int pass)
 {
-    __shared__ unsigned lh[kBins];
     __shared__ unsigned tmp[kBlock + 2];
-    for (int b = threadIdx.x; b < kBins; b += kBlock) lh[b] = 0;
+    const int bins = pass == 1 ? kBins : kLastBins;
     int d0, d1 = 0;
     unsigned kk;
-    pick_digit(hist_all, kBins, k, tmp, &d0, &kk);
-    if (pass == 2) pick_digit(hist_all + kBins, kBins, kk, tmp, &d1, &kk);
-    __syncthreads();
-    const int64_t base = (int64_t)blockIdx.x * kChunk;
-#pragma unroll
-    for (int j = 0; j < kItems; ++j) {
-        int64_t n = base + j * kBlock + threadIdx.x;
-        bool valid = n < N;
-        unsigned key = valid ? __float_as_uint(scores[n]) : 0u;
-        valid = valid && digit_of(key, 0) == d0 && (pass == 1 || digit_of(key, 1) == d1);
-        hist_add(lh, digit_of(key, pass), valid);
+    if (pass == 1) {
+        pick_digit(hist_all, kBins, k, tmp, &d0, &kk);
+        if (blockIdx.x == 0 && threadIdx.x == 0) {
+            state[4] = (unsigned)d0;
+            state[6] = kk;
+        }
+    } else {
+        d0 = (int)state[4];
+        pick_digit(hist_all + kBins, kBins, state[6], tmp, &d1, &kk);
+        if (blockIdx.x == 0 && threadIdx.x == 0) {
+            state[5] = (unsigned)d1;
+            state[7] = kk;
+        }
     }
-    __syncthreads();
-    for (int b = threadIdx.x; b < kBins; b += kBlock) {
-        unsigned v = lh[b];
-        if (v) atomicAdd(&hist_out[b], v);
+    const pv_f4 *s4 = reinterpret_cast<const pv_f4 *>(scores);
+    const int64_t n4 = N >> 2;
+    const int64_t stride = (int64_t)gridDim.x * kBlock;
+    // whole blocks stay in the loop together (the histogram update uses wave-wide votes)
+    for (int64_t base = (int64_t)blockIdx.x * kBlock; base < n4; base += stride) {
+        const int64_t i = base + threadIdx.x;
+        pv_f4 v = i < n4 ? s4[i] : pv_f4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            unsigned key = __float_as_uint(v[e]);
+            bool valid = i < n4 && digit_of(key, 0) == d0 && (pass == 1 || digit_of(key, 1) == d1);
+            if (__ballot(valid)) global_hist_add(hist_out, digit_of(key, pass), bins, valid);
+        }
+    }
+    if (blockIdx.x == 0 && (int)threadIdx.x < (N & 3)) {
+        unsigned key = __float_as_uint(scores[(n4 << 2) + threadIdx.x]);
+        if (digit_of(key, 0) == d0 && (pass == 1 || digit_of(key, 1) == d1))
+            atomicAdd(&hist_out[hist_slot(digit_of(key, pass), bins)], 1u);
     }
 }
 
@@ -197,40 +322,52 @@ __device__ __forceinline__ unsigned block_sum(unsigned v, unsigned *tmp)
     return total;
 }
 
-// Threshold key and number of ties to take, then per-block (greater, equal) counts.
-__global__ __launch_bounds__(kBlock) void k_block_counts(const float *__restrict__ scores,
+// Threshold key and number of ties to take, then per-chunk (greater, equal) counts.
+__global__ __launch_bounds__(kBlock) void k_chunk_counts(const float *__restrict__ scores,
                                                          const unsigned *__restrict__ hist_all,
-                                                         unsigned *__restrict__ state,
-                                                         unsigned *__restrict__ block_counts, int N,
-                                                         unsigned k)
+                                                         unsigned *state,
+                                                         unsigned *__restrict__ chunk_counts, int N,
+                                                         int nchunks)
 {
     __shared__ unsigned tmp[kBlock + 2];
-    int d0, d1, d2;
+    const int d0 = (int)state[4], d1 = (int)state[5];
+    int d2;
     unsigned kk;
-    pick_digit(hist_all, kBins, k, tmp, &d0, &kk);
-    pick_digit(hist_all + kBins, kBins, kk, tmp, &d1, &kk);
-    pick_digit(hist_all + 2 * kBins, 1024, kk, tmp, &d2, &kk);
-    const unsigned thr = ((unsigned)d0 << 21) | ((unsigned)d1 << 10) | (unsigned)d2;
+    pick_digit(hist_all + 2 * kBins, kLastBins, state[7], tmp, &d2, &kk);
+    const unsigned thr = ((unsigned)d0 << 19) | ((unsigned)d1 << 6) | (unsigned)d2;
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         state[0] = thr;
         state[1] = kk;  // how many keys equal to thr are selected (lowest ids first)
     }
-    const int64_t base = (int64_t)blockIdx.x * kChunk + (int64_t)threadIdx.x * kItems;
-    unsigned gt = 0, eq = 0;
+    for (int c = blockIdx.x; c < nchunks; c += gridDim.x) {
+        const int64_t base = (int64_t)c * kChunk + (int64_t)threadIdx.x * kItems;
+        unsigned gt = 0, eq = 0;
+        if (base + kItems <= N) {
+            const pv_f4 *s4 = reinterpret_cast<const pv_f4 *>(scores + base);
 #pragma unroll
-    for (int j = 0; j < kItems; ++j) {
-        int64_t n = base + j;
-        if (n < N) {
-            unsigned key = __float_as_uint(scores[n]);
-            gt += key > thr;
-            eq += key == thr;
+            for (int v = 0; v < kItems / 4; ++v) {
+                pv_f4 x = s4[v];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    unsigned key = __float_as_uint(x[e]);
+                    gt += key > thr;
+                    eq += key == thr;
+                }
+            }
+        } else {
+            for (int j = 0; j < kItems; ++j)
+                if (base + j < N) {
+                    unsigned key = __float_as_uint(scores[base + j]);
+                    gt += key > thr;
+                    eq += key == thr;
+                }
         }
-    }
-    gt = block_sum(gt, tmp);
-    eq = block_sum(eq, tmp);
-    if (threadIdx.x == 0) {
-        block_counts[2 * blockIdx.x] = gt;
-        block_counts[2 * blockIdx.x + 1] = eq;
+        gt = block_sum(gt, tmp);
+        eq = block_sum(eq, tmp);
+        if (threadIdx.x == 0) {
+            chunk_counts[2 * c] = gt;
+            chunk_counts[2 * c + 1] = eq;
+        }
     }
 }
 
@@ -239,62 +376,55 @@ __global__ __launch_bounds__(kBlock) void k_block_counts(const float *__restrict
 // the next call.
 __global__ __launch_bounds__(kBlock) void k_compact_write(const float *__restrict__ scores,
                                                           const unsigned *__restrict__ state,
-                                                          const unsigned *__restrict__ block_counts,
+                                                          const unsigned *__restrict__ chunk_counts,
                                                           unsigned *__restrict__ hist_all,
-                                                          int32_t *__restrict__ out_idx, int N)
+                                                          int32_t *__restrict__ out_idx, int N,
+                                                          int nchunks)
 {
     __shared__ unsigned tmp[kBlock + 2];
     const unsigned thr = state[0], need_eq = state[1];
-    // counts of all earlier blocks
-    unsigned pg = 0, pe = 0;
-    for (int b = threadIdx.x; b < (int)blockIdx.x; b += kBlock) {
-        pg += block_counts[2 * b];
-        pe += block_counts[2 * b + 1];
-    }
-    pg = block_sum(pg, tmp);
-    pe = block_sum(pe, tmp);
-    const int64_t base = (int64_t)blockIdx.x * kChunk + (int64_t)threadIdx.x * kItems;
-    unsigned keys[kItems];
-    unsigned gt = 0, eq = 0;
-#pragma unroll
-    for (int j = 0; j < kItems; ++j) {
-        int64_t n = base + j;
-        keys[j] = n < N ? __float_as_uint(scores[n]) : 0u;
-        if (n < N) {
-            gt += keys[j] > thr;
-            eq += keys[j] == thr;
+    for (int c = blockIdx.x; c < nchunks; c += gridDim.x) {
+        // counts of all earlier chunks
+        unsigned pg = 0, pe = 0;
+        for (int b = threadIdx.x; b < c; b += kBlock) {
+            pg += chunk_counts[2 * b];
+            pe += chunk_counts[2 * b + 1];
         }
-    }
-    unsigned tot;
-    unsigned rg = pg + block_excl_scan(gt, tmp, &tot);  // greater keys before this thread's items
-    unsigned re = pe + block_excl_scan(eq, tmp, &tot);  // equal keys before them
+        pg = block_sum(pg, tmp);
+        pe = block_sum(pe, tmp);
+        const int64_t base = (int64_t)c * kChunk + (int64_t)threadIdx.x * kItems;
+        unsigned keys[kItems];
+        unsigned gt = 0, eq = 0;
 #pragma unroll
-    for (int j = 0; j < kItems; ++j) {
-        int64_t n = base + j;
-        if (n < N) {
-            if (keys[j] > thr) {
-                out_idx[rg + (re < need_eq ? re : need_eq)] = (int32_t)n;
-                ++rg;
-            } else if (keys[j] == thr) {
-                if (re < need_eq) out_idx[rg + re] = (int32_t)n;
-                ++re;
+        for (int j = 0; j < kItems; ++j) {
+            int64_t n = base + j;
+            keys[j] = n < N ? __float_as_uint(scores[n]) : 0u;
+            if (n < N) {
+                gt += keys[j] > thr;
+                eq += keys[j] == thr;
+            }
+        }
+        unsigned tot;
+        unsigned rg = pg + block_excl_scan(gt, tmp, &tot);  // greater keys before this thread's items
+        unsigned re = pe + block_excl_scan(eq, tmp, &tot);  // equal keys before them
+#pragma unroll
+        for (int j = 0; j < kItems; ++j) {
+            int64_t n = base + j;
+            if (n < N) {
+                if (keys[j] > thr) {
+                    out_idx[rg + (re < need_eq ? re : need_eq)] = (int32_t)n;
+                    ++rg;
+                } else if (keys[j] == thr) {
+                    if (re < need_eq) out_idx[rg + re] = (int32_t)n;
+                    ++re;
+                }
             }
         }
     }
     // leave the histograms zero for the next call (all their readers ran in earlier launches)
-    const int64_t z = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-    if (z < 3 * kBins) hist_all[z] = 0;
-    if (gridDim.x * kBlock < 3 * kBins && blockIdx.x == 0)
-        for (int i = gridDim.x * kBlock + threadIdx.x; i < 3 * kBins; i += kBlock) hist_all[i] = 0;
-}
-
-// scores only (k == 0 with a score output requested)
-__global__ __launch_bounds__(kBlock) void k_scores_only(const float *__restrict__ T,
-                                                        const float *__restrict__ W,
-                                                        float *__restrict__ scores, int N, int g)
-{
-    const int64_t n = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-    if (n < N) scores[n] = score_group(T + n * g, W + n * g, g);
+    for (int64_t z = (int64_t)blockIdx.x * kBlock + threadIdx.x; z < 3 * kBins;
+         z += (int64_t)gridDim.x * kBlock)
+        hist_all[z] = 0;
 }
 
 }  // namespace
@@ -306,43 +436,54 @@ pv_status pv_launch_select(pv_ctx *ctx, const pv_layout *l, const float *T, cons
     const int g = l->group_size;
     pv_status st;
     if (!scores) {
-        st = pv_ensure(ctx, ctx->sel_scores, (size_t)N * sizeof(float));
+        st = pv_ensure(ctx, ctx->sel_scores, (size_t)N * sizeof(float) + 16);
         if (st != PV_OK) return st;
         scores = static_cast<float *>(ctx->sel_scores.ptr);
     }
-    const unsigned blocks1 = (unsigned)((N + kBlock - 1) / kBlock);
-    const unsigned blocksC = (unsigned)((N + kChunk - 1) / kChunk);
-    if (k == 0) {
-        pv_timed t(ctx, PV_K_GROUP_SCORES);
-        hipLaunchKernelGGL(k_scores_only, dim3(blocks1), dim3(kBlock), 0, ctx->stream, T, W, scores,
-                           N, g);
-        PV_HIP(ctx, hipGetLastError());
-        return PV_OK;
-    }
+    const int nchunks = (N + kChunk - 1) / kChunk;
     st = pv_ensure(ctx, ctx->sel_hist, 3 * kBins * sizeof(unsigned), /*zero_new=*/true);
     if (st != PV_OK) return st;
-    st = pv_ensure(ctx, ctx->sel_blocks, (size_t)blocksC * 2 * sizeof(unsigned));
+    st = pv_ensure(ctx, ctx->sel_blocks, (size_t)nchunks * 2 * sizeof(unsigned));
     if (st != PV_OK) return st;
-    st = pv_ensure(ctx, ctx->sel_state, 4 * sizeof(unsigned));
+    st = pv_ensure(ctx, ctx->sel_state, 8 * sizeof(unsigned));
     if (st != PV_OK) return st;
     unsigned *hist = static_cast<unsigned *>(ctx->sel_hist.ptr);
-    unsigned *bc = static_cast<unsigned *>(ctx->sel_blocks.ptr);
+    unsigned *cc = static_cast<unsigned *>(ctx->sel_blocks.ptr);
     unsigned *state = static_cast<unsigned *>(ctx->sel_state.ptr);
+    const int want_hist = k > 0 ? 1 : 0;
     {
         pv_timed t(ctx, PV_K_GROUP_SCORES);
-        hipLaunchKernelGGL(k_scores_hist0, dim3(blocks1), dim3(kBlock), 0, ctx->stream, T, W, scores,
-                           hist, N, g);
+        const int64_t nvec = (int64_t)N * (g / 4);
+        int64_t vb = (nvec + kBlock * kVecUnroll - 1) / (kBlock * kVecUnroll);
+        const unsigned vblocks = (unsigned)(vb < kMaxBlocks ? vb : kMaxBlocks);
+        int64_t sb = ((int64_t)N + kBlock - 1) / kBlock;
+        const unsigned sblocks = (unsigned)(sb < kMaxBlocks ? sb : kMaxBlocks);
+#define PV_SCORES(PARTS_)                                                                          \
+    hipLaunchKernelGGL(k_scores_hist0_vec<PARTS_>, dim3(vblocks), dim3(kBlock), 0, ctx->stream, T, \
+                       W, scores, hist, nvec, want_hist)
+        if (g == 4) PV_SCORES(1);
+        else if (g == 8) PV_SCORES(2);
+        else if (g == 16) PV_SCORES(4);
+        else if (g == 32) PV_SCORES(8);
+        else if (g == 64) PV_SCORES(16);
+        else
+            hipLaunchKernelGGL(k_scores_hist0, dim3(sblocks), dim3(kBlock), 0, ctx->stream, T, W,
+                               scores, hist, N, g, want_hist);
+#undef PV_SCORES
     }
-    {
+    if (k > 0) {
         pv_timed t(ctx, PV_K_SELECT);
-        hipLaunchKernelGGL(k_hist_next, dim3(blocksC), dim3(kBlock), 0, ctx->stream, scores, hist,
-                           hist + kBins, N, (unsigned)k, 1);
-        hipLaunchKernelGGL(k_hist_next, dim3(blocksC), dim3(kBlock), 0, ctx->stream, scores, hist,
-                           hist + 2 * kBins, N, (unsigned)k, 2);
-        hipLaunchKernelGGL(k_block_counts, dim3(blocksC), dim3(kBlock), 0, ctx->stream, scores, hist,
-                           state, bc, N, (unsigned)k);
-        hipLaunchKernelGGL(k_compact_write, dim3(blocksC), dim3(kBlock), 0, ctx->stream, scores,
-                           state, bc, hist, out_idx, N);
+        int64_t hb = ((int64_t)(N >> 2) + kBlock - 1) / kBlock;
+        const unsigned hblocks = (unsigned)(hb < 512 ? (hb < 1 ? 1 : hb) : 512);
+        const unsigned cblocks = (unsigned)(nchunks < kMaxBlocks ? nchunks : kMaxBlocks);
+        hipLaunchKernelGGL(k_hist_next, dim3(hblocks), dim3(kBlock), 0, ctx->stream, scores, hist,
+                           hist + kBins, state, N, (unsigned)k, 1);
+        hipLaunchKernelGGL(k_hist_next, dim3(hblocks), dim3(kBlock), 0, ctx->stream, scores, hist,
+                           hist + 2 * kBins, state, N, (unsigned)k, 2);
+        hipLaunchKernelGGL(k_chunk_counts, dim3(cblocks), dim3(kBlock), 0, ctx->stream, scores, hist,
+                           state, cc, N, nchunks);
+        hipLaunchKernelGGL(k_compact_write, dim3(cblocks), dim3(kBlock), 0, ctx->stream, scores,
+                           state, cc, hist, out_idx, N, nchunks);
     }
     PV_HIP(ctx, hipGetLastError());
     return PV_OK;
