@@ -32,7 +32,23 @@
 // lies below Vcut the group cannot be certified and goes to the exact scan.
 // Hence the chosen code is the double-precision argmin with the tie rule of
 // the definition, whatever the fp16 rounding did.
+#include <type_traits>
+
 #include "pv_internal.h"
+
+// Launch shape of the contraction kernel (tunable at build time).
+#ifndef PV_STAGE
+#define PV_STAGE 32   // KiB of operand A per LDS stage
+#endif
+#ifndef PV_NBX
+#define PV_NBX 2      // group tiles (32 groups) per wave
+#endif
+#ifndef PV_WAVES
+#define PV_WAVES 8    // waves per block
+#endif
+#ifndef PV_OCC
+#define PV_OCC 2      // blocks per compute unit the register / LDS budget allows
+#endif
 
 namespace {
 
@@ -40,7 +56,7 @@ typedef _Float16 h8 __attribute__((ext_vector_type(8)));
 typedef float f16v __attribute__((ext_vector_type(16)));
 
 constexpr int kBlock = 256;
-constexpr int kStageTiles = 8;       // codeword tiles (of 32) per LDS stage
+constexpr int kStageTiles = PV_STAGE;      // KiB of operand A per LDS stage
 constexpr int kResidues = 4;         // tile residue classes tracked separately per lane
 constexpr unsigned kTileMask = 0x7FFu;
 constexpr float kHalfMinNormal = 6.103515625e-05f;  // 2^-14
@@ -279,19 +295,26 @@ __device__ __forceinline__ unsigned acc_min(const f16v &acc)
 // The distance contraction.  Block = 4 waves; wave w owns NB group tiles (32
 // groups each) whose B operands stay in registers; the block streams the
 // codeword tiles [t_begin, t_end) of its split through a double-buffered LDS
-// stage shared by the 4 waves.  Output: for every group and partition the
-// smallest and second smallest key.
+// stage shared by the 4 waves.  A stage is filled with direct global->LDS
+// loads (no staging registers) one stage ahead of its use.  Inside a stage the
+// loop is software pipelined: the MFMAs of tile t are issued, then the
+// accumulators of tile t-1 are reduced on the vector ALU while the matrix core
+// works.  Output: for every group and partition the smallest and second
+// smallest key.
 template <int NK, int NB>
-__global__ __launch_bounds__(kBlock, 2) void k_score_mfma(const h8 *__restrict__ A,
+__global__ __launch_bounds__(PV_WAVES * 64, (PV_OCC * PV_WAVES) / 4) void k_score_mfma(const h8 *__restrict__ A,
                                                           const h8 *__restrict__ X,
                                                           uint2 *__restrict__ partials, int ntiles,
                                                           int nsplit, int P, int merge)
 {
-    constexpr int kStageChunks = kStageTiles * NK * 64;            // 16-byte chunks per stage
-    constexpr int kLoads = kStageChunks / kBlock;                  // per thread per stage
-    __shared__ h8 lds[2][kStageChunks];
+    constexpr int S = kStageTiles / NK;                            // tiles per stage
+    constexpr int kStageChunks = S * NK * 64;                      // 16-byte chunks per stage
+    constexpr int kW = PV_WAVES;                                   // waves per block
+    constexpr int kRounds = (kStageChunks / 64 + kW - 1) / kW;     // 64-chunk rows per wave
+    static_assert(S % kResidues == 0, "stage must hold whole residue cycles");
+    __shared__ h8 lds[2 * kStageChunks + NK * 64];   // two stages + one tile of padding
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int gtile0 = (blockIdx.x * (kBlock / 64) + wave) * NB;
+    const int gtile0 = (blockIdx.x * kW + wave) * NB;
     const int split = blockIdx.y;
     const int t_begin = (int)((int64_t)split * ntiles / nsplit);
     const int t_end = (int)((int64_t)(split + 1) * ntiles / nsplit);
@@ -308,54 +331,84 @@ __global__ __launch_bounds__(kBlock, 2) void k_score_mfma(const h8 *__restrict__
 #pragma unroll
         for (int r = 0; r < kResidues; ++r) best[nb][r] = second[nb][r] = 0xFFFFFFFFu;
 
-    const h8 zero8 = {0, 0, 0, 0, 0, 0, 0, 0};
     unsigned vmask = ~kTileMask;
     asm volatile("" : "+v"(vmask));   // keep the mask in a vector register
-    h8 pre[kLoads];
-    auto fetch = [&](int t0) {
-        const int valid = (t_end - t0 < kStageTiles ? t_end - t0 : kStageTiles) * NK * 64;
+
+    // rows of 64 chunks (1 KiB) are copied by one wave each: lane i -> chunk row + i
+    auto fetch = [&](int t0, int buf) {
+        const int valid = (t_end - t0 < S ? t_end - t0 : S) * NK * 64;
         const h8 *src = A + (int64_t)t0 * NK * 64;
 #pragma unroll
-        for (int u = 0; u < kLoads; ++u) {
-            int i = u * kBlock + threadIdx.x;
-            pre[u] = i < valid ? src[i] : zero8;
+        for (int u = 0; u < kRounds; ++u) {
+            const int row = (u * kW + wave) * 64;   // uniform over the wave
+            if (row < valid && row < kStageChunks)
+                __builtin_amdgcn_global_load_lds(
+                    (const void *)(src + row + lane),
+                    (__attribute__((address_space(3))) void *)(&lds[buf * kStageChunks + row]), 16, 0, 0);
         }
-    };
-    auto stash = [&](int buf) {
-#pragma unroll
-        for (int u = 0; u < kLoads; ++u) lds[buf][u * kBlock + threadIdx.x] = pre[u];
     };
 
-    if (t_begin < t_end) {
-        fetch(t_begin);
-        stash(0);
-    }
-    __syncthreads();
-    int buf = 0;
-    for (int t0 = t_begin; t0 < t_end; t0 += kStageTiles) {
-        const bool more = t0 + kStageTiles < t_end;
-        if (more) fetch(t0 + kStageTiles);
+    // While the matrix core works on unit (tile, nb) the vector ALU reduces the unit before
+    // it.  One accumulator set per nb (two by tile parity when NB == 1), so a set is rewritten
+    // a whole tile after it was last read.
+    constexpr int kSets = NB >= 2 ? NB : 2;
+    f16v acc[kSets];
+    h8 a_cur[NK], a_nxt[NK];
+    auto load_a = [&](int buf, int ts, h8 *a) {
 #pragma unroll
-        for (int ts = 0; ts < kStageTiles; ++ts) {
-            if (t0 + ts < t_end) {   // uniform
-                h8 a[NK];
+        for (int j = 0; j < NK; ++j) a[j] = lds[buf * kStageChunks + (ts * NK + j) * 64 + lane];
+    };
+    auto issue = [&](int nb, int set) {
+        f16v c = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 #pragma unroll
-                for (int j = 0; j < NK; ++j) a[j] = lds[buf][(ts * NK + j) * 64 + lane];
-                const unsigned tile = (unsigned)(t0 + ts);
+        for (int j = 0; j < NK; ++j)
+            c = __builtin_amdgcn_mfma_f32_32x32x16_f16(a_cur[j], b[nb][j], c, 0, 0, 0);
+        acc[set] = c;
+    };
+    auto reduce = [&](unsigned tile, int nb, int set, int r) {
+        const unsigned key = and_or(acc_min(acc[set]), vmask, tile);
+        second[nb][r] = umed3(best[nb][r], second[nb][r], key);
+        best[nb][r] = min(best[nb][r], key);
+    };
+    // One stage of `cnt` tiles (FULL: cnt == S, no per-tile guards).
+    auto run_stage = [&](int buf, int t0, int cnt, auto full_tag) {
+        constexpr bool FULL = decltype(full_tag)::value;
+        load_a(buf, 0, a_cur);
+#pragma unroll 1
+        for (int q4 = 0; q4 < S; q4 += kResidues) {
+#pragma unroll
+            for (int u = 0; u < kResidues; ++u) {
+                const int ts = q4 + u;
+                if (FULL || ts + 1 < cnt) load_a(buf, ts + 1, a_nxt);   // one spare tile pads the LDS array
 #pragma unroll
                 for (int nb = 0; nb < NB; ++nb) {
-                    f16v acc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll
-                    for (int j = 0; j < NK; ++j)
-                        acc = __builtin_amdgcn_mfma_f32_32x32x16_f16(a[j], b[nb][j], acc, 0, 0, 0);
-                    const unsigned key = and_or(acc_min(acc), vmask, tile);
-                    second[nb][ts % kResidues] =
-                        umed3(best[nb][ts % kResidues], second[nb][ts % kResidues], key);
-                    best[nb][ts % kResidues] = min(best[nb][ts % kResidues], key);
+                    const int set = NB >= 2 ? nb : (u & 1);
+                    const int prev_set = NB >= 2 ? (nb + NB - 1) % NB : ((u + 1) & 1);
+                    if (FULL || ts < cnt) issue(nb, set);
+                    if (nb > 0) {
+                        if (FULL || ts < cnt) reduce((unsigned)(t0 + ts), nb - 1, prev_set, u);
+                    } else if (ts >= 1 && (FULL || ts - 1 < cnt)) {
+                        reduce((unsigned)(t0 + ts - 1), NB - 1, prev_set, (u + kResidues - 1) % kResidues);
+                    }
                 }
+#pragma unroll
+                for (int j = 0; j < NK; ++j) a_cur[j] = a_nxt[j];
             }
         }
-        if (more) stash(buf ^ 1);
+        if (FULL || cnt == S)
+            reduce((unsigned)(t0 + S - 1), NB - 1, NB >= 2 ? NB - 1 : ((kResidues - 1) & 1), kResidues - 1);
+    };
+
+    if (t_begin < t_end) fetch(t_begin, 0);
+    __builtin_amdgcn_s_waitcnt(0);
+    __syncthreads();
+    int buf = 0;
+    for (int t0 = t_begin; t0 < t_end; t0 += S) {
+        if (t0 + S < t_end) fetch(t0 + S, buf ^ 1);
+        const int cnt = t_end - t0 < S ? t_end - t0 : S;      // uniform
+        if (cnt == S) run_stage(buf, t0, cnt, std::true_type{});
+        else run_stage(buf, t0, cnt, std::false_type{});
+        __builtin_amdgcn_s_waitcnt(0);
         __syncthreads();
         buf ^= 1;
     }
@@ -576,13 +629,14 @@ plan_t make_plan(const pv_layout *l, int64_t k)
     plan_t p;
     p.NK = l->group_size / 8;
     p.ntiles = (1 << l->nbits) / 32;
-    p.NB = k >= 8192 ? 4 : (k >= 2048 ? 2 : 1);
-    const int per_block = (kBlock / 64) * p.NB * 32;
+    p.NB = k >= 4096 ? PV_NBX : 1;
+    const int per_block = PV_WAVES * p.NB * 32;
     p.gblocks = (int)((k + per_block - 1) / per_block);
     p.k_pad = p.gblocks * per_block;
-    // about two blocks per compute unit in flight; a split needs at least one stage of tiles
-    int want = (512 + p.gblocks - 1) / p.gblocks;
-    int max_split = p.ntiles / kStageTiles;
+    // two blocks per compute unit fit (registers, LDS): fill those 512 slots in ONE round,
+    // never spill a few blocks into a second one
+    int want = (256 * PV_OCC) / p.gblocks;
+    int max_split = p.ntiles / 8;
     if (max_split < 1) max_split = 1;
     if (want > max_split) want = max_split;
     if (want > 32) want = 32;
@@ -657,15 +711,13 @@ pv_status pv_launch_mfma_search(pv_ctx *ctx, const pv_layout *l, const float *T,
         pv_timed t(ctx, PV_K_SCORE_MFMA);
         dim3 grid(p.gblocks, p.nsplit);
 #define PV_SCORE(NK_, NB_)                                                                     \
-    hipLaunchKernelGGL((k_score_mfma<NK_, NB_>), grid, dim3(kBlock), 0, sm, A, X, partials,    \
+    hipLaunchKernelGGL((k_score_mfma<NK_, NB_>), grid, dim3(PV_WAVES * 64), 0, sm, A, X, partials,    \
                        p.ntiles, p.nsplit, p.P, p.merge)
         if (p.NK == 1) {
-            if (p.NB == 4) PV_SCORE(1, 4);
-            else if (p.NB == 2) PV_SCORE(1, 2);
+            if (p.NB == PV_NBX) PV_SCORE(1, PV_NBX);
             else PV_SCORE(1, 1);
         } else {
-            if (p.NB == 4) PV_SCORE(2, 4);
-            else if (p.NB == 2) PV_SCORE(2, 2);
+            if (p.NB == PV_NBX) PV_SCORE(2, PV_NBX);
             else PV_SCORE(2, 1);
         }
 #undef PV_SCORE
