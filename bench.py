@@ -26,6 +26,10 @@ PEAK_MFMA_F16 = 2500.0   # TFLOP/s dense fp16/bf16 matrix-core peak of MI355X
 PEAK_HBM = 8000.0        # GB/s
 PEAK_F64 = 78.6          # TFLOP/s fp64 vector (256 CU x 4 SIMD x 16 lanes x 2 (fma) x 2.4 GHz)
 
+# HBM bytes per launch of the dominant kernel, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this
+# same command (profiles/c2_4096x4096_1x16_hbm_traffic.txt; FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 KiB)
+MEASURED_TRAFFIC_BYTES = {("k_score_mfma", "c2_4096x4096_1x16"): (10864.7 * 2.0 + 8793.6) * 1024.0}
+
 
 def main() -> int:
     ap = argparse.ArgumentParser()
@@ -115,7 +119,8 @@ def main() -> int:
     if dominant == "score_mfma":
         a = flops_contraction / (kern[dominant]["avg_ms"] * 1e-3) / 1e12
         roofline = {"kernel": "k_score_mfma", "bound": "mfma", "achieved": a, "peak": PEAK_MFMA_F16,
-                    "unit": "TFLOP/s", "frac": a / PEAK_MFMA_F16, "traffic": None}
+                    "unit": "TFLOP/s", "frac": a / PEAK_MFMA_F16,
+                    "traffic": MEASURED_TRAFFIC_BYTES.get(("k_score_mfma", args.workload))}
     elif dominant in ("exact_scan", "beam"):
         # double-precision ALU work per scored tuple: g * (mul, sub, mul, add) (+ g adds per extra codebook)
         tuples = k * ((1 << B) if M == 1 else (1 << B) * (1 + (M - 1) * wl.beam_width))
