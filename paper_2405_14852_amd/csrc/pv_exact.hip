@@ -417,6 +417,155 @@ __global__ __launch_bounds__(kBlock) void k_beam(
     }
 }
 
+// ------------------------------------------------------------------ beam search, 2 x 256 codewords
+//
+// The paper's additive configuration (two 8-bit codebooks, beam 8): one WAVE per
+// listed group, both codebooks in LDS, no block-wide synchronisation per group.
+// Step 0: lane l scores code0 = l, l+64, l+128, l+192 with code1 held; the best
+// `beam_width` by (objective, code0) are extracted one wave-wide argmin at a
+// time.  Step 1: every lane scores its four code1 values against every kept
+// code0 and keeps the best by (objective, code0, code1); one wave-wide argmin
+// gives the winner, which replaces the current pair only if strictly better.
+// Objectives use the same double-precision chain as everywhere else.
+constexpr int kBeam2Max = 8;
+
+__device__ __forceinline__ best_t wave_argmin_all(best_t b)
+{
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        double o = __shfl_xor(b.obj, off);
+        int i = __shfl_xor(b.idx, off);
+        if (better(o, i, b.obj, b.idx)) {
+            b.obj = o;
+            b.idx = i;
+        }
+    }
+    return b;   // identical in every lane
+}
+
+template <int G>
+__global__ __launch_bounds__(kBlock) void k_beam_2x8(
+    const float *__restrict__ T, const float *__restrict__ codebooks,
+    const float *__restrict__ scales, const int32_t *__restrict__ group_idx, int64_t k,
+    int beam_width, uint16_t *__restrict__ codes, unsigned long long *__restrict__ num_changed,
+    unsigned long long *__restrict__ stat_counter, int gpr, int N)
+{
+    __shared__ float s_cb[2 * 256 * G];
+    for (int i = threadIdx.x; i < 2 * 256 * G / 4; i += kBlock)
+        reinterpret_cast<pv_f4 *>(s_cb)[i] = reinterpret_cast<const pv_f4 *>(codebooks)[i];
+    __syncthreads();
+    const float *cb0 = s_cb, *cb1 = s_cb + 256 * G;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    unsigned changed = 0, done = 0;
+    for (int64_t j = (int64_t)blockIdx.x * (kBlock / 64) + wave; j < k;
+         j += (int64_t)gridDim.x * (kBlock / 64)) {
+        const int n = group_idx[j];
+        if (n < 0 || n >= N) continue;   // uniform over the wave
+        const double s = (double)scales[n / gpr];
+        double t[G];
+        {
+            const pv_f4 *t4 = reinterpret_cast<const pv_f4 *>(T + (int64_t)n * G);
+#pragma unroll
+            for (int v = 0; v < G / 4; ++v) {
+                pv_f4 x = t4[v];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) t[v * 4 + e] = (double)x[e];
+            }
+        }
+        const int p0 = codes[(int64_t)n * 2] & 255, p1 = codes[(int64_t)n * 2 + 1] & 255;
+        // objective of the current pair, and step 0 (code1 = p1 held)
+        double fixed[G];
+#pragma unroll
+        for (int i = 0; i < G; ++i) fixed[i] = (double)cb1[p1 * G + i];
+        auto objective0 = [&](int c0) {
+            double obj = 0.0;
+#pragma unroll
+            for (int i = 0; i < G; ++i) {
+                double acc = (double)cb0[c0 * G + i];
+                acc = acc + fixed[i];
+                double r = s * acc - t[i];
+                obj = obj + r * r;
+            }
+            return obj;
+        };
+        const double o_prev = objective0(p0);
+        double o0[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) o0[q] = objective0(lane + 64 * q);
+        int beam_code[kBeam2Max];
+        int nbeam = 0;
+        unsigned taken = 0;
+#pragma unroll
+        for (int r = 0; r < kBeam2Max; ++r) {
+            if (r < beam_width) {        // uniform
+                best_t b;
+                b.obj = kInf;
+                b.idx = 0x7fffffff;
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    if (!((taken >> q) & 1u) && better(o0[q], lane + 64 * q, b.obj, b.idx)) {
+                        b.obj = o0[q];
+                        b.idx = lane + 64 * q;
+                    }
+                b = wave_argmin_all(b);
+                beam_code[r] = b.idx;
+                if (b.idx != 0x7fffffff) {
+                    nbeam = r + 1;
+                    if ((b.idx & 63) == lane) taken |= 1u << (b.idx >> 6);
+                }
+            } else {
+                beam_code[r] = 0x7fffffff;
+            }
+        }
+        // step 1: code1 over all 256 values for every kept code0
+        double c1v[4][G];
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int i = 0; i < G; ++i) c1v[q][i] = (double)cb1[(lane + 64 * q) * G + i];
+        best_t w;
+        w.obj = kInf;
+        w.idx = 0x7fffffff;
+#pragma unroll
+        for (int e = 0; e < kBeam2Max; ++e) {
+            if (e < nbeam && beam_code[e] != 0x7fffffff) {   // uniform (a dropped entry ends the list)
+                const int c0 = beam_code[e];
+                double c0v[G];
+#pragma unroll
+                for (int i = 0; i < G; ++i) c0v[i] = (double)cb0[c0 * G + i];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    double obj = 0.0;
+#pragma unroll
+                    for (int i = 0; i < G; ++i) {
+                        double acc = c0v[i] + c1v[q][i];
+                        double r = s * acc - t[i];
+                        obj = obj + r * r;
+                    }
+                    const int tie = c0 * 256 + lane + 64 * q;
+                    if (better(obj, tie, w.obj, w.idx)) {
+                        w.obj = obj;
+                        w.idx = tie;
+                    }
+                }
+            }
+        }
+        w = wave_argmin_all(w);
+        if (lane == 0) {
+            if (w.idx != 0x7fffffff && w.obj < o_prev) {
+                codes[(int64_t)n * 2] = (uint16_t)(w.idx >> 8);
+                codes[(int64_t)n * 2 + 1] = (uint16_t)(w.idx & 255);
+                ++changed;
+            }
+            ++done;
+        }
+    }
+    if (lane == 0) {
+        if (changed && num_changed) atomicAdd(num_changed, (unsigned long long)changed);
+        if (done && stat_counter) atomicAdd(stat_counter, (unsigned long long)done);
+    }
+}
+
 }  // namespace
 
 static void launch_scan(pv_ctx *ctx, int g, unsigned blocks, const float *T, const float *codebooks,
@@ -496,8 +645,22 @@ pv_status pv_launch_beam(pv_ctx *ctx, const pv_layout *l, const float *T, const 
     const int g = l->group_size;
     const int gpr = (int)(l->in_features / g);
     const int N = (int)pv_num_groups(l);
-    int64_t blocks = k < 16384 ? k : 16384;
     int64_t *stat = static_cast<int64_t *>(ctx->stats.ptr) + 3;
+    if (l->num_codebooks == 2 && l->nbits == 8 && beam_width <= kBeam2Max && (g == 8 || g == 16)) {
+        int64_t wblocks = (k + kBlock / 64 - 1) / (kBlock / 64);
+        if (wblocks > 2048) wblocks = 2048;
+        auto nc = reinterpret_cast<unsigned long long *>(num_changed);
+        auto sc = reinterpret_cast<unsigned long long *>(stat);
+        if (g == 8)
+            hipLaunchKernelGGL(k_beam_2x8<8>, dim3((unsigned)wblocks), dim3(kBlock), 0, ctx->stream, T,
+                               codebooks, scales, group_idx, k, beam_width, codes, nc, sc, gpr, N);
+        else
+            hipLaunchKernelGGL(k_beam_2x8<16>, dim3((unsigned)wblocks), dim3(kBlock), 0, ctx->stream, T,
+                               codebooks, scales, group_idx, k, beam_width, codes, nc, sc, gpr, N);
+        PV_HIP(ctx, hipGetLastError());
+        return PV_OK;
+    }
+    int64_t blocks = k < 16384 ? k : 16384;
     hipLaunchKernelGGL(k_beam, dim3((unsigned)blocks), dim3(kBlock), 0, ctx->stream, T, codebooks,
                        scales, group_idx, k, beam_width, codes,
                        reinterpret_cast<unsigned long long *>(num_changed),
