@@ -3,30 +3,37 @@
 // score_n = sum_i (T[n,i] - W[n,i])^2 as an fp32 fused-multiply-add chain in
 // index order, so that every implementation of this rule gives the same bits.
 // Scores are non-negative floats, so their bit patterns order like unsigned
-// integers.  The k-th largest key is found by a 3-digit radix select (13 + 13 +
-// 6 bits, most significant first); groups above the threshold are taken, groups
+// integers.  The k-th largest key is found by a 3-digit radix select (11 + 13 +
+// 8 bits, most significant first); groups above the threshold are taken, groups
 // equal to it are taken lowest id first, and the ids are written in ascending
 // order through a two-level prefix sum.  Nothing returns to the host.
 //
 // Launches: [scores + digit-0 histogram] [digit-1 histogram] [digit-2 histogram]
-// [per-chunk counts] [ordered write].  Every block re-derives the digits chosen
-// so far from the (small) histograms instead of waiting for a separate kernel.
-// Blocks are persistent (a few per compute unit, grid-stride over the input) so
-// that clearing and flushing the LDS histogram is paid once per block.
+// [per-chunk counts] [ordered write].  Digit 0 (sign, exponent, two mantissa
+// bits) is counted in an LDS histogram inside the streaming score kernel, whose
+// blocks are persistent so that clearing and flushing it is paid once per block;
+// the later digits see only the few per cent of keys that share the chosen
+// digit 0 and go to global memory directly.  Each launch resolves the digit of
+// the histogram before it and publishes it for the launches that follow.
 #include "pv_internal.h"
+
+#ifndef PV_VOTE_ROUNDS
+#define PV_VOTE_ROUNDS 1   // wave-wide merges before per-lane LDS atomics (guards degenerate inputs)
+#endif
 
 namespace {
 
 constexpr int kBlock = 256;
-constexpr int kBins = 8192;                    // 13-bit digits
-constexpr int kLastBins = 64;                  // the last digit has 6 bits
+constexpr int kBins = 8192;                    // digit 1: 13 mantissa bits (also the slot count of every histogram)
+constexpr int kFirstBins = 2048;                // digit 0: sign, exponent, 2 mantissa bits
+constexpr int kLastBins = 256;                  // digit 2: the low 8 mantissa bits
 constexpr int kItems = 8;                      // groups per thread in the compaction kernels
 constexpr int kChunk = kBlock * kItems;        // groups per chunk there
 constexpr int kMaxBlocks = 1024;               // persistent grid: 4 blocks per compute unit
 
 __device__ __forceinline__ int digit_of(unsigned key, int pass)
 {
-    return pass == 0 ? (int)(key >> 19) : pass == 1 ? (int)((key >> 6) & 8191u) : (int)(key & 63u);
+    return pass == 0 ? (int)(key >> 21) : pass == 1 ? (int)((key >> 8) & 8191u) : (int)(key & 255u);
 }
 
 // Add one count per valid lane to an LDS histogram.  Lanes of a wave that hit
@@ -177,9 +184,9 @@ __global__ __launch_bounds__(kBlock) void k_scores_hist0(const float *__restrict
                                                          unsigned *__restrict__ hist0, int N, int g,
                                                          int want_hist)
 {
-    __shared__ unsigned lh[kBins];
+    __shared__ unsigned lh[kFirstBins];
     if (want_hist)
-        for (int b = threadIdx.x; b < kBins; b += kBlock) lh[b] = 0;
+        for (int b = threadIdx.x; b < kFirstBins; b += kBlock) lh[b] = 0;
     __syncthreads();
     for (int64_t base = (int64_t)blockIdx.x * kBlock; base < N; base += (int64_t)gridDim.x * kBlock) {
         const int64_t n = base + threadIdx.x;
@@ -190,10 +197,10 @@ __global__ __launch_bounds__(kBlock) void k_scores_hist0(const float *__restrict
             scores[n] = s;
             key = __float_as_uint(s);
         }
-        if (want_hist) hist_add<1>(lh, digit_of(key, 0), valid);
+        if (want_hist) hist_add<PV_VOTE_ROUNDS>(lh, digit_of(key, 0), valid);
     }
     __syncthreads();
-    if (want_hist) flush_hist(lh, hist0, kBins);
+    if (want_hist) flush_hist(lh, hist0, kFirstBins);
 }
 
 // Pass 0 for g = 4 * PARTS (PARTS a power of two): every lane loads one 16-byte
@@ -210,9 +217,9 @@ __global__ __launch_bounds__(kBlock) void k_scores_hist0_vec(const float *__rest
                                                              unsigned *__restrict__ hist0,
                                                              int64_t nvec, int want_hist)
 {
-    __shared__ unsigned lh[kBins];
+    __shared__ unsigned lh[kFirstBins];
     if (want_hist)
-        for (int b = threadIdx.x; b < kBins; b += kBlock) lh[b] = 0;
+        for (int b = threadIdx.x; b < kFirstBins; b += kBlock) lh[b] = 0;
     __syncthreads();
     const pv_f4 *T4 = reinterpret_cast<const pv_f4 *>(T);
     const pv_f4 *W4 = reinterpret_cast<const pv_f4 *>(W);
@@ -253,11 +260,11 @@ __global__ __launch_bounds__(kBlock) void k_scores_hist0_vec(const float *__rest
             }
             const bool valid = i < nvec && part == PARTS - 1;
             if (valid) scores[i / PARTS] = s;
-            if (want_hist) hist_add<1>(lh, digit_of(__float_as_uint(s), 0), valid);
+            if (want_hist) hist_add<PV_VOTE_ROUNDS>(lh, digit_of(__float_as_uint(s), 0), valid);
         }
     }
     __syncthreads();
-    if (want_hist) flush_hist(lh, hist0, kBins);
+    if (want_hist) flush_hist(lh, hist0, kFirstBins);
 }
 
 // Passes 1 and 2: histogram of the next digit among keys that match the digits
@@ -276,7 +283,7 @@ __global__ __launch_bounds__(kBlock) void k_hist_next(const float *__restrict__ 
     int d0, d1 = 0;
     unsigned kk;
     if (pass == 1) {
-        pick_digit(hist_all, kBins, k, tmp, &d0, &kk);
+        pick_digit(hist_all, kFirstBins, k, tmp, &d0, &kk);
         if (blockIdx.x == 0 && threadIdx.x == 0) {
             state[4] = (unsigned)d0;
             state[6] = kk;
@@ -334,7 +341,7 @@ __global__ __launch_bounds__(kBlock) void k_chunk_counts(const float *__restrict
     int d2;
     unsigned kk;
     pick_digit(hist_all + 2 * kBins, kLastBins, state[7], tmp, &d2, &kk);
-    const unsigned thr = ((unsigned)d0 << 19) | ((unsigned)d1 << 6) | (unsigned)d2;
+    const unsigned thr = ((unsigned)d0 << 21) | ((unsigned)d1 << 8) | (unsigned)d2;
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         state[0] = thr;
         state[1] = kk;  // how many keys equal to thr are selected (lowest ids first)
