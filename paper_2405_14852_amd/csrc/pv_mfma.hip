@@ -305,7 +305,8 @@ template <int NK, int NB>
 __global__ __launch_bounds__(PV_WAVES * 64, (PV_OCC * PV_WAVES) / 4) void k_score_mfma(const h8 *__restrict__ A,
                                                           const h8 *__restrict__ X,
                                                           uint2 *__restrict__ partials, int ntiles,
-                                                          int nsplit, int P, int merge)
+                                                          int nsplit, int P, int merge,
+                                                          int gblocks, unsigned *__restrict__ next_item)
 {
     constexpr int S = kStageTiles / NK;                            // tiles per stage
     constexpr int kStageChunks = S * NK * 64;                      // 16-byte chunks per stage
@@ -313,9 +314,18 @@ __global__ __launch_bounds__(PV_WAVES * 64, (PV_OCC * PV_WAVES) / 4) void k_scor
     constexpr int kRounds = (kStageChunks / 64 + kW - 1) / kW;     // 64-chunk rows per wave
     static_assert(S % kResidues == 0, "stage must hold whole residue cycles");
     __shared__ h8 lds[2 * kStageChunks + NK * 64];   // two stages + one tile of padding
+    __shared__ unsigned s_item;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int gtile0 = (blockIdx.x * kW + wave) * NB;
-    const int split = blockIdx.y;
+    unsigned vmask = ~kTileMask;
+    asm volatile("" : "+v"(vmask));   // keep the mask in a vector register
+    // Work items = (group block, codeword split).  A block starts with item blockIdx.x; when
+    // there are more items than blocks the rest is handed out through a counter, so the
+    // blocks in flight stay busy until the items run out (every block leaves when its next
+    // item number passes the item count).
+    const unsigned items = (unsigned)gblocks * (unsigned)nsplit;
+    for (unsigned item = blockIdx.x; item < items;) {
+    const int gb = (int)(item % (unsigned)gblocks), split = (int)(item / (unsigned)gblocks);
+    const int gtile0 = (gb * kW + wave) * NB;
     const int t_begin = (int)((int64_t)split * ntiles / nsplit);
     const int t_end = (int)((int64_t)(split + 1) * ntiles / nsplit);
 
@@ -330,9 +340,6 @@ __global__ __launch_bounds__(PV_WAVES * 64, (PV_OCC * PV_WAVES) / 4) void k_scor
     for (int nb = 0; nb < NB; ++nb)
 #pragma unroll
         for (int r = 0; r < kResidues; ++r) best[nb][r] = second[nb][r] = 0xFFFFFFFFu;
-
-    unsigned vmask = ~kTileMask;
-    asm volatile("" : "+v"(vmask));   // keep the mask in a vector register
 
     // rows of 64 chunks (1 KiB) are copied by one wave each: lane i -> chunk row + i
     auto fetch = [&](int t0, int buf) {
@@ -434,6 +441,12 @@ __global__ __launch_bounds__(PV_WAVES * 64, (PV_OCC * PV_WAVES) / 4) void k_scor
                 partials[jpos * P + (split * 2 + hw) * kResidues + r] =
                     make_uint2(best[nb][r], second[nb][r]);
         }
+    }
+    if (items <= gridDim.x) break;          // one item per block: nothing to fetch
+    __syncthreads();                        // every wave is done with the LDS stages
+    if (threadIdx.x == 0) s_item = gridDim.x + atomicAdd(next_item, 1u);
+    __syncthreads();
+    item = s_item;                          // uniform over the block
     }
 }
 
@@ -633,9 +646,14 @@ plan_t make_plan(const pv_layout *l, int64_t k)
     const int per_block = PV_WAVES * p.NB * 32;
     p.gblocks = (int)((k + per_block - 1) / per_block);
     p.k_pad = p.gblocks * per_block;
-    // two blocks per compute unit fit (registers, LDS): fill those 512 slots in ONE round,
-    // never spill a few blocks into a second one
-    int want = (256 * PV_OCC) / p.gblocks;
+    // PV_OCC blocks per compute unit fit (registers, LDS).  Few group blocks: cut the
+    // codeword range so that the items fill those slots in ONE round (a 13th split that
+    // spills 21 blocks into a second round costs 25 %).  Many group blocks: several short
+    // items per slot, handed out dynamically, so the tail is one short item.
+    const int slots = 256 * PV_OCC;
+    int want = slots / p.gblocks;
+    if (want < 4) want = (4 * slots + p.gblocks - 1) / p.gblocks;
+    if (want > 8 && slots / p.gblocks < 4) want = 8;
     int max_split = p.ntiles / 8;
     if (max_split < 1) max_split = 1;
     if (want > max_split) want = max_split;
@@ -709,10 +727,11 @@ pv_status pv_launch_mfma_search(pv_ctx *ctx, const pv_layout *l, const float *T,
     }
     {
         pv_timed t(ctx, PV_K_SCORE_MFMA);
-        dim3 grid(p.gblocks, p.nsplit);
+        const int items = p.gblocks * p.nsplit;
+        dim3 grid(items < 256 * PV_OCC ? items : 256 * PV_OCC);
 #define PV_SCORE(NK_, NB_)                                                                     \
     hipLaunchKernelGGL((k_score_mfma<NK_, NB_>), grid, dim3(PV_WAVES * 64), 0, sm, A, X, partials,    \
-                       p.ntiles, p.nsplit, p.P, p.merge)
+                       p.ntiles, p.nsplit, p.P, p.merge, p.gblocks, fb_count + 1)
         if (p.NK == 1) {
             if (p.NB == PV_NBX) PV_SCORE(1, PV_NBX);
             else PV_SCORE(1, 1);
