@@ -115,8 +115,15 @@ __global__ __launch_bounds__(kBlock) void k_cb_absmax(const float *__restrict__ 
                !(fabsf(v.w) <= 3.0e38f);
         m = fmaxf(m, a);
     }
+    __shared__ float s_m[kBlock / 64];
     for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_down(m, off));
-    if ((threadIdx.x & 63) == 0) atomicMax(&meta[0], __float_as_uint(m));
+    if ((threadIdx.x & 63) == 0) s_m[threadIdx.x >> 6] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) {   // one atomic per block: same-address atomics serialise
+#pragma unroll
+        for (int w = 1; w < kBlock / 64; ++w) m = fmaxf(m, s_m[w]);
+        atomicMax(&meta[0], __float_as_uint(m));
+    }
     if (bad) atomicMax(&meta[3], 1u);
 }
 
@@ -185,8 +192,15 @@ __global__ __launch_bounds__(kBlock) void k_prep(const float *__restrict__ cb, i
 #pragma unroll
             for (int u = 0; u < 2 * NK; ++u) A[((int64_t)tile * NK * 2 + u) * 32 + row] = chunk[u];
         }
+        __shared__ float s_d[kBlock / 64];
         for (int off = 32; off > 0; off >>= 1) d2 = fmaxf(d2, __shfl_down(d2, off));
-        if ((threadIdx.x & 63) == 0) atomicMax(&meta[2], __float_as_uint(d2));
+        if ((threadIdx.x & 63) == 0) s_d[threadIdx.x >> 6] = d2;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+#pragma unroll
+            for (int w = 1; w < kBlock / 64; ++w) d2 = fmaxf(d2, s_d[w]);
+            atomicMax(&meta[2], __float_as_uint(d2));
+        }
         return;
     }
 
@@ -711,7 +725,7 @@ pv_status pv_launch_mfma_search(pv_ctx *ctx, const pv_layout *l, const float *T,
         pv_timed t(ctx, PV_K_PREP);
         const int64_t ncb = (int64_t)csize * g;
         int blocks = (int)((ncb / 4 + kBlock * 4 - 1) / (kBlock * 4));
-        if (blocks > 256) blocks = 256;
+        if (blocks > 128) blocks = 128;
         hipLaunchKernelGGL(k_cb_absmax, dim3(blocks), dim3(kBlock), 0, sm, codebooks, ncb, cb_meta,
                            stats, fb_count, reinterpret_cast<unsigned long long *>(num_changed));
         const int cb_blocks = (csize + kBlock - 1) / kBlock;
