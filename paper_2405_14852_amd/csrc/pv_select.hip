@@ -29,7 +29,10 @@ constexpr int kFirstBins = 2048;                // digit 0: sign, exponent, 2 ma
 constexpr int kLastBins = 256;                  // digit 2: the low 8 mantissa bits
 constexpr int kItems = 8;                      // groups per thread in the compaction kernels
 constexpr int kChunk = kBlock * kItems;        // groups per chunk there
-constexpr int kMaxBlocks = 1024;               // persistent grid: 4 blocks per compute unit
+#ifndef PV_SEL_BLOCKS
+#define PV_SEL_BLOCKS 1024
+#endif
+constexpr int kMaxBlocks = PV_SEL_BLOCKS;      // persistent grid of the streaming kernels
 
 __device__ __forceinline__ int digit_of(unsigned key, int pass)
 {

@@ -54,3 +54,24 @@ def test_product_package_does_not_touch_the_oracle():
         if p.suffix in (".py", ".hip", ".h"):
             text = p.read_text()
             assert "import oracle" not in text and "pvo_" not in text, p
+
+
+def test_create_without_a_gpu_reports_a_device_error(lib):
+    """No GPU in this process: pv_create must fail cleanly (no fallback of any kind)."""
+    try:
+        import torch
+        if torch.cuda.is_available():
+            pytest.skip("a GPU is visible")
+    except ImportError:
+        pass
+    lib.pv_create.restype = ctypes.c_int
+    h = ctypes.c_void_p()
+    st = lib.pv_create(ctypes.byref(h), 0, None)
+    assert st != 0 and not h.value
+
+
+def test_binding_refuses_host_tensors():
+    import torch
+    from paper_2405_14852_amd import binding
+    with pytest.raises(TypeError):
+        binding._dev_ptr(torch.zeros(4), torch.float32, "W")
