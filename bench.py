@@ -2,8 +2,8 @@
 """Benchmark of the V-step re-encoding path on one MI355X.
 
 One "step" is one pass of the whole hot path over one weight matrix:
-    dequantize(codes) -> T = W - alpha*G -> select top-k groups -> re-encode
-    the selected groups -> dequantize(updated codes)
+    dequantize(codes) -> T = W - alpha*G and selection of the top-k groups (one
+    fused call) -> re-encode the selected groups -> dequantize(updated codes)
 on the 1x16 configuration (Llama-2-7B q_proj shape, 4096 x 4096, group 8, one
 codebook of 2^16 codewords, tau = 0.01 -> 20 971 groups re-encoded).
 
@@ -39,6 +39,8 @@ def main() -> int:
     ap.add_argument("--workload", default="c2_4096x4096_1x16")
     ap.add_argument("--search-mode", type=int, default=0,
                     help="0 = matrix-core filter + exact re-rank, 1 = exact scan only")
+    ap.add_argument("--separate-calls", action="store_true",
+                    help="pv_encode_targets + pv_select_topk_groups instead of the fused call")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -77,8 +79,11 @@ def main() -> int:
     def step():
         codes.view(torch.int16).copy_(codes0.view(torch.int16))   # same work every step
         ctx.pv_dequantize(lay, codes, cb, sc, Wq)
-        ctx.pv_encode_targets(lay, W, G, wl.alpha, T)
-        ctx.pv_select_topk_groups(lay, T, W, k, idx)
+        if args.separate_calls:
+            ctx.pv_encode_targets(lay, W, G, wl.alpha, T)
+            ctx.pv_select_topk_groups(lay, T, W, k, idx)
+        else:   # same outputs, T and W are not read back for the scores
+            ctx.pv_encode_targets_select(lay, W, G, wl.alpha, T, k, idx)
         ctx.pv_reencode_groups(lay, T, cb, sc, idx, k, wl.beam_width, codes, nch)
         ctx.pv_dequantize(lay, codes, cb, sc, Wq)
 
@@ -129,14 +134,16 @@ def main() -> int:
         roofline = {"kernel": "k_" + dominant, "bound": "alu", "achieved": a, "peak": PEAK_F64,
                     "unit": "TFLOP/s", "frac": a / PEAK_F64, "traffic": None}
     else:
-        per_param = {"encode_targets": 12.0, "group_scores": 8.0 + 4.0 / g,
+        per_param = {"encode_targets": 12.0 + (0.0 if args.separate_calls else 4.0 / g),
+                     "group_scores": 8.0 + 4.0 / g,
                      "dequantize": 4.0 + 2.0 * M / g}.get(dominant, 0.0)
         a = per_param * params / (kern[dominant]["avg_ms"] * 1e-3) / 1e9
         roofline = {"kernel": "k_" + dominant, "bound": "hbm", "achieved": a, "peak": PEAK_HBM,
                     "unit": "GB/s", "frac": a / PEAK_HBM, "traffic": None}
 
     hbm = {}
-    for name, per_param in (("encode_targets", 12.0), ("group_scores", 8.0 + 4.0 / g),
+    for name, per_param in (("encode_targets", 12.0 + (0.0 if args.separate_calls else 4.0 / g)),
+                            ("group_scores", 8.0 + 4.0 / g),
                             ("dequantize", 4.0 + 2.0 * M / g)):
         if name in kern:
             hbm[name + "_GBps"] = per_param * params / (kern[name]["avg_ms"] * 1e-3) / 1e9
@@ -175,7 +182,8 @@ def main() -> int:
         "config": {"workload": args.workload, "out_features": L.out_features,
                    "in_features": L.in_features, "group_size": g, "num_codebooks": M, "nbits": B,
                    "tau": wl.tau, "k_selected": k, "beam_width": wl.beam_width,
-                   "search_mode": args.search_mode},
+                   "search_mode": args.search_mode,
+                   "calls": "separate" if args.separate_calls else "fused targets+select"},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "reencode_only_groups_per_s": k / (reenc_ms * 1e-3) if reenc_ms else None,

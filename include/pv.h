@@ -75,6 +75,16 @@ pv_status pv_select_topk_groups(pv_ctx *ctx, const pv_layout *layout, const floa
                                 const float *W, int64_t k, int32_t *out_idx,
                                 float *group_scores /* NULL ok */);
 
+/* pv_encode_targets followed by pv_select_topk_groups, as one sweep over memory
+ * (Eq. 7 feeding Alg. 2 line 5): T is written and every group's score is taken
+ * from the registers that hold T and W, so neither is read back.  Outputs (T,
+ * out_idx, group_scores) are bit-identical to the two calls in sequence.
+ * T may alias G exactly; it must not alias W.  k == 0 still writes T (and
+ * group_scores when given). */
+pv_status pv_encode_targets_select(pv_ctx *ctx, const pv_layout *layout, const float *W,
+                                   const float *G, float alpha, float *T, int64_t k,
+                                   int32_t *out_idx, float *group_scores);
+
 /* Eq. 7 argmin restricted to the listed groups (Alg. 3 last line, "find_nearest"):
  * for each listed group with target t (g values of T), row scale s and current
  * code tuple p, minimise  obj(b) = || s * sum_m codebooks[m, b_m, :] - t ||^2

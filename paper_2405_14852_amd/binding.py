@@ -72,6 +72,7 @@ def load_library():
     lib.pv_last_error.restype = ctypes.c_char_p
     lib.pv_encode_targets.argtypes = [vp, lp, vp, vp, f32, vp]
     lib.pv_select_topk_groups.argtypes = [vp, lp, vp, vp, i64, vp, vp]
+    lib.pv_encode_targets_select.argtypes = [vp, lp, vp, vp, f32, vp, i64, vp, vp]
     lib.pv_reencode_groups.argtypes = [vp, lp, vp, vp, vp, vp, i64, i32, vp, vp]
     lib.pv_dequantize.argtypes = [vp, lp, vp, vp, vp, vp]
     lib.pv_set_search_mode.argtypes = [vp, ctypes.c_int]
@@ -80,7 +81,8 @@ def load_library():
     lib.pv_timing_read.argtypes = [vp, ctypes.c_int, ctypes.POINTER(ctypes.c_double),
                                    ctypes.POINTER(i64)]
     lib.pv_reencode_stats.argtypes = [vp, ctypes.POINTER(i64)]
-    for name in ("pv_create", "pv_encode_targets", "pv_select_topk_groups", "pv_reencode_groups",
+    for name in ("pv_create", "pv_encode_targets", "pv_select_topk_groups",
+                 "pv_encode_targets_select", "pv_reencode_groups",
                  "pv_dequantize", "pv_set_search_mode", "pv_timing_enable", "pv_timing_reset",
                  "pv_timing_read", "pv_reencode_stats"):
         getattr(lib, name).restype = ctypes.c_int
@@ -143,6 +145,15 @@ class PVContext:
         self._check(self._lib.pv_select_topk_groups(
             self._h, ctypes.byref(lay), _dev_ptr(T, torch.float32, "T"),
             _dev_ptr(W, torch.float32, "W"), int(k),
+            _dev_ptr(out_idx, torch.int32, "out_idx", allow_none=(k == 0)),
+            _dev_ptr(group_scores, torch.float32, "group_scores", allow_none=True)))
+
+    def pv_encode_targets_select(self, layout: Layout, W, G, alpha: float, T, k: int, out_idx,
+                                 group_scores=None):
+        lay = layout.c()
+        self._check(self._lib.pv_encode_targets_select(
+            self._h, ctypes.byref(lay), _dev_ptr(W, torch.float32, "W"),
+            _dev_ptr(G, torch.float32, "G"), float(alpha), _dev_ptr(T, torch.float32, "T"), int(k),
             _dev_ptr(out_idx, torch.int32, "out_idx", allow_none=(k == 0)),
             _dev_ptr(group_scores, torch.float32, "group_scores", allow_none=True)))
 

@@ -171,6 +171,27 @@ extern "C" pv_status pv_select_topk_groups(pv_ctx *ctx, const pv_layout *l, cons
     return pv_launch_select(ctx, l, T, W, k, out_idx, group_scores);
 }
 
+extern "C" pv_status pv_encode_targets_select(pv_ctx *ctx, const pv_layout *l, const float *W,
+                                              const float *G, float alpha, float *T, int64_t k,
+                                              int32_t *out_idx, float *group_scores)
+{
+    if (!ctx) return PV_ERR_INVALID_ARG;
+    pv_status st = check_layout(ctx, l);
+    if (st != PV_OK) return st;
+    int64_t N = pv_num_groups(l);
+    if (k < 0 || k > N)
+        return pv_fail(ctx, PV_ERR_INVALID_ARG, "k = %lld outside [0, %lld]", (long long)k,
+                       (long long)N);
+    if (!W || !G || !T) return pv_fail(ctx, PV_ERR_INVALID_ARG, "NULL tensor pointer");
+    if (k > 0 && !out_idx) return pv_fail(ctx, PV_ERR_INVALID_ARG, "out_idx is NULL");
+    if (misaligned(W) || misaligned(G) || misaligned(T) || misaligned(group_scores))
+        return pv_fail(ctx, PV_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
+    if (T == W) return pv_fail(ctx, PV_ERR_INVALID_ARG, "T must not alias W (W is scored against T)");
+    if (N == 0) return PV_OK;
+    PV_HIP(ctx, hipSetDevice(ctx->device));
+    return pv_launch_select(ctx, l, T, W, k, out_idx, group_scores, G, alpha);
+}
+
 extern "C" pv_status pv_reencode_groups(pv_ctx *ctx, const pv_layout *l, const float *T,
                                         const float *codebooks, const float *scales,
                                         const int32_t *group_idx, int64_t k, int32_t beam_width,

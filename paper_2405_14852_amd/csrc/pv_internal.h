@@ -83,7 +83,8 @@ pv_status pv_launch_encode_targets(pv_ctx *ctx, const float *W, const float *G, 
 pv_status pv_launch_dequantize(pv_ctx *ctx, const pv_layout *l, const uint16_t *codes,
                                const float *codebooks, const float *scales, float *W_out);
 pv_status pv_launch_select(pv_ctx *ctx, const pv_layout *l, const float *T, const float *W,
-                           int64_t k, int32_t *out_idx, float *scores);
+                           int64_t k, int32_t *out_idx, float *scores, const float *G = nullptr,
+                           float alpha = 0.0f);
 pv_status pv_launch_exact_scan(pv_ctx *ctx, const pv_layout *l, const float *T,
                                const float *codebooks, const float *scales,
                                const int32_t *list, const uint32_t *d_count, int64_t max_count,

@@ -270,6 +270,73 @@ __global__ __launch_bounds__(kBlock) void k_scores_hist0_vec(const float *__rest
     if (want_hist) flush_hist(lh, hist0, kFirstBins);
 }
 
+// Targets and pass 0 in one sweep (g = 4 * PARTS): T = W - alpha * G is formed and stored, and
+// the scores and the digit-0 histogram are taken from the same registers, so T and W are
+// not read back from memory.  The arithmetic is the one of the separate kernels: one fused
+// multiply-add per element of T, then the subtraction T - W and the chain above.
+template <int PARTS>
+__global__ __launch_bounds__(kBlock) void k_targets_scores_hist0_vec(const float *W, const float *G,
+                                                                     float alpha, float *T,
+                                                                     float *__restrict__ scores,
+                                                                     unsigned *__restrict__ hist0,
+                                                                     int64_t nvec, int want_hist)
+{
+    __shared__ unsigned lh[kFirstBins];
+    if (want_hist)
+        for (int b = threadIdx.x; b < kFirstBins; b += kBlock) lh[b] = 0;
+    __syncthreads();
+    const pv_f4 *W4 = reinterpret_cast<const pv_f4 *>(W);
+    const pv_f4 *G4 = reinterpret_cast<const pv_f4 *>(G);
+    pv_f4 *T4 = reinterpret_cast<pv_f4 *>(T);
+    const int part = threadIdx.x & (PARTS - 1);
+    for (int64_t cbase = (int64_t)blockIdx.x * (kBlock * kVecUnroll); cbase < nvec;
+         cbase += (int64_t)gridDim.x * (kBlock * kVecUnroll)) {
+        const int64_t base = cbase + threadIdx.x;
+        pv_f4 w[kVecUnroll], gr[kVecUnroll];
+#pragma unroll
+        for (int u = 0; u < kVecUnroll; ++u) {
+            const int64_t i = base + (int64_t)u * kBlock;
+            if (i < nvec) {
+                w[u] = __builtin_nontemporal_load(&W4[i]);
+                gr[u] = __builtin_nontemporal_load(&G4[i]);
+            } else {
+                w[u] = pv_f4{0.f, 0.f, 0.f, 0.f};
+                gr[u] = w[u];
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kVecUnroll; ++u) {
+            const int64_t i = base + (int64_t)u * kBlock;
+            pv_f4 t;
+            t.x = fmaf(-alpha, gr[u].x, w[u].x);
+            t.y = fmaf(-alpha, gr[u].y, w[u].y);
+            t.z = fmaf(-alpha, gr[u].z, w[u].z);
+            t.w = fmaf(-alpha, gr[u].w, w[u].w);
+            if (i < nvec) __builtin_nontemporal_store(t, &T4[i]);
+            const float d0 = t.x - w[u].x, d1 = t.y - w[u].y;
+            const float d2 = t.z - w[u].z, d3 = t.w - w[u].w;
+            float s = 0.0f;
+#pragma unroll
+            for (int r = 0; r < PARTS; ++r) {
+                float in = r == 0 ? 0.0f : __shfl_up(s, 1);
+                if (part >= r) {
+                    float c = part == 0 ? 0.0f : in;
+                    c = fmaf(d0, d0, c);
+                    c = fmaf(d1, d1, c);
+                    c = fmaf(d2, d2, c);
+                    c = fmaf(d3, d3, c);
+                    if (part == r) s = c;
+                }
+            }
+            const bool valid = i < nvec && part == PARTS - 1;
+            if (valid) scores[i / PARTS] = s;
+            if (want_hist) hist_add<PV_VOTE_ROUNDS>(lh, digit_of(__float_as_uint(s), 0), valid);
+        }
+    }
+    __syncthreads();
+    if (want_hist) flush_hist(lh, hist0, kFirstBins);
+}
+
 // Passes 1 and 2: histogram of the next digit among keys that match the digits
 // chosen so far.  Each launch resolves the digit of the previous histogram and
 // block 0 publishes it in `state` for the launches that follow:
@@ -439,8 +506,9 @@ __global__ __launch_bounds__(kBlock) void k_compact_write(const float *__restric
 
 }  // namespace
 
+// G != nullptr: T is an OUTPUT, formed here as W - alpha * G in the same pass that scores it.
 pv_status pv_launch_select(pv_ctx *ctx, const pv_layout *l, const float *T, const float *W,
-                           int64_t k, int32_t *out_idx, float *scores)
+                           int64_t k, int32_t *out_idx, float *scores, const float *G, float alpha)
 {
     const int N = (int)pv_num_groups(l);
     const int g = l->group_size;
@@ -461,7 +529,29 @@ pv_status pv_launch_select(pv_ctx *ctx, const pv_layout *l, const float *T, cons
     unsigned *cc = static_cast<unsigned *>(ctx->sel_blocks.ptr);
     unsigned *state = static_cast<unsigned *>(ctx->sel_state.ptr);
     const int want_hist = k > 0 ? 1 : 0;
-    {
+    const bool vec_g = g == 4 || g == 8 || g == 16 || g == 32 || g == 64;
+    if (G && !vec_g) {   // no fused kernel for this group size: form T first
+        st = pv_launch_encode_targets(ctx, W, G, alpha, const_cast<float *>(T),
+                                      l->out_features * l->in_features);
+        if (st != PV_OK) return st;
+        G = nullptr;
+    }
+    if (G) {
+        pv_timed t(ctx, PV_K_ENCODE_TARGETS);
+        const int64_t nvec = (int64_t)N * (g / 4);
+        int64_t vb = (nvec + kBlock * kVecUnroll - 1) / (kBlock * kVecUnroll);
+        const unsigned vblocks = (unsigned)(vb < kMaxBlocks ? vb : kMaxBlocks);
+        float *Tw = const_cast<float *>(T);
+#define PV_FUSED(PARTS_)                                                                       \
+    hipLaunchKernelGGL(k_targets_scores_hist0_vec<PARTS_>, dim3(vblocks), dim3(kBlock), 0,     \
+                       ctx->stream, W, G, alpha, Tw, scores, hist, nvec, want_hist)
+        if (g == 4) PV_FUSED(1);
+        else if (g == 8) PV_FUSED(2);
+        else if (g == 16) PV_FUSED(4);
+        else if (g == 32) PV_FUSED(8);
+        else PV_FUSED(16);
+#undef PV_FUSED
+    } else {
         pv_timed t(ctx, PV_K_GROUP_SCORES);
         const int64_t nvec = (int64_t)N * (g / 4);
         int64_t vb = (nvec + kBlock * kVecUnroll - 1) / (kBlock * kVecUnroll);

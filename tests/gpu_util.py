@@ -59,6 +59,17 @@ class GpuRun:
         idx = idx[:k].cpu().numpy()
         return (idx, sc.cpu().numpy()) if want_scores else idx
 
+    def targets_select(self, k, alpha=None, want_scores=False, G=None):
+        """The fused call: returns (T on device, ids[, scores])."""
+        T = torch.empty_like(self.W)
+        idx = torch.empty(max(k, 1), dtype=torch.int32, device=DEV)
+        sc = torch.empty(self.lay.num_groups, dtype=torch.float32, device=DEV) if want_scores else None
+        self.ctx.pv_encode_targets_select(self.lay, self.W, self.G if G is None else G,
+                                          self.wl.alpha if alpha is None else alpha, T, k, idx, sc)
+        torch.cuda.synchronize()
+        idx = idx[:k].cpu().numpy()
+        return (T, idx, sc.cpu().numpy()) if want_scores else (T, idx)
+
     def reencode(self, T, idx_np, beam_width=None, codes=None):
         idx = dev_i32(idx_np)
         codes = self.codes.clone() if codes is None else codes
