@@ -99,6 +99,8 @@ __global__ __launch_bounds__(kBlock) void k_exact_scan(
     __shared__ unsigned s_last;
     __shared__ double s_fin_obj[GPB];
     __shared__ int s_fin_idx[GPB];
+    __shared__ int s_prev[GPB];          // previous code of each group and its codeword,
+    __shared__ float s_cprev[GPB][GS];   // fetched up front: the final tie rule needs them
     const int64_t count = d_count ? (int64_t)*d_count : max_count;
     const int csize = 1 << nbits;
     const int64_t items = (count + GPB - 1) / GPB;
@@ -115,12 +117,14 @@ __global__ __launch_bounds__(kBlock) void k_exact_scan(
             if (n < 0 || n >= N) n = -1;
             s_group[threadIdx.x] = n;
             s_scale[threadIdx.x] = n >= 0 ? scales[n / gpr] : 0.0f;
+            s_prev[threadIdx.x] = n >= 0 ? (int)(codes[n] & (csize - 1)) : 0;
         }
         __syncthreads();
         for (int e = threadIdx.x; e < GPB * g; e += kBlock) {
             int q = e / g, i = e - q * g;
             int n = s_group[q];
             s_t[q][i] = n >= 0 ? T[(int64_t)n * g + i] : 0.0f;
+            s_cprev[q][i] = codebook[(int64_t)s_prev[q] * g + i];
         }
         __syncthreads();
         best_t best[GPB];
@@ -137,30 +141,46 @@ __global__ __launch_bounds__(kBlock) void k_exact_scan(
 #pragma unroll
                 for (int i = 0; i < GS; ++i) tt[q][i] = (double)s_t[q][i];
             }
-            for (int c = c_begin + threadIdx.x; c < c_end; c += kBlock) {
-                const pv_f4 *cw4 = reinterpret_cast<const pv_f4 *>(codebook + (int64_t)c * GS);
-                double obj[GPB];
+            // kBatch codewords per step: all their loads are issued before the arithmetic, so a
+            // step costs one memory round trip (this kernel runs on few groups: latency bound)
+            constexpr int kBatch = 4;
+            for (int c0 = c_begin + threadIdx.x; c0 < c_end; c0 += kBlock * kBatch) {
+                pv_f4 cv[kBatch][GS / 4];
 #pragma unroll
-                for (int q = 0; q < GPB; ++q) obj[q] = 0.0;
+                for (int u = 0; u < kBatch; ++u) {
+                    const int c = c0 + u * kBlock;
+                    const pv_f4 *cw4 = reinterpret_cast<const pv_f4 *>(
+                        codebook + (int64_t)(c < c_end ? c : c_begin) * GS);
 #pragma unroll
-                for (int v4 = 0; v4 < GS / 4; ++v4) {
-                    pv_f4 cv = cw4[v4];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        double acc = (double)cv[e];
-#pragma unroll
-                        for (int q = 0; q < GPB; ++q) {
-                            double r = sc[q] * acc - tt[q][v4 * 4 + e];
-                            obj[q] = obj[q] + r * r;
-                        }
-                    }
+                    for (int v4 = 0; v4 < GS / 4; ++v4) cv[u][v4] = cw4[v4];
                 }
 #pragma unroll
-                for (int q = 0; q < GPB; ++q)
-                    if (obj[q] < best[q].obj) {
-                        best[q].obj = obj[q];
-                        best[q].idx = c;
+                for (int u = 0; u < kBatch; ++u) {
+                    const int c = c0 + u * kBlock;
+                    double obj[GPB];
+#pragma unroll
+                    for (int q = 0; q < GPB; ++q) obj[q] = 0.0;
+#pragma unroll
+                    for (int v4 = 0; v4 < GS / 4; ++v4) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            double acc = (double)cv[u][v4][e];
+#pragma unroll
+                            for (int q = 0; q < GPB; ++q) {
+                                double r = sc[q] * acc - tt[q][v4 * 4 + e];
+                                obj[q] = obj[q] + r * r;
+                            }
+                        }
                     }
+                    if (c < c_end) {
+#pragma unroll
+                        for (int q = 0; q < GPB; ++q)
+                            if (obj[q] < best[q].obj) {
+                                best[q].obj = obj[q];
+                                best[q].idx = c;
+                            }
+                    }
+                }
             }
         } else {
             for (int c = c_begin + threadIdx.x; c < c_end; c += kBlock) {
@@ -246,10 +266,10 @@ __global__ __launch_bounds__(kBlock) void k_exact_scan(
             for (int q = 0; q < GPB; ++q) {
                 if (s_group[q] < 0) continue;
                 const int n = s_group[q];
-                const int prev = codes[n] & (csize - 1);
+                const int prev = s_prev[q];
                 double o_prev = 0.0;
                 for (int i = 0; i < g; ++i) {
-                    double acc = (double)codebook[(int64_t)prev * g + i];
+                    double acc = (double)s_cprev[q][i];
                     double r = (double)s_scale[q] * acc - (double)s_t[q][i];
                     o_prev = o_prev + r * r;
                 }
@@ -266,12 +286,23 @@ __global__ __launch_bounds__(kBlock) void k_exact_scan(
     // the filter's codebook statistics are dead once this (last) kernel of a call runs
     if (reset_meta && blockIdx.x == 0 && threadIdx.x < 8) reset_meta[threadIdx.x] = 0u;
     // fold the re-rank kernel's per-block counters (decided, changed, candidates) into the totals
-    if (rr_counts && blockIdx.x == 0) {
+    if (rr_counts && blockIdx.x == gridDim.x - 1) {
         unsigned long long c0 = 0, c1 = 0, c2 = 0;
-        for (int b = threadIdx.x; b < rr_blocks; b += kBlock) {
-            c0 += rr_counts[3 * b];
-            c1 += rr_counts[3 * b + 1];
-            c2 += rr_counts[3 * b + 2];
+        constexpr int kU = 4;            // independent loads in flight per thread
+        for (int b0 = threadIdx.x; b0 < rr_blocks; b0 += kBlock * kU) {
+            unsigned v[kU][3];
+#pragma unroll
+            for (int u = 0; u < kU; ++u) {
+                const int b = b0 + u * kBlock;
+#pragma unroll
+                for (int e = 0; e < 3; ++e) v[u][e] = b < rr_blocks ? rr_counts[3 * b + e] : 0u;
+            }
+#pragma unroll
+            for (int u = 0; u < kU; ++u) {
+                c0 += v[u][0];
+                c1 += v[u][1];
+                c2 += v[u][2];
+            }
         }
         for (int off = 32; off > 0; off >>= 1) {
             c0 += __shfl_down(c0, off);

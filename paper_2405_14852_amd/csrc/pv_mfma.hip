@@ -548,14 +548,22 @@ __global__ __launch_bounds__(kBlock) void k_rerank(
                 t[v4 * 4 + 3] = v.w;
             }
         }
-        // best key over all partitions, with its partition
+        // the previous code and the filter's records are fetched side by side: their round
+        // trips to memory overlap
+        const int prev = codes[n] & (csize - 1);
         constexpr int kMaxRec = 4;           // P <= 64
         uint2 rec[kMaxRec];
-        unsigned long long bk = ~0ull;
 #pragma unroll
         for (int u = 0; u < kMaxRec; ++u) {
             int p = q + 16 * u;
             rec[u] = p < P ? partials[(int64_t)j * P + p] : make_uint2(0xFFFFFFFFu, 0xFFFFFFFFu);
+        }
+        const double o_prev = exact_obj<G>(codebook + (int64_t)prev * G, s, t);
+        // best key over all partitions, with its partition
+        unsigned long long bk = ~0ull;
+#pragma unroll
+        for (int u = 0; u < kMaxRec; ++u) {
+            int p = q + 16 * u;
             unsigned long long v = ((unsigned long long)rec[u].x << 32) | (unsigned)p;
             bk = v < bk ? v : bk;
         }
@@ -595,8 +603,6 @@ __global__ __launch_bounds__(kBlock) void k_rerank(
         mine.idx = 0x7fffffff;
         eval_half_tile(best_key, best_p, mine);
         cand_t first = team_min(mine);
-        const int prev = codes[n] & (csize - 1);
-        const double o_prev = exact_obj<G>(codebook + (int64_t)prev * G, s, t);
         if (o_prev < first.obj) first.obj = o_prev;   // the previous code is a candidate too
 
         // every codeword that was not evaluated and could still reach E* has a key value below vcut

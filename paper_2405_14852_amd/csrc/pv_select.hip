@@ -289,21 +289,27 @@ __global__ __launch_bounds__(kBlock) void k_targets_scores_hist0_vec(const float
     const pv_f4 *G4 = reinterpret_cast<const pv_f4 *>(G);
     pv_f4 *T4 = reinterpret_cast<pv_f4 *>(T);
     const int part = threadIdx.x & (PARTS - 1);
-    for (int64_t cbase = (int64_t)blockIdx.x * (kBlock * kVecUnroll); cbase < nvec;
-         cbase += (int64_t)gridDim.x * (kBlock * kVecUnroll)) {
-        const int64_t base = cbase + threadIdx.x;
-        pv_f4 w[kVecUnroll], gr[kVecUnroll];
+    const int64_t step = (int64_t)gridDim.x * (kBlock * kVecUnroll);
+    pv_f4 w[kVecUnroll], gr[kVecUnroll], wn[kVecUnroll], gn[kVecUnroll];
+    auto load = [&](int64_t cbase, pv_f4 *pw, pv_f4 *pg) {
 #pragma unroll
         for (int u = 0; u < kVecUnroll; ++u) {
-            const int64_t i = base + (int64_t)u * kBlock;
+            const int64_t i = cbase + threadIdx.x + (int64_t)u * kBlock;
             if (i < nvec) {
-                w[u] = __builtin_nontemporal_load(&W4[i]);
-                gr[u] = __builtin_nontemporal_load(&G4[i]);
+                pw[u] = __builtin_nontemporal_load(&W4[i]);
+                pg[u] = __builtin_nontemporal_load(&G4[i]);
             } else {
-                w[u] = pv_f4{0.f, 0.f, 0.f, 0.f};
-                gr[u] = w[u];
+                pw[u] = pv_f4{0.f, 0.f, 0.f, 0.f};
+                pg[u] = pw[u];
             }
         }
+    };
+    int64_t cbase = (int64_t)blockIdx.x * (kBlock * kVecUnroll);
+    if (cbase < nvec) load(cbase, w, gr);
+    for (; cbase < nvec; cbase += step) {
+        // the loads of the next chunk are in flight while this one is scored
+        if (cbase + step < nvec) load(cbase + step, wn, gn);
+        const int64_t base = cbase + threadIdx.x;
 #pragma unroll
         for (int u = 0; u < kVecUnroll; ++u) {
             const int64_t i = base + (int64_t)u * kBlock;
@@ -331,6 +337,11 @@ __global__ __launch_bounds__(kBlock) void k_targets_scores_hist0_vec(const float
             const bool valid = i < nvec && part == PARTS - 1;
             if (valid) scores[i / PARTS] = s;
             if (want_hist) hist_add<PV_VOTE_ROUNDS>(lh, digit_of(__float_as_uint(s), 0), valid);
+        }
+#pragma unroll
+        for (int u = 0; u < kVecUnroll; ++u) {
+            w[u] = wn[u];
+            gr[u] = gn[u];
         }
     }
     __syncthreads();
