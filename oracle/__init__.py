@@ -44,6 +44,10 @@ def _load():
                                             p, p, p, p, p]
         lib.pvo_group_objective.argtypes = [i64, i64, i32, i32, i32, p, p, p, p, i64, p, p]
         lib.pvo_dequantize.argtypes = [i64, i64, i32, i32, i32, p, p, p, p]
+        f64 = ctypes.c_double
+        lib.pvo_reencode_trust_ratio.argtypes = [i64, i64, i32, i32, i32, p, p, p, p, i64, i64, f64,
+                                                 i32, p, p, p, p]
+        lib.pvo_reencode_trust_ratio.restype = ctypes.c_int
         for f in (lib.pvo_encode_targets, lib.pvo_select_topk_groups, lib.pvo_reencode_groups,
                   lib.pvo_group_objective, lib.pvo_dequantize, lib.pvo_num_threads):
             f.restype = ctypes.c_int
@@ -113,6 +117,31 @@ def reencode_groups(T, codebooks, scales, group_idx, codes, beam_width: int = 1,
         raise ValueError("pvo_reencode_groups failed")
     return new, {"num_changed": int(changed.value), "near_tie": near.astype(bool),
                  "obj_new": obj_new, "obj_prev": obj_prev}
+
+
+def reencode_trust_ratio(T, W, codebooks, scales, codes, k_max: int, chunk: int, ratio: float,
+                         beam_width: int = 1):
+    """Returns (new_codes, info); info: rank_idx [k_max] (selection order), num_applied,
+    change_sq (squared change of the kept groups), norm_sq (||x^k||^2)."""
+    T, W = _f32(T), _f32(W)
+    cb = _f32(codebooks)
+    sc = _f32(scales)
+    M, csize, g = cb.shape
+    B = int(csize).bit_length() - 1
+    out_f, in_f = T.shape
+    new = np.ascontiguousarray(codes, dtype=np.uint16).copy()
+    assert new.shape == (out_f, in_f // g, M), new.shape
+    rank = np.empty(max(k_max, 1), dtype=np.int32)
+    applied = ctypes.c_int64(0)
+    stats = np.zeros(2, dtype=np.float64)
+    rc = _load().pvo_reencode_trust_ratio(out_f, in_f, g, M, B, _ptr(T), _ptr(W), _ptr(cb),
+                                          _ptr(sc), int(k_max), int(chunk), float(ratio),
+                                          int(beam_width), _ptr(new), _ptr(rank),
+                                          ctypes.addressof(applied), _ptr(stats))
+    if rc:
+        raise ValueError("pvo_reencode_trust_ratio failed")
+    return new, {"rank_idx": rank[:k_max], "num_applied": int(applied.value),
+                 "change_sq": float(stats[0]), "norm_sq": float(stats[1])}
 
 
 def group_objective(T, codebooks, scales, group_idx, tuples) -> np.ndarray:

@@ -30,6 +30,10 @@
  *                           single-index descent (App. D).  Beyond those bounds
  *                           the beam result is PARITY UNPINNED.
  *   pvo_dequantize          Alg. 3 line 1: W = scale_row * sum_m codeword_m.
+ *   pvo_reencode_trust_ratio  Sec. 4.3 / App. K: subspace size from the trust ratio,
+ *                           the chunked procedure of App. K step by step (pinned by
+ *                           brute force over all prefix lengths, a closed-form case,
+ *                           independence of the chunk size and the limits ratio = 0 / inf).
  *
  * Arithmetic: objectives in IEEE double on the fp32 inputs, evaluated in index
  * order without contraction (compile with -ffp-contract=off).  The selection
@@ -342,6 +346,121 @@ int pvo_dequantize(int64_t out_features, int64_t in_features, int g, int M, int 
         }
     }
     return bad ? PVO_ERR : PVO_OK;
+}
+
+/* ------------------------------------------------- trust-ratio subspace size */
+
+/* Squared change of one group's dequantised weights when its code tuple goes from
+ * `before` to `after`: the fp32 weights of pvo_dequantize, difference and square in
+ * double, index order. */
+static double group_change(const float *codebooks, int M, int64_t csize, int g, float s,
+                           const uint16_t *before, const uint16_t *after)
+{
+    double d = 0.0;
+    for (int i = 0; i < g; ++i) {
+        float a = codebooks[((int64_t)0 * csize + before[0]) * g + i];
+        float b = codebooks[((int64_t)0 * csize + after[0]) * g + i];
+        for (int m = 1; m < M; ++m) {
+            a = a + codebooks[((int64_t)m * csize + before[m]) * g + i];
+            b = b + codebooks[((int64_t)m * csize + after[m]) * g + i];
+        }
+        double diff = (double)(s * b) - (double)(s * a);
+        d = d + diff * diff;
+    }
+    return d;
+}
+
+/* The subspace size of Sec. 4.3 / App. K (hyperparameter paragraph): tau is the largest
+ * number of weights whose update keeps the trust ratio ||x^{k+1} - x^k|| / ||x^k|| below
+ * `ratio`.  Followed step by step: candidates are taken in the order of the selection
+ * rule (largest update norm first, lower id first), `chunk` groups at a time; each chunk
+ * is re-encoded and its change added to the total; when the total no longer satisfies the
+ * bound, groups of that last chunk are put back to their previous codes, from the end of
+ * the chunk, until it does; at least one group whose code changed is always kept.
+ * Reading: the unit is a weight group, x is this matrix' dequantised weights (the trust
+ * ratio is taken per weight matrix like the selection of Sec. 3.4), the comparison is
+ * strict and done on squares:  sum of changes < ratio^2 * ||x^k||^2, all in double.
+ * At most k_max groups are tried.  Returns the number of groups kept in *num_applied
+ * (the first *num_applied entries of rank_idx), stats[0] = their squared change,
+ * stats[1] = ||x^k||^2. */
+int pvo_reencode_trust_ratio(int64_t out_features, int64_t in_features, int g, int M, int B,
+                             const float *T, const float *W, const float *codebooks,
+                             const float *scales, int64_t k_max, int64_t chunk, double ratio,
+                             int beam_width, uint16_t *codes, int32_t *rank_idx,
+                             int64_t *num_applied, double *stats)
+{
+    if (!T || !W || !codebooks || !scales || !codes || !rank_idx || !num_applied) return PVO_ERR;
+    if (g < 1 || in_features % g || M < 1 || M > PVO_MAX_M || B < 1 || B > 16) return PVO_ERR;
+    int64_t gpr = in_features / g, N = out_features * gpr, csize = (int64_t)1 << B;
+    if (k_max < 0 || k_max > N || chunk < 1 || beam_width < 1 || !(ratio >= 0.0)) return PVO_ERR;
+
+    /* order of the selection rule */
+    scored_t *all = (scored_t *)malloc(sizeof(scored_t) * (size_t)(N > 0 ? N : 1));
+    uint16_t *saved = (uint16_t *)malloc(sizeof(uint16_t) * (size_t)(k_max > 0 ? k_max * M : 1));
+    double *prefix = (double *)malloc(sizeof(double) * (size_t)(k_max + 1));
+    if (!all || !saved || !prefix) { free(all); free(saved); free(prefix); return PVO_ERR; }
+    for (int64_t n = 0; n < N; ++n) {
+        all[n].score = group_score(T + n * g, W + n * g, g);
+        all[n].id = (int32_t)n;
+    }
+    qsort(all, (size_t)N, sizeof(scored_t), cmp_scored);
+    for (int64_t r = 0; r < k_max; ++r) rank_idx[r] = all[r].id;
+    free(all);
+
+    /* ||x^k||^2 of the current dequantised matrix */
+    double normsq = 0.0;
+    for (int64_t n = 0; n < N; ++n) {
+        float s = scales[n / gpr];
+        for (int i = 0; i < g; ++i) {
+            float acc = codebooks[((int64_t)0 * csize + codes[n * M]) * g + i];
+            for (int m = 1; m < M; ++m)
+                acc = acc + codebooks[((int64_t)m * csize + codes[n * M + m]) * g + i];
+            double w = (double)(s * acc);
+            normsq = normsq + w * w;
+        }
+    }
+    const double bound = ratio * ratio * normsq;
+
+    int64_t applied = 0, first_changed = -1;
+    prefix[0] = 0.0;
+    int rc = PVO_OK;
+    for (int64_t start = 0; start < k_max && rc == PVO_OK; start += chunk) {
+        int64_t end = start + chunk < k_max ? start + chunk : k_max;
+        for (int64_t r = start; r < end; ++r)
+            for (int m = 0; m < M; ++m) saved[r * M + m] = codes[(int64_t)rank_idx[r] * M + m];
+        rc = pvo_reencode_groups(out_features, in_features, g, M, B, T, codebooks, scales,
+                                 rank_idx + start, end - start, beam_width, 0, codes, NULL, NULL,
+                                 NULL, NULL);
+        if (rc != PVO_OK) break;
+        for (int64_t r = start; r < end; ++r) {
+            int64_t n = rank_idx[r];
+            double d = group_change(codebooks, M, csize, g, scales[n / gpr], saved + r * M,
+                                    codes + n * M);
+            int diff = 0;
+            for (int m = 0; m < M; ++m) diff |= (saved[r * M + m] != codes[n * M + m]);
+            if (diff && first_changed < 0) first_changed = r;
+            prefix[r + 1] = prefix[r] + d;
+        }
+        applied = end;
+        if (!(prefix[applied] < bound)) {
+            /* undo from the end of this chunk until the bound holds; keep one changed group */
+            while (applied > start && !(prefix[applied] < bound)) {
+                if (first_changed >= 0 && applied - 1 <= first_changed) break;
+                int64_t n = rank_idx[applied - 1];
+                for (int m = 0; m < M; ++m) codes[n * M + m] = saved[(applied - 1) * M + m];
+                --applied;
+            }
+            break;
+        }
+    }
+    *num_applied = applied;
+    if (stats) {
+        stats[0] = prefix[applied];
+        stats[1] = normsq;
+    }
+    free(saved);
+    free(prefix);
+    return rc;
 }
 
 int pvo_num_threads(void)

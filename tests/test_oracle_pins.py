@@ -444,3 +444,138 @@ def test_path_invariants(name, shape):
     W2 = oracle.dequantize(new, wl.codebooks, wl.scales)
     err_new = ((W2 - T).astype(np.float64) ** 2).reshape(-1, g).sum(1)[idx]
     assert np.allclose(err_new, info["obj_new"], rtol=1e-4)
+
+
+# ---------------------------------------------- trust-ratio subspace size (Sec. 4.3, App. K)
+
+def _tr_case(seed, M=1, B=5, beam=1, shape=(24, 128), g=8, sigma_g=1e-2):
+    wl = workloads.make(shape[0], shape[1], g, M, B, seed=seed, sigma_g=sigma_g, beam_width=beam)
+    # current weights = the dequantised codes, as in a real V step (the generator leaves W dense)
+    wl.W = oracle.dequantize(wl.codes, wl.codebooks, wl.scales)
+    T = oracle.encode_targets(wl.W, wl.G, wl.alpha)
+    return wl, T
+
+
+def _rank_order(T, W, g, k):
+    """Selection order (largest score first, lower id first) written out with numpy."""
+    d = (T - W).reshape(-1, g).astype(np.float32)
+    s = np.zeros(d.shape[0], dtype=np.float32)
+    for i in range(g):
+        s = np.float32(d[:, i]) * np.float32(d[:, i]) + s     # exact product + one rounding = fma
+        # (products of fp32 are exact in double; emulate the fused op in double then round)
+    s64 = np.zeros(d.shape[0], dtype=np.float64)
+    acc = np.zeros(d.shape[0], dtype=np.float32)
+    for i in range(g):
+        acc = (d[:, i].astype(np.float64) ** 2 + acc.astype(np.float64)).astype(np.float32)
+    del s, s64
+    order = np.lexsort((np.arange(len(acc)), -acc.astype(np.float64)))
+    return order[:k].astype(np.int32)
+
+
+@pytest.mark.parametrize("seed,M,B,beam", [(31, 1, 5, 1), (32, 2, 3, 4), (33, 1, 8, 1)])
+@pytest.mark.parametrize("ratio", [0.02, 0.1, 0.2])
+def test_trust_ratio_is_the_largest_feasible_prefix(seed, M, B, beam, ratio):
+    """Brute force over every prefix length, through independent routines: plain re-encode of
+    the top-L groups, dequantise, Frobenius norms by numpy."""
+    wl, T = _tr_case(seed, M=M, B=B, beam=beam)
+    g = wl.layout.group_size
+    k_max = 60
+    new, info = oracle.reencode_trust_ratio(T, wl.W, wl.codebooks, wl.scales, wl.codes, k_max,
+                                            chunk=7, ratio=ratio, beam_width=beam)
+    rank = _rank_order(T, wl.W, g, k_max)
+    assert np.array_equal(info["rank_idx"], rank)
+    x0 = oracle.dequantize(wl.codes, wl.codebooks, wl.scales).astype(np.float64)
+    feas, moved = [], []
+    for L in range(k_max + 1):
+        cL, _ = oracle.reencode_groups(T, wl.codebooks, wl.scales, np.sort(rank[:L]), wl.codes,
+                                       beam_width=beam)
+        xL = oracle.dequantize(cL, wl.codebooks, wl.scales).astype(np.float64)
+        feas.append(np.linalg.norm(xL - x0) / np.linalg.norm(x0) < ratio)
+        moved.append(int((cL != wl.codes).any(-1).sum()))
+    best = max(L for L in range(k_max + 1) if feas[L])
+    assert all(feas[: best + 1]), "change must grow with the prefix"
+    if moved[best] == 0 and best < k_max:
+        # the bound fails before any code has moved: one moved group is kept all the same
+        # (it lies in the chunk the procedure was working on)
+        first = min(L for L in range(k_max + 1) if moved[L] > 0)
+        assert first <= (best // 7 + 1) * 7
+        best = first
+    want, _ = oracle.reencode_groups(T, wl.codebooks, wl.scales, np.sort(rank[:best]), wl.codes,
+                                     beam_width=beam)
+    assert np.array_equal(new, want)
+    xb = oracle.dequantize(new, wl.codebooks, wl.scales).astype(np.float64)
+    assert info["change_sq"] == pytest.approx(np.sum((xb - x0) ** 2), rel=1e-12)
+    assert info["norm_sq"] == pytest.approx(np.sum(x0 ** 2), rel=1e-12)
+
+
+def test_trust_ratio_closed_form_scalar_case():
+    """g = 1, codebook {1, 2}, every weight at 1: a flipped weight changes by exactly 1, so with
+    N = 100 and ratio 0.25 the bound 0.0625 * 100 admits exactly 6 flips (6 < 6.25 < 7)."""
+    N = 100
+    cb = np.array([[[1.0], [2.0]]], dtype=np.float32)
+    scales = np.ones(1, dtype=np.float32)
+    codes = np.zeros((1, N, 1), dtype=np.uint16)
+    W = np.ones((1, N), dtype=np.float32)
+    T = W.copy()
+    movers = [5, 17, 3, 42, 99, 60, 8, 77, 23, 11]           # update sizes decrease in this order
+    for r, n in enumerate(movers):
+        T[0, n] = 1.0 + 0.95 - 0.03 * r                      # all nearer to 2 than to 1
+    T[0, 50] = 1.2                                            # moves, but stays nearest to 1
+    new, info = oracle.reencode_trust_ratio(T, W, cb, scales, codes, k_max=20, chunk=4, ratio=0.25)
+    assert info["num_applied"] == 6
+    assert list(info["rank_idx"][:11]) == movers + [50]
+    flipped = np.nonzero(new[0, :, 0])[0]
+    assert sorted(flipped) == sorted(movers[:6])
+    assert info["change_sq"] == 6.0 and info["norm_sq"] == 100.0
+
+
+@pytest.mark.parametrize("ratio", [0.03, 0.1])
+def test_trust_ratio_does_not_depend_on_the_chunk_size(ratio):
+    wl, T = _tr_case(34, B=6)
+    ref = None
+    for chunk in (1, 3, 7, 16, 50, 1000):
+        new, info = oracle.reencode_trust_ratio(T, wl.W, wl.codebooks, wl.scales, wl.codes, 50,
+                                                chunk=chunk, ratio=ratio)
+        cur = (new.tobytes(), info["num_applied"], info["change_sq"])
+        ref = ref or cur
+        assert cur == ref
+
+
+def test_trust_ratio_limits():
+    wl, T = _tr_case(35, B=6)
+    g = wl.layout.group_size
+    k_max = 40
+    rank = _rank_order(T, wl.W, g, k_max)
+    # no bound: the plain V step on the k_max best groups
+    new, info = oracle.reencode_trust_ratio(T, wl.W, wl.codebooks, wl.scales, wl.codes, k_max,
+                                            chunk=9, ratio=1e30)
+    want, winfo = oracle.reencode_groups(T, wl.codebooks, wl.scales, np.sort(rank), wl.codes)
+    assert info["num_applied"] == k_max and np.array_equal(new, want)
+    # bound zero: exactly one group changes, the first in selection order whose code moves
+    new0, info0 = oracle.reencode_trust_ratio(T, wl.W, wl.codebooks, wl.scales, wl.codes, k_max,
+                                              chunk=9, ratio=0.0)
+    changed = np.nonzero((new0 != wl.codes).any(-1).ravel())[0]
+    moved_in_order = [n for n in rank if (want.reshape(-1, 1)[n] != wl.codes.reshape(-1, 1)[n]).any()]
+    first_chunk = list(rank[:9])
+    if moved_in_order and moved_in_order[0] in first_chunk:
+        assert list(changed) == [moved_in_order[0]]
+        assert info0["num_applied"] == list(rank).index(moved_in_order[0]) + 1
+    else:
+        assert len(changed) == 0 and info0["num_applied"] == 0
+
+
+def test_trust_ratio_bound_is_tight():
+    wl, T = _tr_case(36, B=7, shape=(32, 256))
+    k_max = 100
+    new, info = oracle.reencode_trust_ratio(T, wl.W, wl.codebooks, wl.scales, wl.codes, k_max,
+                                            chunk=10, ratio=0.1)
+    L = info["num_applied"]
+    assert 1 < L < k_max
+    bound = 0.1 ** 2 * info["norm_sq"]
+    assert info["change_sq"] < bound
+    # one more group in selection order breaks the bound
+    nxt = np.sort(info["rank_idx"][: L + 1])
+    c2, _ = oracle.reencode_groups(T, wl.codebooks, wl.scales, nxt, wl.codes)
+    x0 = oracle.dequantize(wl.codes, wl.codebooks, wl.scales).astype(np.float64)
+    x2 = oracle.dequantize(c2, wl.codebooks, wl.scales).astype(np.float64)
+    assert np.sum((x2 - x0) ** 2) >= bound
