@@ -41,6 +41,10 @@ def main() -> int:
                     help="0 = matrix-core filter + exact re-rank, 1 = exact scan only")
     ap.add_argument("--separate-calls", action="store_true",
                     help="pv_encode_targets + pv_select_topk_groups instead of the fused call")
+    ap.add_argument("--path", choices=("vstep", "trust_ratio"), default="vstep",
+                    help="trust_ratio: the subspace size is found by pv_reencode_trust_ratio "
+                         "(W = the dequantised codes, gradient x40 so that codes move, ratio 0.01, "
+                         "all k groups of the workload are candidates)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -76,7 +80,23 @@ def main() -> int:
     idx = torch.empty(k, dtype=torch.int32, device=dev)
     nch = torch.zeros(1, dtype=torch.int64, device=dev)
 
+    if args.path == "trust_ratio":
+        G.mul_(40.0)
+        rank = torch.empty(k, dtype=torch.int32, device=dev)
+        napp = torch.zeros(1, dtype=torch.int64, device=dev)
+        tstats = torch.zeros(2, dtype=torch.float64, device=dev)
+
+    def step_trust():
+        codes.view(torch.int16).copy_(codes0.view(torch.int16))
+        ctx.pv_dequantize(lay, codes, cb, sc, Wq)                 # x^k, also the W of Eq. 7
+        ctx.pv_encode_targets(lay, Wq, G, wl.alpha, T)
+        ctx.pv_reencode_trust_ratio(lay, T, Wq, cb, sc, k, max(1, k // 10), 0.01, wl.beam_width,
+                                    codes, rank, napp, tstats)
+        ctx.pv_dequantize(lay, codes, cb, sc, Wq)
+
     def step():
+        if args.path == "trust_ratio":
+            return step_trust()
         codes.view(torch.int16).copy_(codes0.view(torch.int16))   # same work every step
         ctx.pv_dequantize(lay, codes, cb, sc, Wq)
         if args.separate_calls:
@@ -107,7 +127,7 @@ def main() -> int:
     torch.cuda.synchronize()
     kern = {}
     for name in ("dequantize", "encode_targets", "group_scores", "select", "prep", "score_mfma",
-                 "rerank", "exact_scan", "beam"):
+                 "rerank", "exact_scan", "beam", "trust_ratio"):
         ms, n = ctx.pv_timing_read(name)
         if n:
             kern[name] = {"ms_per_step": ms / args.steps, "launches_per_step": n / args.steps,
@@ -149,7 +169,23 @@ def main() -> int:
             hbm[name + "_GBps"] = per_param * params / (kern[name]["avg_ms"] * 1e-3) / 1e9
 
     cpu = None
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and args.path == "trust_ratio":
+        import oracle
+        t1 = time.perf_counter()
+        Wq_ref = oracle.dequantize(wl.codes, wl.codebooks, wl.scales)
+        T_ref = oracle.encode_targets(Wq_ref, wl.G * np.float32(40.0), wl.alpha)
+        new_ref, tinfo = oracle.reencode_trust_ratio(T_ref, Wq_ref, wl.codebooks, wl.scales, wl.codes,
+                                                     k, max(1, k // 10), 0.01, wl.beam_width)
+        oracle.dequantize(new_ref, wl.codebooks, wl.scales)
+        t2 = time.perf_counter()
+        got = codes.view(torch.int16).cpu().numpy().view(np.uint16)
+        cpu = {"value": k / (t2 - t1), "unit": "groups/s", "cores": oracle.num_threads(),
+               "kind": "oracle",
+               "sample": f"one whole trust-ratio step of {args.workload} ({t2 - t1:.2f} s; the oracle "
+                         f"stops re-encoding at the chunk that breaks the bound, {tinfo['num_applied']} kept)",
+               "codes_equal_oracle": bool(np.array_equal(got, new_ref)),
+               "kept_equal_oracle": int(napp.item()) == tinfo["num_applied"]}
+    elif not args.no_cpu_baseline:
         import oracle
         t1 = time.perf_counter()
         Wq_ref = oracle.dequantize(wl.codes, wl.codebooks, wl.scales)
@@ -182,7 +218,7 @@ def main() -> int:
         "config": {"workload": args.workload, "out_features": L.out_features,
                    "in_features": L.in_features, "group_size": g, "num_codebooks": M, "nbits": B,
                    "tau": wl.tau, "k_selected": k, "beam_width": wl.beam_width,
-                   "search_mode": args.search_mode,
+                   "search_mode": args.search_mode, "path": args.path,
                    "calls": "separate" if args.separate_calls else "fused targets+select"},
         "roofline": roofline,
         "cpu_baseline": cpu,
@@ -193,6 +229,9 @@ def main() -> int:
                                       / PEAK_MFMA_F16 if "score_mfma" in kern else None),
         "hbm": hbm, "kernels": kern, "groups_changed": changed, "reencode_stats": stats,
     }
+    if args.path == "trust_ratio":
+        out["trust_ratio"] = {"ratio": 0.01, "candidates": k, "kept": int(napp.item()),
+                              "change_sq": float(tstats[0].item()), "norm_sq": float(tstats[1].item())}
     print(json.dumps(out))
     return 0
 

@@ -109,6 +109,27 @@ pv_status pv_reencode_groups(pv_ctx *ctx, const pv_layout *layout, const float *
                              const int32_t *group_idx, int64_t k, int32_t beam_width,
                              uint16_t *codes, int64_t *num_changed /* NULL ok */);
 
+/* Subspace size from the trust ratio (Sec. 4.3; App. K, hyperparameter paragraph):
+ * tau is not given but found, as the largest number of weights whose update keeps
+ *     || x^{k+1} - x^k || / || x^k ||  <  ratio          (the paper uses 0.01)
+ * where x is this matrix' dequantised weights.  Candidates are the k_max groups of
+ * pv_select_topk_groups(T, W, k_max), ranked by that rule (largest update norm
+ * first, lower id first).  The paper applies them `chunk` groups at a time and
+ * undoes the tail of the chunk that broke the bound; the result is the longest
+ * ranked prefix that satisfies it, and at least one group whose code moves is kept
+ * (if it lies in the chunk at which the procedure stops).  The comparison is done
+ * on squares in double: sum over kept groups of sum_i (w_new - w_old)^2 <
+ * ratio^2 * sum x^2, with w the fp32 weights of pv_dequantize.
+ * codes: in/out, re-encoded (as by pv_reencode_groups) for the kept groups only.
+ * rank_idx: optional i32 [k_max], receives the candidates in rank order (the kept
+ * ones are its first *num_applied entries).  num_applied: device int64.
+ * stats: optional device f64 [2] = {squared change of the kept groups, ||x^k||^2}. */
+pv_status pv_reencode_trust_ratio(pv_ctx *ctx, const pv_layout *layout, const float *T,
+                                  const float *W, const float *codebooks, const float *scales,
+                                  int64_t k_max, int64_t chunk, double ratio, int32_t beam_width,
+                                  uint16_t *codes, int32_t *rank_idx /* NULL ok */,
+                                  int64_t *num_applied, double *stats /* NULL ok */);
+
 /* Alg. 3 line 1: W_out[o, j*g + i] = scales[o] * sum_m codebooks[m, codes[o,j,m], i]
  * with fp32 additions in codebook order and one fp32 multiply.  Codes are
  * masked to B bits. */
@@ -131,7 +152,8 @@ typedef enum {
     PV_K_EXACT_SCAN = 6,  /* exact scan (fallback list or whole call)       */
     PV_K_BEAM = 7,
     PV_K_DEQUANTIZE = 8,
-    PV_K_COUNT = 9
+    PV_K_TRUST_RATIO = 9, /* norms, ranking, prefix sums, roll-back of pv_reencode_trust_ratio */
+    PV_K_COUNT = 10
 } pv_kernel_id;
 
 /* With timing on, each kernel (group) above is bracketed by HIP events on the

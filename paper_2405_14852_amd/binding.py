@@ -18,7 +18,7 @@ _lib = None
 
 KERNEL_IDS = {
     "encode_targets": 0, "group_scores": 1, "select": 2, "prep": 3, "score_mfma": 4,
-    "rerank": 5, "exact_scan": 6, "beam": 7, "dequantize": 8,
+    "rerank": 5, "exact_scan": 6, "beam": 7, "dequantize": 8, "trust_ratio": 9,
 }
 
 
@@ -75,6 +75,8 @@ def load_library():
     lib.pv_encode_targets_select.argtypes = [vp, lp, vp, vp, f32, vp, i64, vp, vp]
     lib.pv_reencode_groups.argtypes = [vp, lp, vp, vp, vp, vp, i64, i32, vp, vp]
     lib.pv_dequantize.argtypes = [vp, lp, vp, vp, vp, vp]
+    lib.pv_reencode_trust_ratio.argtypes = [vp, lp, vp, vp, vp, vp, i64, i64, ctypes.c_double, i32,
+                                            vp, vp, vp, vp]
     lib.pv_set_search_mode.argtypes = [vp, ctypes.c_int]
     lib.pv_timing_enable.argtypes = [vp, ctypes.c_int]
     lib.pv_timing_reset.argtypes = [vp]
@@ -82,7 +84,7 @@ def load_library():
                                    ctypes.POINTER(i64)]
     lib.pv_reencode_stats.argtypes = [vp, ctypes.POINTER(i64)]
     for name in ("pv_create", "pv_encode_targets", "pv_select_topk_groups",
-                 "pv_encode_targets_select", "pv_reencode_groups",
+                 "pv_encode_targets_select", "pv_reencode_groups", "pv_reencode_trust_ratio",
                  "pv_dequantize", "pv_set_search_mode", "pv_timing_enable", "pv_timing_reset",
                  "pv_timing_read", "pv_reencode_stats"):
         getattr(lib, name).restype = ctypes.c_int
@@ -167,6 +169,19 @@ class PVContext:
             _dev_ptr(group_idx, torch.int32, "group_idx", allow_none=(k == 0)), int(k),
             int(beam_width), _dev_ptr(codes, torch.uint16, "codes"),
             _dev_ptr(num_changed, torch.int64, "num_changed", allow_none=True)))
+
+    def pv_reencode_trust_ratio(self, layout: Layout, T, W, codebooks, scales, k_max: int,
+                                chunk: int, ratio: float, beam_width: int, codes, rank_idx,
+                                num_applied, stats=None):
+        lay = layout.c()
+        self._check(self._lib.pv_reencode_trust_ratio(
+            self._h, ctypes.byref(lay), _dev_ptr(T, torch.float32, "T"),
+            _dev_ptr(W, torch.float32, "W"), _dev_ptr(codebooks, torch.float32, "codebooks"),
+            _dev_ptr(scales, torch.float32, "scales"), int(k_max), int(chunk), float(ratio),
+            int(beam_width), _dev_ptr(codes, torch.uint16, "codes"),
+            _dev_ptr(rank_idx, torch.int32, "rank_idx", allow_none=True),
+            _dev_ptr(num_applied, torch.int64, "num_applied"),
+            _dev_ptr(stats, torch.float64, "stats", allow_none=True)))
 
     def pv_dequantize(self, layout: Layout, codes, codebooks, scales, W_out):
         lay = layout.c()

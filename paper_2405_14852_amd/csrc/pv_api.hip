@@ -123,7 +123,7 @@ extern "C" void pv_destroy(pv_ctx *c)
     (void)hipStreamSynchronize(c->stream);
     pv_buffer *bufs[] = {&c->sel_scores, &c->sel_hist, &c->sel_blocks, &c->sel_state, &c->stats,
                          &c->cb_f16,     &c->cb_meta,  &c->x_f16,      &c->x_meta,    &c->partials,
-                         &c->fb_list,   &c->fb_partial, &c->fb_arrivals, &c->rr_counts};
+                         &c->fb_list,   &c->fb_partial, &c->fb_arrivals, &c->rr_counts, &c->trust};
     for (pv_buffer *b : bufs)
         if (b->ptr) (void)hipFree(b->ptr);
     for (auto &t : c->timers)
@@ -192,14 +192,10 @@ extern "C" pv_status pv_encode_targets_select(pv_ctx *ctx, const pv_layout *l, c
     return pv_launch_select(ctx, l, T, W, k, out_idx, group_scores, G, alpha);
 }
 
-extern "C" pv_status pv_reencode_groups(pv_ctx *ctx, const pv_layout *l, const float *T,
-                                        const float *codebooks, const float *scales,
-                                        const int32_t *group_idx, int64_t k, int32_t beam_width,
-                                        uint16_t *codes, int64_t *num_changed)
+static pv_status check_reencode_args(pv_ctx *ctx, const pv_layout *l, int64_t k,
+                                     int32_t beam_width, const float *T, const float *codebooks,
+                                     const float *scales, const uint16_t *codes)
 {
-    if (!ctx) return PV_ERR_INVALID_ARG;
-    pv_status st = check_layout(ctx, l);
-    if (st != PV_OK) return st;
     int64_t N = pv_num_groups(l);
     if (k < 0 || k > N)
         return pv_fail(ctx, PV_ERR_INVALID_ARG, "k = %lld outside [0, %lld]", (long long)k,
@@ -207,11 +203,9 @@ extern "C" pv_status pv_reencode_groups(pv_ctx *ctx, const pv_layout *l, const f
     if (beam_width < 1) return pv_fail(ctx, PV_ERR_INVALID_ARG, "beam_width must be >= 1");
     if (!T || !codebooks || !scales || !codes)
         return pv_fail(ctx, PV_ERR_INVALID_ARG, "NULL tensor pointer");
-    if (k > 0 && !group_idx) return pv_fail(ctx, PV_ERR_INVALID_ARG, "group_idx is NULL");
     if (misaligned(T) || misaligned(codebooks))
         return pv_fail(ctx, PV_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
-    const int M = l->num_codebooks;
-    if (M > 1) {
+    if (l->num_codebooks > 1) {
         int64_t pool = (int64_t)beam_width << l->nbits;
         if (beam_width > 64 || pool > 4096)
             return pv_fail(ctx, PV_ERR_UNSUPPORTED,
@@ -221,8 +215,16 @@ extern "C" pv_status pv_reencode_groups(pv_ctx *ctx, const pv_layout *l, const f
     } else if (l->group_size > 64) {
         return pv_fail(ctx, PV_ERR_UNSUPPORTED, "nearest-codeword search supports group_size <= 64");
     }
-    PV_HIP(ctx, hipSetDevice(ctx->device));
-    st = pv_ensure(ctx, ctx->stats, 8 * sizeof(int64_t));
+    return PV_OK;
+}
+
+pv_status pv_reencode_dispatch(pv_ctx *ctx, const pv_layout *l, const float *T,
+                               const float *codebooks, const float *scales,
+                               const int32_t *group_idx, int64_t k, int32_t beam_width,
+                               uint16_t *codes, int64_t *num_changed)
+{
+    const int M = l->num_codebooks;
+    pv_status st = pv_ensure(ctx, ctx->stats, 8 * sizeof(int64_t));
     if (st != PV_OK) return st;
     int64_t *stats = static_cast<int64_t *>(ctx->stats.ptr);
     const bool filter = M == 1 && k > 0 && ctx->search_mode == 0 && pv_mfma_supported(l);
@@ -239,6 +241,45 @@ extern "C" pv_status pv_reencode_groups(pv_ctx *ctx, const pv_layout *l, const f
                                      num_changed);
     return pv_launch_exact_scan(ctx, l, T, codebooks, scales, group_idx, nullptr, k, codes,
                                 num_changed, stats + 3);
+}
+
+extern "C" pv_status pv_reencode_groups(pv_ctx *ctx, const pv_layout *l, const float *T,
+                                        const float *codebooks, const float *scales,
+                                        const int32_t *group_idx, int64_t k, int32_t beam_width,
+                                        uint16_t *codes, int64_t *num_changed)
+{
+    if (!ctx) return PV_ERR_INVALID_ARG;
+    pv_status st = check_layout(ctx, l);
+    if (st != PV_OK) return st;
+    st = check_reencode_args(ctx, l, k, beam_width, T, codebooks, scales, codes);
+    if (st != PV_OK) return st;
+    if (k > 0 && !group_idx) return pv_fail(ctx, PV_ERR_INVALID_ARG, "group_idx is NULL");
+    PV_HIP(ctx, hipSetDevice(ctx->device));
+    return pv_reencode_dispatch(ctx, l, T, codebooks, scales, group_idx, k, beam_width, codes,
+                                num_changed);
+}
+
+extern "C" pv_status pv_reencode_trust_ratio(pv_ctx *ctx, const pv_layout *l, const float *T,
+                                             const float *W, const float *codebooks,
+                                             const float *scales, int64_t k_max, int64_t chunk,
+                                             double ratio, int32_t beam_width, uint16_t *codes,
+                                             int32_t *rank_idx, int64_t *num_applied,
+                                             double *stats)
+{
+    if (!ctx) return PV_ERR_INVALID_ARG;
+    pv_status st = check_layout(ctx, l);
+    if (st != PV_OK) return st;
+    st = check_reencode_args(ctx, l, k_max, beam_width, T, codebooks, scales, codes);
+    if (st != PV_OK) return st;
+    if (!W) return pv_fail(ctx, PV_ERR_INVALID_ARG, "NULL tensor pointer");
+    if (misaligned(W)) return pv_fail(ctx, PV_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
+    if (chunk < 1) return pv_fail(ctx, PV_ERR_INVALID_ARG, "chunk must be >= 1");
+    if (!(ratio >= 0.0)) return pv_fail(ctx, PV_ERR_INVALID_ARG, "ratio must be >= 0");
+    if (!num_applied) return pv_fail(ctx, PV_ERR_INVALID_ARG, "num_applied is NULL");
+    if (pv_num_groups(l) == 0) return pv_launch_fill_i64(ctx, num_applied, 1, 0);
+    PV_HIP(ctx, hipSetDevice(ctx->device));
+    return pv_launch_trust_ratio(ctx, l, T, W, codebooks, scales, k_max, chunk, ratio, beam_width,
+                                 codes, rank_idx, num_applied, stats);
 }
 
 extern "C" pv_status pv_dequantize(pv_ctx *ctx, const pv_layout *l, const uint16_t *codes,

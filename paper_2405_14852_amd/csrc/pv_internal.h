@@ -49,6 +49,7 @@ struct pv_ctx {
     pv_buffer fb_partial;   // (f64, i32) [k][pieces]  per-piece minima of the split exact scan
     pv_buffer rr_counts;    // u32 [blocks][3]    per-block counters of the re-rank kernel
     pv_buffer fb_arrivals;  // u32 [k/4]          pieces finished per work item (kept zero between calls)
+    pv_buffer trust;        // scratch of the trust-ratio call (saved codes, keys, prefix sums, sort space)
 };
 
 // RAII bracket that records HIP events around a group of launches when timing is on.
@@ -106,3 +107,12 @@ pv_status pv_launch_mfma_search(pv_ctx *ctx, const pv_layout *l, const float *T,
                                 const int32_t *group_idx, int64_t k, uint16_t *codes,
                                 int64_t *num_changed);
 pv_status pv_launch_fill_i64(pv_ctx *ctx, int64_t *p, int64_t n, int64_t value);
+// the search of pv_reencode_groups after argument validation (k may be 0)
+pv_status pv_reencode_dispatch(pv_ctx *ctx, const pv_layout *l, const float *T,
+                               const float *codebooks, const float *scales,
+                               const int32_t *group_idx, int64_t k, int32_t beam_width,
+                               uint16_t *codes, int64_t *num_changed);
+pv_status pv_launch_trust_ratio(pv_ctx *ctx, const pv_layout *l, const float *T, const float *W,
+                                const float *codebooks, const float *scales, int64_t k_max,
+                                int64_t chunk, double ratio, int32_t beam_width, uint16_t *codes,
+                                int32_t *rank_idx, int64_t *num_applied, double *stats);

@@ -90,3 +90,34 @@ def test_c4_block_matrices_sampled():
         sub = np.sort(np.random.default_rng(7).choice(idx, size=2048, replace=False))
         want, info = oracle.reencode_groups(T_ref, wl.codebooks, wl.scales, sub, wl.codes)
         assert np.array_equal(got.reshape(-1)[sub], want.reshape(-1)[sub]) or info["near_tie"].any()
+
+
+def test_c2_full_trust_ratio():
+    """The trust-ratio call at the benchmark shape, x^k = the dequantised current codes, all
+    20 971 candidates ranked and re-encoded, against the oracle's chunked procedure."""
+    from gpu_util import DEV
+    wl = workloads.make_config("c2_4096x4096_1x16", seed=0)
+    wl.W = oracle.dequantize(wl.codes, wl.codebooks, wl.scales)
+    # a gradient large enough that codes move: the update norm is then comparable to the
+    # distance between neighbouring codewords
+    wl.G = wl.G * np.float32(40.0)
+    T_ref = oracle.encode_targets(wl.W, wl.G, wl.alpha)
+    run = GpuRun(wl)
+    k_max, chunk = wl.k, wl.k // 10
+    for ratio in (0.01, 0.03):
+        codes = run.codes.clone()
+        rank = torch.empty(k_max, dtype=torch.int32, device=DEV)
+        napp = torch.zeros(1, dtype=torch.int64, device=DEV)
+        stats = torch.zeros(2, dtype=torch.float64, device=DEV)
+        run.ctx.pv_reencode_trust_ratio(run.lay, dev_f32(T_ref), run.W, run.cb, run.sc, k_max,
+                                        chunk, ratio, 1, codes, rank, napp, stats)
+        torch.cuda.synchronize()
+        want, info = oracle.reencode_trust_ratio(T_ref, wl.W, wl.codebooks, wl.scales, wl.codes,
+                                                 k_max, chunk, ratio)
+        assert np.array_equal(rank.cpu().numpy(), info["rank_idx"])
+        assert int(napp.item()) == info["num_applied"]
+        assert 1 < info["num_applied"]
+        st = stats.cpu().numpy()
+        assert st[0] == pytest.approx(info["change_sq"], rel=1e-12)
+        assert st[1] == pytest.approx(info["norm_sq"], rel=1e-12)
+        assert np.array_equal(host_u16(codes), want)
