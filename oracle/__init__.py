@@ -44,6 +44,8 @@ def _load():
                                             p, p, p, p, p]
         lib.pvo_group_objective.argtypes = [i64, i64, i32, i32, i32, p, p, p, p, i64, p, p]
         lib.pvo_dequantize.argtypes = [i64, i64, i32, i32, i32, p, p, p, p]
+        lib.pvo_encode_targets_adam.argtypes = [i64, i64, p, p, p, p, i64, f32, f32, f32, f32, p]
+        lib.pvo_encode_targets_adam.restype = ctypes.c_int
         f64 = ctypes.c_double
         lib.pvo_reencode_trust_ratio.argtypes = [i64, i64, i32, i32, i32, p, p, p, p, i64, i64, f64,
                                                  i32, p, p, p, p]
@@ -76,6 +78,21 @@ def encode_targets(W, G, alpha: float) -> np.ndarray:
     if rc:
         raise ValueError("pvo_encode_targets failed")
     return T
+
+
+def encode_targets_adam(W, G, m, v, t: int, lr: float, beta1: float = 0.9, beta2: float = 0.95,
+                        eps: float = 1e-8):
+    """Returns (T, m_new, v_new); the inputs are left untouched."""
+    W, G = _f32(W), _f32(G)
+    m2, v2 = _f32(m).copy(), _f32(v).copy()
+    assert W.shape == G.shape == m2.shape == v2.shape and W.ndim == 2
+    T = np.empty_like(W)
+    rc = _load().pvo_encode_targets_adam(W.shape[0], W.shape[1], _ptr(W), _ptr(G), _ptr(m2), _ptr(v2),
+                                         int(t), float(lr), float(beta1), float(beta2), float(eps),
+                                         _ptr(T))
+    if rc:
+        raise ValueError("pvo_encode_targets_adam failed")
+    return T, m2, v2
 
 
 def select_topk_groups(T, W, group_size: int, k: int, return_scores: bool = False):

@@ -9,6 +9,9 @@
  * What follows the paper exactly, and what is a stated reading of it:
  *   pvo_encode_targets      Eq. 7 (linearised subspace V step): the target is
  *                           y - (1/L) * grad, with alpha = 1/L; Alg. 3 V step.
+ *   pvo_encode_targets_adam Sec. 3.4: the same target with the gradient replaced by one
+ *                           Adam update (pinned by exact rational arithmetic, a library
+ *                           optimiser, the first-step closed form).
  *   pvo_select_topk_groups  Alg. 2 "arg top tau" + Sec. 3.4: largest update
  *                           norm, greedily per weight matrix.  Reading: the
  *                           unit is a weight group (one code covers it).
@@ -63,6 +66,49 @@ int pvo_encode_targets(int64_t out_features, int64_t in_features, const float *W
     int64_t n = out_features * in_features;
 #pragma omp parallel for schedule(static)
     for (int64_t i = 0; i < n; ++i) T[i] = fmaf(-alpha, G[i], W[i]);
+    return PVO_OK;
+}
+
+/* beta^t in double by repeated squaring (a fixed sequence of IEEE multiplications) */
+static double powi(double b, int64_t t)
+{
+    double r = 1.0;
+    while (t > 0) {
+        if (t & 1) r = r * b;
+        b = b * b;
+        t >>= 1;
+    }
+    return r;
+}
+
+/* Sec. 3.4: the gradient of Eq. 7 is replaced by a single Adam update (Kingma & Ba's rule
+ * with bias correction; App. K uses beta1 = 0.9, beta2 = 0.95):
+ *     m <- beta1 m + (1 - beta1) g          v <- beta2 v + (1 - beta2) g^2
+ *     T  = W - lr * (m / (1 - beta1^t)) / (sqrt(v / (1 - beta2^t)) + eps)
+ * All in fp32, one rounding per written operation below, so that the result is
+ * reproducible bit for bit; the two bias corrections are formed in double and rounded to
+ * fp32 once.  m and v are updated in place; t >= 1 is the number of this update. */
+int pvo_encode_targets_adam(int64_t out_features, int64_t in_features, const float *W,
+                            const float *G, float *m, float *v, int64_t t, float lr, float beta1,
+                            float beta2, float eps, float *T)
+{
+    if (!W || !G || !m || !v || !T || out_features < 0 || in_features < 0 || t < 1) return PVO_ERR;
+    const float omb1 = 1.0f - beta1, omb2 = 1.0f - beta2;
+    const float c1 = (float)(1.0 - powi((double)beta1, t));
+    const float c2 = (float)(1.0 - powi((double)beta2, t));
+    int64_t n = out_features * in_features;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < n; ++i) {
+        float g = G[i];
+        float mi = fmaf(beta1, m[i], omb1 * g);
+        float vi = fmaf(beta2, v[i], omb2 * (g * g));
+        float mhat = mi / c1;
+        float vhat = vi / c2;
+        float upd = mhat / (sqrtf(vhat) + eps);
+        m[i] = mi;
+        v[i] = vi;
+        T[i] = fmaf(-lr, upd, W[i]);
+    }
     return PVO_OK;
 }
 

@@ -579,3 +579,101 @@ def test_trust_ratio_bound_is_tight():
     x0 = oracle.dequantize(wl.codes, wl.codebooks, wl.scales).astype(np.float64)
     x2 = oracle.dequantize(c2, wl.codebooks, wl.scales).astype(np.float64)
     assert np.sum((x2 - x0) ** 2) >= bound
+
+
+# ------------------------------------------------- Adam update as the direction (Sec. 3.4)
+
+def _sqrt_f32(fr_val: Fraction) -> np.float32:
+    """Correctly rounded fp32 square root of a non-negative rational (integer arithmetic)."""
+    if fr_val == 0:
+        return np.float32(0.0)
+    import math
+    scale = 1 << 200
+    root = math.isqrt(fr_val.numerator * scale * scale // fr_val.denominator)   # floor(sqrt(x) * 2^200)
+    lo = f32_round(Fraction(root, scale))
+    # candidates around the truncated root; pick the one whose square is nearest in the sense of
+    # |c - sqrt(x)|, decided exactly through the midpoints
+    cands = sorted({lo, np.nextafter(lo, np.float32(np.inf)), np.nextafter(lo, np.float32(0))})
+    best = None
+    for c in cands:
+        err = abs(Fraction(float(c)) - Fraction(root, scale))
+        if best is None or err < best[0]:
+            best = (err, c)
+    return best[1]
+
+
+def _adam_exact(w, g, m, v, t, lr, b1, b2, eps):
+    """The oracle's operation sequence in exact rational arithmetic, rounding where it rounds."""
+    F = Fraction
+    b1f, b2f, lrf, epsf = (F(float(np.float32(x))) for x in (b1, b2, lr, eps))
+    omb1 = f32_round(1 - b1f)
+    omb2 = f32_round(1 - b2f)
+
+    def powi_double(b, n):          # IEEE double multiplications, as the oracle does
+        r, b = 1.0, float(b)
+        while n > 0:
+            if n & 1:
+                r = r * b
+            b = b * b
+            n >>= 1
+        return r
+    c1 = np.float32(1.0 - powi_double(np.float32(b1), t))
+    c2 = np.float32(1.0 - powi_double(np.float32(b2), t))
+    mi = f32_round(b1f * F(float(m)) + F(float(f32_round(F(float(omb1)) * F(float(g))))))
+    g2 = f32_round(F(float(g)) * F(float(g)))
+    vi = f32_round(b2f * F(float(v)) + F(float(f32_round(F(float(omb2)) * F(float(g2))))))
+    mhat = f32_round(F(float(mi)) / F(float(c1)))
+    vhat = f32_round(F(float(vi)) / F(float(c2)))
+    den = f32_round(F(float(_sqrt_f32(F(float(vhat))))) + epsf)
+    upd = f32_round(F(float(mhat)) / F(float(den)))
+    T = f32_round(F(float(w)) - lrf * F(float(upd)))
+    return T, mi, vi
+
+
+@pytest.mark.parametrize("t", [1, 2, 7, 1000])
+def test_adam_targets_exact_rational(t):
+    rng = np.random.default_rng(50 + t)
+    n = 24
+    W = (rng.standard_normal((2, n)) * 0.02).astype(np.float32)
+    G = (rng.standard_normal((2, n)) * 1e-3).astype(np.float32)
+    m = (rng.standard_normal((2, n)) * 1e-3).astype(np.float32) if t > 1 else np.zeros((2, n), np.float32)
+    v = (rng.random((2, n)) * 1e-6).astype(np.float32) if t > 1 else np.zeros((2, n), np.float32)
+    G[0, 0] = 0.0                                  # zero gradient, zero moments at t = 1
+    T, m2, v2 = oracle.encode_targets_adam(W, G, m, v, t, 3e-3, 0.9, 0.95, 1e-8)
+    for idx in np.ndindex(W.shape):
+        want = _adam_exact(W[idx], G[idx], m[idx], v[idx], t, 3e-3, 0.9, 0.95, 1e-8)
+        assert (T[idx], m2[idx], v2[idx]) == want, idx
+
+
+def test_adam_targets_follow_a_library_optimiser():
+    """Five consecutive updates against torch.optim.Adam (same rule, different rounding)."""
+    import torch
+    rng = np.random.default_rng(60)
+    W0 = (rng.standard_normal((8, 32)) * 0.02).astype(np.float32)
+    p = torch.nn.Parameter(torch.from_numpy(W0.copy()))
+    opt = torch.optim.Adam([p], lr=3e-3, betas=(0.9, 0.95), eps=1e-8)
+    W = W0.copy()
+    m = np.zeros_like(W)
+    v = np.zeros_like(W)
+    for t in range(1, 6):
+        G = (rng.standard_normal(W.shape) * 1e-3).astype(np.float32)
+        p.grad = torch.from_numpy(G.copy())
+        opt.step()
+        T, m, v = oracle.encode_targets_adam(W, G, m, v, t, 3e-3, 0.9, 0.95, 1e-8)
+        ref = p.detach().numpy()
+        assert np.allclose(T, ref, rtol=0, atol=3e-3 * 2e-5), t     # a few 1e-5 of one step
+        assert np.abs(T - W).max() > 1e-4                            # the steps are not trivial
+        W = T.copy()
+
+
+def test_adam_first_step_is_a_sign_step():
+    rng = np.random.default_rng(61)
+    W = (rng.standard_normal((4, 16)) * 0.02).astype(np.float32)
+    G = (rng.standard_normal((4, 16)) * 1e-3).astype(np.float32)
+    z = np.zeros_like(W)
+    T, m, v = oracle.encode_targets_adam(W, G, z, z, 1, 1e-2, 0.9, 0.95, 1e-12)
+    assert np.allclose(T, W - 1e-2 * np.sign(G), rtol=0, atol=1e-2 * 1e-5)
+    assert np.allclose(m, 0.1 * G, rtol=1e-6) and np.allclose(v, 0.05 * G * G, rtol=1e-6)
+    # selection then ranks by the size of the Adam update, as Sec. 3.4 prescribes
+    idx = oracle.select_topk_groups(T, W, 8, 3)
+    assert len(idx) == 3
