@@ -45,6 +45,9 @@ def main() -> int:
                     help="trust_ratio: the subspace size is found by pv_reencode_trust_ratio "
                          "(W = the dequantised codes, gradient x40 so that codes move, ratio 0.01, "
                          "all k groups of the workload are candidates)")
+    ap.add_argument("--adam", action="store_true",
+                    help="targets from one Adam update (pv_encode_targets_adam, beta 0.9/0.95, lr 3e-3) "
+                         "followed by pv_select_topk_groups, instead of the plain fused call")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -86,6 +89,10 @@ def main() -> int:
         napp = torch.zeros(1, dtype=torch.int64, device=dev)
         tstats = torch.zeros(2, dtype=torch.float64, device=dev)
 
+    m_adam = torch.zeros_like(W) if args.adam else None
+    v_adam = torch.zeros_like(W) if args.adam else None
+    adam_step = [0]
+
     def step_trust():
         codes.view(torch.int16).copy_(codes0.view(torch.int16))
         ctx.pv_dequantize(lay, codes, cb, sc, Wq)                 # x^k, also the W of Eq. 7
@@ -99,7 +106,12 @@ def main() -> int:
             return step_trust()
         codes.view(torch.int16).copy_(codes0.view(torch.int16))   # same work every step
         ctx.pv_dequantize(lay, codes, cb, sc, Wq)
-        if args.separate_calls:
+        if args.adam:
+            adam_step[0] += 1
+            ctx.pv_encode_targets_adam(lay, W, G, m_adam, v_adam, adam_step[0], 3e-3, 0.9, 0.95,
+                                       1e-8, T)
+            ctx.pv_select_topk_groups(lay, T, W, k, idx)
+        elif args.separate_calls:
             ctx.pv_encode_targets(lay, W, G, wl.alpha, T)
             ctx.pv_select_topk_groups(lay, T, W, k, idx)
         else:   # same outputs, T and W are not read back for the scores
@@ -154,7 +166,7 @@ def main() -> int:
         roofline = {"kernel": "k_" + dominant, "bound": "alu", "achieved": a, "peak": PEAK_F64,
                     "unit": "TFLOP/s", "frac": a / PEAK_F64, "traffic": None}
     else:
-        per_param = {"encode_targets": 12.0 + (0.0 if args.separate_calls else 4.0 / g),
+        per_param = {"encode_targets": 28.0 if args.adam else 12.0 + (0.0 if args.separate_calls else 4.0 / g),
                      "group_scores": 8.0 + 4.0 / g,
                      "dequantize": 4.0 + 2.0 * M / g}.get(dominant, 0.0)
         a = per_param * params / (kern[dominant]["avg_ms"] * 1e-3) / 1e9
@@ -162,7 +174,7 @@ def main() -> int:
                     "unit": "GB/s", "frac": a / PEAK_HBM, "traffic": None}
 
     hbm = {}
-    for name, per_param in (("encode_targets", 12.0 + (0.0 if args.separate_calls else 4.0 / g)),
+    for name, per_param in (("encode_targets", 28.0 if args.adam else 12.0 + (0.0 if args.separate_calls else 4.0 / g)),
                             ("group_scores", 8.0 + 4.0 / g),
                             ("dequantize", 4.0 + 2.0 * M / g)):
         if name in kern:
@@ -185,7 +197,7 @@ def main() -> int:
                          f"stops re-encoding at the chunk that breaks the bound, {tinfo['num_applied']} kept)",
                "codes_equal_oracle": bool(np.array_equal(got, new_ref)),
                "kept_equal_oracle": int(napp.item()) == tinfo["num_applied"]}
-    elif not args.no_cpu_baseline:
+    elif not args.no_cpu_baseline and not args.adam:
         import oracle
         t1 = time.perf_counter()
         Wq_ref = oracle.dequantize(wl.codes, wl.codebooks, wl.scales)
@@ -219,7 +231,8 @@ def main() -> int:
                    "in_features": L.in_features, "group_size": g, "num_codebooks": M, "nbits": B,
                    "tau": wl.tau, "k_selected": k, "beam_width": wl.beam_width,
                    "search_mode": args.search_mode, "path": args.path,
-                   "calls": "separate" if args.separate_calls else "fused targets+select"},
+                   "calls": "adam targets + select" if args.adam else
+                            "separate" if args.separate_calls else "fused targets+select"},
         "roofline": roofline,
         "cpu_baseline": cpu,
         "reencode_only_groups_per_s": k / (reenc_ms * 1e-3) if reenc_ms else None,

@@ -65,6 +65,20 @@ const char *pv_last_error(const pv_ctx *ctx);
 pv_status pv_encode_targets(pv_ctx *ctx, const pv_layout *layout, const float *W,
                             const float *G, float alpha, float *T);
 
+/* Sec. 3.4: Eq. 7 with the gradient replaced by a single Adam update (Kingma & Ba's rule
+ * with bias correction; App. K uses beta1 = 0.9, beta2 = 0.95):
+ *     m <- beta1 m + (1 - beta1) G,   v <- beta2 v + (1 - beta2) G^2     (in place)
+ *     T  = W - lr * (m / (1 - beta1^step)) / (sqrt(v / (1 - beta2^step)) + eps)
+ * elementwise in fp32: m' = fma(beta1, m, (1-beta1)*G), v' = fma(beta2, v, (1-beta2)*(G*G)),
+ * two divisions by the bias corrections (formed in double, rounded to fp32 once), a correctly
+ * rounded square root and division, T = fma(-lr, update, W).  step >= 1 counts the updates.
+ * W, G, T and the moments m, v: f32 [out_features, in_features]; T may alias W or G exactly;
+ * T, m, v must be distinct.  Selecting on ||T - W|| afterwards ranks groups by the size of
+ * their Adam update, as Sec. 3.4 prescribes. */
+pv_status pv_encode_targets_adam(pv_ctx *ctx, const pv_layout *layout, const float *W,
+                                 const float *G, float *m, float *v, int64_t step, float lr,
+                                 float beta1, float beta2, float eps, float *T);
+
 /* Alg. 2 line 5 ("arg top tau") with Sec. 3.4's rule (largest update norm, per
  * weight matrix), applied to weight groups: score_n = sum_i (T[n,i] - W[n,i])^2
  * accumulated in fp32 in index order with fused multiply-adds; the k groups with

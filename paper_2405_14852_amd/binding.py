@@ -71,6 +71,7 @@ def load_library():
     lib.pv_last_error.argtypes = [vp]
     lib.pv_last_error.restype = ctypes.c_char_p
     lib.pv_encode_targets.argtypes = [vp, lp, vp, vp, f32, vp]
+    lib.pv_encode_targets_adam.argtypes = [vp, lp, vp, vp, vp, vp, i64, f32, f32, f32, f32, vp]
     lib.pv_select_topk_groups.argtypes = [vp, lp, vp, vp, i64, vp, vp]
     lib.pv_encode_targets_select.argtypes = [vp, lp, vp, vp, f32, vp, i64, vp, vp]
     lib.pv_reencode_groups.argtypes = [vp, lp, vp, vp, vp, vp, i64, i32, vp, vp]
@@ -83,7 +84,7 @@ def load_library():
     lib.pv_timing_read.argtypes = [vp, ctypes.c_int, ctypes.POINTER(ctypes.c_double),
                                    ctypes.POINTER(i64)]
     lib.pv_reencode_stats.argtypes = [vp, ctypes.POINTER(i64)]
-    for name in ("pv_create", "pv_encode_targets", "pv_select_topk_groups",
+    for name in ("pv_create", "pv_encode_targets", "pv_encode_targets_adam", "pv_select_topk_groups",
                  "pv_encode_targets_select", "pv_reencode_groups", "pv_reencode_trust_ratio",
                  "pv_dequantize", "pv_set_search_mode", "pv_timing_enable", "pv_timing_reset",
                  "pv_timing_read", "pv_reencode_stats"):
@@ -141,6 +142,15 @@ class PVContext:
         self._check(self._lib.pv_encode_targets(
             self._h, ctypes.byref(lay), _dev_ptr(W, torch.float32, "W"),
             _dev_ptr(G, torch.float32, "G"), float(alpha), _dev_ptr(T, torch.float32, "T")))
+
+    def pv_encode_targets_adam(self, layout: Layout, W, G, m, v, step: int, lr: float,
+                               beta1: float, beta2: float, eps: float, T):
+        lay = layout.c()
+        self._check(self._lib.pv_encode_targets_adam(
+            self._h, ctypes.byref(lay), _dev_ptr(W, torch.float32, "W"),
+            _dev_ptr(G, torch.float32, "G"), _dev_ptr(m, torch.float32, "m"),
+            _dev_ptr(v, torch.float32, "v"), int(step), float(lr), float(beta1), float(beta2),
+            float(eps), _dev_ptr(T, torch.float32, "T")))
 
     def pv_select_topk_groups(self, layout: Layout, T, W, k: int, out_idx, group_scores=None):
         lay = layout.c()

@@ -151,6 +151,27 @@ extern "C" pv_status pv_encode_targets(pv_ctx *ctx, const pv_layout *l, const fl
     return pv_launch_encode_targets(ctx, W, G, alpha, T, n);
 }
 
+extern "C" pv_status pv_encode_targets_adam(pv_ctx *ctx, const pv_layout *l, const float *W,
+                                            const float *G, float *m, float *v, int64_t step,
+                                            float lr, float beta1, float beta2, float eps, float *T)
+{
+    if (!ctx) return PV_ERR_INVALID_ARG;
+    pv_status st = check_layout(ctx, l);
+    if (st != PV_OK) return st;
+    if (!W || !G || !m || !v || !T) return pv_fail(ctx, PV_ERR_INVALID_ARG, "NULL tensor pointer");
+    if (misaligned(W) || misaligned(G) || misaligned(m) || misaligned(v) || misaligned(T))
+        return pv_fail(ctx, PV_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
+    if (step < 1) return pv_fail(ctx, PV_ERR_INVALID_ARG, "step must be >= 1");
+    if (!(beta1 >= 0.0f && beta1 < 1.0f) || !(beta2 >= 0.0f && beta2 < 1.0f))
+        return pv_fail(ctx, PV_ERR_INVALID_ARG, "beta1 and beta2 must lie in [0, 1)");
+    if (T == (float *)m || T == (float *)v || m == v)
+        return pv_fail(ctx, PV_ERR_INVALID_ARG, "T, m and v must be distinct buffers");
+    int64_t n = l->out_features * l->in_features;
+    if (n == 0) return PV_OK;
+    PV_HIP(ctx, hipSetDevice(ctx->device));
+    return pv_launch_encode_targets_adam(ctx, W, G, m, v, step, lr, beta1, beta2, eps, T, n);
+}
+
 extern "C" pv_status pv_select_topk_groups(pv_ctx *ctx, const pv_layout *l, const float *T,
                                            const float *W, int64_t k, int32_t *out_idx,
                                            float *group_scores)

@@ -81,6 +81,9 @@ static inline int64_t pv_num_groups(const pv_layout *l)
 
 pv_status pv_launch_encode_targets(pv_ctx *ctx, const float *W, const float *G, float alpha,
                                    float *T, int64_t n);
+pv_status pv_launch_encode_targets_adam(pv_ctx *ctx, const float *W, const float *G, float *m,
+                                        float *v, int64_t step, float lr, float beta1, float beta2,
+                                        float eps, float *T, int64_t n);
 pv_status pv_launch_dequantize(pv_ctx *ctx, const pv_layout *l, const uint16_t *codes,
                                const float *codebooks, const float *scales, float *W_out);
 pv_status pv_launch_select(pv_ctx *ctx, const pv_layout *l, const float *T, const float *W,

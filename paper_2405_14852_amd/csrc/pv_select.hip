@@ -12,13 +12,20 @@
 // [per-chunk counts] [ordered write].  Digit 0 (sign, exponent, two mantissa
 // bits) is counted in an LDS histogram inside the streaming score kernel, whose
 // blocks are persistent so that clearing and flushing it is paid once per block;
-// the later digits see only the few per cent of keys that share the chosen
-// digit 0 and go to global memory directly.  Each launch resolves the digit of
-// the histogram before it and publishes it for the launches that follow.
+// the later digits usually see only the few per cent of keys that share the
+// chosen digit 0, but a narrow score distribution (updates of one size, as an
+// optimiser's sign-like step produces) sends nearly all keys there, so they are
+// counted in per-block LDS histograms as well, with wave-wide merging of the
+// leading bin.  Each launch resolves the digit of the histogram before it and
+// publishes it for the launches that follow.
 #include "pv_internal.h"
 
 #ifndef PV_VOTE_ROUNDS
 #define PV_VOTE_ROUNDS 1   // wave-wide merges before per-lane LDS atomics (guards degenerate inputs)
+#endif
+
+#ifndef PV_LATE_VOTE_ROUNDS
+#define PV_LATE_VOTE_ROUNDS 1   // the same for the later digits
 #endif
 
 namespace {
@@ -135,24 +142,6 @@ __device__ __forceinline__ void flush_hist(const unsigned *lh, unsigned *__restr
         unsigned v = lh[b];
         if (v) atomicAdd(&gh[hist_slot(b, bins)], v);
     }
-}
-
-// One count per valid lane straight into a global histogram (few candidates
-// reach the later digits).  One merge round keeps a degenerate input (all keys
-// equal) from serialising on a single address.
-__device__ __forceinline__ void global_hist_add(unsigned *__restrict__ gh, int bin, int bins,
-                                                bool valid)
-{
-    const int lane = threadIdx.x & 63;
-    unsigned long long todo = __ballot(valid);
-    if (todo) {
-        int leader = __ffsll((long long)todo) - 1;
-        int lb = __shfl(bin, leader);
-        unsigned long long same = __ballot(valid && bin == lb);
-        if (lane == leader) atomicAdd(&gh[hist_slot(lb, bins)], (unsigned)__popcll(same));
-        if (valid && bin == lb) valid = false;
-    }
-    if (valid) atomicAdd(&gh[hist_slot(bin, bins)], 1u);
 }
 
 __device__ __forceinline__ float score_group(const float *__restrict__ t,
@@ -360,6 +349,7 @@ __global__ __launch_bounds__(kBlock) void k_hist_next(const float *__restrict__ 
                                                       unsigned k, int pass)
 {
     __shared__ unsigned tmp[kBlock + 2];
+    __shared__ unsigned lh[kBins];
     const int bins = pass == 1 ? kBins : kLastBins;
     int d0, d1 = 0;
     unsigned kk;
@@ -377,6 +367,11 @@ __global__ __launch_bounds__(kBlock) void k_hist_next(const float *__restrict__ 
             state[7] = kk;
         }
     }
+    // Per-block histogram in LDS, flushed once: a narrow score distribution (all updates of
+    // one size, as after a sign-like optimiser step) puts most keys into a few bins, and that
+    // many atomics on a few global addresses would serialise.
+    for (int b = threadIdx.x; b < bins; b += kBlock) lh[b] = 0;
+    __syncthreads();
     const pv_f4 *s4 = reinterpret_cast<const pv_f4 *>(scores);
     const int64_t n4 = N >> 2;
     const int64_t stride = (int64_t)gridDim.x * kBlock;
@@ -388,14 +383,16 @@ __global__ __launch_bounds__(kBlock) void k_hist_next(const float *__restrict__ 
         for (int e = 0; e < 4; ++e) {
             unsigned key = __float_as_uint(v[e]);
             bool valid = i < n4 && digit_of(key, 0) == d0 && (pass == 1 || digit_of(key, 1) == d1);
-            if (__ballot(valid)) global_hist_add(hist_out, digit_of(key, pass), bins, valid);
+            if (__ballot(valid)) hist_add<PV_LATE_VOTE_ROUNDS>(lh, digit_of(key, pass), valid);
         }
     }
     if (blockIdx.x == 0 && (int)threadIdx.x < (N & 3)) {
         unsigned key = __float_as_uint(scores[(n4 << 2) + threadIdx.x]);
         if (digit_of(key, 0) == d0 && (pass == 1 || digit_of(key, 1) == d1))
-            atomicAdd(&hist_out[hist_slot(digit_of(key, pass), bins)], 1u);
+            atomicAdd(&lh[digit_of(key, pass)], 1u);
     }
+    __syncthreads();
+    flush_hist(lh, hist_out, bins);
 }
 
 __device__ __forceinline__ unsigned block_sum(unsigned v, unsigned *tmp)

@@ -58,6 +58,60 @@ def test_encode_targets_in_place():
     assert np.array_equal(W.cpu().numpy(), ref)
 
 
+# ------------------------------------------ targets from an Adam update (Sec. 3.4)
+
+@pytest.mark.parametrize("shape,g", [((3, 6), 2), ((256, 256), 8), ((37, 1048), 8), ((1, 4), 1),
+                                     ((129, 4100), 4), ((5, 7), 7)])
+@pytest.mark.parametrize("step,lr,eps", [(1, 3e-3, 1e-8), (2, 1e-2, 1e-8), (1000, 3e-4, 1e-6)])
+def test_encode_targets_adam_bit_exact(shape, g, step, lr, eps):
+    wl = workloads.make(shape[0], shape[1], g, 1, 4, seed=21, sigma_g=1e-3)
+    rng = np.random.default_rng(21)
+    m = (rng.standard_normal(shape) * 1e-3).astype(np.float32) if step > 1 else np.zeros(shape, np.float32)
+    v = (rng.random(shape) * 1e-6).astype(np.float32) if step > 1 else np.zeros(shape, np.float32)
+    G = wl.G.copy()
+    G.ravel()[::7] = 0.0                          # zero gradients among the rest
+    if step > 1:
+        v.ravel()[::11] = 1e-42                   # subnormal second moments
+    run = GpuRun(wl)
+    md, vd, Gd = dev_f32(m), dev_f32(v), dev_f32(G)
+    T = torch.empty_like(run.W)
+    run.ctx.pv_encode_targets_adam(run.lay, run.W, Gd, md, vd, step, lr, 0.9, 0.95, eps, T)
+    torch.cuda.synchronize()
+    T_ref, m_ref, v_ref = oracle.encode_targets_adam(wl.W, G, m, v, step, lr, 0.9, 0.95, eps)
+    assert np.array_equal(T.cpu().numpy().view(np.uint32), T_ref.view(np.uint32))
+    assert np.array_equal(md.cpu().numpy().view(np.uint32), m_ref.view(np.uint32))
+    assert np.array_equal(vd.cpu().numpy().view(np.uint32), v_ref.view(np.uint32))
+
+
+def test_encode_targets_adam_sequence_in_place_and_errors():
+    """Five updates in a row, T written over the gradient buffer, then selection on the result."""
+    from paper_2405_14852_amd import PVError
+    wl = workloads.make(64, 512, 8, 1, 4, seed=22, sigma_g=1e-3)
+    run = GpuRun(wl)
+    rng = np.random.default_rng(22)
+    m = np.zeros_like(wl.W)
+    v = np.zeros_like(wl.W)
+    md, vd = dev_f32(m), dev_f32(v)
+    for step in range(1, 6):
+        G = (rng.standard_normal(wl.W.shape) * 1e-3).astype(np.float32)
+        Gd = dev_f32(G)
+        run.ctx.pv_encode_targets_adam(run.lay, run.W, Gd, md, vd, step, 3e-3, 0.9, 0.95, 1e-8, Gd)
+        T_ref, m, v = oracle.encode_targets_adam(wl.W, G, m, v, step, 3e-3)
+        assert np.array_equal(Gd.cpu().numpy(), T_ref), step
+    assert np.array_equal(md.cpu().numpy(), m) and np.array_equal(vd.cpu().numpy(), v)
+    idx = run.select(Gd, 50)
+    assert np.array_equal(idx, oracle.select_topk_groups(T_ref, wl.W, 8, 50))
+    T = torch.empty_like(run.W)
+    for bad in (dict(step=0), dict(beta1=1.0), dict(beta2=-0.1)):
+        kw = dict(step=1, lr=1e-3, beta1=0.9, beta2=0.95, eps=1e-8)
+        kw.update(bad)
+        with pytest.raises(PVError):
+            run.ctx.pv_encode_targets_adam(run.lay, run.W, Gd, md, vd, kw["step"], kw["lr"],
+                                           kw["beta1"], kw["beta2"], kw["eps"], T)
+    with pytest.raises(PVError):
+        run.ctx.pv_encode_targets_adam(run.lay, run.W, Gd, md, md, 1, 1e-3, 0.9, 0.95, 1e-8, T)
+
+
 # --------------------------------------------------------------- dequantize
 
 @pytest.mark.parametrize("g,M,B", [(8, 1, 8), (8, 2, 8), (16, 1, 12), (8, 1, 16), (2, 1, 3),
