@@ -46,6 +46,8 @@ def _load():
         lib.pvo_dequantize.argtypes = [i64, i64, i32, i32, i32, p, p, p, p]
         lib.pvo_encode_targets_adam.argtypes = [i64, i64, p, p, p, p, i64, f32, f32, f32, f32, p]
         lib.pvo_encode_targets_adam.restype = ctypes.c_int
+        lib.pvo_codebook_grads.argtypes = [i64, i64, i32, i32, i32, p, p, p, p, p, p]
+        lib.pvo_codebook_grads.restype = ctypes.c_int
         f64 = ctypes.c_double
         lib.pvo_reencode_trust_ratio.argtypes = [i64, i64, i32, i32, i32, p, p, p, p, i64, i64, f64,
                                                  i32, p, p, p, p]
@@ -159,6 +161,25 @@ def reencode_trust_ratio(T, W, codebooks, scales, codes, k_max: int, chunk: int,
         raise ValueError("pvo_reencode_trust_ratio failed")
     return new, {"rank_idx": rank[:k_max], "num_applied": int(applied.value),
                  "change_sq": float(stats[0]), "norm_sq": float(stats[1])}
+
+
+def codebook_grads(G, codes, codebooks, scales):
+    """Returns (grad_codebooks f32 [M, 2^B, g], grad_scales f32 [out])."""
+    G = _f32(G)
+    cb = _f32(codebooks)
+    sc = _f32(scales)
+    M, csize, g = cb.shape
+    B = int(csize).bit_length() - 1
+    codes = np.ascontiguousarray(codes, dtype=np.uint16)
+    out_f, in_f = G.shape
+    assert codes.shape == (out_f, in_f // g, M)
+    gc = np.empty_like(cb)
+    gs = np.empty(out_f, dtype=np.float32)
+    rc = _load().pvo_codebook_grads(out_f, in_f, g, M, B, _ptr(G), _ptr(codes), _ptr(cb), _ptr(sc),
+                                    _ptr(gc), _ptr(gs))
+    if rc:
+        raise ValueError("pvo_codebook_grads failed")
+    return gc, gs
 
 
 def group_objective(T, codebooks, scales, group_idx, tuples) -> np.ndarray:

@@ -33,6 +33,9 @@
  *                           single-index descent (App. D).  Beyond those bounds
  *                           the beam result is PARITY UNPINNED.
  *   pvo_dequantize          Alg. 3 line 1: W = scale_row * sum_m codeword_m.
+ *   pvo_codebook_grads      Alg. 3 P step: chain rule through the dequantiser (pinned by
+ *                           automatic differentiation of an independent dequantiser and by
+ *                           finite differences of a quadratic loss).
  *   pvo_reencode_trust_ratio  Sec. 4.3 / App. K: subspace size from the trust ratio,
  *                           the chunked procedure of App. K step by step (pinned by
  *                           brute force over all prefix lengths, a closed-form case,
@@ -507,6 +510,55 @@ int pvo_reencode_trust_ratio(int64_t out_features, int64_t in_features, int g, i
     free(saved);
     free(prefix);
     return rc;
+}
+
+/* ------------------------------------------------------------ P-step gradients */
+
+/* The P step updates the continuous parameters "by backprop" (Alg. 3, P step; Sec. 3.1:
+ * the c-dimensional gradient over the distinct values; App. K: codebooks and per-channel
+ * scales).  With W[o, j*g + i] = s_o * sum_m C_m[b(o,j,m), i] and G = d phi / d W the chain
+ * rule gives
+ *     d phi / d C_m[c, i] = sum over groups n = (o, j) with b(o,j,m) = c of  s_o * G[o, j*g + i]
+ *     d phi / d s_o       = sum_j sum_i G[o, j*g + i] * (C_0[b_0, i] + C_1[b_1, i] + ...)
+ * Products are formed in double (exact for fp32 factors), sums run in double in ascending
+ * group / index order, results are rounded to fp32 once.  The inner codeword sum of the
+ * scale gradient is the fp32 chain of pvo_dequantize (without the scale). */
+int pvo_codebook_grads(int64_t out_features, int64_t in_features, int g, int M, int B,
+                       const float *G, const uint16_t *codes, const float *codebooks,
+                       const float *scales, float *grad_codebooks /* [M, 2^B, g] */,
+                       float *grad_scales /* [out] or NULL */)
+{
+    if (!G || !codes || !codebooks || !scales || !grad_codebooks) return PVO_ERR;
+    if (g < 1 || in_features % g || M < 1 || B < 1 || B > 16) return PVO_ERR;
+    int64_t gpr = in_features / g, N = out_features * gpr, csize = (int64_t)1 << B;
+    double *acc = (double *)calloc((size_t)(M * csize * g), sizeof(double));
+    if (!acc) return PVO_ERR;
+    for (int64_t n = 0; n < N; ++n) {
+        double s = (double)scales[n / gpr];
+        for (int m = 0; m < M; ++m) {
+            int64_t c = codes[n * M + m];
+            if (c >= csize) { free(acc); return PVO_ERR; }
+            double *row = acc + ((int64_t)m * csize + c) * g;
+            for (int i = 0; i < g; ++i) row[i] = row[i] + s * (double)G[n * g + i];
+        }
+    }
+    for (int64_t e = 0; e < (int64_t)M * csize * g; ++e) grad_codebooks[e] = (float)acc[e];
+    free(acc);
+    if (grad_scales)
+        for (int64_t o = 0; o < out_features; ++o) {
+            double a = 0.0;
+            for (int64_t j = 0; j < gpr; ++j) {
+                int64_t n = o * gpr + j;
+                for (int i = 0; i < g; ++i) {
+                    float q = codebooks[((int64_t)0 * csize + codes[n * M]) * g + i];
+                    for (int m = 1; m < M; ++m)
+                        q = q + codebooks[((int64_t)m * csize + codes[n * M + m]) * g + i];
+                    a = a + (double)G[n * g + i] * (double)q;
+                }
+            }
+            grad_scales[o] = (float)a;
+        }
+    return PVO_OK;
 }
 
 int pvo_num_threads(void)

@@ -677,3 +677,74 @@ def test_adam_first_step_is_a_sign_step():
     # selection then ranks by the size of the Adam update, as Sec. 3.4 prescribes
     idx = oracle.select_topk_groups(T, W, 8, 3)
     assert len(idx) == 3
+
+
+# ------------------------------------------------ P-step gradients (Alg. 3, P step)
+
+def _torch_dequantize(codes, cb, sc):
+    """An independent dequantiser written with torch indexing (float64, differentiable)."""
+    import torch
+    M = cb.shape[0]
+    idx = torch.from_numpy(codes.astype(np.int64))
+    w = sum(cb[m][idx[..., m]] for m in range(M))            # [out, in/g, g]
+    return (sc[:, None, None] * w).reshape(codes.shape[0], -1)
+
+
+@pytest.mark.parametrize("g,M,B,shape", [(8, 1, 4, (12, 64)), (4, 2, 3, (9, 40)), (1, 1, 2, (5, 7)),
+                                         (8, 3, 2, (6, 32))])
+def test_codebook_grads_equal_automatic_differentiation(g, M, B, shape):
+    import torch
+    wl = workloads.make(shape[0], shape[1], g, M, B, seed=70, sigma_g=1e-2)
+    cb = torch.tensor(wl.codebooks, dtype=torch.float64, requires_grad=True)
+    sc = torch.tensor(wl.scales, dtype=torch.float64, requires_grad=True)
+    W = _torch_dequantize(wl.codes, cb, sc)
+    (W * torch.from_numpy(wl.G.astype(np.float64))).sum().backward()   # d/dW of <G, W> is G
+    gc, gs = oracle.codebook_grads(wl.G, wl.codes, wl.codebooks, wl.scales)
+    assert np.allclose(gc, cb.grad.numpy(), rtol=1e-6, atol=1e-9)
+    assert np.allclose(gs, sc.grad.numpy(), rtol=1e-6, atol=1e-9)
+    # codewords nobody uses get exactly zero
+    used = np.zeros((M, 1 << B), bool)
+    for m in range(M):
+        used[m, np.unique(wl.codes[..., m])] = True
+    assert (gc[~used] == 0).all()
+
+
+def test_codebook_grads_by_finite_differences_of_a_quadratic_loss():
+    """phi(W) = 0.5 ||W - Z||^2 has dphi/dW = W - Z; central differences in double are exact for
+    a quadratic up to rounding."""
+    wl = workloads.make(6, 32, 8, 2, 3, seed=71)
+    Z = wl.W.astype(np.float64)
+    cb0, sc0 = wl.codebooks.astype(np.float64), wl.scales.astype(np.float64)
+
+    def deq(cb, sc):
+        w = sum(cb[m][wl.codes[..., m].astype(np.int64)] for m in range(cb.shape[0]))
+        return (sc[:, None, None] * w).reshape(6, 32)
+
+    def phi(cb, sc):
+        return 0.5 * np.sum((deq(cb, sc) - Z) ** 2)
+    G = (deq(cb0, sc0) - Z).astype(np.float32)
+    gc, gs = oracle.codebook_grads(G, wl.codes, wl.codebooks, wl.scales)
+    h = 1e-4
+    rng = np.random.default_rng(71)
+    for _ in range(25):
+        m, c, i = rng.integers(2), rng.integers(8), rng.integers(8)
+        e = np.zeros_like(cb0)
+        e[m, c, i] = h
+        fd = (phi(cb0 + e, sc0) - phi(cb0 - e, sc0)) / (2 * h)
+        assert gc[m, c, i] == pytest.approx(fd, rel=1e-4, abs=1e-7)
+    for o in range(6):
+        e = np.zeros_like(sc0)
+        e[o] = h
+        fd = (phi(cb0, sc0 + e) - phi(cb0, sc0 - e)) / (2 * h)
+        assert gs[o] == pytest.approx(fd, rel=1e-4, abs=1e-7)
+
+
+def test_codebook_grads_exact_small_case():
+    """One row, scale 2, codes [1, 0, 1]: dC[1] = 2 (G_0 + G_2), dC[0] = 2 G_1, ds = <G, q>."""
+    cb = np.array([[[1.0, -1.0], [0.5, 4.0]]], dtype=np.float32)
+    codes = np.array([[[1], [0], [1]]], dtype=np.uint16)
+    G = np.array([[1.0, 2.0, 3.0, 4.0, 5.0, 6.0]], dtype=np.float32)
+    gc, gs = oracle.codebook_grads(G, codes, cb, np.array([2.0], np.float32))
+    assert np.array_equal(gc[0, 1], [2 * (1 + 5), 2 * (2 + 6)])
+    assert np.array_equal(gc[0, 0], [2 * 3, 2 * 4])
+    assert gs[0] == 1 * 0.5 + 2 * 4 + 3 * 1 + 4 * -1 + 5 * 0.5 + 6 * 4
