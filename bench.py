@@ -41,10 +41,11 @@ def main() -> int:
                     help="0 = matrix-core filter + exact re-rank, 1 = exact scan only")
     ap.add_argument("--separate-calls", action="store_true",
                     help="pv_encode_targets + pv_select_topk_groups instead of the fused call")
-    ap.add_argument("--path", choices=("vstep", "trust_ratio"), default="vstep",
+    ap.add_argument("--path", choices=("vstep", "trust_ratio", "pstep"), default="vstep",
                     help="trust_ratio: the subspace size is found by pv_reencode_trust_ratio "
                          "(W = the dequantised codes, gradient x40 so that codes move, ratio 0.01, "
-                         "all k groups of the workload are candidates)")
+                         "all k groups of the workload are candidates); pstep: one call of "
+                         "pv_codebook_grads (gradients of codebooks and scales) per step")
     ap.add_argument("--adam", action="store_true",
                     help="targets from one Adam update (pv_encode_targets_adam, beta 0.9/0.95, lr 3e-3) "
                          "followed by pv_select_topk_groups, instead of the plain fused call")
@@ -101,9 +102,15 @@ def main() -> int:
                                     codes, rank, napp, tstats)
         ctx.pv_dequantize(lay, codes, cb, sc, Wq)
 
+    if args.path == "pstep":
+        gcb = torch.empty_like(cb)
+        gsc = torch.empty_like(sc)
+
     def step():
         if args.path == "trust_ratio":
             return step_trust()
+        if args.path == "pstep":
+            return ctx.pv_codebook_grads(lay, G, codes0, cb, sc, gcb, gsc)
         codes.view(torch.int16).copy_(codes0.view(torch.int16))   # same work every step
         ctx.pv_dequantize(lay, codes, cb, sc, Wq)
         if args.adam:
@@ -139,7 +146,7 @@ def main() -> int:
     torch.cuda.synchronize()
     kern = {}
     for name in ("dequantize", "encode_targets", "group_scores", "select", "prep", "score_mfma",
-                 "rerank", "exact_scan", "beam", "trust_ratio"):
+                 "rerank", "exact_scan", "beam", "trust_ratio", "pstep"):
         ms, n = ctx.pv_timing_read(name)
         if n:
             kern[name] = {"ms_per_step": ms / args.steps, "launches_per_step": n / args.steps,
@@ -153,7 +160,14 @@ def main() -> int:
     dominant = max(kern, key=lambda n: kern[n]["ms_per_step"])
     flops_contraction = 2.0 * k * (1 << B) * g * M            # algorithmic: 2*g*2^B per group
     roofline = None
-    if dominant == "score_mfma":
+    if args.path == "pstep":
+        # algorithmic traffic: G once for the codebook sums and once for the scale sums, codes for
+        # each, the gradients written
+        nbytes = 2.0 * 4.0 * params + 2.0 * 2.0 * M * (params / g) + 4.0 * (M * (1 << B) * g + L.out_features)
+        a = nbytes / (kern["pstep"]["avg_ms"] * 1e-3) / 1e9
+        roofline = {"kernel": "pv_codebook_grads (sort + segmented sums)", "bound": "hbm", "achieved": a,
+                    "peak": PEAK_HBM, "unit": "GB/s", "frac": a / PEAK_HBM, "traffic": None}
+    elif dominant == "score_mfma":
         a = flops_contraction / (kern[dominant]["avg_ms"] * 1e-3) / 1e12
         roofline = {"kernel": "k_score_mfma", "bound": "mfma", "achieved": a, "peak": PEAK_MFMA_F16,
                     "unit": "TFLOP/s", "frac": a / PEAK_MFMA_F16,
@@ -181,7 +195,16 @@ def main() -> int:
             hbm[name + "_GBps"] = per_param * params / (kern[name]["avg_ms"] * 1e-3) / 1e9
 
     cpu = None
-    if not args.no_cpu_baseline and args.path == "trust_ratio":
+    if not args.no_cpu_baseline and args.path == "pstep":
+        import oracle
+        t1 = time.perf_counter()
+        gc_ref, gs_ref = oracle.codebook_grads(wl.G, wl.codes, wl.codebooks, wl.scales)
+        t2 = time.perf_counter()
+        cpu = {"value": (params / g) / (t2 - t1), "unit": "groups/s", "cores": 1, "kind": "oracle",
+               "sample": f"the whole matrix of {args.workload} ({t2 - t1:.3f} s, sequential by definition)",
+               "codebook_grads_equal_oracle": bool(np.array_equal(gcb.cpu().numpy(), gc_ref)),
+               "scale_grads_max_abs_diff": float(np.abs(gsc.cpu().numpy().astype(np.float64) - gs_ref).max())}
+    elif not args.no_cpu_baseline and args.path == "trust_ratio":
         import oracle
         t1 = time.perf_counter()
         Wq_ref = oracle.dequantize(wl.codes, wl.codebooks, wl.scales)
@@ -222,8 +245,10 @@ def main() -> int:
             got = codes.view(torch.int16).cpu().numpy().view(np.uint16)
             cpu["codes_equal_oracle"] = bool(np.array_equal(got, new_ref))
 
+    n_units = (params // g) if args.path == "pstep" else k
     out = {
-        "metric": "groups_reencoded_per_s", "value": k / (ms_per_step * 1e-3), "unit": "groups/s",
+        "metric": "groups_differentiated_per_s" if args.path == "pstep" else "groups_reencoded_per_s",
+        "value": n_units / (ms_per_step * 1e-3), "unit": "groups/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f16" if "score_mfma" in kern else "f64", "data": "synthetic",

@@ -150,6 +150,22 @@ pv_status pv_reencode_trust_ratio(pv_ctx *ctx, const pv_layout *layout, const fl
 pv_status pv_dequantize(pv_ctx *ctx, const pv_layout *layout, const uint16_t *codes,
                         const float *codebooks, const float *scales, float *W_out);
 
+/* P step (Alg. 3, "grad_codebooks = backprop(grad_phi)"; App. K: codebooks and per-channel
+ * scales are trained by backprop): the chain rule through pv_dequantize applied to
+ * G = d phi / d W (f32 [out_features, in_features]):
+ *   grad_codebooks[m, c, i] = sum over groups n = (o, j) with codes[o,j,m] == c of
+ *                             scales[o] * G[o, j*g + i]                  f32 [M, 2^B, g]
+ *   grad_scales[o]          = sum_j sum_i G[o, j*g + i] * (sum_m codebooks[m, codes[o,j,m], i])
+ *                                                                        f32 [out_features], optional
+ * Products are exact in double; sums are taken in double and rounded to fp32 once.  A
+ * codeword's sum runs over its groups in ascending order (bit-reproducible, and equal to a
+ * sequential loop) unless more than 128 groups share the codeword, in which case pieces
+ * of 128 are summed and added in order.  A row's scale gradient is a tree sum.  Unused
+ * codewords get exactly 0.  Nothing is accumulated into the outputs: they are overwritten. */
+pv_status pv_codebook_grads(pv_ctx *ctx, const pv_layout *layout, const float *G,
+                            const uint16_t *codes, const float *codebooks, const float *scales,
+                            float *grad_codebooks, float *grad_scales /* NULL ok */);
+
 /* ---- instrumentation (does not change results) ------------------------- */
 
 /* Search strategy for M == 1: 0 = automatic (matrix-core filter + exact
@@ -167,7 +183,8 @@ typedef enum {
     PV_K_BEAM = 7,
     PV_K_DEQUANTIZE = 8,
     PV_K_TRUST_RATIO = 9, /* norms, ranking, prefix sums, roll-back of pv_reencode_trust_ratio */
-    PV_K_COUNT = 10
+    PV_K_PSTEP = 10,      /* all kernels of pv_codebook_grads                              */
+    PV_K_COUNT = 11
 } pv_kernel_id;
 
 /* With timing on, each kernel (group) above is bracketed by HIP events on the

@@ -18,7 +18,7 @@ _lib = None
 
 KERNEL_IDS = {
     "encode_targets": 0, "group_scores": 1, "select": 2, "prep": 3, "score_mfma": 4,
-    "rerank": 5, "exact_scan": 6, "beam": 7, "dequantize": 8, "trust_ratio": 9,
+    "rerank": 5, "exact_scan": 6, "beam": 7, "dequantize": 8, "trust_ratio": 9, "pstep": 10,
 }
 
 
@@ -76,6 +76,7 @@ def load_library():
     lib.pv_encode_targets_select.argtypes = [vp, lp, vp, vp, f32, vp, i64, vp, vp]
     lib.pv_reencode_groups.argtypes = [vp, lp, vp, vp, vp, vp, i64, i32, vp, vp]
     lib.pv_dequantize.argtypes = [vp, lp, vp, vp, vp, vp]
+    lib.pv_codebook_grads.argtypes = [vp, lp, vp, vp, vp, vp, vp, vp]
     lib.pv_reencode_trust_ratio.argtypes = [vp, lp, vp, vp, vp, vp, i64, i64, ctypes.c_double, i32,
                                             vp, vp, vp, vp]
     lib.pv_set_search_mode.argtypes = [vp, ctypes.c_int]
@@ -86,6 +87,7 @@ def load_library():
     lib.pv_reencode_stats.argtypes = [vp, ctypes.POINTER(i64)]
     for name in ("pv_create", "pv_encode_targets", "pv_encode_targets_adam", "pv_select_topk_groups",
                  "pv_encode_targets_select", "pv_reencode_groups", "pv_reencode_trust_ratio",
+                 "pv_codebook_grads",
                  "pv_dequantize", "pv_set_search_mode", "pv_timing_enable", "pv_timing_reset",
                  "pv_timing_read", "pv_reencode_stats"):
         getattr(lib, name).restype = ctypes.c_int
@@ -192,6 +194,16 @@ class PVContext:
             _dev_ptr(rank_idx, torch.int32, "rank_idx", allow_none=True),
             _dev_ptr(num_applied, torch.int64, "num_applied"),
             _dev_ptr(stats, torch.float64, "stats", allow_none=True)))
+
+    def pv_codebook_grads(self, layout: Layout, G, codes, codebooks, scales, grad_codebooks,
+                          grad_scales=None):
+        lay = layout.c()
+        self._check(self._lib.pv_codebook_grads(
+            self._h, ctypes.byref(lay), _dev_ptr(G, torch.float32, "G"),
+            _dev_ptr(codes, torch.uint16, "codes"), _dev_ptr(codebooks, torch.float32, "codebooks"),
+            _dev_ptr(scales, torch.float32, "scales"),
+            _dev_ptr(grad_codebooks, torch.float32, "grad_codebooks"),
+            _dev_ptr(grad_scales, torch.float32, "grad_scales", allow_none=True)))
 
     def pv_dequantize(self, layout: Layout, codes, codebooks, scales, W_out):
         lay = layout.c()

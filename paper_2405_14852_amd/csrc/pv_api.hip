@@ -123,7 +123,7 @@ extern "C" void pv_destroy(pv_ctx *c)
     (void)hipStreamSynchronize(c->stream);
     pv_buffer *bufs[] = {&c->sel_scores, &c->sel_hist, &c->sel_blocks, &c->sel_state, &c->stats,
                          &c->cb_f16,     &c->cb_meta,  &c->x_f16,      &c->x_meta,    &c->partials,
-                         &c->fb_list,   &c->fb_partial, &c->fb_arrivals, &c->rr_counts, &c->trust};
+                         &c->fb_list,   &c->fb_partial, &c->fb_arrivals, &c->rr_counts, &c->trust, &c->pstep};
     for (pv_buffer *b : bufs)
         if (b->ptr) (void)hipFree(b->ptr);
     for (auto &t : c->timers)
@@ -301,6 +301,32 @@ extern "C" pv_status pv_reencode_trust_ratio(pv_ctx *ctx, const pv_layout *l, co
     PV_HIP(ctx, hipSetDevice(ctx->device));
     return pv_launch_trust_ratio(ctx, l, T, W, codebooks, scales, k_max, chunk, ratio, beam_width,
                                  codes, rank_idx, num_applied, stats);
+}
+
+extern "C" pv_status pv_codebook_grads(pv_ctx *ctx, const pv_layout *l, const float *G,
+                                       const uint16_t *codes, const float *codebooks,
+                                       const float *scales, float *grad_codebooks,
+                                       float *grad_scales)
+{
+    if (!ctx) return PV_ERR_INVALID_ARG;
+    pv_status st = check_layout(ctx, l);
+    if (st != PV_OK) return st;
+    if (!G || !codes || !codebooks || !scales || !grad_codebooks)
+        return pv_fail(ctx, PV_ERR_INVALID_ARG, "NULL tensor pointer");
+    if (l->group_size > 64)
+        return pv_fail(ctx, PV_ERR_UNSUPPORTED, "codebook gradients support group_size <= 64");
+    PV_HIP(ctx, hipSetDevice(ctx->device));
+    if (pv_num_groups(l) == 0) {   // empty matrix: all sums are empty
+        const size_t cb_bytes = sizeof(float) * (size_t)l->num_codebooks *
+                                ((size_t)1 << l->nbits) * (size_t)l->group_size;
+        PV_HIP(ctx, hipMemsetAsync(grad_codebooks, 0, cb_bytes, ctx->stream));
+        if (grad_scales && l->out_features > 0)
+            PV_HIP(ctx, hipMemsetAsync(grad_scales, 0, sizeof(float) * (size_t)l->out_features,
+                                       ctx->stream));
+        return PV_OK;
+    }
+    return pv_launch_codebook_grads(ctx, l, G, codes, codebooks, scales, grad_codebooks,
+                                    grad_scales);
 }
 
 extern "C" pv_status pv_dequantize(pv_ctx *ctx, const pv_layout *l, const uint16_t *codes,

@@ -50,6 +50,7 @@ struct pv_ctx {
     pv_buffer rr_counts;    // u32 [blocks][3]    per-block counters of the re-rank kernel
     pv_buffer fb_arrivals;  // u32 [k/4]          pieces finished per work item (kept zero between calls)
     pv_buffer trust;        // scratch of the trust-ratio call (saved codes, keys, prefix sums, sort space)
+    pv_buffer pstep;        // scratch of the P-step gradients (keys, sorted order, segment starts, sort space)
 };
 
 // RAII bracket that records HIP events around a group of launches when timing is on.
@@ -115,6 +116,9 @@ pv_status pv_reencode_dispatch(pv_ctx *ctx, const pv_layout *l, const float *T,
                                const float *codebooks, const float *scales,
                                const int32_t *group_idx, int64_t k, int32_t beam_width,
                                uint16_t *codes, int64_t *num_changed);
+pv_status pv_launch_codebook_grads(pv_ctx *ctx, const pv_layout *l, const float *G,
+                                   const uint16_t *codes, const float *codebooks,
+                                   const float *scales, float *grad_codebooks, float *grad_scales);
 pv_status pv_launch_trust_ratio(pv_ctx *ctx, const pv_layout *l, const float *T, const float *W,
                                 const float *codebooks, const float *scales, int64_t k_max,
                                 int64_t chunk, double ratio, int32_t beam_width, uint16_t *codes,
