@@ -31,6 +31,101 @@ PEAK_F64 = 78.6          # TFLOP/s fp64 vector (256 CU x 4 SIMD x 16 lanes x 2 (
 MEASURED_TRAFFIC_BYTES = {("k_score_mfma", "c2_4096x4096_1x16"): (10991.7 * 2.0 + 10718.2) * 1024.0}
 
 
+def run_stack(args) -> int:
+    """The whole-model sweep: 32 decoder blocks x 7 linear layers of the Llama-2-7B shapes
+    (6.476e9 parameters, 809.5 M groups, 1x16 codebook per matrix, tau = 0.01 per matrix).
+    Inputs are drawn ON THE DEVICE with torch's generator (same distributions as workloads.py,
+    whose host-side tensors for this configuration would need 78 GB of host memory); the
+    per-matrix path at these shapes is checked against the oracle in tests/test_gpu_fullsize.py.
+    One step = dequantize -> targets + selection -> re-encode -> dequantize for all 224 matrices."""
+    import torch
+
+    import workloads
+    from paper_2405_14852_amd import Layout, PVContext
+
+    dev = torch.device("cuda:0")
+    ctx = PVContext(0)
+    gen = torch.Generator(device=dev)
+    layers = 32
+    mats = []
+    shapes = list(workloads.LLAMA2_7B_BLOCK.values())
+    max_n = max(o * i for o, i in shapes)
+    T = torch.empty(max_n, dtype=torch.float32, device=dev)
+    Wq = torch.empty(max_n, dtype=torch.float32, device=dev)
+    total_params = total_groups = total_k = 0
+    for layer in range(layers):
+        for pid, (name, (o, i)) in enumerate(workloads.LLAMA2_7B_BLOCK.items()):
+            gen.manual_seed(layer * 16 + pid + 1)
+            lay = Layout(o, i, 8, 1, 16)
+            N = o * i // 8
+            k = workloads.num_selected(N, 0.01)
+            m = {
+                "lay": lay, "k": k, "n": o * i,
+                "W": torch.randn(o, i, generator=gen, device=dev) * 0.02,
+                "G": torch.randn(o, i, generator=gen, device=dev) * 1e-4,
+                "cb": torch.randn(1, 65536, 8, generator=gen, device=dev) * 0.02,
+                "sc": torch.rand(o, generator=gen, device=dev) + 0.5,
+                "codes": torch.randint(0, 65536, (o, i // 8, 1), generator=gen, device=dev,
+                                       dtype=torch.int32).to(torch.uint16),
+                "idx": torch.empty(k, dtype=torch.int32, device=dev),
+            }
+            mats.append(m)
+            total_params += o * i
+            total_groups += N
+            total_k += k
+    nch = torch.zeros(1, dtype=torch.int64, device=dev)
+
+    def step():
+        for m in mats:
+            lay = m["lay"]
+            t, wq = T[: m["n"]].view(lay.out_features, lay.in_features), Wq[: m["n"]].view(
+                lay.out_features, lay.in_features)
+            ctx.pv_dequantize(lay, m["codes"], m["cb"], m["sc"], wq)
+            ctx.pv_encode_targets_select(lay, m["W"], m["G"], 1.0, t, m["k"], m["idx"])
+            ctx.pv_reencode_groups(lay, t, m["cb"], m["sc"], m["idx"], m["k"], 1, m["codes"], nch)
+            ctx.pv_dequantize(lay, m["codes"], m["cb"], m["sc"], wq)
+
+    steps = min(args.steps, 5)
+    warmup = min(args.warmup, 1)
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    ms = 1e3 * (time.perf_counter() - t0) / steps
+    ctx.pv_timing_enable(True)
+    ctx.pv_timing_reset()
+    step()
+    torch.cuda.synchronize()
+    kern = {}
+    for name in ("dequantize", "encode_targets", "select", "prep", "score_mfma", "rerank", "exact_scan"):
+        t_ms, n = ctx.pv_timing_read(name)
+        if n:
+            kern[name] = {"ms_per_step": t_ms, "launches_per_step": n}
+    flops = 2.0 * total_k * 65536 * 8
+    a = flops / (kern["score_mfma"]["ms_per_step"] * 1e-3) / 1e12
+    out = {
+        "metric": "groups_reencoded_per_s", "value": total_k / (ms * 1e-3), "unit": "groups/s",
+        "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": ms, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "f16", "data": "synthetic (drawn on the device)",
+        "config": {"workload": "c4_llama2_7b_stack", "matrices": len(mats), "parameters": total_params,
+                   "groups": total_groups, "k_selected": total_k, "tau": 0.01, "group_size": 8,
+                   "num_codebooks": 1, "nbits": 16},
+        "roofline": {"kernel": "k_score_mfma", "bound": "mfma", "achieved": a, "peak": PEAK_MFMA_F16,
+                     "unit": "TFLOP/s", "frac": a / PEAK_MFMA_F16, "traffic": None},
+        "cpu_baseline": None,
+        "note": "the oracle is not timed on this configuration (4.2e12 double operations); see the "
+                "single-matrix workloads for its rate",
+        "streaming_GBps": (12.0 + 0.5 + 2 * 4.25) * total_params
+        / ((kern["dequantize"]["ms_per_step"] + kern["encode_targets"]["ms_per_step"]) * 1e-3) / 1e9,
+        "kernels": kern,
+    }
+    print(json.dumps(out))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -61,6 +156,9 @@ def main() -> int:
 
     import workloads
     from paper_2405_14852_amd import Layout, PVContext
+
+    if args.workload == "c4_llama2_7b_stack":
+        return run_stack(args)
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
