@@ -234,6 +234,8 @@ def reencode_case(wl, mode, idx=None, T_np=None):
     (8, 8, (256, 256), 1.0),        # config 1 as stated
     (8, 16, (64, 1024), 0.3),       # 1x16, several tiles + ragged tail of selected groups
     (16, 16, (48, 1024), 0.4),      # 1-bit config shape
+    (16, 14, (48, 1024), 0.4),      # 14-bit codebook over groups of 16 (0.875 bit, App. K / Sec. 4.4)
+    (8, 14, (40, 512), 0.5),        # 14 bits over groups of 8
     (8, 12, (32, 264), 1.0),
     (16, 5, (16, 256), 1.0),
     (4, 3, (8, 64), 1.0),
