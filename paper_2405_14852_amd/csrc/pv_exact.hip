@@ -85,7 +85,7 @@ __global__ __launch_bounds__(kBlock) void k_exact_scan(
     const float *__restrict__ scales, const int32_t *__restrict__ list,
     const uint32_t *__restrict__ d_count, int64_t max_count, uint16_t *__restrict__ codes,
     unsigned long long *__restrict__ num_changed, unsigned long long *__restrict__ stat_counter,
-    int g_rt, int nbits, int gpr, int N, int nsplit, part_t *partial, unsigned *arrivals,
+    int g_rt, int nbits, int gpr, int N, int nsplit_max, part_t *partial, unsigned *arrivals,
     unsigned *__restrict__ reset_meta, const unsigned *__restrict__ rr_counts, int rr_blocks,
     unsigned long long *__restrict__ rr_stats)
 {
@@ -104,6 +104,14 @@ __global__ __launch_bounds__(kBlock) void k_exact_scan(
     const int64_t count = d_count ? (int64_t)*d_count : max_count;
     const int csize = 1 << nbits;
     const int64_t items = (count + GPB - 1) / GPB;
+    // pieces per codeword range: as many as it takes to give the chip about a thousand work
+    // units, at most nsplit_max (the list length is only known here, on the device)
+    int nsplit = nsplit_max;
+    if (nsplit > 1 && items > 0) {
+        int64_t want = (1024 + items - 1) / items;
+        if (want < 1) want = 1;
+        if (want < nsplit) nsplit = (int)want;
+    }
     for (int64_t w = blockIdx.x; w < items * nsplit; w += gridDim.x) {
         const int64_t item = w / nsplit;
         const int64_t base = item * GPB;
@@ -143,7 +151,7 @@ __global__ __launch_bounds__(kBlock) void k_exact_scan(
             }
             // kBatch codewords per step: all their loads are issued before the arithmetic, so a
             // step costs one memory round trip (this kernel runs on few groups: latency bound)
-            constexpr int kBatch = 4;
+            constexpr int kBatch = GS <= 8 ? 4 : 2;   // keeps the register count at two waves per SIMD
             for (int c0 = c_begin + threadIdx.x; c0 < c_end; c0 += kBlock * kBatch) {
                 pv_f4 cv[kBatch][GS / 4];
 #pragma unroll
@@ -167,7 +175,9 @@ __global__ __launch_bounds__(kBlock) void k_exact_scan(
                             double acc = (double)cv[u][v4][e];
 #pragma unroll
                             for (int q = 0; q < GPB; ++q) {
-                                double r = sc[q] * acc - tt[q][v4 * 4 + e];
+                                // s * c is exact in double (two 24-bit factors), so the fused form
+                                // rounds exactly like the product followed by the subtraction
+                                double r = fma(sc[q], acc, -tt[q][v4 * 4 + e]);
                                 obj[q] = obj[q] + r * r;
                             }
                         }
@@ -207,7 +217,7 @@ __global__ __launch_bounds__(kBlock) void k_exact_scan(
         best_t mine[GPB];
 #pragma unroll
         for (int q = 0; q < GPB; ++q) mine[q] = block_min(best[q], s_obj, s_idx);  // valid in thread 0
-        if (nsplit > 1) {
+        if (nsplit_max > 1) {
             if (threadIdx.x == 0) {
 #pragma unroll
                 for (int q = 0; q < GPB; ++q) {
@@ -215,7 +225,7 @@ __global__ __launch_bounds__(kBlock) void k_exact_scan(
                     pt.obj = mine[q].obj;
                     pt.idx = mine[q].idx;
                     pt.pad = 0;
-                    partial[(base + q) * nsplit + piece] = pt;
+                    partial[(base + q) * nsplit_max + piece] = pt;
                 }
                 __threadfence();
                 s_last = atomicAdd(&arrivals[item], 1u) == (unsigned)(nsplit - 1) ? 1u : 0u;
@@ -230,7 +240,7 @@ __global__ __launch_bounds__(kBlock) void k_exact_scan(
                 b.obj = kInf;
                 b.idx = 0x7fffffff;
                 if (q < GPB && p < nsplit) {
-                    const part_t *pp = &partial[(base + q) * nsplit + p];
+                    const part_t *pp = &partial[(base + q) * nsplit_max + p];
                     unsigned long long ob = __hip_atomic_load(
                         reinterpret_cast<const unsigned long long *>(&pp->obj), __ATOMIC_RELAXED,
                         __HIP_MEMORY_SCOPE_AGENT);

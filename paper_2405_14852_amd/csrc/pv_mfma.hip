@@ -503,7 +503,9 @@ __device__ __forceinline__ double exact_obj(const float *__restrict__ cw, float 
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             double acc = (double)c[e];
-            double r = (double)s * acc - (double)t[v4 * 4 + e];
+            // s * c is exact in double (two 24-bit factors): the fused form rounds exactly
+            // like the product followed by the subtraction
+            double r = fma((double)s, acc, -(double)t[v4 * 4 + e]);
             obj = obj + r * r;
         }
     }
