@@ -470,18 +470,36 @@ __global__ __launch_bounds__(kBlock) void k_beam(
 // Objectives use the same double-precision chain as everywhere else.
 constexpr int kBeam2Max = 8;
 
+// Smallest value over the 64 lanes, in every lane: data-parallel-primitive shifts inside rows
+// of 16 lanes, two row broadcasts, then the last lane's value is read out.
+__device__ __forceinline__ unsigned wave_min_u32(unsigned v)
+{
+    constexpr unsigned kId = 0xFFFFFFFFu;   // lanes without a source keep the identity
+    v = min(v, (unsigned)__builtin_amdgcn_update_dpp((int)kId, (int)v, 0x111, 0xf, 0xf, false));  // row_shr:1
+    v = min(v, (unsigned)__builtin_amdgcn_update_dpp((int)kId, (int)v, 0x112, 0xf, 0xf, false));  // row_shr:2
+    v = min(v, (unsigned)__builtin_amdgcn_update_dpp((int)kId, (int)v, 0x114, 0xf, 0xf, false));  // row_shr:4
+    v = min(v, (unsigned)__builtin_amdgcn_update_dpp((int)kId, (int)v, 0x118, 0xf, 0xf, false));  // row_shr:8
+    v = min(v, (unsigned)__builtin_amdgcn_update_dpp((int)kId, (int)v, 0x142, 0xa, 0xf, false));  // row_bcast:15
+    v = min(v, (unsigned)__builtin_amdgcn_update_dpp((int)kId, (int)v, 0x143, 0xc, 0xf, false));  // row_bcast:31
+    return (unsigned)__builtin_amdgcn_readlane((int)v, 63);
+}
+
+// Lexicographic minimum of (objective, index) over the wave, identical in every lane.
+// Objectives are non-negative doubles, so their bit patterns order like unsigned integers:
+// three 32-bit reductions (high word, low word among the lanes that hold the smallest high
+// word, index among the lanes that hold the smallest objective).
 __device__ __forceinline__ best_t wave_argmin_all(best_t b)
 {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) {
-        double o = __shfl_xor(b.obj, off);
-        int i = __shfl_xor(b.idx, off);
-        if (better(o, i, b.obj, b.idx)) {
-            b.obj = o;
-            b.idx = i;
-        }
-    }
-    return b;   // identical in every lane
+    const unsigned long long bits = (unsigned long long)__double_as_longlong(b.obj);
+    const unsigned hi = (unsigned)(bits >> 32), lo = (unsigned)bits;
+    const unsigned mhi = wave_min_u32(hi);
+    const unsigned mlo = wave_min_u32(hi == mhi ? lo : 0xFFFFFFFFu);
+    const bool mine = hi == mhi && lo == mlo;
+    const unsigned midx = wave_min_u32(mine ? (unsigned)b.idx : 0xFFFFFFFFu);
+    best_t r;
+    r.obj = __longlong_as_double((long long)(((unsigned long long)mhi << 32) | mlo));
+    r.idx = (int)midx;
+    return r;
 }
 
 template <int G>
