@@ -12,7 +12,8 @@
 // order, in double, with exact products - the same sum, in the same order, as a plain
 // loop over the groups.  Segments longer than kLong groups are cut into pieces of kLong,
 // summed by separate teams and added in piece order (a different association:
-// reproducible, but no longer the sequential order).  The scale gradient is one block-wide tree sum per row.
+// reproducible, but no longer the sequential order).  Small codebooks take another route
+// (k_pg_small below).  The scale gradient is one block-wide tree sum per row.
 #include <hipcub/hipcub.hpp>
 
 #include "pv_internal.h"
@@ -193,6 +194,65 @@ __global__ __launch_bounds__(kBlock) void k_pg_combine(const int32_t *__restrict
     out[t] = (float)acc;
 }
 
+// Small codebooks (all M * 2^B * g sums fit one block's LDS as doubles): every codeword is
+// shared by thousands of groups, so sorting buys nothing.  Each block sweeps a contiguous
+// range of groups once, 16 bytes of G per thread, and adds s_o * G into its own LDS table
+// with LDS atomics; the tables are then added up over the blocks in block order.  The order
+// of the atomic additions inside a block is not fixed, so the double sums may differ in
+// their last bits from run to run (the fp32 results almost never do).
+__global__ __launch_bounds__(kBlock) void k_pg_small(const float *__restrict__ G,
+                                                     const uint16_t *__restrict__ codes,
+                                                     const float *__restrict__ scales, int64_t N,
+                                                     int64_t per_block, int g, int M, int nbits,
+                                                     int gpr, double *__restrict__ partial)
+{
+    extern __shared__ double tab[];                     // [M][2^B][g]
+    const int csize = 1 << nbits;
+    const unsigned mask = (unsigned)csize - 1u;
+    const int entries = M * csize * g;
+    for (int e = threadIdx.x; e < entries; e += kBlock) tab[e] = 0.0;
+    __syncthreads();
+    const int vpg = g / 4;                              // 16-byte vectors per group
+    const int64_t lo = (int64_t)blockIdx.x * per_block;
+    const int64_t hi = lo + per_block < N ? lo + per_block : N;
+    const pv_f4 *G4 = reinterpret_cast<const pv_f4 *>(G);
+    for (int64_t v = lo * vpg + threadIdx.x; v < hi * vpg; v += kBlock) {
+        const int64_t n = v / vpg;
+        const int q4 = (int)(v - n * vpg);
+        const pv_f4 gv = __builtin_nontemporal_load(&G4[v]);
+        const double s = (double)scales[n / gpr];
+        for (int m = 0; m < M; ++m) {
+            const int c = codes[n * M + m] & mask;
+            double *row = tab + ((int64_t)m * csize + c) * g + q4 * 4;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) atomicAdd(&row[e], s * (double)gv[e]);
+        }
+    }
+    __syncthreads();
+    double *out = partial + (int64_t)blockIdx.x * entries;
+    for (int e = threadIdx.x; e < entries; e += kBlock) out[e] = tab[e];
+}
+
+// sums the per-block tables in block order, rounds once
+__global__ __launch_bounds__(kBlock) void k_pg_small_final(const double *__restrict__ partial,
+                                                           int blocks, int entries,
+                                                           float *__restrict__ out)
+{
+    const int e = blockIdx.x * kBlock + threadIdx.x;
+    if (e >= entries) return;
+    double acc = 0.0;
+    int b = 0;
+    for (; b + 4 <= blocks; b += 4) {
+        double p[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) p[u] = partial[(int64_t)(b + u) * entries + e];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) acc = acc + p[u];
+    }
+    for (; b < blocks; ++b) acc = acc + partial[(int64_t)b * entries + e];
+    out[e] = (float)acc;
+}
+
 // one block per output row; VEC: g % 4 == 0, a thread takes 16-byte vectors
 template <bool VEC>
 __global__ __launch_bounds__(kBlock) void k_pg_scales(const float *__restrict__ G,
@@ -265,6 +325,29 @@ pv_status pv_launch_codebook_grads(pv_ctx *ctx, const pv_layout *l, const float 
     const int csize = 1 << l->nbits;
     const unsigned mask = (unsigned)csize - 1u;
     hipStream_t sm = ctx->stream;
+
+    // small codebooks: per-block LDS tables instead of a sort
+    const int64_t entries = (int64_t)M * csize * g;
+    if (g % 4 == 0 && entries * 8 <= 64 * 1024 && N / csize >= 64) {
+        int blocks = (int)((N + 4095) / 4096);
+        if (blocks > 512) blocks = 512;
+        if (blocks < 1) blocks = 1;
+        const int64_t per_block = (N + blocks - 1) / blocks;
+        pv_status st2 = pv_ensure(ctx, ctx->pstep, (size_t)blocks * entries * 8);
+        if (st2 != PV_OK) return st2;
+        double *partial = static_cast<double *>(ctx->pstep.ptr);
+        pv_timed t(ctx, PV_K_PSTEP);
+        hipLaunchKernelGGL(k_pg_small, dim3(blocks), dim3(kBlock), (size_t)entries * 8, sm, G, codes,
+                           scales, N, per_block, g, M, l->nbits, gpr, partial);
+        hipLaunchKernelGGL(k_pg_small_final, dim3((unsigned)((entries + kBlock - 1) / kBlock)),
+                           dim3(kBlock), 0, sm, partial, blocks, (int)entries, grad_codebooks);
+        if (grad_scales) {
+            hipLaunchKernelGGL(k_pg_scales<true>, dim3((unsigned)l->out_features), dim3(kBlock), 0, sm,
+                               G, codes, codebooks, g, M, l->nbits, gpr, grad_scales);
+        }
+        PV_HIP(ctx, hipGetLastError());
+        return PV_OK;
+    }
 
     size_t sort_bytes = 0;
     PV_HIP(ctx, hipcub::DeviceRadixSort::SortPairs(nullptr, sort_bytes, (const uint16_t *)nullptr,
