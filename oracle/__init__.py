@@ -48,6 +48,9 @@ def _load():
         lib.pvo_encode_targets_adam.restype = ctypes.c_int
         lib.pvo_codebook_grads.argtypes = [i64, i64, i32, i32, i32, p, p, p, p, p, p]
         lib.pvo_codebook_grads.restype = ctypes.c_int
+        lib.pvo_dequantize_scalar.argtypes = [i64, i64, i32, i32, p, p, p, p]
+        lib.pvo_reencode_scalar.argtypes = [i64, i64, i32, i32, p, p, p, p, i64, p, p]
+        lib.pvo_dequantize_scalar.restype = lib.pvo_reencode_scalar.restype = ctypes.c_int
         f64 = ctypes.c_double
         lib.pvo_reencode_trust_ratio.argtypes = [i64, i64, i32, i32, i32, p, p, p, p, i64, i64, f64,
                                                  i32, p, p, p, p]
@@ -161,6 +164,35 @@ def reencode_trust_ratio(T, W, codebooks, scales, codes, k_max: int, chunk: int,
         raise ValueError("pvo_reencode_trust_ratio failed")
     return new, {"rank_idx": rank[:k_max], "num_applied": int(applied.value),
                  "change_sq": float(stats[0]), "norm_sq": float(stats[1])}
+
+
+def dequantize_scalar(codes, scales, zeros, block: int, nbits: int) -> np.ndarray:
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    sc, zp = _f32(scales), _f32(zeros)
+    out_f, in_f = codes.shape
+    assert sc.shape == zp.shape == (out_f, in_f // block)
+    W = np.empty((out_f, in_f), dtype=np.float32)
+    rc = _load().pvo_dequantize_scalar(out_f, in_f, int(block), int(nbits), _ptr(codes), _ptr(sc),
+                                       _ptr(zp), _ptr(W))
+    if rc:
+        raise ValueError("pvo_dequantize_scalar failed")
+    return W
+
+
+def reencode_scalar(T, scales, zeros, weight_idx, codes, block: int, nbits: int):
+    """Returns (new_codes, num_changed); `codes` is left untouched."""
+    T = _f32(T)
+    sc, zp = _f32(scales), _f32(zeros)
+    out_f, in_f = T.shape
+    idx = np.ascontiguousarray(weight_idx, dtype=np.int32)
+    new = np.ascontiguousarray(codes, dtype=np.uint8).copy()
+    assert new.shape == T.shape
+    changed = ctypes.c_int64(0)
+    rc = _load().pvo_reencode_scalar(out_f, in_f, int(block), int(nbits), _ptr(T), _ptr(sc), _ptr(zp),
+                                     _ptr(idx), idx.shape[0], _ptr(new), ctypes.addressof(changed))
+    if rc:
+        raise ValueError("pvo_reencode_scalar failed")
+    return new, int(changed.value)
 
 
 def codebook_grads(G, codes, codebooks, scales):

@@ -33,6 +33,10 @@
  *                           single-index descent (App. D).  Beyond those bounds
  *                           the beam result is PARITY UNPINNED.
  *   pvo_dequantize          Alg. 3 line 1: W = scale_row * sum_m codeword_m.
+ *   pvo_dequantize_scalar / pvo_reencode_scalar  App. K's scalar representation (uniform grid,
+ *                           block-wise scale and zero point): the V step is rounding to the
+ *                           nearest grid value, written as a search over all values (pinned
+ *                           by the closed-form rounding and a sorted-grid bisection).
  *   pvo_codebook_grads      Alg. 3 P step: chain rule through the dequantiser (pinned by
  *                           automatic differentiation of an independent dequantiser and by
  *                           finite differences of a quadratic loss).
@@ -510,6 +514,60 @@ int pvo_reencode_trust_ratio(int64_t out_features, int64_t in_features, int g, i
     free(saved);
     free(prefix);
     return rc;
+}
+
+/* ------------------------------------------------- scalar uniform grids (App. K) */
+
+/* The scalar representation of App. K ("GPTQ": uniform grid, block-wise scales and zero
+ * points along the input dimension): W[o, i] = s[o, i/blk] * (q[o, i] - z[o, i/blk]) with
+ * q in [0, 2^b).  fp32: one subtraction, one multiplication. */
+int pvo_dequantize_scalar(int64_t out_features, int64_t in_features, int blk, int b,
+                          const uint8_t *codes, const float *scales, const float *zeros,
+                          float *W_out)
+{
+    if (!codes || !scales || !zeros || !W_out || blk < 1 || in_features % blk) return PVO_ERR;
+    if (b < 1 || b > 8) return PVO_ERR;
+    int64_t bpr = in_features / blk;
+    for (int64_t o = 0; o < out_features; ++o)
+        for (int64_t i = 0; i < in_features; ++i) {
+            int q = codes[o * in_features + i];
+            if (q >= (1 << b)) return PVO_ERR;
+            float d = (float)q - zeros[o * bpr + i / blk];
+            W_out[o * in_features + i] = scales[o * bpr + i / blk] * d;
+        }
+    return PVO_OK;
+}
+
+/* V step on that representation (App. K: "V step performs simple rounding to nearest
+ * (scaled) integer"): for every listed weight the grid value nearest to the target, written
+ * as the definition - every q is tried, objective (w_q - t)^2 in double with w_q the fp32
+ * dequantised value; ties: the previous code if it is a minimiser, else the lowest q. */
+int pvo_reencode_scalar(int64_t out_features, int64_t in_features, int blk, int b, const float *T,
+                        const float *scales, const float *zeros, const int32_t *weight_idx,
+                        int64_t k, uint8_t *codes, int64_t *num_changed)
+{
+    if (!T || !scales || !zeros || !codes || blk < 1 || in_features % blk) return PVO_ERR;
+    if (b < 1 || b > 8 || k < 0 || (k > 0 && !weight_idx)) return PVO_ERR;
+    int64_t bpr = in_features / blk, n = out_features * in_features, changed = 0;
+    for (int64_t j = 0; j < k; ++j) {
+        int64_t e = weight_idx[j];
+        if (e < 0 || e >= n) return PVO_ERR;
+        int64_t o = e / in_features, i = e % in_features;
+        float s = scales[o * bpr + i / blk], z = zeros[o * bpr + i / blk];
+        int prev = codes[e], best = -1;
+        double best_obj = 0.0, prev_obj = 0.0;
+        for (int q = 0; q < (1 << b); ++q) {
+            float w = s * ((float)q - z);
+            double r = (double)w - (double)T[e];
+            double obj = r * r;
+            if (q == prev) prev_obj = obj;
+            if (best < 0 || obj < best_obj) { best = q; best_obj = obj; }
+        }
+        if (prev < (1 << b) && prev_obj == best_obj) best = prev;
+        if (best != prev) { codes[e] = (uint8_t)best; ++changed; }
+    }
+    if (num_changed) *num_changed = changed;
+    return PVO_OK;
 }
 
 /* ------------------------------------------------------------ P-step gradients */

@@ -748,3 +748,49 @@ def test_codebook_grads_exact_small_case():
     assert np.array_equal(gc[0, 1], [2 * (1 + 5), 2 * (2 + 6)])
     assert np.array_equal(gc[0, 0], [2 * 3, 2 * 4])
     assert gs[0] == 1 * 0.5 + 2 * 4 + 3 * 1 + 4 * -1 + 5 * 0.5 + 6 * 4
+
+
+# --------------------------------------- scalar uniform grid (App. K, "GPTQ" representation)
+
+@pytest.mark.parametrize("nbits,block", [(2, 128), (3, 16), (4, 32), (8, 8)])
+def test_scalar_reencode_is_rounding_to_the_nearest_grid_value(nbits, block):
+    W, G, codes, sc, zp = workloads.make_scalar(6, 256, block, nbits, seed=90)
+    T = oracle.encode_targets(oracle.dequantize_scalar(codes, sc, zp, block, nbits), G * 20, 1.0)
+    idx = np.arange(T.size, dtype=np.int32)
+    new, changed = oracle.reencode_scalar(T, sc, zp, idx, codes, block, nbits)
+    # closed form: q = clip(rint(t / s + z)); compare where the target is not near a half-way point
+    s_full = np.repeat(sc, block, axis=1).astype(np.float64)
+    z_full = np.repeat(zp, block, axis=1).astype(np.float64)
+    u = T.astype(np.float64) / s_full + z_full
+    q = np.clip(np.rint(u), 0, (1 << nbits) - 1).astype(np.uint8)
+    safe = np.abs(u - np.floor(u) - 0.5) > 1e-3
+    assert safe.mean() > 0.9 and np.array_equal(new[safe], q[safe])
+    assert changed == int((new != codes).sum()) and changed > 0
+    # bisection in the sorted grid of each block: the same nearest value
+    for o, i in [(0, 0), (3, 77), (5, 255), (2, 128)]:
+        vals = (sc[o, i // block] * (np.arange(1 << nbits, dtype=np.float32) - zp[o, i // block])).astype(np.float32)
+        order = np.argsort(vals, kind="stable")
+        pos = np.searchsorted(vals[order], T[o, i])
+        cand = [order[max(pos - 1, 0)], order[min(pos, len(order) - 1)]]
+        near = min(cand, key=lambda c: (abs(float(vals[c]) - float(T[o, i])), c))
+        if abs(abs(float(vals[cand[0]]) - float(T[o, i])) - abs(float(vals[cand[1]]) - float(T[o, i]))) > 1e-9:
+            assert new[o, i] == near
+
+
+def test_scalar_reencode_tie_rule_and_untouched_weights():
+    sc = np.array([[1.0]], np.float32)
+    zp = np.array([[0.0]], np.float32)
+    codes = np.array([[2, 1, 0, 3]], np.uint8)
+    T = np.array([[1.5, 1.5, 7.0, 100.0]], np.float32)          # half-way between 1 and 2
+    new, changed = oracle.reencode_scalar(T, sc, zp, np.array([0, 1, 2], np.int32), codes, 4, 2)
+    assert list(new[0]) == [2, 1, 3, 3]      # ties keep the previous code; 7 clips to 3; weight 3 not listed
+    assert changed == 1
+    new2, _ = oracle.reencode_scalar(T, sc, zp, np.array([0], np.int32), np.array([[0, 1, 0, 3]], np.uint8), 4, 2)
+    assert new2[0, 0] == 1                   # previous code 0 is no minimiser: the lower of the tied values
+
+
+def test_scalar_dequantize_definition():
+    W, G, codes, sc, zp = workloads.make_scalar(5, 64, 16, 3, seed=91)
+    got = oracle.dequantize_scalar(codes, sc, zp, 16, 3)
+    want = np.repeat(sc, 16, axis=1) * (codes.astype(np.float32) - np.repeat(zp, 16, axis=1))
+    assert np.array_equal(got, want.astype(np.float32))

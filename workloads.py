@@ -149,3 +149,20 @@ def make_block_matrix(layer: int, proj: str, seed: int = 0) -> Workload:
     return make(o, i, 8, 1, 16, sigma_g=1e-4, tau=0.01,
                 seed=(seed * 1_000_003 + layer * 16 + pid + 1),
                 name=f"c4_layer{layer}_{proj}")
+
+
+def make_scalar(out_features: int, in_features: int, block: int, nbits: int, *, sigma_w: float = 0.02,
+                sigma_g: float = 1e-3, seed: int = 0):
+    """Inputs for the scalar uniform-grid representation of App. K (block-wise scale and zero
+    point along the input dimension): (W, G, codes u8 [out, in], scales, zeros [out, in/block])."""
+    assert in_features % block == 0
+    W = _rng(seed, 11).standard_normal((out_features, in_features), dtype=np.float32) * np.float32(sigma_w)
+    G = _rng(seed, 12).standard_normal((out_features, in_features), dtype=np.float32) * np.float32(sigma_g)
+    codes = _rng(seed, 13).integers(0, 1 << nbits, size=(out_features, in_features), dtype=np.uint8)
+    shape = (out_features, in_features // block)
+    # a grid that covers about +-3 sigma of the weights
+    scales = (_rng(seed, 14).random(shape, dtype=np.float32) + np.float32(0.5)) \
+        * np.float32(6.0 * sigma_w / ((1 << nbits) - 1))
+    zeros = np.float32(((1 << nbits) - 1) / 2.0) + (_rng(seed, 15).random(shape, dtype=np.float32)
+                                                    - np.float32(0.5))
+    return W.astype(np.float32), G.astype(np.float32), codes, scales.astype(np.float32), zeros.astype(np.float32)
