@@ -166,6 +166,27 @@ pv_status pv_codebook_grads(pv_ctx *ctx, const pv_layout *layout, const float *G
                             const uint16_t *codes, const float *codebooks, const float *scales,
                             float *grad_codebooks, float *grad_scales /* NULL ok */);
 
+/* ---- the scalar representation of App. K ("GPTQ": uniform grid, block-wise scale and zero
+ *      point): W[o, i] = scales[o, i/block] * (codes[o, i] - zeros[o, i/block]),
+ *      codes u8 [out_features, in_features] with values in [0, 2^nbits), nbits <= 8,
+ *      scales and zeros f32 [out_features, in_features / block_size].
+ *      Targets and selection are the calls above with group_size = 1 (the unit is a weight). */
+
+/* fp32: one subtraction, one multiplication per weight. */
+pv_status pv_dequantize_scalar(pv_ctx *ctx, int64_t out_features, int64_t in_features,
+                               int32_t block_size, int32_t nbits, const uint8_t *codes,
+                               const float *scales, const float *zeros, float *W_out);
+
+/* V step on that representation (App. K: rounding to the nearest scaled integer): for each
+ * listed weight (flat ids, ascending, as pv_select_topk_groups returns them for group_size 1)
+ * the grid value nearest to T, i.e. the q minimising (w_q - t)^2 in double with w_q the fp32
+ * dequantised value; ties: the previous code if it is a minimiser, else the lowest q.
+ * codes is updated in place for the listed weights only.  num_changed: optional device int64. */
+pv_status pv_reencode_scalar(pv_ctx *ctx, int64_t out_features, int64_t in_features,
+                             int32_t block_size, int32_t nbits, const float *T, const float *scales,
+                             const float *zeros, const int32_t *weight_idx, int64_t k,
+                             uint8_t *codes, int64_t *num_changed /* NULL ok */);
+
 /* ---- instrumentation (does not change results) ------------------------- */
 
 /* Search strategy for M == 1: 0 = automatic (matrix-core filter + exact

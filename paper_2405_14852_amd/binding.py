@@ -77,6 +77,8 @@ def load_library():
     lib.pv_reencode_groups.argtypes = [vp, lp, vp, vp, vp, vp, i64, i32, vp, vp]
     lib.pv_dequantize.argtypes = [vp, lp, vp, vp, vp, vp]
     lib.pv_codebook_grads.argtypes = [vp, lp, vp, vp, vp, vp, vp, vp]
+    lib.pv_dequantize_scalar.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp, vp]
+    lib.pv_reencode_scalar.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp, vp, i64, vp, vp]
     lib.pv_reencode_trust_ratio.argtypes = [vp, lp, vp, vp, vp, vp, i64, i64, ctypes.c_double, i32,
                                             vp, vp, vp, vp]
     lib.pv_set_search_mode.argtypes = [vp, ctypes.c_int]
@@ -87,7 +89,7 @@ def load_library():
     lib.pv_reencode_stats.argtypes = [vp, ctypes.POINTER(i64)]
     for name in ("pv_create", "pv_encode_targets", "pv_encode_targets_adam", "pv_select_topk_groups",
                  "pv_encode_targets_select", "pv_reencode_groups", "pv_reencode_trust_ratio",
-                 "pv_codebook_grads",
+                 "pv_codebook_grads", "pv_dequantize_scalar", "pv_reencode_scalar",
                  "pv_dequantize", "pv_set_search_mode", "pv_timing_enable", "pv_timing_reset",
                  "pv_timing_read", "pv_reencode_stats"):
         getattr(lib, name).restype = ctypes.c_int
@@ -204,6 +206,23 @@ class PVContext:
             _dev_ptr(scales, torch.float32, "scales"),
             _dev_ptr(grad_codebooks, torch.float32, "grad_codebooks"),
             _dev_ptr(grad_scales, torch.float32, "grad_scales", allow_none=True)))
+
+    def pv_dequantize_scalar(self, out_features: int, in_features: int, block_size: int, nbits: int,
+                             codes, scales, zeros, W_out):
+        self._check(self._lib.pv_dequantize_scalar(
+            self._h, int(out_features), int(in_features), int(block_size), int(nbits),
+            _dev_ptr(codes, torch.uint8, "codes"), _dev_ptr(scales, torch.float32, "scales"),
+            _dev_ptr(zeros, torch.float32, "zeros"), _dev_ptr(W_out, torch.float32, "W_out")))
+
+    def pv_reencode_scalar(self, out_features: int, in_features: int, block_size: int, nbits: int,
+                           T, scales, zeros, weight_idx, k: int, codes, num_changed=None):
+        self._check(self._lib.pv_reencode_scalar(
+            self._h, int(out_features), int(in_features), int(block_size), int(nbits),
+            _dev_ptr(T, torch.float32, "T"), _dev_ptr(scales, torch.float32, "scales"),
+            _dev_ptr(zeros, torch.float32, "zeros"),
+            _dev_ptr(weight_idx, torch.int32, "weight_idx", allow_none=(k == 0)), int(k),
+            _dev_ptr(codes, torch.uint8, "codes"),
+            _dev_ptr(num_changed, torch.int64, "num_changed", allow_none=True)))
 
     def pv_dequantize(self, layout: Layout, codes, codebooks, scales, W_out):
         lay = layout.c()

@@ -344,6 +344,57 @@ extern "C" pv_status pv_dequantize(pv_ctx *ctx, const pv_layout *l, const uint16
     return pv_launch_dequantize(ctx, l, codes, codebooks, scales, W_out);
 }
 
+// ---------------------------------------------------------------- scalar grids
+
+static pv_status check_scalar(pv_ctx *ctx, int64_t out_features, int64_t in_features,
+                              int32_t block_size, int32_t nbits)
+{
+    if (out_features < 0 || in_features < 0) return pv_fail(ctx, PV_ERR_SHAPE, "negative matrix shape");
+    if (block_size < 1 || in_features % block_size != 0)
+        return pv_fail(ctx, PV_ERR_SHAPE, "in_features %lld is not a multiple of block_size %d",
+                       (long long)in_features, block_size);
+    if (nbits < 1 || nbits > 8) return pv_fail(ctx, PV_ERR_SHAPE, "nbits %d not in 1..8", nbits);
+    if (out_features > 0 && in_features > (INT64_C(0x7fffffff) - 1) / out_features)
+        return pv_fail(ctx, PV_ERR_SHAPE, "number of weights must be below 2^31");
+    return PV_OK;
+}
+
+extern "C" pv_status pv_dequantize_scalar(pv_ctx *ctx, int64_t out_features, int64_t in_features,
+                                          int32_t block_size, int32_t nbits, const uint8_t *codes,
+                                          const float *scales, const float *zeros, float *W_out)
+{
+    if (!ctx) return PV_ERR_INVALID_ARG;
+    pv_status st = check_scalar(ctx, out_features, in_features, block_size, nbits);
+    if (st != PV_OK) return st;
+    if (!codes || !scales || !zeros || !W_out)
+        return pv_fail(ctx, PV_ERR_INVALID_ARG, "NULL tensor pointer");
+    if (misaligned(W_out) || (reinterpret_cast<uintptr_t>(codes) & 3u))
+        return pv_fail(ctx, PV_ERR_INVALID_ARG, "W_out must be 16-byte and codes 4-byte aligned");
+    if (out_features * in_features == 0) return PV_OK;
+    PV_HIP(ctx, hipSetDevice(ctx->device));
+    return pv_launch_dequantize_scalar(ctx, out_features, in_features, block_size, codes, scales, zeros,
+                                       W_out);
+}
+
+extern "C" pv_status pv_reencode_scalar(pv_ctx *ctx, int64_t out_features, int64_t in_features,
+                                        int32_t block_size, int32_t nbits, const float *T,
+                                        const float *scales, const float *zeros,
+                                        const int32_t *weight_idx, int64_t k, uint8_t *codes,
+                                        int64_t *num_changed)
+{
+    if (!ctx) return PV_ERR_INVALID_ARG;
+    pv_status st = check_scalar(ctx, out_features, in_features, block_size, nbits);
+    if (st != PV_OK) return st;
+    if (k < 0 || k > out_features * in_features)
+        return pv_fail(ctx, PV_ERR_INVALID_ARG, "k = %lld outside [0, %lld]", (long long)k,
+                       (long long)(out_features * in_features));
+    if (!T || !scales || !zeros || !codes) return pv_fail(ctx, PV_ERR_INVALID_ARG, "NULL tensor pointer");
+    if (k > 0 && !weight_idx) return pv_fail(ctx, PV_ERR_INVALID_ARG, "weight_idx is NULL");
+    PV_HIP(ctx, hipSetDevice(ctx->device));
+    return pv_launch_reencode_scalar(ctx, out_features, in_features, block_size, nbits, T, scales, zeros,
+                                     weight_idx, k, codes, num_changed);
+}
+
 // ---------------------------------------------------------------- instrumentation
 
 extern "C" pv_status pv_set_search_mode(pv_ctx *ctx, int mode)

@@ -116,6 +116,13 @@ pv_status pv_reencode_dispatch(pv_ctx *ctx, const pv_layout *l, const float *T,
                                const float *codebooks, const float *scales,
                                const int32_t *group_idx, int64_t k, int32_t beam_width,
                                uint16_t *codes, int64_t *num_changed);
+pv_status pv_launch_dequantize_scalar(pv_ctx *ctx, int64_t out_features, int64_t in_features, int blk,
+                                      const uint8_t *codes, const float *scales, const float *zeros,
+                                      float *W_out);
+pv_status pv_launch_reencode_scalar(pv_ctx *ctx, int64_t out_features, int64_t in_features, int blk,
+                                    int nbits, const float *T, const float *scales,
+                                    const float *zeros, const int32_t *weight_idx, int64_t k,
+                                    uint8_t *codes, int64_t *num_changed);
 pv_status pv_launch_codebook_grads(pv_ctx *ctx, const pv_layout *l, const float *G,
                                    const uint16_t *codes, const float *codebooks,
                                    const float *scales, float *grad_codebooks, float *grad_scales);
