@@ -148,7 +148,7 @@ def main() -> int:
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on exactly one GPU (--gpus 1); the path shards by "
-              "matrix or by rows with no exchange inside the V step, see DESIGN.md", file=sys.stderr)
+              "matrix or by rows with no exchange inside the V step", file=sys.stderr)
         return 2
 
     import numpy as np
