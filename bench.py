@@ -291,6 +291,8 @@ def main() -> int:
                             ("dequantize", 4.0 + 2.0 * M / g)):
         if name in kern:
             hbm[name + "_GBps"] = per_param * params / (kern[name]["avg_ms"] * 1e-3) / 1e9
+    if "select" in kern:   # the four radix / compaction launches each read the score array once
+        hbm["select_passes_GBps"] = 4 * 4.0 * (params / g) / (kern["select"]["avg_ms"] * 1e-3) / 1e9
 
     cpu = None
     if not args.no_cpu_baseline and args.path == "pstep":
