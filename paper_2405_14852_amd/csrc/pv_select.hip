@@ -3,8 +3,8 @@
 // score_n = sum_i (T[n,i] - W[n,i])^2 as an fp32 fused-multiply-add chain in
 // index order, so that every implementation of this rule gives the same bits.
 // Scores are non-negative floats, so their bit patterns order like unsigned
-// integers.  The k-th largest key is found by a 3-digit radix select (11 + 13 +
-// 8 bits, most significant first); groups above the threshold are taken, groups
+// integers.  The k-th largest key is found by a 3-digit radix select (11 + 12 +
+// 9 bits, most significant first); groups above the threshold are taken, groups
 // equal to it are taken lowest id first, and the ids are written in ascending
 // order through a two-level prefix sum.  Nothing returns to the host.
 //
@@ -31,9 +31,13 @@
 namespace {
 
 constexpr int kBlock = 256;
-constexpr int kBins = 8192;                    // digit 1: 13 mantissa bits (also the slot count of every histogram)
+#ifndef PV_MID_BITS
+#define PV_MID_BITS 12
+#endif
+constexpr int kMidBits = PV_MID_BITS;
+constexpr int kBins = 1 << kMidBits;            // digit 1: the next mantissa bits (also the slot count of every histogram, >= 2048)
 constexpr int kFirstBins = 2048;                // digit 0: sign, exponent, 2 mantissa bits
-constexpr int kLastBins = 256;                  // digit 2: the low 8 mantissa bits
+constexpr int kLastBins = 1 << (21 - kMidBits); // digit 2: the remaining low mantissa bits
 constexpr int kItems = 8;                      // groups per thread in the compaction kernels
 constexpr int kChunk = kBlock * kItems;        // groups per chunk there
 #ifndef PV_SEL_BLOCKS
@@ -43,7 +47,9 @@ constexpr int kMaxBlocks = PV_SEL_BLOCKS;      // persistent grid of the streami
 
 __device__ __forceinline__ int digit_of(unsigned key, int pass)
 {
-    return pass == 0 ? (int)(key >> 21) : pass == 1 ? (int)((key >> 8) & 8191u) : (int)(key & 255u);
+    return pass == 0 ? (int)(key >> 21)
+                     : pass == 1 ? (int)((key >> (21 - kMidBits)) & (unsigned)(kBins - 1))
+                                 : (int)(key & (unsigned)(kLastBins - 1));
 }
 
 // Add one count per valid lane to an LDS histogram.  Lanes of a wave that hit
@@ -96,12 +102,14 @@ __device__ __forceinline__ unsigned block_excl_scan(unsigned v, unsigned *tmp, u
 
 // Global histograms are stored so that the scan below reads them coalesced:
 // digit d of a `bins`-digit histogram has rank r = bins - 1 - d from the top and
-// lives at slot (r % 32) * 256 + r / 32; thread t of the scan owns ranks
-// [32 t, 32 t + 32), i.e. slots t, t + 256, ...  Every histogram occupies kBins slots.
+// lives at slot (r % kPer) * 256 + r / kPer with kPer = kBins / 256 ranks per scan thread;
+// thread t of the scan owns ranks [kPer t, kPer t + kPer), i.e. slots t, t + 256, ...
+// Every histogram occupies kBins slots.
+constexpr int kPer = kBins / kBlock;
 __device__ __forceinline__ int hist_slot(int digit, int bins)
 {
     const int r = bins - 1 - digit;
-    return (r & 31) * kBlock + (r >> 5);
+    return (r % kPer) * kBlock + (r / kPer);
 }
 
 // Given a histogram of `bins` digits and the rank `kk` (1-based, counted from the
@@ -111,7 +119,7 @@ __device__ __forceinline__ int hist_slot(int digit, int bins)
 __device__ void pick_digit(const unsigned *__restrict__ ghist, int bins, unsigned kk,
                            unsigned *tmp, int *digit, unsigned *kk_rem)
 {
-    constexpr int per = kBins / kBlock;  // 32 ranks per thread; thread 0 owns the TOP digits
+    constexpr int per = kPer;            // ranks per thread; thread 0 owns the TOP digits
     const int tid = threadIdx.x;
     unsigned cnt[per];
     unsigned sum = 0;
@@ -419,7 +427,7 @@ __global__ __launch_bounds__(kBlock) void k_chunk_counts(const float *__restrict
     int d2;
     unsigned kk;
     pick_digit(hist_all + 2 * kBins, kLastBins, state[7], tmp, &d2, &kk);
-    const unsigned thr = ((unsigned)d0 << 21) | ((unsigned)d1 << 8) | (unsigned)d2;
+    const unsigned thr = ((unsigned)d0 << 21) | ((unsigned)d1 << (21 - kMidBits)) | (unsigned)d2;
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         state[0] = thr;
         state[1] = kk;  // how many keys equal to thr are selected (lowest ids first)
