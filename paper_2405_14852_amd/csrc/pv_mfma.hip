@@ -512,6 +512,32 @@ __device__ __forceinline__ double exact_obj(const float *__restrict__ cw, float 
     return obj;
 }
 
+// A group the re-rank kernel could not decide alone: the partitions whose codewords must all
+// be evaluated (bit p = partition p), and the best candidate found so far.
+struct fb_rec_t {
+    double obj;
+    unsigned long long mask;
+    int idx;
+    int n;
+};
+
+// the same objective on a codeword already in registers
+template <int G>
+__device__ __forceinline__ double exact_obj_v(const pv_f4 (&c)[G / 4], float s, const float *t)
+{
+    double obj = 0.0;
+#pragma unroll
+    for (int v4 = 0; v4 < G / 4; ++v4) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            double acc = (double)c[v4][e];
+            double r = fma((double)s, acc, -(double)t[v4 * 4 + e]);
+            obj = obj + r * r;
+        }
+    }
+    return obj;
+}
+
 // 16 lanes ("team") per selected group; lane q scores codeword q of a half tile.
 template <int G>
 __global__ __launch_bounds__(kBlock) void k_rerank(
@@ -519,7 +545,7 @@ __global__ __launch_bounds__(kBlock) void k_rerank(
     const float *__restrict__ scales, const int32_t *__restrict__ group_idx, int k,
     const uint2 *__restrict__ partials, int P, int per_half, const float *__restrict__ x_meta,
     const unsigned *__restrict__ cb_meta, uint16_t *__restrict__ codes,
-    unsigned *__restrict__ block_counts, int32_t *__restrict__ fb_list,
+    unsigned *__restrict__ block_counts, fb_rec_t *__restrict__ fb_rec,
     unsigned *__restrict__ fb_count, int gpr, int N, int nbits)
 {
     __shared__ unsigned s_cnt[3];   // groups decided here, codes changed, candidates evaluated
@@ -531,8 +557,15 @@ __global__ __launch_bounds__(kBlock) void k_rerank(
     bool live = n >= 0 && n < N;             // whole 16-lane teams agree on every branch below
     pv_f4 meta = {0.f, 0.f, 0.f, 1.f};
     if (live) meta = reinterpret_cast<const pv_f4 *>(x_meta)[j];
-    if (live && meta.w != 0.0f) {            // the filter was skipped for this group
-        if (q == 0) fb_list[atomicAdd(fb_count, 1u)] = n;
+    if (live && meta.w != 0.0f) {            // the filter was skipped for this group: every partition
+        if (q == 0) {
+            fb_rec_t r;
+            r.obj = __builtin_huge_val();
+            r.mask = P >= 64 ? ~0ull : ((1ull << P) - 1ull);
+            r.idx = 0x7fffffff;
+            r.n = n;
+            fb_rec[atomicAdd(fb_count, 1u)] = r;
+        }
         live = false;
     }
     if (live) {
@@ -615,40 +648,50 @@ __global__ __launch_bounds__(kBlock) void k_rerank(
         const double reach = dstar + dC + (double)meta.z;
         const double vcut_d = (reach * reach + (double)meta.x + (double)meta.y) * (1.0 + 1e-6);
         const float vcut = __double2float_ru(vcut_d);
-        bool uncertain = !(vcut_d < 3.0e38);          // also true for NaN
+        const bool no_bound = !(vcut_d < 3.0e38);     // also true for NaN: nothing can be excluded
         unsigned pending = 0;                         // bit u: rec[u].x needs evaluation
+        unsigned long long open = 0;                  // partitions with a second key below vcut
 #pragma unroll
         for (int u = 0; u < kMaxRec; ++u) {
             int p = q + 16 * u;
             if (p < P) {
-                if (__uint_as_float(rec[u].y & ~kTileMask) < vcut) uncertain = true;
+                if (no_bound || __uint_as_float(rec[u].y & ~kTileMask) < vcut) open |= 1ull << p;
                 if (p != best_p && __uint_as_float(rec[u].x & ~kTileMask) < vcut) pending |= 1u << u;
             }
         }
-        const int team_shift = (threadIdx.x & 63) & ~15;
-        const unsigned long long unc = __ballot(uncertain);
-        if ((unc >> team_shift) & 0xFFFFull) {
-            if (q == 0) fb_list[atomicAdd(fb_count, 1u)] = n;
-        } else {
-            unsigned extra = 0;
-            for (;;) {
-                const unsigned long long pb = __ballot(pending != 0);
-                const unsigned team = (unsigned)((pb >> team_shift) & 0xFFFFull);
-                if (!team) break;
-                const int src = __ffs(team) - 1;      // lane of the team with work
-                const unsigned their = __shfl(pending, src, 16);
-                const int u = __ffs(their) - 1;
-                unsigned key = 0;
 #pragma unroll
-                for (int uu = 0; uu < kMaxRec; ++uu)
-                    if (uu == u) key = rec[uu].x;
-                key = __shfl(key, src, 16);
-                eval_half_tile(key, src + 16 * u, mine);
-                if (q == src) pending &= ~(1u << u);
-                ++extra;
-            }
-            const cand_t win = team_min(mine);
-            if (q == 0) {
+        for (int m = 8; m > 0; m >>= 1) open |= __shfl_xor(open, m, 16);
+        const int team_shift = (threadIdx.x & 63) & ~15;
+        // the best key of every other partition below vcut: its half tile is evaluated here
+        unsigned extra = 0;
+        for (;;) {
+            const unsigned long long pb = __ballot(pending != 0);
+            const unsigned team = (unsigned)((pb >> team_shift) & 0xFFFFull);
+            if (!team) break;
+            const int src = __ffs(team) - 1;      // lane of the team with work
+            const unsigned their = __shfl(pending, src, 16);
+            const int u = __ffs(their) - 1;
+            unsigned key = 0;
+#pragma unroll
+            for (int uu = 0; uu < kMaxRec; ++uu)
+                if (uu == u) key = rec[uu].x;
+            key = __shfl(key, src, 16);
+            eval_half_tile(key, src + 16 * u, mine);
+            if (q == src) pending &= ~(1u << u);
+            ++extra;
+        }
+        const cand_t win = team_min(mine);
+        if (q == 0) {
+            if (open) {
+                // a partition may hide further codewords below vcut: all of its codewords are
+                // evaluated by the partition scan, which also takes the decision
+                fb_rec_t r;
+                r.obj = win.obj;
+                r.mask = open;
+                r.idx = win.idx;
+                r.n = n;
+                fb_rec[atomicAdd(fb_count, 1u)] = r;
+            } else {
                 int pick = win.idx;
                 if (o_prev <= win.obj || pick == 0x7fffffff) pick = prev;
                 if (pick != prev) {
@@ -656,13 +699,160 @@ __global__ __launch_bounds__(kBlock) void k_rerank(
                     atomicAdd(&s_cnt[1], 1u);
                 }
                 atomicAdd(&s_cnt[0], 1u);
-                atomicAdd(&s_cnt[2], 16u * (1u + extra) + 1u);
             }
+            atomicAdd(&s_cnt[2], 16u * (1u + extra) + 1u);
         }
     }
     __syncthreads();
     // per-block totals; the last kernel of the call adds them up (no same-address atomics here)
     if (threadIdx.x < 3) block_counts[3 * blockIdx.x + threadIdx.x] = s_cnt[threadIdx.x];
+}
+
+// One block per undecided group: every codeword of the group's open partitions is evaluated
+// exactly (thread = one codeword position q of 16 tile slots per pass), the lexicographic
+// minimum joins the candidate the re-rank kernel found, and the usual rule decides: the
+// previous code on an exact tie, else the lowest index.  Partition p = (codeword split,
+// half wave, tile residue) as the scoring kernel numbers them.  As the last kernel of a call
+// it also clears the filter's codebook statistics and adds up the re-rank counters.
+template <int G>
+__global__ __launch_bounds__(kBlock) void k_partition_scan(
+    const float *__restrict__ T, const float *__restrict__ codebook,
+    const float *__restrict__ scales, const fb_rec_t *__restrict__ fb_rec,
+    const unsigned *__restrict__ fb_count, uint16_t *__restrict__ codes, int ntiles, int nsplit,
+    int per_half, int gpr, int nbits, unsigned long long *__restrict__ num_changed,
+    unsigned long long *__restrict__ stats, unsigned *__restrict__ reset_meta,
+    const unsigned *__restrict__ rr_counts, int rr_blocks)
+{
+    __shared__ double s_obj[kBlock / 64];
+    __shared__ int s_idx[kBlock / 64];
+    const unsigned count = *fb_count;
+    const int csize = 1 << nbits;
+    const int q = threadIdx.x & 15, slot = threadIdx.x >> 4;
+    constexpr int kSlots = kBlock / 16;
+    const int stride = per_half == 1 ? 1 : kResidues;     // merged records cover every residue
+    unsigned changed = 0;
+    for (unsigned item = blockIdx.x; item < count; item += gridDim.x) {
+        const fb_rec_t rec = fb_rec[item];
+        const int n = rec.n;
+        const float s = scales[n / gpr];
+        float t[G];
+        {
+            const pv_f4 *t4 = reinterpret_cast<const pv_f4 *>(T + (int64_t)n * G);
+#pragma unroll
+            for (int v4 = 0; v4 < G / 4; ++v4) {
+                pv_f4 v = t4[v4];
+                t[v4 * 4 + 0] = v.x;
+                t[v4 * 4 + 1] = v.y;
+                t[v4 * 4 + 2] = v.z;
+                t[v4 * 4 + 3] = v.w;
+            }
+        }
+        const int prev = codes[n] & (csize - 1);
+        cand_t mine;
+        mine.obj = __builtin_huge_val();
+        mine.idx = 0x7fffffff;
+        for (unsigned long long left = rec.mask; left; left &= left - 1) {   // uniform over the block
+            const int p = __ffsll((long long)left) - 1;
+            const int hw = (p / per_half) & 1;
+            const int split = p / (2 * per_half);
+            const int t_begin = (int)((int64_t)split * ntiles / nsplit);
+            const int t_end = (int)((int64_t)(split + 1) * ntiles / nsplit);
+            const int first = t_begin + (per_half == 1 ? 0 : p % per_half);
+            // kAhead codewords per thread in flight (their loads first, then the arithmetic in
+            // ascending codeword order)
+            constexpr int kAhead = G <= 8 ? 4 : 2;
+            const int step = kSlots * stride;
+            for (int tile = first + slot * stride; tile < t_end; tile += step * kAhead) {
+                pv_f4 c[kAhead][G / 4];
+#pragma unroll
+                for (int u = 0; u < kAhead; ++u) {
+                    const int tu = tile + u * step < t_end ? tile + u * step : tile;
+                    const pv_f4 *c4 = reinterpret_cast<const pv_f4 *>(
+                        codebook + (int64_t)(tu * 32 + hw * 16 + q) * G);
+#pragma unroll
+                    for (int v4 = 0; v4 < G / 4; ++v4) c[u][v4] = c4[v4];
+                }
+#pragma unroll
+                for (int u = 0; u < kAhead; ++u) {
+                    if (tile + u * step < t_end) {
+                        const int cw = (tile + u * step) * 32 + hw * 16 + q;
+                        const double o = exact_obj_v<G>(c[u], s, t);
+                        if (cand_better(o, cw, mine.obj, mine.idx)) {
+                            mine.obj = o;
+                            mine.idx = cw;
+                        }
+                    }
+                }
+            }
+        }
+        // block-wide lexicographic minimum
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
+            double o = __shfl_down(mine.obj, off);
+            int i = __shfl_down(mine.idx, off);
+            if (cand_better(o, i, mine.obj, mine.idx)) {
+                mine.obj = o;
+                mine.idx = i;
+            }
+        }
+        __syncthreads();
+        if ((threadIdx.x & 63) == 0) {
+            s_obj[threadIdx.x >> 6] = mine.obj;
+            s_idx[threadIdx.x >> 6] = mine.idx;
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            cand_t win;
+            win.obj = rec.obj;
+            win.idx = rec.idx;
+            for (int w = 0; w < kBlock / 64; ++w)
+                if (cand_better(s_obj[w], s_idx[w], win.obj, win.idx)) {
+                    win.obj = s_obj[w];
+                    win.idx = s_idx[w];
+                }
+            const double o_prev = exact_obj<G>(codebook + (int64_t)prev * G, s, t);
+            int pick = win.idx;
+            if (o_prev <= win.obj || pick == 0x7fffffff) pick = prev;
+            if (pick != prev) {
+                codes[n] = (uint16_t)pick;
+                ++changed;
+            }
+        }
+    }
+    if (threadIdx.x == 0 && changed && num_changed) atomicAdd(num_changed, (unsigned long long)changed);
+    if (blockIdx.x == 0 && threadIdx.x == 0 && count) atomicAdd(&stats[1], (unsigned long long)count);
+    // the filter's codebook statistics are dead once this (last) kernel of a call runs
+    if (blockIdx.x == 0 && threadIdx.x < 8) reset_meta[threadIdx.x] = 0u;
+    // fold the re-rank kernel's per-block counters (decided, changed, candidates) into the totals
+    if (blockIdx.x == gridDim.x - 1) {
+        unsigned long long c0 = 0, c1 = 0, c2 = 0;
+        constexpr int kU = 4;            // independent loads in flight per thread
+        for (int b0 = threadIdx.x; b0 < rr_blocks; b0 += kBlock * kU) {
+            unsigned v[kU][3];
+#pragma unroll
+            for (int u = 0; u < kU; ++u) {
+                const int b = b0 + u * kBlock;
+#pragma unroll
+                for (int e = 0; e < 3; ++e) v[u][e] = b < rr_blocks ? rr_counts[3 * b + e] : 0u;
+            }
+#pragma unroll
+            for (int u = 0; u < kU; ++u) {
+                c0 += v[u][0];
+                c1 += v[u][1];
+                c2 += v[u][2];
+            }
+        }
+        for (int off = 32; off > 0; off >>= 1) {
+            c0 += __shfl_down(c0, off);
+            c1 += __shfl_down(c1, off);
+            c2 += __shfl_down(c2, off);
+        }
+        if ((threadIdx.x & 63) == 0) {
+            if (c0) atomicAdd(&stats[0], c0);
+            if (c2) atomicAdd(&stats[2], c2);
+            if (c1 && num_changed) atomicAdd(num_changed, c1);
+        }
+    }
 }
 
 __global__ void k_fill_u32(unsigned *p, int n, unsigned v)
@@ -728,7 +918,8 @@ pv_status pv_launch_mfma_search(pv_ctx *ctx, const pv_layout *l, const float *T,
     if ((st = pv_ensure(ctx, ctx->x_f16, (size_t)p.k_pad * p.NK * 32)) != PV_OK) return st;
     if ((st = pv_ensure(ctx, ctx->x_meta, (size_t)p.k_pad * 4 * sizeof(float))) != PV_OK) return st;
     if ((st = pv_ensure(ctx, ctx->partials, (size_t)p.k_pad * p.P * sizeof(uint2))) != PV_OK) return st;
-    if ((st = pv_ensure(ctx, ctx->fb_list, ((size_t)k + 4) * sizeof(int32_t))) != PV_OK) return st;
+    if ((st = pv_ensure(ctx, ctx->fb_list, 4 * sizeof(int32_t) + (size_t)k * sizeof(fb_rec_t) + 64)) != PV_OK)
+        return st;
     const int rr_blocks = (int)((k * 16 + kBlock - 1) / kBlock);
     if ((st = pv_ensure(ctx, ctx->rr_counts, (size_t)rr_blocks * 3 * sizeof(unsigned))) != PV_OK) return st;
     unsigned *rr_counts = static_cast<unsigned *>(ctx->rr_counts.ptr);
@@ -737,8 +928,8 @@ pv_status pv_launch_mfma_search(pv_ctx *ctx, const pv_layout *l, const float *T,
     unsigned *cb_meta = static_cast<unsigned *>(ctx->cb_meta.ptr);
     float *x_meta = static_cast<float *>(ctx->x_meta.ptr);
     uint2 *partials = static_cast<uint2 *>(ctx->partials.ptr);
-    int32_t *fb_list = static_cast<int32_t *>(ctx->fb_list.ptr) + 4;
-    unsigned *fb_count = reinterpret_cast<unsigned *>(ctx->fb_list.ptr);
+    unsigned *fb_count = reinterpret_cast<unsigned *>(ctx->fb_list.ptr);       // 4 counters, then the records
+    fb_rec_t *fb_rec = reinterpret_cast<fb_rec_t *>(static_cast<char *>(ctx->fb_list.ptr) + 16);
     unsigned long long *stats = static_cast<unsigned long long *>(ctx->stats.ptr);
     hipStream_t sm = ctx->stream;
     if (ctx->meta_dirty) {   // a previous call did not run to its last kernel
@@ -785,18 +976,26 @@ pv_status pv_launch_mfma_search(pv_ctx *ctx, const pv_layout *l, const float *T,
         if (g == 8)
             hipLaunchKernelGGL(k_rerank<8>, rgrid, dim3(kBlock), 0, sm, T, codebooks, scales,
                                group_idx, (int)k, partials, p.P, p.per_half, x_meta, cb_meta, codes,
-                               rr_counts, fb_list, fb_count, gpr, N, l->nbits);
+                               rr_counts, fb_rec, fb_count, gpr, N, l->nbits);
         else
             hipLaunchKernelGGL(k_rerank<16>, rgrid, dim3(kBlock), 0, sm, T, codebooks, scales,
                                group_idx, (int)k, partials, p.P, p.per_half, x_meta, cb_meta, codes,
-                               rr_counts, fb_list, fb_count, gpr, N, l->nbits);
+                               rr_counts, fb_rec, fb_count, gpr, N, l->nbits);
+    }
+    {
+        pv_timed t(ctx, PV_K_EXACT_SCAN);
+        const unsigned sblocks = (unsigned)(k < 2048 ? k : 2048);
+        auto nc = reinterpret_cast<unsigned long long *>(num_changed);
+        if (g == 8)
+            hipLaunchKernelGGL(k_partition_scan<8>, dim3(sblocks), dim3(kBlock), 0, sm, T, codebooks,
+                               scales, fb_rec, fb_count, codes, p.ntiles, p.nsplit, p.per_half, gpr,
+                               l->nbits, nc, stats, cb_meta, rr_counts, rr_blocks);
+        else
+            hipLaunchKernelGGL(k_partition_scan<16>, dim3(sblocks), dim3(kBlock), 0, sm, T, codebooks,
+                               scales, fb_rec, fb_count, codes, p.ntiles, p.nsplit, p.per_half, gpr,
+                               l->nbits, nc, stats, cb_meta, rr_counts, rr_blocks);
     }
     PV_HIP(ctx, hipGetLastError());
-    pv_status fin = pv_launch_exact_scan_split(ctx, l, T, codebooks, scales, fb_list, fb_count, k,
-                                               codes, num_changed,
-                                               reinterpret_cast<int64_t *>(stats + 1), cb_meta,
-                                               rr_counts, rr_blocks,
-                                               reinterpret_cast<int64_t *>(stats));
-    if (fin == PV_OK) ctx->meta_dirty = false;
-    return fin;
+    ctx->meta_dirty = false;
+    return PV_OK;
 }
