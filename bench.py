@@ -28,7 +28,7 @@ PEAK_F64 = 78.6          # TFLOP/s fp64 vector (256 CU x 4 SIMD x 16 lanes x 2 (
 
 # HBM bytes per launch of the dominant kernel, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this
 # same command (profiles/c2_4096x4096_1x16_hbm_traffic.txt; FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 KiB)
-MEASURED_TRAFFIC_BYTES = {("k_score_mfma", "c2_4096x4096_1x16"): (10991.7 * 2.0 + 10718.2) * 1024.0}
+MEASURED_TRAFFIC_BYTES = {("k_score_mfma", "c2_4096x4096_1x16"): (10890.0 * 2.0 + 10744.1) * 1024.0}
 
 
 def run_stack(args) -> int:
