@@ -142,8 +142,8 @@ def main() -> int:
                          "all k groups of the workload are candidates); pstep: one call of "
                          "pv_codebook_grads (gradients of codebooks and scales) per step")
     ap.add_argument("--adam", action="store_true",
-                    help="targets from one Adam update (pv_encode_targets_adam, beta 0.9/0.95, lr 3e-3) "
-                         "followed by pv_select_topk_groups, instead of the plain fused call")
+                    help="targets from one Adam update and selection by its size in one sweep "
+                         "(pv_encode_targets_adam_select, beta 0.9/0.95, lr 3e-3)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -213,9 +213,8 @@ def main() -> int:
         ctx.pv_dequantize(lay, codes, cb, sc, Wq)
         if args.adam:
             adam_step[0] += 1
-            ctx.pv_encode_targets_adam(lay, W, G, m_adam, v_adam, adam_step[0], 3e-3, 0.9, 0.95,
-                                       1e-8, T)
-            ctx.pv_select_topk_groups(lay, T, W, k, idx)
+            ctx.pv_encode_targets_adam_select(lay, W, G, m_adam, v_adam, adam_step[0], 3e-3, 0.9,
+                                              0.95, 1e-8, T, k, idx)
         elif args.separate_calls:
             ctx.pv_encode_targets(lay, W, G, wl.alpha, T)
             ctx.pv_select_topk_groups(lay, T, W, k, idx)
@@ -278,7 +277,7 @@ def main() -> int:
         roofline = {"kernel": "k_" + dominant, "bound": "alu", "achieved": a, "peak": PEAK_F64,
                     "unit": "TFLOP/s", "frac": a / PEAK_F64, "traffic": None}
     else:
-        per_param = {"encode_targets": 28.0 if args.adam else 12.0 + (0.0 if args.separate_calls else 4.0 / g),
+        per_param = {"encode_targets": 28.0 + 4.0 / g if args.adam else 12.0 + (0.0 if args.separate_calls else 4.0 / g),
                      "group_scores": 8.0 + 4.0 / g,
                      "dequantize": 4.0 + 2.0 * M / g}.get(dominant, 0.0)
         a = per_param * params / (kern[dominant]["avg_ms"] * 1e-3) / 1e9
@@ -286,7 +285,7 @@ def main() -> int:
                     "unit": "GB/s", "frac": a / PEAK_HBM, "traffic": None}
 
     hbm = {}
-    for name, per_param in (("encode_targets", 28.0 if args.adam else 12.0 + (0.0 if args.separate_calls else 4.0 / g)),
+    for name, per_param in (("encode_targets", 28.0 + 4.0 / g if args.adam else 12.0 + (0.0 if args.separate_calls else 4.0 / g)),
                             ("group_scores", 8.0 + 4.0 / g),
                             ("dequantize", 4.0 + 2.0 * M / g)):
         if name in kern:
@@ -356,7 +355,7 @@ def main() -> int:
                    "in_features": L.in_features, "group_size": g, "num_codebooks": M, "nbits": B,
                    "tau": wl.tau, "k_selected": k, "beam_width": wl.beam_width,
                    "search_mode": args.search_mode, "path": args.path,
-                   "calls": "adam targets + select" if args.adam else
+                   "calls": "fused adam targets+select" if args.adam else
                             "separate" if args.separate_calls else "fused targets+select"},
         "roofline": roofline,
         "cpu_baseline": cpu,

@@ -99,6 +99,15 @@ pv_status pv_encode_targets_select(pv_ctx *ctx, const pv_layout *layout, const f
                                    const float *G, float alpha, float *T, int64_t k,
                                    int32_t *out_idx, float *group_scores);
 
+/* pv_encode_targets_adam followed by pv_select_topk_groups as one sweep (Sec. 3.4: the
+ * subspace is chosen by the size of the Adam update): m, v and T are written, the scores come
+ * from the registers that hold T and W.  Outputs are bit-identical to the two calls in
+ * sequence.  T may alias G exactly; T, W, m, v must be distinct. */
+pv_status pv_encode_targets_adam_select(pv_ctx *ctx, const pv_layout *layout, const float *W,
+                                        const float *G, float *m, float *v, int64_t step, float lr,
+                                        float beta1, float beta2, float eps, float *T, int64_t k,
+                                        int32_t *out_idx, float *group_scores /* NULL ok */);
+
 /* Eq. 7 argmin restricted to the listed groups (Alg. 3 last line, "find_nearest"):
  * for each listed group with target t (g values of T), row scale s and current
  * code tuple p, minimise  obj(b) = || s * sum_m codebooks[m, b_m, :] - t ||^2

@@ -73,6 +73,8 @@ def load_library():
     lib.pv_encode_targets.argtypes = [vp, lp, vp, vp, f32, vp]
     lib.pv_encode_targets_adam.argtypes = [vp, lp, vp, vp, vp, vp, i64, f32, f32, f32, f32, vp]
     lib.pv_select_topk_groups.argtypes = [vp, lp, vp, vp, i64, vp, vp]
+    lib.pv_encode_targets_adam_select.argtypes = [vp, lp, vp, vp, vp, vp, i64, f32, f32, f32, f32, vp,
+                                                  i64, vp, vp]
     lib.pv_encode_targets_select.argtypes = [vp, lp, vp, vp, f32, vp, i64, vp, vp]
     lib.pv_reencode_groups.argtypes = [vp, lp, vp, vp, vp, vp, i64, i32, vp, vp]
     lib.pv_dequantize.argtypes = [vp, lp, vp, vp, vp, vp]
@@ -88,6 +90,7 @@ def load_library():
                                    ctypes.POINTER(i64)]
     lib.pv_reencode_stats.argtypes = [vp, ctypes.POINTER(i64)]
     for name in ("pv_create", "pv_encode_targets", "pv_encode_targets_adam", "pv_select_topk_groups",
+                 "pv_encode_targets_adam_select",
                  "pv_encode_targets_select", "pv_reencode_groups", "pv_reencode_trust_ratio",
                  "pv_codebook_grads", "pv_dequantize_scalar", "pv_reencode_scalar",
                  "pv_dequantize", "pv_set_search_mode", "pv_timing_enable", "pv_timing_reset",
@@ -155,6 +158,18 @@ class PVContext:
             _dev_ptr(G, torch.float32, "G"), _dev_ptr(m, torch.float32, "m"),
             _dev_ptr(v, torch.float32, "v"), int(step), float(lr), float(beta1), float(beta2),
             float(eps), _dev_ptr(T, torch.float32, "T")))
+
+    def pv_encode_targets_adam_select(self, layout: Layout, W, G, m, v, step: int, lr: float,
+                                      beta1: float, beta2: float, eps: float, T, k: int, out_idx,
+                                      group_scores=None):
+        lay = layout.c()
+        self._check(self._lib.pv_encode_targets_adam_select(
+            self._h, ctypes.byref(lay), _dev_ptr(W, torch.float32, "W"),
+            _dev_ptr(G, torch.float32, "G"), _dev_ptr(m, torch.float32, "m"),
+            _dev_ptr(v, torch.float32, "v"), int(step), float(lr), float(beta1), float(beta2),
+            float(eps), _dev_ptr(T, torch.float32, "T"), int(k),
+            _dev_ptr(out_idx, torch.int32, "out_idx", allow_none=(k == 0)),
+            _dev_ptr(group_scores, torch.float32, "group_scores", allow_none=True)))
 
     def pv_select_topk_groups(self, layout: Layout, T, W, k: int, out_idx, group_scores=None):
         lay = layout.c()

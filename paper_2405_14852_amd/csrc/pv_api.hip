@@ -172,6 +172,44 @@ extern "C" pv_status pv_encode_targets_adam(pv_ctx *ctx, const pv_layout *l, con
     return pv_launch_encode_targets_adam(ctx, W, G, m, v, step, lr, beta1, beta2, eps, T, n);
 }
 
+extern "C" pv_status pv_encode_targets_adam_select(pv_ctx *ctx, const pv_layout *l, const float *W,
+                                                   const float *G, float *m, float *v, int64_t step,
+                                                   float lr, float beta1, float beta2, float eps,
+                                                   float *T, int64_t k, int32_t *out_idx,
+                                                   float *group_scores)
+{
+    if (!ctx) return PV_ERR_INVALID_ARG;
+    pv_status st = check_layout(ctx, l);
+    if (st != PV_OK) return st;
+    int64_t N = pv_num_groups(l);
+    if (k < 0 || k > N)
+        return pv_fail(ctx, PV_ERR_INVALID_ARG, "k = %lld outside [0, %lld]", (long long)k,
+                       (long long)N);
+    if (!W || !G || !m || !v || !T) return pv_fail(ctx, PV_ERR_INVALID_ARG, "NULL tensor pointer");
+    if (k > 0 && !out_idx) return pv_fail(ctx, PV_ERR_INVALID_ARG, "out_idx is NULL");
+    if (misaligned(W) || misaligned(G) || misaligned(m) || misaligned(v) || misaligned(T) ||
+        misaligned(group_scores))
+        return pv_fail(ctx, PV_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
+    if (step < 1) return pv_fail(ctx, PV_ERR_INVALID_ARG, "step must be >= 1");
+    if (!(beta1 >= 0.0f && beta1 < 1.0f) || !(beta2 >= 0.0f && beta2 < 1.0f))
+        return pv_fail(ctx, PV_ERR_INVALID_ARG, "beta1 and beta2 must lie in [0, 1)");
+    if (T == W || T == m || T == v || m == v)
+        return pv_fail(ctx, PV_ERR_INVALID_ARG, "T, W, m and v must be distinct buffers");
+    if (N == 0) return PV_OK;
+    PV_HIP(ctx, hipSetDevice(ctx->device));
+    const int g = l->group_size;
+    if (!(g == 4 || g == 8 || g == 16 || g == 32 || g == 64)) {
+        // no fused kernel for this group size: the two calls in sequence
+        st = pv_launch_encode_targets_adam(ctx, W, G, m, v, step, lr, beta1, beta2, eps, T,
+                                           l->out_features * l->in_features);
+        if (st != PV_OK) return st;
+        if (k == 0 && !group_scores) return PV_OK;
+        return pv_launch_select(ctx, l, T, W, k, out_idx, group_scores);
+    }
+    const pv_adam_t a = pv_make_adam(step, lr, beta1, beta2, eps);
+    return pv_launch_select(ctx, l, T, W, k, out_idx, group_scores, G, 0.0f, &a, m, v);
+}
+
 extern "C" pv_status pv_select_topk_groups(pv_ctx *ctx, const pv_layout *l, const float *T,
                                            const float *W, int64_t k, int32_t *out_idx,
                                            float *group_scores)

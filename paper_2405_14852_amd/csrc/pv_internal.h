@@ -77,6 +77,32 @@ static inline int64_t pv_num_groups(const pv_layout *l)
     return l->out_features * (l->in_features / l->group_size);
 }
 
+// ---------------------------------------------------------------- Adam direction (Sec. 3.4)
+// The gradient of Eq. 7 replaced by one Adam update.  Per element, in fp32 with one rounding
+// per operation written here (division and square root correctly rounded):
+//   m' = fma(b1, m, (1 - b1) * g)     v' = fma(b2, v, (1 - b2) * (g * g))
+//   T  = fma(-lr, (m' / c1) / (sqrt(v' / c2) + eps), W)
+// c1, c2: the bias corrections 1 - b^t, formed on the host in double and rounded once.
+struct pv_adam_t {
+    float lr, b1, b2, omb1, omb2, c1, c2, eps;
+};
+
+pv_adam_t pv_make_adam(int64_t step, float lr, float beta1, float beta2, float eps);
+
+#ifdef __HIPCC__
+__device__ __forceinline__ float pv_adam_one(float w, float g, float &m, float &v, const pv_adam_t &a)
+{
+    m = fmaf(a.b1, m, a.omb1 * g);
+    v = fmaf(a.b2, v, a.omb2 * (g * g));
+    // plain '/' and sqrtf compile to the correctly rounded sequences (the __fsqrt_rn
+    // intrinsic of this toolchain does not: it differs from IEEE in 14 % of random inputs)
+    const float mhat = m / a.c1;
+    const float vhat = v / a.c2;
+    const float upd = mhat / (sqrtf(vhat) + a.eps);
+    return fmaf(-a.lr, upd, w);
+}
+#endif
+
 // ---------------------------------------------------------------- launchers
 // (each enqueues on ctx->stream; arguments were validated by the caller)
 
@@ -87,9 +113,12 @@ pv_status pv_launch_encode_targets_adam(pv_ctx *ctx, const float *W, const float
                                         float eps, float *T, int64_t n);
 pv_status pv_launch_dequantize(pv_ctx *ctx, const pv_layout *l, const uint16_t *codes,
                                const float *codebooks, const float *scales, float *W_out);
+// G != nullptr: T is an output, formed in the scoring sweep as W - alpha * G, or, with adam and
+// the moments m, v given, as W minus one Adam update of G
 pv_status pv_launch_select(pv_ctx *ctx, const pv_layout *l, const float *T, const float *W,
                            int64_t k, int32_t *out_idx, float *scores, const float *G = nullptr,
-                           float alpha = 0.0f);
+                           float alpha = 0.0f, const pv_adam_t *adam = nullptr, float *m = nullptr,
+                           float *v = nullptr);
 pv_status pv_launch_exact_scan(pv_ctx *ctx, const pv_layout *l, const float *T,
                                const float *codebooks, const float *scales,
                                const int32_t *list, const uint32_t *d_count, int64_t max_count,

@@ -271,12 +271,13 @@ __global__ __launch_bounds__(kBlock) void k_scores_hist0_vec(const float *__rest
 // the scores and the digit-0 histogram are taken from the same registers, so T and W are
 // not read back from memory.  The arithmetic is the one of the separate kernels: one fused
 // multiply-add per element of T, then the subtraction T - W and the chain above.
-template <int PARTS>
+template <int PARTS, bool ADAM>
 __global__ __launch_bounds__(kBlock) void k_targets_scores_hist0_vec(const float *W, const float *G,
                                                                      float alpha, float *T,
                                                                      float *__restrict__ scores,
                                                                      unsigned *__restrict__ hist0,
-                                                                     int64_t nvec, int want_hist)
+                                                                     int64_t nvec, int want_hist,
+                                                                     pv_adam_t adam, float *m, float *v)
 {
     __shared__ unsigned lh[kFirstBins];
     if (want_hist)
@@ -287,6 +288,8 @@ __global__ __launch_bounds__(kBlock) void k_targets_scores_hist0_vec(const float
     pv_f4 *T4 = reinterpret_cast<pv_f4 *>(T);
     const int part = threadIdx.x & (PARTS - 1);
     const int64_t step = (int64_t)gridDim.x * (kBlock * kVecUnroll);
+    pv_f4 *M4 = reinterpret_cast<pv_f4 *>(m);
+    pv_f4 *V4 = reinterpret_cast<pv_f4 *>(v);
     pv_f4 w[kVecUnroll], gr[kVecUnroll], wn[kVecUnroll], gn[kVecUnroll];
     auto load = [&](int64_t cbase, pv_f4 *pw, pv_f4 *pg) {
 #pragma unroll
@@ -311,10 +314,29 @@ __global__ __launch_bounds__(kBlock) void k_targets_scores_hist0_vec(const float
         for (int u = 0; u < kVecUnroll; ++u) {
             const int64_t i = base + (int64_t)u * kBlock;
             pv_f4 t;
-            t.x = fmaf(-alpha, gr[u].x, w[u].x);
-            t.y = fmaf(-alpha, gr[u].y, w[u].y);
-            t.z = fmaf(-alpha, gr[u].z, w[u].z);
-            t.w = fmaf(-alpha, gr[u].w, w[u].w);
+            if constexpr (ADAM) {
+                pv_f4 mm = pv_f4{0.f, 0.f, 0.f, 0.f}, vv = mm;
+                if (i < nvec) {
+                    mm = __builtin_nontemporal_load(&M4[i]);
+                    vv = __builtin_nontemporal_load(&V4[i]);
+                }
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    float mi = mm[e], vi = vv[e];
+                    t[e] = pv_adam_one(w[u][e], gr[u][e], mi, vi, adam);
+                    mm[e] = mi;
+                    vv[e] = vi;
+                }
+                if (i < nvec) {
+                    M4[i] = mm;
+                    V4[i] = vv;
+                }
+            } else {
+                t.x = fmaf(-alpha, gr[u].x, w[u].x);
+                t.y = fmaf(-alpha, gr[u].y, w[u].y);
+                t.z = fmaf(-alpha, gr[u].z, w[u].z);
+                t.w = fmaf(-alpha, gr[u].w, w[u].w);
+            }
             if (i < nvec) __builtin_nontemporal_store(t, &T4[i]);
             const float d0 = t.x - w[u].x, d1 = t.y - w[u].y;
             const float d2 = t.z - w[u].z, d3 = t.w - w[u].w;
@@ -524,7 +546,8 @@ __global__ __launch_bounds__(kBlock) void k_compact_write(const float *__restric
 
 // G != nullptr: T is an OUTPUT, formed here as W - alpha * G in the same pass that scores it.
 pv_status pv_launch_select(pv_ctx *ctx, const pv_layout *l, const float *T, const float *W,
-                           int64_t k, int32_t *out_idx, float *scores, const float *G, float alpha)
+                           int64_t k, int32_t *out_idx, float *scores, const float *G, float alpha,
+                           const pv_adam_t *adam, float *m, float *v)
 {
     const int N = (int)pv_num_groups(l);
     const int g = l->group_size;
@@ -547,6 +570,7 @@ pv_status pv_launch_select(pv_ctx *ctx, const pv_layout *l, const float *T, cons
     const int want_hist = k > 0 ? 1 : 0;
     const bool vec_g = g == 4 || g == 8 || g == 16 || g == 32 || g == 64;
     if (G && !vec_g) {   // no fused kernel for this group size: form T first
+        // (the Adam variant reaches this launcher only for the group sizes that have one)
         st = pv_launch_encode_targets(ctx, W, G, alpha, const_cast<float *>(T),
                                       l->out_features * l->in_features);
         if (st != PV_OK) return st;
@@ -558,9 +582,17 @@ pv_status pv_launch_select(pv_ctx *ctx, const pv_layout *l, const float *T, cons
         int64_t vb = (nvec + kBlock * kVecUnroll - 1) / (kBlock * kVecUnroll);
         const unsigned vblocks = (unsigned)(vb < kMaxBlocks ? vb : kMaxBlocks);
         float *Tw = const_cast<float *>(T);
-#define PV_FUSED(PARTS_)                                                                       \
-    hipLaunchKernelGGL(k_targets_scores_hist0_vec<PARTS_>, dim3(vblocks), dim3(kBlock), 0,     \
-                       ctx->stream, W, G, alpha, Tw, scores, hist, nvec, want_hist)
+        const pv_adam_t a = adam ? *adam : pv_adam_t{};
+#define PV_FUSED(PARTS_)                                                                            \
+    do {                                                                                            \
+        if (adam)                                                                                   \
+            hipLaunchKernelGGL((k_targets_scores_hist0_vec<PARTS_, true>), dim3(vblocks), dim3(kBlock), \
+                               0, ctx->stream, W, G, alpha, Tw, scores, hist, nvec, want_hist, a, m, v); \
+        else                                                                                        \
+            hipLaunchKernelGGL((k_targets_scores_hist0_vec<PARTS_, false>), dim3(vblocks),          \
+                               dim3(kBlock), 0, ctx->stream, W, G, alpha, Tw, scores, hist, nvec,   \
+                               want_hist, a, m, v);                                                 \
+    } while (0)
         if (g == 4) PV_FUSED(1);
         else if (g == 8) PV_FUSED(2);
         else if (g == 16) PV_FUSED(4);

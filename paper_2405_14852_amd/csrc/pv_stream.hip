@@ -47,32 +47,12 @@ __global__ __launch_bounds__(kBlock) void k_encode_targets(const float *W,
         for (int64_t i = n4 << 2; i < n; ++i) T[i] = fmaf(-alpha, G[i], W[i]);
 }
 
-// Sec. 3.4: the gradient of Eq. 7 replaced by one Adam update.  Per element, in fp32 with
-// one rounding per operation written here (division and square root correctly rounded):
-//   m' = fma(b1, m, (1 - b1) * g)     v' = fma(b2, v, (1 - b2) * (g * g))
-//   T  = fma(-lr, (m' / c1) / (sqrt(v' / c2) + eps), W)
-// c1, c2: the bias corrections 1 - b^t, formed on the host in double and rounded once.
-struct adam_t {
-    float lr, b1, b2, omb1, omb2, c1, c2, eps;
-};
-
-__device__ __forceinline__ float adam_one(float w, float g, float &m, float &v, const adam_t &a)
-{
-    m = fmaf(a.b1, m, a.omb1 * g);
-    v = fmaf(a.b2, v, a.omb2 * (g * g));
-    // plain '/' and sqrtf compile to the correctly rounded sequences (the __fsqrt_rn
-    // intrinsic of this toolchain does not: it differs from IEEE in 14 % of random inputs)
-    const float mhat = m / a.c1;
-    const float vhat = v / a.c2;
-    const float upd = mhat / (sqrtf(vhat) + a.eps);
-    return fmaf(-a.lr, upd, w);
-}
-
+// (the Adam arithmetic itself, pv_adam_t / pv_adam_one, is declared with the internal launchers)
 constexpr int kAdamUnroll = 2;
 
 __global__ __launch_bounds__(kBlock) void k_encode_targets_adam(const float *W, const float *G,
                                                                 float *m, float *v, float *T,
-                                                                int64_t n, adam_t a)
+                                                                int64_t n, pv_adam_t a)
 {
     const int64_t n4 = n >> 2;
     const pv_f4 *W4 = reinterpret_cast<const pv_f4 *>(W);
@@ -100,7 +80,7 @@ __global__ __launch_bounds__(kBlock) void k_encode_targets_adam(const float *W, 
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 float mi = mm[u][e], vi = vv[u][e];
-                t[e] = adam_one(w[u][e], g[u][e], mi, vi, a);
+                t[e] = pv_adam_one(w[u][e], g[u][e], mi, vi, a);
                 mm[u][e] = mi;
                 vv[u][e] = vi;
             }
@@ -112,7 +92,7 @@ __global__ __launch_bounds__(kBlock) void k_encode_targets_adam(const float *W, 
     if (blockIdx.x == 0 && threadIdx.x == 0)
         for (int64_t i = n4 << 2; i < n; ++i) {
             float mi = m[i], vi = v[i];
-            T[i] = adam_one(W[i], G[i], mi, vi, a);
+            T[i] = pv_adam_one(W[i], G[i], mi, vi, a);
             m[i] = mi;
             v[i] = vi;
         }
@@ -182,23 +162,18 @@ pv_status pv_launch_encode_targets(pv_ctx *ctx, const float *W, const float *G, 
     return PV_OK;
 }
 
-static double powi(double b, int64_t t)   // b^t by repeated squaring, IEEE double products
+pv_adam_t pv_make_adam(int64_t step, float lr, float beta1, float beta2, float eps)
 {
-    double r = 1.0;
-    while (t > 0) {
-        if (t & 1) r = r * b;
-        b = b * b;
-        t >>= 1;
-    }
-    return r;
-}
-
-pv_status pv_launch_encode_targets_adam(pv_ctx *ctx, const float *W, const float *G, float *m,
-                                        float *v, int64_t step, float lr, float beta1, float beta2,
-                                        float eps, float *T, int64_t n)
-{
-    pv_timed t(ctx, PV_K_ENCODE_TARGETS);
-    adam_t a;
+    auto powi = [](double b, int64_t t) {   // b^t by repeated squaring, IEEE double products
+        double r = 1.0;
+        while (t > 0) {
+            if (t & 1) r = r * b;
+            b = b * b;
+            t >>= 1;
+        }
+        return r;
+    };
+    pv_adam_t a;
     a.lr = lr;
     a.b1 = beta1;
     a.b2 = beta2;
@@ -207,6 +182,15 @@ pv_status pv_launch_encode_targets_adam(pv_ctx *ctx, const float *W, const float
     a.c1 = (float)(1.0 - powi((double)beta1, step));
     a.c2 = (float)(1.0 - powi((double)beta2, step));
     a.eps = eps;
+    return a;
+}
+
+pv_status pv_launch_encode_targets_adam(pv_ctx *ctx, const float *W, const float *G, float *m,
+                                        float *v, int64_t step, float lr, float beta1, float beta2,
+                                        float eps, float *T, int64_t n)
+{
+    pv_timed t(ctx, PV_K_ENCODE_TARGETS);
+    const pv_adam_t a = pv_make_adam(step, lr, beta1, beta2, eps);
     int64_t n4 = n >> 2;
     int64_t blocks = (n4 + kAdamUnroll * kBlock - 1) / (kAdamUnroll * kBlock);
     if (blocks < 1) blocks = 1;

@@ -112,6 +112,33 @@ def test_encode_targets_adam_sequence_in_place_and_errors():
         run.ctx.pv_encode_targets_adam(run.lay, run.W, Gd, md, md, 1, 1e-3, 0.9, 0.95, 1e-8, T)
 
 
+@pytest.mark.parametrize("shape,g", [((256, 256), 8), ((61, 1000), 8), ((33, 4096), 16),
+                                     ((129, 4100), 4), ((5, 12), 1), ((100, 36), 6), ((9, 1280), 64)])
+@pytest.mark.parametrize("step,frac", [(1, 0.3), (3, 0.01), (50, 1.0), (2, 0.0)])
+def test_fused_adam_targets_select_matches_oracle(shape, g, step, frac):
+    wl = workloads.make(shape[0], shape[1], g, 1, 4, seed=23, sigma_g=1e-3)
+    rng = np.random.default_rng(23)
+    m = (rng.standard_normal(shape) * 1e-3).astype(np.float32) if step > 1 else np.zeros(shape, np.float32)
+    v = (rng.random(shape) * 1e-6).astype(np.float32) if step > 1 else np.zeros(shape, np.float32)
+    run = GpuRun(wl)
+    N = wl.layout.num_groups
+    k = int(frac * N)
+    md, vd = dev_f32(m), dev_f32(v)
+    T = torch.empty_like(run.W)
+    idx = torch.empty(max(k, 1), dtype=torch.int32, device=DEV)
+    sc = torch.empty(N, dtype=torch.float32, device=DEV)
+    run.ctx.pv_encode_targets_adam_select(run.lay, run.W, run.G, md, vd, step, 3e-3, 0.9, 0.95, 1e-8,
+                                          T, k, idx, sc)
+    torch.cuda.synchronize()
+    T_ref, m_ref, v_ref = oracle.encode_targets_adam(wl.W, wl.G, m, v, step, 3e-3, 0.9, 0.95, 1e-8)
+    idx_ref, sc_ref = oracle.select_topk_groups(T_ref, wl.W, g, k, return_scores=True)
+    assert np.array_equal(T.cpu().numpy().view(np.uint32), T_ref.view(np.uint32))
+    assert np.array_equal(md.cpu().numpy().view(np.uint32), m_ref.view(np.uint32))
+    assert np.array_equal(vd.cpu().numpy().view(np.uint32), v_ref.view(np.uint32))
+    assert np.array_equal(sc.cpu().numpy().view(np.uint32), sc_ref.view(np.uint32))
+    assert np.array_equal(idx.cpu().numpy()[:k], idx_ref)
+
+
 # --------------------------------------------------------------- dequantize
 
 @pytest.mark.parametrize("g,M,B", [(8, 1, 8), (8, 2, 8), (16, 1, 12), (8, 1, 16), (2, 1, 3),
