@@ -268,6 +268,9 @@ def reencode_case(wl, mode, idx=None, T_np=None):
     (4, 3, (8, 64), 1.0),
     (1, 2, (4, 16), 1.0),
     (8, 1, (4, 64), 1.0),
+    (32, 6, (8, 512), 1.0),         # group sizes beyond the matrix-core filter: exact scan
+    (64, 4, (8, 1024), 1.0),        # the largest group size
+    (12, 5, (8, 240), 1.0),         # a group size that is no multiple of four
 ])
 def test_reencode_m1_matches_oracle(mode, g, B, shape, tau):
     wl = workloads.make(shape[0], shape[1], g, 1, B, seed=7, sigma_g=2e-3, tau=tau)
@@ -340,6 +343,10 @@ def test_reencode_empty_selection_and_errors():
     (2, 5, 16, 16, (8, 256)),
     (4, 3, 4, 4, (8, 64)),
     (2, 2, 2, 64, (4, 32)),
+    (2, 8, 16, 8, (32, 512)),    # two 8-bit codebooks over groups of 16 (wave-per-group kernel)
+    (8, 2, 8, 16, (8, 128)),     # the largest number of codebooks
+    (2, 4, 64, 8, (8, 512)),     # the largest group size
+    (2, 12, 8, 1, (8, 128)),     # the largest candidate pool (beam 1 x 4096 codewords)
 ])
 def test_reencode_beam_matches_oracle(M, B, g, beam, shape):
     wl = workloads.make(shape[0], shape[1], g, M, B, seed=12, sigma_g=2e-3, tau=0.5,
