@@ -7,6 +7,11 @@
  *     T  = pv_encode_targets(W, G, alpha)             Eq. 7; Alg. 3, V step
  *     S  = pv_select_topk_groups(T, W, k)             Alg. 2, line 5; Sec. 3.4
  *     codes[S] = pv_reencode_groups(T, S)             Eq. 7 argmin; Sec. 4.2; App. D, K
+ * Further calls: pv_encode_targets_select (lines 2 and 3 in one sweep),
+ * pv_encode_targets_adam[_select] (Sec. 3.4: an Adam update as the direction),
+ * pv_reencode_trust_ratio (Sec. 4.3: the subspace size from the trust ratio),
+ * pv_codebook_grads (Alg. 3 P step: gradients of codebooks and scales),
+ * pv_dequantize_scalar / pv_reencode_scalar (App. K's scalar uniform-grid representation).
  *
  * Conventions for every call
  *   - All tensor pointers are DEVICE pointers on the context's GPU, owned by the
