@@ -40,6 +40,10 @@
 #ifndef PV_STAGE
 #define PV_STAGE 32   // KiB of operand A per LDS stage
 #endif
+#ifndef PV_STAGE2
+#define PV_STAGE2 48  // the same for two k-steps per tile (g = 16): longer stages pay there even
+                      // though only one block then fits a compute unit's LDS
+#endif
 #ifndef PV_NBX
 #define PV_NBX 2      // group tiles (32 groups) per wave
 #endif
@@ -56,7 +60,6 @@ typedef _Float16 h8 __attribute__((ext_vector_type(8)));
 typedef float f16v __attribute__((ext_vector_type(16)));
 
 constexpr int kBlock = 256;
-constexpr int kStageTiles = PV_STAGE;      // KiB of operand A per LDS stage
 constexpr int kResidues = 4;         // tile residue classes tracked separately per lane
 constexpr unsigned kTileMask = 0x7FFu;
 constexpr float kHalfMinNormal = 6.103515625e-05f;  // 2^-14
@@ -323,7 +326,7 @@ __global__ __launch_bounds__(PV_WAVES * 64, (PV_OCC * PV_WAVES) / 4) void k_scor
                                                           int nsplit, int P, int merge,
                                                           int gblocks, unsigned *__restrict__ next_item)
 {
-    constexpr int S = kStageTiles / NK;                            // tiles per stage
+    constexpr int S = (NK == 1 ? PV_STAGE : PV_STAGE2) / NK;       // tiles per stage
     constexpr int kStageChunks = S * NK * 64;                      // 16-byte chunks per stage
     constexpr int kW = PV_WAVES;                                   // waves per block
     constexpr int kRounds = (kStageChunks / 64 + kW - 1) / kW;     // 64-chunk rows per wave
