@@ -297,6 +297,39 @@ def test_reencode_m1_duplicate_codewords_tie_rule(mode):
     assert np.array_equal(got, want)                     # exact ties resolve identically
 
 
+@pytest.mark.parametrize("g,B", [(8, 10), (16, 9)])
+@pytest.mark.parametrize("case", ["targets_on_codewords", "mixed_magnitudes", "tiny_values", "huge_values",
+                                  "clustered_codebook", "one_dimension_dominates"])
+def test_reencode_m1_inputs_that_stress_the_filter(g, B, case):
+    """Inputs chosen against the fp16 filter and its bounds; the decision must stay the oracle's."""
+    wl = workloads.make(24, 64 * g, g, 1, B, seed=12, sigma_g=2e-3, tau=1.0)
+    rng = np.random.default_rng(12)
+    T_np = None
+    if case == "targets_on_codewords":       # distance exactly zero for the right codeword
+        pick = rng.integers(0, 1 << B, size=wl.layout.num_groups)
+        T_np = (wl.codebooks[0, pick].reshape(24, 64, g) * wl.scales[:, None, None]).reshape(24, 64 * g)
+        T_np = T_np.astype(np.float32)
+    elif case == "mixed_magnitudes":         # half of the codewords a hundred times larger
+        wl.codebooks[0, ::2] *= np.float32(100.0)
+    elif case == "tiny_values":
+        wl.codebooks *= np.float32(1e-20)
+        wl.W *= np.float32(1e-20)
+        wl.G *= np.float32(1e-20)
+    elif case == "huge_values":
+        wl.codebooks *= np.float32(1e15)
+        wl.W *= np.float32(1e15)
+        wl.G *= np.float32(1e15)
+    elif case == "clustered_codebook":       # all codewords within a tiny ball: nothing can be excluded
+        base = wl.codebooks[0, 0].copy()
+        wl.codebooks[0] = base + (rng.standard_normal(wl.codebooks[0].shape) * 1e-7).astype(np.float32)
+    elif case == "one_dimension_dominates":
+        wl.codebooks[0, :, 0] *= np.float32(1000.0)
+        wl.W[:, ::g] *= np.float32(1000.0)
+    _, got, want, info = reencode_case(wl, 0, T_np=T_np)
+    if case == "targets_on_codewords":
+        assert (info["obj_new"] <= 1e-12).all()
+
+
 @pytest.mark.parametrize("mode", [1, 0])
 def test_reencode_fixed_point_when_update_is_zero(mode):
     wl = workloads.make(32, 512, 8, 1, 12, seed=10, tau=1.0)
