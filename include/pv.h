@@ -11,6 +11,7 @@
  * pv_encode_targets_adam[_select] (Sec. 3.4: an Adam update as the direction),
  * pv_reencode_trust_ratio (Sec. 4.3: the subspace size from the trust ratio),
  * pv_codebook_grads (Alg. 3 P step: gradients of codebooks and scales),
+ * pv_dequantize_groups (dequantisation of the re-encoded groups only),
  * pv_dequantize_scalar / pv_reencode_scalar (App. K's scalar uniform-grid representation).
  *
  * Conventions for every call
@@ -163,6 +164,15 @@ pv_status pv_reencode_trust_ratio(pv_ctx *ctx, const pv_layout *layout, const fl
  * masked to B bits. */
 pv_status pv_dequantize(pv_ctx *ctx, const pv_layout *layout, const uint16_t *codes,
                         const float *codebooks, const float *scales, float *W_out);
+
+/* pv_dequantize restricted to the listed groups (Alg. 3 line 1 after a V step that changed
+ * only those): W_out[o, j*g .. j*g+g) is rewritten for each listed flat group id, every other
+ * weight of W_out is left as it is.  If W_out held pv_dequantize of the codes before the V
+ * step and group_idx is the list the step re-encoded, the result equals pv_dequantize of the
+ * new codes.  group_idx: i32 [k], ids outside [0, N) are skipped. */
+pv_status pv_dequantize_groups(pv_ctx *ctx, const pv_layout *layout, const uint16_t *codes,
+                               const float *codebooks, const float *scales,
+                               const int32_t *group_idx, int64_t k, float *W_out);
 
 /* P step (Alg. 3, "grad_codebooks = backprop(grad_phi)"; App. K: codebooks and per-channel
  * scales are trained by backprop): the chain rule through pv_dequantize applied to

@@ -78,6 +78,7 @@ def load_library():
     lib.pv_encode_targets_select.argtypes = [vp, lp, vp, vp, f32, vp, i64, vp, vp]
     lib.pv_reencode_groups.argtypes = [vp, lp, vp, vp, vp, vp, i64, i32, vp, vp]
     lib.pv_dequantize.argtypes = [vp, lp, vp, vp, vp, vp]
+    lib.pv_dequantize_groups.argtypes = [vp, lp, vp, vp, vp, vp, i64, vp]
     lib.pv_codebook_grads.argtypes = [vp, lp, vp, vp, vp, vp, vp, vp]
     lib.pv_dequantize_scalar.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp, vp]
     lib.pv_reencode_scalar.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp, vp, i64, vp, vp]
@@ -93,6 +94,7 @@ def load_library():
                  "pv_encode_targets_adam_select",
                  "pv_encode_targets_select", "pv_reencode_groups", "pv_reencode_trust_ratio",
                  "pv_codebook_grads", "pv_dequantize_scalar", "pv_reencode_scalar",
+                 "pv_dequantize_groups",
                  "pv_dequantize", "pv_set_search_mode", "pv_timing_enable", "pv_timing_reset",
                  "pv_timing_read", "pv_reencode_stats"):
         getattr(lib, name).restype = ctypes.c_int
@@ -211,6 +213,14 @@ class PVContext:
             _dev_ptr(rank_idx, torch.int32, "rank_idx", allow_none=True),
             _dev_ptr(num_applied, torch.int64, "num_applied"),
             _dev_ptr(stats, torch.float64, "stats", allow_none=True)))
+
+    def pv_dequantize_groups(self, layout: Layout, codes, codebooks, scales, group_idx, k: int, W_out):
+        lay = layout.c()
+        self._check(self._lib.pv_dequantize_groups(
+            self._h, ctypes.byref(lay), _dev_ptr(codes, torch.uint16, "codes"),
+            _dev_ptr(codebooks, torch.float32, "codebooks"), _dev_ptr(scales, torch.float32, "scales"),
+            _dev_ptr(group_idx, torch.int32, "group_idx", allow_none=(k == 0)), int(k),
+            _dev_ptr(W_out, torch.float32, "W_out")))
 
     def pv_codebook_grads(self, layout: Layout, G, codes, codebooks, scales, grad_codebooks,
                           grad_scales=None):

@@ -382,6 +382,26 @@ extern "C" pv_status pv_dequantize(pv_ctx *ctx, const pv_layout *l, const uint16
     return pv_launch_dequantize(ctx, l, codes, codebooks, scales, W_out);
 }
 
+extern "C" pv_status pv_dequantize_groups(pv_ctx *ctx, const pv_layout *l, const uint16_t *codes,
+                                          const float *codebooks, const float *scales,
+                                          const int32_t *group_idx, int64_t k, float *W_out)
+{
+    if (!ctx) return PV_ERR_INVALID_ARG;
+    pv_status st = check_layout(ctx, l);
+    if (st != PV_OK) return st;
+    if (k < 0 || k > pv_num_groups(l))
+        return pv_fail(ctx, PV_ERR_INVALID_ARG, "k = %lld outside [0, %lld]", (long long)k,
+                       (long long)pv_num_groups(l));
+    if (!codes || !codebooks || !scales || !W_out)
+        return pv_fail(ctx, PV_ERR_INVALID_ARG, "NULL tensor pointer");
+    if (k > 0 && !group_idx) return pv_fail(ctx, PV_ERR_INVALID_ARG, "group_idx is NULL");
+    if (misaligned(codebooks) || misaligned(W_out))
+        return pv_fail(ctx, PV_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
+    if (k == 0) return PV_OK;
+    PV_HIP(ctx, hipSetDevice(ctx->device));
+    return pv_launch_dequantize_groups(ctx, l, codes, codebooks, scales, group_idx, k, W_out);
+}
+
 // ---------------------------------------------------------------- scalar grids
 
 static pv_status check_scalar(pv_ctx *ctx, int64_t out_features, int64_t in_features,

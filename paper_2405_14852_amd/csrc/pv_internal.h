@@ -113,6 +113,9 @@ pv_status pv_launch_encode_targets_adam(pv_ctx *ctx, const float *W, const float
                                         float eps, float *T, int64_t n);
 pv_status pv_launch_dequantize(pv_ctx *ctx, const pv_layout *l, const uint16_t *codes,
                                const float *codebooks, const float *scales, float *W_out);
+pv_status pv_launch_dequantize_groups(pv_ctx *ctx, const pv_layout *l, const uint16_t *codes,
+                                      const float *codebooks, const float *scales,
+                                      const int32_t *group_idx, int64_t k, float *W_out);
 // G != nullptr: T is an output, formed in the scoring sweep as W - alpha * G, or, with adam and
 // the moments m, v given, as W minus one Adam update of G
 pv_status pv_launch_select(pv_ctx *ctx, const pv_layout *l, const float *T, const float *W,

@@ -141,6 +141,50 @@ __global__ __launch_bounds__(kBlock) void k_dequantize(const uint16_t *__restric
     }
 }
 
+// The same for a list of groups only (the groups a V step re-encoded): every other weight of
+// W_out keeps its value.  One thread per weight vector of a listed group.
+template <int VEC>
+__global__ __launch_bounds__(kBlock) void k_dequantize_groups(const uint16_t *__restrict__ codes,
+                                                              const float *__restrict__ codebooks,
+                                                              const float *__restrict__ scales,
+                                                              const int32_t *__restrict__ group_idx,
+                                                              int64_t total, float *__restrict__ W_out,
+                                                              int g, int M, int nbits, int gpr, int N)
+{
+    const int64_t idx = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (idx >= total) return;
+    const int parts = g / VEC;
+    const int64_t j = idx / parts;
+    const int q = (int)(idx - j * parts);
+    const int n = group_idx[j];
+    if (n < 0 || n >= N) return;
+    const unsigned mask = (1u << nbits) - 1u;
+    const int64_t csize = (int64_t)1 << nbits;
+    const float s = scales[n / gpr];
+    const uint16_t *cp = codes + (int64_t)n * M;
+    if constexpr (VEC == 4) {
+        const pv_f4 *cb4 = reinterpret_cast<const pv_f4 *>(codebooks);
+        pv_f4 acc = cb4[((int64_t)(cp[0] & mask) * g) / 4 + q];
+        for (int m = 1; m < M; ++m) {
+            pv_f4 c = cb4[((m * csize + (cp[m] & mask)) * g) / 4 + q];
+            acc.x = acc.x + c.x;
+            acc.y = acc.y + c.y;
+            acc.z = acc.z + c.z;
+            acc.w = acc.w + c.w;
+        }
+        pv_f4 out;
+        out.x = s * acc.x;
+        out.y = s * acc.y;
+        out.z = s * acc.z;
+        out.w = s * acc.w;
+        reinterpret_cast<pv_f4 *>(W_out)[((int64_t)n * g) / 4 + q] = out;
+    } else {
+        float acc = codebooks[(int64_t)(cp[0] & mask) * g + q];
+        for (int m = 1; m < M; ++m) acc = acc + codebooks[(m * csize + (cp[m] & mask)) * g + q];
+        W_out[(int64_t)n * g + q] = s * acc;
+    }
+}
+
 __global__ void k_fill_i64(int64_t *p, int64_t n, int64_t v)
 {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -219,6 +263,29 @@ pv_status pv_launch_dequantize(pv_ctx *ctx, const pv_layout *l, const uint16_t *
         hipLaunchKernelGGL(k_dequantize<1>, dim3((unsigned)blocks), dim3(kBlock), 0, ctx->stream,
                            codes, codebooks, scales, W_out, total, g, l->num_codebooks, l->nbits,
                            gpr);
+    }
+    PV_HIP(ctx, hipGetLastError());
+    return PV_OK;
+}
+
+pv_status pv_launch_dequantize_groups(pv_ctx *ctx, const pv_layout *l, const uint16_t *codes,
+                                      const float *codebooks, const float *scales,
+                                      const int32_t *group_idx, int64_t k, float *W_out)
+{
+    pv_timed t(ctx, PV_K_DEQUANTIZE);
+    const int g = l->group_size;
+    const int gpr = (int)(l->in_features / g);
+    const int N = (int)pv_num_groups(l);
+    if (g % 4 == 0) {
+        const int64_t total = k * (g / 4);
+        hipLaunchKernelGGL(k_dequantize_groups<4>, dim3((unsigned)((total + kBlock - 1) / kBlock)),
+                           dim3(kBlock), 0, ctx->stream, codes, codebooks, scales, group_idx, total,
+                           W_out, g, l->num_codebooks, l->nbits, gpr, N);
+    } else {
+        const int64_t total = k * g;
+        hipLaunchKernelGGL(k_dequantize_groups<1>, dim3((unsigned)((total + kBlock - 1) / kBlock)),
+                           dim3(kBlock), 0, ctx->stream, codes, codebooks, scales, group_idx, total,
+                           W_out, g, l->num_codebooks, l->nbits, gpr, N);
     }
     PV_HIP(ctx, hipGetLastError());
     return PV_OK;

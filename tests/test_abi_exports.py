@@ -38,8 +38,9 @@ def test_every_declared_symbol_is_exported(lib):
 
 def test_binding_uses_the_same_names():
     import paper_2405_14852_amd as pkg
-    for f in ("pv_encode_targets", "pv_select_topk_groups", "pv_reencode_groups", "pv_dequantize"):
-        assert hasattr(pkg.PVContext, f)
+    # the context's life cycle is the Python object's; every other call keeps its C name
+    for f in set(declared_functions()) - {"pv_create", "pv_destroy", "pv_last_error"}:
+        assert hasattr(pkg.PVContext, f), f
 
 
 def test_null_context_is_rejected_without_a_gpu(lib):

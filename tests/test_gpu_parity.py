@@ -151,6 +151,30 @@ def test_dequantize_bit_exact(g, M, B):
     assert np.array_equal(W.view(np.uint32), ref.view(np.uint32))
 
 
+@pytest.mark.parametrize("g,M,B", [(8, 1, 8), (8, 2, 8), (16, 1, 12), (6, 3, 4), (1, 1, 2)])
+def test_dequantize_groups_updates_only_the_listed_groups(g, M, B):
+    wl = workloads.make(67, 24 * g, g, M, B, seed=13)
+    run = GpuRun(wl)
+    rng = np.random.default_rng(13)
+    N = wl.layout.num_groups
+    idx = np.sort(rng.choice(N, size=N // 5, replace=False)).astype(np.int32)
+    new_codes = wl.codes.copy().reshape(N, M)
+    new_codes[idx] = rng.integers(0, 1 << B, size=(len(idx), M), dtype=np.uint16)
+    new_codes = new_codes.reshape(wl.codes.shape)
+    Wd = dev_f32(oracle.dequantize(wl.codes, wl.codebooks, wl.scales))
+    # codes of OTHER groups are scrambled too: they must not be read
+    scrambled = new_codes.copy().reshape(N, M)
+    other = np.setdiff1d(np.arange(N), idx)
+    want = oracle.dequantize(new_codes, wl.codebooks, wl.scales)
+    want.reshape(N, g)[other] = oracle.dequantize(wl.codes, wl.codebooks, wl.scales).reshape(N, g)[other]
+    scrambled[other] = (scrambled[other] + 1) % (1 << B)
+    from gpu_util import dev_i32
+    run.ctx.pv_dequantize_groups(run.lay, dev_u16(scrambled.reshape(wl.codes.shape)), run.cb, run.sc,
+                                 dev_i32(idx), len(idx), Wd)
+    torch.cuda.synchronize()
+    assert np.array_equal(Wd.cpu().numpy().view(np.uint32), want.view(np.uint32))
+
+
 # ---------------------------------------------------------------- selection
 
 @pytest.mark.parametrize("shape,g", [((256, 256), 8), ((61, 1000), 8), ((33, 4096), 16),
