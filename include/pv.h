@@ -213,8 +213,9 @@ pv_status pv_reencode_scalar(pv_ctx *ctx, int64_t out_features, int64_t in_featu
 
 /* ---- instrumentation (does not change results) ------------------------- */
 
-/* Search strategy for M == 1: 0 = automatic (matrix-core filter + exact
- * re-rank where the shape allows, else exact scan), 1 = exact scan only. */
+/* Search strategy: 0 = automatic (a matrix-core filter with exact certificates
+ * where the shape allows: one codebook with g = 8 or 16, or two 8-bit codebooks
+ * with g = 8 or 16 and beam <= 8; else the exact kernels), 1 = exact kernels only. */
 pv_status pv_set_search_mode(pv_ctx *ctx, int mode);
 
 typedef enum {
@@ -240,10 +241,11 @@ pv_status pv_timing_reset(pv_ctx *ctx);
 pv_status pv_timing_read(pv_ctx *ctx, int kernel_id, double *total_ms, int64_t *launches);
 
 /* Counters of the last pv_reencode_groups call (waits for the stream):
- * stats[0] = groups handled by the matrix-core filter, stats[1] = groups the
- * filter could not certify and that were re-done by the exact scan,
- * stats[2] = candidate codewords evaluated exactly in the re-rank,
- * stats[3] = groups handled by exact scan / beam search from the start. */
+ * stats[0] = groups decided by a matrix-core filter (one codebook: the fp16
+ * contraction; two 8-bit codebooks: the fp64 beam filter), stats[1] = groups the
+ * filter could not certify and that were re-done by the exact scan / exact beam
+ * kernel, stats[2] = candidate codewords evaluated exactly in the re-rank (one
+ * codebook), stats[3] = groups handled by exact scan / beam search from the start. */
 pv_status pv_reencode_stats(pv_ctx *ctx, int64_t stats[4]);
 
 #ifdef __cplusplus

@@ -418,6 +418,102 @@ def test_reencode_beam_duplicate_codewords():
     assert np.array_equal(got, want)
 
 
+# Two 8-bit codebooks (the additive configuration of App. K): mode 0 runs the matrix-core
+# filter with its double-precision certificates and hands the undecided groups to the exact
+# kernel, mode 1 runs the exact kernel alone.  Both must give the oracle's codes.
+
+@pytest.mark.parametrize("mode", [0, 1])
+@pytest.mark.parametrize("g", [8, 16])
+@pytest.mark.parametrize("beam", [1, 2, 5, 8])
+def test_reencode_2x8_both_paths(mode, g, beam):
+    wl = workloads.make(24, 40 * g, g, 2, 8, seed=21 + beam, sigma_g=2e-3, tau=0.47, beam_width=beam)
+    run, got, want, info = reencode_case(wl, mode)
+    st = run.ctx.pv_reencode_stats()
+    if mode == 0:
+        assert st["filtered"] + st["fallback"] == wl.k and st["exact"] == 0
+        assert st["filtered"] > 0.9 * wl.k          # the filter decides nearly every group
+    else:
+        assert st["exact"] == wl.k and st["filtered"] == 0
+
+
+@pytest.mark.parametrize("g", [8, 16])
+@pytest.mark.parametrize("k", [1, 2, 3, 7])
+def test_reencode_2x8_short_lists(g, k):
+    """Fewer groups than one wave's pair, odd list lengths."""
+    wl = workloads.make(4, 16 * g, g, 2, 8, seed=30 + k, sigma_g=2e-3, tau=1.0, beam_width=8)
+    T_np = oracle.encode_targets(wl.W, wl.G, wl.alpha)
+    idx = np.sort(np.random.default_rng(k).choice(wl.layout.num_groups, size=k, replace=False)).astype(np.int32)
+    _, got, want, _ = reencode_case(wl, 0, idx=idx, T_np=T_np)
+    assert np.array_equal(got, want)
+
+
+@pytest.mark.parametrize("g", [8, 16])
+@pytest.mark.parametrize("case", ["duplicates", "scales", "targets_on_sums", "integers", "tiny_values",
+                                  "huge_values", "one_dimension_dominates", "identical_codebooks"])
+def test_reencode_2x8_inputs_that_stress_the_filter(g, case):
+    wl = workloads.make(16, 24 * g, g, 2, 8, seed=40, sigma_g=2e-3, tau=1.0, beam_width=8)
+    rng = np.random.default_rng(41)
+    exact = True          # exact ties must resolve as in the oracle (lexicographic order)
+    if case == "duplicates":
+        wl.codebooks[:, 128:] = wl.codebooks[:, :128]
+    elif case == "scales":
+        wl.scales[2] = 0.0
+        wl.scales[3] = -0.8
+        wl.scales[4] = 1e-6
+        wl.scales[5] = 400.0
+    elif case == "targets_on_sums":      # objective 0 for one pair: the expanded form may go negative
+        c = rng.integers(0, 256, size=(wl.layout.num_groups, 2))
+        rec = wl.codebooks[0][c[:, 0]] + wl.codebooks[1][c[:, 1]]
+        rows = np.repeat(np.arange(16), wl.layout.groups_per_row)
+        wl.W = (rec * wl.scales[rows, None]).reshape(wl.W.shape).astype(np.float32)
+        wl.G[:] = 0
+    elif case == "integers":             # many exact ties between different pairs
+        wl.codebooks = rng.integers(-3, 4, size=wl.codebooks.shape).astype(np.float32)
+        wl.W = rng.integers(-6, 7, size=wl.W.shape).astype(np.float32)
+        wl.G[:] = 0
+        wl.scales[:] = 1.0
+    elif case == "tiny_values":
+        wl.codebooks *= np.float32(1e-18)
+        wl.W *= np.float32(1e-18)
+        wl.G *= np.float32(1e-18)
+    elif case == "huge_values":
+        wl.codebooks *= np.float32(1e15)
+        wl.W *= np.float32(1e15)
+        wl.G *= np.float32(1e15)
+    elif case == "one_dimension_dominates":
+        wl.codebooks[:, :, 0] *= np.float32(1e4)
+        wl.W[:, ::g] *= np.float32(1e4)
+    elif case == "identical_codebooks":
+        wl.codebooks[1] = wl.codebooks[0]
+    run, got, want, info = reencode_case(wl, 0)
+    if exact:
+        assert np.array_equal(got, want)
+    st = run.ctx.pv_reencode_stats()
+    assert st["filtered"] + st["fallback"] == wl.k
+    if case == "scales":
+        gpr = wl.layout.groups_per_row
+        assert np.array_equal(got.reshape(-1, 2)[2 * gpr:3 * gpr], wl.codes.reshape(-1, 2)[2 * gpr:3 * gpr])
+
+
+def test_reencode_2x8_non_finite_inputs_end_normally():
+    wl = workloads.make(8, 128, 8, 2, 8, seed=44, sigma_g=2e-3, tau=1.0, beam_width=8)
+    T_np = oracle.encode_targets(wl.W, wl.G, wl.alpha)
+    T_np[1, :8] = np.nan
+    T_np[2, 8:16] = np.inf
+    wl.scales[5] = np.inf
+    run = GpuRun(wl)
+    idx = np.arange(wl.layout.num_groups, dtype=np.int32)
+    got, _ = run.reencode(dev_f32(T_np), idx)
+    assert got.max() < 256
+    clean = np.ones(wl.layout.num_groups, bool)
+    gpr = wl.layout.groups_per_row
+    clean[gpr * 1] = clean[gpr * 2 + 1] = False
+    clean[5 * gpr:6 * gpr] = False
+    sub = idx[clean]
+    want, info = oracle.reencode_groups(T_np, wl.codebooks, wl.scales, sub, wl.codes, beam_width=8)
+    assert np.array_equal(got.reshape(-1, 2)[sub], want.reshape(-1, 2)[sub]) or info["near_tie"].any()
+
+
 # ------------------------------------------------------------- whole path
 
 @pytest.mark.parametrize("name,shape", [("c1_256x256_1x8", None),
