@@ -7,6 +7,9 @@
 //
 // The scan serves two callers: whole calls for shapes the matrix-core filter
 // does not cover, and the (short) list of groups that filter could not certify.
+// The two-codebook beam search has the same pair: a filter on the fp64 matrix
+// instruction (k_beam_2x8_mfma) whose results are accepted only under
+// double-precision certificates, and the exact kernel behind it.
 #include "pv_internal.h"
 
 #include <type_traits>
@@ -654,10 +657,10 @@ __global__ __launch_bounds__(kBlock) void k_beam_2x8(
 //
 // App. D's expansion  ||s (c0 + c1) - t||^2 = s^2 ||c1||^2 - 2 s <c1, r> + ||r||^2  with
 // r = t - s c0  turns step 1 (every second code against every kept first code) into a
-// 256 x (G+1) by (G+1) x 8 product per group: rows (c1[0..G), ||c1||^2), columns
-// (-2 s r_e[0..G), s^2).  One wave takes TWO groups, so the 16 columns of the fp64
-// 16x16x4 matrix instruction are all used; the vector ALU only keeps the running
-// minimum of the 64 results per lane.  Step 0 (256 candidates per group) uses the same
+// 256 x G by G x 8 product per group: rows c1[0..G), columns -2 s r_e[0..G), and
+// s^2 ||c1||^2 as the accumulator's initial value.  One wave takes TWO groups, so the 16
+// columns of the fp64 16x16x4 matrix instruction are all used; the vector ALU only keeps
+// the two smallest of the 64 results per lane.  Step 0 (256 candidates per group) uses the same
 // expansion on the vector ALU, one group per half wave.
 //
 // The expanded form rounds differently from the reference chain, so it only FILTERS:
@@ -672,6 +675,7 @@ __global__ __launch_bounds__(kBlock) void k_beam_2x8(
 // square) and the 6 index bits written into the low mantissa bits of a step-1 value.
 typedef double d4v __attribute__((ext_vector_type(4)));
 constexpr int kBeamBlock = 512;
+constexpr int kExtra = 3;   // candidates beyond the beam that the step-0 boundary check may pull in
 
 // smallest value over the 32 lanes of each half wave, in every lane of that half
 __device__ __forceinline__ unsigned half_min_u32(unsigned v, int half)
@@ -715,7 +719,10 @@ __device__ __forceinline__ double column_group_min(double v)
     return v;
 }
 
-// running smallest (b1) and second smallest (b2) of a stream of finite values
+// running smallest (b1) and second smallest (b2) of a stream of finite values.  (Assembly: the
+// compiler's fmin/fmax add an instruction per operand to quiet signalling NaNs.  The caller
+// builds v with ordinary code from a matrix result, so the wait the hardware needs after the
+// matrix instruction is already in place when these run.)
 __device__ __forceinline__ void keep_two(double &b1, double &b2, double v)
 {
     double hi;
@@ -746,6 +753,8 @@ __global__ __launch_bounds__(kBeamBlock, 4) void k_beam_2x8_mfma(
     __shared__ double s_wt[kWaves][2][G];
     __shared__ double s_ws[kWaves][2];
     __shared__ int s_wb[kWaves][2][kBeam2Max];
+    __shared__ double s_xo[kWaves][2][kBeam2Max + kExtra];   // rare path: exact objectives and codes
+    __shared__ int s_xc[kWaves][2][kBeam2Max + kExtra];      // of the candidates around the boundary
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     if (threadIdx.x < 256) {
@@ -868,12 +877,60 @@ __global__ __launch_bounds__(kBeamBlock, 4) void k_beam_2x8_mfma(
                 base = m + 1u;
             }
         }
-        {
-            // every dropped candidate is at least `lower`, every kept one below `upper`
-            const double lower = __hiloint2double((int)(k_next & ~0xFFu), 0);
-            const double upper = __hiloint2double((int)((k_last & ~0xFFu) + 0x100u), 0);
-            bad |= !(lower - upper > 2.0 * E);
+        // every dropped candidate is at least lower_of(its key), every kept one below
+        // upper_of(its key): the kept set is certain when the two are more than 2 E apart
+        auto lower_of = [](unsigned kk) { return __hiloint2double((int)(kk & ~0xFFu), 0); };
+        auto upper_of = [](unsigned kk) { return __hiloint2double((int)((kk & ~0xFFu) + 0x100u), 0); };
+        bool open = !bad && !(lower_of(k_next) - upper_of(k_last) > 2.0 * E);
+        if (__ballot(open) != 0ull) {
+            // Rare (a fraction of a percent of the groups): the boundary falls inside the
+            // truncation.  Up to kExtra more candidates are extracted until a clear gap
+            // follows; the kept ones and these are then ranked with the reference chain
+            // (objective, code) and the best `keep` stay.  Both halves run the code, a half
+            // whose set was certain ignores the outcome.
+            unsigned extra[kExtra + 1];
+            extra[0] = k_next;
+            int taken_extra = 0;
+#pragma unroll
+            for (int x = 1; x <= kExtra; ++x) {
+                unsigned head = umin3(key[0] - base, key[1] - base, key[2] - base);
+                head = umin3(head, key[3] - base, key[4] - base);
+                head = umin3(head, key[5] - base, key[6] - base);
+                head = min(head, key[7] - base);
+                const unsigned m = half_min_u32(head, h) + base;
+                base = m + 1u;
+                extra[x] = m;
+                if (taken_extra == 0 && lower_of(m) - upper_of(extra[x - 1]) > 2.0 * E) taken_extra = x;
+            }
+            const int nc = keep + taken_extra;          // candidates to rank, if a gap was found
+            int code = 0;
+            if (hl < keep) code = s_wb[wave][h][hl < kBeam2Max ? hl : 0];
+#pragma unroll
+            for (int x = 0; x < kExtra; ++x)
+                if (hl == keep + x) code = (int)(extra[x] & 0xFFu);
+            double obj = 0.0;
+#pragma unroll
+            for (int i = 0; i < G; ++i) {
+                double acc = (double)s_cb0[code * G + i];
+                acc = acc + s_a1[p1 * KP + i];
+                const double d = s * acc - t[i];
+                obj = obj + d * d;
+            }
+            if (hl < kBeam2Max + kExtra) {
+                s_xo[wave][h][hl] = obj;
+                s_xc[wave][h][hl] = code;
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            int rank = 0;
+            for (int j = 0; j < kBeam2Max + kExtra; ++j)
+                if (j < nc && better(s_xo[wave][h][j], s_xc[wave][h][j], obj, code)) ++rank;
+            __builtin_amdgcn_wave_barrier();
+            if (open && taken_extra > 0 && hl < nc && rank < keep) s_wb[wave][h][rank] = code;
+            if (taken_extra > 0) open = false;
         }
+        bad |= open;
         if (hl == 0) {
 #pragma unroll
             for (int i = 0; i < G; ++i) s_wt[wave][h][i] = t[i];

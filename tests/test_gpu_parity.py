@@ -495,6 +495,22 @@ def test_reencode_2x8_inputs_that_stress_the_filter(g, case):
         assert np.array_equal(got.reshape(-1, 2)[2 * gpr:3 * gpr], wl.codes.reshape(-1, 2)[2 * gpr:3 * gpr])
 
 
+@pytest.mark.parametrize("copies,step", [(10, 3e-6), (12, 3e-6), (40, 1e-5), (12, 1e-7), (256, 2e-7)])
+def test_reencode_2x8_near_copies_around_the_beam_boundary(copies, step):
+    """First codebook made of clusters of near-copies: the 8th and 9th best first codes differ
+    by less than the filter's 24-bit keys resolve (or, for the smallest steps, not at all).
+    The kernel then pulls in up to three more candidates and ranks them exactly, or leaves
+    the group to the exact kernel.  The codes are the oracle's either way."""
+    wl = workloads.make(16, 256, 8, 2, 8, seed=46, sigma_g=2e-3, tau=1.0, beam_width=8)
+    base = wl.codebooks[0].copy()
+    for c in range(256):
+        wl.codebooks[0, c] = base[c // copies] * np.float32(1.0 + step * (c % copies))
+    run, got, want, info = reencode_case(wl, 0)
+    assert np.array_equal(got, want)
+    st = run.ctx.pv_reencode_stats()
+    assert st["filtered"] + st["fallback"] == wl.k
+
+
 def test_reencode_2x8_non_finite_inputs_end_normally():
     wl = workloads.make(8, 128, 8, 2, 8, seed=44, sigma_g=2e-3, tau=1.0, beam_width=8)
     T_np = oracle.encode_targets(wl.W, wl.G, wl.alpha)
