@@ -66,8 +66,10 @@ def test_c2_full_every_group():
     assert stats["fallback"] < 0.02 * 20971      # the certificate holds for nearly every group
 
 
-def test_c3_full_beam_sampled():
-    run_config("c3_11008x4096_2x8", 4096)
+def test_c3_full_beam_every_group():
+    stats = run_config("c3_11008x4096_2x8", None)
+    assert stats["filtered"] + stats["fallback"] == 281804
+    assert stats["fallback"] < 0.01 * 281804     # the certificates hold for nearly every group
 
 
 @pytest.mark.parametrize("name", ["c5a_14336x4096_1x16g16", "c5b_4096x14336_1x16g16"])
