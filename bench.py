@@ -44,14 +44,20 @@ def run_stack(args) -> int:
     from paper_2405_14852_amd import Layout, PVContext
 
     dev = torch.device("cuda:0")
-    ctx = PVContext(0)
+    # The matrices are independent calls.  With --streams S they are dealt round-robin to S
+    # contexts, each on a stream of its own (default priority) with its own T / W scratch, so
+    # that the short latency-bound kernels of one matrix overlap the streaming kernels of another.
+    nstreams = max(1, args.streams)
+    streams = [torch.cuda.current_stream(dev)] + [torch.cuda.Stream(device=dev) for _ in range(nstreams - 1)]
+    ctxs = [PVContext(0, stream=st) for st in streams]
+    ctx = ctxs[0]
     gen = torch.Generator(device=dev)
     layers = 32
     mats = []
     shapes = list(workloads.LLAMA2_7B_BLOCK.values())
     max_n = max(o * i for o, i in shapes)
-    T = torch.empty(max_n, dtype=torch.float32, device=dev)
-    Wq = torch.empty(max_n, dtype=torch.float32, device=dev)
+    Ts = [torch.empty(max_n, dtype=torch.float32, device=dev) for _ in range(nstreams)]
+    Wqs = [torch.empty(max_n, dtype=torch.float32, device=dev) for _ in range(nstreams)]
     total_params = total_groups = total_k = 0
     for layer in range(layers):
         for pid, (name, (o, i)) in enumerate(workloads.LLAMA2_7B_BLOCK.items()):
@@ -73,17 +79,20 @@ def run_stack(args) -> int:
             total_params += o * i
             total_groups += N
             total_k += k
-    nch = torch.zeros(1, dtype=torch.int64, device=dev)
+    nchs = [torch.zeros(1, dtype=torch.int64, device=dev) for _ in range(nstreams)]
+    torch.cuda.synchronize()
 
-    def step():
-        for m in mats:
+    def step(lanes=nstreams):
+        for j, m in enumerate(mats):
+            c = j % lanes
+            cx, nch = ctxs[c], nchs[c]
             lay = m["lay"]
-            t, wq = T[: m["n"]].view(lay.out_features, lay.in_features), Wq[: m["n"]].view(
+            t, wq = Ts[c][: m["n"]].view(lay.out_features, lay.in_features), Wqs[c][: m["n"]].view(
                 lay.out_features, lay.in_features)
-            ctx.pv_dequantize(lay, m["codes"], m["cb"], m["sc"], wq)
-            ctx.pv_encode_targets_select(lay, m["W"], m["G"], 1.0, t, m["k"], m["idx"])
-            ctx.pv_reencode_groups(lay, t, m["cb"], m["sc"], m["idx"], m["k"], 1, m["codes"], nch)
-            ctx.pv_dequantize(lay, m["codes"], m["cb"], m["sc"], wq)
+            cx.pv_dequantize(lay, m["codes"], m["cb"], m["sc"], wq)
+            cx.pv_encode_targets_select(lay, m["W"], m["G"], 1.0, t, m["k"], m["idx"])
+            cx.pv_reencode_groups(lay, t, m["cb"], m["sc"], m["idx"], m["k"], 1, m["codes"], nch)
+            cx.pv_dequantize(lay, m["codes"], m["cb"], m["sc"], wq)
 
     steps = min(args.steps, 5)
     warmup = min(args.warmup, 1)
@@ -95,9 +104,9 @@ def run_stack(args) -> int:
         step()
     torch.cuda.synchronize()
     ms = 1e3 * (time.perf_counter() - t0) / steps
-    ctx.pv_timing_enable(True)
+    ctx.pv_timing_enable(True)      # per-kernel breakdown: one more sweep, all on one stream
     ctx.pv_timing_reset()
-    step()
+    step(lanes=1)
     torch.cuda.synchronize()
     kern = {}
     for name in ("dequantize", "encode_targets", "select", "prep", "score_mfma", "rerank", "exact_scan"):
@@ -112,7 +121,7 @@ def run_stack(args) -> int:
         "scaling": "weak", "vs_baseline": None, "dtype": "f16", "data": "synthetic (drawn on the device)",
         "config": {"workload": "c4_llama2_7b_stack", "matrices": len(mats), "parameters": total_params,
                    "groups": total_groups, "k_selected": total_k, "tau": 0.01, "group_size": 8,
-                   "num_codebooks": 1, "nbits": 16},
+                   "num_codebooks": 1, "nbits": 16, "streams": nstreams},
         "roofline": {"kernel": "k_score_mfma", "bound": "mfma", "achieved": a, "peak": PEAK_MFMA_F16,
                      "unit": "TFLOP/s", "frac": a / PEAK_MFMA_F16, "traffic": None},
         "cpu_baseline": None,
@@ -145,6 +154,8 @@ def main() -> int:
                     help="targets from one Adam update and selection by its size in one sweep "
                          "(pv_encode_targets_adam_select, beta 0.9/0.95, lr 3e-3)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--streams", type=int, default=4,
+                    help="c4_llama2_7b_stack only: contexts/streams the 224 matrices are dealt to")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on exactly one GPU (--gpus 1); the path shards by "
