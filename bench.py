@@ -154,6 +154,9 @@ def main() -> int:
                     help="targets from one Adam update and selection by its size in one sweep "
                          "(pv_encode_targets_adam_select, beta 0.9/0.95, lr 3e-3)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sparse-a9", action="store_true",
+                    help="last dequantize of the step rewrites only the re-encoded groups "
+                         "(pv_dequantize_groups); same weights, not the default")
     ap.add_argument("--streams", type=int, default=4,
                     help="c4_llama2_7b_stack only: contexts/streams the 224 matrices are dealt to")
     args = ap.parse_args()
@@ -232,7 +235,10 @@ def main() -> int:
         else:   # same outputs, T and W are not read back for the scores
             ctx.pv_encode_targets_select(lay, W, G, wl.alpha, T, k, idx)
         ctx.pv_reencode_groups(lay, T, cb, sc, idx, k, wl.beam_width, codes, nch)
-        ctx.pv_dequantize(lay, codes, cb, sc, Wq)
+        if args.sparse_a9:   # Wq holds the old codes' weights: only the re-encoded groups change
+            ctx.pv_dequantize_groups(lay, codes, cb, sc, idx, k, Wq)
+        else:
+            ctx.pv_dequantize(lay, codes, cb, sc, Wq)
 
     for _ in range(args.warmup):
         step()
@@ -366,7 +372,7 @@ def main() -> int:
         "config": {"workload": args.workload, "out_features": L.out_features,
                    "in_features": L.in_features, "group_size": g, "num_codebooks": M, "nbits": B,
                    "tau": wl.tau, "k_selected": k, "beam_width": wl.beam_width,
-                   "search_mode": args.search_mode, "path": args.path,
+                   "search_mode": args.search_mode, "path": args.path, "sparse_a9": bool(args.sparse_a9),
                    "calls": "fused adam targets+select" if args.adam else
                             "separate" if args.separate_calls else "fused targets+select"},
         "roofline": roofline,
