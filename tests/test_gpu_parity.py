@@ -301,6 +301,27 @@ def test_reencode_m1_matches_oracle(mode, g, B, shape, tau):
     reencode_case(wl, mode)
 
 
+@pytest.mark.parametrize("g", [8, 16])
+@pytest.mark.parametrize("k", [1, 31, 32, 33, 511, 512, 513, 4095, 4096, 4097, 4609, 8200])
+def test_reencode_m1_list_lengths_around_the_launch_plan(g, k):
+    """The filter's launch plan changes with the list length (group tiles per wave, codeword
+    splits, merged partitions, padded tail): lengths on both sides of every switch."""
+    wl = workloads.make(96, 96 * g, g, 1, 11, seed=50, sigma_g=2e-3, tau=1.0)
+    T_np = oracle.encode_targets(wl.W, wl.G, wl.alpha)
+    idx = np.sort(np.random.default_rng(k).choice(wl.layout.num_groups, size=k, replace=False)).astype(np.int32)
+    run, got, want, info = reencode_case(wl, 0, idx=idx, T_np=T_np)
+    st = run.ctx.pv_reencode_stats()
+    assert st["filtered"] + st["fallback"] == k
+
+
+@pytest.mark.parametrize("B", [5, 6, 9, 13, 16])
+def test_reencode_m1_codebook_sizes_with_long_lists(B):
+    """More than 4096 listed groups (two group tiles per wave) at every codebook size class."""
+    wl = workloads.make(64, 1024, 8, 1, B, seed=51, sigma_g=2e-3, tau=0.6)
+    assert wl.k > 4096
+    reencode_case(wl, 0)
+
+
 @pytest.mark.parametrize("mode", [1, 0])
 def test_reencode_m1_scale_edge_cases(mode):
     wl = workloads.make(32, 512, 8, 1, 10, seed=8, sigma_g=2e-3, tau=1.0)
