@@ -677,22 +677,18 @@ typedef double d4v __attribute__((ext_vector_type(4)));
 constexpr int kBeamBlock = 512;
 constexpr int kExtra = 3;   // candidates beyond the beam that the step-0 boundary check may pull in
 
-// smallest value over the 32 lanes of each half wave, in every lane of that half
-__device__ __forceinline__ unsigned half_min_u32(unsigned v, int half)
+// smallest value over the 32 lanes of each half wave, in every lane of that half: exchanges
+// inside quads, inside groups of 8 and of 16 lanes, then rows 0/1 and 2/3 swapped
+__device__ __forceinline__ unsigned half_min_u32(unsigned v)
 {
-    constexpr unsigned kId = 0xFFFFFFFFu;
-    v = min(v, (unsigned)__builtin_amdgcn_update_dpp((int)kId, (int)v, 0x111, 0xf, 0xf, false));  // row_shr:1
-    v = min(v, (unsigned)__builtin_amdgcn_update_dpp((int)kId, (int)v, 0x112, 0xf, 0xf, false));  // row_shr:2
-    v = min(v, (unsigned)__builtin_amdgcn_update_dpp((int)kId, (int)v, 0x114, 0xf, 0xf, false));  // row_shr:4
-    v = min(v, (unsigned)__builtin_amdgcn_update_dpp((int)kId, (int)v, 0x118, 0xf, 0xf, false));  // row_shr:8
-    v = min(v, (unsigned)__builtin_amdgcn_update_dpp((int)kId, (int)v, 0x142, 0xa, 0xf, false));  // row_bcast:15
-    const unsigned lo = (unsigned)__builtin_amdgcn_readlane((int)v, 31);
-    const unsigned hi = (unsigned)__builtin_amdgcn_readlane((int)v, 63);
-    return half ? hi : lo;
+    v = min(v, (unsigned)__builtin_amdgcn_update_dpp((int)v, (int)v, 0xB1, 0xf, 0xf, false));   // lane ^ 1
+    v = min(v, (unsigned)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x4E, 0xf, 0xf, false));   // lane ^ 2
+    v = min(v, (unsigned)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x141, 0xf, 0xf, false));  // row_half_mirror
+    v = min(v, (unsigned)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x140, 0xf, 0xf, false));  // row_mirror
+    const auto r = __builtin_amdgcn_permlane16_swap(v, v, false, false);
+    return min(r[0], r[1]);
 }
 
-// smallest value over the 32 lanes that share bit 3 of the lane number (the columns of one
-// group in the matrix instruction's layout), in every one of them
 __device__ __forceinline__ double dpp_quad_f64(double v, int ctrl_sel)
 {
     int lo = __double2loint(v), hi = __double2hiint(v);
@@ -852,7 +848,7 @@ __global__ __launch_bounds__(kBeamBlock, 4) void k_beam_2x8_mfma(
             }
             // keys carry the distance above (a lower bound of) the smallest candidate: the 12
             // mantissa bits that fit beside the code then resolve the gaps between the best few
-            const double floor_v = __hiloint2double((int)(half_min_u32(top, h) & ~0xFFu), 0);
+            const double floor_v = __hiloint2double((int)(half_min_u32(top) & ~0xFFu), 0);
 #pragma unroll
             for (int q = 0; q < 8; ++q)
                 key[q] = ((unsigned)__double2hiint(v[q] - floor_v) & ~0xFFu) | (unsigned)(hl + 32 * q);
@@ -867,7 +863,7 @@ __global__ __launch_bounds__(kBeamBlock, 4) void k_beam_2x8_mfma(
                 head = umin3(head, key[3] - base, key[4] - base);
                 head = umin3(head, key[5] - base, key[6] - base);
                 head = min(head, key[7] - base);
-                const unsigned m = half_min_u32(head, h) + base;
+                const unsigned m = half_min_u32(head) + base;
                 if (rnd < keep) {
                     if (hl == 0) s_wb[wave][h][rnd] = (int)(m & 0xFFu);
                     k_last = m;
@@ -897,7 +893,7 @@ __global__ __launch_bounds__(kBeamBlock, 4) void k_beam_2x8_mfma(
                 head = umin3(head, key[3] - base, key[4] - base);
                 head = umin3(head, key[5] - base, key[6] - base);
                 head = min(head, key[7] - base);
-                const unsigned m = half_min_u32(head, h) + base;
+                const unsigned m = half_min_u32(head) + base;
                 base = m + 1u;
                 extra[x] = m;
                 if (taken_extra == 0 && lower_of(m) - upper_of(extra[x - 1]) > 2.0 * E) taken_extra = x;
