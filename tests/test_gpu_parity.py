@@ -532,6 +532,33 @@ def test_reencode_2x8_near_copies_around_the_beam_boundary(copies, step):
     assert st["filtered"] + st["fallback"] == wl.k
 
 
+@pytest.mark.parametrize("M,B,g,beam", [(2, 8, 8, 8), (2, 8, 8, 2), (3, 4, 8, 4)])
+def test_reencode_beam_repeated_sweeps(M, B, g, beam):
+    """A second call on the same list is a second sweep over the codebooks, seeded with the
+    first sweep's winner (App. D's local search repeated): same codes as the oracle applied
+    twice, objective non-increasing, and a fixed point once nothing moves."""
+    wl = workloads.make(16, 32 * g, g, M, B, seed=60, sigma_g=4e-3, tau=1.0, beam_width=beam)
+    run = GpuRun(wl)
+    T_np = oracle.encode_targets(wl.W, wl.G, wl.alpha)
+    idx = np.arange(wl.layout.num_groups, dtype=np.int32)
+    T = dev_f32(T_np)
+    got = wl.codes
+    want = wl.codes
+    prev_obj = None
+    for sweep in range(4):
+        got, nch = run.reencode(T, idx, codes=dev_u16(got))
+        want, info = oracle.reencode_groups(T_np, wl.codebooks, wl.scales, idx, want, beam_width=beam)
+        assert np.array_equal(got, want) or info["near_tie"].any()
+        got = want       # continue from the oracle's codes when a near-tie was resolved differently
+        assert nch == info["num_changed"] or info["near_tie"].any()
+        if prev_obj is not None:
+            assert (info["obj_prev"] <= prev_obj * (1 + 1e-12)).all()
+        prev_obj = info["obj_new"]
+        if info["num_changed"] == 0:
+            break
+    assert sweep >= 1        # the second sweep still finds better tuples for some groups
+
+
 def test_reencode_2x8_non_finite_inputs_end_normally():
     wl = workloads.make(8, 128, 8, 2, 8, seed=44, sigma_g=2e-3, tau=1.0, beam_width=8)
     T_np = oracle.encode_targets(wl.W, wl.G, wl.alpha)
