@@ -76,54 +76,20 @@ __device__ __forceinline__ double segment_sum(const int32_t *__restrict__ order,
     return acc;
 }
 
-// One block: extra[c] = number of pieces of codeword c beyond the first, as an exclusive
-// prefix over c (extra[csize] = total).  A segment of len groups has ceil(len / kLong) pieces.
-__global__ __launch_bounds__(kBlock) void k_pg_extra(const int32_t *__restrict__ start, int csize,
-                                                     int32_t *__restrict__ extra)
-{
-    __shared__ int s_wave[kBlock / 64];
-    __shared__ int s_carry;
-    constexpr int kOwn = 16;                  // consecutive codewords per thread
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    if (threadIdx.x == 0) s_carry = 0;
-    __syncthreads();
-    for (int base = 0; base < csize; base += kBlock * kOwn) {
-        const int c0 = base + threadIdx.x * kOwn;
-        int cnt[kOwn], mine = 0;
-#pragma unroll
-        for (int e = 0; e < kOwn; ++e) {
-            const int c = c0 + e;
-            int len = c < csize ? start[c + 1] - start[c] : 0;
-            cnt[e] = len > kLong ? (len + kLong - 1) / kLong - 1 : 0;
-            mine += cnt[e];
-        }
-        int inc = mine;
-#pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-            int u = __shfl_up(inc, off);
-            if (lane >= off) inc += u;
-        }
-        if (lane == 63) s_wave[wave] = inc;
-        __syncthreads();
-        int run = s_carry + inc - mine;
-        int total = 0;
-#pragma unroll
-        for (int w = 0; w < kBlock / 64; ++w) {
-            if (w < wave) run += s_wave[w];
-            total += s_wave[w];
-        }
-#pragma unroll
-        for (int e = 0; e < kOwn; ++e) {
-            const int c = c0 + e;
-            if (c < csize) extra[c] = run;
-            run += cnt[e];
-        }
-        __syncthreads();
-        if (threadIdx.x == 0) s_carry += total;
-        __syncthreads();
+// extra[c] = number of pieces of the codewords before c beyond their first ones (an exclusive
+// prefix sum, extra[csize] = total), by the library's device scan over this functor.  A
+// segment of len groups has ceil(len / kLong) pieces.
+struct extra_pieces {
+    const int32_t *start;
+    int csize;
+    __host__ __device__ int operator()(int c) const
+    {
+        if (c >= csize) return 0;
+        const int len = start[c + 1] - start[c];
+        return len > kLong ? (len + kLong - 1) / kLong - 1 : 0;
     }
-    if (threadIdx.x == 0) extra[csize] = s_carry;
-}
+};
+typedef hipcub::TransformInputIterator<int, extra_pieces, hipcub::CountingInputIterator<int>> extra_iter;
 
 // TEAM lanes per work item (the group size rounded up to a power of two); lane i sums
 // dimension i.  Items [0, csize): the first piece of every codeword - written straight to
@@ -349,10 +315,15 @@ pv_status pv_launch_codebook_grads(pv_ctx *ctx, const pv_layout *l, const float 
         return PV_OK;
     }
 
-    size_t sort_bytes = 0;
+    size_t sort_bytes = 0, scan_bytes = 0;
     PV_HIP(ctx, hipcub::DeviceRadixSort::SortPairs(nullptr, sort_bytes, (const uint16_t *)nullptr,
                                                    (uint16_t *)nullptr, (const int32_t *)nullptr,
                                                    (int32_t *)nullptr, (int)N, 0, l->nbits, sm));
+    PV_HIP(ctx, hipcub::DeviceScan::ExclusiveSum(
+                    nullptr, scan_bytes,
+                    extra_iter(hipcub::CountingInputIterator<int>(0), extra_pieces{nullptr, csize}),
+                    (int32_t *)nullptr, csize + 1, sm));
+    if (scan_bytes > sort_bytes) sort_bytes = scan_bytes;   // one temporary area serves both
     const size_t nn = (size_t)N;
     const int64_t max_extra = N / kLong + 1;
     size_t o_keys = 0;
@@ -391,7 +362,10 @@ pv_status pv_launch_codebook_grads(pv_ctx *ctx, const pv_layout *l, const float 
         PV_HIP(ctx, hipcub::DeviceRadixSort::SortPairs(sort_tmp, sort_bytes, keys, keys2, vals, order,
                                                        (int)N, 0, l->nbits, sm));
         hipLaunchKernelGGL(k_pg_starts, dim3(nblocks), dim3(kBlock), 0, sm, keys2, N, csize, start);
-        hipLaunchKernelGGL(k_pg_extra, dim3(1), dim3(kBlock), 0, sm, start, csize, extra);
+        PV_HIP(ctx, hipcub::DeviceScan::ExclusiveSum(
+                        sort_tmp, sort_bytes,
+                        extra_iter(hipcub::CountingInputIterator<int>(0), extra_pieces{start, csize}),
+                        extra, csize + 1, sm));
         float *out = grad_codebooks + (int64_t)m * csize * g;
 #define PV_ACC(TEAM_)                                                                            \
     hipLaunchKernelGGL(k_pg_accumulate<TEAM_>, dim3(ablocks), dim3(kBlock), 0, sm, start, extra,    \
