@@ -154,6 +154,9 @@ def main() -> int:
                     help="targets from one Adam update and selection by its size in one sweep "
                          "(pv_encode_targets_adam_select, beta 0.9/0.95, lr 3e-3)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--structured", action="store_true",
+                    help="W = the dequantised initial codes and the gradient x40 (the regime of a "
+                         "real V step) instead of the configuration's dense Gaussian W")
     ap.add_argument("--sparse-a9", action="store_true",
                     help="last dequantize of the step rewrites only the re-encoded groups "
                          "(pv_dequantize_groups); same weights, not the default")
@@ -195,6 +198,13 @@ def main() -> int:
     Wq = torch.empty_like(W)
     idx = torch.empty(k, dtype=torch.int32, device=dev)
     nch = torch.zeros(1, dtype=torch.int64, device=dev)
+
+    if args.structured and args.path == "vstep":
+        # the regime of a real V step: W is the dequantised current codes and the update is a
+        # fraction of the codeword spacing (gradient x40, as in the trust-ratio path)
+        ctx.pv_dequantize(lay, codes0, cb, sc, W)
+        G.mul_(40.0)
+        torch.cuda.synchronize()
 
     if args.path == "trust_ratio":
         G.mul_(40.0)
@@ -339,6 +349,9 @@ def main() -> int:
                "kept_equal_oracle": int(napp.item()) == tinfo["num_applied"]}
     elif not args.no_cpu_baseline and not args.adam:
         import oracle
+        if args.structured:      # the oracle's own copies of the same inputs
+            wl.W = oracle.dequantize(wl.codes, wl.codebooks, wl.scales)
+            wl.G = wl.G * np.float32(40.0)
         t1 = time.perf_counter()
         Wq_ref = oracle.dequantize(wl.codes, wl.codebooks, wl.scales)
         T_ref = oracle.encode_targets(wl.W, wl.G, wl.alpha)
@@ -372,7 +385,7 @@ def main() -> int:
         "config": {"workload": args.workload, "out_features": L.out_features,
                    "in_features": L.in_features, "group_size": g, "num_codebooks": M, "nbits": B,
                    "tau": wl.tau, "k_selected": k, "beam_width": wl.beam_width,
-                   "search_mode": args.search_mode, "path": args.path, "sparse_a9": bool(args.sparse_a9),
+                   "search_mode": args.search_mode, "path": args.path, "sparse_a9": bool(args.sparse_a9), "structured": bool(args.structured),
                    "calls": "fused adam targets+select" if args.adam else
                             "separate" if args.separate_calls else "fused targets+select"},
         "roofline": roofline,

@@ -36,7 +36,7 @@ struct pv_ctx {
 
     // scratch, grown on demand (never shrunk)
     pv_buffer sel_scores;   // f32 [N]            group scores when the caller passes none
-    pv_buffer sel_hist;     // u32 [3][2048]      radix-select histograms (kept zero between calls)
+    pv_buffer sel_hist;     // u32 [copies + 2][bins]  radix-select histograms (kept zero between calls)
     pv_buffer sel_blocks;   // u32 [nblocks][2]   per-block (greater, equal) counts
     pv_buffer sel_state;    // u32 [4]            threshold key, ties to take
     pv_buffer stats;        // i64 [8]            counters of the last re-encode

@@ -106,6 +106,18 @@ __device__ __forceinline__ unsigned block_excl_scan(unsigned v, unsigned *tmp, u
 // thread t of the scan owns ranks [kPer t, kPer t + kPer), i.e. slots t, t + 256, ...
 // Every histogram occupies kBins slots.
 constexpr int kPer = kBins / kBlock;
+// The first histogram is fed by every block of the scoring sweep at about the same moment, and
+// most of the counts fall on a dozen bins: its atomics would queue on a dozen addresses (5 to
+// 14 us on 2 M groups, depending on where the scores fall).  It is kept in kSub copies (two
+// already take the queue below the kernel's streaming time; more only cost the readers), block
+// b adds to copy b % kSub, the reader adds the copies.
+#ifndef PV_HIST_COPIES
+#define PV_HIST_COPIES 2
+#endif
+constexpr int kSub = PV_HIST_COPIES;
+constexpr int kHist1 = kSub * kBins;          // offsets of the second and third histogram
+constexpr int kHist2 = kHist1 + kBins;
+constexpr int kHistTotal = kHist2 + kBins;
 __device__ __forceinline__ int hist_slot(int digit, int bins)
 {
     const int r = bins - 1 - digit;
@@ -116,6 +128,7 @@ __device__ __forceinline__ int hist_slot(int digit, int bins)
 // largest digit), find the digit d with  count(> d) < kk <= count(>= d)  and
 // return kk - count(> d).  All threads of the block call this; the result goes
 // to all.  `tmp` is kBlock + 2 unsigneds of LDS.
+template <int COPIES = 1>
 __device__ void pick_digit(const unsigned *__restrict__ ghist, int bins, unsigned kk,
                            unsigned *tmp, int *digit, unsigned *kk_rem)
 {
@@ -125,7 +138,13 @@ __device__ void pick_digit(const unsigned *__restrict__ ghist, int bins, unsigne
     unsigned sum = 0;
 #pragma unroll
     for (int j = 0; j < per; ++j) {
-        cnt[j] = (tid * per + j) < bins ? ghist[j * kBlock + tid] : 0u;
+        unsigned part[COPIES];     // all loads of the copies in flight together
+#pragma unroll
+        for (int c = 0; c < COPIES; ++c)
+            part[c] = (tid * per + j) < bins ? ghist[c * kBins + j * kBlock + tid] : 0u;
+        cnt[j] = 0u;
+#pragma unroll
+        for (int c = 0; c < COPIES; ++c) cnt[j] += part[c];
         sum += cnt[j];
     }
     unsigned total;
@@ -200,7 +219,7 @@ __global__ __launch_bounds__(kBlock) void k_scores_hist0(const float *__restrict
         if (want_hist) hist_add<PV_VOTE_ROUNDS>(lh, digit_of(key, 0), valid);
     }
     __syncthreads();
-    if (want_hist) flush_hist(lh, hist0, kFirstBins);
+    if (want_hist) flush_hist(lh, hist0 + (blockIdx.x % kSub) * kBins, kFirstBins);
 }
 
 // Pass 0 for g = 4 * PARTS (PARTS a power of two): every lane loads one 16-byte
@@ -264,7 +283,7 @@ __global__ __launch_bounds__(kBlock) void k_scores_hist0_vec(const float *__rest
         }
     }
     __syncthreads();
-    if (want_hist) flush_hist(lh, hist0, kFirstBins);
+    if (want_hist) flush_hist(lh, hist0 + (blockIdx.x % kSub) * kBins, kFirstBins);
 }
 
 // Targets and pass 0 in one sweep (g = 4 * PARTS): T = W - alpha * G is formed and stored, and
@@ -364,7 +383,7 @@ __global__ __launch_bounds__(kBlock) void k_targets_scores_hist0_vec(const float
         }
     }
     __syncthreads();
-    if (want_hist) flush_hist(lh, hist0, kFirstBins);
+    if (want_hist) flush_hist(lh, hist0 + (blockIdx.x % kSub) * kBins, kFirstBins);
 }
 
 // Passes 1 and 2: histogram of the next digit among keys that match the digits
@@ -384,14 +403,14 @@ __global__ __launch_bounds__(kBlock) void k_hist_next(const float *__restrict__ 
     int d0, d1 = 0;
     unsigned kk;
     if (pass == 1) {
-        pick_digit(hist_all, kFirstBins, k, tmp, &d0, &kk);
+        pick_digit<kSub>(hist_all, kFirstBins, k, tmp, &d0, &kk);
         if (blockIdx.x == 0 && threadIdx.x == 0) {
             state[4] = (unsigned)d0;
             state[6] = kk;
         }
     } else {
         d0 = (int)state[4];
-        pick_digit(hist_all + kBins, kBins, state[6], tmp, &d1, &kk);
+        pick_digit(hist_all + kHist1, kBins, state[6], tmp, &d1, &kk);
         if (blockIdx.x == 0 && threadIdx.x == 0) {
             state[5] = (unsigned)d1;
             state[7] = kk;
@@ -448,7 +467,7 @@ __global__ __launch_bounds__(kBlock) void k_chunk_counts(const float *__restrict
     const int d0 = (int)state[4], d1 = (int)state[5];
     int d2;
     unsigned kk;
-    pick_digit(hist_all + 2 * kBins, kLastBins, state[7], tmp, &d2, &kk);
+    pick_digit(hist_all + kHist2, kLastBins, state[7], tmp, &d2, &kk);
     const unsigned thr = ((unsigned)d0 << 21) | ((unsigned)d1 << (21 - kMidBits)) | (unsigned)d2;
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         state[0] = thr;
@@ -537,7 +556,7 @@ __global__ __launch_bounds__(kBlock) void k_compact_write(const float *__restric
         }
     }
     // leave the histograms zero for the next call (all their readers ran in earlier launches)
-    for (int64_t z = (int64_t)blockIdx.x * kBlock + threadIdx.x; z < 3 * kBins;
+    for (int64_t z = (int64_t)blockIdx.x * kBlock + threadIdx.x; z < kHistTotal;
          z += (int64_t)gridDim.x * kBlock)
         hist_all[z] = 0;
 }
@@ -558,7 +577,7 @@ pv_status pv_launch_select(pv_ctx *ctx, const pv_layout *l, const float *T, cons
         scores = static_cast<float *>(ctx->sel_scores.ptr);
     }
     const int nchunks = (N + kChunk - 1) / kChunk;
-    st = pv_ensure(ctx, ctx->sel_hist, 3 * kBins * sizeof(unsigned), /*zero_new=*/true);
+    st = pv_ensure(ctx, ctx->sel_hist, (size_t)kHistTotal * sizeof(unsigned), /*zero_new=*/true);
     if (st != PV_OK) return st;
     st = pv_ensure(ctx, ctx->sel_blocks, (size_t)nchunks * 2 * sizeof(unsigned));
     if (st != PV_OK) return st;
@@ -625,9 +644,9 @@ pv_status pv_launch_select(pv_ctx *ctx, const pv_layout *l, const float *T, cons
         const unsigned hblocks = (unsigned)(hb < 512 ? (hb < 1 ? 1 : hb) : 512);
         const unsigned cblocks = (unsigned)(nchunks < kMaxBlocks ? nchunks : kMaxBlocks);
         hipLaunchKernelGGL(k_hist_next, dim3(hblocks), dim3(kBlock), 0, ctx->stream, scores, hist,
-                           hist + kBins, state, N, (unsigned)k, 1);
+                           hist + kHist1, state, N, (unsigned)k, 1);
         hipLaunchKernelGGL(k_hist_next, dim3(hblocks), dim3(kBlock), 0, ctx->stream, scores, hist,
-                           hist + 2 * kBins, state, N, (unsigned)k, 2);
+                           hist + kHist2, state, N, (unsigned)k, 2);
         hipLaunchKernelGGL(k_chunk_counts, dim3(cblocks), dim3(kBlock), 0, ctx->stream, scores, hist,
                            state, cc, N, nchunks);
         hipLaunchKernelGGL(k_compact_write, dim3(cblocks), dim3(kBlock), 0, ctx->stream, scores,
