@@ -312,6 +312,33 @@ def main() -> int:
         roofline = {"kernel": "k_" + dominant, "bound": "hbm", "achieved": a, "peak": PEAK_HBM,
                     "unit": "GB/s", "frac": a / PEAK_HBM, "traffic": None}
 
+    # ceilings of this machine at this moment, measured with two kernels of the library: a plain
+    # 64 MiB streaming copy and a loop of nothing but fp16 matrix instructions
+    csrc = torch.empty(16 * 1024 * 1024, dtype=torch.float32, device=dev).normal_()
+    cdst = torch.empty_like(csrc)
+    sink = torch.empty(256 * 16 * 64, dtype=torch.float32, device=dev)
+    mfma_iters = 4096
+    for _ in range(3):
+        ctx.pv_probe_copy(cdst, csrc)
+        waves = ctx.pv_probe_mfma_f16(mfma_iters, sink)
+    torch.cuda.synchronize()
+    ctx.pv_timing_enable(True)
+    ctx.pv_timing_reset()
+    for _ in range(20):
+        ctx.pv_probe_copy(cdst, csrc)
+    for _ in range(5):
+        ctx.pv_probe_mfma_f16(mfma_iters, sink)
+    t_copy, n_copy = ctx.pv_timing_read("probe_copy")
+    t_mfma, n_mfma = ctx.pv_timing_read("probe_mfma")
+    ctx.pv_timing_enable(False)
+    ceilings = {
+        "copy_GBps": 2.0 * csrc.numel() * 4 / (t_copy / n_copy * 1e-3) / 1e9,
+        "mfma_f16_TFLOPs": waves * mfma_iters * 2.0 * 32 * 32 * 16 / (t_mfma / n_mfma * 1e-3) / 1e12,
+        "how": "pv_probe_copy on 64 MiB (read + write), pv_probe_mfma_f16 (4 waves per SIMD, "
+               "independent v_mfma_f32_32x32x16_f16 only), HIP events",
+    }
+    del csrc, cdst
+
     hbm = {}
     for name, per_param in (("encode_targets", 28.0 + 4.0 / g if args.adam else 12.0 + (0.0 if args.separate_calls else 4.0 / g)),
                             ("group_scores", 8.0 + 4.0 / g),
@@ -395,7 +422,7 @@ def main() -> int:
                                        if "score_mfma" in kern else None),
         "scoring_frac_of_mfma_peak": (flops_contraction / (kern["score_mfma"]["avg_ms"] * 1e-3) / 1e12
                                       / PEAK_MFMA_F16 if "score_mfma" in kern else None),
-        "hbm": hbm, "kernels": kern, "groups_changed": changed, "reencode_stats": stats,
+        "hbm": hbm, "measured_ceilings": ceilings, "kernels": kern, "groups_changed": changed, "reencode_stats": stats,
     }
     if args.path == "trust_ratio":
         out["trust_ratio"] = {"ratio": 0.01, "candidates": k, "kept": int(napp.item()),

@@ -230,7 +230,9 @@ typedef enum {
     PV_K_DEQUANTIZE = 8,
     PV_K_TRUST_RATIO = 9, /* norms, ranking, prefix sums, roll-back of pv_reencode_trust_ratio */
     PV_K_PSTEP = 10,      /* all kernels of pv_codebook_grads                              */
-    PV_K_COUNT = 11
+    PV_K_PROBE_COPY = 11, /* pv_probe_copy                                                 */
+    PV_K_PROBE_MFMA = 12, /* pv_probe_mfma_f16                                             */
+    PV_K_COUNT = 13
 } pv_kernel_id;
 
 /* With timing on, each kernel (group) above is bracketed by HIP events on the
@@ -239,6 +241,19 @@ typedef enum {
 pv_status pv_timing_enable(pv_ctx *ctx, int on);
 pv_status pv_timing_reset(pv_ctx *ctx);
 pv_status pv_timing_read(pv_ctx *ctx, int kernel_id, double *total_ms, int64_t *launches);
+
+/* Machine ceilings measured with two kernels of this library, for callers that want to
+ * relate a measured rate to what the same box reaches at that moment (bench.py reports
+ * them beside the published peaks).  Both enqueue on the context's stream and are timed
+ * like every other kernel (PV_K_PROBE_COPY, PV_K_PROBE_MFMA).
+ * pv_probe_copy: dst[0 .. bytes) = src[0 .. bytes), device pointers, 16-byte aligned,
+ * bytes a multiple of 16, non-overlapping: one streaming pass, 2 * bytes of HBM traffic.
+ * pv_probe_mfma_f16: every wave of a grid that fills the chip (4 waves per SIMD) issues
+ * `iters` independent v_mfma_f32_32x32x16_f16 (2 * 32 * 32 * 16 FLOP each) and nothing else;
+ * sink: f32 [256 * 16 * 64] device buffer that receives the accumulators (so that the work
+ * cannot be removed); *waves_out (host pointer, NULL ok) = number of waves launched. */
+pv_status pv_probe_copy(pv_ctx *ctx, void *dst, const void *src, int64_t bytes);
+pv_status pv_probe_mfma_f16(pv_ctx *ctx, int64_t iters, float *sink, int64_t *waves_out);
 
 /* Counters of the last pv_reencode_groups call (waits for the stream):
  * stats[0] = groups decided by a matrix-core filter (one codebook: the fp16

@@ -19,6 +19,7 @@ _lib = None
 KERNEL_IDS = {
     "encode_targets": 0, "group_scores": 1, "select": 2, "prep": 3, "score_mfma": 4,
     "rerank": 5, "exact_scan": 6, "beam": 7, "dequantize": 8, "trust_ratio": 9, "pstep": 10,
+    "probe_copy": 11, "probe_mfma": 12,
 }
 
 
@@ -90,13 +91,15 @@ def load_library():
     lib.pv_timing_read.argtypes = [vp, ctypes.c_int, ctypes.POINTER(ctypes.c_double),
                                    ctypes.POINTER(i64)]
     lib.pv_reencode_stats.argtypes = [vp, ctypes.POINTER(i64)]
+    lib.pv_probe_copy.argtypes = [vp, vp, vp, i64]
+    lib.pv_probe_mfma_f16.argtypes = [vp, i64, vp, ctypes.POINTER(i64)]
     for name in ("pv_create", "pv_encode_targets", "pv_encode_targets_adam", "pv_select_topk_groups",
                  "pv_encode_targets_adam_select",
                  "pv_encode_targets_select", "pv_reencode_groups", "pv_reencode_trust_ratio",
                  "pv_codebook_grads", "pv_dequantize_scalar", "pv_reencode_scalar",
                  "pv_dequantize_groups",
                  "pv_dequantize", "pv_set_search_mode", "pv_timing_enable", "pv_timing_reset",
-                 "pv_timing_read", "pv_reencode_stats"):
+                 "pv_timing_read", "pv_reencode_stats", "pv_probe_copy", "pv_probe_mfma_f16"):
         getattr(lib, name).restype = ctypes.c_int
     _lib = lib
     return lib
@@ -271,6 +274,19 @@ class PVContext:
         ms, n = ctypes.c_double(0), ctypes.c_int64(0)
         self._check(self._lib.pv_timing_read(self._h, kid, ctypes.byref(ms), ctypes.byref(n)))
         return ms.value, n.value
+
+    def pv_probe_copy(self, dst, src):
+        nbytes = src.numel() * src.element_size()
+        if dst.numel() * dst.element_size() != nbytes:
+            raise ValueError("dst and src differ in size")
+        self._check(self._lib.pv_probe_copy(self._h, ctypes.c_void_p(dst.data_ptr()),
+                                            ctypes.c_void_p(src.data_ptr()), int(nbytes)))
+
+    def pv_probe_mfma_f16(self, iters: int, sink):
+        waves = ctypes.c_int64(0)
+        self._check(self._lib.pv_probe_mfma_f16(self._h, int(iters), _dev_ptr(sink, torch.float32, "sink"),
+                                                ctypes.byref(waves)))
+        return waves.value
 
     def pv_reencode_stats(self):
         arr = (ctypes.c_int64 * 4)()

@@ -463,6 +463,28 @@ extern "C" pv_status pv_set_search_mode(pv_ctx *ctx, int mode)
     return PV_OK;
 }
 
+extern "C" pv_status pv_probe_copy(pv_ctx *ctx, void *dst, const void *src, int64_t bytes)
+{
+    if (!ctx) return PV_ERR_INVALID_ARG;
+    if (!dst || !src) return pv_fail(ctx, PV_ERR_INVALID_ARG, "NULL pointer");
+    if (bytes < 0 || (bytes & 15) || misaligned(dst) || misaligned(src))
+        return pv_fail(ctx, PV_ERR_INVALID_ARG, "pointers and size must be multiples of 16 bytes");
+    if (bytes / 16 / 256 >= (int64_t)1 << 31) return pv_fail(ctx, PV_ERR_INVALID_ARG, "size too large");
+    if (bytes == 0) return PV_OK;
+    PV_HIP(ctx, hipSetDevice(ctx->device));
+    return pv_launch_probe_copy(ctx, dst, src, bytes);
+}
+
+extern "C" pv_status pv_probe_mfma_f16(pv_ctx *ctx, int64_t iters, float *sink, int64_t *waves_out)
+{
+    if (!ctx) return PV_ERR_INVALID_ARG;
+    if (!sink) return pv_fail(ctx, PV_ERR_INVALID_ARG, "sink is NULL");
+    if (iters < 4 || iters > ((int64_t)1 << 24) || (iters & 3))
+        return pv_fail(ctx, PV_ERR_INVALID_ARG, "iters must be a multiple of 4 in [4, 2^24]");
+    PV_HIP(ctx, hipSetDevice(ctx->device));
+    return pv_launch_probe_mfma(ctx, iters, sink, waves_out);
+}
+
 extern "C" pv_status pv_timing_enable(pv_ctx *ctx, int on)
 {
     if (!ctx) return PV_ERR_INVALID_ARG;

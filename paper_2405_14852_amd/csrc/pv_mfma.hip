@@ -898,7 +898,47 @@ plan_t make_plan(const pv_layout *l, int64_t k)
     return p;
 }
 
+// Nothing but matrix instructions: four independent accumulators per wave, four waves per
+// SIMD over the whole chip (the matrix-core ceiling of the box at its current clock).
+constexpr int kProbeBlocks = 256 * 4;
+__global__ __launch_bounds__(kBlock, 4) void k_probe_mfma(float *__restrict__ sink, int64_t iters)
+{
+    const int lane = threadIdx.x & 63;
+    h8 a, b;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        a[e] = (_Float16)(0.001f * (float)(lane + e));
+        b[e] = (_Float16)(0.5f + 0.01f * (float)e);
+    }
+    f16v acc[4];
+#pragma unroll
+    for (int n = 0; n < 4; ++n)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[n][r] = 0.0f;
+    for (int64_t it = 0; it + 4 <= iters; it += 4) {
+#pragma unroll
+        for (int n = 0; n < 4; ++n) acc[n] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a, b, acc[n], 0, 0, 0);
+    }
+    if (blockIdx.x < 256) {
+        float s = 0.0f;
+#pragma unroll
+        for (int n = 0; n < 4; ++n)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) s += acc[n][r];
+        sink[((int64_t)blockIdx.x * 16 + (threadIdx.x >> 6)) * 64 + lane] = s;
+    }
+}
+
 }  // namespace
+
+pv_status pv_launch_probe_mfma(pv_ctx *ctx, int64_t iters, float *sink, int64_t *waves_out)
+{
+    pv_timed t(ctx, PV_K_PROBE_MFMA);
+    hipLaunchKernelGGL(k_probe_mfma, dim3(kProbeBlocks), dim3(kBlock), 0, ctx->stream, sink, iters);
+    PV_HIP(ctx, hipGetLastError());
+    if (waves_out) *waves_out = (int64_t)kProbeBlocks * (kBlock / 64);
+    return PV_OK;
+}
 
 bool pv_mfma_supported(const pv_layout *l)
 {

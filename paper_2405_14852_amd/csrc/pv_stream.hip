@@ -185,6 +185,15 @@ __global__ __launch_bounds__(kBlock) void k_dequantize_groups(const uint16_t *__
     }
 }
 
+// plain streaming copy, one 16-byte vector per thread (the ceiling the streaming kernels of
+// this file are compared with)
+__global__ __launch_bounds__(kBlock) void k_probe_copy(const pv_f4 *__restrict__ src,
+                                                       pv_f4 *__restrict__ dst, int64_t n)
+{
+    const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (i < n) __builtin_nontemporal_store(__builtin_nontemporal_load(&src[i]), &dst[i]);
+}
+
 __global__ void k_fill_i64(int64_t *p, int64_t n, int64_t v)
 {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -287,6 +296,17 @@ pv_status pv_launch_dequantize_groups(pv_ctx *ctx, const pv_layout *l, const uin
                            dim3(kBlock), 0, ctx->stream, codes, codebooks, scales, group_idx, total,
                            W_out, g, l->num_codebooks, l->nbits, gpr, N);
     }
+    PV_HIP(ctx, hipGetLastError());
+    return PV_OK;
+}
+
+pv_status pv_launch_probe_copy(pv_ctx *ctx, void *dst, const void *src, int64_t bytes)
+{
+    pv_timed t(ctx, PV_K_PROBE_COPY);
+    const int64_t n = bytes / 16;
+    const int64_t blocks = (n + kBlock - 1) / kBlock;
+    hipLaunchKernelGGL(k_probe_copy, dim3((unsigned)blocks), dim3(kBlock), 0, ctx->stream,
+                       static_cast<const pv_f4 *>(src), static_cast<pv_f4 *>(dst), n);
     PV_HIP(ctx, hipGetLastError());
     return PV_OK;
 }

@@ -411,6 +411,31 @@ def test_reencode_empty_selection_and_errors():
         run.ctx.pv_dequantize(bad, run.codes, run.cb, run.sc, T)
 
 
+# ------------------------------------------------------- ceiling probes
+
+def test_probe_kernels_copy_exactly_and_report_plausible_rates():
+    from paper_2405_14852_amd import PVContext, PVError
+    ctx = PVContext(0)
+    src = torch.randn(1 << 20, dtype=torch.float32, device=DEV)
+    dst = torch.zeros_like(src)
+    ctx.pv_probe_copy(dst, src)
+    torch.cuda.synchronize()
+    assert torch.equal(dst, src)
+    sink = torch.zeros(256 * 16 * 64, dtype=torch.float32, device=DEV)
+    ctx.pv_probe_mfma_f16(1024, sink)          # the first launch loads the code
+    ctx.pv_timing_enable(True)
+    waves = ctx.pv_probe_mfma_f16(1024, sink)
+    ms, n = ctx.pv_timing_read("probe_mfma")
+    assert waves == 256 * 4 * 4 and n == 1
+    rate = waves * 1024 * 2.0 * 32 * 32 * 16 / (ms * 1e-3) / 1e12
+    assert 200.0 < rate < 2600.0           # TFLOP/s: below the published peak, far above vector rates
+    assert torch.isfinite(sink).all() and float(sink.abs().max()) > 0
+    with pytest.raises(PVError):
+        ctx.pv_probe_mfma_f16(3, sink)
+    with pytest.raises(PVError):
+        ctx.pv_probe_copy(dst[1:], src[1:])     # 4-byte offset: not 16-byte aligned
+
+
 # ------------------------------------------------------- re-encode, beam search
 
 @pytest.mark.parametrize("M,B,g,beam,shape", [
