@@ -13,6 +13,8 @@
  * pv_codebook_grads (Alg. 3 P step: gradients of codebooks and scales),
  * pv_dequantize_groups (dequantisation of the re-encoded groups only),
  * pv_dequantize_scalar / pv_reencode_scalar (App. K's scalar uniform-grid representation).
+ * Instrumentation: pv_set_search_mode, pv_timing_*, pv_reencode_stats, and the two ceiling
+ * probes pv_probe_copy / pv_probe_mfma_f16.
  *
  * Conventions for every call
  *   - All tensor pointers are DEVICE pointers on the context's GPU, owned by the
