@@ -138,8 +138,8 @@ def run_stack(args) -> int:
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="c2_4096x4096_1x16")
     ap.add_argument("--search-mode", type=int, default=0,
                     help="0 = matrix-core filter + exact re-rank, 1 = exact scan only")
