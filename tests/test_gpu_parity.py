@@ -584,6 +584,35 @@ def test_reencode_beam_repeated_sweeps(M, B, g, beam):
     assert sweep >= 1        # the second sweep still finds better tuples for some groups
 
 
+@pytest.mark.parametrize("seed", range(8))
+def test_reencode_2x8_filter_agrees_with_the_exact_kernel_on_large_lists(seed):
+    """Tens of thousands of groups per case, varied gradient sizes, scale spreads, codebook
+    spreads and beam widths: the filtered path (mode 0) and the exact kernel (mode 1) must
+    write identical codes; a sample is checked against the oracle as well."""
+    rng = np.random.default_rng(1000 + seed)
+    g = 8 if seed % 2 == 0 else 16
+    beam = int(rng.integers(1, 9))
+    wl = workloads.make(512, 128 * g, g, 2, 8, seed=70 + seed, sigma_g=float(10.0 ** rng.uniform(-4, -2)),
+                        sigma_c=float(10.0 ** rng.uniform(-2.5, -1.0)), tau=0.6, beam_width=beam)
+    wl.scales *= np.float32(10.0 ** rng.uniform(-1, 1))
+    if seed % 3 == 0:
+        wl.scales[rng.integers(0, 512, size=40)] *= np.float32(-1.0)
+    T_np = oracle.encode_targets(wl.W, wl.G, wl.alpha)
+    idx = oracle.select_topk_groups(T_np, wl.W, g, wl.k)
+    run = GpuRun(wl)
+    T = dev_f32(T_np)
+    run.ctx.pv_set_search_mode(1)
+    exact, n_exact = run.reencode(T, idx)
+    run.ctx.pv_set_search_mode(0)
+    fast, n_fast = run.reencode(T, idx)
+    st = run.ctx.pv_reencode_stats()
+    assert np.array_equal(fast, exact) and n_fast == n_exact
+    assert st["filtered"] + st["fallback"] == wl.k and st["filtered"] > 0.9 * wl.k
+    sub = np.sort(rng.choice(idx, size=512, replace=False))
+    want, info = oracle.reencode_groups(T_np, wl.codebooks, wl.scales, sub, wl.codes, beam_width=beam)
+    assert np.array_equal(fast.reshape(-1, 2)[sub], want.reshape(-1, 2)[sub]) or info["near_tie"].any()
+
+
 def test_reencode_2x8_non_finite_inputs_end_normally():
     wl = workloads.make(8, 128, 8, 2, 8, seed=44, sigma_g=2e-3, tau=1.0, beam_width=8)
     T_np = oracle.encode_targets(wl.W, wl.G, wl.alpha)
