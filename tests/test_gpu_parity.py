@@ -322,6 +322,35 @@ def test_reencode_m1_codebook_sizes_with_long_lists(B):
     reencode_case(wl, 0)
 
 
+@pytest.mark.parametrize("seed", range(8))
+def test_reencode_m1_filter_agrees_with_the_exact_scan_on_large_lists(seed):
+    """Tens of thousands of groups per case, varied gradient sizes, scale and codebook spreads:
+    the matrix-core filter with its certificate (mode 0) and the exact scan (mode 1) must
+    write identical codes; a sample is checked against the oracle as well."""
+    rng = np.random.default_rng(2000 + seed)
+    g = 8 if seed % 2 == 0 else 16
+    B = int(rng.integers(9, 14))
+    wl = workloads.make(256, 128 * g, g, 1, B, seed=90 + seed, sigma_g=float(10.0 ** rng.uniform(-4, -2)),
+                        sigma_c=float(10.0 ** rng.uniform(-2.5, -1.0)), tau=0.7)
+    wl.scales *= np.float32(10.0 ** rng.uniform(-1, 1))
+    if seed % 3 == 0:
+        wl.scales[rng.integers(0, 256, size=20)] *= np.float32(-1.0)
+    T_np = oracle.encode_targets(wl.W, wl.G, wl.alpha)
+    idx = oracle.select_topk_groups(T_np, wl.W, g, wl.k)
+    run = GpuRun(wl)
+    T = dev_f32(T_np)
+    run.ctx.pv_set_search_mode(1)
+    exact, n_exact = run.reencode(T, idx)
+    run.ctx.pv_set_search_mode(0)
+    fast, n_fast = run.reencode(T, idx)
+    st = run.ctx.pv_reencode_stats()
+    assert np.array_equal(fast, exact) and n_fast == n_exact
+    assert st["filtered"] + st["fallback"] == wl.k
+    sub = np.sort(rng.choice(idx, size=512, replace=False))
+    want, info = oracle.reencode_groups(T_np, wl.codebooks, wl.scales, sub, wl.codes)
+    assert np.array_equal(fast.reshape(-1)[sub], want.reshape(-1)[sub]) or info["near_tie"].any()
+
+
 @pytest.mark.parametrize("mode", [1, 0])
 def test_reencode_m1_scale_edge_cases(mode):
     wl = workloads.make(32, 512, 8, 1, 10, seed=8, sigma_g=2e-3, tau=1.0)
