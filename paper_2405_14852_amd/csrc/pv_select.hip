@@ -40,6 +40,7 @@ constexpr int kFirstBins = 2048;                // digit 0: sign, exponent, 2 ma
 constexpr int kLastBins = 1 << (21 - kMidBits); // digit 2: the remaining low mantissa bits
 constexpr int kItems = 8;                      // groups per thread in the compaction kernels
 constexpr int kChunk = kBlock * kItems;        // groups per chunk there
+static_assert(kChunk < 65536, "the compaction packs two per-chunk counts into 32 bits");
 #ifndef PV_SEL_BLOCKS
 #define PV_SEL_BLOCKS 1024
 #endif
@@ -425,14 +426,25 @@ __global__ __launch_bounds__(kBlock) void k_hist_next(const float *__restrict__ 
     const int64_t n4 = N >> 2;
     const int64_t stride = (int64_t)gridDim.x * kBlock;
     // whole blocks stay in the loop together (the histogram update uses wave-wide votes)
-    for (int64_t base = (int64_t)blockIdx.x * kBlock; base < n4; base += stride) {
-        const int64_t i = base + threadIdx.x;
-        pv_f4 v = i < n4 ? s4[i] : pv_f4{0.f, 0.f, 0.f, 0.f};
+    // four vectors per thread in flight: with many groups (single-weight units) the loop is
+    // otherwise one memory round trip per vector
+    constexpr int kAhead = 4;
+    for (int64_t base = (int64_t)blockIdx.x * kBlock; base < n4; base += stride * kAhead) {
+        pv_f4 v[kAhead];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            unsigned key = __float_as_uint(v[e]);
-            bool valid = i < n4 && digit_of(key, 0) == d0 && (pass == 1 || digit_of(key, 1) == d1);
-            if (__ballot(valid)) hist_add<PV_LATE_VOTE_ROUNDS>(lh, digit_of(key, pass), valid);
+        for (int u = 0; u < kAhead; ++u) {
+            const int64_t i = base + u * stride + threadIdx.x;
+            v[u] = i < n4 ? s4[i] : pv_f4{0.f, 0.f, 0.f, 0.f};
+        }
+#pragma unroll
+        for (int u = 0; u < kAhead; ++u) {
+            const int64_t i = base + u * stride + threadIdx.x;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                unsigned key = __float_as_uint(v[u][e]);
+                bool valid = i < n4 && digit_of(key, 0) == d0 && (pass == 1 || digit_of(key, 1) == d1);
+                if (__ballot(valid)) hist_add<PV_LATE_VOTE_ROUNDS>(lh, digit_of(key, pass), valid);
+            }
         }
     }
     if (blockIdx.x == 0 && (int)threadIdx.x < (N & 3)) {
@@ -517,30 +529,47 @@ __global__ __launch_bounds__(kBlock) void k_compact_write(const float *__restric
 {
     __shared__ unsigned tmp[kBlock + 2];
     const unsigned thr = state[0], need_eq = state[1];
+    // counts of all earlier chunks: [0, done) is already in (pg, pe), a block that takes several
+    // chunks only adds the ones in between
+    unsigned pg = 0, pe = 0;
+    int done = 0;
+    const uint2 *cc2 = reinterpret_cast<const uint2 *>(chunk_counts);
     for (int c = blockIdx.x; c < nchunks; c += gridDim.x) {
-        // counts of all earlier chunks
-        unsigned pg = 0, pe = 0;
-        for (int b = threadIdx.x; b < c; b += kBlock) {
-            pg += chunk_counts[2 * b];
-            pe += chunk_counts[2 * b + 1];
+        unsigned ag = 0, ae = 0;
+        for (int b = done + threadIdx.x; b < c; b += kBlock) {
+            const uint2 v = cc2[b];
+            ag += v.x;
+            ae += v.y;
         }
-        pg = block_sum(pg, tmp);
-        pe = block_sum(pe, tmp);
+        pg += block_sum(ag, tmp);
+        pe += block_sum(ae, tmp);
+        done = c;
         const int64_t base = (int64_t)c * kChunk + (int64_t)threadIdx.x * kItems;
         unsigned keys[kItems];
         unsigned gt = 0, eq = 0;
+        if (base + kItems <= N) {
+            const pv_f4 *s4 = reinterpret_cast<const pv_f4 *>(scores + base);
 #pragma unroll
-        for (int j = 0; j < kItems; ++j) {
-            int64_t n = base + j;
-            keys[j] = n < N ? __float_as_uint(scores[n]) : 0u;
-            if (n < N) {
+            for (int v = 0; v < kItems / 4; ++v) {
+                const pv_f4 x = s4[v];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) keys[v * 4 + e] = __float_as_uint(x[e]);
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < kItems; ++j) keys[j] = base + j < N ? __float_as_uint(scores[base + j]) : 0u;
+        }
+#pragma unroll
+        for (int j = 0; j < kItems; ++j)
+            if (base + j < N) {
                 gt += keys[j] > thr;
                 eq += keys[j] == thr;
             }
-        }
+        // one scan for both counts: a chunk holds kChunk = 2048 keys, so each fits 16 bits
         unsigned tot;
-        unsigned rg = pg + block_excl_scan(gt, tmp, &tot);  // greater keys before this thread's items
-        unsigned re = pe + block_excl_scan(eq, tmp, &tot);  // equal keys before them
+        const unsigned both = block_excl_scan(gt | (eq << 16), tmp, &tot);
+        unsigned rg = pg + (both & 0xFFFFu);   // greater keys before this thread's items
+        unsigned re = pe + (both >> 16);       // equal keys before them
 #pragma unroll
         for (int j = 0; j < kItems; ++j) {
             int64_t n = base + j;
