@@ -123,7 +123,7 @@ extern "C" void pv_destroy(pv_ctx *c)
     (void)hipStreamSynchronize(c->stream);
     pv_buffer *bufs[] = {&c->sel_scores, &c->sel_hist, &c->sel_blocks, &c->sel_state, &c->stats,
                          &c->cb_f16,     &c->cb_meta,  &c->x_f16,      &c->x_meta,    &c->partials,
-                         &c->fb_list,   &c->fb_partial, &c->fb_arrivals, &c->rr_counts, &c->trust, &c->pstep};
+                         &c->fb_list, &c->rr_counts, &c->trust, &c->pstep};
     for (pv_buffer *b : bufs)
         if (b->ptr) (void)hipFree(b->ptr);
     for (auto &t : c->timers)

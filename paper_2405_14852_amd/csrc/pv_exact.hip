@@ -25,12 +25,6 @@ struct best_t {
     int idx;
 };
 
-struct part_t {
-    double obj;
-    int idx;
-    int pad;
-};
-
 __device__ __forceinline__ unsigned umin3(unsigned a, unsigned b, unsigned c)
 {
     return min(min(a, b), c);
@@ -78,13 +72,11 @@ __device__ __forceinline__ best_t block_min(best_t b, double *s_obj, int *s_idx)
 
 // ------------------------------------------------------------------ M = 1 scan
 //
-// Work item = (GPB consecutive list entries, one piece of the codeword range).
-// Thread t scores codewords t, t + 256, ... of the piece against the GPB
-// targets (a codeword is read once for GPB groups).  Ascending scan + strict
-// '<' keeps the lowest index among equal objectives.  The block that finishes
-// the last piece of an item combines the pieces (ascending ranges, so the
-// lexicographic (obj, idx) minimum is the lowest index), lets the previous
-// code win an exact tie with the minimum, and writes the code.
+// Work item = GPB consecutive list entries.  Thread t scores codewords t, t + 256, ...
+// against the GPB targets (a codeword is read once for GPB groups).  Ascending scan +
+// strict '<' keeps the lowest index among equal objectives; the block-wide lexicographic
+// (obj, idx) minimum is then the lowest index, the previous code wins an exact tie with
+// the minimum, and the code is written.
 // G > 0: group size known at compile time (vector loads, targets in
 // registers); G == 0: any group size up to kMaxG.
 constexpr int GPB = 4;
@@ -95,9 +87,7 @@ __global__ __launch_bounds__(kBlock) void k_exact_scan(
     const float *__restrict__ scales, const int32_t *__restrict__ list,
     const uint32_t *__restrict__ d_count, int64_t max_count, uint16_t *__restrict__ codes,
     unsigned long long *__restrict__ num_changed, unsigned long long *__restrict__ stat_counter,
-    int g_rt, int nbits, int gpr, int N, int nsplit_max, part_t *partial, unsigned *arrivals,
-    unsigned *__restrict__ reset_meta, const unsigned *__restrict__ rr_counts, int rr_blocks,
-    unsigned long long *__restrict__ rr_stats)
+    int g_rt, int nbits, int gpr, int N)
 {
     constexpr int GS = G > 0 ? G : kMaxG;
     const int g = G > 0 ? G : g_rt;
@@ -106,28 +96,14 @@ __global__ __launch_bounds__(kBlock) void k_exact_scan(
     __shared__ int s_group[GPB];
     __shared__ double s_obj[kBlock / 64];
     __shared__ int s_idx[kBlock / 64];
-    __shared__ unsigned s_last;
-    __shared__ double s_fin_obj[GPB];
-    __shared__ int s_fin_idx[GPB];
     __shared__ int s_prev[GPB];          // previous code of each group and its codeword,
     __shared__ float s_cprev[GPB][GS];   // fetched up front: the final tie rule needs them
     const int64_t count = d_count ? (int64_t)*d_count : max_count;
     const int csize = 1 << nbits;
     const int64_t items = (count + GPB - 1) / GPB;
-    // pieces per codeword range: as many as it takes to give the chip about a thousand work
-    // units, at most nsplit_max (the list length is only known here, on the device)
-    int nsplit = nsplit_max;
-    if (nsplit > 1 && items > 0) {
-        int64_t want = (1024 + items - 1) / items;
-        if (want < 1) want = 1;
-        if (want < nsplit) nsplit = (int)want;
-    }
-    for (int64_t w = blockIdx.x; w < items * nsplit; w += gridDim.x) {
-        const int64_t item = w / nsplit;
+    for (int64_t item = blockIdx.x; item < items; item += gridDim.x) {
         const int64_t base = item * GPB;
-        const int piece = (int)(w % nsplit);
-        const int c_begin = (int)((int64_t)piece * csize / nsplit);
-        const int c_end = (int)((int64_t)(piece + 1) * csize / nsplit);
+        const int c_begin = 0, c_end = csize;
         __syncthreads();
         if (threadIdx.x < GPB) {
             int64_t j = base + threadIdx.x;
@@ -227,60 +203,6 @@ __global__ __launch_bounds__(kBlock) void k_exact_scan(
         best_t mine[GPB];
 #pragma unroll
         for (int q = 0; q < GPB; ++q) mine[q] = block_min(best[q], s_obj, s_idx);  // valid in thread 0
-        if (nsplit_max > 1) {
-            if (threadIdx.x == 0) {
-#pragma unroll
-                for (int q = 0; q < GPB; ++q) {
-                    part_t pt;
-                    pt.obj = mine[q].obj;
-                    pt.idx = mine[q].idx;
-                    pt.pad = 0;
-                    partial[(base + q) * nsplit_max + piece] = pt;
-                }
-                __threadfence();
-                s_last = atomicAdd(&arrivals[item], 1u) == (unsigned)(nsplit - 1) ? 1u : 0u;
-            }
-            __syncthreads();
-            if (!s_last) continue;                // uniform over the block
-            // all pieces of this item are in memory: combine them, 32 lanes per group
-            __threadfence();
-            {
-                const int q = threadIdx.x >> 5, p = threadIdx.x & 31;
-                best_t b;
-                b.obj = kInf;
-                b.idx = 0x7fffffff;
-                if (q < GPB && p < nsplit) {
-                    const part_t *pp = &partial[(base + q) * nsplit_max + p];
-                    unsigned long long ob = __hip_atomic_load(
-                        reinterpret_cast<const unsigned long long *>(&pp->obj), __ATOMIC_RELAXED,
-                        __HIP_MEMORY_SCOPE_AGENT);
-                    b.idx = __hip_atomic_load(&pp->idx, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    b.obj = __longlong_as_double((long long)ob);
-                }
-#pragma unroll
-                for (int off = 16; off > 0; off >>= 1) {
-                    double o = __shfl_xor(b.obj, off, 32);
-                    int i = __shfl_xor(b.idx, off, 32);
-                    if (better(o, i, b.obj, b.idx)) {
-                        b.obj = o;
-                        b.idx = i;
-                    }
-                }
-                if (q < GPB && p == 0) {
-                    s_fin_obj[q] = b.obj;
-                    s_fin_idx[q] = b.idx;
-                }
-            }
-            __syncthreads();
-            if (threadIdx.x == 0) {
-                arrivals[item] = 0;               // ready for the next call
-#pragma unroll
-                for (int q = 0; q < GPB; ++q) {
-                    mine[q].obj = s_fin_obj[q];
-                    mine[q].idx = s_fin_idx[q];
-                }
-            }
-        }
         if (threadIdx.x == 0) {
 #pragma unroll
             for (int q = 0; q < GPB; ++q) {
@@ -301,38 +223,6 @@ __global__ __launch_bounds__(kBlock) void k_exact_scan(
                 }
                 if (stat_counter) atomicAdd(stat_counter, 1ull);
             }
-        }
-    }
-    // the filter's codebook statistics are dead once this (last) kernel of a call runs
-    if (reset_meta && blockIdx.x == 0 && threadIdx.x < 8) reset_meta[threadIdx.x] = 0u;
-    // fold the re-rank kernel's per-block counters (decided, changed, candidates) into the totals
-    if (rr_counts && blockIdx.x == gridDim.x - 1) {
-        unsigned long long c0 = 0, c1 = 0, c2 = 0;
-        constexpr int kU = 4;            // independent loads in flight per thread
-        for (int b0 = threadIdx.x; b0 < rr_blocks; b0 += kBlock * kU) {
-            unsigned v[kU][3];
-#pragma unroll
-            for (int u = 0; u < kU; ++u) {
-                const int b = b0 + u * kBlock;
-#pragma unroll
-                for (int e = 0; e < 3; ++e) v[u][e] = b < rr_blocks ? rr_counts[3 * b + e] : 0u;
-            }
-#pragma unroll
-            for (int u = 0; u < kU; ++u) {
-                c0 += v[u][0];
-                c1 += v[u][1];
-                c2 += v[u][2];
-            }
-        }
-        for (int off = 32; off > 0; off >>= 1) {
-            c0 += __shfl_down(c0, off);
-            c1 += __shfl_down(c1, off);
-            c2 += __shfl_down(c2, off);
-        }
-        if ((threadIdx.x & 63) == 0) {
-            if (c0) atomicAdd(&rr_stats[0], c0);
-            if (c2) atomicAdd(&rr_stats[2], c2);
-            if (c1 && num_changed) atomicAdd(num_changed, c1);
         }
     }
 }
@@ -1037,26 +927,6 @@ __global__ __launch_bounds__(kBeamBlock, 4) void k_beam_2x8_mfma(
 
 }  // namespace
 
-static void launch_scan(pv_ctx *ctx, int g, unsigned blocks, const float *T, const float *codebooks,
-                        const float *scales, const int32_t *list, const uint32_t *d_count,
-                        int64_t max_count, uint16_t *codes, int64_t *num_changed,
-                        int64_t *d_stat_counter, int nbits, int gpr, int N, int nsplit,
-                        part_t *partial, unsigned *arrivals, unsigned *reset_meta,
-                        const unsigned *rr_counts = nullptr, int rr_blocks = 0,
-                        unsigned long long *rr_stats = nullptr)
-{
-    auto nc = reinterpret_cast<unsigned long long *>(num_changed);
-    auto sc = reinterpret_cast<unsigned long long *>(d_stat_counter);
-#define PV_SCAN(G_)                                                                              \
-    hipLaunchKernelGGL(k_exact_scan<G_>, dim3(blocks), dim3(kBlock), 0, ctx->stream, T, codebooks, \
-                       scales, list, d_count, max_count, codes, nc, sc, g, nbits, gpr, N, nsplit,  \
-                       partial, arrivals, reset_meta, rr_counts, rr_blocks, rr_stats)
-    if (g == 8) PV_SCAN(8);
-    else if (g == 16) PV_SCAN(16);
-    else PV_SCAN(0);
-#undef PV_SCAN
-}
-
 pv_status pv_launch_exact_scan(pv_ctx *ctx, const pv_layout *l, const float *T,
                                const float *codebooks, const float *scales, const int32_t *list,
                                const uint32_t *d_count, int64_t max_count, uint16_t *codes,
@@ -1069,39 +939,16 @@ pv_status pv_launch_exact_scan(pv_ctx *ctx, const pv_layout *l, const float *T,
     int64_t blocks = (max_count + GPB - 1) / GPB;
     if (blocks > 4096) blocks = 4096;
     if (blocks < 1) blocks = 1;
-    launch_scan(ctx, g, (unsigned)blocks, T, codebooks, scales, list, d_count, max_count, codes,
-                num_changed, d_stat_counter, l->nbits, gpr, N, 1, nullptr, nullptr, nullptr);
-    PV_HIP(ctx, hipGetLastError());
-    return PV_OK;
-}
-
-pv_status pv_launch_exact_scan_split(pv_ctx *ctx, const pv_layout *l, const float *T,
-                                     const float *codebooks, const float *scales,
-                                     const int32_t *list, const uint32_t *d_count,
-                                     int64_t max_count, uint16_t *codes, int64_t *num_changed,
-                                     int64_t *d_stat_counter, unsigned *reset_meta,
-                                     const unsigned *rr_counts, int rr_blocks, int64_t *rr_stats)
-{
-    const int g = l->group_size;
-    const int gpr = (int)(l->in_features / g);
-    const int N = (int)pv_num_groups(l);
-    const int csize = 1 << l->nbits;
-    int nsplit = csize / 1024;          // at least 4 passes of 256 codewords per piece
-    if (nsplit > 32) nsplit = 32;
-    if (nsplit < 1) nsplit = 1;
-    const int64_t items = (max_count + GPB - 1) / GPB;
-    pv_status st = pv_ensure(ctx, ctx->fb_partial, (size_t)(items * GPB) * nsplit * sizeof(part_t));
-    if (st != PV_OK) return st;
-    st = pv_ensure(ctx, ctx->fb_arrivals, (size_t)items * sizeof(unsigned), /*zero_new=*/true);
-    if (st != PV_OK) return st;
-    pv_timed t(ctx, PV_K_EXACT_SCAN);
-    int64_t blocks = items * nsplit;
-    if (blocks > 2048) blocks = 2048;
-    launch_scan(ctx, g, (unsigned)blocks, T, codebooks, scales, list, d_count, max_count, codes,
-                num_changed, d_stat_counter, l->nbits, gpr, N, nsplit,
-                static_cast<part_t *>(ctx->fb_partial.ptr),
-                static_cast<unsigned *>(ctx->fb_arrivals.ptr), reset_meta, rr_counts, rr_blocks,
-                reinterpret_cast<unsigned long long *>(rr_stats));
+    auto nc = reinterpret_cast<unsigned long long *>(num_changed);
+    auto sc = reinterpret_cast<unsigned long long *>(d_stat_counter);
+#define PV_SCAN(G_)                                                                               \
+    hipLaunchKernelGGL(k_exact_scan<G_>, dim3((unsigned)blocks), dim3(kBlock), 0, ctx->stream, T,   \
+                       codebooks, scales, list, d_count, max_count, codes, nc, sc, g, l->nbits, gpr, \
+                       N)
+    if (g == 8) PV_SCAN(8);
+    else if (g == 16) PV_SCAN(16);
+    else PV_SCAN(0);
+#undef PV_SCAN
     PV_HIP(ctx, hipGetLastError());
     return PV_OK;
 }

@@ -46,9 +46,7 @@ struct pv_ctx {
     pv_buffer x_meta;       // f32 [k_pad][4]     per-group bounds and flags
     pv_buffer partials;     // u32 [k_pad][P][2]  best / runner-up keys per partition
     pv_buffer fb_list;      // i32 [k] + counter  groups handed to the exact scan
-    pv_buffer fb_partial;   // (f64, i32) [k][pieces]  per-piece minima of the split exact scan
     pv_buffer rr_counts;    // u32 [blocks][3]    per-block counters of the re-rank kernel
-    pv_buffer fb_arrivals;  // u32 [k/4]          pieces finished per work item (kept zero between calls)
     pv_buffer trust;        // scratch of the trust-ratio call (saved codes, keys, prefix sums, sort space)
     pv_buffer pstep;        // scratch of the P-step gradients (keys, sorted order, segment starts, sort space)
 };
@@ -126,14 +124,6 @@ pv_status pv_launch_exact_scan(pv_ctx *ctx, const pv_layout *l, const float *T,
                                const float *codebooks, const float *scales,
                                const int32_t *list, const uint32_t *d_count, int64_t max_count,
                                uint16_t *codes, int64_t *num_changed, int64_t *d_stat_counter);
-// the same scan with each group's codeword range cut into pieces over several blocks
-// (short lists: latency matters more than codebook re-reads)
-pv_status pv_launch_exact_scan_split(pv_ctx *ctx, const pv_layout *l, const float *T,
-                                     const float *codebooks, const float *scales,
-                                     const int32_t *list, const uint32_t *d_count,
-                                     int64_t max_count, uint16_t *codes, int64_t *num_changed,
-                                     int64_t *d_stat_counter, unsigned *reset_meta,
-                                     const unsigned *rr_counts, int rr_blocks, int64_t *rr_stats);
 pv_status pv_launch_beam(pv_ctx *ctx, const pv_layout *l, const float *T, const float *codebooks,
                          const float *scales, const int32_t *group_idx, int64_t k,
                          int32_t beam_width, uint16_t *codes, int64_t *num_changed);
