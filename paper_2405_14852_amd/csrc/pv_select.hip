@@ -387,6 +387,88 @@ __global__ __launch_bounds__(kBlock) void k_targets_scores_hist0_vec(const float
     if (want_hist) flush_hist(lh, hist0 + (blockIdx.x % kSub) * kBins, kFirstBins);
 }
 
+// The same sweep for group sizes 1 and 2: a 16-byte vector holds 4 / GS whole groups and every
+// lane scores its own (no exchange between lanes).  The last nelem % 4 elements, which fill
+// no vector, are left to thread 0 of block 0.
+template <int GS>
+__global__ __launch_bounds__(kBlock) void k_targets_scores_hist0_sub(const float *W, const float *G,
+                                                                     float alpha, float *T,
+                                                                     float *__restrict__ scores,
+                                                                     unsigned *__restrict__ hist0,
+                                                                     int64_t nelem, int want_hist)
+{
+    constexpr int kPerVec = 4 / GS;               // groups per vector
+    __shared__ unsigned lh[kFirstBins];
+    if (want_hist)
+        for (int b = threadIdx.x; b < kFirstBins; b += kBlock) lh[b] = 0;
+    __syncthreads();
+    const pv_f4 *W4 = reinterpret_cast<const pv_f4 *>(W);
+    const pv_f4 *G4 = reinterpret_cast<const pv_f4 *>(G);
+    pv_f4 *T4 = reinterpret_cast<pv_f4 *>(T);
+    const int64_t nvec = nelem >> 2;
+    // whole blocks stay in the loop together (the histogram update uses wave-wide votes)
+    for (int64_t cbase = (int64_t)blockIdx.x * (kBlock * kVecUnroll); cbase < nvec;
+         cbase += (int64_t)gridDim.x * (kBlock * kVecUnroll)) {
+        pv_f4 w[kVecUnroll], gr[kVecUnroll];
+#pragma unroll
+        for (int u = 0; u < kVecUnroll; ++u) {
+            const int64_t i = cbase + threadIdx.x + (int64_t)u * kBlock;
+            if (i < nvec) {
+                w[u] = __builtin_nontemporal_load(&W4[i]);
+                gr[u] = __builtin_nontemporal_load(&G4[i]);
+            } else {
+                w[u] = pv_f4{0.f, 0.f, 0.f, 0.f};
+                gr[u] = w[u];
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kVecUnroll; ++u) {
+            const int64_t i = cbase + threadIdx.x + (int64_t)u * kBlock;
+            const bool valid = i < nvec;
+            pv_f4 t;
+            float sc[kPerVec];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) t[e] = fmaf(-alpha, gr[u][e], w[u][e]);
+#pragma unroll
+            for (int q = 0; q < kPerVec; ++q) {
+                float s = 0.0f;
+#pragma unroll
+                for (int e = 0; e < GS; ++e) {
+                    const float d = t[q * GS + e] - w[u][q * GS + e];
+                    s = fmaf(d, d, s);
+                }
+                sc[q] = s;
+            }
+            if (valid) {
+                __builtin_nontemporal_store(t, &T4[i]);
+#pragma unroll
+                for (int q = 0; q < kPerVec; ++q) scores[i * kPerVec + q] = sc[q];
+            }
+            if (want_hist) {
+#pragma unroll
+                for (int q = 0; q < kPerVec; ++q)
+                    hist_add<PV_VOTE_ROUNDS>(lh, digit_of(__float_as_uint(sc[q]), 0), valid);
+            }
+        }
+    }
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        // the elements after the last whole vector: whole groups, since nelem is a multiple of GS
+        for (int64_t i = nvec << 2; i < nelem; i += GS) {
+            float s = 0.0f;
+            for (int e = 0; e < GS; ++e) {
+                const float tv = fmaf(-alpha, G[i + e], W[i + e]);
+                T[i + e] = tv;
+                const float d = tv - W[i + e];
+                s = fmaf(d, d, s);
+            }
+            scores[i / GS] = s;
+            if (want_hist) atomicAdd(&lh[digit_of(__float_as_uint(s), 0)], 1u);
+        }
+    }
+    __syncthreads();
+    if (want_hist) flush_hist(lh, hist0 + (blockIdx.x % kSub) * kBins, kFirstBins);
+}
+
 // Passes 1 and 2: histogram of the next digit among keys that match the digits
 // chosen so far.  Each launch resolves the digit of the previous histogram and
 // block 0 publishes it in `state` for the launches that follow:
@@ -617,6 +699,19 @@ pv_status pv_launch_select(pv_ctx *ctx, const pv_layout *l, const float *T, cons
     unsigned *state = static_cast<unsigned *>(ctx->sel_state.ptr);
     const int want_hist = k > 0 ? 1 : 0;
     const bool vec_g = g == 4 || g == 8 || g == 16 || g == 32 || g == 64;
+    if (G && !adam && (g == 1 || g == 2)) {
+        pv_timed t(ctx, PV_K_ENCODE_TARGETS);
+        const int64_t nelem = (int64_t)N * g;
+        int64_t vb = ((nelem >> 2) + kBlock * kVecUnroll - 1) / (kBlock * kVecUnroll);
+        const unsigned vblocks = (unsigned)(vb < 1 ? 1 : (vb < kMaxBlocks ? vb : kMaxBlocks));
+        float *Tw = const_cast<float *>(T);
+        if (g == 1)
+            hipLaunchKernelGGL(k_targets_scores_hist0_sub<1>, dim3(vblocks), dim3(kBlock), 0, ctx->stream,
+                               W, G, alpha, Tw, scores, hist, nelem, want_hist);
+        else
+            hipLaunchKernelGGL(k_targets_scores_hist0_sub<2>, dim3(vblocks), dim3(kBlock), 0, ctx->stream,
+                               W, G, alpha, Tw, scores, hist, nelem, want_hist);
+    } else {
     if (G && !vec_g) {   // no fused kernel for this group size: form T first
         // (the Adam variant reaches this launcher only for the group sizes that have one)
         st = pv_launch_encode_targets(ctx, W, G, alpha, const_cast<float *>(T),
@@ -667,6 +762,7 @@ pv_status pv_launch_select(pv_ctx *ctx, const pv_layout *l, const float *T, cons
                                scores, hist, N, g, want_hist);
 #undef PV_SCORES
     }
+    }   // group sizes other than 1 and 2
     if (k > 0) {
         pv_timed t(ctx, PV_K_SELECT);
         int64_t hb = ((int64_t)(N >> 2) + kBlock - 1) / kBlock;

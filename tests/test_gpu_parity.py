@@ -222,7 +222,8 @@ def test_select_all_zero_scores():
 
 @pytest.mark.parametrize("shape,g", [((256, 256), 8), ((61, 1000), 8), ((33, 4096), 16),
                                      ((129, 4100), 4), ((5, 12), 1), ((100, 36), 6),
-                                     ((17, 640), 32), ((9, 1280), 64)])
+                                     ((17, 640), 32), ((9, 1280), 64),
+                                     ((301, 4099), 1), ((257, 2050), 2), ((3, 7), 1), ((1, 2), 2)])
 @pytest.mark.parametrize("frac,alpha", [(0.0, 1.0), (0.01, 1.0), (0.3, 0.37), (1.0, 1.0)])
 def test_fused_targets_select_matches_oracle(shape, g, frac, alpha):
     wl = workloads.make(shape[0], shape[1], g, 1, 4, seed=14, sigma_g=1e-3)
