@@ -289,12 +289,8 @@ pv_status pv_reencode_dispatch(pv_ctx *ctx, const pv_layout *l, const float *T,
     const bool filter = M == 1 && k > 0 && ctx->search_mode == 0 && pv_mfma_supported(l);
     if (filter)   // its first kernel clears the counters
         return pv_launch_mfma_search(ctx, l, T, codebooks, scales, group_idx, k, codes, num_changed);
-    st = pv_launch_fill_i64(ctx, stats, 8, 0);
+    st = pv_launch_fill_i64(ctx, stats, 8, 0, num_changed);
     if (st != PV_OK) return st;
-    if (num_changed) {
-        st = pv_launch_fill_i64(ctx, num_changed, 1, 0);
-        if (st != PV_OK) return st;
-    }
     if (k == 0) return PV_OK;
     if (M > 1) return pv_launch_beam(ctx, l, T, codebooks, scales, group_idx, k, beam_width, codes,
                                      num_changed);

@@ -194,10 +194,13 @@ __global__ __launch_bounds__(kBlock) void k_probe_copy(const pv_f4 *__restrict__
     if (i < n) __builtin_nontemporal_store(__builtin_nontemporal_load(&src[i]), &dst[i]);
 }
 
-__global__ void k_fill_i64(int64_t *p, int64_t n, int64_t v)
+// p[0 .. n) = v and, when q is given, *q = v (the counters of a call and the caller's
+// num_changed in one launch)
+__global__ void k_fill_i64(int64_t *p, int64_t n, int64_t v, int64_t *q)
 {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) p[i] = v;
+    if (q && i == 0) *q = v;
 }
 
 }  // namespace
@@ -311,10 +314,10 @@ pv_status pv_launch_probe_copy(pv_ctx *ctx, void *dst, const void *src, int64_t 
     return PV_OK;
 }
 
-pv_status pv_launch_fill_i64(pv_ctx *ctx, int64_t *p, int64_t n, int64_t value)
+pv_status pv_launch_fill_i64(pv_ctx *ctx, int64_t *p, int64_t n, int64_t value, int64_t *also)
 {
     hipLaunchKernelGGL(k_fill_i64, dim3((unsigned)((n + 63) / 64)), dim3(64), 0, ctx->stream, p, n,
-                       value);
+                       value, also);
     PV_HIP(ctx, hipGetLastError());
     return PV_OK;
 }
