@@ -26,7 +26,11 @@
  *     are numbered row by row: n = o * (in_features / group_size) + j;
  *     N = number of groups must be < 2^31.
  *   - Calls enqueue work on the context's HIP stream and return without waiting;
- *     results are ordered by that stream.  One context per host thread.
+ *     results are ordered by that stream.  One context per host thread.  The one
+ *     exception: when a call needs more scratch memory than the context holds (the
+ *     first call of a shape, or a larger k), it waits for the stream, frees the old
+ *     block and allocates a larger one before it enqueues anything; calls of a shape
+ *     the context has seen before never wait, allocate or free.
  *   - Errors are reported by the return code only; on an error nothing has been
  *     enqueued or written.  pv_last_error gives a short text for the last error
  *     of a context.
@@ -133,7 +137,12 @@ pv_status pv_encode_targets_adam_select(pv_ctx *ctx, const pv_layout *layout, co
  * ascending, unique, each in [0, N) (ids outside the range are skipped).
  * scales: f32 [out_features]; a zero scale keeps the previous code.
  * num_changed: optional device int64, receives the number of groups whose code
- * tuple changed. */
+ * tuple changed.
+ * A stored code is read modulo 2^B (its low B bits): bits above B are ignored in the
+ * search and in num_changed, and stay as they are in a group whose code is kept (a group
+ * that changes is written with a clean B-bit code).
+ * Limits (PV_ERR_UNSUPPORTED): group_size <= 64; for M >= 2 also beam_width <= 64 and
+ * beam_width * 2^B <= 4096 (the candidate pool of one beam step lives in LDS). */
 pv_status pv_reencode_groups(pv_ctx *ctx, const pv_layout *layout, const float *T,
                              const float *codebooks /* f32 [M, 2^B, g] */,
                              const float *scales /* f32 [out_features] */,

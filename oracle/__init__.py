@@ -15,7 +15,12 @@ import numpy as np
 
 _HERE = Path(__file__).resolve().parent
 _SRC = _HERE / "pvo.c"
-_LIB = _HERE / "libpvo.so"
+# PVO_SANITIZE=1: a second build with the address and undefined-behaviour sanitizers of gcc, for
+# running the CPU tests once under them:
+#   PVO_SANITIZE=1 LD_PRELOAD=$(gcc -print-file-name=libasan.so) ASAN_OPTIONS=detect_leaks=0 \
+#       python -m pytest tests -m "not gpu"
+_SANITIZE = os.environ.get("PVO_SANITIZE", "0") not in ("", "0")
+_LIB = _HERE / ("libpvo_san.so" if _SANITIZE else "libpvo.so")
 
 _lib = None
 
@@ -26,6 +31,9 @@ def build(force: bool = False) -> Path:
         tmp = _LIB.with_suffix(f".tmp{os.getpid()}.so")
         cmd = ["gcc", "-O2", "-std=c11", "-ffp-contract=off", "-fopenmp", "-fPIC",
                "-shared", "-Wall", "-Wextra", "-o", str(tmp), str(_SRC), "-lm"]
+        if _SANITIZE:
+            cmd[1:2] = ["-O1", "-g", "-fno-omit-frame-pointer", "-fsanitize=address,undefined",
+                        "-fno-sanitize-recover=undefined"]
         subprocess.run(cmd, check=True)
         os.replace(tmp, _LIB)
     return _LIB

@@ -305,8 +305,13 @@ int pvo_reencode_groups(int64_t out_features, int64_t in_features, int g, int M,
     if (beam_width < 1 || k < 0) return PVO_ERR;
     if (k > 0 && !group_idx) return PVO_ERR;
     int64_t gpr = in_features / g, N = out_features * gpr, csize = (int64_t)1 << B;
-    for (int64_t j = 0; j < k; ++j)
+    for (int64_t j = 0; j < k; ++j) {
         if (group_idx[j] < 0 || group_idx[j] >= N) return PVO_ERR;
+        /* a stored code is an index into a codebook of 2^B codewords (Sec. 3.1: the partition
+         * assigns each group one of the c values); anything else is not a code */
+        for (int m = 0; m < M; ++m)
+            if (codes[(int64_t)group_idx[j] * M + m] >= csize) return PVO_ERR;
+    }
     int beam_path = use_beam || M > 1;
     int64_t changed = 0;
     int failed = 0;

@@ -85,3 +85,25 @@ class GpuRun:
         self.ctx.pv_dequantize(self.lay, dev_u16(codes_np), self.cb, self.sc, W)
         torch.cuda.synchronize()
         return W.cpu().numpy()
+
+
+NEAR_TIE_REL = 1e-6   # tolerance for differing codes: best two objectives closer than this (relative)
+
+
+def check_codes_on(wl, T_np, sub, got, want, info):
+    """Per-group acceptance rule on the listed groups `sub` (the list the oracle re-encoded, in
+    its order): codes are identical, except on groups the oracle itself flags as near-ties, where
+    the GPU's tuple, evaluated in the oracle's arithmetic, must lie within NEAR_TIE_REL (relative)
+    of the oracle's objective.  Returns the number of differing (near-tie) groups."""
+    import oracle
+    M = wl.layout.num_codebooks
+    sub = np.asarray(sub)
+    g2, w2 = got.reshape(-1, M), want.reshape(-1, M)
+    diff = np.nonzero((g2[sub] != w2[sub]).any(1))[0]
+    if len(diff) == 0:
+        return 0
+    assert info["near_tie"][diff].all(), f"{len(diff)} differing groups, not all near-ties"
+    obj = oracle.group_objective(T_np, wl.codebooks, wl.scales, sub[diff], g2[sub[diff]])
+    ref = info["obj_new"][diff]
+    assert (np.abs(obj - ref) <= NEAR_TIE_REL * np.maximum(ref, 1e-300)).all()
+    return len(diff)

@@ -12,28 +12,20 @@ import torch
 
 import oracle
 import workloads
-from gpu_util import DEV, GpuRun, dev_f32, dev_u16, host_u16
+from gpu_util import DEV, GpuRun, check_codes_on, dev_f32, dev_u16, host_u16
 
 pytestmark = pytest.mark.gpu
 
-NEAR_TIE_REL = 1e-6   # spec tolerance for differing codes
 RECON_REL = 1e-5      # spec tolerance for reconstructed weights (relative L2)
 
 
 def check_codes(wl, T_np, idx, got, want, info):
     M = wl.layout.num_codebooks
-    g2, w2 = got.reshape(-1, M), want.reshape(-1, M)
+    g2 = got.reshape(-1, M)
     mask = np.ones(len(g2), bool)
     mask[idx] = False
     assert np.array_equal(g2[mask], wl.codes.reshape(-1, M)[mask]), "unselected codes changed"
-    diff = np.nonzero((g2[idx] != w2[idx]).any(1))[0]
-    if len(diff) == 0:
-        return 0
-    assert info["near_tie"][diff].all(), f"{len(diff)} differing groups, not all near-ties"
-    obj = oracle.group_objective(T_np, wl.codebooks, wl.scales, idx[diff], g2[idx[diff]])
-    ref = info["obj_new"][diff]
-    assert (np.abs(obj - ref) <= NEAR_TIE_REL * np.maximum(ref, 1e-300)).all()
-    return len(diff)
+    return check_codes_on(wl, T_np, idx, got, want, info)
 
 
 # ------------------------------------------------------------------ targets
@@ -349,7 +341,7 @@ def test_reencode_m1_filter_agrees_with_the_exact_scan_on_large_lists(seed):
     assert st["filtered"] + st["fallback"] == wl.k
     sub = np.sort(rng.choice(idx, size=512, replace=False))
     want, info = oracle.reencode_groups(T_np, wl.codebooks, wl.scales, sub, wl.codes)
-    assert np.array_equal(fast.reshape(-1)[sub], want.reshape(-1)[sub]) or info["near_tie"].any()
+    check_codes_on(wl, T_np, sub, fast, want, info)
 
 
 @pytest.mark.parametrize("mode", [1, 0])
@@ -439,6 +431,40 @@ def test_reencode_empty_selection_and_errors():
     bad = type(run.lay)(8, 64, 8, 1, 17)
     with pytest.raises(PVError):
         run.ctx.pv_dequantize(bad, run.codes, run.cb, run.sc, T)
+
+
+@pytest.mark.parametrize("mode", [1, 0])
+@pytest.mark.parametrize("g,M,B,beam", [(8, 1, 10, 1), (16, 1, 9, 1), (8, 2, 8, 8), (8, 3, 4, 4), (4, 1, 3, 1)])
+def test_reencode_reads_stored_codes_modulo_the_codebook_size(mode, g, M, B, beam):
+    """Stray bits above B in the stored codes: the library reads the low B bits (the oracle
+    refuses such input, so it is given the clean codes); a group that keeps its code keeps its
+    stray bits, a group that changes is written clean, num_changed counts tuples modulo 2^B."""
+    wl = workloads.make(16, 32 * g, g, M, B, seed=77, sigma_g=2e-3, tau=1.0, beam_width=beam)
+    rng = np.random.default_rng(77)
+    stray = (rng.integers(0, 1 << (16 - B), size=wl.codes.shape) << B).astype(np.uint16)
+    stray[rng.random(wl.codes.shape) < 0.5] = 0
+    dirty = wl.codes | stray
+    T_np = oracle.encode_targets(wl.W, wl.G, wl.alpha)
+    # half of the groups get their own reconstruction as target, so that they keep their code
+    keep = rng.random(wl.layout.num_groups) < 0.5
+    W_own = oracle.dequantize(wl.codes, wl.codebooks, wl.scales).reshape(-1, g)
+    T_np = T_np.reshape(-1, g).copy()
+    T_np[keep] = W_own[keep]
+    T_np = T_np.reshape(wl.W.shape)
+    idx = np.arange(wl.layout.num_groups, dtype=np.int32)
+    run = GpuRun(wl)
+    run.ctx.pv_set_search_mode(mode)
+    got, nch = run.reencode(dev_f32(T_np), idx, codes=dev_u16(dirty))
+    want, info = oracle.reencode_groups(T_np, wl.codebooks, wl.scales, idx, wl.codes, beam_width=beam)
+    mask = np.uint16((1 << B) - 1)
+    ndiff = check_codes_on(wl, T_np, idx, got & mask, want, info)
+    assert abs(nch - info["num_changed"]) <= ndiff
+    g2, w2, d2, c2 = got.reshape(-1, M), want.reshape(-1, M), dirty.reshape(-1, M), wl.codes.reshape(-1, M)
+    same = (w2 == c2).all(1) & ((g2 & mask) == w2).all(1)
+    assert same.sum() > 0 and (~same).sum() > 0
+    assert np.array_equal(g2[same], d2[same])                    # kept groups: untouched, stray bits stay
+    moved = (w2 != c2).any(1) & ((g2 & mask) == w2).all(1)
+    assert np.array_equal(g2[moved], w2[moved])                  # changed groups: written clean
 
 
 # ------------------------------------------------------- ceiling probes
@@ -603,9 +629,10 @@ def test_reencode_beam_repeated_sweeps(M, B, g, beam):
     for sweep in range(4):
         got, nch = run.reencode(T, idx, codes=dev_u16(got))
         want, info = oracle.reencode_groups(T_np, wl.codebooks, wl.scales, idx, want, beam_width=beam)
-        assert np.array_equal(got, want) or info["near_tie"].any()
+        ndiff = check_codes_on(wl, T_np, idx, got, want, info)
+        # a group resolved differently on a near-tie may count as changed on one side only
+        assert abs(nch - info["num_changed"]) <= ndiff
         got = want       # continue from the oracle's codes when a near-tie was resolved differently
-        assert nch == info["num_changed"] or info["near_tie"].any()
         if prev_obj is not None:
             assert (info["obj_prev"] <= prev_obj * (1 + 1e-12)).all()
         prev_obj = info["obj_new"]
@@ -640,7 +667,7 @@ def test_reencode_2x8_filter_agrees_with_the_exact_kernel_on_large_lists(seed):
     assert st["filtered"] + st["fallback"] == wl.k and st["filtered"] > 0.9 * wl.k
     sub = np.sort(rng.choice(idx, size=512, replace=False))
     want, info = oracle.reencode_groups(T_np, wl.codebooks, wl.scales, sub, wl.codes, beam_width=beam)
-    assert np.array_equal(fast.reshape(-1, 2)[sub], want.reshape(-1, 2)[sub]) or info["near_tie"].any()
+    check_codes_on(wl, T_np, sub, fast, want, info)
 
 
 def test_reencode_2x8_non_finite_inputs_end_normally():
@@ -659,7 +686,7 @@ def test_reencode_2x8_non_finite_inputs_end_normally():
     clean[5 * gpr:6 * gpr] = False
     sub = idx[clean]
     want, info = oracle.reencode_groups(T_np, wl.codebooks, wl.scales, sub, wl.codes, beam_width=8)
-    assert np.array_equal(got.reshape(-1, 2)[sub], want.reshape(-1, 2)[sub]) or info["near_tie"].any()
+    check_codes_on(wl, T_np, sub, got, want, info)
 
 
 # ------------------------------------------------------------- whole path

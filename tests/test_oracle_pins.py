@@ -238,6 +238,71 @@ def test_m1_tie_rule_previous_code_then_lowest_index():
     assert info["num_changed"] == 2
 
 
+@pytest.mark.parametrize("ulps,flagged", [(0, True), (2, True), (4, True), (5, False), (8, False),
+                                          (1000, False)])
+def test_m1_near_tie_flag_is_the_stated_relative_tolerance(ulps, flagged):
+    """The flag that excuses a differing code: best two objectives closer than 1e-6 RELATIVE.
+    One weight per group, target 0, scale 1: the objectives are the squared codewords.  With
+    codewords 1 and 1 + ulps * 2^-23 the relative gap of the objectives is about
+    ulps * 2.38e-7: 4 ulps = 9.5e-7 (flagged), 5 ulps = 1.19e-6 (not flagged).  A tolerance off
+    by a factor of two in either direction, or an absolute one, fails a case."""
+    hi = np.float32(1.0) + np.float32(ulps) * np.float32(2.0 ** -23)
+    for scale_pow in (0, -20, 20):      # the rule is relative: the flag must not depend on magnitude
+        unit = np.float32(2.0 ** scale_pow)
+        cb = np.array([[[1.0 * unit], [hi * unit], [3.0 * unit], [-2.5 * unit]]], np.float32)
+        T = np.zeros((1, 1), np.float32)
+        codes0 = np.array([2], np.uint16).reshape(1, 1, 1)
+        new, info = oracle.reencode_groups(T, cb, np.ones(1, np.float32), np.arange(1), codes0)
+        assert new.ravel().tolist() == [0]
+        lo_obj, hi_obj = float(unit) ** 2, (float(hi) * float(unit)) ** 2
+        assert info["obj_new"][0] == lo_obj
+        assert ((hi_obj - lo_obj) < 1e-6 * hi_obj or hi_obj == lo_obj) == flagged   # the case is what it claims
+        assert bool(info["near_tie"][0]) == flagged
+
+
+@pytest.mark.parametrize("ulps,flagged", [(2, True), (4, True), (5, False), (8, False)])
+def test_beam_near_tie_flag_at_the_prune_boundary(ulps, flagged):
+    """Beam 1 over two codebooks of two codewords: at the first codebook the kept candidate
+    (objective 1) and the dropped one (objective (1 + ulps * 2^-23)^2) are the only boundary
+    in the run that is close: the second step's candidates are far apart and the winner is the
+    previous tuple.  The flag must follow that one boundary."""
+    hi = np.float32(1.0) + np.float32(ulps) * np.float32(2.0 ** -23)
+    cb = np.array([[[1.0], [hi]], [[0.0], [5.0]]], np.float32)        # [M=2, 2, g=1]
+    T = np.zeros((1, 1), np.float32)
+    codes0 = np.array([0, 0], np.uint16).reshape(1, 1, 2)
+    new, info = oracle.reencode_groups(T, cb, np.ones(1, np.float32), np.arange(1), codes0,
+                                       beam_width=1)
+    assert new.ravel().tolist() == [0, 0] and info["num_changed"] == 0
+    assert info["obj_new"][0] == 1.0
+    assert bool(info["near_tie"][0]) == flagged
+    # the final best two (1 against 36) and the keep-or-replace decision are not close: with a
+    # beam that drops nothing at the first step the same inputs are flagged only through the
+    # final pair (1, hi^2)
+    new2, info2 = oracle.reencode_groups(T, cb, np.ones(1, np.float32), np.arange(1), codes0,
+                                         beam_width=2)
+    assert new2.ravel().tolist() == [0, 0]
+    assert bool(info2["near_tie"][0]) == flagged
+
+
+@pytest.mark.parametrize("M,B", [(1, 3), (2, 2), (1, 15)])
+def test_reencode_rejects_a_stored_code_outside_the_codebook(M, B):
+    """A stored code >= 2^B is not an index into the codebook; the oracle refuses the call (as
+    its dequantiser does) instead of reading outside the table.  Unlisted groups are not looked at."""
+    rng = np.random.default_rng(5)
+    g = 2
+    cb = rng.standard_normal((M, 1 << B, g)).astype(np.float32)
+    T = rng.standard_normal((2, 4 * g)).astype(np.float32)
+    codes0 = rng.integers(0, 1 << B, size=(2, 4, M)).astype(np.uint16)
+    oracle.reencode_groups(T, cb, np.ones(2, np.float32), np.arange(8), codes0, beam_width=2)
+    bad = codes0.copy()
+    bad[1, 2, M - 1] = 1 << B
+    with pytest.raises(ValueError):
+        oracle.reencode_groups(T, cb, np.ones(2, np.float32), np.arange(8), bad, beam_width=2)
+    listed = np.array([0, 1, 2, 3, 4, 5, 7])      # group 6 = (1, 2) is not listed
+    new, _ = oracle.reencode_groups(T, cb, np.ones(2, np.float32), listed, bad, beam_width=2)
+    assert new[1, 2, M - 1] == 1 << B
+
+
 def test_lemma_3_1_quadratic_model_brute_force():
     """argmin over all code tuples of <grad, x-y> + L/2 ||x-y||^2 equals the
     nearest representable point to y - grad/L (Lemma 3.1)."""
