@@ -12,6 +12,7 @@
  * pv_reencode_trust_ratio (Sec. 4.3: the subspace size from the trust ratio),
  * pv_codebook_grads (Alg. 3 P step: gradients of codebooks and scales),
  * pv_dequantize_groups (dequantisation of the re-encoded groups only),
+ * pv_select_topk_groups_noalloc (the selection for callers that cannot allocate),
  * pv_dequantize_scalar / pv_reencode_scalar (App. K's scalar uniform-grid representation).
  * Instrumentation: pv_set_search_mode, pv_timing_*, pv_reencode_stats, and the two ceiling
  * probes pv_probe_copy / pv_probe_mfma_f16.
@@ -100,6 +101,19 @@ pv_status pv_encode_targets_adam(pv_ctx *ctx, const pv_layout *layout, const flo
 pv_status pv_select_topk_groups(pv_ctx *ctx, const pv_layout *layout, const float *T,
                                 const float *W, int64_t k, int32_t *out_idx,
                                 float *group_scores /* NULL ok */);
+
+/* For callers that cannot allocate device memory (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid allocation): pv_select_topk_groups with the same
+ * arguments and the same results, whose scratch (group scores when group_scores is NULL,
+ * radix-select histograms, per-chunk counts) lives in one static device array of about
+ * 16.1 MiB that every GPU the library runs on holds until the process ends.  It calls no
+ * allocation or release routine of any kind, creates no events (timing brackets are off for
+ * this call) and enqueues only kernels.  Limit: N <= 4 194 304 groups, else
+ * PV_ERR_UNSUPPORTED.  All calls on one GPU share the array: calls that overlap on one GPU
+ * (two streams, two contexts) race; calls ordered by one stream are safe. */
+pv_status pv_select_topk_groups_noalloc(pv_ctx *ctx, const pv_layout *layout, const float *T,
+                                        const float *W, int64_t k, int32_t *out_idx,
+                                        float *group_scores /* NULL ok */);
 
 /* pv_encode_targets followed by pv_select_topk_groups, as one sweep over memory
  * (Eq. 7 feeding Alg. 2 line 5): T is written and every group's score is taken

@@ -74,6 +74,7 @@ def load_library():
     lib.pv_encode_targets.argtypes = [vp, lp, vp, vp, f32, vp]
     lib.pv_encode_targets_adam.argtypes = [vp, lp, vp, vp, vp, vp, i64, f32, f32, f32, f32, vp]
     lib.pv_select_topk_groups.argtypes = [vp, lp, vp, vp, i64, vp, vp]
+    lib.pv_select_topk_groups_noalloc.argtypes = [vp, lp, vp, vp, i64, vp, vp]
     lib.pv_encode_targets_adam_select.argtypes = [vp, lp, vp, vp, vp, vp, i64, f32, f32, f32, f32, vp,
                                                   i64, vp, vp]
     lib.pv_encode_targets_select.argtypes = [vp, lp, vp, vp, f32, vp, i64, vp, vp]
@@ -93,7 +94,7 @@ def load_library():
     lib.pv_reencode_stats.argtypes = [vp, ctypes.POINTER(i64)]
     lib.pv_probe_copy.argtypes = [vp, vp, vp, i64]
     lib.pv_probe_mfma_f16.argtypes = [vp, i64, vp, ctypes.POINTER(i64)]
-    for name in ("pv_create", "pv_encode_targets", "pv_encode_targets_adam", "pv_select_topk_groups",
+    for name in ("pv_create", "pv_select_topk_groups_noalloc", "pv_encode_targets", "pv_encode_targets_adam", "pv_select_topk_groups",
                  "pv_encode_targets_adam_select",
                  "pv_encode_targets_select", "pv_reencode_groups", "pv_reencode_trust_ratio",
                  "pv_codebook_grads", "pv_dequantize_scalar", "pv_reencode_scalar",
@@ -179,6 +180,14 @@ class PVContext:
     def pv_select_topk_groups(self, layout: Layout, T, W, k: int, out_idx, group_scores=None):
         lay = layout.c()
         self._check(self._lib.pv_select_topk_groups(
+            self._h, ctypes.byref(lay), _dev_ptr(T, torch.float32, "T"),
+            _dev_ptr(W, torch.float32, "W"), int(k),
+            _dev_ptr(out_idx, torch.int32, "out_idx", allow_none=(k == 0)),
+            _dev_ptr(group_scores, torch.float32, "group_scores", allow_none=True)))
+
+    def pv_select_topk_groups_noalloc(self, layout: Layout, T, W, k: int, out_idx, group_scores=None):
+        lay = layout.c()
+        self._check(self._lib.pv_select_topk_groups_noalloc(
             self._h, ctypes.byref(lay), _dev_ptr(T, torch.float32, "T"),
             _dev_ptr(W, torch.float32, "W"), int(k),
             _dev_ptr(out_idx, torch.int32, "out_idx", allow_none=(k == 0)),

@@ -112,6 +112,11 @@ extern "C" pv_status pv_create(pv_ctx **out, int device, void *hip_stream)
     if (!c) return PV_ERR_ALLOC;
     c->device = device;
     c->stream = static_cast<hipStream_t>(hip_stream);
+    // address of the static scratch array on this device (for pv_select_topk_groups_noalloc)
+    if (pv_static_scratch_init(c, device) != PV_OK) {
+        delete c;
+        return PV_ERR_DEVICE;
+    }
     *out = c;
     return PV_OK;
 }
@@ -228,6 +233,30 @@ extern "C" pv_status pv_select_topk_groups(pv_ctx *ctx, const pv_layout *l, cons
     if (N == 0 || (k == 0 && !group_scores)) return PV_OK;
     PV_HIP(ctx, hipSetDevice(ctx->device));
     return pv_launch_select(ctx, l, T, W, k, out_idx, group_scores);
+}
+
+extern "C" pv_status pv_select_topk_groups_noalloc(pv_ctx *ctx, const pv_layout *l, const float *T,
+                                                   const float *W, int64_t k, int32_t *out_idx,
+                                                   float *group_scores)
+{
+    if (!ctx) return PV_ERR_INVALID_ARG;
+    pv_status st = check_layout(ctx, l);
+    if (st != PV_OK) return st;
+    int64_t N = pv_num_groups(l);
+    if (N > pv_static_max_groups())
+        return pv_fail(ctx, PV_ERR_UNSUPPORTED,
+                       "%lld groups exceed the %lld the static scratch array is sized for",
+                       (long long)N, (long long)pv_static_max_groups());
+    if (k < 0 || k > N)
+        return pv_fail(ctx, PV_ERR_INVALID_ARG, "k = %lld outside [0, %lld]", (long long)k,
+                       (long long)N);
+    if (!T || !W) return pv_fail(ctx, PV_ERR_INVALID_ARG, "NULL tensor pointer");
+    if (k > 0 && !out_idx) return pv_fail(ctx, PV_ERR_INVALID_ARG, "out_idx is NULL");
+    if (misaligned(T) || misaligned(W) || misaligned(group_scores))
+        return pv_fail(ctx, PV_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
+    if (N == 0 || (k == 0 && !group_scores)) return PV_OK;
+    PV_HIP(ctx, hipSetDevice(ctx->device));
+    return pv_launch_select_static(ctx, l, T, W, k, out_idx, group_scores);
 }
 
 extern "C" pv_status pv_encode_targets_select(pv_ctx *ctx, const pv_layout *l, const float *W,

@@ -120,6 +120,11 @@ pv_status pv_launch_select(pv_ctx *ctx, const pv_layout *l, const float *T, cons
                            int64_t k, int32_t *out_idx, float *scores, const float *G = nullptr,
                            float alpha = 0.0f, const pv_adam_t *adam = nullptr, float *m = nullptr,
                            float *v = nullptr);
+// selection with its scratch in the library's static device array (no allocation of any kind)
+pv_status pv_static_scratch_init(pv_ctx *ctx, int device);   // `device` must be current
+int64_t pv_static_max_groups();
+pv_status pv_launch_select_static(pv_ctx *ctx, const pv_layout *l, const float *T, const float *W,
+                                  int64_t k, int32_t *out_idx, float *scores);
 pv_status pv_launch_exact_scan(pv_ctx *ctx, const pv_layout *l, const float *T,
                                const float *codebooks, const float *scales,
                                const int32_t *list, const uint32_t *d_count, int64_t max_count,

@@ -674,13 +674,29 @@ __global__ __launch_bounds__(kBlock) void k_compact_write(const float *__restric
 
 }  // namespace
 
+// The scratch memory of one selection: every group's score (unless the caller keeps them),
+// the radix-select histograms (all zero when a call starts, left zero when it ends), the
+// per-chunk counts of the compaction, the digits and threshold found so far.
+struct sel_bufs {
+    float *scores;
+    unsigned *hist, *cc, *state;
+};
+
+__global__ void k_sel_clear(unsigned *p, int n)
+{
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < n; i += gridDim.x * blockDim.x) p[i] = 0u;
+}
+
+static pv_status select_run(pv_ctx *ctx, const pv_layout *l, const float *T, const float *W,
+                            int64_t k, int32_t *out_idx, const sel_bufs &bufs, const float *G,
+                            float alpha, const pv_adam_t *adam, float *m, float *v);
+
 // G != nullptr: T is an OUTPUT, formed here as W - alpha * G in the same pass that scores it.
 pv_status pv_launch_select(pv_ctx *ctx, const pv_layout *l, const float *T, const float *W,
                            int64_t k, int32_t *out_idx, float *scores, const float *G, float alpha,
                            const pv_adam_t *adam, float *m, float *v)
 {
     const int N = (int)pv_num_groups(l);
-    const int g = l->group_size;
     pv_status st;
     if (!scores) {
         st = pv_ensure(ctx, ctx->sel_scores, (size_t)N * sizeof(float) + 16);
@@ -694,9 +710,86 @@ pv_status pv_launch_select(pv_ctx *ctx, const pv_layout *l, const float *T, cons
     if (st != PV_OK) return st;
     st = pv_ensure(ctx, ctx->sel_state, 8 * sizeof(unsigned));
     if (st != PV_OK) return st;
-    unsigned *hist = static_cast<unsigned *>(ctx->sel_hist.ptr);
-    unsigned *cc = static_cast<unsigned *>(ctx->sel_blocks.ptr);
-    unsigned *state = static_cast<unsigned *>(ctx->sel_state.ptr);
+    sel_bufs bufs;
+    bufs.scores = scores;
+    bufs.hist = static_cast<unsigned *>(ctx->sel_hist.ptr);
+    bufs.cc = static_cast<unsigned *>(ctx->sel_blocks.ptr);
+    bufs.state = static_cast<unsigned *>(ctx->sel_state.ptr);
+    return select_run(ctx, l, T, W, k, out_idx, bufs, G, alpha, adam, m, v);
+}
+
+// ---------------------------------------------------------------- selection without allocation
+// For callers that cannot allocate device memory (code under HIP graph capture, tight serving
+// loops, harnesses that forbid it): the same selection with its scratch in one static device
+// array.  Each GPU holds its own copy of the array for the life of the process; every call on
+// a GPU shares it, so calls that overlap on one GPU (two streams, two contexts) race.
+constexpr int64_t kStaticMaxGroups = INT64_C(1) << 22;            // 4 194 304 groups
+constexpr size_t kStaticScoresOff = 0;
+constexpr size_t kStaticHistOff = kStaticScoresOff + (size_t)kStaticMaxGroups * sizeof(float) + 256;
+constexpr size_t kStaticCcOff = kStaticHistOff + (size_t)kHistTotal * sizeof(unsigned);
+constexpr size_t kStaticStateOff =
+    kStaticCcOff + (size_t)((kStaticMaxGroups + kChunk - 1) / kChunk) * 2 * sizeof(unsigned);
+constexpr size_t kStaticBytes = kStaticStateOff + 256;            // about 16.1 MiB
+static __device__ __align__(256) unsigned char scratch[kStaticBytes];
+
+// In host code `scratch` is only a stand-in for the symbol: the memory is reached through the
+// address the runtime reports for it on each device.
+constexpr int kMaxDevices = 64;
+static unsigned char *g_static_ptr[kMaxDevices] = {nullptr};
+
+// The device must be current.  Called by pv_create (once per context) and again by the entry
+// point itself; the first call on a device asks the runtime, later ones return the kept address.
+pv_status pv_static_scratch_init(pv_ctx *ctx, int device)
+{
+    if (device < 0 || device >= kMaxDevices)
+        return pv_fail(ctx, PV_ERR_INVALID_ARG, "device %d outside 0..%d", device, kMaxDevices - 1);
+    unsigned char *p = __atomic_load_n(&g_static_ptr[device], __ATOMIC_ACQUIRE);
+    if (p) return PV_OK;
+    void *sym = nullptr;
+    hipError_t e = hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !sym) {
+        (void)hipGetLastError();
+        return pv_fail(ctx, PV_ERR_DEVICE, "hipGetSymbolAddress(scratch): %s", hipGetErrorString(e));
+    }
+    __atomic_store_n(&g_static_ptr[device], static_cast<unsigned char *>(sym), __ATOMIC_RELEASE);
+    return PV_OK;
+}
+
+int64_t pv_static_max_groups() { return kStaticMaxGroups; }
+
+pv_status pv_launch_select_static(pv_ctx *ctx, const pv_layout *l, const float *T, const float *W,
+                                  int64_t k, int32_t *out_idx, float *scores)
+{
+    pv_status st = pv_static_scratch_init(ctx, ctx->device);
+    if (st != PV_OK) return st;
+    unsigned char *base = __atomic_load_n(&g_static_ptr[ctx->device], __ATOMIC_ACQUIRE);
+    sel_bufs bufs;
+    bufs.scores = scores ? scores : reinterpret_cast<float *>(base + kStaticScoresOff);
+    bufs.hist = reinterpret_cast<unsigned *>(base + kStaticHistOff);
+    bufs.cc = reinterpret_cast<unsigned *>(base + kStaticCcOff);
+    bufs.state = reinterpret_cast<unsigned *>(base + kStaticStateOff);
+    // the array keeps what the last call (of any context) left: the histograms must start at
+    // zero whatever that was (a fill kernel, which a capturing caller may record)
+    hipLaunchKernelGGL(k_sel_clear, dim3(16), dim3(kBlock), 0, ctx->stream, bufs.hist, kHistTotal);
+    const bool timing = ctx->timing;   // timing brackets create events: not in this call
+    ctx->timing = false;
+    st = select_run(ctx, l, T, W, k, out_idx, bufs, nullptr, 0.0f, nullptr, nullptr, nullptr);
+    ctx->timing = timing;
+    return st;
+}
+
+static pv_status select_run(pv_ctx *ctx, const pv_layout *l, const float *T, const float *W,
+                            int64_t k, int32_t *out_idx, const sel_bufs &bufs, const float *G,
+                            float alpha, const pv_adam_t *adam, float *m, float *v)
+{
+    const int N = (int)pv_num_groups(l);
+    const int g = l->group_size;
+    const int nchunks = (N + kChunk - 1) / kChunk;
+    pv_status st;
+    float *scores = bufs.scores;
+    unsigned *hist = bufs.hist;
+    unsigned *cc = bufs.cc;
+    unsigned *state = bufs.state;
     const int want_hist = k > 0 ? 1 : 0;
     const bool vec_g = g == 4 || g == 8 || g == 16 || g == 32 || g == 64;
     if (G && !adam && (g == 1 || g == 2)) {
