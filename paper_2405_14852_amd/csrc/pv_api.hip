@@ -315,6 +315,7 @@ pv_status pv_reencode_dispatch(pv_ctx *ctx, const pv_layout *l, const float *T,
     pv_status st = pv_ensure(ctx, ctx->stats, 8 * sizeof(int64_t));
     if (st != PV_OK) return st;
     int64_t *stats = static_cast<int64_t *>(ctx->stats.ptr);
+    ctx->rr_blocks_last = 0;
     const bool filter = M == 1 && k > 0 && ctx->search_mode == 0 && pv_mfma_supported(l);
     if (filter)   // its first kernel clears the counters
         return pv_launch_mfma_search(ctx, l, T, codebooks, scales, group_idx, k, codes, num_changed);
@@ -571,5 +572,17 @@ extern "C" pv_status pv_reencode_stats(pv_ctx *ctx, int64_t stats[4])
     int64_t host[8];
     PV_HIP(ctx, hipMemcpy(host, ctx->stats.ptr, sizeof(host), hipMemcpyDeviceToHost));
     for (int i = 0; i < 4; ++i) stats[i] = host[i];
+    if (ctx->rr_blocks_last > 0 && ctx->rr_counts.ptr) {
+        // the one-codebook filter leaves its counters per block of the re-rank kernel:
+        // {decided by the filter, codes changed, candidates evaluated, finished by a scan}
+        std::vector<uint32_t> per_block((size_t)ctx->rr_blocks_last * 4);
+        PV_HIP(ctx, hipMemcpy(per_block.data(), ctx->rr_counts.ptr, per_block.size() * sizeof(uint32_t),
+                              hipMemcpyDeviceToHost));
+        for (int b = 0; b < ctx->rr_blocks_last; ++b) {
+            stats[0] += per_block[4 * (size_t)b + 0];
+            stats[1] += per_block[4 * (size_t)b + 3];
+            stats[2] += per_block[4 * (size_t)b + 2];
+        }
+    }
     return PV_OK;
 }

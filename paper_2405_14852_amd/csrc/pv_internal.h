@@ -29,7 +29,8 @@ struct pv_ctx {
     hipStream_t stream = nullptr;
     char err[256] = {0};
     int search_mode = 0;
-    bool meta_dirty = false;   // cb_meta was not reset by the last kernel of a call
+    int meta_phase = 0;        // which of the two statistics slots of cb_meta the next filter call uses
+    int rr_blocks_last = 0;    // blocks of the last call's re-rank kernel (their counters are summed on request)
     bool timing = false;
     pv_timer timers[PV_K_COUNT];
     std::vector<hipEvent_t> event_pool;
@@ -41,12 +42,12 @@ struct pv_ctx {
     pv_buffer sel_state;    // u32 [4]            threshold key, ties to take
     pv_buffer stats;        // i64 [8]            counters of the last re-encode
     pv_buffer cb_f16;       // prepared codebook operand for the matrix-core filter
-    pv_buffer cb_meta;      // f32/u32 [16]       scale exponent, max norms, rounding bounds
-    pv_buffer x_f16;        // prepared target operand [k_pad][16*NK] halves
+    pv_buffer cb_meta;      // u32 [2][8]         two slots of codebook statistics (scale, norms, rounding bound)
+    pv_buffer x_f16;        // prepared target operand [k_pad / 32][2][32][8] halves
     pv_buffer x_meta;       // f32 [k_pad][4]     per-group bounds and flags
-    pv_buffer partials;     // u32 [k_pad][P][2]  best / runner-up keys per partition
-    pv_buffer fb_list;      // i32 [k] + counter  groups handed to the exact scan
-    pv_buffer rr_counts;    // u32 [blocks][3]    per-block counters of the re-rank kernel
+    pv_buffer partials;     // i32 [P][k_pad][2]  best / runner-up keys per partition
+    pv_buffer fb_list;      // counters (work-item hand-out) and, for the beam path, the groups left to the exact kernel
+    pv_buffer rr_counts;    // u32 [blocks][4]    per-block counters of the re-rank kernel
     pv_buffer trust;        // scratch of the trust-ratio call (saved codes, keys, prefix sums, sort space)
     pv_buffer pstep;        // scratch of the P-step gradients (keys, sorted order, segment starts, sort space)
 };

@@ -7,42 +7,42 @@
 // the distance of every codeword to every selected group is one dense
 // contraction.  It is evaluated on fp16 MFMA (fp32 accumulate) for fp16-rounded
 // copies c_hi, x_hi of the operands, scaled by a power of two P so that the
-// largest codebook entry lies in [16, 32).  The spare K slots of the
-// 32x32x16 instruction carry ||c_hi||^2 and ||x_hi||^2 (each split into three
-// fp16 pieces, times 1), so an accumulator IS the approximate squared distance
-//     D~(c) = || c_hi - x_hi ||^2 + off        (+- E1 of fp32 accumulation),
-// a positive float whose bit pattern orders like an unsigned integer.
+// largest codebook entry lies in [16, 32), in the form of a "closeness"
+//     kv(c) = SHIFT + 2 <c_hi, x_hi> - ||c_hi||^2  =  SHIFT + ||x_hi||^2 - || c_hi - x_hi ||^2
+// which is LARGE for near codewords.  SHIFT = (||x_hi|| + min_c ||c|| + margin)^2 is a constant
+// of the group that makes kv non-negative for at least the smallest codeword, so a negative kv
+// marks a codeword farther away than that one.
+//   g = 8:  the spare K slots of the 32x32x16 instruction carry -||c_hi||^2 (three fp16
+//           pieces against -1) and SHIFT (three pieces against 1): the accumulator IS kv.
+//   g = 16: all 16 K slots carry data, so the accumulator is 2 <c_hi, x_hi> alone.  The
+//           codebook is laid out in ascending order of ||c_hi||^2, so that the norms of the
+//           32 U codewords behind one key differ by next to nothing: after the maximum of the
+//           products was taken (never below zero, which can only raise it), the smallest of
+//           those norms is subtracted (again raising the key at most) and SHIFT added.
 //
-// Running minimum (per lane, in registers): the 16 accumulators of a lane
-// belong to one group (column) and to 16 consecutive codewords (a "half
-// tile"); they are reduced with v_min3_u32, the low 11 bits of the minimum are
-// replaced by the tile number, and the lane keeps the smallest and the second
-// smallest such key per partition.  A partition is (codeword range of the
-// workgroup) x (half wave) x (tile residue class).
+// Running maximum (per lane, in registers): the 16 accumulators of a lane belong to one group
+// (column) and to 16 consecutive codeword positions (a "half tile"); they are reduced with
+// v_max3_i32 on the float bits (correct whenever the maximum is non-negative; if every value
+// is negative the result is some negative value, which is all that is needed), the chain runs
+// on over the U tiles of a "super-unit", the low 11 bits of the result are replaced by the
+// super-unit number, and the lane keeps the largest and second largest such key per partition.
+// A partition is (codeword range of the work item) x (half wave) x (super-unit residue class).
 //
-// Exact re-rank + certificate (k_rerank): the 16 codewords of the best half
-// tile and the previous code are evaluated in double -> E*.  A codeword that
-// was not evaluated lies in a half tile whose key is at least the partition's
-// runner-up key (or the best key of a partition that was not evaluated), and
-//     | ||P C[c] - P x|| - ||c_hi - x_hi|| | <= dC + dx        (triangle inequality)
-// with dC = max_c ||P C[c] - c_hi|| and dx = ||P x - x_hi|| (+ division
-// rounding), so any codeword that could still reach E* has
-//     key value < Vcut = (P sqrt(E*)/|s| + dC + dx)^2 + off + E1 .
-// Every best-key half tile below Vcut is evaluated as well; if a runner-up key
-// lies below Vcut the group cannot be certified and goes to the exact scan.
-// Hence the chosen code is the double-precision argmin with the tie rule of
-// the definition, whatever the fp16 rounding did.
-#include <type_traits>
-
+// Exact re-rank + certificate (k_rerank): the 16 U codewords behind the best key and the
+// previous code are evaluated in double -> E*.  With the triangle inequality
+//     | ||P C[c] - P x|| - ||c_hi - x_hi|| | <= dC + dx
+// (dC = max_c ||P C[c] - c_hi||, dx = ||P x - x_hi|| + division rounding) a codeword can reach
+// E* only if  kv(c) >= SHIFT + ||x_hi||^2 - (P sqrt(E*)/|s| + dC + dx)^2, and the key behind
+// which it sits is at least kv(c) - E1 (fp32 accumulation, dropped pieces, truncation).  Every
+// best key at or above that cut is evaluated as well; a partition whose runner-up key reaches
+// the cut may hide further codewords and is scanned completely, in the same kernel.  Hence the
+// chosen code is the double-precision argmin with the tie rule of the definition, whatever the
+// fp16 rounding did.
 #include "pv_internal.h"
 
 // Launch shape of the contraction kernel (tunable at build time).
 #ifndef PV_STAGE
-#define PV_STAGE 32   // KiB of operand A per LDS stage
-#endif
-#ifndef PV_STAGE2
-#define PV_STAGE2 48  // the same for two k-steps per tile (g = 16): longer stages pay there even
-                      // though only one block then fits a compute unit's LDS
+#define PV_STAGE 32   // KiB of operand A per LDS stage (= codeword tiles per stage)
 #endif
 #ifndef PV_NBX
 #define PV_NBX 2      // group tiles (32 groups) per wave
@@ -53,6 +53,12 @@
 #ifndef PV_OCC
 #define PV_OCC 2      // blocks per compute unit the register / LDS budget allows
 #endif
+#ifndef PV_SUPER
+#define PV_SUPER 2    // codeword tiles behind one key (a super-unit)
+#endif
+#ifndef PV_DEPTH
+#define PV_DEPTH 2    // units (matrix instructions) in flight before a unit's accumulators are reduced
+#endif
 
 namespace {
 
@@ -60,14 +66,20 @@ typedef _Float16 h8 __attribute__((ext_vector_type(8)));
 typedef float f16v __attribute__((ext_vector_type(16)));
 
 constexpr int kBlock = 256;
-constexpr int kResidues = 4;         // tile residue classes tracked separately per lane
-constexpr unsigned kTileMask = 0x7FFu;
+constexpr int kU = PV_SUPER;
+constexpr int kResidues = 4;         // super-unit residue classes tracked separately per lane
+constexpr unsigned kKeyMask = 0x7FFu;
+constexpr int kNoKey = (int)0x80000000;             // "no key": below every key a lane can form
 constexpr float kHalfMinNormal = 6.103515625e-05f;  // 2^-14
 constexpr float kGamma = 7.62939453125e-06f;        // 2^-17: fp32 accumulation bound per unit of sum|terms|
+constexpr float kNormMargin = 0.04f;                // >= max_c | ||c_hi|| - ||P c|| | (half an fp16 ulp below 32, 16 dims)
+constexpr int kNormBins = 65536;                    // buckets of the norm ordering (g = 16)
 
-// cb_meta layout (unsigned[8]): [0] bits of max|C|, [1] bits of max ||c_hi||^2,
-// [2] bits of max ||P c - c_hi||^2, [3] bad-codebook flag
-// x_meta layout (float[4] per selected group): off, E1, dx, flag (1 = skip the filter)
+// cb_meta layout (unsigned[8]): [0] bits of max|C|, [1] ~bits of min_c ||c||^2 (unscaled),
+// [2] bits of max ||P c - c_hi||^2, [3] bad-codebook flag, [4] blocks of the re-rank kernel done,
+// [5] bits of max_c ||c||^2 (unscaled)
+// x_meta layout (float[4] per selected group): SHIFT as the kernel adds it, ||x_hi||^2, E1,
+// dx (negative: the filter is skipped for this group)
 
 __device__ __forceinline__ float scale_from_maxabs(unsigned maxbits, bool *ok)
 {
@@ -94,106 +106,235 @@ __device__ __forceinline__ void split3(float v, _Float16 *p)
     p[2] = to_half_flush(r);
 }
 
-// Largest |entry| of the codebook (fixes the common scale P).  Block 0 also
-// clears the per-call counters, which only later launches touch.
-__global__ __launch_bounds__(kBlock) void k_cb_absmax(const float *__restrict__ cb, int64_t n,
-                                                      unsigned *__restrict__ meta,
-                                                      unsigned long long *__restrict__ stats,
-                                                      unsigned *__restrict__ fb_count,
-                                                      unsigned long long *__restrict__ num_changed)
+// Bucket of a squared norm of scaled fp16 codeword entries (at most 16 * 32^2): the 32 octaves
+// below 2^15, 2048 buckets each; ascending in the norm.
+__device__ __forceinline__ int norm_bucket(float n2)
 {
+    const int e = (int)(__float_as_uint(n2) >> 12);
+    const int top = (int)(0x47000000u >> 12);      // bits of 32768.0f
+    const int key = e - (top - (kNormBins - 1));
+    return key < 0 ? 0 : (key > kNormBins - 1 ? kNormBins - 1 : key);
+}
+
+// fp16 copy of one scaled codeword: c_hi (as floats), its squared norm, the squared rounding error
+template <int G>
+__device__ __forceinline__ void round_codeword(const float *__restrict__ cw, float P, bool ok,
+                                               float (&hf)[G], float &n2, float &d2)
+{
+    n2 = 0.0f;
+    d2 = 0.0f;
+    const pv_f4 *src = reinterpret_cast<const pv_f4 *>(cw);
+#pragma unroll
+    for (int v4 = 0; v4 < G / 4; ++v4) {
+        pv_f4 raw = src[v4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            const int i = v4 * 4 + e;
+            float v = ok ? P * raw[e] : 0.0f;
+            hf[i] = (float)to_half_flush(v);
+            n2 = fmaf(hf[i], hf[i], n2);
+            float d = v - hf[i];
+            d2 = fmaf(d, d, d2);
+        }
+    }
+}
+
+// Codebook statistics, one thread per codeword: largest |entry| (fixes the common scale P),
+// smallest squared norm, non-finite entries.  Block 0 also clears the per-call counters, and
+// the grid clears the tables of the norm ordering (g = 16), which only later launches touch.
+// The statistics live in one of two slots, alternating from call to call: this kernel clears
+// the slot of the next call (nothing of this call reads it), so no kernel has to run last.
+template <int G>
+__global__ __launch_bounds__(kBlock) void k_cb_stats(const float *__restrict__ cb, int csize,
+                                                     unsigned *__restrict__ meta,
+                                                     unsigned *__restrict__ meta_next,
+                                                     unsigned long long *__restrict__ stats,
+                                                     unsigned *__restrict__ fb_count,
+                                                     unsigned long long *__restrict__ num_changed,
+                                                     unsigned *__restrict__ hist,
+                                                     unsigned *__restrict__ nmin_bits, int nsu_alloc,
+                                                     unsigned long long *__restrict__ change_slots,
+                                                     int nslots)
+{
+    for (int i = blockIdx.x * kBlock + threadIdx.x; i < nslots; i += gridDim.x * kBlock) change_slots[i] = 0ull;
     if (blockIdx.x == 0) {
         if (threadIdx.x < 8) stats[threadIdx.x] = 0ull;
+        if (threadIdx.x < 8) meta_next[threadIdx.x] = 0u;   // the statistics slot of the next call
         if (threadIdx.x < 4) fb_count[threadIdx.x] = 0u;
         if (threadIdx.x == 0 && num_changed) *num_changed = 0ull;
     }
-    float m = 0.0f;
-    bool bad = false;
-    const pv_f4 *cb4 = reinterpret_cast<const pv_f4 *>(cb);
-    const int64_t n4 = n >> 2;   // the codebook holds 2^B * g floats with g a multiple of 8
-    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < n4; i += (int64_t)gridDim.x * kBlock) {
-        pv_f4 v = cb4[i];
-        float a = fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w)));
-        bad |= !(fabsf(v.x) <= 3.0e38f) || !(fabsf(v.y) <= 3.0e38f) || !(fabsf(v.z) <= 3.0e38f) ||
-               !(fabsf(v.w) <= 3.0e38f);
-        m = fmaxf(m, a);
+    const int tid = blockIdx.x * kBlock + threadIdx.x, nthreads = gridDim.x * kBlock;
+    if (hist) {
+        for (int i = tid; i < kNormBins; i += nthreads) hist[i] = 0u;
+        for (int i = tid; i < nsu_alloc; i += nthreads) nmin_bits[i] = 0x7F800000u;   // +inf
     }
-    __shared__ float s_m[kBlock / 64];
-    for (int off = 32; off > 0; off >>= 1) m = fmaxf(m, __shfl_down(m, off));
-    if ((threadIdx.x & 63) == 0) s_m[threadIdx.x >> 6] = m;
+    float m = 0.0f, nmin = __builtin_huge_valf(), nmax = 0.0f;
+    bool bad = false;
+    for (int c = tid; c < csize; c += nthreads) {
+        const pv_f4 *src = reinterpret_cast<const pv_f4 *>(cb + (int64_t)c * G);
+        float n2 = 0.0f;
+#pragma unroll
+        for (int v4 = 0; v4 < G / 4; ++v4) {
+            pv_f4 v = src[v4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float a = fabsf(v[e]);
+                bad |= !(a <= 3.0e38f);
+                m = fmaxf(m, a);
+                n2 = fmaf(v[e], v[e], n2);
+            }
+        }
+        nmin = fminf(nmin, n2);
+        nmax = fmaxf(nmax, n2);
+    }
+    __shared__ float s_m[kBlock / 64], s_n[kBlock / 64], s_x[kBlock / 64];
+    for (int off = 32; off > 0; off >>= 1) {
+        m = fmaxf(m, __shfl_down(m, off));
+        nmin = fminf(nmin, __shfl_down(nmin, off));
+        nmax = fmaxf(nmax, __shfl_down(nmax, off));
+    }
+    if ((threadIdx.x & 63) == 0) {
+        s_m[threadIdx.x >> 6] = m;
+        s_n[threadIdx.x >> 6] = nmin;
+        s_x[threadIdx.x >> 6] = nmax;
+    }
     __syncthreads();
     if (threadIdx.x == 0) {   // one atomic per block: same-address atomics serialise
 #pragma unroll
-        for (int w = 1; w < kBlock / 64; ++w) m = fmaxf(m, s_m[w]);
+        for (int w = 1; w < kBlock / 64; ++w) {
+            m = fmaxf(m, s_m[w]);
+            nmin = fminf(nmin, s_n[w]);
+            nmax = fmaxf(nmax, s_x[w]);
+        }
         atomicMax(&meta[0], __float_as_uint(m));
+        if (nmin >= 0.0f && nmin < 3.0e38f) atomicMax(&meta[1], ~__float_as_uint(nmin));
+        if (nmax >= 0.0f && nmax < 3.0e38f) atomicMax(&meta[5], __float_as_uint(nmax));
+        else bad = true;
     }
     if (bad) atomicMax(&meta[3], 1u);
 }
 
+// Norm ordering, step 1 (g = 16): bucket of every codeword's ||c_hi||^2 and the bucket counts.
+template <int G>
+__global__ __launch_bounds__(kBlock) void k_cb_bucket(const float *__restrict__ cb, int csize,
+                                                      const unsigned *__restrict__ meta,
+                                                      uint16_t *__restrict__ bucket,
+                                                      unsigned *__restrict__ hist)
+{
+    bool ok;
+    const float P = scale_from_maxabs(meta[0], &ok);
+    const int c = blockIdx.x * kBlock + threadIdx.x;
+    if (c >= csize) return;
+    float hf[G], n2, d2;
+    round_codeword<G>(cb + (int64_t)c * G, P, ok, hf, n2, d2);
+    const int b = norm_bucket(n2);
+    bucket[c] = (uint16_t)b;
+    atomicAdd(&hist[b], 1u);
+}
+
+// Step 2: exclusive prefix sum of the bucket counts, in place (one block of 1024 threads).
+__global__ __launch_bounds__(1024) void k_cb_scan(unsigned *__restrict__ hist)
+{
+    constexpr int per = kNormBins / 1024;
+    __shared__ unsigned s_w[16];
+    unsigned v[per], sum = 0;
+#pragma unroll
+    for (int i = 0; i < per; ++i) {
+        v[i] = hist[threadIdx.x * per + i];
+        sum += v[i];
+    }
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    unsigned inc = sum;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        unsigned u = __shfl_up(inc, off);
+        if (lane >= off) inc += u;
+    }
+    if (lane == 63) s_w[wave] = inc;
+    __syncthreads();
+    unsigned before = 0;
+    for (int w = 0; w < wave; ++w) before += s_w[w];
+    unsigned run = before + inc - sum;
+#pragma unroll
+    for (int i = 0; i < per; ++i) {
+        hist[threadIdx.x * per + i] = run;
+        run += v[i];
+    }
+}
+
 // Operand preparation, one launch for both sides.
 //
-// Blocks [0, cb_blocks): one thread per codeword -> fp16 operand rows in MFMA
-// order + the rounding bound dC.  Operand A of tile t (32 codewords), k-step j,
-// k-half h, row r is the 16-byte chunk A[((t * NK + j) * 2 + h) * 32 + r].
-// Codeword c sits in tile c / 32 at row 8*(q/4) + 4*hw + q%4 with
-// hw = (c/16)%2, q = c%16, so that accumulator q of half wave hw is codeword
-// 32*t + 16*hw + q.
+// Blocks [0, cb_blocks): one thread per codeword position of the padded table.  A codeword is
+// placed at position pos (g = 8: its own index; g = 16: the next free slot of its norm bucket,
+// so positions ascend in ||c_hi||^2 up to the bucket width), perm[pos] names it.  The 32 U
+// positions of super-unit su are split in two runs of 16 U, one per half wave hw, each run in
+// U pieces of 16, one per tile: position pos = ((su * 2 + hw) * U + uu) * 16 + q sits in tile
+// su * U + uu at row 8*(q/4) + 4*hw + q%4, so that accumulator q of half wave hw is that
+// position, and the 16 U positions behind one key of a lane are consecutive (for g = 16: in
+// norm order, their smallest norm is nmin[su * 2 + hw]).  Operand A of tile t, k-half h, row r
+// is the 16-byte chunk A[(t * 2 + h) * 32 + r]:
+//   g = 8:  k-half 0 = 2 c_hi, k-half 1 = { three pieces of ||c_hi||^2, 1, 1, 1, 0, 0 }
+//   g = 16: k-half 0 = 2 c_hi[0..8), k-half 1 = 2 c_hi[8..16)
+// Positions past the codebook's end (padding up to whole super-units) are zero rows.
 //
-// Remaining blocks: one thread per selected group (position j in the list):
-// x = t / s, its fp16 copy in MFMA operand order, per-group bounds.  Operand B
-// of group tile gt, k-step j, k-half h, column col is the chunk
-// X[((gt * NK + j) * 2 + h) * 32 + col].
+// Remaining blocks: one thread per selected group (position j in the list): x = t / s, its
+// fp16 copy, per-group bounds.  Operand B of group tile gt, k-half h, column col is the chunk
+// X[(gt * 2 + h) * 32 + col]:
+//   g = 8:  k-half 0 = x_hi, k-half 1 = { -1, -1, -1, three pieces of SHIFT, 0, 0 }
+//   g = 16: the two halves of x_hi (SHIFT travels in x_meta)
 template <int G>
-__global__ __launch_bounds__(kBlock) void k_prep(const float *__restrict__ cb, int csize,
+__global__ __launch_bounds__(kBlock) void k_prep(const float *__restrict__ cb, int csize, int cpad,
                                                  int cb_blocks, unsigned *__restrict__ meta,
-                                                 h8 *__restrict__ A, const float *__restrict__ T,
+                                                 h8 *__restrict__ A, uint16_t *__restrict__ perm,
+                                                 const uint16_t *__restrict__ bucket,
+                                                 unsigned *__restrict__ bucket_next,
+                                                 unsigned *__restrict__ nmin_bits,
+                                                 const float *__restrict__ T,
                                                  const float *__restrict__ scales,
                                                  const int32_t *__restrict__ group_idx, int k,
                                                  int k_pad, int gpr, int N, h8 *__restrict__ X,
                                                  float *__restrict__ x_meta)
 {
-    constexpr int NK = G / 8;
     bool ok;
     const float P = scale_from_maxabs(meta[0], &ok);
-    h8 chunk[2 * NK];
+    h8 chunk[2];
 #pragma unroll
-    for (int u = 0; u < 2 * NK; ++u)
+    for (int u = 0; u < 2; ++u)
 #pragma unroll
         for (int e = 0; e < 8; ++e) chunk[u][e] = (_Float16)0.0f;
 
     if ((int)blockIdx.x < cb_blocks) {
         const int c = blockIdx.x * kBlock + threadIdx.x;
         float d2 = 0.0f;
-        if (c < csize) {
-            float n2 = 0.0f;
-            const pv_f4 *src = reinterpret_cast<const pv_f4 *>(cb + (int64_t)c * G);
+        if (c < cpad) {
+            int pos = c;
+            if (c < csize) {
+                float hf[G], n2;
+                round_codeword<G>(cb + (int64_t)c * G, P, ok, hf, n2, d2);
 #pragma unroll
-            for (int v4 = 0; v4 < G / 4; ++v4) {
-                pv_f4 raw = src[v4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int i = v4 * 4 + e;
-                    float v = ok ? P * raw[e] : 0.0f;
-                    _Float16 hv = to_half_flush(v);
-                    float hf = (float)hv;
-                    n2 = fmaf(hf, hf, n2);
-                    float d = v - hf;
-                    d2 = fmaf(d, d, d2);
-                    chunk[i >> 3][i & 7] = (_Float16)(-2.0f * hf);
+                for (int i = 0; i < G; ++i) chunk[i >> 3][i & 7] = (_Float16)(2.0f * hf[i]);
+                if (G == 8) {
+                    _Float16 pieces[3];
+                    split3(n2, pieces);
+                    chunk[1][0] = pieces[0];
+                    chunk[1][1] = pieces[1];
+                    chunk[1][2] = pieces[2];
+                    chunk[1][3] = (_Float16)1.0f;
+                    chunk[1][4] = (_Float16)1.0f;
+                    chunk[1][5] = (_Float16)1.0f;
+                } else {
+                    pos = (int)atomicAdd(&bucket_next[bucket[c]], 1u);
+                    atomicMin(&nmin_bits[pos / (16 * kU)], __float_as_uint(n2));
                 }
+                perm[pos] = (uint16_t)c;
+            } else if (G == 16) {
+                atomicMin(&nmin_bits[pos / (16 * kU)], 0u);   // padding rows count as norm 0
             }
-            _Float16 pieces[3];
-            split3(n2, pieces);
-            chunk[NK][0] = pieces[0];
-            chunk[NK][1] = pieces[1];
-            chunk[NK][2] = pieces[2];
-            chunk[NK][3] = (_Float16)1.0f;
-            chunk[NK][4] = (_Float16)1.0f;
-            chunk[NK][5] = (_Float16)1.0f;
-            const int tile = c >> 5, hw = (c >> 4) & 1, q = c & 15;
+            const int q = pos & 15, uu = (pos >> 4) % kU, hw = (pos / (16 * kU)) & 1;
+            const int tile = (pos / (32 * kU)) * kU + uu;
             const int row = 8 * (q >> 2) + 4 * hw + (q & 3);
 #pragma unroll
-            for (int u = 0; u < 2 * NK; ++u) A[((int64_t)tile * NK * 2 + u) * 32 + row] = chunk[u];
+            for (int u = 0; u < 2; ++u) A[((int64_t)tile * 2 + u) * 32 + row] = chunk[u];
         }
         __shared__ float s_d[kBlock / 64];
         for (int off = 32; off > 0; off >>= 1) d2 = fmaxf(d2, __shfl_down(d2, off));
@@ -209,16 +350,16 @@ __global__ __launch_bounds__(kBlock) void k_prep(const float *__restrict__ cb, i
 
     const int j = ((int)blockIdx.x - cb_blocks) * kBlock + threadIdx.x;
     if (j >= k_pad) return;
-    ok = ok && meta[3] == 0u;
-    // ||c_hi|| <= sqrt(G) * 32 because every scaled codebook entry is below 32 in magnitude
-    const float cmax = 32.0f * (G == 8 ? 2.8285f : 4.0004f);
-    float off = 0.0f, e1 = 0.0f, dx = 0.0f, flag = 1.0f;
+    ok = ok && meta[3] == 0u && meta[1] != 0u;
+    // ||c_hi|| <= P max_c ||c|| + rounding
+    const float cmax = P * sqrtf(__uint_as_float(meta[5])) * 1.0001f + kNormMargin;
+    float shift = 0.0f, xx = 0.0f, e1 = 0.0f, dx = -1.0f;
     const int n = j < k ? group_idx[j] : -1;
     if (n >= 0 && n < N && ok) {
         const float s = scales[n / gpr];
         bool fits = (s != 0.0f) && (fabsf(s) < 3.0e38f);
         const float div = fits ? s : 1.0f;
-        float xx = 0.0f, d2 = 0.0f, u2 = 0.0f;
+        float d2 = 0.0f, u2 = 0.0f;
         const pv_f4 *src = reinterpret_cast<const pv_f4 *>(T + (int64_t)n * G);
 #pragma unroll
         for (int v4 = 0; v4 < G / 4; ++v4) {
@@ -237,108 +378,133 @@ __global__ __launch_bounds__(kBlock) void k_prep(const float *__restrict__ cb, i
                 chunk[i >> 3][i & 7] = hv;
             }
         }
-        if (fits && xx < 57000.0f) {
-            const float xn = sqrtf(xx) * 1.0001f;
-            // bound of the fp32 accumulation error of one accumulator, plus dropped fp16 pieces
-            const float e1p = kGamma * (cmax + xn) * (cmax + xn) * 1.01f + 2.5e-4f;
-            off = 4.0f * e1p;
+        const float xn = sqrtf(xx) * 1.0001f;
+        // the smallest codeword, scaled: kv of that codeword is then non-negative
+        const float cn0 = P * sqrtf(__uint_as_float(~meta[1])) * 1.0001f + kNormMargin;
+        const float want = (xn + cn0) * (xn + cn0) * 1.0001f + 1.0e-3f;
+        if (fits && xx < 57000.0f && want < 60000.0f) {
+            // bound of the fp32 accumulation error of one accumulator (g = 8: products, norm
+            // pieces and SHIFT add up to at most 2 (cmax + xn)^2 in magnitude; g = 16: the
+            // products alone, then two fp32 additions on the vector ALU), plus dropped fp16 pieces
+            const float e1p = (G == 8 ? 2.0f : 1.0f) * kGamma * (cmax + xn) * (cmax + xn) * 1.01f +
+                              (G == 8 ? 5.0e-4f : 4.0e-7f * (cmax + xn) * (cmax + xn));
             e1 = 1.01f * e1p;
             // rounding of x to fp16, plus the fp32 division and scaling roundings (2^-22 ||u||)
             dx = sqrtf(d2) * 1.0001f + 2.4e-7f * sqrtf(u2) + 1.0e-30f;
-            flag = 0.0f;
-            _Float16 pieces[3];
-            split3(xx + off, pieces);
-            chunk[NK][0] = (_Float16)1.0f;
-            chunk[NK][1] = (_Float16)1.0f;
-            chunk[NK][2] = (_Float16)1.0f;
-            chunk[NK][3] = pieces[0];
-            chunk[NK][4] = pieces[1];
-            chunk[NK][5] = pieces[2];
+            if (G == 8) {
+                _Float16 pieces[3];
+                split3(want, pieces);
+                shift = ((float)pieces[0] + (float)pieces[1]) + (float)pieces[2];
+                chunk[1][0] = (_Float16)-1.0f;
+                chunk[1][1] = (_Float16)-1.0f;
+                chunk[1][2] = (_Float16)-1.0f;
+                chunk[1][3] = pieces[0];
+                chunk[1][4] = pieces[1];
+                chunk[1][5] = pieces[2];
+            } else {
+                shift = want;
+            }
         } else {
+            xx = 0.0f;
 #pragma unroll
-            for (int u = 0; u < 2 * NK; ++u)
+            for (int u = 0; u < 2; ++u)
 #pragma unroll
                 for (int e = 0; e < 8; ++e) chunk[u][e] = (_Float16)0.0f;
         }
     }
     const int gt = j >> 5, col = j & 31;
 #pragma unroll
-    for (int u = 0; u < 2 * NK; ++u) X[((int64_t)gt * NK * 2 + u) * 32 + col] = chunk[u];
+    for (int u = 0; u < 2; ++u) X[((int64_t)gt * 2 + u) * 32 + col] = chunk[u];
     pv_f4 m;
-    m.x = off;
-    m.y = e1;
-    m.z = dx;
-    m.w = flag;
+    m.x = shift;
+    m.y = xx;
+    m.z = e1;
+    m.w = dx;
     reinterpret_cast<pv_f4 *>(x_meta)[j] = m;
 }
 
 // Plain C so that the compiler sees the reads of MFMA results and inserts the
 // wait states the hardware requires between a matrix instruction and a vector
 // read of its destination (it does not look inside inline assembly).  It folds
-// the pair of mins into one v_min3_u32.
-__device__ __forceinline__ unsigned umin3(unsigned a, unsigned b, unsigned c)
+// the pair of maxima into one v_max3_i32.
+__device__ __forceinline__ int imax3(int a, int b, int c)
 {
-    return min(min(a, b), c);
+    return max(max(a, b), c);
 }
 
-// (m & mask) | tile in one instruction; operands are ordinary vector results.
-__device__ __forceinline__ unsigned and_or(unsigned m, unsigned vmask, unsigned tile)
+// (m & mask) | unit in one instruction; operands are ordinary vector results.
+__device__ __forceinline__ int and_or(int m, unsigned vmask, unsigned unit)
 {
-    unsigned r;
-    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(m), "v"(vmask), "s"(tile));
+    int r;
+    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(m), "v"(vmask), "s"(unit));
     return r;
 }
 
-__device__ __forceinline__ unsigned umed3(unsigned a, unsigned b, unsigned c)
+__device__ __forceinline__ int imed3(int a, int b, int c)
 {
-    unsigned r;
-    asm("v_med3_u32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    int r;
+    asm("v_med3_i32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
     return r;
 }
 
-// Smallest of the 16 accumulators (positive floats compared as integers).  A single chain:
-// a tree of independent v_min3 measured no faster here (the waves of a SIMD interleave).
-__device__ __forceinline__ unsigned acc_min(const f16v &acc)
+// Largest of a running value and the 16 accumulators (float bits compared as signed integers:
+// the order of non-negative floats; a negative float lies below every non-negative one).
+// A single chain: a tree of independent v_max3 measured no faster here (the waves of a SIMD
+// interleave).
+template <bool FIRST>
+__device__ __forceinline__ int acc_max(const f16v &acc, int run)
 {
-    unsigned m = umin3(__float_as_uint(acc[0]), __float_as_uint(acc[1]), __float_as_uint(acc[2]));
-    m = umin3(m, __float_as_uint(acc[3]), __float_as_uint(acc[4]));
-    m = umin3(m, __float_as_uint(acc[5]), __float_as_uint(acc[6]));
-    m = umin3(m, __float_as_uint(acc[7]), __float_as_uint(acc[8]));
-    m = umin3(m, __float_as_uint(acc[9]), __float_as_uint(acc[10]));
-    m = umin3(m, __float_as_uint(acc[11]), __float_as_uint(acc[12]));
-    m = umin3(m, __float_as_uint(acc[13]), __float_as_uint(acc[14]));
-    return min(m, __float_as_uint(acc[15]));
+    int m;
+    if (FIRST && run == kNoKey) {
+        m = imax3(__float_as_int(acc[0]), __float_as_int(acc[1]), __float_as_int(acc[2]));
+        m = imax3(m, __float_as_int(acc[3]), __float_as_int(acc[4]));
+        m = imax3(m, __float_as_int(acc[5]), __float_as_int(acc[6]));
+        m = imax3(m, __float_as_int(acc[7]), __float_as_int(acc[8]));
+        m = imax3(m, __float_as_int(acc[9]), __float_as_int(acc[10]));
+        m = imax3(m, __float_as_int(acc[11]), __float_as_int(acc[12]));
+        m = imax3(m, __float_as_int(acc[13]), __float_as_int(acc[14]));
+        return max(m, __float_as_int(acc[15]));
+    }
+    m = imax3(run, __float_as_int(acc[0]), __float_as_int(acc[1]));
+    m = imax3(m, __float_as_int(acc[2]), __float_as_int(acc[3]));
+    m = imax3(m, __float_as_int(acc[4]), __float_as_int(acc[5]));
+    m = imax3(m, __float_as_int(acc[6]), __float_as_int(acc[7]));
+    m = imax3(m, __float_as_int(acc[8]), __float_as_int(acc[9]));
+    m = imax3(m, __float_as_int(acc[10]), __float_as_int(acc[11]));
+    m = imax3(m, __float_as_int(acc[12]), __float_as_int(acc[13]));
+    return imax3(m, __float_as_int(acc[14]), __float_as_int(acc[15]));
 }
 
-// The distance contraction.  Block = 4 waves; wave w owns NB group tiles (32
-// groups each) whose B operands stay in registers; the block streams the
-// codeword tiles [t_begin, t_end) of its split through a double-buffered LDS
-// stage shared by the 4 waves.  A stage is filled with direct global->LDS
-// loads (no staging registers) one stage ahead of its use.  Inside a stage the
-// loop is software pipelined: the MFMAs of tile t are issued, then the
-// accumulators of tile t-1 are reduced on the vector ALU while the matrix core
-// works.  Output: for every group and partition the smallest and second
-// smallest key.
-template <int NK, int NB>
-__global__ __launch_bounds__(PV_WAVES * 64, (PV_OCC * PV_WAVES) / 4) void k_score_mfma(const h8 *__restrict__ A,
-                                                          const h8 *__restrict__ X,
-                                                          uint2 *__restrict__ partials, int ntiles,
-                                                          int nsplit, int P, int merge,
-                                                          int gblocks, unsigned *__restrict__ next_item)
+// The distance contraction.  Block = PV_WAVES waves; wave w owns NB group tiles (32 groups
+// each) whose B operands stay in registers; the block streams the codeword tiles of its split
+// through a double-buffered LDS stage shared by its waves.  A stage is filled with direct
+// global->LDS loads (no staging registers) one stage ahead of its use.  Inside a stage the
+// loop is software pipelined: the MFMA of unit (tile, group tile) is issued, then the
+// accumulators of the unit before it are reduced on the vector ALU while the matrix core
+// works.  Output: for every group and partition the largest and second largest key.
+template <int G, int NB>
+__global__ __launch_bounds__(PV_WAVES * 64, (PV_OCC * PV_WAVES) / 4) void k_score_mfma(
+    const h8 *__restrict__ A, const h8 *__restrict__ X, const float *__restrict__ x_meta,
+    const float *__restrict__ nmin, int2 *__restrict__ partials, int ncyc, int nsplit, int per_half,
+    int gblocks, int k_pad, unsigned *__restrict__ next_item)
 {
-    constexpr int S = (NK == 1 ? PV_STAGE : PV_STAGE2) / NK;       // tiles per stage
-    constexpr int kStageChunks = S * NK * 64;                      // 16-byte chunks per stage
+    constexpr int S = PV_STAGE;                                    // tiles per stage
+    constexpr int kStageChunks = S * 64;                           // 16-byte chunks per stage
     constexpr int kW = PV_WAVES;                                   // waves per block
     constexpr int kRounds = (kStageChunks / 64 + kW - 1) / kW;     // 64-chunk rows per wave
-    static_assert(S % kResidues == 0, "stage must hold whole residue cycles");
+    constexpr int kSuStage = S / kU;                               // super-units per stage
+    constexpr int kCycle = kResidues * kU;                         // tiles per residue cycle
+    static_assert(S % kCycle == 0, "stage must hold whole residue cycles");
+    static_assert(2 * kSuStage <= 64, "one lane per staged norm");
     // two stages in SEPARATE arrays (+ one tile of padding each): the compiler then knows that
     // the asynchronous fill of one does not alias the reads of the other and does not wait
     // for the fill before every read
-    __shared__ h8 lds0[kStageChunks + NK * 64];
-    __shared__ h8 lds1[kStageChunks + NK * 64];
+    __shared__ h8 lds0[kStageChunks + 64];
+    __shared__ h8 lds1[kStageChunks + 64];
+    __shared__ float ldn0[64], ldn1[64];     // smallest norm behind each key of the stage (g = 16)
     __shared__ unsigned s_item;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    unsigned vmask = ~kTileMask;
+    unsigned vmask = ~kKeyMask;
     asm volatile("" : "+v"(vmask));   // keep the mask in a vector register
     // Work items = (group block, codeword split).  A block starts with item blockIdx.x; when
     // there are more items than blocks the rest is handed out through a counter, so the
@@ -348,25 +514,31 @@ __global__ __launch_bounds__(PV_WAVES * 64, (PV_OCC * PV_WAVES) / 4) void k_scor
     for (unsigned item = blockIdx.x; item < items;) {
     const int gb = (int)(item % (unsigned)gblocks), split = (int)(item / (unsigned)gblocks);
     const int gtile0 = (gb * kW + wave) * NB;
-    const int t_begin = (int)((int64_t)split * ntiles / nsplit);
-    const int t_end = (int)((int64_t)(split + 1) * ntiles / nsplit);
+    // a split is a whole number of residue cycles (the table is padded to one)
+    const int t_begin = (int)((int64_t)split * ncyc / nsplit) * kCycle;
+    const int t_end = (int)((int64_t)(split + 1) * ncyc / nsplit) * kCycle;
 
-    h8 b[NB][NK];
+    h8 b[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) b[nb] = X[(int64_t)(gtile0 + nb) * 64 + lane];
+    // g = 16: SHIFT of the lane's group (added to the key on the vector ALU)
+    float shift[NB];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb)
-#pragma unroll
-        for (int j = 0; j < NK; ++j) b[nb][j] = X[((int64_t)(gtile0 + nb) * NK + j) * 64 + lane];
+        shift[nb] = G == 16 ? x_meta[((int64_t)(gtile0 + nb) * 32 + (lane & 31)) * 4] : 0.0f;
 
-    unsigned best[NB][kResidues], second[NB][kResidues];
+    int best[NB][kResidues], second[NB][kResidues], run[NB];
 #pragma unroll
-    for (int nb = 0; nb < NB; ++nb)
+    for (int nb = 0; nb < NB; ++nb) {
+        run[nb] = kNoKey;
 #pragma unroll
-        for (int r = 0; r < kResidues; ++r) best[nb][r] = second[nb][r] = 0xFFFFFFFFu;
+        for (int r = 0; r < kResidues; ++r) best[nb][r] = second[nb][r] = kNoKey;
+    }
 
     // rows of 64 chunks (1 KiB) are copied by one wave each: lane i -> chunk row + i
-    auto fetch = [&](int t0, h8 *dst) {
-        const int valid = (t_end - t0 < S ? t_end - t0 : S) * NK * 64;
-        const h8 *src = A + (int64_t)t0 * NK * 64;
+    auto fetch = [&](int t0, h8 *dst, float *dstn) {
+        const int valid = (t_end - t0 < S ? t_end - t0 : S) * 64;
+        const h8 *src = A + (int64_t)t0 * 64;
 #pragma unroll
         for (int u = 0; u < kRounds; ++u) {
             const int row = (u * kW + wave) * 64;   // uniform over the wave
@@ -375,104 +547,122 @@ __global__ __launch_bounds__(PV_WAVES * 64, (PV_OCC * PV_WAVES) / 4) void k_scor
                     (const void *)(src + row + lane),
                     (__attribute__((address_space(3))) void *)(&dst[row]), 16, 0, 0);
         }
+        if (G == 16 && wave == kW - 1)   // the norm table is padded: reads past the split's end are harmless
+            __builtin_amdgcn_global_load_lds((const void *)(nmin + (t0 / kU) * 2 + lane),
+                                             (__attribute__((address_space(3))) void *)(&dstn[0]), 4,
+                                             0, 0);
     };
 
-    // While the matrix core works on unit (tile, nb) the vector ALU reduces the unit before
-    // it.  One accumulator set per nb (two by tile parity when NB == 1), so a set is rewritten
-    // a whole tile after it was last read.
-    constexpr int kSets = NB >= 2 ? NB : 2;
+    // Units (tile, nb) are issued in order; while the matrix core works on the last kD of them
+    // the vector ALU reduces the unit kD back.  Four accumulator sets, used round robin, so a
+    // set is rewritten three units after it was last read.
+    constexpr int kD = PV_DEPTH;
+    constexpr int kSets = 4;
+    constexpr int kUnitsCycle = NB * kCycle;            // units per residue cycle (unrolled)
+    static_assert(kUnitsCycle % kSets == 0 && kD >= 1 && kD < kSets, "accumulator sets must line up");
     f16v acc[kSets];
-    h8 a_cur[NK], a_nxt[NK];
-    auto load_a = [&](const h8 *buf, int ts, h8 *a) {
-#pragma unroll
-        for (int j = 0; j < NK; ++j) a[j] = buf[(ts * NK + j) * 64 + lane];
-    };
+    h8 a_cur, a_nxt;
     auto issue = [&](int nb, int set) {
-        f16v c = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
-#pragma unroll
-        for (int j = 0; j < NK; ++j)
-            c = __builtin_amdgcn_mfma_f32_32x32x16_f16(a_cur[j], b[nb][j], c, 0, 0, 0);
-        acc[set] = c;
+        const f16v z = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+        acc[set] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a_cur, b[nb], z, 0, 0, 0);
     };
-    auto reduce = [&](unsigned tile, int nb, int set, int r) {
-        const unsigned key = and_or(acc_min(acc[set]), vmask, tile);
-        second[nb][r] = umed3(best[nb][r], second[nb][r], key);
-        best[nb][r] = min(best[nb][r], key);
+    // rel: the tile's place in its residue cycle (a constant after unrolling: it picks the
+    // registers); su_stage: its super-unit within the stage.  The key is closed at the last
+    // tile of a super-unit.
+    auto reduce = [&](const float *bufn, int t0, int su_stage, int rel, int nb, int set) {
+        const int uu = rel % kU;
+        // g = 16: the chain starts at zero (the products can be negative, and a negative
+        // maximum would not come out of the integer comparison: zero bounds it from above)
+        if (uu == 0) run[nb] = G == 16 ? acc_max<false>(acc[set], 0) : acc_max<true>(acc[set], kNoKey);
+        else run[nb] = acc_max<false>(acc[set], run[nb]);
+        if (uu == kU - 1) {
+            const int r = rel / kU;
+            int kv = run[nb];
+            if (G == 16) kv = __float_as_int((__int_as_float(kv) - bufn[su_stage * 2 + (lane >> 5)]) + shift[nb]);
+            const int key = and_or(kv, vmask, (unsigned)(t0 / kU + su_stage));
+            second[nb][r] = imed3(best[nb][r], second[nb][r], key);
+            best[nb][r] = max(best[nb][r], key);
+        }
     };
-    // One stage of `cnt` tiles (FULL: cnt == S, no per-tile guards).
-    auto run_stage = [&](const h8 *buf, int t0, int cnt, auto full_tag) {
-        constexpr bool FULL = decltype(full_tag)::value;
-        load_a(buf, 0, a_cur);
+    // One stage of `cnt` tiles (a whole number of residue cycles).
+    auto run_stage = [&](const h8 *buf, const float *bufn, int t0, int cnt) {
+        a_cur = buf[lane];
 #pragma unroll 1
-        for (int q4 = 0; q4 < S; q4 += kResidues) {
+        for (int q4 = 0; q4 < cnt; q4 += kCycle) {
 #pragma unroll
-            for (int u = 0; u < kResidues; ++u) {
-                const int ts = q4 + u;
-                if (FULL || ts + 1 < cnt) load_a(buf, ts + 1, a_nxt);   // one spare tile pads the LDS array
-#pragma unroll
-                for (int nb = 0; nb < NB; ++nb) {
-                    const int set = NB >= 2 ? nb : (u & 1);
-                    const int prev_set = NB >= 2 ? (nb + NB - 1) % NB : ((u + 1) & 1);
-                    if (FULL || ts < cnt) issue(nb, set);
-                    if (nb > 0) {
-                        if (FULL || ts < cnt) reduce((unsigned)(t0 + ts), nb - 1, prev_set, u);
-                    } else if (ts >= 1 && (FULL || ts - 1 < cnt)) {
-                        reduce((unsigned)(t0 + ts - 1), NB - 1, prev_set, (u + kResidues - 1) % kResidues);
-                    }
-                }
-#pragma unroll
-                for (int j = 0; j < NK; ++j) a_cur[j] = a_nxt[j];
+            for (int vr = 0; vr < kUnitsCycle; ++vr) {
+                const int u = vr / NB, nb = vr % NB, ts = q4 + u;
+                if (nb == 0) a_nxt = buf[(ts + 1) * 64 + lane];   // one spare tile pads the LDS array
+                issue(nb, vr % kSets);
+                // the unit kD back: tile q4 + dq (dq may point into the cycle before), group tile wnb
+                const int dq = (vr - kD >= 0) ? (vr - kD) / NB : -((kD - vr + NB - 1) / NB);
+                const int wnb = ((vr - kD) % NB + NB) % NB;
+                if (q4 > 0 || vr >= kD)
+                    reduce(bufn, t0, (q4 + dq) / kU, (dq + kCycle) % kCycle, wnb,
+                           ((vr - kD) % kSets + kSets) % kSets);
+                // keep this order: left to itself the scheduler moves a unit's reduction up
+                // behind its own matrix instruction, and the wave then waits out that
+                // instruction's whole latency instead of working on older units
+                __builtin_amdgcn_sched_barrier(0);
+                if (nb == NB - 1) a_cur = a_nxt;
             }
         }
-        if (FULL || cnt == S)
-            reduce((unsigned)(t0 + S - 1), NB - 1, NB >= 2 ? NB - 1 : ((kResidues - 1) & 1), kResidues - 1);
+        // the last kD units of the stage (its last residue cycle)
+#pragma unroll
+        for (int w = kUnitsCycle - kD; w < kUnitsCycle; ++w)
+            reduce(bufn, t0, (cnt - kCycle + w / NB) / kU, w / NB, w % NB, w % kSets);
     };
 
-    if (t_begin < t_end) fetch(t_begin, lds0);
+    if (t_begin < t_end) fetch(t_begin, lds0, ldn0);
     __builtin_amdgcn_s_waitcnt(0);
     __syncthreads();
     // stages alternate between the two arrays; each half of the loop body names its arrays
     // statically
     for (int t0 = t_begin; t0 < t_end; t0 += 2 * S) {
         {
-            if (t0 + S < t_end) fetch(t0 + S, lds1);
-            const int cnt = t_end - t0 < S ? t_end - t0 : S;      // uniform
-            if (cnt == S) run_stage(lds0, t0, cnt, std::true_type{});
-            else run_stage(lds0, t0, cnt, std::false_type{});
+            if (t0 + S < t_end) fetch(t0 + S, lds1, ldn1);
+            run_stage(lds0, ldn0, t0, t_end - t0 < S ? t_end - t0 : S);      // uniform
             __builtin_amdgcn_s_waitcnt(0);
             __syncthreads();
         }
         const int t1 = t0 + S;
         if (t1 < t_end) {
-            if (t1 + S < t_end) fetch(t1 + S, lds0);
-            const int cnt = t_end - t1 < S ? t_end - t1 : S;
-            if (cnt == S) run_stage(lds1, t1, cnt, std::true_type{});
-            else run_stage(lds1, t1, cnt, std::false_type{});
+            if (t1 + S < t_end) fetch(t1 + S, lds0, ldn0);
+            run_stage(lds1, ldn1, t1, t_end - t1 < S ? t_end - t1 : S);
             __builtin_amdgcn_s_waitcnt(0);
             __syncthreads();
         }
     }
 
+    // records: partials[p * k_pad + j], so that the 32 lanes of a half wave write 256
+    // consecutive bytes
     const int col = lane & 31, hw = lane >> 5;
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) {
         const int64_t jpos = (int64_t)(gtile0 + nb) * 32 + col;
-        if (merge) {
-            unsigned b1 = best[nb][0], b2 = second[nb][0];
+        // the two largest of two (largest, second largest) pairs
+        auto join = [](int &b1, int &b2, int c1, int c2) {
+            const int hi = max(b1, c1), lo = min(b1, c1);
+            b2 = max(max(b2, c2), lo);
+            b1 = hi;
+        };
+        if (per_half == 1) {          // all residue classes in one record
+            int b1 = best[nb][0], b2 = second[nb][0];
 #pragma unroll
-            for (int r = 1; r < kResidues; ++r) {
-                // two smallest of {b1, b2, best[r], second[r]} (b1 <= b2, best <= second)
-                unsigned lo = min(b1, best[nb][r]);
-                unsigned hi = max(b1, best[nb][r]);
-                b2 = min(min(b2, second[nb][r]), hi);
-                b1 = lo;
+            for (int r = 1; r < kResidues; ++r) join(b1, b2, best[nb][r], second[nb][r]);
+            partials[(int64_t)(split * 2 + hw) * k_pad + jpos] = make_int2(b1, b2);
+        } else if (per_half == 2) {   // classes r and r + 2 share a record
+#pragma unroll
+            for (int r = 0; r < 2; ++r) {
+                int b1 = best[nb][r], b2 = second[nb][r];
+                join(b1, b2, best[nb][r + 2], second[nb][r + 2]);
+                partials[(int64_t)((split * 2 + hw) * 2 + r) * k_pad + jpos] = make_int2(b1, b2);
             }
-            partials[jpos * P + (split * 2 + hw)] = make_uint2(b1, b2);
         } else {
 #pragma unroll
             for (int r = 0; r < kResidues; ++r)
-                partials[jpos * P + (split * 2 + hw) * kResidues + r] =
-                    make_uint2(best[nb][r], second[nb][r]);
+                partials[(int64_t)((split * 2 + hw) * kResidues + r) * k_pad + jpos] =
+                    make_int2(best[nb][r], second[nb][r]);
         }
     }
     if (items <= gridDim.x) break;          // one item per block: nothing to fetch
@@ -515,64 +705,72 @@ __device__ __forceinline__ double exact_obj(const float *__restrict__ cw, float 
     return obj;
 }
 
-// A group the re-rank kernel could not decide alone: the partitions whose codewords must all
-// be evaluated (bit p = partition p), and the best candidate found so far.
-struct fb_rec_t {
+// largest value a key can stand for: the super-unit bits replaced by ones; a negative key
+// (every value behind it negative) is bounded by zero
+__device__ __forceinline__ float key_upper(int key)
+{
+    return key < 0 ? 0.0f : __int_as_float(key | (int)kKeyMask);
+}
+
+// A group the team could not decide alone: the partitions whose codewords must all be
+// evaluated (bit p = partition p), and the best candidate found so far.
+struct open_rec_t {
     double obj;
+    double reach2;             // a codeword can reach obj only if ||c_hi - x_hi||^2 <= reach2
     unsigned long long mask;
     int idx;
     int n;
+    int j;                     // position in the list (names the group's fp16 operand)
 };
 
-// the same objective on a codeword already in registers
-template <int G>
-__device__ __forceinline__ double exact_obj_v(const pv_f4 (&c)[G / 4], float s, const float *t)
-{
-    double obj = 0.0;
-#pragma unroll
-    for (int v4 = 0; v4 < G / 4; ++v4) {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            double acc = (double)c[v4][e];
-            double r = fma((double)s, acc, -(double)t[v4 * 4 + e]);
-            obj = obj + r * r;
-        }
-    }
-    return obj;
-}
-
-// 16 lanes ("team") per selected group; lane q scores codeword q of a half tile.
+// 16 lanes ("team") per selected group; lane q scores position q of a half tile.  Groups
+// with a partition left open are finished by the whole block afterwards, one at a time: for
+// every position of the open partitions || c_hi - x_hi ||^2 is formed exactly (in double, from
+// the fp16 operands the matrix cores saw) and the codewords that can still reach the best
+// objective found are evaluated.  Every block leaves its counters in block_counts (summed by
+// whoever asks for the call's statistics) and passes its changed codes on through atomics; no
+// block waits for another and none publishes plain stores to another (a device-wide release
+// costs a write-back of the whole L2 of the block's die).
 template <int G>
 __global__ __launch_bounds__(kBlock) void k_rerank(
     const float *__restrict__ T, const float *__restrict__ codebook,
-    const float *__restrict__ scales, const int32_t *__restrict__ group_idx, int k,
-    const uint2 *__restrict__ partials, int P, int per_half, const float *__restrict__ x_meta,
-    const unsigned *__restrict__ cb_meta, uint16_t *__restrict__ codes,
-    unsigned *__restrict__ block_counts, fb_rec_t *__restrict__ fb_rec,
-    unsigned *__restrict__ fb_count, int gpr, int N, int nbits)
+    const float *__restrict__ scales, const int32_t *__restrict__ group_idx, int k, int k_pad,
+    const int2 *__restrict__ partials, int P, int per_half, int ncyc, int nsplit,
+    const float *__restrict__ x_meta, const unsigned *__restrict__ cb_meta, const h8 *__restrict__ A,
+    const h8 *__restrict__ X, const uint16_t *__restrict__ perm, uint16_t *__restrict__ codes,
+    unsigned *__restrict__ block_counts, unsigned long long *__restrict__ change_slots,
+    unsigned long long *__restrict__ num_changed, int gpr, int N, int nbits)
 {
-    __shared__ unsigned s_cnt[3];   // groups decided here, codes changed, candidates evaluated
-    if (threadIdx.x < 3) s_cnt[threadIdx.x] = 0;
+    constexpr int kTeams = kBlock / 16;
+    __shared__ unsigned s_cnt[4];   // groups decided by the teams, codes changed, candidates evaluated, groups scanned
+    __shared__ open_rec_t s_open[kTeams];
+    __shared__ unsigned s_nopen;
+    __shared__ double s_obj[kBlock / 64];
+    __shared__ int s_idx[kBlock / 64];
+    if (threadIdx.x < 4) s_cnt[threadIdx.x] = 0;
+    if (threadIdx.x == 0) s_nopen = 0;
     __syncthreads();
+    const int csize = 1 << nbits;
     const int gid = blockIdx.x * kBlock + threadIdx.x;
     const int j = gid >> 4, q = gid & 15;
     const int n = j < k ? group_idx[j] : -1;
     bool live = n >= 0 && n < N;             // whole 16-lane teams agree on every branch below
-    pv_f4 meta = {0.f, 0.f, 0.f, 1.f};
+    pv_f4 meta = {0.f, 0.f, 0.f, -1.f};
     if (live) meta = reinterpret_cast<const pv_f4 *>(x_meta)[j];
-    if (live && meta.w != 0.0f) {            // the filter was skipped for this group: every partition
+    if (live && meta.w < 0.0f) {             // the filter was skipped for this group: every partition
         if (q == 0) {
-            fb_rec_t r;
+            open_rec_t r;
             r.obj = __builtin_huge_val();
+            r.reach2 = __builtin_huge_val();       // no operand to test against: every codeword
             r.mask = P >= 64 ? ~0ull : ((1ull << P) - 1ull);
             r.idx = 0x7fffffff;
             r.n = n;
-            fb_rec[atomicAdd(fb_count, 1u)] = r;
+            r.j = j;
+            s_open[atomicAdd(&s_nopen, 1u)] = r;
         }
         live = false;
     }
     if (live) {
-        const int csize = 1 << nbits;
         const float s = scales[n / gpr];
         float t[G];
         {
@@ -590,37 +788,44 @@ __global__ __launch_bounds__(kBlock) void k_rerank(
         // trips to memory overlap
         const int prev = codes[n] & (csize - 1);
         constexpr int kMaxRec = 4;           // P <= 64
-        uint2 rec[kMaxRec];
+        int2 rec[kMaxRec];
 #pragma unroll
         for (int u = 0; u < kMaxRec; ++u) {
             int p = q + 16 * u;
-            rec[u] = p < P ? partials[(int64_t)j * P + p] : make_uint2(0xFFFFFFFFu, 0xFFFFFFFFu);
+            rec[u] = p < P ? partials[(int64_t)p * k_pad + j] : make_int2(kNoKey, kNoKey);
         }
         const double o_prev = exact_obj<G>(codebook + (int64_t)prev * G, s, t);
         // best key over all partitions, with its partition
-        unsigned long long bk = ~0ull;
+        long long bk = (long long)0x8000000000000000ull;
 #pragma unroll
         for (int u = 0; u < kMaxRec; ++u) {
             int p = q + 16 * u;
-            unsigned long long v = ((unsigned long long)rec[u].x << 32) | (unsigned)p;
-            bk = v < bk ? v : bk;
+            long long v = ((long long)rec[u].x << 32) | (long long)(unsigned)(63 - p);
+            bk = v > bk ? v : bk;
         }
 #pragma unroll
         for (int m = 8; m > 0; m >>= 1) {
-            unsigned long long o = __shfl_xor(bk, m, 16);
-            bk = o < bk ? o : bk;
+            long long o = __shfl_xor(bk, m, 16);
+            bk = o > bk ? o : bk;
         }
-        const unsigned best_key = (unsigned)(bk >> 32);
-        const int best_p = (int)(bk & 0xFFFFFFFFu);
+        const int best_key = (int)(bk >> 32);
+        const int best_p = 63 - (int)(bk & 0xFFFFFFFFll);
 
-        auto eval_half_tile = [&](unsigned key, int p, cand_t &c) {
-            const int tile = (int)(key & kTileMask);
+        // the 16 U positions behind a key: lane q takes position q of each of the U half tiles
+        auto eval_key = [&](int key, int p, cand_t &c) {
+            const int su = key & (int)kKeyMask;
             const int hw = (p / per_half) & 1;
-            const int cw = tile * 32 + hw * 16 + q;
-            double o = exact_obj<G>(codebook + (int64_t)cw * G, s, t);
-            if (cand_better(o, cw, c.obj, c.idx)) {
-                c.obj = o;
-                c.idx = cw;
+#pragma unroll
+            for (int uu = 0; uu < kU; ++uu) {
+                const int pos = ((su * 2 + hw) * kU + uu) * 16 + q;
+                if (pos < csize) {
+                    const int cw = G == 8 ? pos : (int)perm[pos];   // g = 8: positions are codewords
+                    double o = exact_obj<G>(codebook + (int64_t)cw * G, s, t);
+                    if (cand_better(o, cw, c.obj, c.idx)) {
+                        c.obj = o;
+                        c.idx = cw;
+                    }
+                }
             }
         };
         auto team_min = [&](cand_t c) {
@@ -639,33 +844,36 @@ __global__ __launch_bounds__(kBlock) void k_rerank(
         cand_t mine;
         mine.obj = __builtin_huge_val();
         mine.idx = 0x7fffffff;
-        eval_half_tile(best_key, best_p, mine);
+        if (best_key != kNoKey) eval_key(best_key, best_p, mine);
         cand_t first = team_min(mine);
         if (o_prev < first.obj) first.obj = o_prev;   // the previous code is a candidate too
 
-        // every codeword that was not evaluated and could still reach E* has a key value below vcut
+        // every codeword that was not evaluated and could still reach E* sits behind a key
+        // whose upper bound is at least kcut
         bool okP;
         const float Pscale = scale_from_maxabs(cb_meta[0], &okP);
         const double dC = sqrt((double)__uint_as_float(cb_meta[2])) * 1.0001 + 1e-30;
         const double dstar = sqrt(first.obj) * (double)Pscale / fabs((double)s) * (1.0 + 1e-9);
-        const double reach = dstar + dC + (double)meta.z;
-        const double vcut_d = (reach * reach + (double)meta.x + (double)meta.y) * (1.0 + 1e-6);
-        const float vcut = __double2float_ru(vcut_d);
-        const bool no_bound = !(vcut_d < 3.0e38);     // also true for NaN: nothing can be excluded
+        const double reach = dstar + dC + (double)meta.w;
+        const double base = (double)meta.x + (double)meta.y;
+        const double kcut_d = base * (1.0 - 1e-6) - reach * reach * (1.0 + 1e-6) - (double)meta.z;
+        const float kcut = __double2float_rd(kcut_d);
+        const bool no_bound = !(kcut_d > -3.0e38);     // also true for NaN: nothing can be excluded
         unsigned pending = 0;                         // bit u: rec[u].x needs evaluation
-        unsigned long long open = 0;                  // partitions with a second key below vcut
+        unsigned long long open = 0;                  // partitions with a second key at or above kcut
 #pragma unroll
         for (int u = 0; u < kMaxRec; ++u) {
             int p = q + 16 * u;
             if (p < P) {
-                if (no_bound || __uint_as_float(rec[u].y & ~kTileMask) < vcut) open |= 1ull << p;
-                if (p != best_p && __uint_as_float(rec[u].x & ~kTileMask) < vcut) pending |= 1u << u;
+                if (rec[u].y != kNoKey && (no_bound || key_upper(rec[u].y) >= kcut)) open |= 1ull << p;
+                if (p != best_p && rec[u].x != kNoKey && (no_bound || key_upper(rec[u].x) >= kcut))
+                    pending |= 1u << u;
             }
         }
 #pragma unroll
         for (int m = 8; m > 0; m >>= 1) open |= __shfl_xor(open, m, 16);
         const int team_shift = (threadIdx.x & 63) & ~15;
-        // the best key of every other partition below vcut: its half tile is evaluated here
+        // the best key of every other partition at or above kcut: its positions are evaluated here
         unsigned extra = 0;
         for (;;) {
             const unsigned long long pb = __ballot(pending != 0);
@@ -674,26 +882,31 @@ __global__ __launch_bounds__(kBlock) void k_rerank(
             const int src = __ffs(team) - 1;      // lane of the team with work
             const unsigned their = __shfl(pending, src, 16);
             const int u = __ffs(their) - 1;
-            unsigned key = 0;
+            int key = 0;
 #pragma unroll
             for (int uu = 0; uu < kMaxRec; ++uu)
                 if (uu == u) key = rec[uu].x;
             key = __shfl(key, src, 16);
-            eval_half_tile(key, src + 16 * u, mine);
+            eval_key(key, src + 16 * u, mine);
             if (q == src) pending &= ~(1u << u);
             ++extra;
         }
         const cand_t win = team_min(mine);
         if (q == 0) {
             if (open) {
-                // a partition may hide further codewords below vcut: all of its codewords are
-                // evaluated by the partition scan, which also takes the decision
-                fb_rec_t r;
+                // a partition may hide further codewords at or above kcut: all of its
+                // positions are evaluated by the block, which also takes the decision
+                open_rec_t r;
+                const double e_star = o_prev < win.obj ? o_prev : win.obj;
+                const double rr = sqrt(e_star) * (double)Pscale / fabs((double)s) * (1.0 + 1e-9) + dC +
+                                  (double)meta.w;
                 r.obj = win.obj;
+                r.reach2 = no_bound ? __builtin_huge_val() : rr * rr * (1.0 + 1e-9);
                 r.mask = open;
                 r.idx = win.idx;
                 r.n = n;
-                fb_rec[atomicAdd(fb_count, 1u)] = r;
+                r.j = j;
+                s_open[atomicAdd(&s_nopen, 1u)] = r;
             } else {
                 int pick = win.idx;
                 if (o_prev <= win.obj || pick == 0x7fffffff) pick = prev;
@@ -703,44 +916,21 @@ __global__ __launch_bounds__(kBlock) void k_rerank(
                 }
                 atomicAdd(&s_cnt[0], 1u);
             }
-            atomicAdd(&s_cnt[2], 16u * (1u + extra) + 1u);
+            atomicAdd(&s_cnt[2], 16u * kU * (1u + extra) + 1u);
         }
     }
     __syncthreads();
-    // per-block totals; the last kernel of the call adds them up (no same-address atomics here)
-    if (threadIdx.x < 3) block_counts[3 * blockIdx.x + threadIdx.x] = s_cnt[threadIdx.x];
-}
 
-// One block per undecided group: every codeword of the group's open partitions is evaluated
-// exactly (thread = one codeword position q of 16 tile slots per pass), the lexicographic
-// minimum joins the candidate the re-rank kernel found, and the usual rule decides: the
-// previous code on an exact tie, else the lowest index.  Partition p = (codeword split,
-// half wave, tile residue) as the scoring kernel numbers them.  As the last kernel of a call
-// it also clears the filter's codebook statistics and adds up the re-rank counters.
-template <int G>
-__global__ __launch_bounds__(kBlock) void k_partition_scan(
-    const float *__restrict__ T, const float *__restrict__ codebook,
-    const float *__restrict__ scales, const fb_rec_t *__restrict__ fb_rec,
-    const unsigned *__restrict__ fb_count, uint16_t *__restrict__ codes, int ntiles, int nsplit,
-    int per_half, int gpr, int nbits, unsigned long long *__restrict__ num_changed,
-    unsigned long long *__restrict__ stats, unsigned *__restrict__ reset_meta,
-    const unsigned *__restrict__ rr_counts, int rr_blocks)
-{
-    __shared__ double s_obj[kBlock / 64];
-    __shared__ int s_idx[kBlock / 64];
-    const unsigned count = *fb_count;
-    const int csize = 1 << nbits;
-    const int q = threadIdx.x & 15, slot = threadIdx.x >> 4;
-    constexpr int kSlots = kBlock / 16;
-    const int stride = per_half == 1 ? 1 : kResidues;     // merged records cover every residue
-    unsigned changed = 0;
-    for (unsigned item = blockIdx.x; item < count; item += gridDim.x) {
-        const fb_rec_t rec = fb_rec[item];
-        const int n = rec.n;
-        const float s = scales[n / gpr];
+    // ---- groups left open: every position of their open partitions, by the whole block.
+    // Partition p = (codeword split, half wave, residue class) as the scoring kernel numbers them.
+    const unsigned nopen = s_nopen;
+    for (unsigned item = 0; item < nopen; ++item) {
+        const open_rec_t rec = s_open[item];
+        const int n2 = rec.n;
+        const float s = scales[n2 / gpr];
         float t[G];
         {
-            const pv_f4 *t4 = reinterpret_cast<const pv_f4 *>(T + (int64_t)n * G);
+            const pv_f4 *t4 = reinterpret_cast<const pv_f4 *>(T + (int64_t)n2 * G);
 #pragma unroll
             for (int v4 = 0; v4 < G / 4; ++v4) {
                 pv_f4 v = t4[v4];
@@ -750,7 +940,20 @@ __global__ __launch_bounds__(kBlock) void k_partition_scan(
                 t[v4 * 4 + 3] = v.w;
             }
         }
-        const int prev = codes[n] & (csize - 1);
+        const int prev = codes[n2] & (csize - 1);
+        const int qq = threadIdx.x & 15, slot = threadIdx.x >> 4;
+        // the group's fp16 operand as the matrix cores saw it
+        float xh[G];
+        {
+            const int gt = rec.j >> 5, col = rec.j & 31;
+#pragma unroll
+            for (int h = 0; h < G / 8; ++h) {
+                const h8 v = X[((int64_t)gt * 2 + h) * 32 + col];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) xh[h * 8 + e] = (float)v[e];
+            }
+        }
+        const bool test = rec.reach2 < 1.0e300;
         cand_t mine;
         mine.obj = __builtin_huge_val();
         mine.idx = 0x7fffffff;
@@ -758,30 +961,41 @@ __global__ __launch_bounds__(kBlock) void k_partition_scan(
             const int p = __ffsll((long long)left) - 1;
             const int hw = (p / per_half) & 1;
             const int split = p / (2 * per_half);
-            const int t_begin = (int)((int64_t)split * ntiles / nsplit);
-            const int t_end = (int)((int64_t)(split + 1) * ntiles / nsplit);
-            const int first = t_begin + (per_half == 1 ? 0 : p % per_half);
-            // kAhead codewords per thread in flight (their loads first, then the arithmetic in
-            // ascending codeword order)
-            constexpr int kAhead = G <= 8 ? 4 : 2;
-            const int step = kSlots * stride;
-            for (int tile = first + slot * stride; tile < t_end; tile += step * kAhead) {
-                pv_f4 c[kAhead][G / 4];
+            const int su_begin = (int)((int64_t)split * ncyc / nsplit) * kResidues;
+            const int su_end = (int)((int64_t)(split + 1) * ncyc / nsplit) * kResidues;
+            // the classes of the record: p % per_half, + per_half, ... (relative to the split's start)
+            for (int rel = (p % per_half) + slot * per_half; su_begin + rel < su_end; rel += kTeams * per_half) {
+                const int su = su_begin + rel;
+                h8 a[kU][G / 8];
 #pragma unroll
-                for (int u = 0; u < kAhead; ++u) {
-                    const int tu = tile + u * step < t_end ? tile + u * step : tile;
-                    const pv_f4 *c4 = reinterpret_cast<const pv_f4 *>(
-                        codebook + (int64_t)(tu * 32 + hw * 16 + q) * G);
+                for (int uu = 0; uu < kU; ++uu) {   // the loads first, then the arithmetic
+                    const int row = 8 * (qq >> 2) + 4 * hw + (qq & 3);
 #pragma unroll
-                    for (int v4 = 0; v4 < G / 4; ++v4) c[u][v4] = c4[v4];
+                    for (int h = 0; h < G / 8; ++h) a[uu][h] = A[((int64_t)(su * kU + uu) * 2 + h) * 32 + row];
                 }
 #pragma unroll
-                for (int u = 0; u < kAhead; ++u) {
-                    if (tile + u * step < t_end) {
-                        const int cw = (tile + u * step) * 32 + hw * 16 + q;
-                        const double o = exact_obj_v<G>(c[u], s, t);
-                        if (cand_better(o, cw, mine.obj, mine.idx)) {
-                            mine.obj = o;
+                for (int uu = 0; uu < kU; ++uu) {
+                    const int pos = ((su * 2 + hw) * kU + uu) * 16 + qq;
+                    if (pos >= csize) continue;
+                    bool take = true;
+                    if (test) {
+                        // || c_hi - x_hi ||^2: the operand holds 2 c_hi; differences and squares of
+                        // fp16 values are exact in double
+                        double dd = 0.0;
+#pragma unroll
+                        for (int h = 0; h < G / 8; ++h)
+#pragma unroll
+                            for (int e = 0; e < 8; ++e) {
+                                const double d = 0.5 * (double)(float)a[uu][h][e] - (double)xh[h * 8 + e];
+                                dd = fma(d, d, dd);
+                            }
+                        take = !(dd > rec.reach2);
+                    }
+                    if (take) {
+                        const int cw = G == 8 ? pos : (int)perm[pos];
+                        const double obj = exact_obj<G>(codebook + (int64_t)cw * G, s, t);
+                        if (cand_better(obj, cw, mine.obj, mine.idx)) {
+                            mine.obj = obj;
                             mine.idx = cw;
                         }
                     }
@@ -817,43 +1031,26 @@ __global__ __launch_bounds__(kBlock) void k_partition_scan(
             int pick = win.idx;
             if (o_prev <= win.obj || pick == 0x7fffffff) pick = prev;
             if (pick != prev) {
-                codes[n] = (uint16_t)pick;
-                ++changed;
+                codes[n2] = (uint16_t)pick;
+                s_cnt[1] += 1u;
             }
+            s_cnt[3] += 1u;
         }
     }
-    if (threadIdx.x == 0 && changed && num_changed) atomicAdd(num_changed, (unsigned long long)changed);
-    if (blockIdx.x == 0 && threadIdx.x == 0 && count) atomicAdd(&stats[1], (unsigned long long)count);
-    // the filter's codebook statistics are dead once this (last) kernel of a call runs
-    if (blockIdx.x == 0 && threadIdx.x < 8) reset_meta[threadIdx.x] = 0u;
-    // fold the re-rank kernel's per-block counters (decided, changed, candidates) into the totals
-    if (blockIdx.x == gridDim.x - 1) {
-        unsigned long long c0 = 0, c1 = 0, c2 = 0;
-        constexpr int kU = 4;            // independent loads in flight per thread
-        for (int b0 = threadIdx.x; b0 < rr_blocks; b0 += kBlock * kU) {
-            unsigned v[kU][3];
-#pragma unroll
-            for (int u = 0; u < kU; ++u) {
-                const int b = b0 + u * kBlock;
-#pragma unroll
-                for (int e = 0; e < 3; ++e) v[u][e] = b < rr_blocks ? rr_counts[3 * b + e] : 0u;
-            }
-#pragma unroll
-            for (int u = 0; u < kU; ++u) {
-                c0 += v[u][0];
-                c1 += v[u][1];
-                c2 += v[u][2];
-            }
-        }
-        for (int off = 32; off > 0; off >>= 1) {
-            c0 += __shfl_down(c0, off);
-            c1 += __shfl_down(c1, off);
-            c2 += __shfl_down(c2, off);
-        }
-        if ((threadIdx.x & 63) == 0) {
-            if (c0) atomicAdd(&stats[0], c0);
-            if (c2) atomicAdd(&stats[2], c2);
-            if (c1 && num_changed) atomicAdd(num_changed, c1);
+    __syncthreads();
+    // per-block totals: groups decided by the teams, codes changed, candidates evaluated, groups scanned
+    if (threadIdx.x < 4) block_counts[4 * blockIdx.x + threadIdx.x] = s_cnt[threadIdx.x];
+    // *num_changed: thousands of atomics on one address would queue for longer than the kernel
+    // runs, so 64 blocks share a slot that carries (arrivals << 40 | sum); the block that finds
+    // all others arrived passes the sum on
+    if (threadIdx.x == 0 && num_changed) {
+        const unsigned first = (blockIdx.x >> 6) << 6;
+        const unsigned members = gridDim.x - first < 64u ? gridDim.x - first : 64u;
+        const unsigned long long old =
+            atomicAdd(&change_slots[blockIdx.x >> 6], (1ull << 40) | (unsigned long long)s_cnt[1]);
+        if ((unsigned)(old >> 40) == members - 1u) {
+            const unsigned long long total = (old & ((1ull << 40) - 1ull)) + s_cnt[1];
+            if (total) atomicAdd(num_changed, total);
         }
     }
 }
@@ -865,14 +1062,17 @@ __global__ void k_fill_u32(unsigned *p, int n, unsigned v)
 }
 
 struct plan_t {
-    int NK, NB, k_pad, gblocks, nsplit, P, per_half, merge, ntiles;
+    int NB, k_pad, gblocks, nsplit, P, per_half, ntiles, ncyc, nsu, cpad;
 };
 
 plan_t make_plan(const pv_layout *l, int64_t k)
 {
     plan_t p;
-    p.NK = l->group_size / 8;
     p.ntiles = (1 << l->nbits) / 32;
+    constexpr int cycle = kResidues * kU;    // tiles per residue cycle
+    p.ncyc = (p.ntiles + cycle - 1) / cycle; // whole cycles: the table is padded with zero rows
+    p.nsu = p.ncyc * kResidues;
+    p.cpad = p.nsu * kU * 32;
     p.NB = k >= 4096 ? PV_NBX : 1;
     const int per_block = PV_WAVES * p.NB * 32;
     p.gblocks = (int)((k + per_block - 1) / per_block);
@@ -885,15 +1085,17 @@ plan_t make_plan(const pv_layout *l, int64_t k)
     int want = slots / p.gblocks;
     if (want < 4) want = (4 * slots + p.gblocks - 1) / p.gblocks;
     if (want > 8 && slots / p.gblocks < 4) want = 8;
-    int max_split = p.ntiles / 8;
+    int max_split = p.nsu * kU / 8;
+    if (max_split > p.ncyc) max_split = p.ncyc;
     if (max_split < 1) max_split = 1;
     if (want > max_split) want = max_split;
     if (want > 32) want = 32;
     if (want < 1) want = 1;
     p.nsplit = want;
-    // keep all residue classes apart while the record count per group stays small
-    p.merge = (p.nsplit * 2 * kResidues > 32) ? 1 : 0;
-    p.per_half = p.merge ? 1 : kResidues;
+    // as many residue classes apart as 64 records per group allow: the more partitions, the
+    // fewer groups have two keys above the cut in one of them
+    p.per_half = kResidues;
+    while (p.per_half > 1 && p.nsplit * 2 * p.per_half > 64) p.per_half >>= 1;
     p.P = p.nsplit * 2 * p.per_half;
     return p;
 }
@@ -955,61 +1157,85 @@ pv_status pv_launch_mfma_search(pv_ctx *ctx, const pv_layout *l, const float *T,
     const int csize = 1 << l->nbits;
     const int gpr = (int)(l->in_features / g);
     const int N = (int)pv_num_groups(l);
+    const int nsu_alloc = 2 * p.nsu + 64;    // two norms per super-unit; the scoring kernel stages 64 at a time
     pv_status st;
-    if ((st = pv_ensure(ctx, ctx->cb_f16, (size_t)csize * p.NK * 32)) != PV_OK) return st;
-    if ((st = pv_ensure(ctx, ctx->cb_meta, 8 * sizeof(unsigned), /*zero_new=*/true)) != PV_OK) return st;
-    if ((st = pv_ensure(ctx, ctx->x_f16, (size_t)p.k_pad * p.NK * 32)) != PV_OK) return st;
+    // codebook operand, then: position -> codeword, norm buckets, bucket counts / offsets,
+    // smallest norm per super-unit
+    const size_t a_bytes = (size_t)p.cpad * 32;
+    const size_t perm_off = a_bytes, bucket_off = perm_off + (size_t)p.cpad * 2;
+    const size_t hist_off = (bucket_off + (size_t)csize * 2 + 255) & ~(size_t)255;
+    const size_t nmin_off = hist_off + (size_t)kNormBins * 4;
+    if ((st = pv_ensure(ctx, ctx->cb_f16, nmin_off + (size_t)nsu_alloc * 4)) != PV_OK) return st;
+    if ((st = pv_ensure(ctx, ctx->cb_meta, 16 * sizeof(unsigned), /*zero_new=*/true)) != PV_OK) return st;
+    if ((st = pv_ensure(ctx, ctx->x_f16, (size_t)p.k_pad * 32)) != PV_OK) return st;
     if ((st = pv_ensure(ctx, ctx->x_meta, (size_t)p.k_pad * 4 * sizeof(float))) != PV_OK) return st;
-    if ((st = pv_ensure(ctx, ctx->partials, (size_t)p.k_pad * p.P * sizeof(uint2))) != PV_OK) return st;
-    if ((st = pv_ensure(ctx, ctx->fb_list, 4 * sizeof(int32_t) + (size_t)k * sizeof(fb_rec_t) + 64)) != PV_OK)
-        return st;
+    if ((st = pv_ensure(ctx, ctx->partials, (size_t)p.k_pad * p.P * sizeof(int2))) != PV_OK) return st;
+    if ((st = pv_ensure(ctx, ctx->fb_list, 64)) != PV_OK) return st;
     const int rr_blocks = (int)((k * 16 + kBlock - 1) / kBlock);
-    if ((st = pv_ensure(ctx, ctx->rr_counts, (size_t)rr_blocks * 3 * sizeof(unsigned))) != PV_OK) return st;
+    const int nslots = (rr_blocks + 63) / 64;
+    if ((st = pv_ensure(ctx, ctx->rr_counts, (size_t)rr_blocks * 4 * sizeof(unsigned) + (size_t)nslots * 8 + 16)) != PV_OK)
+        return st;
     unsigned *rr_counts = static_cast<unsigned *>(ctx->rr_counts.ptr);
-    h8 *A = static_cast<h8 *>(ctx->cb_f16.ptr);
+    unsigned long long *change_slots = reinterpret_cast<unsigned long long *>(
+        static_cast<char *>(ctx->rr_counts.ptr) + (((size_t)rr_blocks * 4 * sizeof(unsigned) + 7) & ~(size_t)7));
+    char *cbase = static_cast<char *>(ctx->cb_f16.ptr);
+    h8 *A = reinterpret_cast<h8 *>(cbase);
+    uint16_t *perm = reinterpret_cast<uint16_t *>(cbase + perm_off);
+    uint16_t *bucket = reinterpret_cast<uint16_t *>(cbase + bucket_off);
+    unsigned *hist = reinterpret_cast<unsigned *>(cbase + hist_off);
+    unsigned *nmin_bits = reinterpret_cast<unsigned *>(cbase + nmin_off);
     h8 *X = static_cast<h8 *>(ctx->x_f16.ptr);
     unsigned *cb_meta = static_cast<unsigned *>(ctx->cb_meta.ptr);
     float *x_meta = static_cast<float *>(ctx->x_meta.ptr);
-    uint2 *partials = static_cast<uint2 *>(ctx->partials.ptr);
-    unsigned *fb_count = reinterpret_cast<unsigned *>(ctx->fb_list.ptr);       // 4 counters, then the records
-    fb_rec_t *fb_rec = reinterpret_cast<fb_rec_t *>(static_cast<char *>(ctx->fb_list.ptr) + 16);
+    int2 *partials = static_cast<int2 *>(ctx->partials.ptr);
+    unsigned *fb_count = reinterpret_cast<unsigned *>(ctx->fb_list.ptr);       // 4 counters
     unsigned long long *stats = static_cast<unsigned long long *>(ctx->stats.ptr);
+    auto nc = reinterpret_cast<unsigned long long *>(num_changed);
     hipStream_t sm = ctx->stream;
-    if (ctx->meta_dirty) {   // a previous call did not run to its last kernel
-        hipLaunchKernelGGL(k_fill_u32, dim3(1), dim3(64), 0, sm, cb_meta, 8, 0u);
-    }
-    ctx->meta_dirty = true;
+    // two statistics slots, used alternately (the first kernel of a call clears the other one)
+    unsigned *cb_meta_next = cb_meta + (ctx->meta_phase ? 0 : 8);
+    cb_meta += ctx->meta_phase ? 8 : 0;
+    ctx->meta_phase ^= 1;
+    ctx->rr_blocks_last = rr_blocks;
     {
         pv_timed t(ctx, PV_K_PREP);
-        const int64_t ncb = (int64_t)csize * g;
-        int blocks = (int)((ncb / 4 + kBlock * 4 - 1) / (kBlock * 4));
+        int blocks = (csize + kBlock - 1) / kBlock;
         if (blocks > 128) blocks = 128;
-        hipLaunchKernelGGL(k_cb_absmax, dim3(blocks), dim3(kBlock), 0, sm, codebooks, ncb, cb_meta,
-                           stats, fb_count, reinterpret_cast<unsigned long long *>(num_changed));
-        const int cb_blocks = (csize + kBlock - 1) / kBlock;
+        const int cb_blocks = (p.cpad + kBlock - 1) / kBlock;
         const int x_blocks = (p.k_pad + kBlock - 1) / kBlock;
-        if (g == 8)
+        if (g == 8) {
+            hipLaunchKernelGGL(k_cb_stats<8>, dim3(blocks), dim3(kBlock), 0, sm, codebooks, csize,
+                               cb_meta, cb_meta_next, stats, fb_count, nc, (unsigned *)nullptr,
+                               (unsigned *)nullptr, 0, change_slots, nslots);
             hipLaunchKernelGGL(k_prep<8>, dim3(cb_blocks + x_blocks), dim3(kBlock), 0, sm, codebooks,
-                               csize, cb_blocks, cb_meta, A, T, scales, group_idx, (int)k, p.k_pad,
-                               gpr, N, X, x_meta);
-        else
+                               csize, p.cpad, cb_blocks, cb_meta, A, perm, bucket, hist, nmin_bits, T,
+                               scales, group_idx, (int)k, p.k_pad, gpr, N, X, x_meta);
+        } else {
+            hipLaunchKernelGGL(k_cb_stats<16>, dim3(blocks), dim3(kBlock), 0, sm, codebooks, csize,
+                               cb_meta, cb_meta_next, stats, fb_count, nc, hist, nmin_bits, nsu_alloc,
+                               change_slots, nslots);
+            hipLaunchKernelGGL(k_cb_bucket<16>, dim3((csize + kBlock - 1) / kBlock), dim3(kBlock), 0,
+                               sm, codebooks, csize, cb_meta, bucket, hist);
+            hipLaunchKernelGGL(k_cb_scan, dim3(1), dim3(1024), 0, sm, hist);
             hipLaunchKernelGGL(k_prep<16>, dim3(cb_blocks + x_blocks), dim3(kBlock), 0, sm,
-                               codebooks, csize, cb_blocks, cb_meta, A, T, scales, group_idx, (int)k,
-                               p.k_pad, gpr, N, X, x_meta);
+                               codebooks, csize, p.cpad, cb_blocks, cb_meta, A, perm, bucket, hist,
+                               nmin_bits, T, scales, group_idx, (int)k, p.k_pad, gpr, N, X, x_meta);
+        }
     }
     {
         pv_timed t(ctx, PV_K_SCORE_MFMA);
         const int items = p.gblocks * p.nsplit;
         dim3 grid(items < 256 * PV_OCC ? items : 256 * PV_OCC);
-#define PV_SCORE(NK_, NB_)                                                                     \
-    hipLaunchKernelGGL((k_score_mfma<NK_, NB_>), grid, dim3(PV_WAVES * 64), 0, sm, A, X, partials,    \
-                       p.ntiles, p.nsplit, p.P, p.merge, p.gblocks, fb_count + 1)
-        if (p.NK == 1) {
-            if (p.NB == PV_NBX) PV_SCORE(1, PV_NBX);
-            else PV_SCORE(1, 1);
+        const float *nmin = reinterpret_cast<const float *>(nmin_bits);
+#define PV_SCORE(G_, NB_)                                                                          \
+    hipLaunchKernelGGL((k_score_mfma<G_, NB_>), grid, dim3(PV_WAVES * 64), 0, sm, A, X, x_meta, nmin, \
+                       partials, p.ncyc, p.nsplit, p.per_half, p.gblocks, p.k_pad, fb_count + 1)
+        if (g == 8) {
+            if (p.NB == PV_NBX) PV_SCORE(8, PV_NBX);
+            else PV_SCORE(8, 1);
         } else {
-            if (p.NB == PV_NBX) PV_SCORE(2, PV_NBX);
-            else PV_SCORE(2, 1);
+            if (p.NB == PV_NBX) PV_SCORE(16, PV_NBX);
+            else PV_SCORE(16, 1);
         }
 #undef PV_SCORE
     }
@@ -1018,27 +1244,13 @@ pv_status pv_launch_mfma_search(pv_ctx *ctx, const pv_layout *l, const float *T,
         const dim3 rgrid((unsigned)rr_blocks);
         if (g == 8)
             hipLaunchKernelGGL(k_rerank<8>, rgrid, dim3(kBlock), 0, sm, T, codebooks, scales,
-                               group_idx, (int)k, partials, p.P, p.per_half, x_meta, cb_meta, codes,
-                               rr_counts, fb_rec, fb_count, gpr, N, l->nbits);
+                               group_idx, (int)k, p.k_pad, partials, p.P, p.per_half, p.ncyc, p.nsplit,
+                               x_meta, cb_meta, A, X, perm, codes, rr_counts, change_slots, nc, gpr, N, l->nbits);
         else
             hipLaunchKernelGGL(k_rerank<16>, rgrid, dim3(kBlock), 0, sm, T, codebooks, scales,
-                               group_idx, (int)k, partials, p.P, p.per_half, x_meta, cb_meta, codes,
-                               rr_counts, fb_rec, fb_count, gpr, N, l->nbits);
-    }
-    {
-        pv_timed t(ctx, PV_K_EXACT_SCAN);
-        const unsigned sblocks = (unsigned)(k < 2048 ? k : 2048);
-        auto nc = reinterpret_cast<unsigned long long *>(num_changed);
-        if (g == 8)
-            hipLaunchKernelGGL(k_partition_scan<8>, dim3(sblocks), dim3(kBlock), 0, sm, T, codebooks,
-                               scales, fb_rec, fb_count, codes, p.ntiles, p.nsplit, p.per_half, gpr,
-                               l->nbits, nc, stats, cb_meta, rr_counts, rr_blocks);
-        else
-            hipLaunchKernelGGL(k_partition_scan<16>, dim3(sblocks), dim3(kBlock), 0, sm, T, codebooks,
-                               scales, fb_rec, fb_count, codes, p.ntiles, p.nsplit, p.per_half, gpr,
-                               l->nbits, nc, stats, cb_meta, rr_counts, rr_blocks);
+                               group_idx, (int)k, p.k_pad, partials, p.P, p.per_half, p.ncyc, p.nsplit,
+                               x_meta, cb_meta, A, X, perm, codes, rr_counts, change_slots, nc, gpr, N, l->nbits);
     }
     PV_HIP(ctx, hipGetLastError());
-    ctx->meta_dirty = false;
     return PV_OK;
 }
