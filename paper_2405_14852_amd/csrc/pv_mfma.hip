@@ -56,6 +56,9 @@
 #ifndef PV_SUPER
 #define PV_SUPER 2    // codeword tiles behind one key (a super-unit)
 #endif
+#ifndef PV_TEAM
+#define PV_TEAM 8     // lanes of the re-rank kernel that share one group
+#endif
 #ifndef PV_DEPTH
 #define PV_DEPTH 2    // units (matrix instructions) in flight before a unit's accumulators are reduced
 #endif
@@ -114,6 +117,21 @@ __device__ __forceinline__ int norm_bucket(float n2)
     const int top = (int)(0x47000000u >> 12);      // bits of 32768.0f
     const int key = e - (top - (kNormBins - 1));
     return key < 0 ? 0 : (key > kNormBins - 1 ? kNormBins - 1 : key);
+}
+
+// Residue cycles of the table owned by codeword split `split` of `nsplit`: cycles are dealt to
+// the splits round robin by rank (for g = 16 the rank is the norm order, so every split sees
+// every norm band: codewords near a target have similar norms, and they should fall into
+// different partitions), and a split's cycles lie next to each other in memory.
+__device__ __host__ __forceinline__ int split_count(int split, int ncyc, int nsplit)
+{
+    return (ncyc - split + nsplit - 1) / nsplit;
+}
+__device__ __host__ __forceinline__ int split_begin(int split, int ncyc, int nsplit)
+{
+    // sum of split_count over the splits before: the first ncyc % nsplit splits hold one more
+    const int q = ncyc / nsplit, r = ncyc % nsplit;
+    return split * q + (split < r ? split : r);
 }
 
 // fp16 copy of one scaled codeword: c_hi (as floats), its squared norm, the squared rounding error
@@ -265,8 +283,9 @@ __global__ __launch_bounds__(1024) void k_cb_scan(unsigned *__restrict__ hist)
 // Operand preparation, one launch for both sides.
 //
 // Blocks [0, cb_blocks): one thread per codeword position of the padded table.  A codeword is
-// placed at position pos (g = 8: its own index; g = 16: the next free slot of its norm bucket,
-// so positions ascend in ||c_hi||^2 up to the bucket width), perm[pos] names it.  The 32 U
+// placed at position pos (g = 8: its own index; g = 16: the next free rank of its norm bucket,
+// ranks ascending in ||c_hi||^2 up to the bucket width, and the residue cycles of the ranking
+// dealt round robin to the codeword splits), perm[pos] names it.  The 32 U
 // positions of super-unit su are split in two runs of 16 U, one per half wave hw, each run in
 // U pieces of 16, one per tile: position pos = ((su * 2 + hw) * U + uu) * 16 + q sits in tile
 // su * U + uu at row 8*(q/4) + 4*hw + q%4, so that accumulator q of half wave hw is that
@@ -282,6 +301,9 @@ __global__ __launch_bounds__(1024) void k_cb_scan(unsigned *__restrict__ hist)
 // X[(gt * 2 + h) * 32 + col]:
 //   g = 8:  k-half 0 = x_hi, k-half 1 = { -1, -1, -1, three pieces of SHIFT, 0, 0 }
 //   g = 16: the two halves of x_hi (SHIFT travels in x_meta)
+// and x_stage[j] = { the g target values, the row scale, the current code, the group id } is
+// what the re-rank kernel needs of the group, in one place (its loads then depend on nothing
+// but the list position).
 template <int G>
 __global__ __launch_bounds__(kBlock) void k_prep(const float *__restrict__ cb, int csize, int cpad,
                                                  int cb_blocks, unsigned *__restrict__ meta,
@@ -293,7 +315,9 @@ __global__ __launch_bounds__(kBlock) void k_prep(const float *__restrict__ cb, i
                                                  const float *__restrict__ scales,
                                                  const int32_t *__restrict__ group_idx, int k,
                                                  int k_pad, int gpr, int N, h8 *__restrict__ X,
-                                                 float *__restrict__ x_meta)
+                                                 float *__restrict__ x_meta,
+                                                 const uint16_t *__restrict__ codes, int csize_mask,
+                                                 float *__restrict__ x_stage, int ncyc, int nsplit)
 {
     bool ok;
     const float P = scale_from_maxabs(meta[0], &ok);
@@ -323,7 +347,12 @@ __global__ __launch_bounds__(kBlock) void k_prep(const float *__restrict__ cb, i
                     chunk[1][4] = (_Float16)1.0f;
                     chunk[1][5] = (_Float16)1.0f;
                 } else {
-                    pos = (int)atomicAdd(&bucket_next[bucket[c]], 1u);
+                    // rank in norm order -> place in memory: cycle rc of the ranking is cycle
+                    // rc / nsplit of split rc % nsplit
+                    const int rank = (int)atomicAdd(&bucket_next[bucket[c]], 1u);
+                    constexpr int per_cycle = 32 * kU * kResidues;
+                    const int rc = rank / per_cycle;
+                    pos = (split_begin(rc % nsplit, ncyc, nsplit) + rc / nsplit) * per_cycle + rank % per_cycle;
                     atomicMin(&nmin_bits[pos / (16 * kU)], __float_as_uint(n2));
                 }
                 perm[pos] = (uint16_t)c;
@@ -354,8 +383,24 @@ __global__ __launch_bounds__(kBlock) void k_prep(const float *__restrict__ cb, i
     // ||c_hi|| <= P max_c ||c|| + rounding
     const float cmax = P * sqrtf(__uint_as_float(meta[5])) * 1.0001f + kNormMargin;
     float shift = 0.0f, xx = 0.0f, e1 = 0.0f, dx = -1.0f;
-    const int n = j < k ? group_idx[j] : -1;
-    if (n >= 0 && n < N && ok) {
+    int n = j < k ? group_idx[j] : -1;
+    if (n >= N) n = -1;
+    pv_f4 *stage = reinterpret_cast<pv_f4 *>(x_stage + (int64_t)j * (G + 4));
+    {
+        pv_f4 tail = {0.0f, 0.0f, 0.0f, 0.0f};
+        if (n >= 0) {
+            tail.x = scales[n / gpr];
+            tail.y = __int_as_float((int)codes[n] & csize_mask);
+        }
+        tail.z = __int_as_float(n);
+        stage[G / 4] = tail;
+    }
+    if (n >= 0) {
+        const pv_f4 *src = reinterpret_cast<const pv_f4 *>(T + (int64_t)n * G);
+#pragma unroll
+        for (int v4 = 0; v4 < G / 4; ++v4) stage[v4] = src[v4];
+    }
+    if (n >= 0 && ok) {
         const float s = scales[n / gpr];
         bool fits = (s != 0.0f) && (fabsf(s) < 3.0e38f);
         const float div = fits ? s : 1.0f;
@@ -475,6 +520,18 @@ __device__ __forceinline__ int acc_max(const f16v &acc, int run)
     return imax3(m, __float_as_int(acc[14]), __float_as_int(acc[15]));
 }
 
+// place of the record of (partition p, list position j)
+__device__ __forceinline__ int64_t rec_at(int p, int64_t j, int P, int k_pad)
+{
+#ifdef PV_REC_BY_GROUP
+    (void)k_pad;
+    return j * P + p;
+#else
+    (void)P;
+    return (int64_t)p * k_pad + j;
+#endif
+}
+
 // The distance contraction.  Block = PV_WAVES waves; wave w owns NB group tiles (32 groups
 // each) whose B operands stay in registers; the block streams the codeword tiles of its split
 // through a double-buffered LDS stage shared by its waves.  A stage is filled with direct
@@ -515,8 +572,8 @@ __global__ __launch_bounds__(PV_WAVES * 64, (PV_OCC * PV_WAVES) / 4) void k_scor
     const int gb = (int)(item % (unsigned)gblocks), split = (int)(item / (unsigned)gblocks);
     const int gtile0 = (gb * kW + wave) * NB;
     // a split is a whole number of residue cycles (the table is padded to one)
-    const int t_begin = (int)((int64_t)split * ncyc / nsplit) * kCycle;
-    const int t_end = (int)((int64_t)(split + 1) * ncyc / nsplit) * kCycle;
+    const int t_begin = split_begin(split, ncyc, nsplit) * kCycle;
+    const int t_end = t_begin + split_count(split, ncyc, nsplit) * kCycle;
 
     h8 b[NB];
 #pragma unroll
@@ -650,18 +707,18 @@ __global__ __launch_bounds__(PV_WAVES * 64, (PV_OCC * PV_WAVES) / 4) void k_scor
             int b1 = best[nb][0], b2 = second[nb][0];
 #pragma unroll
             for (int r = 1; r < kResidues; ++r) join(b1, b2, best[nb][r], second[nb][r]);
-            partials[(int64_t)(split * 2 + hw) * k_pad + jpos] = make_int2(b1, b2);
+            partials[rec_at(split * 2 + hw, jpos, nsplit * 2, k_pad)] = make_int2(b1, b2);
         } else if (per_half == 2) {   // classes r and r + 2 share a record
 #pragma unroll
             for (int r = 0; r < 2; ++r) {
                 int b1 = best[nb][r], b2 = second[nb][r];
                 join(b1, b2, best[nb][r + 2], second[nb][r + 2]);
-                partials[(int64_t)((split * 2 + hw) * 2 + r) * k_pad + jpos] = make_int2(b1, b2);
+                partials[rec_at((split * 2 + hw) * 2 + r, jpos, nsplit * 4, k_pad)] = make_int2(b1, b2);
             }
         } else {
 #pragma unroll
             for (int r = 0; r < kResidues; ++r)
-                partials[(int64_t)((split * 2 + hw) * kResidues + r) * k_pad + jpos] =
+                partials[rec_at((split * 2 + hw) * kResidues + r, jpos, nsplit * 2 * kResidues, k_pad)] =
                     make_int2(best[nb][r], second[nb][r]);
         }
     }
@@ -712,56 +769,81 @@ __device__ __forceinline__ float key_upper(int key)
     return key < 0 ? 0.0f : __int_as_float(key | (int)kKeyMask);
 }
 
+// || c_hi - x_hi ||^2 of one table position from the operand row the matrix cores saw (it holds
+// 2 c_hi as fp16), in fp32: every term is non-negative, so the result lies within
+// (G + 2) 2^-24 of the exact value, relatively.  kDdSlack covers that with room to spare.
+constexpr float kDdSlack = 4.0e-6f;
+template <int G>
+__device__ __forceinline__ float approx_dd(const h8 *__restrict__ A, int tile, int row, const float (&xh)[G])
+{
+    float dd = 0.0f;
+#pragma unroll
+    for (int h = 0; h < G / 8; ++h) {
+        const h8 a = A[((int64_t)tile * 2 + h) * 32 + row];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float d = 0.5f * (float)a[e] - xh[h * 8 + e];
+            dd = fmaf(d, d, dd);
+        }
+    }
+    return dd;
+}
+
 // A group the team could not decide alone: the partitions whose codewords must all be
 // evaluated (bit p = partition p), and the best candidate found so far.
 struct open_rec_t {
     double obj;
-    double reach2;             // a codeword can reach obj only if ||c_hi - x_hi||^2 <= reach2
+    float reach2;              // a codeword can reach obj only if ||c_hi - x_hi||^2 <= reach2
     unsigned long long mask;
     int idx;
     int n;
     int j;                     // position in the list (names the group's fp16 operand)
 };
 
-// 16 lanes ("team") per selected group; lane q scores position q of a half tile.  Groups
+// A team of kTeam lanes per selected group; a lane scores 16 / kTeam positions of each half tile
+// behind a key.  Groups
 // with a partition left open are finished by the whole block afterwards, one at a time: for
-// every position of the open partitions || c_hi - x_hi ||^2 is formed exactly (in double, from
-// the fp16 operands the matrix cores saw) and the codewords that can still reach the best
-// objective found are evaluated.  Every block leaves its counters in block_counts (summed by
+// every position of the open partitions || c_hi - x_hi ||^2 is formed from the fp16 operands
+// the matrix cores saw and the codewords that can still reach the best objective found are
+// evaluated.  Every block leaves its counters in block_counts (summed by
 // whoever asks for the call's statistics) and passes its changed codes on through atomics; no
 // block waits for another and none publishes plain stores to another (a device-wide release
 // costs a write-back of the whole L2 of the block's die).
 template <int G>
 __global__ __launch_bounds__(kBlock) void k_rerank(
-    const float *__restrict__ T, const float *__restrict__ codebook,
-    const float *__restrict__ scales, const int32_t *__restrict__ group_idx, int k, int k_pad,
+    const float *__restrict__ x_stage, const float *__restrict__ codebook, int k, int k_pad,
     const int2 *__restrict__ partials, int P, int per_half, int ncyc, int nsplit,
     const float *__restrict__ x_meta, const unsigned *__restrict__ cb_meta, const h8 *__restrict__ A,
     const h8 *__restrict__ X, const uint16_t *__restrict__ perm, uint16_t *__restrict__ codes,
     unsigned *__restrict__ block_counts, unsigned long long *__restrict__ change_slots,
-    unsigned long long *__restrict__ num_changed, int gpr, int N, int nbits)
+    unsigned long long *__restrict__ num_changed, int nbits)
 {
-    constexpr int kTeams = kBlock / 16;
+    constexpr int kTeam = PV_TEAM;                 // lanes per group
+    constexpr int kTeams = kBlock / kTeam;         // groups per block
+    constexpr int kPer = 16 / kTeam;               // positions of a half tile per lane
+    static_assert(kTeam == 4 || kTeam == 8 || kTeam == 16, "a team is a power of two of at most 16 lanes");
     __shared__ unsigned s_cnt[4];   // groups decided by the teams, codes changed, candidates evaluated, groups scanned
     __shared__ open_rec_t s_open[kTeams];
     __shared__ unsigned s_nopen;
-    __shared__ double s_obj[kBlock / 64];
-    __shared__ int s_idx[kBlock / 64];
     if (threadIdx.x < 4) s_cnt[threadIdx.x] = 0;
     if (threadIdx.x == 0) s_nopen = 0;
     __syncthreads();
     const int csize = 1 << nbits;
     const int gid = blockIdx.x * kBlock + threadIdx.x;
-    const int j = gid >> 4, q = gid & 15;
-    const int n = j < k ? group_idx[j] : -1;
-    bool live = n >= 0 && n < N;             // whole 16-lane teams agree on every branch below
-    pv_f4 meta = {0.f, 0.f, 0.f, -1.f};
-    if (live) meta = reinterpret_cast<const pv_f4 *>(x_meta)[j];
+    const int j = gid / kTeam, q = gid % kTeam;
+    // everything the team needs of its group sits at the list position: one round of loads
+    const bool inlist = j < k;
+    const pv_f4 *stage = reinterpret_cast<const pv_f4 *>(x_stage + (int64_t)(inlist ? j : 0) * (G + 4));
+    const pv_f4 tail = stage[G / 4];
+    pv_f4 meta = reinterpret_cast<const pv_f4 *>(x_meta)[inlist ? j : 0];
+    const int n = inlist ? __float_as_int(tail.z) : -1;
+    bool live = n >= 0;                      // whole teams agree on every branch below
+    if (!live) meta.w = -1.0f;
     if (live && meta.w < 0.0f) {             // the filter was skipped for this group: every partition
         if (q == 0) {
             open_rec_t r;
             r.obj = __builtin_huge_val();
-            r.reach2 = __builtin_huge_val();       // no operand to test against: every codeword
+            r.reach2 = __builtin_huge_valf();      // no operand to test against: every codeword
             r.mask = P >= 64 ? ~0ull : ((1ull << P) - 1ull);
             r.idx = 0x7fffffff;
             r.n = n;
@@ -771,68 +853,98 @@ __global__ __launch_bounds__(kBlock) void k_rerank(
         live = false;
     }
     if (live) {
-        const float s = scales[n / gpr];
+        const float s = tail.x;
         float t[G];
-        {
-            const pv_f4 *t4 = reinterpret_cast<const pv_f4 *>(T + (int64_t)n * G);
 #pragma unroll
-            for (int v4 = 0; v4 < G / 4; ++v4) {
-                pv_f4 v = t4[v4];
-                t[v4 * 4 + 0] = v.x;
-                t[v4 * 4 + 1] = v.y;
-                t[v4 * 4 + 2] = v.z;
-                t[v4 * 4 + 3] = v.w;
-            }
+        for (int v4 = 0; v4 < G / 4; ++v4) {
+            pv_f4 v = stage[v4];
+            t[v4 * 4 + 0] = v.x;
+            t[v4 * 4 + 1] = v.y;
+            t[v4 * 4 + 2] = v.z;
+            t[v4 * 4 + 3] = v.w;
         }
-        // the previous code and the filter's records are fetched side by side: their round
-        // trips to memory overlap
-        const int prev = codes[n] & (csize - 1);
-        constexpr int kMaxRec = 4;           // P <= 64
+        const int prev = __float_as_int(tail.y);
+        constexpr int kMaxRec = 64 / kTeam;  // P <= 64
         int2 rec[kMaxRec];
 #pragma unroll
         for (int u = 0; u < kMaxRec; ++u) {
-            int p = q + 16 * u;
-            rec[u] = p < P ? partials[(int64_t)p * k_pad + j] : make_int2(kNoKey, kNoKey);
+            int p = q + kTeam * u;
+            rec[u] = p < P ? partials[rec_at(p, j, P, k_pad)] : make_int2(kNoKey, kNoKey);
         }
         const double o_prev = exact_obj<G>(codebook + (int64_t)prev * G, s, t);
         // best key over all partitions, with its partition
         long long bk = (long long)0x8000000000000000ull;
 #pragma unroll
         for (int u = 0; u < kMaxRec; ++u) {
-            int p = q + 16 * u;
+            int p = q + kTeam * u;
             long long v = ((long long)rec[u].x << 32) | (long long)(unsigned)(63 - p);
             bk = v > bk ? v : bk;
         }
 #pragma unroll
-        for (int m = 8; m > 0; m >>= 1) {
-            long long o = __shfl_xor(bk, m, 16);
+        for (int m = kTeam / 2; m > 0; m >>= 1) {
+            long long o = __shfl_xor(bk, m, kTeam);
             bk = o > bk ? o : bk;
         }
         const int best_key = (int)(bk >> 32);
         const int best_p = 63 - (int)(bk & 0xFFFFFFFFll);
 
-        // the 16 U positions behind a key: lane q takes position q of each of the U half tiles
-        auto eval_key = [&](int key, int p, cand_t &c) {
+        // the group's fp16 operand as the matrix cores saw it
+        float xh[G];
+        {
+            const int gt = j >> 5, col = j & 31;
+#pragma unroll
+            for (int h = 0; h < G / 8; ++h) {
+                const h8 v = X[((int64_t)gt * 2 + h) * 32 + col];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) xh[h * 8 + e] = (float)v[e];
+            }
+        }
+        bool okP;
+        const float Pscale = scale_from_maxabs(cb_meta[0], &okP);
+        const float dC = sqrtf(__uint_as_float(cb_meta[2])) * 1.0001f + 1e-30f;
+        const float p_over_s = Pscale / fabsf(s);     // inf for a vanishing scale: nothing is excluded then
+        // The 16 U positions behind a key (lane q takes positions q, q + kTeam, ... of each of the
+        // U half tiles) are looked at in two levels: || c_hi - x_hi ||^2 from the fp16 operand rows (cheap,
+        // consecutive rows), and the exact objective only for positions that can still reach
+        // the best objective known: || c_hi - x_hi || <= P sqrt(E) / |s| + dC + dx.
+        constexpr int kMine = kU * kPer;               // positions of a key per lane
+        auto level1 = [&](int key, int p, float (&dd)[kMine], int (&pos)[kMine]) {
             const int su = key & (int)kKeyMask;
             const int hw = (p / per_half) & 1;
 #pragma unroll
-            for (int uu = 0; uu < kU; ++uu) {
-                const int pos = ((su * 2 + hw) * kU + uu) * 16 + q;
-                if (pos < csize) {
-                    const int cw = G == 8 ? pos : (int)perm[pos];   // g = 8: positions are codewords
-                    double o = exact_obj<G>(codebook + (int64_t)cw * G, s, t);
-                    if (cand_better(o, cw, c.obj, c.idx)) {
-                        c.obj = o;
-                        c.idx = cw;
-                    }
+            for (int uu = 0; uu < kU; ++uu)
+#pragma unroll
+                for (int e = 0; e < kPer; ++e) {
+                    const int qq = q + kTeam * e;
+                    const int row = 8 * (qq >> 2) + 4 * hw + (qq & 3);
+                    pos[uu * kPer + e] = ((su * 2 + hw) * kU + uu) * 16 + qq;
+                    // unconditional (the padded table has the row), so that the loads of all the
+                    // lane's positions are in flight together
+                    dd[uu * kPer + e] = approx_dd<G>(A, su * kU + uu, row, xh);
                 }
+#pragma unroll
+            for (int i = 0; i < kMine; ++i)
+                if (pos[i] >= csize) dd[i] = __builtin_huge_valf();
+        };
+        auto exact_at = [&](int pos, cand_t &c) {
+            const int cw = G == 8 ? pos : (int)perm[pos];   // g = 8: positions are codewords
+            const double o = exact_obj<G>(codebook + (int64_t)cw * G, s, t);
+            if (cand_better(o, cw, c.obj, c.idx)) {
+                c.obj = o;
+                c.idx = cw;
             }
+        };
+        // upper bound, in fp32 with every rounding covered, of (P sqrt(E) / |s| + dC + dx)^2
+        auto reach2_of = [&](double e_star) {
+            const float rr = sqrtf(__double2float_ru(e_star)) * p_over_s * 1.000002f + dC + meta.w;
+            const float r2 = rr * rr * 1.000002f;
+            return r2 == r2 ? r2 : __builtin_huge_valf();   // NaN: nothing can be excluded
         };
         auto team_min = [&](cand_t c) {
 #pragma unroll
-            for (int m = 8; m > 0; m >>= 1) {
-                double o = __shfl_xor(c.obj, m, 16);
-                int i = __shfl_xor(c.idx, m, 16);
+            for (int m = kTeam / 2; m > 0; m >>= 1) {
+                double o = __shfl_xor(c.obj, m, kTeam);
+                int i = __shfl_xor(c.idx, m, kTeam);
                 if (cand_better(o, i, c.obj, c.idx)) {
                     c.obj = o;
                     c.idx = i;
@@ -844,26 +956,61 @@ __global__ __launch_bounds__(kBlock) void k_rerank(
         cand_t mine;
         mine.obj = __builtin_huge_val();
         mine.idx = 0x7fffffff;
-        if (best_key != kNoKey) eval_key(best_key, best_p, mine);
+        unsigned exact_evals = 1;                      // the previous code
+        double e_star = o_prev;
+        if (best_key != kNoKey) {
+            float dd[kMine];
+            int pos[kMine];
+            level1(best_key, best_p, dd, pos);
+            // the position that looks nearest is evaluated first: it fixes the reach for the rest
+            int wu = 0;
+            float dmin = dd[0];
+#pragma unroll
+            for (int uu = 1; uu < kMine; ++uu)
+                if (dd[uu] < dmin) {
+                    dmin = dd[uu];
+                    wu = uu;
+                }
+            unsigned long long pick = ((unsigned long long)__float_as_uint(dmin) << 32) | (unsigned)q;
+#pragma unroll
+            for (int m = kTeam / 2; m > 0; m >>= 1) {
+                unsigned long long o = __shfl_xor(pick, m, kTeam);
+                pick = o < pick ? o : pick;
+            }
+            const bool chosen = (int)(pick & 15u) == q && dmin < 3.0e38f;
+            if (chosen) {
+                int pw = pos[0];                   // pos[wu] without dynamic register indexing
+#pragma unroll
+                for (int uu = 1; uu < kMine; ++uu)
+                    if (uu == wu) pw = pos[uu];
+                exact_at(pw, mine);
+            }
+            const double o0 = __shfl(mine.obj, (int)(pick & 15u), kTeam);
+            if (o0 < e_star) e_star = o0;
+            const float r2f = reach2_of(e_star);
+#pragma unroll
+            for (int uu = 0; uu < kMine; ++uu)
+                if (!(chosen && uu == wu) && dd[uu] * (1.0f - kDdSlack) <= r2f && pos[uu] < csize) {
+                    exact_at(pos[uu], mine);
+                    ++exact_evals;
+                }
+            if (chosen) ++exact_evals;
+        }
         cand_t first = team_min(mine);
-        if (o_prev < first.obj) first.obj = o_prev;   // the previous code is a candidate too
+        if (first.obj < e_star) e_star = first.obj;
 
         // every codeword that was not evaluated and could still reach E* sits behind a key
         // whose upper bound is at least kcut
-        bool okP;
-        const float Pscale = scale_from_maxabs(cb_meta[0], &okP);
-        const double dC = sqrt((double)__uint_as_float(cb_meta[2])) * 1.0001 + 1e-30;
-        const double dstar = sqrt(first.obj) * (double)Pscale / fabs((double)s) * (1.0 + 1e-9);
-        const double reach = dstar + dC + (double)meta.w;
-        const double base = (double)meta.x + (double)meta.y;
-        const double kcut_d = base * (1.0 - 1e-6) - reach * reach * (1.0 + 1e-6) - (double)meta.z;
-        const float kcut = __double2float_rd(kcut_d);
-        const bool no_bound = !(kcut_d > -3.0e38);     // also true for NaN: nothing can be excluded
+        const float reach2f = reach2_of(e_star);
+        // lower bound of SHIFT + ||x_hi||^2 - reach2 - E1 (fp32, every rounding covered)
+        const float base = meta.x + meta.y;
+        const float kcut = (base * 0.999999f - reach2f * 1.000001f) - meta.z - 1.0e-6f * (base + reach2f);
+        const bool no_bound = !(kcut > -3.0e38f);      // also true for NaN: nothing can be excluded
         unsigned pending = 0;                         // bit u: rec[u].x needs evaluation
         unsigned long long open = 0;                  // partitions with a second key at or above kcut
 #pragma unroll
         for (int u = 0; u < kMaxRec; ++u) {
-            int p = q + 16 * u;
+            int p = q + kTeam * u;
             if (p < P) {
                 if (rec[u].y != kNoKey && (no_bound || key_upper(rec[u].y) >= kcut)) open |= 1ull << p;
                 if (p != best_p && rec[u].x != kNoKey && (no_bound || key_upper(rec[u].x) >= kcut))
@@ -871,37 +1018,47 @@ __global__ __launch_bounds__(kBlock) void k_rerank(
             }
         }
 #pragma unroll
-        for (int m = 8; m > 0; m >>= 1) open |= __shfl_xor(open, m, 16);
-        const int team_shift = (threadIdx.x & 63) & ~15;
+        for (int m = kTeam / 2; m > 0; m >>= 1) open |= __shfl_xor(open, m, kTeam);
+        const int team_shift = (threadIdx.x & 63) & ~(kTeam - 1);
         // the best key of every other partition at or above kcut: its positions are evaluated here
         unsigned extra = 0;
         for (;;) {
             const unsigned long long pb = __ballot(pending != 0);
-            const unsigned team = (unsigned)((pb >> team_shift) & 0xFFFFull);
+            const unsigned team = (unsigned)((pb >> team_shift) & ((1ull << kTeam) - 1ull));
             if (!team) break;
             const int src = __ffs(team) - 1;      // lane of the team with work
-            const unsigned their = __shfl(pending, src, 16);
+            const unsigned their = __shfl(pending, src, kTeam);
             const int u = __ffs(their) - 1;
             int key = 0;
 #pragma unroll
             for (int uu = 0; uu < kMaxRec; ++uu)
                 if (uu == u) key = rec[uu].x;
-            key = __shfl(key, src, 16);
-            eval_key(key, src + 16 * u, mine);
+            key = __shfl(key, src, kTeam);
+            {
+                float dd[kMine];
+                int pos[kMine];
+                level1(key, src + kTeam * u, dd, pos);
+#pragma unroll
+                for (int uu = 0; uu < kMine; ++uu)
+                    if (dd[uu] * (1.0f - kDdSlack) <= reach2f && pos[uu] < csize) {
+                        exact_at(pos[uu], mine);
+                        ++exact_evals;
+                    }
+            }
             if (q == src) pending &= ~(1u << u);
             ++extra;
         }
+        (void)extra;
+#pragma unroll
+        for (int m = kTeam / 2; m > 0; m >>= 1) exact_evals += __shfl_xor(exact_evals, m, kTeam);
         const cand_t win = team_min(mine);
         if (q == 0) {
             if (open) {
                 // a partition may hide further codewords at or above kcut: all of its
                 // positions are evaluated by the block, which also takes the decision
                 open_rec_t r;
-                const double e_star = o_prev < win.obj ? o_prev : win.obj;
-                const double rr = sqrt(e_star) * (double)Pscale / fabs((double)s) * (1.0 + 1e-9) + dC +
-                                  (double)meta.w;
                 r.obj = win.obj;
-                r.reach2 = no_bound ? __builtin_huge_val() : rr * rr * (1.0 + 1e-9);
+                r.reach2 = no_bound ? __builtin_huge_valf() : reach2_of(o_prev < win.obj ? o_prev : win.obj);
                 r.mask = open;
                 r.idx = win.idx;
                 r.n = n;
@@ -916,32 +1073,40 @@ __global__ __launch_bounds__(kBlock) void k_rerank(
                 }
                 atomicAdd(&s_cnt[0], 1u);
             }
-            atomicAdd(&s_cnt[2], 16u * kU * (1u + extra) + 1u);
+            atomicAdd(&s_cnt[2], exact_evals - (unsigned)(kTeam - 1));   // the previous code was counted by every lane
         }
     }
     __syncthreads();
 
-    // ---- groups left open: every position of their open partitions, by the whole block.
+    // ---- groups left open: every position of their open partitions, by the whole block, one
+    // group at a time.
     // Partition p = (codeword split, half wave, residue class) as the scoring kernel numbers them.
+#ifdef PV_TIMING_ONLY_NO_OPEN
+    const unsigned nopen = 0;
+#else
     const unsigned nopen = s_nopen;
+#endif
+    __shared__ double s_obj[kBlock / 64];
+    __shared__ int s_idx[kBlock / 64];
     for (unsigned item = 0; item < nopen; ++item) {
         const open_rec_t rec = s_open[item];
         const int n2 = rec.n;
-        const float s = scales[n2 / gpr];
+        const pv_f4 *stage2 = reinterpret_cast<const pv_f4 *>(x_stage + (int64_t)rec.j * (G + 4));
+        const pv_f4 tail2 = stage2[G / 4];
+        const float s = tail2.x;
         float t[G];
-        {
-            const pv_f4 *t4 = reinterpret_cast<const pv_f4 *>(T + (int64_t)n2 * G);
 #pragma unroll
-            for (int v4 = 0; v4 < G / 4; ++v4) {
-                pv_f4 v = t4[v4];
-                t[v4 * 4 + 0] = v.x;
-                t[v4 * 4 + 1] = v.y;
-                t[v4 * 4 + 2] = v.z;
-                t[v4 * 4 + 3] = v.w;
-            }
+        for (int v4 = 0; v4 < G / 4; ++v4) {
+            pv_f4 v = stage2[v4];
+            t[v4 * 4 + 0] = v.x;
+            t[v4 * 4 + 1] = v.y;
+            t[v4 * 4 + 2] = v.z;
+            t[v4 * 4 + 3] = v.w;
         }
-        const int prev = codes[n2] & (csize - 1);
+        const int prev = __float_as_int(tail2.y);
+        const int lane = threadIdx.x & 63;
         const int qq = threadIdx.x & 15, slot = threadIdx.x >> 4;
+        constexpr int kSlots = kBlock / 16;
         // the group's fp16 operand as the matrix cores saw it
         float xh[G];
         {
@@ -953,7 +1118,8 @@ __global__ __launch_bounds__(kBlock) void k_rerank(
                 for (int e = 0; e < 8; ++e) xh[h * 8 + e] = (float)v[e];
             }
         }
-        const bool test = rec.reach2 < 1.0e300;
+        const bool test = rec.reach2 < 3.0e38f;
+        const float r2f = rec.reach2;
         cand_t mine;
         mine.obj = __builtin_huge_val();
         mine.idx = 0x7fffffff;
@@ -961,42 +1127,38 @@ __global__ __launch_bounds__(kBlock) void k_rerank(
             const int p = __ffsll((long long)left) - 1;
             const int hw = (p / per_half) & 1;
             const int split = p / (2 * per_half);
-            const int su_begin = (int)((int64_t)split * ncyc / nsplit) * kResidues;
-            const int su_end = (int)((int64_t)(split + 1) * ncyc / nsplit) * kResidues;
-            // the classes of the record: p % per_half, + per_half, ... (relative to the split's start)
-            for (int rel = (p % per_half) + slot * per_half; su_begin + rel < su_end; rel += kTeams * per_half) {
-                const int su = su_begin + rel;
-                h8 a[kU][G / 8];
+            const int su_begin = split_begin(split, ncyc, nsplit) * kResidues;
+            const int su_end = su_begin + split_count(split, ncyc, nsplit) * kResidues;
+            const int row = 8 * (qq >> 2) + 4 * hw + (qq & 3);
+            // the classes of the record: p % per_half, + per_half, ... (relative to the split's
+            // start); kBatch super-units per lane at a time, so that their operand rows are in
+            // flight together
+            constexpr int kBatch = 2;
+            for (int rel0 = (p % per_half) + slot * per_half; su_begin + rel0 < su_end;
+                 rel0 += kSlots * per_half * kBatch) {
+                float dd[kBatch][kU];
 #pragma unroll
-                for (int uu = 0; uu < kU; ++uu) {   // the loads first, then the arithmetic
-                    const int row = 8 * (qq >> 2) + 4 * hw + (qq & 3);
+                for (int bb = 0; bb < kBatch; ++bb) {
+                    // unconditional loads (a row of the split's last super-unit stands in past its
+                    // end), so that the whole batch is in flight together
+                    const int su = su_begin + rel0 + bb * kSlots * per_half;
+                    const int su_c = su < su_end ? su : su_end - 1;
 #pragma unroll
-                    for (int h = 0; h < G / 8; ++h) a[uu][h] = A[((int64_t)(su * kU + uu) * 2 + h) * 32 + row];
+                    for (int uu = 0; uu < kU; ++uu) dd[bb][uu] = approx_dd<G>(A, su_c * kU + uu, row, xh);
                 }
 #pragma unroll
-                for (int uu = 0; uu < kU; ++uu) {
-                    const int pos = ((su * 2 + hw) * kU + uu) * 16 + qq;
-                    if (pos >= csize) continue;
-                    bool take = true;
-                    if (test) {
-                        // || c_hi - x_hi ||^2: the operand holds 2 c_hi; differences and squares of
-                        // fp16 values are exact in double
-                        double dd = 0.0;
+                for (int bb = 0; bb < kBatch; ++bb) {
+                    const int su = su_begin + rel0 + bb * kSlots * per_half;
 #pragma unroll
-                        for (int h = 0; h < G / 8; ++h)
-#pragma unroll
-                            for (int e = 0; e < 8; ++e) {
-                                const double d = 0.5 * (double)(float)a[uu][h][e] - (double)xh[h * 8 + e];
-                                dd = fma(d, d, dd);
+                    for (int uu = 0; uu < kU; ++uu) {
+                        const int pos = ((su * 2 + hw) * kU + uu) * 16 + qq;
+                        if (su < su_end && pos < csize && (!test || dd[bb][uu] * (1.0f - kDdSlack) <= r2f)) {
+                            const int cw = G == 8 ? pos : (int)perm[pos];
+                            const double obj = exact_obj<G>(codebook + (int64_t)cw * G, s, t);
+                            if (cand_better(obj, cw, mine.obj, mine.idx)) {
+                                mine.obj = obj;
+                                mine.idx = cw;
                             }
-                        take = !(dd > rec.reach2);
-                    }
-                    if (take) {
-                        const int cw = G == 8 ? pos : (int)perm[pos];
-                        const double obj = exact_obj<G>(codebook + (int64_t)cw * G, s, t);
-                        if (cand_better(obj, cw, mine.obj, mine.idx)) {
-                            mine.obj = obj;
-                            mine.idx = cw;
                         }
                     }
                 }
@@ -1005,15 +1167,15 @@ __global__ __launch_bounds__(kBlock) void k_rerank(
         // block-wide lexicographic minimum
 #pragma unroll
         for (int off = 32; off > 0; off >>= 1) {
-            double o = __shfl_down(mine.obj, off);
-            int i = __shfl_down(mine.idx, off);
+            double o = __shfl_xor(mine.obj, off);
+            int i = __shfl_xor(mine.idx, off);
             if (cand_better(o, i, mine.obj, mine.idx)) {
                 mine.obj = o;
                 mine.idx = i;
             }
         }
         __syncthreads();
-        if ((threadIdx.x & 63) == 0) {
+        if (lane == 0) {
             s_obj[threadIdx.x >> 6] = mine.obj;
             s_idx[threadIdx.x >> 6] = mine.idx;
         }
@@ -1032,9 +1194,9 @@ __global__ __launch_bounds__(kBlock) void k_rerank(
             if (o_prev <= win.obj || pick == 0x7fffffff) pick = prev;
             if (pick != prev) {
                 codes[n2] = (uint16_t)pick;
-                s_cnt[1] += 1u;
+                atomicAdd(&s_cnt[1], 1u);
             }
-            s_cnt[3] += 1u;
+            atomicAdd(&s_cnt[3], 1u);
         }
     }
     __syncthreads();
@@ -1168,10 +1330,13 @@ pv_status pv_launch_mfma_search(pv_ctx *ctx, const pv_layout *l, const float *T,
     if ((st = pv_ensure(ctx, ctx->cb_f16, nmin_off + (size_t)nsu_alloc * 4)) != PV_OK) return st;
     if ((st = pv_ensure(ctx, ctx->cb_meta, 16 * sizeof(unsigned), /*zero_new=*/true)) != PV_OK) return st;
     if ((st = pv_ensure(ctx, ctx->x_f16, (size_t)p.k_pad * 32)) != PV_OK) return st;
-    if ((st = pv_ensure(ctx, ctx->x_meta, (size_t)p.k_pad * 4 * sizeof(float))) != PV_OK) return st;
+    // per-group bounds, then the staged targets / scale / code / id of each group
+    const size_t stage_off = (size_t)p.k_pad * 4 * sizeof(float);
+    if ((st = pv_ensure(ctx, ctx->x_meta, stage_off + (size_t)p.k_pad * (g + 4) * sizeof(float))) != PV_OK)
+        return st;
     if ((st = pv_ensure(ctx, ctx->partials, (size_t)p.k_pad * p.P * sizeof(int2))) != PV_OK) return st;
     if ((st = pv_ensure(ctx, ctx->fb_list, 64)) != PV_OK) return st;
-    const int rr_blocks = (int)((k * 16 + kBlock - 1) / kBlock);
+    const int rr_blocks = (int)((k * PV_TEAM + kBlock - 1) / kBlock);
     const int nslots = (rr_blocks + 63) / 64;
     if ((st = pv_ensure(ctx, ctx->rr_counts, (size_t)rr_blocks * 4 * sizeof(unsigned) + (size_t)nslots * 8 + 16)) != PV_OK)
         return st;
@@ -1187,6 +1352,7 @@ pv_status pv_launch_mfma_search(pv_ctx *ctx, const pv_layout *l, const float *T,
     h8 *X = static_cast<h8 *>(ctx->x_f16.ptr);
     unsigned *cb_meta = static_cast<unsigned *>(ctx->cb_meta.ptr);
     float *x_meta = static_cast<float *>(ctx->x_meta.ptr);
+    float *x_stage = x_meta + (size_t)p.k_pad * 4;
     int2 *partials = static_cast<int2 *>(ctx->partials.ptr);
     unsigned *fb_count = reinterpret_cast<unsigned *>(ctx->fb_list.ptr);       // 4 counters
     unsigned long long *stats = static_cast<unsigned long long *>(ctx->stats.ptr);
@@ -1209,7 +1375,8 @@ pv_status pv_launch_mfma_search(pv_ctx *ctx, const pv_layout *l, const float *T,
                                (unsigned *)nullptr, 0, change_slots, nslots);
             hipLaunchKernelGGL(k_prep<8>, dim3(cb_blocks + x_blocks), dim3(kBlock), 0, sm, codebooks,
                                csize, p.cpad, cb_blocks, cb_meta, A, perm, bucket, hist, nmin_bits, T,
-                               scales, group_idx, (int)k, p.k_pad, gpr, N, X, x_meta);
+                               scales, group_idx, (int)k, p.k_pad, gpr, N, X, x_meta, codes, csize - 1,
+                               x_stage, p.ncyc, p.nsplit);
         } else {
             hipLaunchKernelGGL(k_cb_stats<16>, dim3(blocks), dim3(kBlock), 0, sm, codebooks, csize,
                                cb_meta, cb_meta_next, stats, fb_count, nc, hist, nmin_bits, nsu_alloc,
@@ -1219,7 +1386,8 @@ pv_status pv_launch_mfma_search(pv_ctx *ctx, const pv_layout *l, const float *T,
             hipLaunchKernelGGL(k_cb_scan, dim3(1), dim3(1024), 0, sm, hist);
             hipLaunchKernelGGL(k_prep<16>, dim3(cb_blocks + x_blocks), dim3(kBlock), 0, sm,
                                codebooks, csize, p.cpad, cb_blocks, cb_meta, A, perm, bucket, hist,
-                               nmin_bits, T, scales, group_idx, (int)k, p.k_pad, gpr, N, X, x_meta);
+                               nmin_bits, T, scales, group_idx, (int)k, p.k_pad, gpr, N, X, x_meta,
+                               codes, csize - 1, x_stage, p.ncyc, p.nsplit);
         }
     }
     {
@@ -1243,13 +1411,13 @@ pv_status pv_launch_mfma_search(pv_ctx *ctx, const pv_layout *l, const float *T,
         pv_timed t(ctx, PV_K_RERANK);
         const dim3 rgrid((unsigned)rr_blocks);
         if (g == 8)
-            hipLaunchKernelGGL(k_rerank<8>, rgrid, dim3(kBlock), 0, sm, T, codebooks, scales,
-                               group_idx, (int)k, p.k_pad, partials, p.P, p.per_half, p.ncyc, p.nsplit,
-                               x_meta, cb_meta, A, X, perm, codes, rr_counts, change_slots, nc, gpr, N, l->nbits);
+            hipLaunchKernelGGL(k_rerank<8>, rgrid, dim3(kBlock), 0, sm, x_stage, codebooks, (int)k,
+                               p.k_pad, partials, p.P, p.per_half, p.ncyc, p.nsplit, x_meta, cb_meta, A, X,
+                               perm, codes, rr_counts, change_slots, nc, l->nbits);
         else
-            hipLaunchKernelGGL(k_rerank<16>, rgrid, dim3(kBlock), 0, sm, T, codebooks, scales,
-                               group_idx, (int)k, p.k_pad, partials, p.P, p.per_half, p.ncyc, p.nsplit,
-                               x_meta, cb_meta, A, X, perm, codes, rr_counts, change_slots, nc, gpr, N, l->nbits);
+            hipLaunchKernelGGL(k_rerank<16>, rgrid, dim3(kBlock), 0, sm, x_stage, codebooks, (int)k,
+                               p.k_pad, partials, p.P, p.per_half, p.ncyc, p.nsplit, x_meta, cb_meta, A, X,
+                               perm, codes, rr_counts, change_slots, nc, l->nbits);
     }
     PV_HIP(ctx, hipGetLastError());
     return PV_OK;
