@@ -250,19 +250,36 @@ __global__ __launch_bounds__(kBlock) void k_cb_bucket(const float *__restrict__ 
     atomicAdd(&hist[b], 1u);
 }
 
-// Step 2: exclusive prefix sum of the bucket counts, in place (one block of 1024 threads).
-__global__ __launch_bounds__(1024) void k_cb_scan(unsigned *__restrict__ hist)
+// Step 2: exclusive prefix sum of the bucket counts.  Block b owns 1024 buckets; it adds up
+// everything before them itself (coalesced reads of a table that sits in L2: cheaper than any
+// exchange between blocks) and scans its own.
+constexpr int kScanBlock = 1024;
+__global__ __launch_bounds__(kScanBlock) void k_cb_scan(const unsigned *__restrict__ hist,
+                                                        unsigned *__restrict__ offsets)
 {
-    constexpr int per = kNormBins / 1024;
-    __shared__ unsigned s_w[16];
-    unsigned v[per], sum = 0;
-#pragma unroll
-    for (int i = 0; i < per; ++i) {
-        v[i] = hist[threadIdx.x * per + i];
-        sum += v[i];
-    }
+    __shared__ unsigned s_w[kScanBlock / 64];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    unsigned inc = sum;
+    const int first = blockIdx.x * kScanBlock;
+    unsigned before = 0;
+    for (int i0 = 0; i0 < first; i0 += 8 * kScanBlock) {   // eight loads in flight per thread
+        unsigned v8[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int i = i0 + u * kScanBlock + threadIdx.x;
+            v8[u] = i < first ? hist[i] : 0u;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) before += v8[u];
+    }
+    for (int off = 32; off > 0; off >>= 1) before += __shfl_xor(before, off);
+    if (lane == 0) s_w[wave] = before;
+    __syncthreads();
+    unsigned base = 0;
+#pragma unroll
+    for (int w = 0; w < kScanBlock / 64; ++w) base += s_w[w];
+    __syncthreads();
+    const unsigned v = hist[first + threadIdx.x];
+    unsigned inc = v;
 #pragma unroll
     for (int off = 1; off < 64; off <<= 1) {
         unsigned u = __shfl_up(inc, off);
@@ -270,14 +287,8 @@ __global__ __launch_bounds__(1024) void k_cb_scan(unsigned *__restrict__ hist)
     }
     if (lane == 63) s_w[wave] = inc;
     __syncthreads();
-    unsigned before = 0;
-    for (int w = 0; w < wave; ++w) before += s_w[w];
-    unsigned run = before + inc - sum;
-#pragma unroll
-    for (int i = 0; i < per; ++i) {
-        hist[threadIdx.x * per + i] = run;
-        run += v[i];
-    }
+    for (int w = 0; w < wave; ++w) base += s_w[w];
+    offsets[first + threadIdx.x] = base + inc - v;
 }
 
 // Operand preparation, one launch for both sides.
@@ -499,6 +510,17 @@ __device__ __forceinline__ int imed3(int a, int b, int c)
 template <bool FIRST>
 __device__ __forceinline__ int acc_max(const f16v &acc, int run)
 {
+#ifdef PV_TREE
+    // two independent chains
+    int m1 = imax3(__float_as_int(acc[0]), __float_as_int(acc[1]), __float_as_int(acc[2]));
+    int m2 = imax3(__float_as_int(acc[8]), __float_as_int(acc[9]), __float_as_int(acc[10]));
+    m1 = imax3(m1, __float_as_int(acc[3]), __float_as_int(acc[4]));
+    m2 = imax3(m2, __float_as_int(acc[11]), __float_as_int(acc[12]));
+    m1 = imax3(m1, __float_as_int(acc[5]), __float_as_int(acc[6]));
+    m2 = imax3(m2, __float_as_int(acc[13]), __float_as_int(acc[14]));
+    m1 = imax3(m1, __float_as_int(acc[7]), (FIRST && run == kNoKey) ? __float_as_int(acc[7]) : run);
+    return imax3(m1, m2, __float_as_int(acc[15]));
+#endif
     int m;
     if (FIRST && run == kNoKey) {
         m = imax3(__float_as_int(acc[0]), __float_as_int(acc[1]), __float_as_int(acc[2]));
@@ -650,6 +672,23 @@ __global__ __launch_bounds__(PV_WAVES * 64, (PV_OCC * PV_WAVES) / 4) void k_scor
             for (int vr = 0; vr < kUnitsCycle; ++vr) {
                 const int u = vr / NB, nb = vr % NB, ts = q4 + u;
                 if (nb == 0) a_nxt = buf[(ts + 1) * 64 + lane];   // one spare tile pads the LDS array
+#ifdef PV_PAIR
+                // all group tiles of a codeword tile are issued back to back, then the units of
+                // the tile before are reduced
+                issue(nb, vr % kSets);
+                if (nb == NB - 1) {
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int wnb = 0; wnb < NB; ++wnb) {
+                        const int wr = vr - (NB - 1) + wnb - NB;      // unit of the tile before
+                        const int dq = u - 1;
+                        if (q4 > 0 || wr >= 0)
+                            reduce(bufn, t0, (q4 + dq) / kU, (dq + kCycle) % kCycle, wnb,
+                                   (wr % kSets + kSets) % kSets);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+#else
                 issue(nb, vr % kSets);
                 // the unit kD back: tile q4 + dq (dq may point into the cycle before), group tile wnb
                 const int dq = (vr - kD >= 0) ? (vr - kD) / NB : -((kD - vr + NB - 1) / NB);
@@ -661,6 +700,7 @@ __global__ __launch_bounds__(PV_WAVES * 64, (PV_OCC * PV_WAVES) / 4) void k_scor
                 // behind its own matrix instruction, and the wave then waits out that
                 // instruction's whole latency instead of working on older units
                 __builtin_amdgcn_sched_barrier(0);
+#endif
                 if (nb == NB - 1) a_cur = a_nxt;
             }
         }
@@ -1326,7 +1366,8 @@ pv_status pv_launch_mfma_search(pv_ctx *ctx, const pv_layout *l, const float *T,
     const size_t a_bytes = (size_t)p.cpad * 32;
     const size_t perm_off = a_bytes, bucket_off = perm_off + (size_t)p.cpad * 2;
     const size_t hist_off = (bucket_off + (size_t)csize * 2 + 255) & ~(size_t)255;
-    const size_t nmin_off = hist_off + (size_t)kNormBins * 4;
+    const size_t offs_off = hist_off + (size_t)kNormBins * 4;
+    const size_t nmin_off = offs_off + (size_t)kNormBins * 4;
     if ((st = pv_ensure(ctx, ctx->cb_f16, nmin_off + (size_t)nsu_alloc * 4)) != PV_OK) return st;
     if ((st = pv_ensure(ctx, ctx->cb_meta, 16 * sizeof(unsigned), /*zero_new=*/true)) != PV_OK) return st;
     if ((st = pv_ensure(ctx, ctx->x_f16, (size_t)p.k_pad * 32)) != PV_OK) return st;
@@ -1348,6 +1389,7 @@ pv_status pv_launch_mfma_search(pv_ctx *ctx, const pv_layout *l, const float *T,
     uint16_t *perm = reinterpret_cast<uint16_t *>(cbase + perm_off);
     uint16_t *bucket = reinterpret_cast<uint16_t *>(cbase + bucket_off);
     unsigned *hist = reinterpret_cast<unsigned *>(cbase + hist_off);
+    unsigned *offsets = reinterpret_cast<unsigned *>(cbase + offs_off);
     unsigned *nmin_bits = reinterpret_cast<unsigned *>(cbase + nmin_off);
     h8 *X = static_cast<h8 *>(ctx->x_f16.ptr);
     unsigned *cb_meta = static_cast<unsigned *>(ctx->cb_meta.ptr);
@@ -1383,9 +1425,9 @@ pv_status pv_launch_mfma_search(pv_ctx *ctx, const pv_layout *l, const float *T,
                                change_slots, nslots);
             hipLaunchKernelGGL(k_cb_bucket<16>, dim3((csize + kBlock - 1) / kBlock), dim3(kBlock), 0,
                                sm, codebooks, csize, cb_meta, bucket, hist);
-            hipLaunchKernelGGL(k_cb_scan, dim3(1), dim3(1024), 0, sm, hist);
+            hipLaunchKernelGGL(k_cb_scan, dim3(kNormBins / kScanBlock), dim3(kScanBlock), 0, sm, hist, offsets);
             hipLaunchKernelGGL(k_prep<16>, dim3(cb_blocks + x_blocks), dim3(kBlock), 0, sm,
-                               codebooks, csize, p.cpad, cb_blocks, cb_meta, A, perm, bucket, hist,
+                               codebooks, csize, p.cpad, cb_blocks, cb_meta, A, perm, bucket, offsets,
                                nmin_bits, T, scales, group_idx, (int)k, p.k_pad, gpr, N, X, x_meta,
                                codes, csize - 1, x_stage, p.ncyc, p.nsplit);
         }
