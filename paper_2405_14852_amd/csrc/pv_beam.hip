@@ -1,0 +1,564 @@
+// Beam search over two 8-bit codebooks of 8-dimensional codewords (Sec. 4.2, App. K: beam 8;
+// App. D: the expansion of the squared distance) as a FILTER in single and half precision,
+// with the decision left to the reference arithmetic (double, the chain of the plain
+// definition).  A group that cannot be certified goes to a list that the exact kernel
+// (one wave per group, double throughout) works through afterwards.
+//
+// With x = t / s the objective of a pair is  s^2 || c0 + c1 - x ||^2.
+//
+// Step 0 (256 first codes against the current second code), one group per LANE: the lane
+// forms y0 = x - C1[p1] and, for every first code, || c0 ||^2 - 2 <c0, y0> + || y0 ||^2 in
+// fp32 (the codebook rows are LDS broadcasts), keeping the nine smallest values sorted, the
+// code in the low 8 bits.  The kept set (the smallest beam_width) is accepted when the next
+// value lies above the last kept one by more than twice the rounding bound of that form.
+//
+// Step 1 (256 second codes against each kept first code) is a dense contraction, done on
+// the fp16 matrix cores exactly like the one-codebook filter: columns are (group, kept
+// code) pairs, y1 = x - C0[c0], rows the second codebook, the spare K slots carry the
+// squared norms and a shift, so an accumulator is a closeness
+//     kv = SHIFT + 2 <c1_hi, y1_hi> - || c1_hi ||^2 = SHIFT + || y1_hi ||^2 - || c1_hi - y1_hi ||^2 .
+// A lane keeps the largest and second largest key (tile number in the low bits) of its
+// column and half.  The 16 lanes of a group then evaluate the 16 codewords behind the
+// group's best key with the reference chain, which fixes the best objective E*; by the
+// triangle inequality a pair can reach E* only if its key is at least
+//     SHIFT + || y1_hi ||^2 - (P sqrt(E*) / |s| + dC + dy)^2 - E1 ,
+// every best key at or above that cut is evaluated as well, and a second key at or above it
+// sends the group to the list.  The winner among the evaluated pairs (objective, then pair)
+// replaces the current pair if it is strictly better, as everywhere else.
+#include "pv_internal.h"
+
+namespace {
+
+typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+typedef float f16v __attribute__((ext_vector_type(16)));
+
+constexpr int kBlock = 256;
+constexpr int kWaves = kBlock / 64;
+constexpr int G = 8;
+constexpr int kKeep = 8;                            // largest beam the kernel takes
+constexpr unsigned kKeyMask = 0x7FFu;
+constexpr int kNoKey = (int)0x80000000;
+constexpr float kHalfMinNormal = 6.103515625e-05f;  // 2^-14
+constexpr float kGamma = 7.62939453125e-06f;        // 2^-17: fp32 accumulation bound per unit of sum|terms|
+constexpr float kNormMargin = 0.04f;
+
+__device__ __forceinline__ _Float16 to_half_flush(float v)
+{
+    return fabsf(v) < kHalfMinNormal ? (_Float16)0.0f : (_Float16)v;
+}
+
+__device__ __forceinline__ void split3(float v, _Float16 *p)
+{
+    p[0] = to_half_flush(v);
+    float r = v - (float)p[0];
+    p[1] = to_half_flush(r);
+    r = r - (float)p[1];
+    p[2] = to_half_flush(r);
+}
+
+__device__ __forceinline__ int imax3(int a, int b, int c) { return max(max(a, b), c); }
+
+__device__ __forceinline__ int and_or(int m, unsigned vmask, unsigned unit)
+{
+    int r;
+    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(m), "v"(vmask), "s"(unit));
+    return r;
+}
+
+__device__ __forceinline__ int imed3(int a, int b, int c)
+{
+    int r;
+    asm("v_med3_i32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+
+__device__ __forceinline__ unsigned umed3(unsigned a, unsigned b, unsigned c)
+{
+    unsigned r;
+    asm("v_med3_u32 %0, %1, %2, %3" : "=v"(r) : "v"(a), "v"(b), "v"(c));
+    return r;
+}
+
+__device__ __forceinline__ float key_upper(int key)
+{
+    return key < 0 ? 0.0f : __int_as_float(key | (int)kKeyMask);
+}
+
+__device__ __forceinline__ bool better(double o1, int i1, double o2, int i2)
+{
+    return o1 < o2 || (o1 == o2 && i1 < i2);
+}
+
+// the reference chain for one pair
+__device__ __forceinline__ double pair_objective(const float *c0, const float *c1, double s,
+                                                 const float *t)
+{
+    double obj = 0.0;
+#pragma unroll
+    for (int i = 0; i < G; ++i) {
+        double acc = (double)c0[i];
+        acc = acc + (double)c1[i];
+        const double r = s * acc - (double)t[i];
+        obj = obj + r * r;
+    }
+    return obj;
+}
+
+struct tables_t {
+    float c0[256 * G];      // first codebook
+    float c1[256 * G];      // second codebook
+    float n0[256];          // || c0 ||^2 (fp32 chain)
+    h8 a1[8 * 64];          // second codebook as matrix operand: tile, k-half, row
+    float red[kWaves][6];
+    float P, cmax0, cmax1, cmin1, dC1;
+    int bad;
+};
+
+struct wave_t {
+    float x[64][G];         // t / s of the wave's 64 groups
+    float t[64][G];
+    float s[64];
+    double o_prev[64];
+    int n[64];
+    unsigned char keep[64][kKeep];   // kept first codes
+    unsigned char prev[64][2];
+    unsigned char ok[64];   // the group is still with the filter
+};
+
+__global__ __launch_bounds__(kBlock, 2) void k_beam_2x8_f16(
+    const float *__restrict__ T, const float *__restrict__ codebooks,
+    const float *__restrict__ scales, const int32_t *__restrict__ group_idx, int64_t k,
+    int beam_width, uint16_t *__restrict__ codes, unsigned long long *__restrict__ num_changed,
+    unsigned long long *__restrict__ stat_fast, int32_t *__restrict__ redo_list,
+    unsigned long long *__restrict__ redo_count, int gpr, int N)
+{
+    __shared__ tables_t tb;
+    __shared__ wave_t ws[kWaves];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    wave_t &w = ws[wave];
+
+    // ---------------------------------------------------------------- tables (every block its own)
+    {
+        const int c = threadIdx.x;               // codeword c of both codebooks
+        float m = 0.0f, nmax0 = 0.0f, nmax1 = 0.0f, nmin1 = __builtin_huge_valf();
+        bool bad = false;
+        float a[G], b[G];
+        float n0 = 0.0f, n1 = 0.0f;
+#pragma unroll
+        for (int i = 0; i < G; ++i) {
+            a[i] = codebooks[c * G + i];
+            b[i] = codebooks[(256 + c) * G + i];
+            bad |= !(fabsf(a[i]) <= 3.0e38f) || !(fabsf(b[i]) <= 3.0e38f);
+            tb.c0[c * G + i] = a[i];
+            tb.c1[c * G + i] = b[i];
+            m = fmaxf(m, fmaxf(fabsf(a[i]), fabsf(b[i])));
+            n0 = fmaf(a[i], a[i], n0);
+            n1 = fmaf(b[i], b[i], n1);
+        }
+        tb.n0[c] = n0;
+        nmax0 = n0;
+        nmax1 = n1;
+        nmin1 = n1;
+        for (int off = 32; off > 0; off >>= 1) {
+            m = fmaxf(m, __shfl_xor(m, off));
+            nmax0 = fmaxf(nmax0, __shfl_xor(nmax0, off));
+            nmax1 = fmaxf(nmax1, __shfl_xor(nmax1, off));
+            nmin1 = fminf(nmin1, __shfl_xor(nmin1, off));
+        }
+        const unsigned long long anybad = __ballot(bad);
+        if (lane == 0) {
+            tb.red[wave][0] = m;
+            tb.red[wave][1] = nmax0;
+            tb.red[wave][2] = nmax1;
+            tb.red[wave][3] = nmin1;
+            tb.red[wave][4] = anybad ? 1.0f : 0.0f;
+        }
+        __syncthreads();
+        float M = 0.0f, X0 = 0.0f, X1 = 0.0f, N1 = __builtin_huge_valf(), B = 0.0f;
+#pragma unroll
+        for (int v = 0; v < kWaves; ++v) {
+            M = fmaxf(M, tb.red[v][0]);
+            X0 = fmaxf(X0, tb.red[v][1]);
+            X1 = fmaxf(X1, tb.red[v][2]);
+            N1 = fminf(N1, tb.red[v][3]);
+            B = fmaxf(B, tb.red[v][4]);
+        }
+        const bool ok = (M > 0.0f) && (M < 3.0e38f) && (M >= 1.0e-30f) && B == 0.0f && X0 < 3.0e38f &&
+                        X1 < 3.0e38f;
+        float P = 1.0f;
+        if (ok) {
+            int ex;
+            (void)frexpf(M, &ex);
+            P = ldexpf(1.0f, 5 - ex);            // M * P in [16, 32)
+        }
+        // operand row of codeword c of the second codebook: 2 c_hi | three pieces of ||c_hi||^2, 1, 1, 1
+        h8 ch0, ch1;
+        float nh = 0.0f, d2 = 0.0f;
+#pragma unroll
+        for (int i = 0; i < G; ++i) {
+            const float v = ok ? P * b[i] : 0.0f;
+            const float hf = (float)to_half_flush(v);
+            nh = fmaf(hf, hf, nh);
+            const float d = v - hf;
+            d2 = fmaf(d, d, d2);
+            ch0[i] = (_Float16)(2.0f * hf);
+        }
+        _Float16 pieces[3];
+        split3(nh, pieces);
+#pragma unroll
+        for (int i = 0; i < 8; ++i) ch1[i] = (_Float16)0.0f;
+        ch1[0] = pieces[0];
+        ch1[1] = pieces[1];
+        ch1[2] = pieces[2];
+        ch1[3] = (_Float16)1.0f;
+        ch1[4] = (_Float16)1.0f;
+        ch1[5] = (_Float16)1.0f;
+        {
+            const int tile = c >> 5, hw = (c >> 4) & 1, q = c & 15;
+            const int row = 8 * (q >> 2) + 4 * hw + (q & 3);
+            tb.a1[(tile * 2 + 0) * 32 + row] = ch0;
+            tb.a1[(tile * 2 + 1) * 32 + row] = ch1;
+        }
+        for (int off = 32; off > 0; off >>= 1) d2 = fmaxf(d2, __shfl_xor(d2, off));
+        __syncthreads();
+        if (lane == 0) tb.red[wave][5] = d2;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            float D = 0.0f;
+#pragma unroll
+            for (int v = 0; v < kWaves; ++v) D = fmaxf(D, tb.red[v][5]);
+            tb.P = P;
+            tb.cmax0 = sqrtf(X0) * 1.0001f;                        // unscaled
+            tb.cmax1 = P * sqrtf(X1) * 1.0001f + kNormMargin;      // scaled, of the fp16 copy
+            tb.cmin1 = P * sqrtf(N1) * 1.0001f + kNormMargin;
+            tb.dC1 = sqrtf(D) * 1.0001f + 1.0e-30f;
+            tb.bad = ok ? 0 : 1;
+        }
+        __syncthreads();
+    }
+    const float P = tb.P;
+    const bool tables_ok = tb.bad == 0;
+    const int keep = beam_width < kKeep ? beam_width : kKeep;
+    unsigned vmask = ~kKeyMask;
+    asm volatile("" : "+v"(vmask));
+    // the eight operand tiles of the second codebook stay in registers
+    h8 a1[8];
+#pragma unroll
+    for (int tl = 0; tl < 8; ++tl) a1[tl] = tb.a1[tl * 64 + lane];
+
+    unsigned changed = 0, fast = 0;
+    const int64_t batches = (k + 63) / 64;
+    for (int64_t bi = (int64_t)blockIdx.x * kWaves + wave; bi < batches; bi += (int64_t)gridDim.x * kWaves) {
+        // ------------------------------------------------------------ step 0: lane = group
+        {
+            const int64_t j = bi * 64 + lane;
+            int n = j < k ? group_idx[j] : -1;
+            if (n >= N) n = -1;
+            const bool valid = n >= 0;
+            const int nn = valid ? n : 0;
+            const float s = valid ? scales[nn / gpr] : 1.0f;
+            float t[G];
+            {
+                const pv_f4 *t4 = reinterpret_cast<const pv_f4 *>(T + (int64_t)nn * G);
+                const pv_f4 v0 = t4[0], v1 = t4[1];
+                t[0] = v0.x; t[1] = v0.y; t[2] = v0.z; t[3] = v0.w;
+                t[4] = v1.x; t[5] = v1.y; t[6] = v1.z; t[7] = v1.w;
+            }
+            const int p0 = codes[(int64_t)nn * 2] & 255, p1 = codes[(int64_t)nn * 2 + 1] & 255;
+            bool ok = valid && tables_ok && (s != 0.0f) && (fabsf(s) < 3.0e38f);
+            const float div = ok ? s : 1.0f;
+            float x[G], y[G];
+            float yy = 0.0f, xx = 0.0f;
+#pragma unroll
+            for (int i = 0; i < G; ++i) {
+                x[i] = t[i] / div;
+                y[i] = x[i] - tb.c1[p1 * G + i];
+                yy = fmaf(y[i], y[i], yy);
+                xx = fmaf(x[i], x[i], xx);
+            }
+            ok = ok && (xx < 1.0e30f) && (yy < 1.0e30f);   // also catches NaN
+            const double o_prev = pair_objective(&tb.c0[p0 * G], &tb.c1[p1 * G], (double)s, t);
+            // fp32 form of || c0 - y ||^2, never below zero by more than its rounding; a margin
+            // keeps the bits ordered like integers
+            const float span = tb.cmax0 + sqrtf(yy) + sqrtf(xx);
+            const float e0 = 4.0e-6f * span * span;        // rounding bound of the form (4 * 2^-20)
+            const float lift = yy * 1.00001f + e0;
+            unsigned top[kKeep + 1];
+#pragma unroll
+            for (int r = 0; r <= kKeep; ++r) top[r] = 0x7F800000u;          // +inf
+            for (int c0 = 0; c0 < 256; ++c0) {
+                const pv_f4 r0 = *reinterpret_cast<const pv_f4 *>(&tb.c0[c0 * G]);
+                const pv_f4 r1 = *reinterpret_cast<const pv_f4 *>(&tb.c0[c0 * G + 4]);
+                float dot = r0.x * y[0];
+                dot = fmaf(r0.y, y[1], dot);
+                dot = fmaf(r0.z, y[2], dot);
+                dot = fmaf(r0.w, y[3], dot);
+                dot = fmaf(r1.x, y[4], dot);
+                dot = fmaf(r1.y, y[5], dot);
+                dot = fmaf(r1.z, y[6], dot);
+                dot = fmaf(r1.w, y[7], dot);
+                const float d = fmaf(-2.0f, dot, tb.n0[c0]) + lift;
+                unsigned carry = (__float_as_uint(d) & ~0xFFu) | (unsigned)c0;
+                // sorted insertion, two levels at a time
+#pragma unroll
+                for (int r = 0; r + 1 <= kKeep; r += 2) {
+                    const unsigned lo = min(top[r], carry);
+                    const unsigned mid = umed3(top[r], top[r + 1], carry);
+                    carry = max(top[r + 1], carry);
+                    top[r] = lo;
+                    top[r + 1] = mid;
+                }
+                top[kKeep] = min(top[kKeep], carry);
+            }
+            // the kept set is certain when the first dropped value clears the last kept one by
+            // twice the rounding bound plus the 8 bits given to the code
+            {
+                unsigned last = top[0], next = top[1];
+#pragma unroll
+                for (int r = 1; r < kKeep; ++r)
+                    if (r < keep) {
+                        last = top[r];
+                        next = top[r + 1];
+                    }
+                const float vl = __uint_as_float(last | 0xFFu), vn = __uint_as_float(next & ~0xFFu);
+                ok = ok && (vn - vl > 2.0f * e0 + 1.0e-6f * vn);   // false for NaN
+            }
+            w.n[lane] = valid ? n : -1;
+            w.s[lane] = s;
+            w.o_prev[lane] = o_prev;
+            w.ok[lane] = ok ? 1 : 0;
+            w.prev[lane][0] = (unsigned char)p0;
+            w.prev[lane][1] = (unsigned char)p1;
+#pragma unroll
+            for (int i = 0; i < G; ++i) {
+                w.x[lane][i] = x[i];
+                w.t[lane][i] = t[i];
+            }
+#pragma unroll
+            for (int r = 0; r < kKeep; ++r) w.keep[lane][r] = (unsigned char)(top[r] & 0xFFu);
+        }
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_s_waitcnt(0);
+
+        // ------------------------------------------------------------ step 1: 16 column tiles of 4 groups
+        const int col = lane & 31, hw = lane >> 5;
+        const int gq = col >> 3, e = col & 7;            // group of the tile, kept code
+#pragma unroll 1
+        for (int ct = 0; ct < 16; ++ct) {
+            const int gl = ct * 4 + gq;                  // the group's lane of step 0
+            const bool gok = w.ok[gl] != 0;
+            const bool head = e == 0 && hw == 0 && w.n[gl] >= 0;   // the lane that speaks for the group
+            if (!__any(gok)) {                           // nothing of this tile is with the filter
+                if (head) redo_list[atomicAdd(redo_count, 1ull)] = w.n[gl];
+                continue;
+            }
+            const bool live = gok && e < keep;
+            const int c0e = w.keep[gl][e];
+            const float s = w.s[gl];
+            // operand column: y1 = P (x - C0[c0e]) as fp16, norms, shift
+            float u[G], hf[G];
+            float yy = 0.0f, d2 = 0.0f, u2 = 0.0f;
+            bool fits = live;
+#pragma unroll
+            for (int i = 0; i < G; ++i) {
+                u[i] = P * (w.x[gl][i] - tb.c0[c0e * G + i]);
+                if (!(fabsf(u[i]) < 240.0f)) fits = false;
+                hf[i] = (float)to_half_flush(fits ? u[i] : 0.0f);
+                yy = fmaf(hf[i], hf[i], yy);
+                const float d = u[i] - hf[i];
+                d2 = fmaf(d, d, d2);
+                u2 = fmaf(u[i], u[i], u2);
+            }
+            const float yn = sqrtf(yy) * 1.0001f;
+            const float want = (yn + tb.cmin1) * (yn + tb.cmin1) * 1.0001f + 1.0e-3f;
+            fits = fits && yy < 57000.0f && want < 60000.0f;
+            _Float16 sp[3];
+            split3(fits ? want : 0.0f, sp);
+            const float shift = ((float)sp[0] + (float)sp[1]) + (float)sp[2];
+            const float base = shift + yy;
+            const float e1 = 1.01f * (2.0f * kGamma * (tb.cmax1 + yn) * (tb.cmax1 + yn) * 1.01f + 5.0e-4f);
+            // rounding of y1 to fp16, plus the fp32 division, subtraction and scaling
+            const float dy = sqrtf(d2) * 1.0001f + 2.4e-7f * (sqrtf(u2) + 2.0f * P * tb.cmax0) + 1.0e-30f;
+            h8 bop;
+            if (hw == 0) {
+#pragma unroll
+                for (int i = 0; i < G; ++i) bop[i] = (_Float16)(fits ? hf[i] : 0.0f);
+            } else {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) bop[i] = (_Float16)0.0f;
+                if (fits) {
+                    bop[0] = (_Float16)-1.0f;
+                    bop[1] = (_Float16)-1.0f;
+                    bop[2] = (_Float16)-1.0f;
+                    bop[3] = sp[0];
+                    bop[4] = sp[1];
+                    bop[5] = sp[2];
+                }
+            }
+            // a column that does not fit takes its whole group out of the filter
+            const bool colbad = live && !fits;
+            // 8 row tiles; the unit before is reduced while the matrix core works
+            int best = kNoKey, second = kNoKey;
+            f16v acc[2];
+            const f16v z = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
+            auto reduce = [&](const f16v &a, int tile) {
+                int m = imax3(__float_as_int(a[0]), __float_as_int(a[1]), __float_as_int(a[2]));
+                m = imax3(m, __float_as_int(a[3]), __float_as_int(a[4]));
+                m = imax3(m, __float_as_int(a[5]), __float_as_int(a[6]));
+                m = imax3(m, __float_as_int(a[7]), __float_as_int(a[8]));
+                m = imax3(m, __float_as_int(a[9]), __float_as_int(a[10]));
+                m = imax3(m, __float_as_int(a[11]), __float_as_int(a[12]));
+                m = imax3(m, __float_as_int(a[13]), __float_as_int(a[14]));
+                m = max(m, __float_as_int(a[15]));
+                const int key = and_or(m, vmask, (unsigned)tile);
+                second = imed3(best, second, key);
+                best = max(best, key);
+            };
+            acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a1[0], bop, z, 0, 0, 0);
+#pragma unroll
+            for (int tl = 1; tl < 8; ++tl) {
+                acc[tl & 1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(a1[tl], bop, z, 0, 0, 0);
+                reduce(acc[(tl - 1) & 1], tl - 1);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            reduce(acc[1], 7);
+            if (!live || !fits) best = second = kNoKey;
+
+            // ---- the group's 16 lanes: (col & ~7) + 0..7 in both halves
+            // the lane whose best key stands for the smallest distance (keys of different columns
+            // are closenesses relative to different bases: the distances are what compares)
+            const float dist = best == kNoKey ? __builtin_huge_valf() : fmaxf(base - key_upper(best), 0.0f);
+            unsigned long long bk = ((unsigned long long)__float_as_uint(dist) << 32) | (unsigned)lane;
+#pragma unroll
+            for (int m = 1; m < 8; m <<= 1) {
+                const unsigned long long o = __shfl_xor(bk, m);
+                bk = o < bk ? o : bk;
+            }
+            {
+                const unsigned long long o = __shfl_xor(bk, 32);
+                bk = o < bk ? o : bk;
+            }
+            const int glane = (int)(bk & 63ull);
+            const int gkey = __shfl(best, glane);
+            unsigned gbad = colbad ? 1u : 0u;
+#pragma unroll
+            for (int m = 1; m < 8; m <<= 1) gbad |= __shfl_xor(gbad, m);
+            gbad |= __shfl_xor(gbad, 32);
+            bool open = gbad != 0u || gkey == kNoKey;   // filter left (or nothing to look at)
+            // reference objective of the 16 pairs behind a key: lane (e, hw) takes codeword
+            // e + 8 hw of the key's half tile
+            const double sd = (double)s;
+            float tt[G];
+#pragma unroll
+            for (int i = 0; i < G; ++i) tt[i] = w.t[gl][i];
+            double wobj = __builtin_huge_val();
+            int widx = 0x7fffffff;
+            auto eval_key = [&](int key, int klane) {
+                const int tile = key & (int)kKeyMask;
+                const int khw = klane >> 5, ke = klane & 7;
+                const int c0 = w.keep[gl][ke];
+                const int c1 = tile * 32 + khw * 16 + e + 8 * hw;
+                const double o = pair_objective(&tb.c0[c0 * G], &tb.c1[c1 * G], sd, tt);
+                const int tie = c0 * 256 + c1;
+                if (better(o, tie, wobj, widx)) {
+                    wobj = o;
+                    widx = tie;
+                }
+            };
+            auto group_min = [&](double &o, int &i) {
+#pragma unroll
+                for (int m = 1; m < 8; m <<= 1) {
+                    const double oo = __shfl_xor(o, m);
+                    const int ii = __shfl_xor(i, m);
+                    if (better(oo, ii, o, i)) {
+                        o = oo;
+                        i = ii;
+                    }
+                }
+                const double oo = __shfl_xor(o, 32);
+                const int ii = __shfl_xor(i, 32);
+                if (better(oo, ii, o, i)) {
+                    o = oo;
+                    i = ii;
+                }
+            };
+            if (!open) eval_key(gkey, glane);
+            double gobj = wobj;
+            int gidx = widx;
+            group_min(gobj, gidx);
+            const double o_prev = w.o_prev[gl];
+            const double e_star = gobj < o_prev ? gobj : o_prev;
+            // every pair that was not evaluated and could still reach E* sits behind a key whose
+            // upper bound is at least kcut (fp32, every rounding covered)
+            const float rr = sqrtf(__double2float_ru(e_star)) * (P / fabsf(s)) * 1.000002f + tb.dC1 + dy;
+            float reach2 = rr * rr * 1.000002f;
+            if (!(reach2 == reach2)) reach2 = __builtin_huge_valf();
+            const float kcut = (base * 0.999999f - reach2 * 1.000001f) - e1 - 1.0e-6f * (base + reach2);
+            const bool no_bound = !(kcut > -3.0e38f);
+            bool pending = !open && live && fits && lane != glane && best != kNoKey &&
+                           (no_bound || key_upper(best) >= kcut);
+            bool lopen = !open && live && fits && second != kNoKey && (no_bound || key_upper(second) >= kcut);
+            // keys of the other lanes at or above their cut: evaluated by the group as well
+            const unsigned long long gmask = (0xFFull << (lane & 24)) | (0xFFull << (32 + (lane & 24)));
+            for (;;) {
+                const unsigned long long pb = __ballot(pending) & gmask;
+                if (!__any(pb != 0ull)) break;
+                if (pb) {
+                    const int src = __ffsll((long long)pb) - 1;
+                    const int key = __shfl(best, src);
+                    eval_key(key, src);
+                    if (lane == src) pending = false;
+                }
+            }
+            gobj = wobj;
+            gidx = widx;
+            group_min(gobj, gidx);
+            unsigned go = lopen ? 1u : 0u;
+#pragma unroll
+            for (int m = 1; m < 8; m <<= 1) go |= __shfl_xor(go, m);
+            go |= __shfl_xor(go, 32);
+            open = open || go != 0u;
+            if (head) {
+                const int n = w.n[gl];
+                if (!gok || open) {
+                    const unsigned long long slot = atomicAdd(redo_count, 1ull);
+                    redo_list[slot] = n;
+                } else {
+                    if (gidx != 0x7fffffff && gobj < o_prev) {
+                        codes[(int64_t)n * 2] = (uint16_t)(gidx >> 8);
+                        codes[(int64_t)n * 2 + 1] = (uint16_t)(gidx & 255);
+                        ++changed;
+                    }
+                    ++fast;
+                }
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+    }
+    for (int off = 32; off > 0; off >>= 1) {
+        changed += __shfl_xor(changed, off);
+        fast += __shfl_xor(fast, off);
+    }
+    if (lane == 0) {
+        if (changed && num_changed) atomicAdd(num_changed, (unsigned long long)changed);
+        if (fast && stat_fast) atomicAdd(stat_fast, (unsigned long long)fast);
+    }
+}
+
+}  // namespace
+
+pv_status pv_launch_beam_2x8_f16(pv_ctx *ctx, const float *T, const float *codebooks,
+                                 const float *scales, const int32_t *group_idx, int64_t k,
+                                 int32_t beam_width, uint16_t *codes, int64_t *num_changed,
+                                 unsigned long long *stat_fast, int32_t *redo_list,
+                                 unsigned long long *redo_count, int gpr, int N)
+{
+    int64_t blocks = (k + 64 * kWaves - 1) / (64 * kWaves);
+    if (blocks > 768) blocks = 768;
+    if (blocks < 1) blocks = 1;
+    hipLaunchKernelGGL(k_beam_2x8_f16, dim3((unsigned)blocks), dim3(kBlock), 0, ctx->stream, T,
+                       codebooks, scales, group_idx, k, beam_width, codes,
+                       reinterpret_cast<unsigned long long *>(num_changed), stat_fast, redo_list,
+                       redo_count, gpr, N);
+    return PV_OK;
+}

@@ -983,8 +983,16 @@ pv_status pv_launch_beam(pv_ctx *ctx, const pv_layout *l, const float *T, const 
                        st0 + 4, gpr, N);                                                           \
     hipLaunchKernelGGL(k_beam_2x8<G_>, dim3((unsigned)rblocks), dim3(kBlock), 0, ctx->stream, T,   \
                        codebooks, scales, redo, k, beam_width, codes, nc, st0 + 1, gpr, N, st0 + 4)
-            if (g == 8) { PV_BEAM2(8); }
-            else { PV_BEAM2(16); }
+            if (g == 8) {
+                // fp32 / fp16 filter (pv_beam.hip), then the exact kernel on what it leaves
+                pv_launch_beam_2x8_f16(ctx, T, codebooks, scales, group_idx, k, beam_width, codes,
+                                       num_changed, st0, redo, st0 + 4, gpr, N);
+                hipLaunchKernelGGL(k_beam_2x8<8>, dim3((unsigned)rblocks), dim3(kBlock), 0, ctx->stream,
+                                   T, codebooks, scales, redo, k, beam_width, codes, nc, st0 + 1, gpr, N,
+                                   st0 + 4);
+            } else {
+                PV_BEAM2(16);
+            }
 #undef PV_BEAM2
             PV_HIP(ctx, hipGetLastError());
             return PV_OK;

@@ -133,6 +133,13 @@ pv_status pv_launch_exact_scan(pv_ctx *ctx, const pv_layout *l, const float *T,
 pv_status pv_launch_beam(pv_ctx *ctx, const pv_layout *l, const float *T, const float *codebooks,
                          const float *scales, const int32_t *group_idx, int64_t k,
                          int32_t beam_width, uint16_t *codes, int64_t *num_changed);
+// two 8-bit codebooks, g = 8, beam <= 8: fp32 / fp16 matrix-core filter; groups it cannot
+// certify are appended to redo_list (count in *redo_count) for the exact kernel
+pv_status pv_launch_beam_2x8_f16(pv_ctx *ctx, const float *T, const float *codebooks,
+                                 const float *scales, const int32_t *group_idx, int64_t k,
+                                 int32_t beam_width, uint16_t *codes, int64_t *num_changed,
+                                 unsigned long long *stat_fast, int32_t *redo_list,
+                                 unsigned long long *redo_count, int gpr, int N);
 bool pv_mfma_supported(const pv_layout *l);
 pv_status pv_launch_mfma_search(pv_ctx *ctx, const pv_layout *l, const float *T,
                                 const float *codebooks, const float *scales,
