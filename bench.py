@@ -25,19 +25,33 @@ if str(ROOT) not in sys.path:
 PEAK_MFMA_F16 = 2500.0   # TFLOP/s dense fp16/bf16 matrix-core peak of MI355X
 PEAK_HBM = 8000.0        # GB/s
 PEAK_F64 = 78.6          # TFLOP/s fp64 vector (256 CU x 4 SIMD x 16 lanes x 2 (fma) x 2.4 GHz)
-
-# HBM bytes per launch of the dominant kernel, from rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this
-# same command (profiles/c2_4096x4096_1x16_hbm_traffic.txt; FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0 KiB)
-MEASURED_TRAFFIC_BYTES = {("k_score_mfma", "c2_4096x4096_1x16"): (10890.0 * 2.0 + 10744.1) * 1024.0}
+PEAK_F32 = 157.3         # TFLOP/s fp32 vector
 
 
-def run_stack(args) -> int:
+def measured_traffic(kernel: str, workload: str):
+    """HBM bytes per launch of `kernel` on `workload`, from the rocprofv3 FETCH_SIZE / WRITE_SIZE
+    summary under profiles/ (a line 'traffic_bytes_per_launch <kernel> <bytes> commit <hash>'),
+    or None when no summary of that workload has been taken."""
+    f = ROOT / "profiles" / f"{workload}_hbm_traffic.txt"
+    for line in f.read_text().splitlines() if f.exists() else ():
+        w = line.split()
+        if len(w) >= 3 and w[0] == "traffic_bytes_per_launch" and w[1] == kernel:
+            return float(w[2]), (w[4] if len(w) >= 5 else None)
+    return None, None
+
+
+def run_stack(args, with_oracle: bool):
     """The whole-model sweep: 32 decoder blocks x 7 linear layers of the Llama-2-7B shapes
     (6.476e9 parameters, 809.5 M groups, 1x16 codebook per matrix, tau = 0.01 per matrix).
     Inputs are drawn ON THE DEVICE with torch's generator (same distributions as workloads.py,
-    whose host-side tensors for this configuration would need 78 GB of host memory); the
-    per-matrix path at these shapes is checked against the oracle in tests/test_gpu_fullsize.py.
-    One step = dequantize -> targets + selection -> re-encode -> dequantize for all 224 matrices."""
+    whose host-side tensors for this configuration would need 78 GB of host memory).
+    One step = dequantize -> targets + selection -> re-encode -> dequantize for all 224 matrices,
+    dealt to several contexts on streams of their own.  With `with_oracle` one device-drawn
+    matrix is copied to the host before the sweep and its result afterwards: the oracle repeats
+    its step there (ids in full, the search on a bounded sample of the selected groups), which
+    both checks what the sweep computed and gives the oracle's rate on this configuration.
+    Returns the result line as a dict."""
+    import numpy as np
     import torch
 
     import workloads
@@ -66,6 +80,7 @@ def run_stack(args) -> int:
             N = o * i // 8
             k = workloads.num_selected(N, 0.01)
             m = {
+                "name": f"layer{layer}.{name}",
                 "lay": lay, "k": k, "n": o * i,
                 "W": torch.randn(o, i, generator=gen, device=dev) * 0.02,
                 "G": torch.randn(o, i, generator=gen, device=dev) * 1e-4,
@@ -82,6 +97,16 @@ def run_stack(args) -> int:
     nchs = [torch.zeros(1, dtype=torch.int64, device=dev) for _ in range(nstreams)]
     torch.cuda.synchronize()
 
+    # the matrix the oracle repeats: one of the wide ones in the middle of the stack, which the
+    # sweep reaches on a stream other than the first
+    probe = next(j for j, m in enumerate(mats) if m["name"] == "layer17.down_proj")
+    host = None
+    if with_oracle:
+        m = mats[probe]
+        host = {key: m[key].cpu().numpy() for key in ("W", "G", "cb", "sc")}
+        host["codes0"] = m["codes"].view(torch.int16).cpu().numpy().view(np.uint16)
+        codes0_dev = [mm["codes"].view(torch.int16).clone() for mm in mats]   # restored after the check
+
     def step(lanes=nstreams):
         for j, m in enumerate(mats):
             c = j % lanes
@@ -94,11 +119,41 @@ def run_stack(args) -> int:
             cx.pv_reencode_groups(lay, t, m["cb"], m["sc"], m["idx"], m["k"], 1, m["codes"], nch)
             cx.pv_dequantize(lay, m["codes"], m["cb"], m["sc"], wq)
 
-    steps = min(args.steps, 5)
-    warmup = min(args.warmup, 1)
+    steps = max(1, min(args.steps, 5))
+    warmup = max(1, min(args.warmup, 1))
     for _ in range(warmup):
         step()
     torch.cuda.synchronize()
+    check = None
+    if with_oracle:
+        # the first (warm-up) sweep started from the drawn codes: that is the one the oracle repeats
+        import oracle
+        m = mats[probe]
+        got = m["codes"].view(torch.int16).cpu().numpy().view(np.uint16)
+        idx_gpu = m["idx"].cpu().numpy()
+        t1 = time.perf_counter()
+        T_ref = oracle.encode_targets(host["W"], host["G"], 1.0)
+        idx_ref = oracle.select_topk_groups(T_ref, host["W"], 8, m["k"])
+        t2 = time.perf_counter()
+        sample = idx_ref[:: max(1, len(idx_ref) // 8192)]
+        new_ref, info = oracle.reencode_groups(T_ref, host["cb"], host["sc"], sample, host["codes0"])
+        t3 = time.perf_counter()
+        differ = np.nonzero(got.reshape(-1)[sample] != new_ref.reshape(-1)[sample])[0]
+        ok = bool(np.array_equal(idx_gpu, idx_ref)) and bool(info["near_tie"][differ].all())
+        untouched = np.ones(got.size, bool)
+        untouched[idx_ref] = False
+        ok = ok and bool(np.array_equal(got.reshape(-1)[untouched], host["codes0"].reshape(-1)[untouched]))
+        # per-group cost of the search does not depend on the data: scale the sample to the matrix
+        secs = (t2 - t1) + (t3 - t2) * (m["k"] / len(sample))
+        check = {"value": m["k"] / secs, "unit": "groups/s", "cores": oracle.num_threads(), "kind": "oracle",
+                 "sample": f"{m['name']} of the device-drawn stack copied to the host: targets and selection "
+                           f"in full ({t2 - t1:.2f} s), search on {len(sample)} of {m['k']} selected groups "
+                           f"({t3 - t2:.2f} s) and scaled; the rate is per matrix, the stack has 224",
+                 "ids_equal_oracle": bool(np.array_equal(idx_gpu, idx_ref)),
+                 "codes_equal_oracle_on_sample": ok, "sample_groups_differing_on_near_ties": int(len(differ))}
+        for mm, c0 in zip(mats, codes0_dev):
+            mm["codes"].view(torch.int16).copy_(c0)
+        torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(steps):
         step()
@@ -113,6 +168,7 @@ def run_stack(args) -> int:
         t_ms, n = ctx.pv_timing_read(name)
         if n:
             kern[name] = {"ms_per_step": t_ms, "launches_per_step": n}
+    ctx.pv_timing_enable(False)
     flops = 2.0 * total_k * 65536 * 8
     a = flops / (kern["score_mfma"]["ms_per_step"] * 1e-3) / 1e12
     out = {
@@ -124,15 +180,16 @@ def run_stack(args) -> int:
                    "num_codebooks": 1, "nbits": 16, "streams": nstreams},
         "roofline": {"kernel": "k_score_mfma", "bound": "mfma", "achieved": a, "peak": PEAK_MFMA_F16,
                      "unit": "TFLOP/s", "frac": a / PEAK_MFMA_F16, "traffic": None},
-        "cpu_baseline": None,
-        "note": "the oracle is not timed on this configuration (4.2e12 double operations); see the "
-                "single-matrix workloads for its rate",
+        "cpu_baseline": check,
         "streaming_GBps": (12.0 + 0.5 + 2 * 4.25) * total_params
         / ((kern["dequantize"]["ms_per_step"] + kern["encode_targets"]["ms_per_step"]) * 1e-3) / 1e9,
         "kernels": kern,
     }
-    print(json.dumps(out))
-    return 0
+    for c in ctxs:
+        c.close()
+    del mats, Ts, Wqs
+    torch.cuda.empty_cache()
+    return out
 
 
 def main() -> int:
@@ -160,6 +217,9 @@ def main() -> int:
     ap.add_argument("--sparse-a9", action="store_true",
                     help="last dequantize of the step rewrites only the re-encoded groups "
                          "(pv_dequantize_groups); same weights, not the default")
+    ap.add_argument("--no-stack", dest="stack", action="store_false",
+                    help="leave out the `stack` key (the 224-matrix sweep of c4_llama2_7b_stack, "
+                         "which the default line carries beside the single-matrix figure)")
     ap.add_argument("--streams", type=int, default=4,
                     help="c4_llama2_7b_stack only: contexts/streams the 224 matrices are dealt to")
     args = ap.parse_args()
@@ -175,7 +235,8 @@ def main() -> int:
     from paper_2405_14852_amd import Layout, PVContext
 
     if args.workload == "c4_llama2_7b_stack":
-        return run_stack(args)
+        print(json.dumps(run_stack(args, with_oracle=not args.no_cpu_baseline)))
+        return 0
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -253,10 +314,18 @@ def main() -> int:
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    # the K timed steps run as (up to) five batches with a synchronisation after each, so that
+    # the line also carries the spread; ms_per_step is the whole region over K
+    nb = min(5, args.steps)
+    sizes = [args.steps // nb + (1 if b < args.steps % nb else 0) for b in range(nb)]
+    batch_ms = []
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
+    for n in sizes:
+        tb = time.perf_counter()
+        for _ in range(n):
+            step()
+        torch.cuda.synchronize()
+        batch_ms.append(1e3 * (time.perf_counter() - tb) / n)
     dt = time.perf_counter() - t0
     ms_per_step = 1e3 * dt / args.steps
     changed = int(nch.item())
@@ -293,24 +362,35 @@ def main() -> int:
                     "peak": PEAK_HBM, "unit": "GB/s", "frac": a / PEAK_HBM, "traffic": None}
     elif dominant == "score_mfma":
         a = flops_contraction / (kern[dominant]["avg_ms"] * 1e-3) / 1e12
+        traffic, at_commit = measured_traffic("k_score_mfma", args.workload)
         roofline = {"kernel": "k_score_mfma", "bound": "mfma", "achieved": a, "peak": PEAK_MFMA_F16,
                     "unit": "TFLOP/s", "frac": a / PEAK_MFMA_F16,
-                    "traffic": MEASURED_TRAFFIC_BYTES.get(("k_score_mfma", args.workload))}
+                    "traffic": traffic, "traffic_measured_at_commit": at_commit}
     elif dominant in ("exact_scan", "beam"):
         # algorithmic double-precision work: 2 g FLOP (one multiply-add per dimension) for every
         # objective the search is defined to evaluate, whatever form the kernel computes it in
         tuples = k * ((1 << B) if M == 1 else (1 << B) * (1 + (M - 1) * wl.beam_width))
         fl = tuples * g * 2.0
-        a = fl / (kern[dominant]["avg_ms"] * 1e-3) / 1e12
-        roofline = {"kernel": "k_" + dominant, "bound": "alu", "achieved": a, "peak": PEAK_F64,
-                    "unit": "TFLOP/s", "frac": a / PEAK_F64, "traffic": None}
+        # the beam launches of one step (filter + exact remainder) count as one unit of work
+        a = fl / (kern[dominant]["ms_per_step"] * 1e-3) / 1e12
+        filtered = dominant == "beam" and args.search_mode == 0 and M == 2 and B == 8
+        # the filtered 2 x 8-bit search evaluates in fp32 / fp16 with fp32 accumulation (the
+        # contraction has only g terms per objective, its cost is the comparison work on the
+        # vector units); the exact kernels evaluate in fp64
+        peak = PEAK_F32 if filtered else PEAK_F64
+        roofline = {"kernel": "k_beam_2x8_f16 + k_beam_2x8" if filtered else "k_" + dominant,
+                    "bound": "alu", "achieved": a, "peak": peak, "unit": "TFLOP/s", "frac": a / peak,
+                    "traffic": None}
+        if filtered:
+            roofline["frac_of_mfma_f16_peak"] = a / PEAK_MFMA_F16
     else:
         per_param = {"encode_targets": 28.0 + 4.0 / g if args.adam else 12.0 + (0.0 if args.separate_calls else 4.0 / g),
                      "group_scores": 8.0 + 4.0 / g,
-                     "dequantize": 4.0 + 2.0 * M / g}.get(dominant, 0.0)
-        a = per_param * params / (kern[dominant]["avg_ms"] * 1e-3) / 1e9
-        roofline = {"kernel": "k_" + dominant, "bound": "hbm", "achieved": a, "peak": PEAK_HBM,
-                    "unit": "GB/s", "frac": a / PEAK_HBM, "traffic": None}
+                     "dequantize": 4.0 + 2.0 * M / g}.get(dominant)
+        if per_param is not None:     # a kernel with no traffic model here gets no roofline at all
+            a = per_param * params / (kern[dominant]["avg_ms"] * 1e-3) / 1e9
+            roofline = {"kernel": "k_" + dominant, "bound": "hbm", "achieved": a, "peak": PEAK_HBM,
+                        "unit": "GB/s", "frac": a / PEAK_HBM, "traffic": None}
 
     # ceilings of this machine at this moment, measured with two kernels of the library: a plain
     # 64 MiB streaming copy and a loop of nothing but fp16 matrix instructions
@@ -417,6 +497,8 @@ def main() -> int:
                             "separate" if args.separate_calls else "fused targets+select"},
         "roofline": roofline,
         "cpu_baseline": cpu,
+        "batches": {"count": nb, "ms_per_step_median": float(np.median(batch_ms)),
+                    "ms_per_step_min": min(batch_ms), "ms_per_step_max": max(batch_ms)},
         "reencode_only_groups_per_s": k / (reenc_ms * 1e-3) if reenc_ms else None,
         "scoring_algorithmic_TFLOPs": (flops_contraction / (kern["score_mfma"]["avg_ms"] * 1e-3) / 1e12
                                        if "score_mfma" in kern else None),
@@ -427,6 +509,14 @@ def main() -> int:
     if args.path == "trust_ratio":
         out["trust_ratio"] = {"ratio": 0.01, "candidates": k, "kept": int(napp.item()),
                               "change_sq": float(tstats[0].item()), "norm_sq": float(tstats[1].item())}
+    if args.stack:
+        # the whole-model sweep beside the single-matrix figure (a few seconds of GPU time)
+        ctx.close()
+        del W, G, T, Wq
+        torch.cuda.empty_cache()
+        st = run_stack(args, with_oracle=not args.no_cpu_baseline)
+        out["stack"] = {key: st[key] for key in ("value", "unit", "steps", "ms_per_step", "config",
+                                                  "roofline", "cpu_baseline", "streaming_GBps")}
     print(json.dumps(out))
     return 0
 
