@@ -50,6 +50,12 @@ def _load():
         lib.pvo_select_topk_groups.argtypes = [i64, i64, i32, p, p, i64, p, p]
         lib.pvo_reencode_groups.argtypes = [i64, i64, i32, i32, i32, p, p, p, p, i64, i32, i32,
                                             p, p, p, p, p]
+        lib.pvo_reencode_stochastic.argtypes = [i64, i64, i32, i32, p, p, p, p, i64, i32, ctypes.c_uint64,
+                                                p, p, p, p, p, p, p]
+        lib.pvo_random_bits.argtypes = [ctypes.c_uint64, ctypes.c_uint64]
+        lib.pvo_random_bits.restype = ctypes.c_uint64
+        lib.pvo_uniform.argtypes = [ctypes.c_uint64, ctypes.c_uint64]
+        lib.pvo_uniform.restype = ctypes.c_double
         lib.pvo_group_objective.argtypes = [i64, i64, i32, i32, i32, p, p, p, p, i64, p, p]
         lib.pvo_dequantize.argtypes = [i64, i64, i32, i32, i32, p, p, p, p]
         lib.pvo_encode_targets_adam.argtypes = [i64, i64, p, p, p, p, i64, f32, f32, f32, f32, p]
@@ -147,6 +153,66 @@ def reencode_groups(T, codebooks, scales, group_idx, codes, beam_width: int = 1,
         raise ValueError("pvo_reencode_groups failed")
     return new, {"num_changed": int(changed.value), "near_tie": near.astype(bool),
                  "obj_new": obj_new, "obj_prev": obj_prev}
+
+
+def uniform(seed: int, counter: int) -> float:
+    """The variate in [0, 1) that the stochastic rounding draws for group `counter`."""
+    return float(_load().pvo_uniform(int(seed) & (2 ** 64 - 1), int(counter)))
+
+
+def random_bits(seed: int, counter: int) -> int:
+    return int(_load().pvo_random_bits(int(seed) & (2 ** 64 - 1), int(counter)))
+
+
+def reencode_stochastic(T, codebooks, scales, group_idx, codes, power: int = 5, seed: int = 0):
+    """App. F, K = 2 nearest codewords, p proportional to distance^-power (App. K: power 5).
+    Returns (new_codes, info) and leaves `codes` untouched."""
+    T = _f32(T)
+    cb = _f32(codebooks)
+    sc = _f32(scales)
+    M, csize, g = cb.shape
+    if M != 1:
+        raise ValueError("stochastic rounding is defined for one codebook")
+    B = int(csize).bit_length() - 1
+    assert (1 << B) == csize
+    out_f, in_f = T.shape
+    idx = np.ascontiguousarray(group_idx, dtype=np.int32)
+    k = idx.shape[0]
+    new = np.ascontiguousarray(codes, dtype=np.uint16).copy()
+    assert new.shape == (out_f, in_f // g, 1), new.shape
+    changed = ctypes.c_int64(0)
+    two = np.zeros((k, 2), dtype=np.int32)
+    obj = np.zeros((k, 2), dtype=np.float64)
+    pn = np.zeros(k, dtype=np.float64)
+    u = np.zeros(k, dtype=np.float64)
+    near = np.zeros(k, dtype=np.uint8)
+    rc = _load().pvo_reencode_stochastic(out_f, in_f, g, B, _ptr(T), _ptr(cb), _ptr(sc), _ptr(idx), k,
+                                         int(power), int(seed) & (2 ** 64 - 1), _ptr(new),
+                                         ctypes.addressof(changed), _ptr(two), _ptr(obj), _ptr(pn),
+                                         _ptr(u), _ptr(near))
+    if rc:
+        raise ValueError("pvo_reencode_stochastic failed")
+    return new, {"num_changed": changed.value, "nearest_two": two, "objective_two": obj,
+                 "p_nearest": pn, "variate": u, "near_tie": near.astype(bool)}
+
+
+def ste_step(buffer, G, alpha: float, codebooks, scales, codes, k=None, beam_width: int = 1):
+    """One step of straight-through estimation (App. E): the auxiliary full-precision buffer takes
+    the gradient step (computed at the quantised weights, passed in as G), then the codes are moved
+    to approximate the buffer best in L2.  k = None re-encodes every group (plain STE); with k the
+    step is restricted to the k groups whose buffer is farthest from the current quantised weights
+    (the combination of subspace updates with STE, Sec. 4.3).  Returns (buffer, codes, info)."""
+    cb = _f32(codebooks)
+    g = cb.shape[2]
+    new_buffer = encode_targets(buffer, G, alpha)
+    out_f, in_f = new_buffer.shape
+    if k is None:
+        idx = np.arange(out_f * (in_f // g), dtype=np.int32)
+    else:
+        idx = select_topk_groups(new_buffer, dequantize(codes, codebooks, scales), g, k)
+    new_codes, info = reencode_groups(new_buffer, codebooks, scales, idx, codes, beam_width=beam_width)
+    info["group_idx"] = idx
+    return new_buffer, new_codes, info
 
 
 def reencode_trust_ratio(T, W, codebooks, scales, codes, k_max: int, chunk: int, ratio: float,

@@ -32,6 +32,13 @@
  *                           to the M = 1 definition, beam 1 = one pass of greedy
  *                           single-index descent (App. D).  Beyond those bounds
  *                           the beam result is PARITY UNPINNED.
+ *   pvo_reencode_stochastic App. F: the K = 2 nearest-codeword approximation of stochastic
+ *                           rounding, probabilities proportional to distance^-power (App. K:
+ *                           temperature 0.2, power 5); the variates come from a counter-based
+ *                           generator defined here (pinned by the exact probabilities of a
+ *                           two-point grid, the unbiasedness of the scalar case, App. F's
+ *                           biased counter-example, brute force on the two nearest and the
+ *                           reference output of the generator's published test vector).
  *   pvo_dequantize          Alg. 3 line 1: W = scale_row * sum_m codeword_m.
  *   pvo_dequantize_scalar / pvo_reencode_scalar  App. K's scalar representation (uniform grid,
  *                           block-wise scale and zero point): the V step is rounding to the
@@ -351,6 +358,89 @@ int pvo_reencode_groups(int64_t out_features, int64_t in_features, int g, int M,
         free(cand);
     }
     if (failed) return PVO_ERR;
+    if (num_changed) *num_changed = changed;
+    return PVO_OK;
+}
+
+/* ------------------------------------------------------- stochastic rounding */
+
+/* Random bits of (seed, counter): the output function of the SplitMix64 generator (Steele, Lea
+ * and Flood, 2014) on the state seed + (counter + 1) * its odd increment.  Counter-based: one
+ * variate per weight group, whatever order the groups are visited in. */
+uint64_t pvo_random_bits(uint64_t seed, uint64_t counter)
+{
+    uint64_t z = seed + (counter + 1u) * UINT64_C(0x9E3779B97F4A7C15);
+    z = (z ^ (z >> 30)) * UINT64_C(0xBF58476D1CE4E5B9);
+    z = (z ^ (z >> 27)) * UINT64_C(0x94D049BB133111EB);
+    return z ^ (z >> 31);
+}
+
+/* the top 53 bits as a double in [0, 1) */
+double pvo_uniform(uint64_t seed, uint64_t counter)
+{
+    return (double)(pvo_random_bits(seed, counter) >> 11) * 0x1.0p-53;
+}
+
+/* Stochastic rounding for vector quantisation, the K = 2 approximation of App. F: find the two
+ * codewords nearest to the target (objective of Eq. 7 restricted to the group; equal objectives
+ * in index order) and round to one of them with probability proportional to
+ * distance^(-power), distance = sqrt(objective).  power = 1 is the formula of App. F,
+ * power = 5 the temperature 0.2 of App. K.  The variate of group n is pvo_uniform(seed, n); the
+ * nearest codeword is taken when it is below p(nearest) = 1 / (1 + (d_1 / d_2)^power).
+ * Reading: a target that coincides with a codeword is rounded to it with certainty, and a
+ * codebook of one codeword leaves no choice.  One codebook only: App. F speaks of a codebook or
+ * lattice, additive codes have no list of "nearest vectors" short of the full product.
+ * Optional outputs per listed group: the two indices, both objectives, p(nearest), the variate
+ * and a flag for decisions that rounding could turn (the second and third objectives, or the
+ * first two, within the near-tie tolerance; the variate within 1e-9 of p). */
+int pvo_reencode_stochastic(int64_t out_features, int64_t in_features, int g, int B,
+                            const float *T, const float *codebook, const float *scales,
+                            const int32_t *group_idx, int64_t k, int power, uint64_t seed,
+                            uint16_t *codes, int64_t *num_changed, int32_t *nearest_two,
+                            double *objective_two, double *p_nearest, double *variate,
+                            uint8_t *near_flags)
+{
+    if (!T || !codebook || !scales || !codes) return PVO_ERR;
+    if (g < 1 || in_features % g || B < 1 || B > 16 || power < 1 || power > 64 || k < 0)
+        return PVO_ERR;
+    if (k > 0 && !group_idx) return PVO_ERR;
+    int64_t gpr = in_features / g, N = out_features * gpr, csize = (int64_t)1 << B;
+    for (int64_t j = 0; j < k; ++j)
+        if (group_idx[j] < 0 || group_idx[j] >= N) return PVO_ERR;
+    int64_t changed = 0;
+#pragma omp parallel for schedule(dynamic, 16) reduction(+ : changed)
+    for (int64_t j = 0; j < k; ++j) {
+        int64_t n = group_idx[j];
+        const float *t = T + n * g;
+        float s = scales[n / gpr];
+        double o1 = INFINITY, o2 = INFINITY, o3 = INFINITY;
+        int64_t c1 = -1, c2 = -1;
+        for (int64_t c = 0; c < csize; ++c) {       /* ascending: '<' keeps the lower index */
+            uint16_t cc = (uint16_t)c;
+            double o = tuple_objective(codebook, 1, csize, g, &cc, s, t);
+            if (o < o1) { o3 = o2; o2 = o1; c2 = c1; o1 = o; c1 = c; }
+            else if (o < o2) { o3 = o2; o2 = o; c2 = c; }
+            else if (o < o3) o3 = o;
+        }
+        double p = 1.0;
+        if (c2 >= 0 && o1 > 0.0) {
+            double r = sqrt(o1 / o2), rn = r;
+            for (int e = 1; e < power; ++e) rn = rn * r;
+            p = 1.0 / (1.0 + rn);
+        }
+        double u = pvo_uniform(seed, (uint64_t)n);
+        int64_t pick = (c2 < 0 || u < p) ? c1 : c2;
+        if (c1 < 0) pick = codes[n];                /* every objective is NaN: keep */
+        changed += (codes[n] != (uint16_t)pick);
+        codes[n] = (uint16_t)pick;
+        if (nearest_two) { nearest_two[2 * j] = (int32_t)c1; nearest_two[2 * j + 1] = (int32_t)c2; }
+        if (objective_two) { objective_two[2 * j] = o1; objective_two[2 * j + 1] = o2; }
+        if (p_nearest) p_nearest[j] = p;
+        if (variate) variate[j] = u;
+        if (near_flags)
+            near_flags[j] = (uint8_t)(c2 >= 0 && (near_tie(o1, o2) || (csize > 2 && near_tie(o2, o3)) ||
+                                                   fabs(u - p) <= 1e-9));
+    }
     if (num_changed) *num_changed = changed;
     return PVO_OK;
 }
