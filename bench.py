@@ -202,11 +202,13 @@ def main() -> int:
                     help="0 = matrix-core filter + exact re-rank, 1 = exact scan only")
     ap.add_argument("--separate-calls", action="store_true",
                     help="pv_encode_targets + pv_select_topk_groups instead of the fused call")
-    ap.add_argument("--path", choices=("vstep", "trust_ratio", "pstep"), default="vstep",
+    ap.add_argument("--path", choices=("vstep", "trust_ratio", "pstep", "stochastic"), default="vstep",
                     help="trust_ratio: the subspace size is found by pv_reencode_trust_ratio "
                          "(W = the dequantised codes, gradient x40 so that codes move, ratio 0.01, "
                          "all k groups of the workload are candidates); pstep: one call of "
-                         "pv_codebook_grads (gradients of codebooks and scales) per step")
+                         "pv_codebook_grads (gradients of codebooks and scales) per step; "
+                         "stochastic: the V step with pv_reencode_groups_stochastic (two nearest "
+                         "codewords, power 5) in place of the nearest-codeword search")
     ap.add_argument("--adam", action="store_true",
                     help="targets from one Adam update and selection by its size in one sweep "
                          "(pv_encode_targets_adam_select, beta 0.9/0.95, lr 3e-3)")
@@ -305,7 +307,10 @@ def main() -> int:
             ctx.pv_select_topk_groups(lay, T, W, k, idx)
         else:   # same outputs, T and W are not read back for the scores
             ctx.pv_encode_targets_select(lay, W, G, wl.alpha, T, k, idx)
-        ctx.pv_reencode_groups(lay, T, cb, sc, idx, k, wl.beam_width, codes, nch)
+        if args.path == "stochastic":
+            ctx.pv_reencode_groups_stochastic(lay, T, cb, sc, idx, k, 5, 2024, codes, nch)
+        else:
+            ctx.pv_reencode_groups(lay, T, cb, sc, idx, k, wl.beam_width, codes, nch)
         if args.sparse_a9:   # Wq holds the old codes' weights: only the re-encoded groups change
             ctx.pv_dequantize_groups(lay, codes, cb, sc, idx, k, Wq)
         else:
@@ -339,7 +344,7 @@ def main() -> int:
     torch.cuda.synchronize()
     kern = {}
     for name in ("dequantize", "encode_targets", "group_scores", "select", "prep", "score_mfma",
-                 "rerank", "exact_scan", "beam", "trust_ratio", "pstep"):
+                 "rerank", "exact_scan", "beam", "trust_ratio", "pstep", "stochastic"):
         ms, n = ctx.pv_timing_read(name)
         if n:
             kern[name] = {"ms_per_step": ms / args.steps, "launches_per_step": n / args.steps,
@@ -348,7 +353,7 @@ def main() -> int:
 
     g, B, M = L.group_size, L.nbits, L.num_codebooks
     params = L.out_features * L.in_features
-    reenc_ms = sum(kern[n]["ms_per_step"] for n in ("prep", "score_mfma", "rerank", "exact_scan", "beam")
+    reenc_ms = sum(kern[n]["ms_per_step"] for n in ("prep", "score_mfma", "rerank", "exact_scan", "beam", "stochastic")
                    if n in kern)
     dominant = max(kern, key=lambda n: kern[n]["ms_per_step"])
     flops_contraction = 2.0 * k * (1 << B) * g * M            # algorithmic: 2*g*2^B per group
@@ -366,7 +371,7 @@ def main() -> int:
         roofline = {"kernel": "k_score_mfma", "bound": "mfma", "achieved": a, "peak": PEAK_MFMA_F16,
                     "unit": "TFLOP/s", "frac": a / PEAK_MFMA_F16,
                     "traffic": traffic, "traffic_measured_at_commit": at_commit}
-    elif dominant in ("exact_scan", "beam"):
+    elif dominant in ("exact_scan", "beam", "stochastic"):
         # algorithmic double-precision work: 2 g FLOP (one multiply-add per dimension) for every
         # objective the search is defined to evaluate, whatever form the kernel computes it in
         tuples = k * ((1 << B) if M == 1 else (1 << B) * (1 + (M - 1) * wl.beam_width))
@@ -454,6 +459,21 @@ def main() -> int:
                          f"stops re-encoding at the chunk that breaks the bound, {tinfo['num_applied']} kept)",
                "codes_equal_oracle": bool(np.array_equal(got, new_ref)),
                "kept_equal_oracle": int(napp.item()) == tinfo["num_applied"]}
+    elif not args.no_cpu_baseline and args.path == "stochastic":
+        import oracle
+        T_ref = oracle.encode_targets(wl.W, wl.G, wl.alpha)
+        idx_ref = oracle.select_topk_groups(T_ref, wl.W, g, k)
+        sample = idx_ref[:: max(1, len(idx_ref) // 4096)]
+        t1 = time.perf_counter()
+        new_ref, sinfo = oracle.reencode_stochastic(T_ref, wl.codebooks, wl.scales, sample, wl.codes,
+                                                    power=5, seed=2024)
+        t2 = time.perf_counter()
+        got = codes.view(torch.int16).cpu().numpy().view(np.uint16)
+        differ = np.nonzero(got.reshape(-1)[sample] != new_ref.reshape(-1)[sample])[0]
+        cpu = {"value": len(sample) / (t2 - t1), "unit": "groups/s", "cores": oracle.num_threads(),
+               "kind": "oracle", "sample": f"the rounding of {len(sample)} of {k} selected groups "
+                                           f"({t2 - t1:.2f} s); search only, no streaming parts",
+               "codes_equal_oracle_on_sample": bool(sinfo["near_tie"][differ].all())}
     elif not args.no_cpu_baseline and not args.adam:
         import oracle
         if args.structured:      # the oracle's own copies of the same inputs

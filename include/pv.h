@@ -163,6 +163,31 @@ pv_status pv_reencode_groups(pv_ctx *ctx, const pv_layout *layout, const float *
                              const int32_t *group_idx, int64_t k, int32_t beam_width,
                              uint16_t *codes, int64_t *num_changed /* NULL ok */);
 
+/* Stochastic rounding of the listed groups (App. F: the K-nearest approximation for vector
+ * quantisation, K = 2; App. K: temperature 0.2, i.e. power = 5), the baseline the paper
+ * compares the V step with.  For each listed group n with target t and row scale s:
+ *   - the two codewords with the smallest obj(c) = || s * codebook[c, :] - t ||^2 are found by
+ *     a scan of all 2^B codewords (double precision on the fp32 inputs, equal objectives in
+ *     index order): c_1 with d_1 = sqrt(obj(c_1)) and c_2 with d_2 >= d_1;
+ *   - p = 1 / (1 + (d_1 / d_2)^power), i.e. probabilities proportional to distance^-power
+ *     (power = 1: the formula of App. F); d_1 = 0 gives p = 1;
+ *   - u = (bits >> 11) * 2^-53 with bits the SplitMix64 output function applied to
+ *     seed + (n + 1) * 0x9E3779B97F4A7C15 (a function of seed and group id only, so the result
+ *     does not depend on the order or partition of the list);
+ *   - the code becomes c_1 if u < p, else c_2.
+ * One codebook only (PV_ERR_UNSUPPORTED for M >= 2; App. F speaks of one codebook or lattice);
+ * group_size <= 64; 1 <= power <= 64.  Pointers, layouts, the treatment of ids outside [0, N),
+ * of unlisted groups, of stored bits above B and of num_changed are those of
+ * pv_reencode_groups.  The straight-through buffer of App. E needs no call of its own:
+ * pv_encode_targets with T aliasing W keeps the buffer, pv_reencode_groups (all groups, or
+ * those pv_select_topk_groups picks against the dequantised weights) projects it. */
+pv_status pv_reencode_groups_stochastic(pv_ctx *ctx, const pv_layout *layout, const float *T,
+                                        const float *codebooks /* f32 [1, 2^B, g] */,
+                                        const float *scales /* f32 [out_features] */,
+                                        const int32_t *group_idx, int64_t k, int32_t power,
+                                        uint64_t seed, uint16_t *codes,
+                                        int64_t *num_changed /* NULL ok */);
+
 /* Subspace size from the trust ratio (Sec. 4.3; App. K, hyperparameter paragraph):
  * tau is not given but found, as the largest number of weights whose update keeps
  *     || x^{k+1} - x^k || / || x^k ||  <  ratio          (the paper uses 0.01)
@@ -257,7 +282,8 @@ typedef enum {
     PV_K_PSTEP = 10,      /* all kernels of pv_codebook_grads                              */
     PV_K_PROBE_COPY = 11, /* pv_probe_copy                                                 */
     PV_K_PROBE_MFMA = 12, /* pv_probe_mfma_f16                                             */
-    PV_K_COUNT = 13
+    PV_K_STOCHASTIC = 13, /* pv_reencode_groups_stochastic                                 */
+    PV_K_COUNT = 14
 } pv_kernel_id;
 
 /* With timing on, each kernel (group) above is bracketed by HIP events on the

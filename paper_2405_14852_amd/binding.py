@@ -18,7 +18,7 @@ _lib = None
 
 KERNEL_IDS = {
     "encode_targets": 0, "group_scores": 1, "select": 2, "prep": 3, "score_mfma": 4,
-    "rerank": 5, "exact_scan": 6, "beam": 7, "dequantize": 8, "trust_ratio": 9, "pstep": 10,
+    "rerank": 5, "exact_scan": 6, "beam": 7, "dequantize": 8, "trust_ratio": 9, "pstep": 10, "stochastic": 13,
     "probe_copy": 11, "probe_mfma": 12,
 }
 
@@ -79,6 +79,7 @@ def load_library():
                                                   i64, vp, vp]
     lib.pv_encode_targets_select.argtypes = [vp, lp, vp, vp, f32, vp, i64, vp, vp]
     lib.pv_reencode_groups.argtypes = [vp, lp, vp, vp, vp, vp, i64, i32, vp, vp]
+    lib.pv_reencode_groups_stochastic.argtypes = [vp, lp, vp, vp, vp, vp, i64, i32, ctypes.c_uint64, vp, vp]
     lib.pv_dequantize.argtypes = [vp, lp, vp, vp, vp, vp]
     lib.pv_dequantize_groups.argtypes = [vp, lp, vp, vp, vp, vp, i64, vp]
     lib.pv_codebook_grads.argtypes = [vp, lp, vp, vp, vp, vp, vp, vp]
@@ -96,7 +97,8 @@ def load_library():
     lib.pv_probe_mfma_f16.argtypes = [vp, i64, vp, ctypes.POINTER(i64)]
     for name in ("pv_create", "pv_select_topk_groups_noalloc", "pv_encode_targets", "pv_encode_targets_adam", "pv_select_topk_groups",
                  "pv_encode_targets_adam_select",
-                 "pv_encode_targets_select", "pv_reencode_groups", "pv_reencode_trust_ratio",
+                 "pv_encode_targets_select", "pv_reencode_groups", "pv_reencode_groups_stochastic",
+                 "pv_reencode_trust_ratio",
                  "pv_codebook_grads", "pv_dequantize_scalar", "pv_reencode_scalar",
                  "pv_dequantize_groups",
                  "pv_dequantize", "pv_set_search_mode", "pv_timing_enable", "pv_timing_reset",
@@ -211,6 +213,17 @@ class PVContext:
             _dev_ptr(scales, torch.float32, "scales"),
             _dev_ptr(group_idx, torch.int32, "group_idx", allow_none=(k == 0)), int(k),
             int(beam_width), _dev_ptr(codes, torch.uint16, "codes"),
+            _dev_ptr(num_changed, torch.int64, "num_changed", allow_none=True)))
+
+    def pv_reencode_groups_stochastic(self, layout: Layout, T, codebooks, scales, group_idx, k: int,
+                                      power: int, seed: int, codes, num_changed=None):
+        lay = layout.c()
+        self._check(self._lib.pv_reencode_groups_stochastic(
+            self._h, ctypes.byref(lay), _dev_ptr(T, torch.float32, "T"),
+            _dev_ptr(codebooks, torch.float32, "codebooks"),
+            _dev_ptr(scales, torch.float32, "scales"),
+            _dev_ptr(group_idx, torch.int32, "group_idx", allow_none=(k == 0)), int(k),
+            int(power), int(seed) & (2 ** 64 - 1), _dev_ptr(codes, torch.uint16, "codes"),
             _dev_ptr(num_changed, torch.int64, "num_changed", allow_none=True)))
 
     def pv_reencode_trust_ratio(self, layout: Layout, T, W, codebooks, scales, k_max: int,

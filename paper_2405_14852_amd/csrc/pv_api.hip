@@ -344,6 +344,32 @@ extern "C" pv_status pv_reencode_groups(pv_ctx *ctx, const pv_layout *l, const f
                                 num_changed);
 }
 
+extern "C" pv_status pv_reencode_groups_stochastic(pv_ctx *ctx, const pv_layout *l, const float *T,
+                                                   const float *codebooks, const float *scales,
+                                                   const int32_t *group_idx, int64_t k,
+                                                   int32_t power, uint64_t seed, uint16_t *codes,
+                                                   int64_t *num_changed)
+{
+    if (!ctx) return PV_ERR_INVALID_ARG;
+    pv_status st = check_layout(ctx, l);
+    if (st != PV_OK) return st;
+    st = check_reencode_args(ctx, l, k, 1, T, codebooks, scales, codes);
+    if (st != PV_OK) return st;
+    if (l->num_codebooks != 1)
+        return pv_fail(ctx, PV_ERR_UNSUPPORTED, "stochastic rounding is defined for one codebook");
+    if (power < 1 || power > 64)
+        return pv_fail(ctx, PV_ERR_INVALID_ARG, "power = %d outside [1, 64]", (int)power);
+    if (k > 0 && !group_idx) return pv_fail(ctx, PV_ERR_INVALID_ARG, "group_idx is NULL");
+    PV_HIP(ctx, hipSetDevice(ctx->device));
+    if (num_changed) {
+        st = pv_launch_fill_i64(ctx, num_changed, 1, 0);
+        if (st != PV_OK) return st;
+    }
+    if (k == 0) return PV_OK;
+    return pv_launch_round_two_nearest(ctx, l, T, codebooks, scales, group_idx, k, power, seed,
+                                       codes, num_changed);
+}
+
 extern "C" pv_status pv_reencode_trust_ratio(pv_ctx *ctx, const pv_layout *l, const float *T,
                                              const float *W, const float *codebooks,
                                              const float *scales, int64_t k_max, int64_t chunk,
