@@ -231,11 +231,19 @@ pv_status pv_dequantize_groups(pv_ctx *ctx, const pv_layout *layout, const uint1
  *                             scales[o] * G[o, j*g + i]                  f32 [M, 2^B, g]
  *   grad_scales[o]          = sum_j sum_i G[o, j*g + i] * (sum_m codebooks[m, codes[o,j,m], i])
  *                                                                        f32 [out_features], optional
- * Products are exact in double; sums are taken in double and rounded to fp32 once.  A
- * codeword's sum runs over its groups in ascending order (bit-reproducible, and equal to a
- * sequential loop) unless more than 128 groups share the codeword, in which case pieces
- * of 128 are summed and added in order.  A row's scale gradient is a tree sum.  Unused
- * codewords get exactly 0.  Nothing is accumulated into the outputs: they are overwritten. */
+ * Products are exact in double and every result is rounded to fp32 once.  Two routes, both a
+ * function of the inputs only (a second call returns the same bits):
+ *   - the table of M * 2^B * g sums does not fit one block's LDS as 8-byte entries (64 KiB), or
+ *     fewer than 64 groups share a codeword on average: the groups are sorted by code and a
+ *     codeword's sum runs over its groups in ascending order, in double - equal to a
+ *     sequential loop - unless more than 128 groups share the codeword, in which case pieces
+ *     of 128 are summed that way and added in order;
+ *   - else (small codebooks): the terms are added in 64-bit fixed point scaled by a power of
+ *     two taken from max|scales| * max|G|, exact up to 2^-39 of that product per term, in
+ *     any order; if a gradient or a scale is not finite every entry of grad_codebooks is NaN.
+ * A row's scale gradient is a tree sum in double.  Unused codewords get exactly 0.  Nothing
+ * is accumulated into the outputs: they are overwritten.  G and codebooks must be 16-byte
+ * aligned. */
 pv_status pv_codebook_grads(pv_ctx *ctx, const pv_layout *layout, const float *G,
                             const uint16_t *codes, const float *codebooks, const float *scales,
                             float *grad_codebooks, float *grad_scales /* NULL ok */);

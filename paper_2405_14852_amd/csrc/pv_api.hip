@@ -403,6 +403,8 @@ extern "C" pv_status pv_codebook_grads(pv_ctx *ctx, const pv_layout *l, const fl
     if (st != PV_OK) return st;
     if (!G || !codes || !codebooks || !scales || !grad_codebooks)
         return pv_fail(ctx, PV_ERR_INVALID_ARG, "NULL tensor pointer");
+    if (misaligned(G) || misaligned(codebooks))
+        return pv_fail(ctx, PV_ERR_INVALID_ARG, "tensor pointers must be 16-byte aligned");
     if (l->group_size > 64)
         return pv_fail(ctx, PV_ERR_UNSUPPORTED, "codebook gradients support group_size <= 64");
     PV_HIP(ctx, hipSetDevice(ctx->device));

@@ -49,7 +49,7 @@ struct pv_ctx {
     pv_buffer fb_list;      // counters (work-item hand-out) and, for the beam path, the groups left to the exact kernel
     pv_buffer rr_counts;    // u32 [blocks][4]    per-block counters of the re-rank kernel
     pv_buffer trust;        // scratch of the trust-ratio call (saved codes, keys, prefix sums, sort space)
-    pv_buffer pstep;        // scratch of the P-step gradients (keys, sorted order, segment starts, sort space)
+    pv_buffer pstep;        // scratch of the P-step gradients (digit histograms, keys and group ids of the sorting passes, segment starts, piece sums)
 };
 
 // RAII bracket that records HIP events around a group of launches when timing is on.

@@ -5,41 +5,233 @@
 //     d phi / d C_m[c, i] = sum over groups n = (o, j) with b(o,j,m) = c of  s_o * G[n, i]
 //     d phi / d s_o       = sum_j sum_i G[o, j*g + i] * (C_0[b_0, i] + C_1[b_1, i] + ...)
 //
-// The codebook gradient is a scatter-add of N * g values into 2^B * g sums.  Atomics
-// would serialise on popular codewords and give run-dependent roundings; instead the
-// groups are SORTED by code (stable radix sort of 16-bit keys: equal codes stay in
-// ascending group order) and every codeword's segment is summed by g lanes in that
-// order, in double, with exact products - the same sum, in the same order, as a plain
-// loop over the groups.  Segments longer than kLong groups are cut into pieces of kLong,
-// summed by separate teams and added in piece order (a different association:
-// reproducible, but no longer the sequential order).  Small codebooks take another route
-// (k_pg_small below).  The scale gradient is one block-wide tree sum per row.
-#include <hipcub/hipcub.hpp>
-
+// The codebook gradient is a scatter-add of N * g values into 2^B * g sums.  Floating-point
+// atomics would serialise on popular codewords and give run-dependent roundings (and atomics
+// on device memory are slow on a part whose L2 is split over several dies); instead the
+// groups are SORTED by code with a stable radix sort written for this key width - 8 bits a
+// pass, so at most two passes of histogram, prefix sum and scatter, with ranks taken from
+// wave ballots and per-wave counters in LDS so that equal codes keep ascending group order
+// and no atomic touches device memory - and every codeword's segment is summed by g
+// lanes in that order, in double, with exact products: the same sum, in the same order, as a
+// plain loop over the groups.  Segments longer than kLong groups are cut into pieces of kLong
+// that are summed by the teams of one block and added in piece order (a different
+// association from the plain loop: reproducible from run to run, but no longer the sequential
+// rounding).  Small codebooks take another route (k_pg_small below).  The scale gradient is
+// one block-wide tree sum per row.
 #include "pv_internal.h"
 
 namespace {
 
 constexpr int kBlock = 256;
-constexpr int kLong = 128;    // groups per piece: a segment up to this long is summed by one team alone
+constexpr int kLong = 128;       // groups per piece: a segment up to this long is summed by one team alone
+constexpr int kSortBlock = 1024;          // threads of a sorting block: 16 waves
+constexpr int kPer = 8;                   // rounds: keys per thread in a sorting pass
+constexpr int kTile = kSortBlock * kPer;  // keys per block
+constexpr int kSortWaves = kSortBlock / 64;
 
-__global__ __launch_bounds__(kBlock) void k_pg_keys(const uint16_t *__restrict__ codes, int64_t N,
-                                                    int M, int m, unsigned mask,
-                                                    uint16_t *__restrict__ keys,
-                                                    int32_t *__restrict__ vals)
+// digit of key e in this pass; FIRST: the keys are the codes themselves (codebook m of M,
+// masked to B bits), else the keys written by the previous pass
+template <bool FIRST>
+__device__ __forceinline__ unsigned key_at(const uint16_t *__restrict__ keys, int64_t e, int M, int m,
+                                           unsigned mask)
 {
-    const int64_t n = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-    if (n >= N) return;
-    keys[n] = (uint16_t)(codes[n * M + m] & mask);
-    vals[n] = (int32_t)n;
+    return FIRST ? (unsigned)(keys[e * M + m] & mask) : (unsigned)keys[e];
+}
+
+// Key j of this thread: wave w of the block owns the 64 * kPer consecutive keys that start at
+// tile + w * 64 * kPer and takes them 64 at a time, so that (wave, round, lane) order is the
+// order of the keys.
+__device__ __forceinline__ int64_t sort_index(int j)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    return (int64_t)blockIdx.x * kTile + (int64_t)(wave * kPer + j) * 64 + lane;
+}
+
+// hist[d * nblocks + b] = keys of tile b whose digit is d
+template <bool FIRST>
+__global__ __launch_bounds__(kSortBlock) void k_pg_digit_hist(const uint16_t *__restrict__ keys,
+                                                              int64_t N, int M, int m, unsigned mask,
+                                                              int shift, int nblocks,
+                                                              unsigned *__restrict__ hist)
+{
+    __shared__ unsigned h[256];
+    if (threadIdx.x < 256) h[threadIdx.x] = 0u;
+    unsigned k[kPer];
+#pragma unroll
+    for (int j = 0; j < kPer; ++j) {          // all loads in flight before the first is used
+        const int64_t e = sort_index(j);
+        k[j] = key_at<FIRST>(keys, e < N ? e : N - 1, M, m, mask);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < kPer; ++j)
+        if (sort_index(j) < N) atomicAdd(&h[(k[j] >> shift) & 255u], 1u);
+    __syncthreads();
+    if (threadIdx.x < 256) hist[(int64_t)threadIdx.x * nblocks + blockIdx.x] = h[threadIdx.x];
+}
+
+// Row d of the histogram (one block per digit): rowpre[d][b] = keys with digit d in the tiles
+// before b, total[d] = keys with digit d.  The rows do not depend on one another; the offsets
+// of the digits themselves (a prefix sum over 256 totals) are taken by every scatter block.
+__global__ __launch_bounds__(kBlock) void k_pg_row_scan(const unsigned *__restrict__ hist, int nblocks,
+                                                        unsigned *__restrict__ rowpre,
+                                                        unsigned *__restrict__ total)
+{
+    __shared__ unsigned s_wave[kBlock / 64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const unsigned *in = hist + (int64_t)blockIdx.x * nblocks;
+    unsigned *out = rowpre + (int64_t)blockIdx.x * nblocks;
+    unsigned carry = 0;
+    for (int b0 = 0; b0 < nblocks; b0 += kBlock) {
+        const int b = b0 + threadIdx.x;
+        const unsigned cnt = b < nblocks ? in[b] : 0u;
+        unsigned incl = cnt;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const unsigned o = __shfl_up(incl, off);
+            if (lane >= off) incl += o;
+        }
+        __syncthreads();                  // s_wave is reused from the previous round
+        if (lane == 63) s_wave[wave] = incl;
+        __syncthreads();
+        unsigned before = 0, all = 0;
+#pragma unroll
+        for (int w = 0; w < kBlock / 64; ++w) {
+            before += w < wave ? s_wave[w] : 0u;
+            all += s_wave[w];
+        }
+        if (b < nblocks) out[b] = carry + before + incl - cnt;
+        carry += all;
+    }
+    if (threadIdx.x == 0) total[blockIdx.x] = carry;
+}
+
+// Stable scatter of tile b by this pass' digit.  In every round the 64 lanes of a wave find,
+// with one ballot per digit bit, the lanes that hold the same digit; a key's rank is the
+// wave's running count of that digit (wcnt[wave][d], kept in LDS by the last lane of each
+// set) plus the number of such lanes below it.  The counts of the waves are then turned
+// into offsets in wave order, so that keys with equal digits keep the order they came in.
+// The tile is first put in digit order in LDS and written out from there: neighbouring
+// threads then write neighbouring addresses (a run per digit) instead of one line each.
+template <bool FIRST>
+__global__ __launch_bounds__(kSortBlock) void k_pg_digit_scatter(
+    const uint16_t *__restrict__ keys, const int32_t *__restrict__ vals, int64_t N, int M, int m,
+    unsigned mask, int shift, int nblocks, const unsigned *__restrict__ rowpre,
+    const unsigned *__restrict__ total, uint16_t *__restrict__ keys_out,
+    int32_t *__restrict__ vals_out)
+{
+    __shared__ unsigned wcnt[kSortWaves][256];
+    __shared__ unsigned s_first[256];     // first slot of digit d inside the tile
+    __shared__ unsigned s_dest[256];      // where that slot goes in the output
+    __shared__ unsigned s_w4[8];
+    __shared__ uint16_t s_key[kTile];
+    __shared__ int32_t s_val[kTile];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    unsigned k[kPer], rank[kPer];
+    int32_t v[kPer];
+#pragma unroll
+    for (int j = 0; j < kPer; ++j) {
+        const int64_t e = sort_index(j);
+        const int64_t ec = e < N ? e : N - 1;
+        k[j] = key_at<FIRST>(keys, ec, M, m, mask);
+        v[j] = FIRST ? (int32_t)ec : vals[ec];
+    }
+    unsigned dig_total = 0, dig_pre = 0;
+    if (threadIdx.x < 256) {
+        dig_total = total[threadIdx.x];
+        dig_pre = rowpre[(int64_t)threadIdx.x * nblocks + blockIdx.x];
+    }
+    for (int w = threadIdx.x; w < kSortWaves * 256; w += kSortBlock) (&wcnt[0][0])[w] = 0u;
+    __syncthreads();
+    const unsigned long long below = (1ull << lane) - 1ull;
+#pragma unroll
+    for (int j = 0; j < kPer; ++j) {
+        const bool valid = sort_index(j) < N;
+        const unsigned d = (k[j] >> shift) & 255u;
+        unsigned long long same = __ballot(valid);
+#pragma unroll
+        for (int bit = 0; bit < 8; ++bit) {
+            const unsigned long long has = __ballot((d >> bit) & 1u);
+            same &= ((d >> bit) & 1u) ? has : ~has;
+        }
+        const unsigned before = wcnt[wave][d];
+        rank[j] = before + (unsigned)__popcll(same & below);
+        if (valid && lane == 63 - __clzll(same)) wcnt[wave][d] = before + (unsigned)__popcll(same);
+    }
+    __syncthreads();
+    // threads 0..255 (four waves), one digit each: offsets of the waves inside the digit, then
+    // two 256-entry prefix sums: of the tile's digit counts (slots in LDS) and of the global
+    // digit totals (where each digit starts in the output)
+    unsigned tile_cnt = 0;
+    if (threadIdx.x < 256) {
+        unsigned c[kSortWaves];
+#pragma unroll
+        for (int w = 0; w < kSortWaves; ++w) c[w] = wcnt[w][threadIdx.x];
+#pragma unroll
+        for (int w = 0; w < kSortWaves; ++w) {
+            wcnt[w][threadIdx.x] = tile_cnt;
+            tile_cnt += c[w];
+        }
+        unsigned a = tile_cnt, g2 = dig_total;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const unsigned oa = __shfl_up(a, off), og = __shfl_up(g2, off);
+            if (lane >= off) {
+                a += oa;
+                g2 += og;
+            }
+        }
+        if (lane == 63) {
+            s_w4[wave] = a;
+            s_w4[4 + wave] = g2;
+        }
+        tile_cnt = a - tile_cnt;          // exclusive inside the wave
+        dig_total = g2 - dig_total;
+    }
+    __syncthreads();
+    if (threadIdx.x < 256) {
+        unsigned a = 0, g2 = 0;
+        for (int w = 0; w < wave; ++w) {
+            a += s_w4[w];
+            g2 += s_w4[4 + w];
+        }
+        s_first[threadIdx.x] = tile_cnt + a;
+        s_dest[threadIdx.x] = dig_total + g2 + dig_pre;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int j = 0; j < kPer; ++j) {
+        if (sort_index(j) < N) {
+            const unsigned d = (k[j] >> shift) & 255u;
+            const unsigned slot = s_first[d] + wcnt[wave][d] + rank[j];
+            s_key[slot] = (uint16_t)k[j];
+            s_val[slot] = v[j];
+        }
+    }
+    __syncthreads();
+    const int64_t left = N - (int64_t)blockIdx.x * kTile;
+    const int in_tile = left < kTile ? (int)left : kTile;
+#pragma unroll
+    for (int j = 0; j < kPer; ++j) {
+        const int slot = j * kSortBlock + threadIdx.x;
+        if (slot < in_tile) {
+            const unsigned key = s_key[slot];
+            const unsigned d = (key >> shift) & 255u;
+            const unsigned pos = s_dest[d] + ((unsigned)slot - s_first[d]);
+            keys_out[pos] = (uint16_t)key;
+            vals_out[pos] = s_val[slot];
+        }
+    }
 }
 
 // start[c] = first position of code c in the sorted order (= position of the next present
-// code when c is absent); start[csize] = N
+// code when c is absent); start[csize] = N.  Also clears the length of the list of long segments.
 __global__ __launch_bounds__(kBlock) void k_pg_starts(const uint16_t *__restrict__ sorted, int64_t N,
-                                                      int csize, int32_t *__restrict__ start)
+                                                      int csize, int32_t *__restrict__ start,
+                                                      unsigned *__restrict__ nlong)
 {
     const int64_t r = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (r == 0) *nlong = 0u;
     if (r >= N) return;
     const int cur = sorted[r];
     const int prev = r == 0 ? -1 : (int)sorted[r - 1];
@@ -48,136 +240,192 @@ __global__ __launch_bounds__(kBlock) void k_pg_starts(const uint16_t *__restrict
         for (int c = cur + 1; c <= csize; ++c) start[c] = (int32_t)N;
 }
 
-// Sum of s_o * G[n, i] over the sorted positions [lo, hi), in order, four groups in flight.
-__device__ __forceinline__ double segment_sum(const int32_t *__restrict__ order,
+// Sum of s_o * G[n, i] over ids[a .. b) in that order, kInFlight gathers issued together.
+constexpr int kInFlight = 8;
+template <bool HAVE_SCALES, class IDS>
+__device__ __forceinline__ double ordered_sum(IDS ids, const float *__restrict__ s_of,
                                               const float *__restrict__ G,
                                               const float *__restrict__ scales, int gpr, int g,
-                                              int i, int lo, int hi)
+                                              int i, int a, int b, double acc = 0.0)
 {
-    double acc = 0.0;
-    int r = lo;
-    for (; r + 4 <= hi; r += 4) {
-        int n[4];
+    for (int r0 = a; r0 < b; r0 += kInFlight) {
+        float gv[kInFlight], sv[kInFlight];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) n[u] = order[r + u];
-        float gv[4], sv[4];
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            gv[u] = G[(int64_t)n[u] * g + i];
-            sv[u] = scales[n[u] / gpr];
+        for (int u = 0; u < kInFlight; ++u) {
+            const int r = r0 + u < b ? r0 + u : b - 1;
+            const int n = ids[r];
+            gv[u] = G[(int64_t)n * g + i];
+            sv[u] = HAVE_SCALES ? s_of[r] : scales[n / gpr];
         }
 #pragma unroll
-        for (int u = 0; u < 4; ++u) acc = acc + (double)sv[u] * (double)gv[u];
-    }
-    for (; r < hi; ++r) {
-        const int n = order[r];
-        acc = acc + (double)scales[n / gpr] * (double)G[(int64_t)n * g + i];
+        for (int u = 0; u < kInFlight; ++u) {
+            const double next = acc + (double)sv[u] * (double)gv[u];
+            acc = r0 + u < b ? next : acc;
+        }
     }
     return acc;
 }
 
-// extra[c] = number of pieces of the codewords before c beyond their first ones (an exclusive
-// prefix sum, extra[csize] = total), by the library's device scan over this functor.  A
-// segment of len groups has ceil(len / kLong) pieces.
-struct extra_pieces {
-    const int32_t *start;
-    int csize;
-    __host__ __device__ int operator()(int c) const
-    {
-        if (c >= csize) return 0;
-        const int len = start[c + 1] - start[c];
-        return len > kLong ? (len + kLong - 1) / kLong - 1 : 0;
-    }
-};
-typedef hipcub::TransformInputIterator<int, extra_pieces, hipcub::CountingInputIterator<int>> extra_iter;
-
-// TEAM lanes per work item (the group size rounded up to a power of two); lane i sums
-// dimension i.  Items [0, csize): the first piece of every codeword - written straight to
-// the output when it is the only one.  Items csize + e: extra piece e (its codeword is found
-// by bisection over the prefix `extra`); partial sums go to `partial` for k_pg_combine.
+// Segments of up to kLong groups: one team of TEAM lanes per codeword (TEAM = the group size
+// rounded up to a power of two, at least 8).  The team stages the segment's ids and row
+// scales in LDS, then lane i sums dimension i in segment order.  A longer segment is put on
+// the list for k_pg_long.
 template <int TEAM>
-__global__ __launch_bounds__(kBlock) void k_pg_accumulate(const int32_t *__restrict__ start,
-                                                          const int32_t *__restrict__ extra,
-                                                          const int32_t *__restrict__ order,
-                                                          const float *__restrict__ G,
-                                                          const float *__restrict__ scales,
-                                                          int gpr, int g, int csize,
-                                                          double *__restrict__ first_partial,
-                                                          double *__restrict__ partial,
-                                                          float *__restrict__ out)
+__global__ __launch_bounds__(kBlock) void k_pg_short(const int32_t *__restrict__ start,
+                                                     const int32_t *__restrict__ order,
+                                                     const float *__restrict__ G,
+                                                     const float *__restrict__ scales, int gpr, int g,
+                                                     int csize, int32_t *__restrict__ long_list,
+                                                     unsigned *__restrict__ nlong,
+                                                     float *__restrict__ out)
 {
     constexpr int kTeams = kBlock / TEAM;
-    const int i = threadIdx.x % TEAM;
-    const int64_t item = (int64_t)blockIdx.x * kTeams + threadIdx.x / TEAM;
-    if (i >= g) return;
-    if (item < csize) {
-        const int c = (int)item;
-        const int lo = start[c], hi = start[c + 1];
-        const bool single = hi - lo <= kLong;
-        const double acc = segment_sum(order, G, scales, gpr, g, i, lo, single ? hi : lo + kLong);
-        if (single) out[(int64_t)c * g + i] = (float)acc;
-        else first_partial[(int64_t)c * g + i] = acc;
-        return;
+    __shared__ int s_id[kTeams][kLong];
+    __shared__ float s_s[kTeams][kLong];
+    const int team = threadIdx.x / TEAM, i = threadIdx.x % TEAM;
+    const int c = blockIdx.x * kTeams + team;
+    int lo = 0, len = 0;
+    bool mine = false;
+    if (c < csize) {
+        lo = start[c];
+        len = start[c + 1] - lo;
+        mine = len <= kLong;
+        if (!mine) {
+            len = 0;
+            if (i == 0) long_list[atomicAdd(nlong, 1u)] = c;
+        }
     }
-    const int e = (int)(item - csize);
-    if (e >= extra[csize]) return;
-    int lo_c = 0, hi_c = csize;               // largest c with extra[c] <= e
-    while (hi_c - lo_c > 1) {
-        const int mid = (lo_c + hi_c) >> 1;
-        if (extra[mid] <= e) lo_c = mid;
-        else hi_c = mid;
+    for (int r = i; r < len; r += TEAM) s_id[team][r] = order[lo + r];
+    __syncthreads();
+    // the first kFirst gathers of G and the row scales of the whole segment are requested
+    // together: a typical segment costs one round trip here, not one per few groups
+    constexpr int kFirst = 32;
+    float gv[kFirst];
+    const int ii = i < g ? i : 0;
+    if (len > 0) {
+#pragma unroll
+        for (int u = 0; u < kFirst; ++u)
+            gv[u] = G[(int64_t)s_id[team][u < len ? u : len - 1] * g + ii];
     }
-    const int c = lo_c;
-    const int piece = e - extra[c] + 1;
-    const int lo = start[c] + piece * kLong;
-    const int end = start[c + 1];
-    const int hi = lo + kLong < end ? lo + kLong : end;
-    partial[(int64_t)e * g + i] = segment_sum(order, G, scales, gpr, g, i, lo, hi);
+    for (int r = i; r < len; r += TEAM) s_s[team][r] = scales[s_id[team][r] / gpr];
+    __syncthreads();
+    if (mine && i < g) {
+        double acc = 0.0;
+        if (len > 0) {
+#pragma unroll
+            for (int u = 0; u < kFirst; ++u) {
+                const double next = acc + (double)s_s[team][u < len ? u : len - 1] * (double)gv[u];
+                acc = u < len ? next : acc;
+            }
+            if (len > kFirst)
+                acc = ordered_sum<true>(s_id[team], s_s[team], G, scales, gpr, g, i, kFirst, len, acc);
+        }
+        out[(int64_t)c * g + i] = (float)acc;
+    }
 }
 
-// codewords with several pieces: the piece sums added in piece order
-__global__ __launch_bounds__(kBlock) void k_pg_combine(const int32_t *__restrict__ extra, int g,
-                                                       int csize,
-                                                       const double *__restrict__ first_partial,
-                                                       const double *__restrict__ partial,
-                                                       float *__restrict__ out)
+// Segments longer than kLong: one block per segment.  Its teams sum pieces of kLong ids in
+// order (piece p of the segment that starts at sorted position lo keeps its sum in
+// partial[lo / kLong + p], p >= 1: the ranges of different segments cannot meet; piece 0 stays
+// in LDS), and the first g threads add the piece sums in piece order.
+template <int TEAM>
+__global__ __launch_bounds__(kBlock) void k_pg_long(const int32_t *__restrict__ long_list,
+                                                    const unsigned *__restrict__ nlong,
+                                                    const int32_t *__restrict__ start,
+                                                    const int32_t *__restrict__ order,
+                                                    const float *__restrict__ G,
+                                                    const float *__restrict__ scales, int gpr, int g,
+                                                    double *partial, float *__restrict__ out)
 {
-    const int64_t t = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-    if (t >= (int64_t)csize * g) return;
-    const int c = (int)(t / g), i = (int)(t % g);
-    const int e0 = extra[c], e1 = extra[c + 1];
-    if (e1 == e0) return;
-    double acc = first_partial[t];
-    int e = e0;
-    for (; e + 4 <= e1; e += 4) {             // four loads in flight, added in piece order
-        double p[4];
+    constexpr int kTeams = kBlock / TEAM;
+    __shared__ double s_first[64];
+    const int team = threadIdx.x / TEAM, i = threadIdx.x % TEAM;
+    const int count = (int)*nlong;
+    for (int li = blockIdx.x; li < count; li += gridDim.x) {
+        const int c = long_list[li];
+        const int lo = start[c], len = start[c + 1] - lo;
+        const int32_t *ids = order + lo;
+        const int pieces = (len + kLong - 1) / kLong;
+        double *mine = partial + (int64_t)(lo / kLong) * g;
+        for (int p = team; p < pieces; p += kTeams) {
+            const int a = p * kLong, b = a + kLong < len ? a + kLong : len;
+            if (i < g) {
+                const double acc = ordered_sum<false>(ids, nullptr, G, scales, gpr, g, i, a, b);
+                if (p == 0) s_first[i] = acc;
+                else mine[(int64_t)p * g + i] = acc;
+            }
+        }
+        __syncthreads();
+        if ((int)threadIdx.x < g) {
+            double acc = s_first[threadIdx.x];
+            int p = 1;
+            for (; p + 4 <= pieces; p += 4) {          // four loads in flight, added in piece order
+                double v[4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) p[u] = partial[(int64_t)(e + u) * g + i];
+                for (int u = 0; u < 4; ++u) v[u] = mine[(int64_t)(p + u) * g + threadIdx.x];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) acc = acc + p[u];
+                for (int u = 0; u < 4; ++u) acc = acc + v[u];
+            }
+            for (; p < pieces; ++p) acc = acc + mine[(int64_t)p * g + threadIdx.x];
+            out[(int64_t)c * g + threadIdx.x] = (float)acc;
+        }
+        __syncthreads();
     }
-    for (; e < e1; ++e) acc = acc + partial[(int64_t)e * g + i];
-    out[t] = (float)acc;
 }
 
-// Small codebooks (all M * 2^B * g sums fit one block's LDS as doubles): every codeword is
-// shared by thousands of groups, so sorting buys nothing.  Each block sweeps a contiguous
-// range of groups once, 16 bytes of G per thread, and adds s_o * G into its own LDS table
-// with LDS atomics; the tables are then added up over the blocks in block order.  The order
-// of the atomic additions inside a block is not fixed, so the double sums may differ in
-// their last bits from run to run (the fp32 results almost never do).
+// Small codebooks (all M * 2^B * g sums fit one block's LDS): every codeword is shared by
+// thousands of groups, so sorting buys nothing.  Each block sweeps a contiguous range of
+// groups once, 16 bytes of G per thread, and adds s_o * G into its own LDS table with LDS
+// atomics.  To make the result independent of the order in which the atomics land, the
+// table is kept in 64-bit FIXED POINT: with X = max|s| * max|G| (both maxima are taken
+// beforehand, the product of two floats is exact in double) every term is scaled by a power
+// of two that leaves `headroom` bits for the number of terms one block can add, and rounded
+// to an integer once; integer addition is associative, so a table is a function of the
+// block's inputs only.  The tables are added over the blocks as integers too (exactly) and
+// the total is scaled back and rounded to fp32.  A term keeps 62 - headroom bits below X
+// (>= 39 for the largest matrices), so a sum differs from the exact one by far less than
+// the rounding of a sequential double loop does.  Gradients or scales that are not finite
+// make every entry NaN.
 __global__ __launch_bounds__(kBlock) void k_pg_small(const float *__restrict__ G,
                                                      const uint16_t *__restrict__ codes,
                                                      const float *__restrict__ scales, int64_t N,
                                                      int64_t per_block, int g, int M, int nbits,
-                                                     int gpr, double *__restrict__ partial)
+                                                     int gpr, int out_features,
+                                                     const unsigned *__restrict__ gmax_bits,
+                                                     int nmax, int headroom, long long *__restrict__ partial,
+                                                     double *__restrict__ meta)
 {
-    extern __shared__ double tab[];                     // [M][2^B][g]
+    extern __shared__ unsigned long long tab[];         // [M][2^B][g]
+    __shared__ unsigned s_max[2 * (kBlock / 64)];
     const int csize = 1 << nbits;
     const unsigned mask = (unsigned)csize - 1u;
     const int entries = M * csize * g;
-    for (int e = threadIdx.x; e < entries; e += kBlock) tab[e] = 0.0;
+    for (int e = threadIdx.x; e < entries; e += kBlock) tab[e] = 0ull;
+    // largest |scale| (as bits: NaN > inf > every finite value)
+    unsigned sb = 0u, gb = 0u;
+    for (int o = threadIdx.x; o < out_features; o += kBlock) sb = max(sb, __float_as_uint(fabsf(scales[o])));
+    for (int o = threadIdx.x; o < nmax; o += kBlock) gb = max(gb, gmax_bits[o]);
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        sb = max(sb, (unsigned)__shfl_down(sb, off));
+        gb = max(gb, (unsigned)__shfl_down(gb, off));
+    }
+    if ((threadIdx.x & 63) == 0) {
+        s_max[threadIdx.x >> 6] = sb;
+        s_max[4 + (threadIdx.x >> 6)] = gb;
+    }
     __syncthreads();
+    sb = max(max(s_max[0], s_max[1]), max(s_max[2], s_max[3]));
+    gb = max(max(s_max[4], s_max[5]), max(s_max[6], s_max[7]));
+    const double X = (double)__uint_as_float(sb) * (double)__uint_as_float(gb);
+    const bool poison = !(X < __builtin_huge_val());
+    int ex = 0;
+    (void)frexp(X, &ex);                                  // X < 2^ex
+    const double up = (X > 0.0 && !poison) ? ldexp(1.0, 62 - headroom - ex) : 0.0;
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        meta[0] = (X > 0.0 && !poison) ? ldexp(1.0, -(62 - headroom - ex)) : 0.0;
+        meta[1] = poison ? 1.0 : 0.0;
+    }
     const int vpg = g / 4;                              // 16-byte vectors per group
     const int64_t lo = (int64_t)blockIdx.x * per_block;
     const int64_t hi = lo + per_block < N ? lo + per_block : N;
@@ -186,37 +434,83 @@ __global__ __launch_bounds__(kBlock) void k_pg_small(const float *__restrict__ G
         const int64_t n = v / vpg;
         const int q4 = (int)(v - n * vpg);
         const pv_f4 gv = __builtin_nontemporal_load(&G4[v]);
-        const double s = (double)scales[n / gpr];
+        const double s = (double)scales[n / gpr] * up;  // a power of two: exact
         for (int m = 0; m < M; ++m) {
             const int c = codes[n * M + m] & mask;
-            double *row = tab + ((int64_t)m * csize + c) * g + q4 * 4;
+            unsigned long long *row = tab + ((int64_t)m * csize + c) * g + q4 * 4;
 #pragma unroll
-            for (int e = 0; e < 4; ++e) atomicAdd(&row[e], s * (double)gv[e]);
+            for (int e = 0; e < 4; ++e)
+                atomicAdd(&row[e], (unsigned long long)__double2ll_rn(s * (double)gv[e]));
         }
     }
     __syncthreads();
-    double *out = partial + (int64_t)blockIdx.x * entries;
-    for (int e = threadIdx.x; e < entries; e += kBlock) out[e] = tab[e];
+    long long *out = partial + (int64_t)blockIdx.x * entries;
+    for (int e = threadIdx.x; e < entries; e += kBlock) out[e] = (long long)tab[e];
 }
 
-// sums the per-block tables in block order, rounds once
-__global__ __launch_bounds__(kBlock) void k_pg_small_final(const double *__restrict__ partial,
+// adds the per-block tables as integers (16 threads per entry, each a slice of the blocks),
+// scales back and rounds once
+constexpr int kSlices = 16;
+__global__ __launch_bounds__(kBlock) void k_pg_small_final(const long long *__restrict__ partial,
                                                            int blocks, int entries,
+                                                           const double *__restrict__ meta,
                                                            float *__restrict__ out)
 {
-    const int e = blockIdx.x * kBlock + threadIdx.x;
-    if (e >= entries) return;
-    double acc = 0.0;
-    int b = 0;
-    for (; b + 4 <= blocks; b += 4) {
-        double p[4];
+    __shared__ long long s_hi[kSlices][kBlock / kSlices];
+    __shared__ long long s_lo[kSlices][kBlock / kSlices];
+    const int col = threadIdx.x % (kBlock / kSlices), sl = threadIdx.x / (kBlock / kSlices);
+    const int e = blockIdx.x * (kBlock / kSlices) + col;
+    long long hi = 0, lo = 0;                           // total = hi * 2^32 + lo
+    if (e < entries) {
+        for (int b0 = sl; b0 < blocks; b0 += kSlices * 4) {
+            long long p[4];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) p[u] = partial[(int64_t)(b + u) * entries + e];
+            for (int u = 0; u < 4; ++u) {
+                const int b = b0 + u * kSlices;
+                p[u] = b < blocks ? partial[(int64_t)b * entries + e] : 0;
+            }
 #pragma unroll
-        for (int u = 0; u < 4; ++u) acc = acc + p[u];
+            for (int u = 0; u < 4; ++u) {
+                hi += p[u] >> 32;
+                lo += p[u] & 0xffffffffll;
+            }
+        }
     }
-    for (; b < blocks; ++b) acc = acc + partial[(int64_t)b * entries + e];
-    out[e] = (float)acc;
+    s_hi[sl][col] = hi;
+    s_lo[sl][col] = lo;
+    __syncthreads();
+    if (sl == 0 && e < entries) {
+        for (int q = 1; q < kSlices; ++q) {
+            hi += s_hi[q][col];
+            lo += s_lo[q][col];
+        }
+        // |hi| < 2^40 and 0 <= lo < 2^41: both conversions are exact, the sum rounds once
+        const double total = (double)hi * 4294967296.0 + (double)lo;
+        out[e] = meta[1] != 0.0 ? __builtin_nanf("") : (float)(total * meta[0]);
+    }
+}
+
+// largest |G| seen by each block, as bits, for callers that do not ask for the scale gradient
+// (whose kernel takes the maximum of each row on its way)
+__global__ __launch_bounds__(kBlock) void k_pg_absmax(const float *__restrict__ G, int64_t n4,
+                                                      unsigned *__restrict__ gmax_bits)
+{
+    const pv_f4 *G4 = reinterpret_cast<const pv_f4 *>(G);
+    unsigned mb = 0u;
+    for (int64_t v = (int64_t)blockIdx.x * kBlock + threadIdx.x; v < n4; v += (int64_t)gridDim.x * kBlock) {
+        const pv_f4 x = G4[v];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) mb = max(mb, __float_as_uint(fabsf(x[e])));
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) mb = max(mb, (unsigned)__shfl_down(mb, off));
+    __shared__ unsigned tmp_max[kBlock / 64];
+    if ((threadIdx.x & 63) == 0) tmp_max[threadIdx.x >> 6] = mb;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int w = 1; w < kBlock / 64; ++w) mb = max(mb, tmp_max[w]);
+        gmax_bits[blockIdx.x] = mb;
+    }
 }
 
 // one block per output row; VEC: g % 4 == 0, a thread takes 16-byte vectors
@@ -225,9 +519,11 @@ __global__ __launch_bounds__(kBlock) void k_pg_scales(const float *__restrict__ 
                                                       const uint16_t *__restrict__ codes,
                                                       const float *__restrict__ codebooks, int g,
                                                       int M, int nbits, int gpr,
-                                                      float *__restrict__ grad_scales)
+                                                      float *__restrict__ grad_scales,
+                                                      unsigned *__restrict__ gmax_bits /* [rows], NULL ok */)
 {
     __shared__ double tmp[kBlock / 64];
+    unsigned mb = 0u;                     // largest |G| of the row, as bits
     const int64_t o = blockIdx.x;
     const int64_t csize = (int64_t)1 << nbits;
     const unsigned mask = (unsigned)csize - 1u;
@@ -255,6 +551,8 @@ __global__ __launch_bounds__(kBlock) void k_pg_scales(const float *__restrict__ 
             acc = acc + (double)gv.y * (double)q.y;
             acc = acc + (double)gv.z * (double)q.z;
             acc = acc + (double)gv.w * (double)q.w;
+            mb = max(max(mb, __float_as_uint(fabsf(gv.x))), __float_as_uint(fabsf(gv.y)));
+            mb = max(max(mb, __float_as_uint(fabsf(gv.z))), __float_as_uint(fabsf(gv.w)));
         }
     } else {
         for (int64_t e = threadIdx.x; e < in_features; e += kBlock) {
@@ -263,8 +561,16 @@ __global__ __launch_bounds__(kBlock) void k_pg_scales(const float *__restrict__ 
             float q = codebooks[(int64_t)(codes[n * M] & mask) * g + i];
             for (int m = 1; m < M; ++m)
                 q = q + codebooks[(m * csize + (codes[n * M + m] & mask)) * g + i];
-            acc = acc + (double)G[o * in_features + e] * (double)q;
+            const float gv = G[o * in_features + e];
+            acc = acc + (double)gv * (double)q;
+            mb = max(mb, __float_as_uint(fabsf(gv)));
         }
+    }
+    __shared__ unsigned tmp_max[kBlock / 64];
+    if (gmax_bits) {     // one plain store per row: atomics on one device address would queue up
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) mb = max(mb, (unsigned)__shfl_down(mb, off));
+        if ((threadIdx.x & 63) == 0) tmp_max[threadIdx.x >> 6] = mb;
     }
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) acc = acc + __shfl_down(acc, off);
@@ -274,6 +580,11 @@ __global__ __launch_bounds__(kBlock) void k_pg_scales(const float *__restrict__ 
         double t = 0.0;
         for (int w = 0; w < kBlock / 64; ++w) t = t + tmp[w];
         grad_scales[o] = (float)t;
+        if (gmax_bits) {
+            unsigned m4 = 0u;
+            for (int w = 0; w < kBlock / 64; ++w) m4 = max(m4, tmp_max[w]);
+            gmax_bits[o] = m4;
+        }
     }
 }
 
@@ -299,97 +610,117 @@ pv_status pv_launch_codebook_grads(pv_ctx *ctx, const pv_layout *l, const float 
         if (blocks > 512) blocks = 512;
         if (blocks < 1) blocks = 1;
         const int64_t per_block = (N + blocks - 1) / blocks;
-        pv_status st2 = pv_ensure(ctx, ctx->pstep, (size_t)blocks * entries * 8);
+        int headroom = 1;                                 // 2^headroom > terms one block adds to an entry
+        while (((int64_t)1 << headroom) <= per_block) ++headroom;
+        const int64_t n4 = N * g / 4;
+        int64_t mblocks = (n4 + kBlock * 8 - 1) / (kBlock * 8);
+        if (mblocks > 2048) mblocks = 2048;
+        const int nmax = grad_scales ? (int)l->out_features : (int)mblocks;
+        const size_t o_meta = align_up((size_t)blocks * entries * 8);
+        const size_t o_gmax = o_meta + 256;
+        pv_status st2 = pv_ensure(ctx, ctx->pstep, o_gmax + (size_t)nmax * 4);
         if (st2 != PV_OK) return st2;
-        double *partial = static_cast<double *>(ctx->pstep.ptr);
+        long long *partial = static_cast<long long *>(ctx->pstep.ptr);
+        double *meta = reinterpret_cast<double *>(static_cast<char *>(ctx->pstep.ptr) + o_meta);
+        unsigned *gmax = reinterpret_cast<unsigned *>(static_cast<char *>(ctx->pstep.ptr) + o_gmax);
         pv_timed t(ctx, PV_K_PSTEP);
-        hipLaunchKernelGGL(k_pg_small, dim3(blocks), dim3(kBlock), (size_t)entries * 8, sm, G, codes,
-                           scales, N, per_block, g, M, l->nbits, gpr, partial);
-        hipLaunchKernelGGL(k_pg_small_final, dim3((unsigned)((entries + kBlock - 1) / kBlock)),
-                           dim3(kBlock), 0, sm, partial, blocks, (int)entries, grad_codebooks);
-        if (grad_scales) {
+        if (grad_scales)     // first: it reads all of G anyway and takes max|G| of each row on its way
             hipLaunchKernelGGL(k_pg_scales<true>, dim3((unsigned)l->out_features), dim3(kBlock), 0, sm,
-                               G, codes, codebooks, g, M, l->nbits, gpr, grad_scales);
-        }
+                               G, codes, codebooks, g, M, l->nbits, gpr, grad_scales, gmax);
+        else
+            hipLaunchKernelGGL(k_pg_absmax, dim3((unsigned)mblocks), dim3(kBlock), 0, sm, G, n4, gmax);
+        hipLaunchKernelGGL(k_pg_small, dim3(blocks), dim3(kBlock), (size_t)entries * 8, sm, G, codes,
+                           scales, N, per_block, g, M, l->nbits, gpr, (int)l->out_features, gmax,
+                           nmax, headroom, partial, meta);
+        hipLaunchKernelGGL(k_pg_small_final,
+                           dim3((unsigned)((entries + kBlock / kSlices - 1) / (kBlock / kSlices))),
+                           dim3(kBlock), 0, sm, partial, blocks, (int)entries, meta, grad_codebooks);
         PV_HIP(ctx, hipGetLastError());
         return PV_OK;
     }
 
-    size_t sort_bytes = 0, scan_bytes = 0;
-    PV_HIP(ctx, hipcub::DeviceRadixSort::SortPairs(nullptr, sort_bytes, (const uint16_t *)nullptr,
-                                                   (uint16_t *)nullptr, (const int32_t *)nullptr,
-                                                   (int32_t *)nullptr, (int)N, 0, l->nbits, sm));
-    PV_HIP(ctx, hipcub::DeviceScan::ExclusiveSum(
-                    nullptr, scan_bytes,
-                    extra_iter(hipcub::CountingInputIterator<int>(0), extra_pieces{nullptr, csize}),
-                    (int32_t *)nullptr, csize + 1, sm));
-    if (scan_bytes > sort_bytes) sort_bytes = scan_bytes;   // one temporary area serves both
     const size_t nn = (size_t)N;
-    const int64_t max_extra = N / kLong + 1;
-    size_t o_keys = 0;
-    size_t o_keys2 = o_keys + align_up(nn * 2);
-    size_t o_vals = o_keys2 + align_up(nn * 2);
-    size_t o_order = o_vals + align_up(nn * 4);
-    size_t o_start = o_order + align_up(nn * 4);
-    size_t o_extra = o_start + align_up((size_t)(csize + 1) * 4);
-    size_t o_first = o_extra + align_up((size_t)(csize + 1) * 4);
-    size_t o_part = o_first + align_up((size_t)csize * g * 8);
-    size_t o_sort = o_part + align_up((size_t)max_extra * g * 8);
-    size_t total = o_sort + align_up(sort_bytes);
+    const int nblocks = (int)((N + kTile - 1) / kTile);           // tiles of a sorting pass
+    const int hist_n = 256 * nblocks;
+    size_t o_start = 0;
+    size_t o_long = o_start + align_up((size_t)(csize + 1) * 4);
+    size_t o_nlong = o_long + align_up((size_t)csize * 4);
+    size_t o_total = o_nlong + 256;
+    size_t o_hist = o_total + 1024;
+    size_t o_base = o_hist + align_up((size_t)hist_n * 4);
+    size_t o_keys_a = o_base + align_up((size_t)hist_n * 4);
+    size_t o_keys_b = o_keys_a + align_up(nn * 2);
+    size_t o_vals_a = o_keys_b + align_up(nn * 2);
+    size_t o_order = o_vals_a + align_up(nn * 4);
+    size_t o_part = o_order + align_up(nn * 4);
+    size_t total = o_part + align_up((size_t)(N / kLong + 2) * g * 8);
     pv_status st = pv_ensure(ctx, ctx->pstep, total);
     if (st != PV_OK) return st;
     char *base = static_cast<char *>(ctx->pstep.ptr);
-    uint16_t *keys = reinterpret_cast<uint16_t *>(base + o_keys);
-    uint16_t *keys2 = reinterpret_cast<uint16_t *>(base + o_keys2);
-    int32_t *vals = reinterpret_cast<int32_t *>(base + o_vals);
-    int32_t *order = reinterpret_cast<int32_t *>(base + o_order);
     int32_t *start = reinterpret_cast<int32_t *>(base + o_start);
-    int32_t *extra = reinterpret_cast<int32_t *>(base + o_extra);
-    double *first_partial = reinterpret_cast<double *>(base + o_first);
+    int32_t *long_list = reinterpret_cast<int32_t *>(base + o_long);
+    unsigned *nlong = reinterpret_cast<unsigned *>(base + o_nlong);
+    unsigned *dig_totals = reinterpret_cast<unsigned *>(base + o_total);
+    unsigned *hist = reinterpret_cast<unsigned *>(base + o_hist);
+    unsigned *hbase = reinterpret_cast<unsigned *>(base + o_base);
+    uint16_t *keys_a = reinterpret_cast<uint16_t *>(base + o_keys_a);
+    uint16_t *keys_b = reinterpret_cast<uint16_t *>(base + o_keys_b);
+    int32_t *vals_a = reinterpret_cast<int32_t *>(base + o_vals_a);
+    int32_t *order = reinterpret_cast<int32_t *>(base + o_order);
     double *partial = reinterpret_cast<double *>(base + o_part);
-    void *sort_tmp = base + o_sort;
 
     pv_timed t(ctx, PV_K_PSTEP);
-    const unsigned nblocks = (unsigned)((N + kBlock - 1) / kBlock);
-    int team = 1;
+    int team = 8;
     while (team < g) team <<= 1;      // lanes per work item (g <= 64 checked by the caller)
     const int teams_per_block = kBlock / team;
-    const unsigned ablocks = (unsigned)((csize + max_extra + teams_per_block - 1) / teams_per_block);
-    const unsigned cblocks = (unsigned)(((int64_t)csize * g + kBlock - 1) / kBlock);
+    const unsigned sblocks = (unsigned)((csize + teams_per_block - 1) / teams_per_block);
+    int64_t max_long = N / (kLong + 1);           // segments that can be longer than kLong
+    if (max_long > csize) max_long = csize;
+    if (max_long > 2048) max_long = 2048;         // blocks stride over the list
+    const bool two = l->nbits > 8;
     for (int m = 0; m < M; ++m) {
-        hipLaunchKernelGGL(k_pg_keys, dim3(nblocks), dim3(kBlock), 0, sm, codes, N, M, m, mask, keys,
-                           vals);
-        PV_HIP(ctx, hipcub::DeviceRadixSort::SortPairs(sort_tmp, sort_bytes, keys, keys2, vals, order,
-                                                       (int)N, 0, l->nbits, sm));
-        hipLaunchKernelGGL(k_pg_starts, dim3(nblocks), dim3(kBlock), 0, sm, keys2, N, csize, start);
-        PV_HIP(ctx, hipcub::DeviceScan::ExclusiveSum(
-                        sort_tmp, sort_bytes,
-                        extra_iter(hipcub::CountingInputIterator<int>(0), extra_pieces{start, csize}),
-                        extra, csize + 1, sm));
+        // pass over the low 8 bits of the codes (the only one when B <= 8) ...
+        uint16_t *k1 = two ? keys_a : keys_b;
+        int32_t *v1 = two ? vals_a : order;
+        hipLaunchKernelGGL(k_pg_digit_hist<true>, dim3(nblocks), dim3(kSortBlock), 0, sm, codes, N, M, m,
+                           mask, 0, nblocks, hist);
+        hipLaunchKernelGGL(k_pg_row_scan, dim3(256), dim3(kBlock), 0, sm, hist, nblocks, hbase, dig_totals);
+        hipLaunchKernelGGL(k_pg_digit_scatter<true>, dim3(nblocks), dim3(kSortBlock), 0, sm, codes,
+                           (const int32_t *)nullptr, N, M, m, mask, 0, nblocks, hbase, dig_totals, k1, v1);
+        if (two) {   // ... and over the high ones
+            hipLaunchKernelGGL(k_pg_digit_hist<false>, dim3(nblocks), dim3(kSortBlock), 0, sm, keys_a, N,
+                               1, 0, mask, 8, nblocks, hist);
+            hipLaunchKernelGGL(k_pg_row_scan, dim3(256), dim3(kBlock), 0, sm, hist, nblocks, hbase,
+                               dig_totals);
+            hipLaunchKernelGGL(k_pg_digit_scatter<false>, dim3(nblocks), dim3(kSortBlock), 0, sm, keys_a,
+                               vals_a, N, 1, 0, mask, 8, nblocks, hbase, dig_totals, keys_b, order);
+        }
+        hipLaunchKernelGGL(k_pg_starts, dim3((unsigned)((N + kBlock - 1) / kBlock)), dim3(kBlock), 0,
+                           sm, keys_b, N, csize, start, nlong);
         float *out = grad_codebooks + (int64_t)m * csize * g;
 #define PV_ACC(TEAM_)                                                                            \
-    hipLaunchKernelGGL(k_pg_accumulate<TEAM_>, dim3(ablocks), dim3(kBlock), 0, sm, start, extra,    \
-                       order, G, scales, gpr, g, csize, first_partial, partial, out)
+    do {                                                                                         \
+        hipLaunchKernelGGL(k_pg_short<TEAM_>, dim3(sblocks), dim3(kBlock), 0, sm, start, order, G, \
+                           scales, gpr, g, csize, long_list, nlong, out);                         \
+        if (max_long > 0)                                                                        \
+            hipLaunchKernelGGL(k_pg_long<TEAM_>, dim3((unsigned)max_long), dim3(kBlock), 0, sm,   \
+                               long_list, nlong, start, order, G, scales, gpr, g, partial, out);  \
+    } while (0)
         switch (team) {
-        case 1: PV_ACC(1); break;
-        case 2: PV_ACC(2); break;
-        case 4: PV_ACC(4); break;
         case 8: PV_ACC(8); break;
         case 16: PV_ACC(16); break;
         case 32: PV_ACC(32); break;
         default: PV_ACC(64); break;
         }
 #undef PV_ACC
-        hipLaunchKernelGGL(k_pg_combine, dim3(cblocks), dim3(kBlock), 0, sm, extra, g, csize,
-                           first_partial, partial, out);
     }
     if (grad_scales) {
         if (g % 4 == 0)
             hipLaunchKernelGGL(k_pg_scales<true>, dim3((unsigned)l->out_features), dim3(kBlock), 0, sm,
-                               G, codes, codebooks, g, M, l->nbits, gpr, grad_scales);
+                               G, codes, codebooks, g, M, l->nbits, gpr, grad_scales, (unsigned *)nullptr);
         else
             hipLaunchKernelGGL(k_pg_scales<false>, dim3((unsigned)l->out_features), dim3(kBlock), 0, sm,
-                               G, codes, codebooks, g, M, l->nbits, gpr, grad_scales);
+                               G, codes, codebooks, g, M, l->nbits, gpr, grad_scales, (unsigned *)nullptr);
     }
     PV_HIP(ctx, hipGetLastError());
     return PV_OK;

@@ -86,3 +86,65 @@ def test_codebook_grads_second_call_and_errors():
     from paper_2405_14852_amd import Layout
     with pytest.raises(PVError):
         run.ctx.pv_codebook_grads(Layout(16, 2048, 128, 2, 6), run.G, run.codes, run.cb, run.sc, gc, gs)
+
+
+def test_codebook_grads_long_buckets_sorted_in_lds_and_in_global_memory():
+    """The bucketed route (the table of sums does not fit LDS) with one codeword held by more than
+    8192 groups, one by a few thousand, one by just over 128 and the rest spread thinly: the three
+    ways a bucket is put into group order.  Thin buckets are bit-exact, the long ones within the
+    tolerance of a different association, and a second run repeats the first bit for bit."""
+    wl = workloads.make(64, 4096, 8, 1, 11, seed=85, sigma_g=1e-2)       # 32768 groups, 2048 codewords
+    rng = np.random.default_rng(85)
+    u = rng.random(wl.codes.shape)
+    wl.codes[u < 0.5] = 1234
+    wl.codes[(u >= 0.5) & (u < 0.6)] = 7
+    flat = wl.codes.reshape(-1)
+    free = np.nonzero((flat != 1234) & (flat != 7))[0]
+    flat[free[:150]] = 2000
+    counts = np.bincount(flat, minlength=2048)
+    assert counts[1234] > 8192 and 128 < counts[7] <= 8192 and 128 < counts[2000] < 400
+    gc, gs, gc_ref, gs_ref = run_case(wl)
+    mag = np.abs(wl.G).sum() * np.abs(wl.scales).max()
+    assert close_sum(gc, gc_ref, mag)
+    thin = counts <= 128
+    assert thin.sum() > 1900
+    assert np.array_equal(gc[0, thin].view(np.uint32), gc_ref[0, thin].view(np.uint32))
+    again, _, _, _ = run_case(wl)
+    assert np.array_equal(gc.view(np.uint32), again.view(np.uint32))
+
+
+@pytest.mark.parametrize("g,M,B,shape", [(8, 1, 16, (256, 2048)), (16, 1, 12, (128, 2048)), (8, 2, 8, (512, 4096)),
+                                         (8, 1, 8, (64, 512))])
+def test_codebook_grads_repeat_bit_for_bit(g, M, B, shape):
+    wl = workloads.make(shape[0], shape[1], g, M, B, seed=86, sigma_g=1e-2)
+    a = run_case(wl)
+    b = run_case(wl)
+    assert np.array_equal(a[0].view(np.uint32), b[0].view(np.uint32))
+    assert np.array_equal(a[1].view(np.uint32), b[1].view(np.uint32))
+
+
+def test_codebook_grads_rejects_misaligned_pointers():
+    from paper_2405_14852_amd import PVError
+    wl = workloads.make(16, 128, 8, 1, 6, seed=87)
+    run = GpuRun(wl)
+    gc = torch.empty(tuple(wl.codebooks.shape), dtype=torch.float32, device=DEV)
+    big = torch.zeros(16 * 128 + 4, dtype=torch.float32, device=DEV)
+    with pytest.raises(PVError):
+        run.ctx.pv_codebook_grads(run.lay, big[1:1 + 16 * 128].view(16, 128), run.codes, run.cb, run.sc, gc, None)
+
+
+def test_codebook_grads_small_codebook_route_is_close_to_the_exact_sum_and_flags_non_finite_input():
+    """The fixed-point route (the table of sums fits LDS): its sums are exact up to 2^-39 of the
+    largest term, so they agree with the oracle's double loop to the last fp32 bit almost always;
+    a gradient that is not finite turns the whole result into NaN."""
+    wl = workloads.make(256, 2048, 8, 2, 6, seed=88, sigma_g=1e-2)       # 65536 groups, 64 codewords
+    gc, gs, gc_ref, gs_ref = run_case(wl)
+    assert (gc.view(np.uint32) != gc_ref.view(np.uint32)).mean() < 0.01
+    assert close_sum(gc, gc_ref, 1e-3 * np.abs(wl.G).sum() * np.abs(wl.scales).max())
+    wl.G[5, 17] = np.inf
+    gc, gs, _, _ = run_case(wl)
+    assert np.isnan(gc).all()
+    wl.G[5, 17] = 0.0
+    wl.G *= 0
+    gc, gs, _, _ = run_case(wl)
+    assert (gc == 0).all() and (gs == 0).all()
