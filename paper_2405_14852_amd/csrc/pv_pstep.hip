@@ -19,210 +19,22 @@
 // rounding).  Small codebooks take another route (k_pg_small below).  The scale gradient is
 // one block-wide tree sum per row.
 #include "pv_internal.h"
+#include "pv_radix.h"
 
 namespace {
 
 constexpr int kBlock = 256;
 constexpr int kLong = 128;       // groups per piece: a segment up to this long is summed by one team alone
-constexpr int kSortBlock = 1024;          // threads of a sorting block: 16 waves
-constexpr int kPer = 8;                   // rounds: keys per thread in a sorting pass
-constexpr int kTile = kSortBlock * kPer;  // keys per block
-constexpr int kSortWaves = kSortBlock / 64;
-
-// digit of key e in this pass; FIRST: the keys are the codes themselves (codebook m of M,
-// masked to B bits), else the keys written by the previous pass
-template <bool FIRST>
-__device__ __forceinline__ unsigned key_at(const uint16_t *__restrict__ keys, int64_t e, int M, int m,
-                                           unsigned mask)
-{
-    return FIRST ? (unsigned)(keys[e * M + m] & mask) : (unsigned)keys[e];
-}
-
-// Key j of this thread: wave w of the block owns the 64 * kPer consecutive keys that start at
-// tile + w * 64 * kPer and takes them 64 at a time, so that (wave, round, lane) order is the
-// order of the keys.
-__device__ __forceinline__ int64_t sort_index(int j)
-{
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    return (int64_t)blockIdx.x * kTile + (int64_t)(wave * kPer + j) * 64 + lane;
-}
-
-// hist[d * nblocks + b] = keys of tile b whose digit is d
-template <bool FIRST>
-__global__ __launch_bounds__(kSortBlock) void k_pg_digit_hist(const uint16_t *__restrict__ keys,
-                                                              int64_t N, int M, int m, unsigned mask,
-                                                              int shift, int nblocks,
-                                                              unsigned *__restrict__ hist)
-{
-    __shared__ unsigned h[256];
-    if (threadIdx.x < 256) h[threadIdx.x] = 0u;
-    unsigned k[kPer];
-#pragma unroll
-    for (int j = 0; j < kPer; ++j) {          // all loads in flight before the first is used
-        const int64_t e = sort_index(j);
-        k[j] = key_at<FIRST>(keys, e < N ? e : N - 1, M, m, mask);
+// the codes of codebook m as sort keys, masked to B bits
+struct code_keys {
+    const uint16_t *codes;
+    int M, m;
+    unsigned mask;
+    __device__ __forceinline__ unsigned operator()(int64_t e) const
+    {
+        return (unsigned)(codes[e * M + m] & mask);
     }
-    __syncthreads();
-#pragma unroll
-    for (int j = 0; j < kPer; ++j)
-        if (sort_index(j) < N) atomicAdd(&h[(k[j] >> shift) & 255u], 1u);
-    __syncthreads();
-    if (threadIdx.x < 256) hist[(int64_t)threadIdx.x * nblocks + blockIdx.x] = h[threadIdx.x];
-}
-
-// Row d of the histogram (one block per digit): rowpre[d][b] = keys with digit d in the tiles
-// before b, total[d] = keys with digit d.  The rows do not depend on one another; the offsets
-// of the digits themselves (a prefix sum over 256 totals) are taken by every scatter block.
-__global__ __launch_bounds__(kBlock) void k_pg_row_scan(const unsigned *__restrict__ hist, int nblocks,
-                                                        unsigned *__restrict__ rowpre,
-                                                        unsigned *__restrict__ total)
-{
-    __shared__ unsigned s_wave[kBlock / 64];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const unsigned *in = hist + (int64_t)blockIdx.x * nblocks;
-    unsigned *out = rowpre + (int64_t)blockIdx.x * nblocks;
-    unsigned carry = 0;
-    for (int b0 = 0; b0 < nblocks; b0 += kBlock) {
-        const int b = b0 + threadIdx.x;
-        const unsigned cnt = b < nblocks ? in[b] : 0u;
-        unsigned incl = cnt;
-#pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-            const unsigned o = __shfl_up(incl, off);
-            if (lane >= off) incl += o;
-        }
-        __syncthreads();                  // s_wave is reused from the previous round
-        if (lane == 63) s_wave[wave] = incl;
-        __syncthreads();
-        unsigned before = 0, all = 0;
-#pragma unroll
-        for (int w = 0; w < kBlock / 64; ++w) {
-            before += w < wave ? s_wave[w] : 0u;
-            all += s_wave[w];
-        }
-        if (b < nblocks) out[b] = carry + before + incl - cnt;
-        carry += all;
-    }
-    if (threadIdx.x == 0) total[blockIdx.x] = carry;
-}
-
-// Stable scatter of tile b by this pass' digit.  In every round the 64 lanes of a wave find,
-// with one ballot per digit bit, the lanes that hold the same digit; a key's rank is the
-// wave's running count of that digit (wcnt[wave][d], kept in LDS by the last lane of each
-// set) plus the number of such lanes below it.  The counts of the waves are then turned
-// into offsets in wave order, so that keys with equal digits keep the order they came in.
-// The tile is first put in digit order in LDS and written out from there: neighbouring
-// threads then write neighbouring addresses (a run per digit) instead of one line each.
-template <bool FIRST>
-__global__ __launch_bounds__(kSortBlock) void k_pg_digit_scatter(
-    const uint16_t *__restrict__ keys, const int32_t *__restrict__ vals, int64_t N, int M, int m,
-    unsigned mask, int shift, int nblocks, const unsigned *__restrict__ rowpre,
-    const unsigned *__restrict__ total, uint16_t *__restrict__ keys_out,
-    int32_t *__restrict__ vals_out)
-{
-    __shared__ unsigned wcnt[kSortWaves][256];
-    __shared__ unsigned s_first[256];     // first slot of digit d inside the tile
-    __shared__ unsigned s_dest[256];      // where that slot goes in the output
-    __shared__ unsigned s_w4[8];
-    __shared__ uint16_t s_key[kTile];
-    __shared__ int32_t s_val[kTile];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    unsigned k[kPer], rank[kPer];
-    int32_t v[kPer];
-#pragma unroll
-    for (int j = 0; j < kPer; ++j) {
-        const int64_t e = sort_index(j);
-        const int64_t ec = e < N ? e : N - 1;
-        k[j] = key_at<FIRST>(keys, ec, M, m, mask);
-        v[j] = FIRST ? (int32_t)ec : vals[ec];
-    }
-    unsigned dig_total = 0, dig_pre = 0;
-    if (threadIdx.x < 256) {
-        dig_total = total[threadIdx.x];
-        dig_pre = rowpre[(int64_t)threadIdx.x * nblocks + blockIdx.x];
-    }
-    for (int w = threadIdx.x; w < kSortWaves * 256; w += kSortBlock) (&wcnt[0][0])[w] = 0u;
-    __syncthreads();
-    const unsigned long long below = (1ull << lane) - 1ull;
-#pragma unroll
-    for (int j = 0; j < kPer; ++j) {
-        const bool valid = sort_index(j) < N;
-        const unsigned d = (k[j] >> shift) & 255u;
-        unsigned long long same = __ballot(valid);
-#pragma unroll
-        for (int bit = 0; bit < 8; ++bit) {
-            const unsigned long long has = __ballot((d >> bit) & 1u);
-            same &= ((d >> bit) & 1u) ? has : ~has;
-        }
-        const unsigned before = wcnt[wave][d];
-        rank[j] = before + (unsigned)__popcll(same & below);
-        if (valid && lane == 63 - __clzll(same)) wcnt[wave][d] = before + (unsigned)__popcll(same);
-    }
-    __syncthreads();
-    // threads 0..255 (four waves), one digit each: offsets of the waves inside the digit, then
-    // two 256-entry prefix sums: of the tile's digit counts (slots in LDS) and of the global
-    // digit totals (where each digit starts in the output)
-    unsigned tile_cnt = 0;
-    if (threadIdx.x < 256) {
-        unsigned c[kSortWaves];
-#pragma unroll
-        for (int w = 0; w < kSortWaves; ++w) c[w] = wcnt[w][threadIdx.x];
-#pragma unroll
-        for (int w = 0; w < kSortWaves; ++w) {
-            wcnt[w][threadIdx.x] = tile_cnt;
-            tile_cnt += c[w];
-        }
-        unsigned a = tile_cnt, g2 = dig_total;
-#pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-            const unsigned oa = __shfl_up(a, off), og = __shfl_up(g2, off);
-            if (lane >= off) {
-                a += oa;
-                g2 += og;
-            }
-        }
-        if (lane == 63) {
-            s_w4[wave] = a;
-            s_w4[4 + wave] = g2;
-        }
-        tile_cnt = a - tile_cnt;          // exclusive inside the wave
-        dig_total = g2 - dig_total;
-    }
-    __syncthreads();
-    if (threadIdx.x < 256) {
-        unsigned a = 0, g2 = 0;
-        for (int w = 0; w < wave; ++w) {
-            a += s_w4[w];
-            g2 += s_w4[4 + w];
-        }
-        s_first[threadIdx.x] = tile_cnt + a;
-        s_dest[threadIdx.x] = dig_total + g2 + dig_pre;
-    }
-    __syncthreads();
-#pragma unroll
-    for (int j = 0; j < kPer; ++j) {
-        if (sort_index(j) < N) {
-            const unsigned d = (k[j] >> shift) & 255u;
-            const unsigned slot = s_first[d] + wcnt[wave][d] + rank[j];
-            s_key[slot] = (uint16_t)k[j];
-            s_val[slot] = v[j];
-        }
-    }
-    __syncthreads();
-    const int64_t left = N - (int64_t)blockIdx.x * kTile;
-    const int in_tile = left < kTile ? (int)left : kTile;
-#pragma unroll
-    for (int j = 0; j < kPer; ++j) {
-        const int slot = j * kSortBlock + threadIdx.x;
-        if (slot < in_tile) {
-            const unsigned key = s_key[slot];
-            const unsigned d = (key >> shift) & 255u;
-            const unsigned pos = s_dest[d] + ((unsigned)slot - s_first[d]);
-            keys_out[pos] = (uint16_t)key;
-            vals_out[pos] = s_val[slot];
-        }
-    }
-}
+};
 
 // start[c] = first position of code c in the sorted order (= position of the next present
 // code when c is absent); start[csize] = N.  Also clears the length of the list of long segments.
@@ -640,7 +452,7 @@ pv_status pv_launch_codebook_grads(pv_ctx *ctx, const pv_layout *l, const float 
     }
 
     const size_t nn = (size_t)N;
-    const int nblocks = (int)((N + kTile - 1) / kTile);           // tiles of a sorting pass
+    const int nblocks = (int)((N + kSortTile - 1) / kSortTile);           // tiles of a sorting pass
     const int hist_n = 256 * nblocks;
     size_t o_start = 0;
     size_t o_long = o_start + align_up((size_t)(csize + 1) * 4);
@@ -682,18 +494,21 @@ pv_status pv_launch_codebook_grads(pv_ctx *ctx, const pv_layout *l, const float 
         // pass over the low 8 bits of the codes (the only one when B <= 8) ...
         uint16_t *k1 = two ? keys_a : keys_b;
         int32_t *v1 = two ? vals_a : order;
-        hipLaunchKernelGGL(k_pg_digit_hist<true>, dim3(nblocks), dim3(kSortBlock), 0, sm, codes, N, M, m,
-                           mask, 0, nblocks, hist);
-        hipLaunchKernelGGL(k_pg_row_scan, dim3(256), dim3(kBlock), 0, sm, hist, nblocks, hbase, dig_totals);
-        hipLaunchKernelGGL(k_pg_digit_scatter<true>, dim3(nblocks), dim3(kSortBlock), 0, sm, codes,
-                           (const int32_t *)nullptr, N, M, m, mask, 0, nblocks, hbase, dig_totals, k1, v1);
+        const code_keys ck{codes, M, m, mask};
+        hipLaunchKernelGGL(k_digit_hist<code_keys>, dim3(nblocks), dim3(kSortBlock), 0, sm, ck, N, 0,
+                           nblocks, hist);
+        hipLaunchKernelGGL(k_row_scan, dim3(256), dim3(kRadixBlock), 0, sm, hist, nblocks, hbase, dig_totals);
+        hipLaunchKernelGGL((k_digit_scatter<code_keys, uint16_t>), dim3(nblocks), dim3(kSortBlock), 0,
+                           sm, ck, (const int32_t *)nullptr, N, 0, nblocks, hbase, dig_totals, k1, v1);
         if (two) {   // ... and over the high ones
-            hipLaunchKernelGGL(k_pg_digit_hist<false>, dim3(nblocks), dim3(kSortBlock), 0, sm, keys_a, N,
-                               1, 0, mask, 8, nblocks, hist);
-            hipLaunchKernelGGL(k_pg_row_scan, dim3(256), dim3(kBlock), 0, sm, hist, nblocks, hbase,
+            const plain_keys<uint16_t> pk{keys_a};
+            hipLaunchKernelGGL(k_digit_hist<plain_keys<uint16_t>>, dim3(nblocks), dim3(kSortBlock), 0,
+                               sm, pk, N, 8, nblocks, hist);
+            hipLaunchKernelGGL(k_row_scan, dim3(256), dim3(kRadixBlock), 0, sm, hist, nblocks, hbase,
                                dig_totals);
-            hipLaunchKernelGGL(k_pg_digit_scatter<false>, dim3(nblocks), dim3(kSortBlock), 0, sm, keys_a,
-                               vals_a, N, 1, 0, mask, 8, nblocks, hbase, dig_totals, keys_b, order);
+            hipLaunchKernelGGL((k_digit_scatter<plain_keys<uint16_t>, uint16_t>), dim3(nblocks),
+                               dim3(kSortBlock), 0, sm, pk, (const int32_t *)vals_a, N, 8, nblocks, hbase,
+                               dig_totals, keys_b, order);
         }
         hipLaunchKernelGGL(k_pg_starts, dim3((unsigned)((N + kBlock - 1) / kBlock)), dim3(kBlock), 0,
                            sm, keys_b, N, csize, start, nlong);

@@ -8,8 +8,9 @@
 // chunk.  Since the change only grows with the number of groups, the result is
 // the longest prefix of the ranked candidates that satisfies the bound, so the
 // work is done once for all candidates:
-//   ranked candidates (radix select, then a stable sort of the k_max selected
-//   keys) -> all candidates re-encoded in place (previous codes saved) ->
+//   ranked candidates (radix select, then a stable descending sort of the k_max
+//   selected keys: inside one block's LDS when they fit, else the four-pass
+//   device-wide radix sort) -> all candidates re-encoded in place (previous codes saved) ->
 //   squared change per candidate -> prefix sums in rank order -> first prefix
 //   that breaks the bound -> codes of the candidates behind it restored.
 // Everything stays on the device; the kept count is written to device memory.
@@ -19,9 +20,8 @@
 // prefix sums and ||x^k||^2 are double sums in a fixed (launch-independent)
 // association, so a run is reproducible; they differ from a sequential sum by
 // rounding only.
-#include <hipcub/hipcub.hpp>
-
 #include "pv_internal.h"
+#include "pv_radix.h"
 
 namespace {
 
@@ -83,6 +83,199 @@ __global__ __launch_bounds__(kBlock) void k_tr_gather(const int32_t *__restrict_
     }
 }
 
+// Ranking of up to kSmallMax candidates in two kernels.  First every block sorts one tile of
+// kRankTile candidates in LDS: a stable radix sort of the complemented keys (descending
+// scores, equal scores in the order they came in, i.e. ascending ids), four passes of 8 bits,
+// the (key, position) pairs held in registers between passes - wave w holds the consecutive
+// run w * kRankRounds * 64 .., 64 pairs a round - and written through LDS once per pass to
+// the slot their digit rank gives them.  Slots beyond k are padded with the largest key and
+// positions >= k, so they stay behind.  Then k_tr_merge_ranks places every candidate among
+// the other tiles by bisection.
+constexpr int kRankRounds = 1;
+constexpr int kRankTile = kSortBlock * kRankRounds;      // 1024
+constexpr int kRankTilesMax = 32;
+constexpr int kSmallMax = kRankTile * kRankTilesMax;     // 32768
+// The kernel also does what k_tr_gather does for the device-wide route: the keys are read
+// straight from the scores of the selected groups, the candidates' codes are saved, and block 0
+// adds up the partial norms and resets the state.
+__global__ __launch_bounds__(kSortBlock) void k_tr_sort_tiles(
+    const int32_t *__restrict__ idx, const float *__restrict__ scores, int k,
+    const uint16_t *__restrict__ codes, int M, uint16_t *__restrict__ old_codes,
+    const double *__restrict__ norm_partial, int norm_parts, tr_state *__restrict__ state,
+    unsigned *__restrict__ tile_keys, int32_t *__restrict__ tile_pos)
+{
+    __shared__ unsigned s_key[kRankTile];
+    __shared__ unsigned s_pos[kRankTile];
+    __shared__ unsigned wcnt[kSortWaves][256];
+    __shared__ unsigned s_first[256];
+    __shared__ unsigned s_w4[4];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int tile0 = blockIdx.x * kRankTile;
+    unsigned key[kRankRounds], pos[kRankRounds], rank[kRankRounds];
+#pragma unroll
+    for (int j = 0; j < kRankRounds; ++j) {
+        const int e = tile0 + (wave * kRankRounds + j) * 64 + lane;
+        pos[j] = (unsigned)e;
+        key[j] = 0xFFFFFFFFu;
+        if (e < k) {
+            const int64_t n = idx[e];
+            key[j] = ~__float_as_uint(scores[n]);   // scores are >= +0: the bits order like the values
+            for (int m = 0; m < M; ++m) old_codes[(int64_t)e * M + m] = codes[n * M + m];
+        }
+    }
+    if (blockIdx.x == 0) {                // the partial norms, added as k_tr_gather adds them
+        __shared__ double s_norm[kBlock / 64];
+        double acc = 0.0;
+        if (threadIdx.x < kBlock) {
+            for (int i = threadIdx.x; i < norm_parts; i += kBlock) acc = acc + norm_partial[i];
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) acc = acc + __shfl_down(acc, off);
+            if (lane == 0) s_norm[wave] = acc;
+        }
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            double t = 0.0;
+            for (int w = 0; w < kBlock / 64; ++w) t = t + s_norm[w];
+            state->normsq = t;
+            state->first_violation = kNone;
+            state->first_moved = kNone;
+            state->kept = 0;
+        }
+    }
+    const unsigned long long below = (1ull << lane) - 1ull;
+    for (int shift = 0; shift < 32; shift += 8) {
+        for (int w = threadIdx.x; w < kSortWaves * 256; w += kSortBlock) (&wcnt[0][0])[w] = 0u;
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < kRankRounds; ++j) {
+            const unsigned d = (key[j] >> shift) & 255u;
+            unsigned long long same = ~0ull;
+#pragma unroll
+            for (int bit = 0; bit < 8; ++bit) {
+                const unsigned long long has = __ballot((d >> bit) & 1u);
+                same &= ((d >> bit) & 1u) ? has : ~has;
+            }
+            const unsigned before = wcnt[wave][d];
+            rank[j] = before + (unsigned)__popcll(same & below);
+            if (lane == 63 - __clzll(same)) wcnt[wave][d] = before + (unsigned)__popcll(same);
+        }
+        __syncthreads();
+        unsigned cnt = 0;
+        if (threadIdx.x < 256) {          // one digit each: offsets of the waves, then of the digits
+            unsigned c[kSortWaves];
+#pragma unroll
+            for (int w = 0; w < kSortWaves; ++w) c[w] = wcnt[w][threadIdx.x];
+#pragma unroll
+            for (int w = 0; w < kSortWaves; ++w) {
+                wcnt[w][threadIdx.x] = cnt;
+                cnt += c[w];
+            }
+            unsigned a = cnt;
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                const unsigned oa = __shfl_up(a, off);
+                if (lane >= off) a += oa;
+            }
+            if (lane == 63) s_w4[wave] = a;
+            cnt = a - cnt;                // exclusive inside the wave
+        }
+        __syncthreads();
+        if (threadIdx.x < 256) {
+            unsigned a = 0;
+            for (int w = 0; w < wave; ++w) a += s_w4[w];
+            s_first[threadIdx.x] = cnt + a;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int j = 0; j < kRankRounds; ++j) {
+            const unsigned d = (key[j] >> shift) & 255u;
+            const unsigned slot = s_first[d] + wcnt[wave][d] + rank[j];
+            s_key[slot] = key[j];
+            s_pos[slot] = pos[j];
+        }
+        __syncthreads();
+        if (shift < 24) {
+#pragma unroll
+            for (int j = 0; j < kRankRounds; ++j) {
+                const int e = (wave * kRankRounds + j) * 64 + lane;
+                key[j] = s_key[e];
+                pos[j] = s_pos[e];
+            }
+        }
+    }
+    for (int r = threadIdx.x; r < kRankTile && tile0 + r < k; r += kSortBlock) {
+        tile_keys[tile0 + r] = s_key[r];
+        tile_pos[tile0 + r] = (int32_t)s_pos[r];
+    }
+}
+
+// Rank of every candidate among all tiles: its place in its own sorted tile plus, for every
+// other tile, the number of that tile's (complemented) keys that come before it - keys that
+// are smaller, and in the tiles before its own also the equal ones, whose ids are lower.
+// All tiles' keys sit in LDS; the bisections of one candidate over the tiles advance together.
+constexpr int kMergeParts = 8;                                  // threads per candidate
+constexpr int kMergeCands = kSortBlock / kMergeParts;           // candidates per block
+__global__ __launch_bounds__(kSortBlock) void k_tr_merge_ranks(const unsigned *__restrict__ tile_keys,
+                                                               const int32_t *__restrict__ tile_pos,
+                                                               int k, int32_t *__restrict__ order)
+{
+    __shared__ unsigned s_all[kSmallMax];
+    {   // all keys into LDS, 16 bytes a load, every load of a thread in flight together (the
+        // array is padded to 256 bytes, so the last vector may reach past k)
+        typedef unsigned u4 __attribute__((ext_vector_type(4)));
+        const u4 *src = reinterpret_cast<const u4 *>(tile_keys);
+        const int nvec = (k + 3) >> 2;
+        constexpr int kVecs = kSmallMax / 4 / kSortBlock;       // 8 vectors a thread at most
+        u4 buf[kVecs];
+#pragma unroll
+        for (int u = 0; u < kVecs; ++u) {
+            const int v = u * kSortBlock + threadIdx.x;
+            buf[u] = src[v < nvec ? v : 0];
+        }
+#pragma unroll
+        for (int u = 0; u < kVecs; ++u) {
+            const int v = u * kSortBlock + threadIdx.x;
+            if (v < nvec) reinterpret_cast<u4 *>(s_all)[v] = buf[u];
+        }
+    }
+    __syncthreads();
+    const int tiles = (k + kRankTile - 1) / kRankTile;
+    const int part = threadIdx.x % kMergeParts;                 // this thread's tiles: part, part + 8, ..
+    const int e = blockIdx.x * kMergeCands + threadIdx.x / kMergeParts;
+    const int ec = e < k ? e : k - 1;
+    const int own = ec / kRankTile, local = ec - own * kRankTile;
+    const unsigned key = s_all[ec];
+    constexpr int kSlots = kRankTilesMax / kMergeParts;
+    int lo[kSlots], len[kSlots];
+#pragma unroll
+    for (int q = 0; q < kSlots; ++q) {
+        const int b = part + q * kMergeParts;
+        lo[q] = 0;
+        const int left = k - b * kRankTile;
+        len[q] = (b < tiles && b != own) ? (left < kRankTile ? left : kRankTile) : 0;
+    }
+    // lo[q] = number of keys of that tile that come before this one, by halving the range
+    for (int step = 0; step < 11; ++step) {
+#pragma unroll
+        for (int q = 0; q < kSlots; ++q) {
+            const int b = part + q * kMergeParts;
+            const int half = len[q] >> 1;
+            const int at = b * kRankTile + lo[q] + half;
+            const unsigned probe = s_all[len[q] > 0 ? at : 0];
+            const bool before = b < own ? probe <= key : probe < key;
+            const bool go = len[q] > 0 && before;
+            lo[q] = go ? lo[q] + half + 1 : lo[q];
+            len[q] = len[q] > 0 ? (before ? len[q] - half - 1 : half) : 0;
+        }
+    }
+    int rank = 0;
+#pragma unroll
+    for (int q = 0; q < kSlots; ++q) rank += lo[q];
+#pragma unroll
+    for (int off = 1; off < kMergeParts; off <<= 1) rank += __shfl_xor(rank, off);
+    if (part == 0 && e < k) order[local + rank] = tile_pos[e];
+}
+
 // dequantised weight i of a group (fp32 additions in codebook order, one multiply)
 __device__ __forceinline__ float deq_weight(const float *__restrict__ codebooks,
                                             const uint16_t *code, int M, int64_t csize, int g,
@@ -117,6 +310,55 @@ __device__ __forceinline__ double candidate_change(int64_t n, int64_t j,
         }
     *moved = mv;
     return d;
+}
+
+// ||x^k||^2 for one codebook and g = 4 * LPG (8 or 16): LPG neighbouring lanes share a group
+// and read neighbouring 16-byte pieces of its codeword, so that one request to L2 brings the
+// whole codeword (the kernel is bound by the number of such requests: the codebook is L2
+// resident, the rows are picked at random).  Block b sums the groups
+// [b * per_block, (b + 1) * per_block); a thread adds the squares of its four weights of the
+// groups t / LPG, t / LPG + 256 / LPG, ..., in that order, kGroups groups in flight.
+template <int LPG>
+__global__ __launch_bounds__(kBlock) void k_tr_normsq_rows(const uint16_t *__restrict__ codes,
+                                                           const float *__restrict__ codebooks,
+                                                           const float *__restrict__ scales, int64_t N,
+                                                           int64_t per_block, int nbits, int gpr,
+                                                           double *__restrict__ partial)
+{
+    __shared__ double tmp[kBlock / 64];
+    constexpr int kGroups = 8;
+    constexpr int kStride = kBlock / LPG;
+    const unsigned mask = (1u << nbits) - 1u;
+    const int64_t lo = (int64_t)blockIdx.x * per_block;
+    const int64_t hi = lo + per_block < N ? lo + per_block : N;
+    const int piece = threadIdx.x % LPG;
+    const pv_f4 *cb4 = reinterpret_cast<const pv_f4 *>(codebooks);
+    double acc = 0.0;
+    for (int64_t n0 = lo + threadIdx.x / LPG; n0 < hi; n0 += (int64_t)kStride * kGroups) {
+        unsigned code[kGroups];
+        float s[kGroups];
+#pragma unroll
+        for (int u = 0; u < kGroups; ++u) {
+            const int64_t n = n0 + (int64_t)u * kStride;
+            code[u] = n < hi ? (codes[n] & mask) : 0u;
+            s[u] = n < hi ? scales[n / gpr] : 0.0f;
+        }
+        pv_f4 c[kGroups];
+#pragma unroll
+        for (int u = 0; u < kGroups; ++u) c[u] = cb4[(int64_t)code[u] * LPG + piece];
+#pragma unroll
+        for (int u = 0; u < kGroups; ++u) {
+            if (n0 + (int64_t)u * kStride < hi) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    double w = (double)(s[u] * c[u][e]);
+                    acc = acc + w * w;
+                }
+            }
+        }
+    }
+    acc = block_sum(acc, tmp);
+    if (threadIdx.x == 0) partial[blockIdx.x] = acc;
 }
 
 // ||x^k||^2: block b sums the groups [b * per_block, (b + 1) * per_block), thread t of it the
@@ -269,6 +511,7 @@ __global__ __launch_bounds__(kBlock) void k_tr_tile_offsets(double *__restrict__
 __global__ __launch_bounds__(kBlock) void k_tr_prefix(const double *__restrict__ delta,
                                                       const uint8_t *__restrict__ moved, int k,
                                                       const double *__restrict__ tile_off,
+                                                      bool offsets_ready /* else: tile sums */,
                                                       double ratio, double *__restrict__ prefix,
                                                       tr_state *__restrict__ state)
 {
@@ -287,7 +530,13 @@ __global__ __launch_bounds__(kBlock) void k_tr_prefix(const double *__restrict__
         mine = mine + d[e];
     }
     double total;
-    const double off = tile_off[blockIdx.x] + tile_exclusive(mine, s_wave, &total);
+    double before_tile = 0.0;
+    if (offsets_ready) {
+        before_tile = tile_off[blockIdx.x];
+    } else {              // few tiles: the sums of the tiles before this one, added in tile order
+        for (int t = 0; t < (int)blockIdx.x; ++t) before_tile = before_tile + tile_off[t];
+    }
+    const double off = before_tile + tile_exclusive(mine, s_wave, &total);
     const double bound = ratio * ratio * state->normsq;
     unsigned viol = kNone, first_mv = kNone;
     double run = off;
@@ -357,16 +606,13 @@ pv_status pv_launch_trust_ratio(pv_ctx *ctx, const pv_layout *l, const float *T,
     const int gpr = (int)(l->in_features / g);
     const int k = (int)k_max;
     const int tiles = (k + kTile - 1) / kTile;
-    int norm_blocks = (int)((N + 4095) / 4096);
-    if (norm_blocks > 1024) norm_blocks = 1024;
+    int norm_blocks = (int)((N + 1023) / 1024);       // a round of gathers per thread: latency, not volume, sets the time
+    if (norm_blocks > 4096) norm_blocks = 4096;
     if (norm_blocks < 1) norm_blocks = 1;
     const int64_t per_block = (N + norm_blocks - 1) / norm_blocks;
 
-    size_t sort_bytes = 0;
-    if (k > 0)
-        PV_HIP(ctx, hipcub::DeviceRadixSort::SortPairsDescending(
-                        nullptr, sort_bytes, (const unsigned *)nullptr, (unsigned *)nullptr,
-                        (const int32_t *)nullptr, (int32_t *)nullptr, k, 0, 32, ctx->stream));
+    const int sort_tiles = (k + kSortTile - 1) / kSortTile;      // tiles of a device-wide sorting pass
+    const bool small_sort = k <= kSmallMax;
     // one scratch block, carved up
     const size_t kk = (size_t)(k > 0 ? k : 1);
     size_t o_state = 0;
@@ -381,8 +627,12 @@ pv_status pv_launch_trust_ratio(pv_ctx *ctx, const pv_layout *l, const float *T,
     size_t o_moved = o_prefix + align_up((kk + 1) * 8);
     size_t o_tiles = o_moved + align_up(kk);
     size_t o_norm = o_tiles + align_up((size_t)(tiles > 0 ? tiles : 1) * 8);
-    size_t o_sort = o_norm + align_up((size_t)norm_blocks * 8);
-    size_t total = o_sort + align_up(sort_bytes);
+    size_t o_keys3 = o_norm + align_up((size_t)norm_blocks * 8);
+    size_t o_vals2 = o_keys3 + align_up(small_sort ? 0 : kk * 4);
+    size_t o_hist = o_vals2 + align_up(small_sort ? 0 : kk * 4);
+    size_t o_rowpre = o_hist + align_up(small_sort ? 0 : (size_t)sort_tiles * 256 * 4);
+    size_t o_totals = o_rowpre + align_up(small_sort ? 0 : (size_t)sort_tiles * 256 * 4);
+    size_t total = o_totals + 1024;
     pv_status st = pv_ensure(ctx, ctx->trust, total);
     if (st != PV_OK) return st;
     st = pv_ensure(ctx, ctx->sel_scores, (size_t)N * sizeof(float) + 16);
@@ -400,14 +650,24 @@ pv_status pv_launch_trust_ratio(pv_ctx *ctx, const pv_layout *l, const float *T,
     uint8_t *moved = reinterpret_cast<uint8_t *>(base + o_moved);
     double *tile_sum = reinterpret_cast<double *>(base + o_tiles);
     double *norm_partial = reinterpret_cast<double *>(base + o_norm);
-    void *sort_tmp = base + o_sort;
+    unsigned *keys3 = reinterpret_cast<unsigned *>(base + o_keys3);
+    int32_t *vals2 = reinterpret_cast<int32_t *>(base + o_vals2);
+    unsigned *hist = reinterpret_cast<unsigned *>(base + o_hist);
+    unsigned *rowpre = reinterpret_cast<unsigned *>(base + o_rowpre);
+    unsigned *totals = reinterpret_cast<unsigned *>(base + o_totals);
     float *scores = static_cast<float *>(ctx->sel_scores.ptr);
     hipStream_t sm = ctx->stream;
 
     // ||x^k||^2 of the codes as they are now (partial sums; the gather kernel adds them up)
     {
         pv_timed t(ctx, PV_K_TRUST_RATIO);
-        if (M == 1 && g % 4 == 0)
+        if (M == 1 && g == 8)
+            hipLaunchKernelGGL(k_tr_normsq_rows<2>, dim3(norm_blocks), dim3(kBlock), 0, sm, codes, codebooks,
+                               scales, N, per_block, l->nbits, gpr, norm_partial);
+        else if (M == 1 && g == 16)
+            hipLaunchKernelGGL(k_tr_normsq_rows<4>, dim3(norm_blocks), dim3(kBlock), 0, sm, codes, codebooks,
+                               scales, N, per_block, l->nbits, gpr, norm_partial);
+        else if (M == 1 && g % 4 == 0)
             hipLaunchKernelGGL((k_tr_normsq<1, true>), dim3(norm_blocks), dim3(kBlock), 0, sm, codes,
                                codebooks, scales, N, per_block, g, M, l->nbits, gpr, norm_partial);
         else
@@ -420,12 +680,44 @@ pv_status pv_launch_trust_ratio(pv_ctx *ctx, const pv_layout *l, const float *T,
     const unsigned kblocks = (unsigned)((k + kBlock - 1) / kBlock);
     {
         pv_timed t(ctx, PV_K_TRUST_RATIO);
-        hipLaunchKernelGGL(k_tr_gather, dim3(kblocks > 0 ? kblocks : 1), dim3(kBlock), 0, sm, idx, k,
-                           scores, codes, M, old_codes, keys, pos, norm_partial, norm_blocks, state);
-        // equal keys keep their order (ascending ids): the sort is stable
-        if (k > 0)
-            PV_HIP(ctx, hipcub::DeviceRadixSort::SortPairsDescending(sort_tmp, sort_bytes, keys, keys2,
-                                                                     pos, order, k, 0, 32, sm));
+        if (!(k > 0 && small_sort))
+            hipLaunchKernelGGL(k_tr_gather, dim3(kblocks > 0 ? kblocks : 1), dim3(kBlock), 0, sm, idx, k,
+                               scores, codes, M, old_codes, keys, pos, norm_partial, norm_blocks, state);
+        // descending keys; equal keys keep their order (ascending ids): the sort is stable
+        if (k > 0 && small_sort) {
+            const unsigned rtiles = (unsigned)((k + kRankTile - 1) / kRankTile);
+            hipLaunchKernelGGL(k_tr_sort_tiles, dim3(rtiles), dim3(kSortBlock), 0, sm, idx, scores, k, codes,
+                               M, old_codes, norm_partial, norm_blocks, state, keys2, pos);
+            hipLaunchKernelGGL(k_tr_merge_ranks, dim3((unsigned)((k + kMergeCands - 1) / kMergeCands)),
+                               dim3(kSortBlock), 0, sm, keys2, pos, k, order);
+        } else if (k > 0) {
+            // four passes over the complemented keys; (keys2, pos) and (keys3, vals2) take turns
+            for (int pass = 0; pass < 4; ++pass) {
+                unsigned *k_out = (pass & 1) ? keys3 : keys2;
+                int32_t *v_out = pass == 3 ? order : ((pass & 1) ? vals2 : pos);
+                const unsigned *k_in = (pass & 1) ? keys2 : keys3;
+                const int32_t *v_in = (pass & 1) ? pos : vals2;
+                if (pass == 0) {
+                    const descending_keys dk{keys};
+                    hipLaunchKernelGGL(k_digit_hist<descending_keys>, dim3(sort_tiles), dim3(kSortBlock),
+                                       0, sm, dk, (int64_t)k, 0, sort_tiles, hist);
+                    hipLaunchKernelGGL(k_row_scan, dim3(256), dim3(kRadixBlock), 0, sm, hist, sort_tiles,
+                                       rowpre, totals);
+                    hipLaunchKernelGGL((k_digit_scatter<descending_keys, unsigned>), dim3(sort_tiles),
+                                       dim3(kSortBlock), 0, sm, dk, (const int32_t *)nullptr, (int64_t)k, 0,
+                                       sort_tiles, rowpre, totals, k_out, v_out);
+                } else {
+                    const plain_keys<unsigned> pk{k_in};
+                    hipLaunchKernelGGL(k_digit_hist<plain_keys<unsigned>>, dim3(sort_tiles),
+                                       dim3(kSortBlock), 0, sm, pk, (int64_t)k, 8 * pass, sort_tiles, hist);
+                    hipLaunchKernelGGL(k_row_scan, dim3(256), dim3(kRadixBlock), 0, sm, hist, sort_tiles,
+                                       rowpre, totals);
+                    hipLaunchKernelGGL((k_digit_scatter<plain_keys<unsigned>, unsigned>), dim3(sort_tiles),
+                                       dim3(kSortBlock), 0, sm, pk, v_in, (int64_t)k, 8 * pass, sort_tiles,
+                                       rowpre, totals, k_out, v_out);
+                }
+            }
+        }
     }
     if (k > 0) {
         st = pv_reencode_dispatch(ctx, l, T, codebooks, scales, idx, k, beam_width, codes, nullptr);
@@ -437,9 +729,11 @@ pv_status pv_launch_trust_ratio(pv_ctx *ctx, const pv_layout *l, const float *T,
             hipLaunchKernelGGL(k_tr_delta, dim3(kblocks), dim3(kBlock), 0, sm, idx, order, k, old_codes,
                                codes, codebooks, scales, g, M, l->nbits, gpr, delta, moved);
             hipLaunchKernelGGL(k_tr_tile_sums, dim3(tiles), dim3(kBlock), 0, sm, delta, k, tile_sum);
-            hipLaunchKernelGGL(k_tr_tile_offsets, dim3(1), dim3(kBlock), 0, sm, tile_sum, tiles);
+            const bool few = tiles <= 256;   // then every block adds the earlier tile sums itself
+            if (!few)
+                hipLaunchKernelGGL(k_tr_tile_offsets, dim3(1), dim3(kBlock), 0, sm, tile_sum, tiles);
             hipLaunchKernelGGL(k_tr_prefix, dim3(tiles), dim3(kBlock), 0, sm, delta, moved, k,
-                               tile_sum, ratio, prefix, state);
+                               (const double *)tile_sum, !few, ratio, prefix, state);
         }
         hipLaunchKernelGGL(k_tr_rollback, dim3(kblocks > 0 ? kblocks : 1), dim3(kBlock), 0, sm, idx,
                            order, k, old_codes, codes, M, state, prefix, chunk, rank_idx, num_applied,

@@ -102,3 +102,17 @@ def test_trust_ratio_argument_errors():
             run.ctx.pv_reencode_trust_ratio(run.lay, T, run.W, run.cb, run.sc, k_max, chunk, ratio,
                                             1, codes, None, napp)
     assert np.array_equal(host_u16(codes), wl.codes)     # nothing was written
+
+
+@pytest.mark.parametrize("k_max", [1024, 1025, 20971, 32768, 32769, 40000])
+def test_trust_ratio_ranks_more_candidates_than_one_block_sorts(k_max):
+    """Up to 32768 candidates are ranked as tiles of 1024 sorted in LDS and merged by bisection (one
+    tile, a tile and one element, twenty-one tiles with a ragged tail, thirty-two full tiles); beyond
+    that the ranking takes the device-wide sorting passes (tiles of 8192).  Scores are made to
+    repeat (few distinct gradient magnitudes) so that equal keys have to keep ascending ids."""
+    wl = workloads.make(256, 2048, 8, 1, 8, seed=45, sigma_g=1e-2)      # 65536 groups
+    rng = np.random.default_rng(45)
+    wl.G[:] = rng.choice(np.array([1e-3, 2e-3, -2e-3, 4e-3], np.float32), size=wl.G.shape)
+    wl.G[rng.random(wl.G.shape) < 0.3] = 0.0
+    L, info = run_case(wl, k_max=k_max, chunk=997, ratio=0.02)
+    assert 0 < L <= k_max
