@@ -510,17 +510,6 @@ __device__ __forceinline__ int imed3(int a, int b, int c)
 template <bool FIRST>
 __device__ __forceinline__ int acc_max(const f16v &acc, int run)
 {
-#ifdef PV_TREE
-    // two independent chains
-    int m1 = imax3(__float_as_int(acc[0]), __float_as_int(acc[1]), __float_as_int(acc[2]));
-    int m2 = imax3(__float_as_int(acc[8]), __float_as_int(acc[9]), __float_as_int(acc[10]));
-    m1 = imax3(m1, __float_as_int(acc[3]), __float_as_int(acc[4]));
-    m2 = imax3(m2, __float_as_int(acc[11]), __float_as_int(acc[12]));
-    m1 = imax3(m1, __float_as_int(acc[5]), __float_as_int(acc[6]));
-    m2 = imax3(m2, __float_as_int(acc[13]), __float_as_int(acc[14]));
-    m1 = imax3(m1, __float_as_int(acc[7]), (FIRST && run == kNoKey) ? __float_as_int(acc[7]) : run);
-    return imax3(m1, m2, __float_as_int(acc[15]));
-#endif
     int m;
     if (FIRST && run == kNoKey) {
         m = imax3(__float_as_int(acc[0]), __float_as_int(acc[1]), __float_as_int(acc[2]));
@@ -545,13 +534,8 @@ __device__ __forceinline__ int acc_max(const f16v &acc, int run)
 // place of the record of (partition p, list position j)
 __device__ __forceinline__ int64_t rec_at(int p, int64_t j, int P, int k_pad)
 {
-#ifdef PV_REC_BY_GROUP
-    (void)k_pad;
-    return j * P + p;
-#else
     (void)P;
     return (int64_t)p * k_pad + j;
-#endif
 }
 
 // The distance contraction.  Block = PV_WAVES waves; wave w owns NB group tiles (32 groups
@@ -672,23 +656,6 @@ __global__ __launch_bounds__(PV_WAVES * 64, (PV_OCC * PV_WAVES) / 4) void k_scor
             for (int vr = 0; vr < kUnitsCycle; ++vr) {
                 const int u = vr / NB, nb = vr % NB, ts = q4 + u;
                 if (nb == 0) a_nxt = buf[(ts + 1) * 64 + lane];   // one spare tile pads the LDS array
-#ifdef PV_PAIR
-                // all group tiles of a codeword tile are issued back to back, then the units of
-                // the tile before are reduced
-                issue(nb, vr % kSets);
-                if (nb == NB - 1) {
-                    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                    for (int wnb = 0; wnb < NB; ++wnb) {
-                        const int wr = vr - (NB - 1) + wnb - NB;      // unit of the tile before
-                        const int dq = u - 1;
-                        if (q4 > 0 || wr >= 0)
-                            reduce(bufn, t0, (q4 + dq) / kU, (dq + kCycle) % kCycle, wnb,
-                                   (wr % kSets + kSets) % kSets);
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-#else
                 issue(nb, vr % kSets);
                 // the unit kD back: tile q4 + dq (dq may point into the cycle before), group tile wnb
                 const int dq = (vr - kD >= 0) ? (vr - kD) / NB : -((kD - vr + NB - 1) / NB);
@@ -700,7 +667,6 @@ __global__ __launch_bounds__(PV_WAVES * 64, (PV_OCC * PV_WAVES) / 4) void k_scor
                 // behind its own matrix instruction, and the wave then waits out that
                 // instruction's whole latency instead of working on older units
                 __builtin_amdgcn_sched_barrier(0);
-#endif
                 if (nb == NB - 1) a_cur = a_nxt;
             }
         }
@@ -1121,11 +1087,7 @@ __global__ __launch_bounds__(kBlock) void k_rerank(
     // ---- groups left open: every position of their open partitions, by the whole block, one
     // group at a time.
     // Partition p = (codeword split, half wave, residue class) as the scoring kernel numbers them.
-#ifdef PV_TIMING_ONLY_NO_OPEN
-    const unsigned nopen = 0;
-#else
     const unsigned nopen = s_nopen;
-#endif
     __shared__ double s_obj[kBlock / 64];
     __shared__ int s_idx[kBlock / 64];
     for (unsigned item = 0; item < nopen; ++item) {

@@ -101,6 +101,11 @@ __global__ __launch_bounds__(kBlock) void k_encode_targets_adam(const float *W, 
 // One thread per VEC consecutive weights of a group: reads the group's code(s),
 // gathers VEC floats of each codeword (the codebook stays in L2), adds them in
 // codebook order, multiplies by the row scale, writes VEC floats.
+// VEC == 4: a thread takes kDeqAhead vectors a block-width apart and has all their codes, then
+// all their codewords, in flight together (two round trips per thread whatever the count:
+// with one vector a thread the kernel is bound by those trips, not by the 4 bytes a weight
+// it writes).
+constexpr int kDeqAhead = 4;
 template <int VEC>
 __global__ __launch_bounds__(kBlock) void k_dequantize(const uint16_t *__restrict__ codes,
                                                        const float *__restrict__ codebooks,
@@ -108,33 +113,60 @@ __global__ __launch_bounds__(kBlock) void k_dequantize(const uint16_t *__restric
                                                        float *__restrict__ W_out, int64_t total,
                                                        int g, int M, int nbits, int gpr)
 {
-    const int64_t idx = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-    if (idx >= total) return;
-    const int parts = g / VEC;
-    const int n = (int)(idx / parts);
-    const int q = (int)(idx - (int64_t)n * parts);
-    const int o = n / gpr;
     const unsigned mask = (1u << nbits) - 1u;
     const int64_t csize = (int64_t)1 << nbits;
-    const float s = scales[o];
-    const uint16_t *cp = codes + (int64_t)n * M;
     if constexpr (VEC == 4) {
+        const int parts = g / 4;
         const pv_f4 *cb4 = reinterpret_cast<const pv_f4 *>(codebooks);
-        pv_f4 acc = cb4[((int64_t)(cp[0] & mask) * g) / 4 + q];
-        for (int m = 1; m < M; ++m) {
-            pv_f4 c = cb4[((m * csize + (cp[m] & mask)) * g) / 4 + q];
-            acc.x = acc.x + c.x;
-            acc.y = acc.y + c.y;
-            acc.z = acc.z + c.z;
-            acc.w = acc.w + c.w;
+        const int64_t first = (int64_t)blockIdx.x * (kBlock * kDeqAhead) + threadIdx.x;
+        int64_t at[kDeqAhead];
+        int q[kDeqAhead];
+        unsigned code[kDeqAhead];
+        float s[kDeqAhead];
+        const uint16_t *cp[kDeqAhead];
+#pragma unroll
+        for (int u = 0; u < kDeqAhead; ++u) {
+            const int64_t idx = first + (int64_t)u * kBlock;
+            at[u] = idx < total ? idx : total - 1;
+            const int n = (int)(at[u] / parts);
+            q[u] = (int)(at[u] - (int64_t)n * parts);
+            cp[u] = codes + (int64_t)n * M;
+            code[u] = cp[u][0] & mask;
+            s[u] = scales[n / gpr];
         }
-        pv_f4 out;
-        out.x = s * acc.x;
-        out.y = s * acc.y;
-        out.z = s * acc.z;
-        out.w = s * acc.w;
-        __builtin_nontemporal_store(out, &reinterpret_cast<pv_f4 *>(W_out)[idx]);
+        pv_f4 acc[kDeqAhead];
+#pragma unroll
+        for (int u = 0; u < kDeqAhead; ++u) acc[u] = cb4[((int64_t)code[u] * g) / 4 + q[u]];
+        for (int m = 1; m < M; ++m) {
+            pv_f4 c[kDeqAhead];
+#pragma unroll
+            for (int u = 0; u < kDeqAhead; ++u)
+                c[u] = cb4[((m * csize + (cp[u][m] & mask)) * g) / 4 + q[u]];
+#pragma unroll
+            for (int u = 0; u < kDeqAhead; ++u) {
+                acc[u].x = acc[u].x + c[u].x;
+                acc[u].y = acc[u].y + c[u].y;
+                acc[u].z = acc[u].z + c[u].z;
+                acc[u].w = acc[u].w + c[u].w;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < kDeqAhead; ++u) {
+            pv_f4 out;
+            out.x = s[u] * acc[u].x;
+            out.y = s[u] * acc[u].y;
+            out.z = s[u] * acc[u].z;
+            out.w = s[u] * acc[u].w;
+            if (first + (int64_t)u * kBlock < total)
+                __builtin_nontemporal_store(out, &reinterpret_cast<pv_f4 *>(W_out)[at[u]]);
+        }
     } else {
+        const int64_t idx = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+        if (idx >= total) return;
+        const int n = (int)(idx / g);
+        const int q = (int)(idx - (int64_t)n * g);
+        const float s = scales[n / gpr];
+        const uint16_t *cp = codes + (int64_t)n * M;
         float acc = codebooks[(int64_t)(cp[0] & mask) * g + q];
         for (int m = 1; m < M; ++m) acc = acc + codebooks[(m * csize + (cp[m] & mask)) * g + q];
         W_out[idx] = s * acc;
@@ -265,7 +297,7 @@ pv_status pv_launch_dequantize(pv_ctx *ctx, const pv_layout *l, const uint16_t *
     const int gpr = (int)(l->in_features / g);
     if (g % 4 == 0) {
         int64_t total = N * (g / 4);
-        int64_t blocks = (total + kBlock - 1) / kBlock;
+        int64_t blocks = (total + kBlock * kDeqAhead - 1) / (kBlock * kDeqAhead);
         hipLaunchKernelGGL(k_dequantize<4>, dim3((unsigned)blocks), dim3(kBlock), 0, ctx->stream,
                            codes, codebooks, scales, W_out, total, g, l->num_codebooks, l->nbits,
                            gpr);
