@@ -322,6 +322,7 @@ __global__ __launch_bounds__(kBlock) void k_prep(const float *__restrict__ cb, i
                                                  const uint16_t *__restrict__ bucket,
                                                  unsigned *__restrict__ bucket_next,
                                                  unsigned *__restrict__ nmin_bits,
+                                                 float *__restrict__ cnorm,
                                                  const float *__restrict__ T,
                                                  const float *__restrict__ scales,
                                                  const int32_t *__restrict__ group_idx, int k,
@@ -365,10 +366,12 @@ __global__ __launch_bounds__(kBlock) void k_prep(const float *__restrict__ cb, i
                     const int rc = rank / per_cycle;
                     pos = (split_begin(rc % nsplit, ncyc, nsplit) + rc / nsplit) * per_cycle + rank % per_cycle;
                     atomicMin(&nmin_bits[pos / (16 * kU)], __float_as_uint(n2));
+                    cnorm[pos] = n2;           // for the re-rank kernel's cheap distances
                 }
                 perm[pos] = (uint16_t)c;
             } else if (G == 16) {
                 atomicMin(&nmin_bits[pos / (16 * kU)], 0u);   // padding rows count as norm 0
+                cnorm[pos] = 0.0f;
             }
             const int q = pos & 15, uu = (pos >> 4) % kU, hw = (pos / (16 * kU)) & 1;
             const int tile = (pos / (32 * kU)) * kU + uu;
@@ -775,24 +778,39 @@ __device__ __forceinline__ float key_upper(int key)
     return key < 0 ? 0.0f : __int_as_float(key | (int)kKeyMask);
 }
 
-// || c_hi - x_hi ||^2 of one table position from the operand row the matrix cores saw (it holds
-// 2 c_hi as fp16), in fp32: every term is non-negative, so the result lies within
-// (G + 2) 2^-24 of the exact value, relatively.  kDdSlack covers that with room to spare.
-constexpr float kDdSlack = 4.0e-6f;
+// || c_hi - x_hi ||^2 of one table position as || x_hi ||^2 + || c_hi ||^2 - <2 c_hi, x_hi>: the
+// product straight from the fp16 operands the matrix cores saw, two terms per instruction
+// (v_dot2c_f32_f16, fp32 accumulate), the codeword's norm from the operand row (g = 8: its
+// three pieces) or from the table k_prep keeps in position order (g = 16).  The three terms
+// cancel, so the error is absolute: (G + 4) 2^-24 (|| c_hi || + || x_hi ||)^2 bounds the
+// roundings of the two norms, of the G / 2 accumulation steps and of the final sum; kDdAbs
+// times that square covers it eight times over.  The value is only ever compared from below
+// (value - bound <= reach), so a generous bound costs a few needless exact evaluations.
+constexpr float kDdAbs = 1.0e-5f;
+typedef _Float16 h2 __attribute__((ext_vector_type(2)));
 template <int G>
-__device__ __forceinline__ float approx_dd(const h8 *__restrict__ A, int tile, int row, const float (&xh)[G])
+__device__ __forceinline__ float approx_dd(const h8 *__restrict__ A, const float *__restrict__ cnorm,
+                                           int tile, int row, int pos, const h8 (&xq)[G / 8], float xx)
 {
-    float dd = 0.0f;
+    float dot = 0.0f;
 #pragma unroll
     for (int h = 0; h < G / 8; ++h) {
         const h8 a = A[((int64_t)tile * 2 + h) * 32 + row];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const float d = 0.5f * (float)a[e] - xh[h * 8 + e];
-            dd = fmaf(d, d, dd);
+        for (int e = 0; e < 4; ++e) {
+            const h2 av = {a[2 * e], a[2 * e + 1]};
+            const h2 xv = {xq[h][2 * e], xq[h][2 * e + 1]};
+            dot = __builtin_amdgcn_fdot2(av, xv, dot, false);
         }
     }
-    return dd;
+    float cc;
+    if (G == 8) {
+        const h8 nrm = A[((int64_t)tile * 2 + 1) * 32 + row];
+        cc = ((float)nrm[0] + (float)nrm[1]) + (float)nrm[2];
+    } else {
+        cc = cnorm[pos];
+    }
+    return fmaxf((xx + cc) - dot, 0.0f);
 }
 
 // A group the team could not decide alone: the partitions whose codewords must all be
@@ -815,12 +833,16 @@ struct open_rec_t {
 // whoever asks for the call's statistics) and passes its changed codes on through atomics; no
 // block waits for another and none publishes plain stores to another (a device-wide release
 // costs a write-back of the whole L2 of the block's die).
+#ifndef PV_RR_OCC
+#define PV_RR_OCC 4   // blocks of the re-rank kernel per compute unit the register budget must allow (g = 16: 149 -> 128 registers, four waves per SIMD instead of three; five would spill)
+#endif
 template <int G>
-__global__ __launch_bounds__(kBlock) void k_rerank(
+__global__ __launch_bounds__(kBlock, PV_RR_OCC) void k_rerank(
     const float *__restrict__ x_stage, const float *__restrict__ codebook, int k, int k_pad,
     const int2 *__restrict__ partials, int P, int per_half, int ncyc, int nsplit,
     const float *__restrict__ x_meta, const unsigned *__restrict__ cb_meta, const h8 *__restrict__ A,
-    const h8 *__restrict__ X, const uint16_t *__restrict__ perm, uint16_t *__restrict__ codes,
+    const float *__restrict__ cnorm, const h8 *__restrict__ X, const uint16_t *__restrict__ perm,
+    uint16_t *__restrict__ codes,
     unsigned *__restrict__ block_counts, unsigned long long *__restrict__ change_slots,
     unsigned long long *__restrict__ num_changed, int nbits)
 {
@@ -895,18 +917,18 @@ __global__ __launch_bounds__(kBlock) void k_rerank(
         const int best_p = 63 - (int)(bk & 0xFFFFFFFFll);
 
         // the group's fp16 operand as the matrix cores saw it
-        float xh[G];
+        h8 xq[G / 8];
         {
             const int gt = j >> 5, col = j & 31;
 #pragma unroll
-            for (int h = 0; h < G / 8; ++h) {
-                const h8 v = X[((int64_t)gt * 2 + h) * 32 + col];
-#pragma unroll
-                for (int e = 0; e < 8; ++e) xh[h * 8 + e] = (float)v[e];
-            }
+            for (int h = 0; h < G / 8; ++h) xq[h] = X[((int64_t)gt * 2 + h) * 32 + col];
         }
         bool okP;
         const float Pscale = scale_from_maxabs(cb_meta[0], &okP);
+        // what the cheap distance may be off by, at most (see approx_dd)
+        const float nsum = Pscale * sqrtf(__uint_as_float(cb_meta[5])) * 1.0001f + kNormMargin +
+                           sqrtf(meta.y) * 1.0001f;
+        const float dabs = kDdAbs * nsum * nsum;
         const float dC = sqrtf(__uint_as_float(cb_meta[2])) * 1.0001f + 1e-30f;
         const float p_over_s = Pscale / fabsf(s);     // inf for a vanishing scale: nothing is excluded then
         // The 16 U positions behind a key (lane q takes positions q, q + kTeam, ... of each of the
@@ -926,7 +948,7 @@ __global__ __launch_bounds__(kBlock) void k_rerank(
                     pos[uu * kPer + e] = ((su * 2 + hw) * kU + uu) * 16 + qq;
                     // unconditional (the padded table has the row), so that the loads of all the
                     // lane's positions are in flight together
-                    dd[uu * kPer + e] = approx_dd<G>(A, su * kU + uu, row, xh);
+                    dd[uu * kPer + e] = approx_dd<G>(A, cnorm, su * kU + uu, row, pos[uu * kPer + e], xq, meta.y);
                 }
 #pragma unroll
             for (int i = 0; i < kMine; ++i)
@@ -996,7 +1018,7 @@ __global__ __launch_bounds__(kBlock) void k_rerank(
             const float r2f = reach2_of(e_star);
 #pragma unroll
             for (int uu = 0; uu < kMine; ++uu)
-                if (!(chosen && uu == wu) && dd[uu] * (1.0f - kDdSlack) <= r2f && pos[uu] < csize) {
+                if (!(chosen && uu == wu) && dd[uu] - dabs <= r2f && pos[uu] < csize) {
                     exact_at(pos[uu], mine);
                     ++exact_evals;
                 }
@@ -1046,7 +1068,7 @@ __global__ __launch_bounds__(kBlock) void k_rerank(
                 level1(key, src + kTeam * u, dd, pos);
 #pragma unroll
                 for (int uu = 0; uu < kMine; ++uu)
-                    if (dd[uu] * (1.0f - kDdSlack) <= reach2f && pos[uu] < csize) {
+                    if (dd[uu] - dabs <= reach2f && pos[uu] < csize) {
                         exact_at(pos[uu], mine);
                         ++exact_evals;
                     }
@@ -1110,16 +1132,17 @@ __global__ __launch_bounds__(kBlock) void k_rerank(
         const int qq = threadIdx.x & 15, slot = threadIdx.x >> 4;
         constexpr int kSlots = kBlock / 16;
         // the group's fp16 operand as the matrix cores saw it
-        float xh[G];
+        h8 xq[G / 8];
         {
             const int gt = rec.j >> 5, col = rec.j & 31;
 #pragma unroll
-            for (int h = 0; h < G / 8; ++h) {
-                const h8 v = X[((int64_t)gt * 2 + h) * 32 + col];
-#pragma unroll
-                for (int e = 0; e < 8; ++e) xh[h * 8 + e] = (float)v[e];
-            }
+            for (int h = 0; h < G / 8; ++h) xq[h] = X[((int64_t)gt * 2 + h) * 32 + col];
         }
+        const float xx = x_meta[(int64_t)rec.j * 4 + 1];
+        bool okP2;
+        const float nsum = scale_from_maxabs(cb_meta[0], &okP2) * sqrtf(__uint_as_float(cb_meta[5])) * 1.0001f +
+                           kNormMargin + sqrtf(xx) * 1.0001f;
+        const float dabs = kDdAbs * nsum * nsum;
         const bool test = rec.reach2 < 3.0e38f;
         const float r2f = rec.reach2;
         cand_t mine;
@@ -1146,7 +1169,9 @@ __global__ __launch_bounds__(kBlock) void k_rerank(
                     const int su = su_begin + rel0 + bb * kSlots * per_half;
                     const int su_c = su < su_end ? su : su_end - 1;
 #pragma unroll
-                    for (int uu = 0; uu < kU; ++uu) dd[bb][uu] = approx_dd<G>(A, su_c * kU + uu, row, xh);
+                    for (int uu = 0; uu < kU; ++uu)
+                        dd[bb][uu] = approx_dd<G>(A, cnorm, su_c * kU + uu, row,
+                                                  ((su_c * 2 + hw) * kU + uu) * 16 + qq, xq, xx);
                 }
 #pragma unroll
                 for (int bb = 0; bb < kBatch; ++bb) {
@@ -1154,7 +1179,7 @@ __global__ __launch_bounds__(kBlock) void k_rerank(
 #pragma unroll
                     for (int uu = 0; uu < kU; ++uu) {
                         const int pos = ((su * 2 + hw) * kU + uu) * 16 + qq;
-                        if (su < su_end && pos < csize && (!test || dd[bb][uu] * (1.0f - kDdSlack) <= r2f)) {
+                        if (su < su_end && pos < csize && (!test || dd[bb][uu] - dabs <= r2f)) {
                             const int cw = G == 8 ? pos : (int)perm[pos];
                             const double obj = exact_obj<G>(codebook + (int64_t)cw * G, s, t);
                             if (cand_better(obj, cw, mine.obj, mine.idx)) {
@@ -1330,7 +1355,8 @@ pv_status pv_launch_mfma_search(pv_ctx *ctx, const pv_layout *l, const float *T,
     const size_t hist_off = (bucket_off + (size_t)csize * 2 + 255) & ~(size_t)255;
     const size_t offs_off = hist_off + (size_t)kNormBins * 4;
     const size_t nmin_off = offs_off + (size_t)kNormBins * 4;
-    if ((st = pv_ensure(ctx, ctx->cb_f16, nmin_off + (size_t)nsu_alloc * 4)) != PV_OK) return st;
+    const size_t cnorm_off = (nmin_off + (size_t)nsu_alloc * 4 + 255) & ~(size_t)255;   // g = 16: norm per position
+    if ((st = pv_ensure(ctx, ctx->cb_f16, cnorm_off + (size_t)p.cpad * 4)) != PV_OK) return st;
     if ((st = pv_ensure(ctx, ctx->cb_meta, 16 * sizeof(unsigned), /*zero_new=*/true)) != PV_OK) return st;
     if ((st = pv_ensure(ctx, ctx->x_f16, (size_t)p.k_pad * 32)) != PV_OK) return st;
     // per-group bounds, then the staged targets / scale / code / id of each group
@@ -1353,6 +1379,7 @@ pv_status pv_launch_mfma_search(pv_ctx *ctx, const pv_layout *l, const float *T,
     unsigned *hist = reinterpret_cast<unsigned *>(cbase + hist_off);
     unsigned *offsets = reinterpret_cast<unsigned *>(cbase + offs_off);
     unsigned *nmin_bits = reinterpret_cast<unsigned *>(cbase + nmin_off);
+    float *cnorm = reinterpret_cast<float *>(cbase + cnorm_off);
     h8 *X = static_cast<h8 *>(ctx->x_f16.ptr);
     unsigned *cb_meta = static_cast<unsigned *>(ctx->cb_meta.ptr);
     float *x_meta = static_cast<float *>(ctx->x_meta.ptr);
@@ -1378,7 +1405,7 @@ pv_status pv_launch_mfma_search(pv_ctx *ctx, const pv_layout *l, const float *T,
                                cb_meta, cb_meta_next, stats, fb_count, nc, (unsigned *)nullptr,
                                (unsigned *)nullptr, 0, change_slots, nslots);
             hipLaunchKernelGGL(k_prep<8>, dim3(cb_blocks + x_blocks), dim3(kBlock), 0, sm, codebooks,
-                               csize, p.cpad, cb_blocks, cb_meta, A, perm, bucket, hist, nmin_bits, T,
+                               csize, p.cpad, cb_blocks, cb_meta, A, perm, bucket, hist, nmin_bits, cnorm, T,
                                scales, group_idx, (int)k, p.k_pad, gpr, N, X, x_meta, codes, csize - 1,
                                x_stage, p.ncyc, p.nsplit);
         } else {
@@ -1390,7 +1417,7 @@ pv_status pv_launch_mfma_search(pv_ctx *ctx, const pv_layout *l, const float *T,
             hipLaunchKernelGGL(k_cb_scan, dim3(kNormBins / kScanBlock), dim3(kScanBlock), 0, sm, hist, offsets);
             hipLaunchKernelGGL(k_prep<16>, dim3(cb_blocks + x_blocks), dim3(kBlock), 0, sm,
                                codebooks, csize, p.cpad, cb_blocks, cb_meta, A, perm, bucket, offsets,
-                               nmin_bits, T, scales, group_idx, (int)k, p.k_pad, gpr, N, X, x_meta,
+                               nmin_bits, cnorm, T, scales, group_idx, (int)k, p.k_pad, gpr, N, X, x_meta,
                                codes, csize - 1, x_stage, p.ncyc, p.nsplit);
         }
     }
@@ -1416,12 +1443,12 @@ pv_status pv_launch_mfma_search(pv_ctx *ctx, const pv_layout *l, const float *T,
         const dim3 rgrid((unsigned)rr_blocks);
         if (g == 8)
             hipLaunchKernelGGL(k_rerank<8>, rgrid, dim3(kBlock), 0, sm, x_stage, codebooks, (int)k,
-                               p.k_pad, partials, p.P, p.per_half, p.ncyc, p.nsplit, x_meta, cb_meta, A, X,
-                               perm, codes, rr_counts, change_slots, nc, l->nbits);
+                               p.k_pad, partials, p.P, p.per_half, p.ncyc, p.nsplit, x_meta, cb_meta, A,
+                               cnorm, X, perm, codes, rr_counts, change_slots, nc, l->nbits);
         else
             hipLaunchKernelGGL(k_rerank<16>, rgrid, dim3(kBlock), 0, sm, x_stage, codebooks, (int)k,
-                               p.k_pad, partials, p.P, p.per_half, p.ncyc, p.nsplit, x_meta, cb_meta, A, X,
-                               perm, codes, rr_counts, change_slots, nc, l->nbits);
+                               p.k_pad, partials, p.P, p.per_half, p.ncyc, p.nsplit, x_meta, cb_meta, A,
+                               cnorm, X, perm, codes, rr_counts, change_slots, nc, l->nbits);
     }
     PV_HIP(ctx, hipGetLastError());
     return PV_OK;
