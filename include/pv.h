@@ -166,9 +166,12 @@ pv_status pv_reencode_groups(pv_ctx *ctx, const pv_layout *layout, const float *
 /* Stochastic rounding of the listed groups (App. F: the K-nearest approximation for vector
  * quantisation, K = 2; App. K: temperature 0.2, i.e. power = 5), the baseline the paper
  * compares the V step with.  For each listed group n with target t and row scale s:
- *   - the two codewords with the smallest obj(c) = || s * codebook[c, :] - t ||^2 are found by
- *     a scan of all 2^B codewords (double precision on the fp32 inputs, equal objectives in
- *     index order): c_1 with d_1 = sqrt(obj(c_1)) and c_2 with d_2 >= d_1;
+ *   - the two codewords with the smallest obj(c) = || s * codebook[c, :] - t ||^2 (double
+ *     precision on the fp32 inputs, equal objectives in index order) are found: c_1 with
+ *     d_1 = sqrt(obj(c_1)) and c_2 with d_2 >= d_1 - by the matrix-core filter of
+ *     pv_reencode_groups with its certificate taken from the second nearest where that filter
+ *     applies (g = 8 or 16, B >= 5, search mode 0), else by a scan of all 2^B codewords; both
+ *     give the same pair;
  *   - p = 1 / (1 + (d_1 / d_2)^power), i.e. probabilities proportional to distance^-power
  *     (power = 1: the formula of App. F); d_1 = 0 gives p = 1;
  *   - u = (bits >> 11) * 2^-53 with bits the SplitMix64 output function applied to

@@ -361,6 +361,14 @@ extern "C" pv_status pv_reencode_groups_stochastic(pv_ctx *ctx, const pv_layout 
         return pv_fail(ctx, PV_ERR_INVALID_ARG, "power = %d outside [1, 64]", (int)power);
     if (k > 0 && !group_idx) return pv_fail(ctx, PV_ERR_INVALID_ARG, "group_idx is NULL");
     PV_HIP(ctx, hipSetDevice(ctx->device));
+    if (k > 0 && ctx->search_mode == 0 && pv_mfma_supported(l)) {
+        // the matrix-core filter with the certificate taken from the second nearest; its first
+        // kernel clears the counters
+        st = pv_ensure(ctx, ctx->stats, 8 * sizeof(int64_t));
+        if (st != PV_OK) return st;
+        return pv_launch_mfma_search(ctx, l, T, codebooks, scales, group_idx, k, codes, num_changed,
+                                     power, seed);
+    }
     if (num_changed) {
         st = pv_launch_fill_i64(ctx, num_changed, 1, 0);
         if (st != PV_OK) return st;

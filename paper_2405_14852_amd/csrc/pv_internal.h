@@ -141,10 +141,39 @@ pv_status pv_launch_beam_2x8_f16(pv_ctx *ctx, const float *T, const float *codeb
                                  unsigned long long *stat_fast, int32_t *redo_list,
                                  unsigned long long *redo_count, int gpr, int N);
 bool pv_mfma_supported(const pv_layout *l);
+// power == 0: the nearest codeword (deterministic V step); power >= 1: stochastic rounding over
+// the two nearest with that power and seed
 pv_status pv_launch_mfma_search(pv_ctx *ctx, const pv_layout *l, const float *T,
                                 const float *codebooks, const float *scales,
                                 const int32_t *group_idx, int64_t k, uint16_t *codes,
-                                int64_t *num_changed);
+                                int64_t *num_changed, int32_t power = 0, uint64_t seed = 0);
+// Stochastic rounding over the two nearest codewords (App. F, K = 2; App. K: power 5): given the
+// two smallest objectives of a group (o1 <= o2, index kNoCode = absent) the code to take.  The
+// nearest one is taken when the group's variate u - the top 53 bits of the SplitMix64 output
+// function at seed + (group + 1) * increment - lies below p = 1 / (1 + (d1 / d2)^power),
+// d = sqrt(objective).  Every step is a correctly rounded double operation, so every kernel
+// that calls this (and the CPU reference, which writes the same chain) decides alike.
+#ifdef __HIPCC__
+constexpr int kPvNoCode = 0x7fffffff;
+__device__ __forceinline__ int pv_round_pick(double o1, int i1, double o2, int i2, int power,
+                                             unsigned long long seed, unsigned long long group)
+{
+    double p = 1.0;
+    if (i2 != kPvNoCode && o1 > 0.0) {
+        const double r = __dsqrt_rn(__ddiv_rn(o1, o2));
+        double rn = r;
+        for (int e = 1; e < power; ++e) rn = __dmul_rn(rn, r);
+        p = __ddiv_rn(1.0, __dadd_rn(1.0, rn));
+    }
+    unsigned long long z = seed + (group + 1ull) * 0x9E3779B97F4A7C15ull;
+    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+    z = z ^ (z >> 31);
+    const double u = (double)(z >> 11) * 0x1.0p-53;
+    return (i2 == kPvNoCode || u < p) ? i1 : i2;
+}
+#endif
+
 pv_status pv_launch_round_two_nearest(pv_ctx *ctx, const pv_layout *l, const float *T,
                                       const float *codebook, const float *scales,
                                       const int32_t *group_idx, int64_t k, int32_t power,

@@ -1244,6 +1244,374 @@ __global__ __launch_bounds__(kBlock, PV_RR_OCC) void k_rerank(
     }
 }
 
+// ------------------------------------------------ stochastic rounding over the two nearest
+//
+// The same filter serves App. F's rounding over the TWO nearest codewords: the certificate is
+// the one of k_rerank with the best objective replaced by the second best found so far, E2.
+// A codeword that was not evaluated can belong to the two nearest only if its objective
+// reaches E2, hence only if its key is at least the cut taken from E2; every best key at or
+// above that cut has its 16 U positions looked at (cheap distance first, exact objective for
+// those within reach of E2), and a partition whose runner-up key reaches the cut is scanned
+// completely by the block.  The two nearest (objective, then index) go to pv_round_pick.
+struct two_t {
+    double o1, o2;
+    int i1, i2;
+};
+
+__device__ __forceinline__ void two_clear(two_t &b)
+{
+    b.o1 = b.o2 = __builtin_huge_val();
+    b.i1 = b.i2 = kPvNoCode;
+}
+
+__device__ __forceinline__ void two_insert(two_t &b, double o, int c)
+{
+    if (cand_better(o, c, b.o1, b.i1)) {
+        b.o2 = b.o1; b.i2 = b.i1;
+        b.o1 = o; b.i1 = c;
+    } else if (cand_better(o, c, b.o2, b.i2)) {
+        b.o2 = o; b.i2 = c;
+    }
+}
+
+// the two smallest of the union of two such pairs (a codeword sits in at most one of them)
+__device__ __forceinline__ two_t two_merge(two_t a, const two_t &b)
+{
+    if (b.i1 != kPvNoCode) two_insert(a, b.o1, b.i1);
+    if (b.i2 != kPvNoCode) two_insert(a, b.o2, b.i2);
+    return a;
+}
+
+template <int WIDTH>
+__device__ __forceinline__ two_t two_reduce(two_t b)
+{
+#pragma unroll
+    for (int m = WIDTH / 2; m > 0; m >>= 1) {
+        two_t o;
+        o.o1 = __shfl_xor(b.o1, m, WIDTH);
+        o.o2 = __shfl_xor(b.o2, m, WIDTH);
+        o.i1 = __shfl_xor(b.i1, m, WIDTH);
+        o.i2 = __shfl_xor(b.i2, m, WIDTH);
+        b = two_merge(b, o);
+    }
+    return b;
+}
+
+struct open2_t {
+    two_t best;
+    float reach2;
+    unsigned long long mask;
+    int n;
+    int j;
+};
+
+template <int G>
+__global__ __launch_bounds__(kBlock) void k_round_top2(
+    const float *__restrict__ x_stage, const float *__restrict__ codebook, int k, int k_pad,
+    const int2 *__restrict__ partials, int P, int per_half, int ncyc, int nsplit,
+    const float *__restrict__ x_meta, const unsigned *__restrict__ cb_meta, const h8 *__restrict__ A,
+    const float *__restrict__ cnorm, const h8 *__restrict__ X, const uint16_t *__restrict__ perm,
+    uint16_t *__restrict__ codes, unsigned *__restrict__ block_counts,
+    unsigned long long *__restrict__ change_slots, unsigned long long *__restrict__ num_changed,
+    int nbits, int power, unsigned long long seed)
+{
+    constexpr int kTeam = PV_TEAM;
+    constexpr int kTeams = kBlock / kTeam;
+    constexpr int kPer = 16 / kTeam;
+    constexpr int kMine = kU * kPer;               // positions of a key per lane
+    __shared__ unsigned s_cnt[4];   // groups decided by the teams, codes changed, candidates evaluated, groups scanned
+    __shared__ open2_t s_open[kTeams];
+    __shared__ unsigned s_nopen;
+    if (threadIdx.x < 4) s_cnt[threadIdx.x] = 0;
+    if (threadIdx.x == 0) s_nopen = 0;
+    __syncthreads();
+    const int csize = 1 << nbits;
+    const int gid = blockIdx.x * kBlock + threadIdx.x;
+    const int j = gid / kTeam, q = gid % kTeam;
+    const bool inlist = j < k;
+    const pv_f4 *stage = reinterpret_cast<const pv_f4 *>(x_stage + (int64_t)(inlist ? j : 0) * (G + 4));
+    const pv_f4 tail = stage[G / 4];
+    pv_f4 meta = reinterpret_cast<const pv_f4 *>(x_meta)[inlist ? j : 0];
+    const int n = inlist ? __float_as_int(tail.z) : -1;
+    bool live = n >= 0;                      // whole teams agree on every branch below
+    if (!live) meta.w = -1.0f;
+    bool okP;
+    const float Pscale = scale_from_maxabs(cb_meta[0], &okP);
+    const float cmaxn = Pscale * sqrtf(__uint_as_float(cb_meta[5])) * 1.0001f + kNormMargin;
+    auto decide = [&](const two_t &b, int group, int prev) {
+        int pick = prev;                     // nothing could be evaluated (non-finite input): keep
+        if (b.i1 != kPvNoCode) pick = pv_round_pick(b.o1, b.i1, b.o2, b.i2, power, seed, (unsigned long long)group);
+        if (pick != prev) {
+            codes[group] = (uint16_t)pick;
+            atomicAdd(&s_cnt[1], 1u);
+        }
+    };
+    if (live && meta.w < 0.0f) {             // the filter was skipped for this group: every partition
+        if (q == 0) {
+            open2_t r;
+            two_clear(r.best);
+            r.reach2 = __builtin_huge_valf();
+            r.mask = P >= 64 ? ~0ull : ((1ull << P) - 1ull);
+            r.n = n;
+            r.j = j;
+            s_open[atomicAdd(&s_nopen, 1u)] = r;
+        }
+        live = false;
+    }
+    if (live) {
+        const float s = tail.x;
+        float t[G];
+#pragma unroll
+        for (int v4 = 0; v4 < G / 4; ++v4) {
+            pv_f4 v = stage[v4];
+            t[v4 * 4 + 0] = v.x;
+            t[v4 * 4 + 1] = v.y;
+            t[v4 * 4 + 2] = v.z;
+            t[v4 * 4 + 3] = v.w;
+        }
+        const int prev = __float_as_int(tail.y);
+        constexpr int kMaxRec = 64 / kTeam;  // P <= 64
+        int2 rec[kMaxRec];
+#pragma unroll
+        for (int u = 0; u < kMaxRec; ++u) {
+            int p = q + kTeam * u;
+            rec[u] = p < P ? partials[rec_at(p, j, P, k_pad)] : make_int2(kNoKey, kNoKey);
+        }
+        // the two largest keys over all partitions, runner-up keys included: entry = key, partition,
+        // whether it is the partition's best (low bit) - the largest key is always a best one
+        auto entry = [](int key, int p, int is_best) {
+            return ((long long)key << 32) | (long long)(unsigned)(((63 - p) << 1) | is_best);
+        };
+        long long bk = (long long)0x8000000000000000ull;
+#pragma unroll
+        for (int u = 0; u < kMaxRec; ++u) {
+            const long long v = entry(rec[u].x, q + kTeam * u, 1);
+            bk = v > bk ? v : bk;
+        }
+#pragma unroll
+        for (int m = kTeam / 2; m > 0; m >>= 1) {
+            long long o = __shfl_xor(bk, m, kTeam);
+            bk = o > bk ? o : bk;
+        }
+        long long bk2 = (long long)0x8000000000000000ull;
+#pragma unroll
+        for (int u = 0; u < kMaxRec; ++u) {
+            const long long vx = entry(rec[u].x, q + kTeam * u, 1), vy = entry(rec[u].y, q + kTeam * u, 0);
+            if (vx != bk && vx > bk2) bk2 = vx;
+            if (vy > bk2) bk2 = vy;
+        }
+#pragma unroll
+        for (int m = kTeam / 2; m > 0; m >>= 1) {
+            long long o = __shfl_xor(bk2, m, kTeam);
+            bk2 = o > bk2 ? o : bk2;
+        }
+        const int best_key = (int)(bk >> 32);
+        const int best_p = 63 - (int)((bk & 0xFFFFFFFFll) >> 1);
+        const int next_key = (int)(bk2 >> 32);
+        const int next_p = 63 - (int)((bk2 & 0xFFFFFFFFll) >> 1);
+        const bool next_is_best = (bk2 & 1ll) != 0;      // the best key of its partition (else its runner-up)
+        h8 xq[G / 8];
+        {
+            const int gt = j >> 5, col = j & 31;
+#pragma unroll
+            for (int h = 0; h < G / 8; ++h) xq[h] = X[((int64_t)gt * 2 + h) * 32 + col];
+        }
+        const float nsum = cmaxn + sqrtf(meta.y) * 1.0001f;
+        const float dabs = kDdAbs * nsum * nsum;
+        const float p_over_s = Pscale / fabsf(s);
+        const float dC = sqrtf(__uint_as_float(cb_meta[2])) * 1.0001f + 1e-30f;
+        auto reach2_of = [&](double e) {
+            const float rr = sqrtf(__double2float_ru(e)) * p_over_s * 1.000002f + dC + meta.w;
+            const float r2 = rr * rr * 1.000002f;
+            return r2 == r2 ? r2 : __builtin_huge_valf();
+        };
+        two_t mine;
+        two_clear(mine);
+        unsigned exact_evals = 0;
+        // the positions behind a key: cheap distance first, exact objective for those within reach
+        auto eval_key = [&](int key, int p, float reach2) {
+            const int su = key & (int)kKeyMask;
+            const int hw = (p / per_half) & 1;
+#pragma unroll
+            for (int uu = 0; uu < kU; ++uu)
+#pragma unroll
+                for (int e = 0; e < kPer; ++e) {
+                    const int qq = q + kTeam * e;
+                    const int row = 8 * (qq >> 2) + 4 * hw + (qq & 3);
+                    const int pos = ((su * 2 + hw) * kU + uu) * 16 + qq;
+                    const float dd = approx_dd<G>(A, cnorm, su * kU + uu, row, pos, xq, meta.y);
+                    if (pos < csize && dd - dabs <= reach2) {
+                        const int cw = G == 8 ? pos : (int)perm[pos];
+                        two_insert(mine, exact_obj<G>(codebook + (int64_t)cw * G, s, t), cw);
+                        ++exact_evals;
+                    }
+                }
+        };
+        if (best_key != kNoKey) eval_key(best_key, best_p, __builtin_huge_valf());
+        // The second nearest usually sits behind the second largest key, not among the neighbours
+        // of the nearest: that key is evaluated before the cut is taken, else the cut would come
+        // from a poor second objective and leave nearly every partition open.
+        if (next_key != kNoKey && next_p < P) {
+            const two_t sofar = two_reduce<kTeam>(mine);
+            eval_key(next_key, next_p, sofar.i2 == kPvNoCode ? __builtin_huge_valf() : reach2_of(sofar.o2));
+        }
+        const two_t first = two_reduce<kTeam>(mine);
+        // every codeword that was not evaluated and could still reach E2 sits behind a key at or above kcut
+        const float reach2f = first.i2 == kPvNoCode ? __builtin_huge_valf() : reach2_of(first.o2);
+        const float base = meta.x + meta.y;
+        const float kcut = (base * 0.999999f - reach2f * 1.000001f) - meta.z - 1.0e-6f * (base + reach2f);
+        const bool no_bound = !(kcut > -3.0e38f);
+        unsigned pending = 0;
+        unsigned long long open = 0;
+#pragma unroll
+        for (int u = 0; u < kMaxRec; ++u) {
+            int p = q + kTeam * u;
+            if (p < P) {
+                if (rec[u].y != kNoKey && (no_bound || key_upper(rec[u].y) >= kcut)) open |= 1ull << p;
+                if (p != best_p && !(next_is_best && p == next_p) && rec[u].x != kNoKey &&
+                    (no_bound || key_upper(rec[u].x) >= kcut))
+                    pending |= 1u << u;
+            }
+        }
+#pragma unroll
+        for (int m = kTeam / 2; m > 0; m >>= 1) open |= __shfl_xor(open, m, kTeam);
+        const int team_shift = (threadIdx.x & 63) & ~(kTeam - 1);
+        for (;;) {
+            const unsigned long long pb = __ballot(pending != 0);
+            const unsigned team = (unsigned)((pb >> team_shift) & ((1ull << kTeam) - 1ull));
+            if (!team) break;
+            const int src = __ffs(team) - 1;
+            const unsigned their = __shfl(pending, src, kTeam);
+            const int u = __ffs(their) - 1;
+            int key = 0;
+#pragma unroll
+            for (int uu = 0; uu < kMaxRec; ++uu)
+                if (uu == u) key = rec[uu].x;
+            key = __shfl(key, src, kTeam);
+            eval_key(key, src + kTeam * u, reach2f);
+            if (q == src) pending &= ~(1u << u);
+        }
+#pragma unroll
+        for (int m = kTeam / 2; m > 0; m >>= 1) exact_evals += __shfl_xor(exact_evals, m, kTeam);
+        const two_t win = two_reduce<kTeam>(mine);
+        if (q == 0) {
+            if (open) {
+                open2_t r;
+                r.best = win;
+                r.reach2 = (no_bound || win.i2 == kPvNoCode) ? __builtin_huge_valf() : reach2_of(win.o2);
+                r.mask = open;
+                r.n = n;
+                r.j = j;
+                s_open[atomicAdd(&s_nopen, 1u)] = r;
+            } else {
+                decide(win, n, prev);
+                atomicAdd(&s_cnt[0], 1u);
+            }
+            atomicAdd(&s_cnt[2], exact_evals);
+        }
+    }
+    __syncthreads();
+
+    // ---- groups left open: every position of their open partitions, by the whole block
+    const unsigned nopen = s_nopen;
+    __shared__ two_t s_two[kBlock / 64];
+    for (unsigned item = 0; item < nopen; ++item) {
+        const open2_t rec = s_open[item];
+        const pv_f4 *stage2 = reinterpret_cast<const pv_f4 *>(x_stage + (int64_t)rec.j * (G + 4));
+        const pv_f4 tail2 = stage2[G / 4];
+        const float s = tail2.x;
+        float t[G];
+#pragma unroll
+        for (int v4 = 0; v4 < G / 4; ++v4) {
+            pv_f4 v = stage2[v4];
+            t[v4 * 4 + 0] = v.x;
+            t[v4 * 4 + 1] = v.y;
+            t[v4 * 4 + 2] = v.z;
+            t[v4 * 4 + 3] = v.w;
+        }
+        const int prev = __float_as_int(tail2.y);
+        const int lane = threadIdx.x & 63;
+        const int qq = threadIdx.x & 15, slot = threadIdx.x >> 4;
+        constexpr int kSlots = kBlock / 16;
+        h8 xq[G / 8];
+        {
+            const int gt = rec.j >> 5, col = rec.j & 31;
+#pragma unroll
+            for (int h = 0; h < G / 8; ++h) xq[h] = X[((int64_t)gt * 2 + h) * 32 + col];
+        }
+        const float xx = x_meta[(int64_t)rec.j * 4 + 1];
+        const float nsum = cmaxn + sqrtf(xx) * 1.0001f;
+        const float dabs = kDdAbs * nsum * nsum;
+        const bool test = rec.reach2 < 3.0e38f;
+        const float r2f = rec.reach2;
+        two_t mine;
+        two_clear(mine);
+        for (unsigned long long left = rec.mask; left; left &= left - 1) {   // uniform over the block
+            const int p = __ffsll((long long)left) - 1;
+            const int hw = (p / per_half) & 1;
+            const int split = p / (2 * per_half);
+            const int su_begin = split_begin(split, ncyc, nsplit) * kResidues;
+            const int su_end = su_begin + split_count(split, ncyc, nsplit) * kResidues;
+            const int row = 8 * (qq >> 2) + 4 * hw + (qq & 3);
+            constexpr int kBatch = 2;
+            for (int rel0 = (p % per_half) + slot * per_half; su_begin + rel0 < su_end;
+                 rel0 += kSlots * per_half * kBatch) {
+                float dd[kBatch][kU];
+#pragma unroll
+                for (int bb = 0; bb < kBatch; ++bb) {
+                    const int su = su_begin + rel0 + bb * kSlots * per_half;
+                    const int su_c = su < su_end ? su : su_end - 1;
+#pragma unroll
+                    for (int uu = 0; uu < kU; ++uu)
+                        dd[bb][uu] = approx_dd<G>(A, cnorm, su_c * kU + uu, row,
+                                                  ((su_c * 2 + hw) * kU + uu) * 16 + qq, xq, xx);
+                }
+#pragma unroll
+                for (int bb = 0; bb < kBatch; ++bb) {
+                    const int su = su_begin + rel0 + bb * kSlots * per_half;
+#pragma unroll
+                    for (int uu = 0; uu < kU; ++uu) {
+                        const int pos = ((su * 2 + hw) * kU + uu) * 16 + qq;
+                        if (su < su_end && pos < csize && (!test || dd[bb][uu] - dabs <= r2f)) {
+                            const int cw = G == 8 ? pos : (int)perm[pos];
+                            two_insert(mine, exact_obj<G>(codebook + (int64_t)cw * G, s, t), cw);
+                        }
+                    }
+                }
+            }
+        }
+        mine = two_reduce<64>(mine);
+        __syncthreads();
+        if (lane == 0) s_two[threadIdx.x >> 6] = mine;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            // a codeword of an open partition may already sit in the team's pair (it was behind an
+            // evaluated key): the same index is not taken twice
+            two_t win = rec.best;
+            for (int w = 0; w < kBlock / 64; ++w) {
+                const two_t o = s_two[w];
+                if (o.i1 != kPvNoCode && o.i1 != win.i1 && o.i1 != win.i2) two_insert(win, o.o1, o.i1);
+                if (o.i2 != kPvNoCode && o.i2 != win.i1 && o.i2 != win.i2) two_insert(win, o.o2, o.i2);
+            }
+            decide(win, rec.n, prev);
+            atomicAdd(&s_cnt[3], 1u);
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x < 4) block_counts[4 * blockIdx.x + threadIdx.x] = s_cnt[threadIdx.x];
+    // *num_changed through the slots 64 blocks share (see k_rerank)
+    if (threadIdx.x == 0 && num_changed) {
+        const unsigned first = (blockIdx.x >> 6) << 6;
+        const unsigned members = gridDim.x - first < 64u ? gridDim.x - first : 64u;
+        const unsigned long long old =
+            atomicAdd(&change_slots[blockIdx.x >> 6], (1ull << 40) | (unsigned long long)s_cnt[1]);
+        if ((unsigned)(old >> 40) == members - 1u) {
+            const unsigned long long total = (old & ((1ull << 40) - 1ull)) + s_cnt[1];
+            if (total) atomicAdd(num_changed, total);
+        }
+    }
+}
+
 __global__ void k_fill_u32(unsigned *p, int n, unsigned v)
 {
     int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -1339,7 +1707,7 @@ bool pv_mfma_supported(const pv_layout *l)
 pv_status pv_launch_mfma_search(pv_ctx *ctx, const pv_layout *l, const float *T,
                                 const float *codebooks, const float *scales,
                                 const int32_t *group_idx, int64_t k, uint16_t *codes,
-                                int64_t *num_changed)
+                                int64_t *num_changed, int32_t power, uint64_t seed)
 {
     const plan_t p = make_plan(l, k);
     const int g = l->group_size;
@@ -1441,7 +1809,16 @@ pv_status pv_launch_mfma_search(pv_ctx *ctx, const pv_layout *l, const float *T,
     {
         pv_timed t(ctx, PV_K_RERANK);
         const dim3 rgrid((unsigned)rr_blocks);
-        if (g == 8)
+        if (power > 0) {
+#define PV_ROUND2(G_)                                                                              \
+    hipLaunchKernelGGL(k_round_top2<G_>, rgrid, dim3(kBlock), 0, sm, x_stage, codebooks, (int)k,    \
+                       p.k_pad, partials, p.P, p.per_half, p.ncyc, p.nsplit, x_meta, cb_meta, A,    \
+                       cnorm, X, perm, codes, rr_counts, change_slots, nc, l->nbits, (int)power,    \
+                       (unsigned long long)seed)
+            if (g == 8) PV_ROUND2(8);
+            else PV_ROUND2(16);
+#undef PV_ROUND2
+        } else if (g == 8)
             hipLaunchKernelGGL(k_rerank<8>, rgrid, dim3(kBlock), 0, sm, x_stage, codebooks, (int)k,
                                p.k_pad, partials, p.P, p.per_half, p.ncyc, p.nsplit, x_meta, cb_meta, A,
                                cnorm, X, perm, codes, rr_counts, change_slots, nc, l->nbits);

@@ -75,15 +75,6 @@ __device__ __forceinline__ two_t wave_two(two_t b)
     return b;
 }
 
-__device__ __forceinline__ double uniform_of(unsigned long long seed, unsigned long long counter)
-{
-    unsigned long long z = seed + (counter + 1ull) * 0x9E3779B97F4A7C15ull;
-    z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
-    z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
-    z = z ^ (z >> 31);
-    return (double)(z >> 11) * 0x1.0p-53;
-}
-
 // G > 0: group size known at compile time; G == 0: any group size up to kMaxG.
 template <int G>
 __global__ __launch_bounds__(kBlock) void k_round_two_nearest(
@@ -200,17 +191,8 @@ __global__ __launch_bounds__(kBlock) void k_round_two_nearest(
             for (int w = 1; w < kBlock / 64; ++w) b = merge(b, s_two[q][w]);
             const int prev = (int)(codes[n] & (csize - 1));
             int pick = prev;                           // every objective NaN: keep
-            if (b.i1 != kNone) {
-                double p = 1.0;
-                if (b.i2 != kNone && b.o1 > 0.0) {
-                    const double r = __dsqrt_rn(__ddiv_rn(b.o1, b.o2));
-                    double rn = r;
-                    for (int e = 1; e < power; ++e) rn = __dmul_rn(rn, r);
-                    p = __ddiv_rn(1.0, __dadd_rn(1.0, rn));
-                }
-                const double u = uniform_of(seed, (unsigned long long)n);
-                pick = (b.i2 == kNone || u < p) ? b.i1 : b.i2;
-            }
+            if (b.i1 != kNone)
+                pick = pv_round_pick(b.o1, b.i1, b.o2, b.i2, power, seed, (unsigned long long)n);
             if (pick != prev) {
                 codes[n] = (uint16_t)pick;
                 if (num_changed) atomicAdd(num_changed, 1ull);

@@ -30,13 +30,15 @@ def stochastic_on_gpu(ctx, wl, T_np, idx_np, power, seed, codes_np=None):
                                        ((32, 96), 4, 6), ((24, 120), 12, 7), ((16, 64), 8, 1),
                                        ((128, 1024), 8, 16)])
 @pytest.mark.parametrize("power", [1, 5])
-def test_stochastic_rounding_matches_oracle(shape, g, B, power):
+@pytest.mark.parametrize("mode", [0, 1])
+def test_stochastic_rounding_matches_oracle(shape, g, B, power, mode):
     wl = workloads.make(shape[0], shape[1], g, 1, B, sigma_g=5e-3, tau=0.3, seed=300 + B)
     T = oracle.encode_targets(wl.W, wl.G, wl.alpha)
     N = wl.layout.num_groups
     k = workloads.num_selected(N, 0.05 if B == 16 else 0.3)
     idx = oracle.select_topk_groups(T, wl.W, g, k)
     ctx = PVContext(0)
+    ctx.pv_set_search_mode(mode)       # 0: matrix-core filter where the shape allows, 1: exact scan
     seed = 0x1234_5678_9ABC_DEF0 + power
     got, nch = stochastic_on_gpu(ctx, wl, T, idx, power, seed)
     want, info = oracle.reencode_stochastic(T, wl.codebooks, wl.scales, idx, wl.codes, power=power,
@@ -190,3 +192,40 @@ def test_buffer_flips_a_code_that_the_plain_v_step_never_moves():
         seen.append(int(host_u16(codes).reshape(-1)[0]))
     assert seen == [0, 0, 1, 1]
     ctx.close()
+
+
+@pytest.mark.parametrize("g,B", [(8, 8), (8, 12), (16, 9)])
+def test_stochastic_rounding_on_inputs_that_strain_the_filter(g, B):
+    """Duplicate and nearly equal codewords (equal objectives must fall in index order, the second
+    nearest is then a twin of the nearest), a zero and a negative scale, rows whose targets lie far
+    outside the codebook, a target that is a codeword: the filtered route has to hand the same two
+    nearest to the rounding rule as the scan does."""
+    out_f, in_f = 48, 64 * g
+    wl = workloads.make(out_f, in_f, g, 1, B, sigma_g=5e-3, seed=700 + B)
+    rng = np.random.default_rng(B)
+    cb = wl.codebooks
+    csize = 1 << B
+    twins = rng.choice(csize, size=csize // 4, replace=False)
+    cb[0, twins] = cb[0, (twins + 1) % csize]                       # exact duplicates
+    near = rng.choice(csize, size=csize // 8, replace=False)
+    cb[0, near] = cb[0, (near + 3) % csize] * np.float32(1 + 1e-7)   # nearly equal
+    wl.scales[3] = 0.0
+    wl.scales[5] = -0.75
+    wl.scales[7] = 1e-20
+    T = oracle.encode_targets(wl.W, wl.G, wl.alpha)
+    T[9] *= 1e6                                                      # far outside the codebook
+    T[11] *= 1e-12
+    T[13, :g] = wl.scales[13] * cb[0, 17]                            # on a codeword
+    N = wl.layout.num_groups
+    idx = np.arange(N, dtype=np.int32)
+    for mode in (0, 1):
+        ctx = PVContext(0)
+        ctx.pv_set_search_mode(mode)
+        got, nch = stochastic_on_gpu(ctx, wl, T, idx, 5, 4242)
+        want, info = oracle.reencode_stochastic(T, cb, wl.scales, idx, wl.codes, power=5, seed=4242)
+        differ = np.nonzero(got.reshape(-1) != want.reshape(-1))[0]
+        assert len(differ) == 0 or info["near_tie"][differ].all(), (mode, len(differ), differ[:8])
+        # exact duplicates are no near-ties of the rule's making: there the result must be identical
+        exact_twin = info["objective_two"][:, 0] == info["objective_two"][:, 1]
+        assert (got.reshape(-1)[exact_twin] == want.reshape(-1)[exact_twin]).all()
+        ctx.close()
