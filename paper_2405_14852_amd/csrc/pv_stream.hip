@@ -105,7 +105,10 @@ __global__ __launch_bounds__(kBlock) void k_encode_targets_adam(const float *W, 
 // all their codewords, in flight together (two round trips per thread whatever the count:
 // with one vector a thread the kernel is bound by those trips, not by the 4 bytes a weight
 // it writes).
-constexpr int kDeqAhead = 4;
+#ifndef PV_DEQ_AHEAD
+#define PV_DEQ_AHEAD 2   // measured: 1 leaves two-codebook layouts bound by round trips, 4 and 8 lose to register pressure
+#endif
+constexpr int kDeqAhead = PV_DEQ_AHEAD;
 template <int VEC>
 __global__ __launch_bounds__(kBlock) void k_dequantize(const uint16_t *__restrict__ codes,
                                                        const float *__restrict__ codebooks,
