@@ -419,10 +419,12 @@ extern "C" pv_status pv_codebook_grads(pv_ctx *ctx, const pv_layout *l, const fl
     if (pv_num_groups(l) == 0) {   // empty matrix: all sums are empty
         const size_t cb_bytes = sizeof(float) * (size_t)l->num_codebooks *
                                 ((size_t)1 << l->nbits) * (size_t)l->group_size;
-        PV_HIP(ctx, hipMemsetAsync(grad_codebooks, 0, cb_bytes, ctx->stream));
-        if (grad_scales && l->out_features > 0)
-            PV_HIP(ctx, hipMemsetAsync(grad_scales, 0, sizeof(float) * (size_t)l->out_features,
-                                       ctx->stream));
+        pv_status fs = pv_launch_fill_f32(ctx, grad_codebooks, (int64_t)(cb_bytes / sizeof(float)), 0.0f);
+        if (fs != PV_OK) return fs;
+        if (grad_scales && l->out_features > 0) {
+            fs = pv_launch_fill_f32(ctx, grad_scales, l->out_features, 0.0f);
+            if (fs != PV_OK) return fs;
+        }
         return PV_OK;
     }
     return pv_launch_codebook_grads(ctx, l, G, codes, codebooks, scales, grad_codebooks,

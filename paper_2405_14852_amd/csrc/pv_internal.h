@@ -178,6 +178,7 @@ pv_status pv_launch_round_two_nearest(pv_ctx *ctx, const pv_layout *l, const flo
                                       const float *codebook, const float *scales,
                                       const int32_t *group_idx, int64_t k, int32_t power,
                                       uint64_t seed, uint16_t *codes, int64_t *num_changed);
+pv_status pv_launch_fill_f32(pv_ctx *ctx, float *p, int64_t n, float value);
 pv_status pv_launch_fill_i64(pv_ctx *ctx, int64_t *p, int64_t n, int64_t value,
                              int64_t *also = nullptr);   // *also = value too, in the same launch
 pv_status pv_launch_probe_copy(pv_ctx *ctx, void *dst, const void *src, int64_t bytes);

@@ -346,25 +346,50 @@ __global__ __launch_bounds__(kBlock) void k_pg_scales(const float *__restrict__ 
         const int64_t nv = in_features / 4;
         const pv_f4 *G4 = reinterpret_cast<const pv_f4 *>(G + o * in_features);
         const pv_f4 *C4 = reinterpret_cast<const pv_f4 *>(codebooks);
-        for (int64_t e = threadIdx.x; e < nv; e += kBlock) {
-            const int64_t n = o * gpr + e / vpg;
-            const int q4 = (int)(e % vpg);
-            const pv_f4 gv = __builtin_nontemporal_load(&G4[e]);
-            pv_f4 q = C4[((int64_t)(codes[n * M] & mask) * g) / 4 + q4];
-            for (int m = 1; m < M; ++m) {
-                const pv_f4 c = C4[((m * csize + (codes[n * M + m] & mask)) * g) / 4 + q4];
-                q.x = q.x + c.x;
-                q.y = q.y + c.y;
-                q.z = q.z + c.z;
-                q.w = q.w + c.w;
+        // kAhead vectors of a thread at a time: their codes, then their codewords, are in flight
+        // together (a row is only a few vectors per thread: one at a time the kernel is a chain
+        // of round trips); the terms are still added in index order
+        constexpr int kAhead = 4;
+        for (int64_t e0 = threadIdx.x; e0 < nv; e0 += (int64_t)kBlock * kAhead) {
+            pv_f4 gv[kAhead], q[kAhead];
+            unsigned code[kAhead];
+            int q4[kAhead];
+            int64_t n[kAhead];
+#pragma unroll
+            for (int u = 0; u < kAhead; ++u) {
+                const int64_t e = e0 + (int64_t)u * kBlock;
+                const int64_t ec = e < nv ? e : nv - 1;
+                n[u] = o * gpr + ec / vpg;
+                q4[u] = (int)(ec % vpg);
+                gv[u] = __builtin_nontemporal_load(&G4[ec]);
+                code[u] = codes[n[u] * M] & mask;
             }
-            // per thread the terms are added in index order
-            acc = acc + (double)gv.x * (double)q.x;
-            acc = acc + (double)gv.y * (double)q.y;
-            acc = acc + (double)gv.z * (double)q.z;
-            acc = acc + (double)gv.w * (double)q.w;
-            mb = max(max(mb, __float_as_uint(fabsf(gv.x))), __float_as_uint(fabsf(gv.y)));
-            mb = max(max(mb, __float_as_uint(fabsf(gv.z))), __float_as_uint(fabsf(gv.w)));
+#pragma unroll
+            for (int u = 0; u < kAhead; ++u) q[u] = C4[((int64_t)code[u] * g) / 4 + q4[u]];
+            for (int m = 1; m < M; ++m) {
+                pv_f4 c[kAhead];
+#pragma unroll
+                for (int u = 0; u < kAhead; ++u)
+                    c[u] = C4[((m * csize + (codes[n[u] * M + m] & mask)) * g) / 4 + q4[u]];
+#pragma unroll
+                for (int u = 0; u < kAhead; ++u) {
+                    q[u].x = q[u].x + c[u].x;
+                    q[u].y = q[u].y + c[u].y;
+                    q[u].z = q[u].z + c[u].z;
+                    q[u].w = q[u].w + c[u].w;
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < kAhead; ++u) {
+                if (e0 + (int64_t)u * kBlock < nv) {
+                    acc = acc + (double)gv[u].x * (double)q[u].x;
+                    acc = acc + (double)gv[u].y * (double)q[u].y;
+                    acc = acc + (double)gv[u].z * (double)q[u].z;
+                    acc = acc + (double)gv[u].w * (double)q[u].w;
+                    mb = max(max(mb, __float_as_uint(fabsf(gv[u].x))), __float_as_uint(fabsf(gv[u].y)));
+                    mb = max(max(mb, __float_as_uint(fabsf(gv[u].z))), __float_as_uint(fabsf(gv[u].w)));
+                }
+            }
         }
     } else {
         for (int64_t e = threadIdx.x; e < in_features; e += kBlock) {

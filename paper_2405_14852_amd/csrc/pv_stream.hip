@@ -238,6 +238,12 @@ __global__ void k_fill_i64(int64_t *p, int64_t n, int64_t v, int64_t *q)
     if (q && i == 0) *q = v;
 }
 
+// p[0 .. n) = v (a kernel rather than a memset node: callers may capture the stream in a graph)
+__global__ __launch_bounds__(kBlock) void k_fill_f32(float *p, int64_t n, float v)
+{
+    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += (int64_t)gridDim.x * kBlock) p[i] = v;
+}
+
 }  // namespace
 
 pv_status pv_launch_encode_targets(pv_ctx *ctx, const float *W, const float *G, float alpha,
@@ -345,6 +351,16 @@ pv_status pv_launch_probe_copy(pv_ctx *ctx, void *dst, const void *src, int64_t 
     const int64_t blocks = (n + kBlock - 1) / kBlock;
     hipLaunchKernelGGL(k_probe_copy, dim3((unsigned)blocks), dim3(kBlock), 0, ctx->stream,
                        static_cast<const pv_f4 *>(src), static_cast<pv_f4 *>(dst), n);
+    PV_HIP(ctx, hipGetLastError());
+    return PV_OK;
+}
+
+pv_status pv_launch_fill_f32(pv_ctx *ctx, float *p, int64_t n, float value)
+{
+    if (n <= 0) return PV_OK;
+    int64_t blocks = (n + kBlock - 1) / kBlock;
+    if (blocks > 1024) blocks = 1024;
+    hipLaunchKernelGGL(k_fill_f32, dim3((unsigned)blocks), dim3(kBlock), 0, ctx->stream, p, n, value);
     PV_HIP(ctx, hipGetLastError());
     return PV_OK;
 }

@@ -148,3 +148,18 @@ def test_codebook_grads_small_codebook_route_is_close_to_the_exact_sum_and_flags
     wl.G *= 0
     gc, gs, _, _ = run_case(wl)
     assert (gc == 0).all() and (gs == 0).all()
+
+
+def test_codebook_grads_of_an_empty_matrix_are_zero():
+    from paper_2405_14852_amd import Layout, PVContext
+    ctx = PVContext(0)
+    lay = Layout(0, 64, 8, 1, 6)
+    gc = torch.full((1, 64, 8), 3.0, dtype=torch.float32, device=DEV)
+    G = torch.zeros((1, 64), dtype=torch.float32, device=DEV)          # never read
+    codes = torch.zeros((1, 8, 1), dtype=torch.int16, device=DEV).view(torch.uint16)
+    cb = torch.zeros((1, 64, 8), dtype=torch.float32, device=DEV)
+    sc = torch.zeros((1,), dtype=torch.float32, device=DEV)
+    ctx.pv_codebook_grads(lay, G, codes, cb, sc, gc, None)
+    torch.cuda.synchronize()
+    assert (gc == 0).all()
+    ctx.close()
