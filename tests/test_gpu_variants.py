@@ -229,3 +229,33 @@ def test_stochastic_rounding_on_inputs_that_strain_the_filter(g, B):
         exact_twin = info["objective_two"][:, 0] == info["objective_two"][:, 1]
         assert (got.reshape(-1)[exact_twin] == want.reshape(-1)[exact_twin]).all()
         ctx.close()
+
+
+@pytest.mark.parametrize("g,M,B,beam,stochastic", [(8, 1, 12, 1, False), (16, 1, 11, 1, False), (8, 2, 8, 8, False),
+                                                   (8, 1, 12, 1, True), (16, 1, 10, 1, True)])
+def test_repeated_calls_from_the_same_state_give_the_same_codes(g, M, B, beam, stochastic):
+    """Thirty calls from the same codes, on one context (scratch, alternating statistics slots
+    and counters are reused): every result is the first one, bit for bit, and num_changed too."""
+    wl = workloads.make(192, 64 * g, g, M, B, beam_width=beam, sigma_g=5e-3, tau=0.5, seed=900 + B + g)
+    lay = lay_of(wl)
+    T = oracle.encode_targets(wl.W, wl.G, wl.alpha)
+    k = wl.k
+    idx = oracle.select_topk_groups(T, wl.W, g, k)
+    ctx = PVContext(0)
+    Td, cb, sc, idxd = dev_f32(T), dev_f32(wl.codebooks), dev_f32(wl.scales), dev_i32(idx)
+    start = dev_u16(wl.codes)
+    nch = torch.zeros(1, dtype=torch.int64, device=DEV)
+    first = None
+    for rep in range(30):
+        codes = start.clone()
+        if stochastic:
+            ctx.pv_reencode_groups_stochastic(lay, Td, cb, sc, idxd, k, 5, 31337, codes, nch)
+        else:
+            ctx.pv_reencode_groups(lay, Td, cb, sc, idxd, k, beam, codes, nch)
+        torch.cuda.synchronize()
+        got = (host_u16(codes).copy(), int(nch.item()))
+        if first is None:
+            first = got
+        else:
+            assert np.array_equal(got[0], first[0]) and got[1] == first[1], rep
+    ctx.close()
