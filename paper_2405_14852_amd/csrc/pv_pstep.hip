@@ -194,29 +194,33 @@ __global__ __launch_bounds__(kBlock) void k_pg_long(const int32_t *__restrict__ 
 // of two that leaves `headroom` bits for the number of terms one block can add, and rounded
 // to an integer once; integer addition is associative, so a table is a function of the
 // block's inputs only.  The tables are added over the blocks as integers too (exactly) and
-// the total is scaled back and rounded to fp32.  A term keeps 62 - headroom bits below X
-// (>= 39 for the largest matrices), so a sum differs from the exact one by far less than
-// the rounding of a sequential double loop does.  Gradients or scales that are not finite
-// make every entry NaN.
-__global__ __launch_bounds__(kBlock) void k_pg_small(const float *__restrict__ G,
-                                                     const uint16_t *__restrict__ codes,
-                                                     const float *__restrict__ scales, int64_t N,
-                                                     int64_t per_block, int g, int M, int nbits,
-                                                     int gpr, int out_features,
-                                                     const unsigned *__restrict__ gmax_bits,
-                                                     int nmax, int headroom, long long *__restrict__ partial,
-                                                     double *__restrict__ meta)
+// the total is scaled back and rounded to fp32.  A term keeps min(62 - headroom, 50) bits
+// below X (>= 39 for the largest matrices), so a sum differs from the exact one by far less
+// than the rounding of a sequential double loop does.  Gradients or scales that are not
+// finite make every entry NaN.  The kernel is bound by the LDS atomics (sixteen per group and
+// codebook), not by reading G: indices are kept in 32 bits relative to the block's range and
+// the conversion to an integer is one addition, so that the vector ALU stays out of the way.
+constexpr int kSmallBlock = 1024;                         // one table serves sixteen waves
+constexpr int kSmallAhead = 2;                            // vectors of a thread in flight
+// VPG: 16-byte vectors per group when that is 1, 2 or 4 (a shift finds the group), else 0
+template <int VPG>
+__global__ __launch_bounds__(kSmallBlock) void k_pg_small(
+    const float *__restrict__ G, const uint16_t *__restrict__ codes,
+    const float *__restrict__ scales, int64_t N, int64_t per_block, int g, int M, int nbits,
+    int gpr, int out_features, const unsigned *__restrict__ gmax_bits, int nmax, int headroom,
+    long long *__restrict__ partial, double *__restrict__ meta)
 {
     extern __shared__ unsigned long long tab[];         // [M][2^B][g]
-    __shared__ unsigned s_max[2 * (kBlock / 64)];
+    __shared__ unsigned s_max[2 * (kSmallBlock / 64)];
+    constexpr int kW = kSmallBlock / 64;
     const int csize = 1 << nbits;
     const unsigned mask = (unsigned)csize - 1u;
     const int entries = M * csize * g;
-    for (int e = threadIdx.x; e < entries; e += kBlock) tab[e] = 0ull;
+    for (int e = threadIdx.x; e < entries; e += kSmallBlock) tab[e] = 0ull;
     // largest |scale| (as bits: NaN > inf > every finite value)
     unsigned sb = 0u, gb = 0u;
-    for (int o = threadIdx.x; o < out_features; o += kBlock) sb = max(sb, __float_as_uint(fabsf(scales[o])));
-    for (int o = threadIdx.x; o < nmax; o += kBlock) gb = max(gb, gmax_bits[o]);
+    for (int o = threadIdx.x; o < out_features; o += kSmallBlock) sb = max(sb, __float_as_uint(fabsf(scales[o])));
+    for (int o = threadIdx.x; o < nmax; o += kSmallBlock) gb = max(gb, gmax_bits[o]);
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) {
         sb = max(sb, (unsigned)__shfl_down(sb, off));
@@ -224,40 +228,79 @@ __global__ __launch_bounds__(kBlock) void k_pg_small(const float *__restrict__ G
     }
     if ((threadIdx.x & 63) == 0) {
         s_max[threadIdx.x >> 6] = sb;
-        s_max[4 + (threadIdx.x >> 6)] = gb;
+        s_max[kW + (threadIdx.x >> 6)] = gb;
     }
     __syncthreads();
-    sb = max(max(s_max[0], s_max[1]), max(s_max[2], s_max[3]));
-    gb = max(max(s_max[4], s_max[5]), max(s_max[6], s_max[7]));
+    sb = gb = 0u;
+#pragma unroll
+    for (int w = 0; w < kW; ++w) {
+        sb = max(sb, s_max[w]);
+        gb = max(gb, s_max[kW + w]);
+    }
     const double X = (double)__uint_as_float(sb) * (double)__uint_as_float(gb);
     const bool poison = !(X < __builtin_huge_val());
     int ex = 0;
     (void)frexp(X, &ex);                                  // X < 2^ex
-    const double up = (X > 0.0 && !poison) ? ldexp(1.0, 62 - headroom - ex) : 0.0;
+    const int kbits = 62 - headroom < 50 ? 62 - headroom : 50;   // bits of a term below 2^ex
+    const double up = (X > 0.0 && !poison) ? ldexp(1.0, kbits - ex) : 0.0;
     if (blockIdx.x == 0 && threadIdx.x == 0) {
-        meta[0] = (X > 0.0 && !poison) ? ldexp(1.0, -(62 - headroom - ex)) : 0.0;
+        meta[0] = (X > 0.0 && !poison) ? ldexp(1.0, -(kbits - ex)) : 0.0;
         meta[1] = poison ? 1.0 : 0.0;
     }
-    const int vpg = g / 4;                              // 16-byte vectors per group
+    const unsigned vpg = VPG > 0 ? (unsigned)VPG : (unsigned)(g / 4);   // 16-byte vectors per group
     const int64_t lo = (int64_t)blockIdx.x * per_block;
     const int64_t hi = lo + per_block < N ? lo + per_block : N;
-    const pv_f4 *G4 = reinterpret_cast<const pv_f4 *>(G);
-    for (int64_t v = lo * vpg + threadIdx.x; v < hi * vpg; v += kBlock) {
-        const int64_t n = v / vpg;
-        const int q4 = (int)(v - n * vpg);
-        const pv_f4 gv = __builtin_nontemporal_load(&G4[v]);
-        const double s = (double)scales[n / gpr] * up;  // a power of two: exact
-        for (int m = 0; m < M; ++m) {
-            const int c = codes[n * M + m] & mask;
-            unsigned long long *row = tab + ((int64_t)m * csize + c) * g + q4 * 4;
+    // everything inside the block's range is counted from its first group in 32 bits
+    const unsigned nvec = hi > lo ? (unsigned)(hi - lo) * vpg : 0u;
+    const unsigned row0 = (unsigned)(lo / gpr), rem0 = (unsigned)(lo - (int64_t)row0 * gpr);
+    const pv_f4 *G4 = reinterpret_cast<const pv_f4 *>(G) + lo * vpg;
+    const uint16_t *codes0 = codes + lo * M;
+    // x + 1.5 * 2^52 holds the integer nearest to x (ties to even) in its low mantissa bits
+    // for |x| < 2^51; the terms stay below 2^50
+    constexpr double kMagic = 6755399441055744.0;
+    const long long magic_bits = __double_as_longlong(kMagic);
+    // Within a codeword's row the elements are permuted by bits of the code (power-of-two
+    // groups): for a given element the 64 lanes of an atomic then spread over all LDS banks
+    // instead of the few that a row stride of 8 g bytes leaves them.
+    const unsigned swm = (g & (g - 1)) == 0 ? (unsigned)g - 1u : 0u;
+    for (unsigned v0 = threadIdx.x; v0 < nvec; v0 += kSmallBlock * kSmallAhead) {
+        pv_f4 gv[kSmallAhead];
+        float sf[kSmallAhead];
+        unsigned nl[kSmallAhead], q4[kSmallAhead], c01[kSmallAhead][2];
+#pragma unroll
+        for (int u = 0; u < kSmallAhead; ++u) {
+            const unsigned v = v0 + (unsigned)u * kSmallBlock;
+            const unsigned vc = v < nvec ? v : nvec - 1u;   // clamped: the loads of a batch go out together
+            nl[u] = vc / vpg;
+            q4[u] = vc - nl[u] * vpg;
+            gv[u] = __builtin_nontemporal_load(&G4[vc]);
+            sf[u] = scales[row0 + (rem0 + nl[u]) / (unsigned)gpr];
+#pragma unroll
+            for (int m = 0; m < 2; ++m) c01[u][m] = m < M ? codes0[(size_t)nl[u] * M + m] & mask : 0u;
+        }
+#pragma unroll
+        for (int u = 0; u < kSmallAhead; ++u) {
+            if (v0 + (unsigned)u * kSmallBlock >= nvec) break;
+            const double ss = (double)sf[u] * up;           // a power of two: exact
+            unsigned long long term[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e)
-                atomicAdd(&row[e], (unsigned long long)__double2ll_rn(s * (double)gv[e]));
+                term[e] = (unsigned long long)(__double_as_longlong(ss * (double)gv[u][e] + kMagic) - magic_bits);
+            for (int m = 0; m < M; ++m) {
+                const unsigned c = m < 2 ? c01[u][m] : codes0[(size_t)nl[u] * M + m] & mask;
+                unsigned long long *row = tab + ((size_t)m * csize + c) * g;
+                const unsigned sw = (c >> 2) & swm;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) atomicAdd(&row[(q4[u] * 4u + e) ^ sw], term[e]);
+            }
         }
     }
     __syncthreads();
     long long *out = partial + (int64_t)blockIdx.x * entries;
-    for (int e = threadIdx.x; e < entries; e += kBlock) out[e] = (long long)tab[e];
+    for (int e = threadIdx.x; e < entries; e += kSmallBlock) {
+        const unsigned sw = (((unsigned)e / (unsigned)g) >> 2) & swm;
+        out[e] = (long long)tab[(unsigned)e ^ sw];
+    }
 }
 
 // adds the per-block tables as integers (16 threads per entry, each a slice of the blocks),
@@ -466,9 +509,15 @@ pv_status pv_launch_codebook_grads(pv_ctx *ctx, const pv_layout *l, const float 
                                G, codes, codebooks, g, M, l->nbits, gpr, grad_scales, gmax);
         else
             hipLaunchKernelGGL(k_pg_absmax, dim3((unsigned)mblocks), dim3(kBlock), 0, sm, G, n4, gmax);
-        hipLaunchKernelGGL(k_pg_small, dim3(blocks), dim3(kBlock), (size_t)entries * 8, sm, G, codes,
-                           scales, N, per_block, g, M, l->nbits, gpr, (int)l->out_features, gmax,
-                           nmax, headroom, partial, meta);
+#define PV_SMALL(V_)                                                                             \
+    hipLaunchKernelGGL(k_pg_small<V_>, dim3(blocks), dim3(kSmallBlock), (size_t)entries * 8, sm, G, \
+                       codes, scales, N, per_block, g, M, l->nbits, gpr, (int)l->out_features,  \
+                       gmax, nmax, headroom, partial, meta)
+        if (g == 8) PV_SMALL(2);
+        else if (g == 16) PV_SMALL(4);
+        else if (g == 4) PV_SMALL(1);
+        else PV_SMALL(0);
+#undef PV_SMALL
         hipLaunchKernelGGL(k_pg_small_final,
                            dim3((unsigned)((entries + kBlock / kSlices - 1) / (kBlock / kSlices))),
                            dim3(kBlock), 0, sm, partial, blocks, (int)entries, meta, grad_codebooks);

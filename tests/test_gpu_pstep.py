@@ -150,6 +150,23 @@ def test_codebook_grads_small_codebook_route_is_close_to_the_exact_sum_and_flags
     assert (gc == 0).all() and (gs == 0).all()
 
 
+@pytest.mark.parametrize("g,M,B,shape", [(16, 1, 6, (128, 2048)), (16, 2, 8, (512, 4096)), (12, 1, 5, (96, 1536)),
+                                         (8, 3, 5, (128, 1024)), (4, 2, 4, (64, 512)), (8, 1, 6, (100, 1000)),
+                                         (8, 2, 8, (1031, 1160))])
+def test_codebook_grads_small_codebook_route_shapes(g, M, B, shape):
+    """The fixed-point route over the group sizes it has a kernel for (4, 8, 16 and the general
+    one), more than two codebooks, and block ranges that start in the middle of a row."""
+    wl = workloads.make(shape[0], shape[1], g, M, B, seed=89, sigma_g=1e-2)
+    gc, gs, gc_ref, gs_ref = run_case(wl)
+    assert (gc.view(np.uint32) != gc_ref.view(np.uint32)).mean() < 0.01
+    assert close_sum(gc, gc_ref, 1e-3 * np.abs(wl.G).sum() * np.abs(wl.scales).max())
+    q = oracle.dequantize(wl.codes, wl.codebooks, np.ones_like(wl.scales))
+    assert close_sum(gs, gs_ref, np.abs(wl.G * q).sum(axis=1))
+    again, gs2, _, _ = run_case(wl)
+    assert np.array_equal(gc.view(np.uint32), again.view(np.uint32))
+    assert np.array_equal(gs.view(np.uint32), gs2.view(np.uint32))
+
+
 def test_codebook_grads_of_an_empty_matrix_are_zero():
     from paper_2405_14852_amd import Layout, PVContext
     ctx = PVContext(0)
