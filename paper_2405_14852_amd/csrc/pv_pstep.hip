@@ -253,6 +253,7 @@ __global__ __launch_bounds__(kSmallBlock) void k_pg_small(
     // everything inside the block's range is counted from its first group in 32 bits
     const unsigned nvec = hi > lo ? (unsigned)(hi - lo) * vpg : 0u;
     const unsigned row0 = (unsigned)(lo / gpr), rem0 = (unsigned)(lo - (int64_t)row0 * gpr);
+    const double inv_gpr = 1.0 / (double)gpr;
     const pv_f4 *G4 = reinterpret_cast<const pv_f4 *>(G) + lo * vpg;
     const uint16_t *codes0 = codes + lo * M;
     // x + 1.5 * 2^52 holds the integer nearest to x (ties to even) in its low mantissa bits
@@ -274,7 +275,7 @@ __global__ __launch_bounds__(kSmallBlock) void k_pg_small(
             nl[u] = vc / vpg;
             q4[u] = vc - nl[u] * vpg;
             gv[u] = __builtin_nontemporal_load(&G4[vc]);
-            sf[u] = scales[row0 + (rem0 + nl[u]) / (unsigned)gpr];
+            sf[u] = scales[row0 + pv_row_of(rem0 + nl[u], inv_gpr)];
 #pragma unroll
             for (int m = 0; m < 2; ++m) c01[u][m] = m < M ? codes0[(size_t)nl[u] * M + m] & mask : 0u;
         }

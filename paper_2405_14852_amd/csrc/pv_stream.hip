@@ -109,17 +109,19 @@ __global__ __launch_bounds__(kBlock) void k_encode_targets_adam(const float *W, 
 #define PV_DEQ_AHEAD 2   // measured: 1 leaves two-codebook layouts bound by round trips, 4 and 8 lose to register pressure
 #endif
 constexpr int kDeqAhead = PV_DEQ_AHEAD;
-template <int VEC>
+// PARTS: 16-byte vectors per group when known at compile time (1, 2 or 4), else 0
+template <int VEC, int PARTS>
 __global__ __launch_bounds__(kBlock) void k_dequantize(const uint16_t *__restrict__ codes,
                                                        const float *__restrict__ codebooks,
                                                        const float *__restrict__ scales,
                                                        float *__restrict__ W_out, int64_t total,
-                                                       int g, int M, int nbits, int gpr)
+                                                       int g, int M, int nbits, int gpr,
+                                                       double inv_gpr)
 {
     const unsigned mask = (1u << nbits) - 1u;
     const int64_t csize = (int64_t)1 << nbits;
     if constexpr (VEC == 4) {
-        const int parts = g / 4;
+        const int parts = PARTS > 0 ? PARTS : g / 4;
         const pv_f4 *cb4 = reinterpret_cast<const pv_f4 *>(codebooks);
         const int64_t first = (int64_t)blockIdx.x * (kBlock * kDeqAhead) + threadIdx.x;
         int64_t at[kDeqAhead];
@@ -135,7 +137,7 @@ __global__ __launch_bounds__(kBlock) void k_dequantize(const uint16_t *__restric
             q[u] = (int)(at[u] - (int64_t)n * parts);
             cp[u] = codes + (int64_t)n * M;
             code[u] = cp[u][0] & mask;
-            s[u] = scales[n / gpr];
+            s[u] = scales[pv_row_of((unsigned)n, inv_gpr)];
         }
         pv_f4 acc[kDeqAhead];
 #pragma unroll
@@ -307,15 +309,21 @@ pv_status pv_launch_dequantize(pv_ctx *ctx, const pv_layout *l, const uint16_t *
     if (g % 4 == 0) {
         int64_t total = N * (g / 4);
         int64_t blocks = (total + kBlock * kDeqAhead - 1) / (kBlock * kDeqAhead);
-        hipLaunchKernelGGL(k_dequantize<4>, dim3((unsigned)blocks), dim3(kBlock), 0, ctx->stream,
-                           codes, codebooks, scales, W_out, total, g, l->num_codebooks, l->nbits,
-                           gpr);
+#define PV_DEQ(P_)                                                                               \
+    hipLaunchKernelGGL((k_dequantize<4, P_>), dim3((unsigned)blocks), dim3(kBlock), 0, ctx->stream, \
+                       codes, codebooks, scales, W_out, total, g, l->num_codebooks, l->nbits,   \
+                       gpr, 1.0 / (double)gpr)
+        if (g == 8) PV_DEQ(2);
+        else if (g == 16) PV_DEQ(4);
+        else if (g == 4) PV_DEQ(1);
+        else PV_DEQ(0);
+#undef PV_DEQ
     } else {
         int64_t total = N * g;
         int64_t blocks = (total + kBlock - 1) / kBlock;
-        hipLaunchKernelGGL(k_dequantize<1>, dim3((unsigned)blocks), dim3(kBlock), 0, ctx->stream,
+        hipLaunchKernelGGL((k_dequantize<1, 0>), dim3((unsigned)blocks), dim3(kBlock), 0, ctx->stream,
                            codes, codebooks, scales, W_out, total, g, l->num_codebooks, l->nbits,
-                           gpr);
+                           gpr, 1.0 / (double)gpr);
     }
     PV_HIP(ctx, hipGetLastError());
     return PV_OK;
