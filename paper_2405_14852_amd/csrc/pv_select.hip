@@ -15,8 +15,7 @@
 // the later digits usually see only the few per cent of keys that share the
 // chosen digit 0, but a narrow score distribution (updates of one size, as an
 // optimiser's sign-like step produces) sends nearly all keys there, so they are
-// counted in per-block LDS histograms as well, with wave-wide merging of the
-// leading bin.  Each launch resolves the digit of the histogram before it and
+// counted in per-block LDS histograms as well.  Each launch resolves the digit of the histogram before it and
 // publishes it for the launches that follow.
 #include "pv_internal.h"
 
@@ -25,7 +24,7 @@
 #endif
 
 #ifndef PV_LATE_VOTE_ROUNDS
-#define PV_LATE_VOTE_ROUNDS 1   // the same for the later digits
+#define PV_LATE_VOTE_ROUNDS 0   // the same for the later digits: measured slower than plain LDS atomics, also on a one-bin distribution
 #endif
 
 namespace {
