@@ -473,7 +473,8 @@ __global__ __launch_bounds__(kBlock) void k_targets_scores_hist0_sub(const float
 // block 0 publishes it in `state` for the launches that follow:
 // state[4] = digit 0, state[5] = digit 1, state[6] = rank left after digit 0,
 // state[7] = rank left after digit 1.
-__global__ __launch_bounds__(kBlock) void k_hist_next(const float *__restrict__ scores,
+constexpr int kHistBlock = 512;   // measured against 256 and 1024 threads on 2 M and 5.6 M groups
+__global__ __launch_bounds__(kHistBlock) void k_hist_next(const float *__restrict__ scores,
                                                       const unsigned *__restrict__ hist_all,
                                                       unsigned *__restrict__ hist_out,
                                                       unsigned *__restrict__ state, int N,
@@ -501,16 +502,15 @@ __global__ __launch_bounds__(kBlock) void k_hist_next(const float *__restrict__ 
     // Per-block histogram in LDS, flushed once: a narrow score distribution (all updates of
     // one size, as after a sign-like optimiser step) puts most keys into a few bins, and that
     // many atomics on a few global addresses would serialise.
-    for (int b = threadIdx.x; b < bins; b += kBlock) lh[b] = 0;
+    for (int b = threadIdx.x; b < bins; b += kHistBlock) lh[b] = 0;
     __syncthreads();
     const pv_f4 *s4 = reinterpret_cast<const pv_f4 *>(scores);
     const int64_t n4 = N >> 2;
-    const int64_t stride = (int64_t)gridDim.x * kBlock;
-    // whole blocks stay in the loop together (the histogram update uses wave-wide votes)
+    const int64_t stride = (int64_t)gridDim.x * kHistBlock;
     // four vectors per thread in flight: with many groups (single-weight units) the loop is
     // otherwise one memory round trip per vector
     constexpr int kAhead = 4;
-    for (int64_t base = (int64_t)blockIdx.x * kBlock; base < n4; base += stride * kAhead) {
+    for (int64_t base = (int64_t)blockIdx.x * kHistBlock; base < n4; base += stride * kAhead) {
         pv_f4 v[kAhead];
 #pragma unroll
         for (int u = 0; u < kAhead; ++u) {
@@ -524,7 +524,7 @@ __global__ __launch_bounds__(kBlock) void k_hist_next(const float *__restrict__ 
             for (int e = 0; e < 4; ++e) {
                 unsigned key = __float_as_uint(v[u][e]);
                 bool valid = i < n4 && digit_of(key, 0) == d0 && (pass == 1 || digit_of(key, 1) == d1);
-                if (__ballot(valid)) hist_add<PV_LATE_VOTE_ROUNDS>(lh, digit_of(key, pass), valid);
+                hist_add<PV_LATE_VOTE_ROUNDS>(lh, digit_of(key, pass), valid);
             }
         }
     }
@@ -534,7 +534,10 @@ __global__ __launch_bounds__(kBlock) void k_hist_next(const float *__restrict__ 
             atomicAdd(&lh[digit_of(key, pass)], 1u);
     }
     __syncthreads();
-    flush_hist(lh, hist_out, bins);
+    for (int b = threadIdx.x; b < bins; b += kHistBlock) {
+        unsigned v = lh[b];
+        if (v) atomicAdd(&hist_out[hist_slot(b, bins)], v);
+    }
 }
 
 __device__ __forceinline__ unsigned block_sum(unsigned v, unsigned *tmp)
@@ -857,12 +860,12 @@ static pv_status select_run(pv_ctx *ctx, const pv_layout *l, const float *T, con
     }   // group sizes other than 1 and 2
     if (k > 0) {
         pv_timed t(ctx, PV_K_SELECT);
-        int64_t hb = ((int64_t)(N >> 2) + kBlock - 1) / kBlock;
+        int64_t hb = ((int64_t)(N >> 2) + kHistBlock - 1) / kHistBlock;
         const unsigned hblocks = (unsigned)(hb < 512 ? (hb < 1 ? 1 : hb) : 512);
         const unsigned cblocks = (unsigned)(nchunks < kMaxBlocks ? nchunks : kMaxBlocks);
-        hipLaunchKernelGGL(k_hist_next, dim3(hblocks), dim3(kBlock), 0, ctx->stream, scores, hist,
+        hipLaunchKernelGGL(k_hist_next, dim3(hblocks), dim3(kHistBlock), 0, ctx->stream, scores, hist,
                            hist + kHist1, state, N, (unsigned)k, 1);
-        hipLaunchKernelGGL(k_hist_next, dim3(hblocks), dim3(kBlock), 0, ctx->stream, scores, hist,
+        hipLaunchKernelGGL(k_hist_next, dim3(hblocks), dim3(kHistBlock), 0, ctx->stream, scores, hist,
                            hist + kHist2, state, N, (unsigned)k, 2);
         hipLaunchKernelGGL(k_chunk_counts, dim3(cblocks), dim3(kBlock), 0, ctx->stream, scores, hist,
                            state, cc, N, nchunks);
