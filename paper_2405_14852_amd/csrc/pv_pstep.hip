@@ -202,22 +202,17 @@ __global__ __launch_bounds__(kBlock) void k_pg_long(const int32_t *__restrict__ 
 // the conversion to an integer is one addition, so that the vector ALU stays out of the way.
 constexpr int kSmallBlock = 1024;                         // one table serves sixteen waves
 constexpr int kSmallAhead = 2;                            // vectors of a thread in flight
-// VPG: 16-byte vectors per group when that is 1, 2 or 4 (a shift finds the group), else 0
-template <int VPG>
-__global__ __launch_bounds__(kSmallBlock) void k_pg_small(
-    const float *__restrict__ G, const uint16_t *__restrict__ codes,
-    const float *__restrict__ scales, int64_t N, int64_t per_block, int g, int M, int nbits,
-    int gpr, int out_features, const unsigned *__restrict__ gmax_bits, int nmax, int headroom,
-    long long *__restrict__ partial, double *__restrict__ meta)
+// The power of two that turns a term s_o * G into a 64-bit integer (see k_pg_small): from the
+// largest |scale| and the largest |G| (as bits: NaN > inf > every finite value), leaving
+// `headroom` bits for the terms one block adds to an entry.  Block 0 leaves the inverse factor
+// and the poison flag (some input not finite) in meta[0], meta[1].  All threads of a
+// kSmallBlock-wide block call this; s_max is 2 * kSmallBlock / 64 unsigneds of LDS.
+__device__ __forceinline__ double fixed_point_unit(const float *__restrict__ scales, int out_features,
+                                                   const unsigned *__restrict__ gmax_bits, int nmax,
+                                                   int headroom, unsigned *s_max,
+                                                   double *__restrict__ meta)
 {
-    extern __shared__ unsigned long long tab[];         // [M][2^B][g]
-    __shared__ unsigned s_max[2 * (kSmallBlock / 64)];
     constexpr int kW = kSmallBlock / 64;
-    const int csize = 1 << nbits;
-    const unsigned mask = (unsigned)csize - 1u;
-    const int entries = M * csize * g;
-    for (int e = threadIdx.x; e < entries; e += kSmallBlock) tab[e] = 0ull;
-    // largest |scale| (as bits: NaN > inf > every finite value)
     unsigned sb = 0u, gb = 0u;
     for (int o = threadIdx.x; o < out_features; o += kSmallBlock) sb = max(sb, __float_as_uint(fabsf(scales[o])));
     for (int o = threadIdx.x; o < nmax; o += kSmallBlock) gb = max(gb, gmax_bits[o]);
@@ -242,11 +237,36 @@ __global__ __launch_bounds__(kSmallBlock) void k_pg_small(
     int ex = 0;
     (void)frexp(X, &ex);                                  // X < 2^ex
     const int kbits = 62 - headroom < 50 ? 62 - headroom : 50;   // bits of a term below 2^ex
-    const double up = (X > 0.0 && !poison) ? ldexp(1.0, kbits - ex) : 0.0;
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         meta[0] = (X > 0.0 && !poison) ? ldexp(1.0, -(kbits - ex)) : 0.0;
         meta[1] = poison ? 1.0 : 0.0;
     }
+    return (X > 0.0 && !poison) ? ldexp(1.0, kbits - ex) : 0.0;
+}
+
+// x + 1.5 * 2^52 holds the integer nearest to x (ties to even) in its low mantissa bits for
+// |x| < 2^51; the terms stay below 2^50
+__device__ __forceinline__ unsigned long long fixed_point_term(double x)
+{
+    constexpr double kMagic = 6755399441055744.0;
+    return (unsigned long long)(__double_as_longlong(x + kMagic) - __double_as_longlong(kMagic));
+}
+
+// VPG: 16-byte vectors per group when that is 1, 2 or 4 (a shift finds the group), else 0
+template <int VPG>
+__global__ __launch_bounds__(kSmallBlock) void k_pg_small(
+    const float *__restrict__ G, const uint16_t *__restrict__ codes,
+    const float *__restrict__ scales, int64_t N, int64_t per_block, int g, int M, int nbits,
+    int gpr, int out_features, const unsigned *__restrict__ gmax_bits, int nmax, int headroom,
+    long long *__restrict__ partial, double *__restrict__ meta)
+{
+    extern __shared__ unsigned long long tab[];         // [M][2^B][g]
+    __shared__ unsigned s_max[2 * (kSmallBlock / 64)];
+    const int csize = 1 << nbits;
+    const unsigned mask = (unsigned)csize - 1u;
+    const int entries = M * csize * g;
+    for (int e = threadIdx.x; e < entries; e += kSmallBlock) tab[e] = 0ull;
+    const double up = fixed_point_unit(scales, out_features, gmax_bits, nmax, headroom, s_max, meta);
     const unsigned vpg = VPG > 0 ? (unsigned)VPG : (unsigned)(g / 4);   // 16-byte vectors per group
     const int64_t lo = (int64_t)blockIdx.x * per_block;
     const int64_t hi = lo + per_block < N ? lo + per_block : N;
@@ -256,10 +276,6 @@ __global__ __launch_bounds__(kSmallBlock) void k_pg_small(
     const double inv_gpr = 1.0 / (double)gpr;
     const pv_f4 *G4 = reinterpret_cast<const pv_f4 *>(G) + lo * vpg;
     const uint16_t *codes0 = codes + lo * M;
-    // x + 1.5 * 2^52 holds the integer nearest to x (ties to even) in its low mantissa bits
-    // for |x| < 2^51; the terms stay below 2^50
-    constexpr double kMagic = 6755399441055744.0;
-    const long long magic_bits = __double_as_longlong(kMagic);
     // Within a codeword's row the elements are permuted by bits of the code (power-of-two
     // groups): for a given element the 64 lanes of an atomic then spread over all LDS banks
     // instead of the few that a row stride of 8 g bytes leaves them.
@@ -286,7 +302,7 @@ __global__ __launch_bounds__(kSmallBlock) void k_pg_small(
             unsigned long long term[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e)
-                term[e] = (unsigned long long)(__double_as_longlong(ss * (double)gv[u][e] + kMagic) - magic_bits);
+                term[e] = fixed_point_term(ss * (double)gv[u][e]);
             for (int m = 0; m < M; ++m) {
                 const unsigned c = m < 2 ? c01[u][m] : codes0[(size_t)nl[u] * M + m] & mask;
                 unsigned long long *row = tab + ((size_t)m * csize + c) * g;
