@@ -57,8 +57,9 @@
 #define PV_SUPER 2    // codeword tiles behind one key (a super-unit)
 #endif
 #ifndef PV_TEAM
-#define PV_TEAM 8     // lanes of the re-rank kernel that share one group
+#define PV_TEAM 8     // lanes of the re-rank kernel that share one group at g = 8 (twice as many at g = 16: measured)
 #endif
+constexpr int rerank_team(int g) { return g == 16 && PV_TEAM < 16 ? 2 * PV_TEAM : PV_TEAM; }
 #ifndef PV_DEPTH
 #define PV_DEPTH 2    // units (matrix instructions) in flight before a unit's accumulators are reduced
 #endif
@@ -846,7 +847,7 @@ __global__ __launch_bounds__(kBlock, PV_RR_OCC) void k_rerank(
     unsigned *__restrict__ block_counts, unsigned long long *__restrict__ change_slots,
     unsigned long long *__restrict__ num_changed, int nbits)
 {
-    constexpr int kTeam = PV_TEAM;                 // lanes per group
+    constexpr int kTeam = rerank_team(G);          // lanes per group
     constexpr int kTeams = kBlock / kTeam;         // groups per block
     constexpr int kPer = 16 / kTeam;               // positions of a half tile per lane
     static_assert(kTeam == 4 || kTeam == 8 || kTeam == 16, "a team is a power of two of at most 16 lanes");
@@ -1315,7 +1316,7 @@ __global__ __launch_bounds__(kBlock) void k_round_top2(
     unsigned long long *__restrict__ change_slots, unsigned long long *__restrict__ num_changed,
     int nbits, int power, unsigned long long seed)
 {
-    constexpr int kTeam = PV_TEAM;
+    constexpr int kTeam = rerank_team(G);
     constexpr int kTeams = kBlock / kTeam;
     constexpr int kPer = 16 / kTeam;
     constexpr int kMine = kU * kPer;               // positions of a key per lane
@@ -1733,7 +1734,7 @@ pv_status pv_launch_mfma_search(pv_ctx *ctx, const pv_layout *l, const float *T,
         return st;
     if ((st = pv_ensure(ctx, ctx->partials, (size_t)p.k_pad * p.P * sizeof(int2))) != PV_OK) return st;
     if ((st = pv_ensure(ctx, ctx->fb_list, 64)) != PV_OK) return st;
-    const int rr_blocks = (int)((k * PV_TEAM + kBlock - 1) / kBlock);
+    const int rr_blocks = (int)((k * rerank_team(l->group_size) + kBlock - 1) / kBlock);
     const int nslots = (rr_blocks + 63) / 64;
     if ((st = pv_ensure(ctx, ctx->rr_counts, (size_t)rr_blocks * 4 * sizeof(unsigned) + (size_t)nslots * 8 + 16)) != PV_OK)
         return st;
