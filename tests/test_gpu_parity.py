@@ -143,6 +143,23 @@ def test_dequantize_bit_exact(g, M, B):
     assert np.array_equal(W.view(np.uint32), ref.view(np.uint32))
 
 
+def test_dequantize_two_codebooks_with_codes_on_an_odd_halfword():
+    """The codes of a two-codebook group are read with one 4-byte load when the array allows
+    it; an array that starts on an odd 2-byte boundary takes the general kernel: same weights."""
+    wl = workloads.make(67, 192, 8, 2, 8, seed=23)
+    run = GpuRun(wl)
+    flat = wl.codes.reshape(-1)
+    big = torch.zeros(flat.size + 8, dtype=torch.int16, device=DEV)
+    big[1:1 + flat.size] = torch.from_numpy(flat.view(np.int16)).to(DEV)
+    shifted = big[1:1 + flat.size].view(torch.uint16)
+    assert shifted.data_ptr() % 4 == 2
+    W = torch.empty((67, 192), dtype=torch.float32, device=DEV)
+    run.ctx.pv_dequantize(run.lay, shifted, run.cb, run.sc, W)
+    torch.cuda.synchronize()
+    ref = oracle.dequantize(wl.codes, wl.codebooks, wl.scales)
+    assert np.array_equal(W.cpu().numpy().view(np.uint32), ref.view(np.uint32))
+
+
 @pytest.mark.parametrize("g,M,B", [(8, 1, 8), (8, 2, 8), (16, 1, 12), (6, 3, 4), (1, 1, 2)])
 def test_dequantize_groups_updates_only_the_listed_groups(g, M, B):
     wl = workloads.make(67, 24 * g, g, M, B, seed=13)
