@@ -937,7 +937,7 @@ __global__ __launch_bounds__(kBlock, PV_RR_OCC) void k_rerank(
         // consecutive rows), and the exact objective only for positions that can still reach
         // the best objective known: || c_hi - x_hi || <= P sqrt(E) / |s| + dC + dx.
         constexpr int kMine = kU * kPer;               // positions of a key per lane
-        auto level1 = [&](int key, int p, float (&dd)[kMine], int (&pos)[kMine]) {
+        auto level1 = [&](int key, int p, float (&dd)[kMine], int (&pos)[kMine], int (&cwd)[kMine]) {
             const int su = key & (int)kKeyMask;
             const int hw = (p / per_half) & 1;
 #pragma unroll
@@ -950,13 +950,15 @@ __global__ __launch_bounds__(kBlock, PV_RR_OCC) void k_rerank(
                     // unconditional (the padded table has the row), so that the loads of all the
                     // lane's positions are in flight together
                     dd[uu * kPer + e] = approx_dd<G>(A, cnorm, su * kU + uu, row, pos[uu * kPer + e], xq, meta.y);
+                    // the codeword behind the position comes along (g = 8: positions are
+                    // codewords), so that an exact evaluation is one more round trip, not two
+                    cwd[uu * kPer + e] = G == 8 ? pos[uu * kPer + e] : (int)perm[pos[uu * kPer + e]];
                 }
 #pragma unroll
             for (int i = 0; i < kMine; ++i)
                 if (pos[i] >= csize) dd[i] = __builtin_huge_valf();
         };
-        auto exact_at = [&](int pos, cand_t &c) {
-            const int cw = G == 8 ? pos : (int)perm[pos];   // g = 8: positions are codewords
+        auto exact_at = [&](int cw, cand_t &c) {
             const double o = exact_obj<G>(codebook + (int64_t)cw * G, s, t);
             if (cand_better(o, cw, c.obj, c.idx)) {
                 c.obj = o;
@@ -989,8 +991,8 @@ __global__ __launch_bounds__(kBlock, PV_RR_OCC) void k_rerank(
         double e_star = o_prev;
         if (best_key != kNoKey) {
             float dd[kMine];
-            int pos[kMine];
-            level1(best_key, best_p, dd, pos);
+            int pos[kMine], cwd[kMine];
+            level1(best_key, best_p, dd, pos, cwd);
             // the position that looks nearest is evaluated first: it fixes the reach for the rest
             int wu = 0;
             float dmin = dd[0];
@@ -1008,10 +1010,10 @@ __global__ __launch_bounds__(kBlock, PV_RR_OCC) void k_rerank(
             }
             const bool chosen = (int)(pick & 15u) == q && dmin < 3.0e38f;
             if (chosen) {
-                int pw = pos[0];                   // pos[wu] without dynamic register indexing
+                int pw = cwd[0];                   // cwd[wu] without dynamic register indexing
 #pragma unroll
                 for (int uu = 1; uu < kMine; ++uu)
-                    if (uu == wu) pw = pos[uu];
+                    if (uu == wu) pw = cwd[uu];
                 exact_at(pw, mine);
             }
             const double o0 = __shfl(mine.obj, (int)(pick & 15u), kTeam);
@@ -1020,7 +1022,7 @@ __global__ __launch_bounds__(kBlock, PV_RR_OCC) void k_rerank(
 #pragma unroll
             for (int uu = 0; uu < kMine; ++uu)
                 if (!(chosen && uu == wu) && dd[uu] - dabs <= r2f && pos[uu] < csize) {
-                    exact_at(pos[uu], mine);
+                    exact_at(cwd[uu], mine);
                     ++exact_evals;
                 }
             if (chosen) ++exact_evals;
@@ -1065,12 +1067,12 @@ __global__ __launch_bounds__(kBlock, PV_RR_OCC) void k_rerank(
             key = __shfl(key, src, kTeam);
             {
                 float dd[kMine];
-                int pos[kMine];
-                level1(key, src + kTeam * u, dd, pos);
+                int pos[kMine], cwd[kMine];
+                level1(key, src + kTeam * u, dd, pos, cwd);
 #pragma unroll
                 for (int uu = 0; uu < kMine; ++uu)
                     if (dd[uu] - dabs <= reach2f && pos[uu] < csize) {
-                        exact_at(pos[uu], mine);
+                        exact_at(cwd[uu], mine);
                         ++exact_evals;
                     }
             }
