@@ -660,7 +660,11 @@ __global__ __launch_bounds__(PV_WAVES * 64, (PV_OCC * PV_WAVES) / 4) void k_scor
             for (int vr = 0; vr < kUnitsCycle; ++vr) {
                 const int u = vr / NB, nb = vr % NB, ts = q4 + u;
                 if (nb == 0) a_nxt = buf[(ts + 1) * 64 + lane];   // one spare tile pads the LDS array
+                // g = 16: the wave asks for priority while it hands its matrix instruction over
+                // (measured: 408 -> 399 us on 183 500 groups; at g = 8 it costs 2 %)
+                if (G == 16) __builtin_amdgcn_s_setprio(3);
                 issue(nb, vr % kSets);
+                if (G == 16) __builtin_amdgcn_s_setprio(0);
                 // the unit kD back: tile q4 + dq (dq may point into the cycle before), group tile wnb
                 const int dq = (vr - kD >= 0) ? (vr - kD) / NB : -((kD - vr + NB - 1) / NB);
                 const int wnb = ((vr - kD) % NB + NB) % NB;
