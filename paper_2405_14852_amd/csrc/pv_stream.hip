@@ -109,17 +109,9 @@ __global__ __launch_bounds__(kBlock) void k_encode_targets_adam(const float *W, 
 #define PV_DEQ_AHEAD 2   // measured: 1 leaves two-codebook layouts bound by round trips, 4 and 8 lose to register pressure
 #endif
 constexpr int kDeqAhead = PV_DEQ_AHEAD;
-#ifndef PV_DEQ_NT
-#define PV_DEQ_NT 1
-#endif
-#ifndef PV_DEQ_BLOCK
-#define PV_DEQ_BLOCK 256
-#endif
-constexpr int kDeqBlock = PV_DEQ_BLOCK;
 // PARTS: 16-byte vectors per group when known at compile time (1, 2 or 4), else 0
-// MM: number of codebooks when it is 1 or 2 (the codes of a group come with one load), else 0
-template <int VEC, int PARTS, int MM>
-__global__ __launch_bounds__(kDeqBlock) void k_dequantize(const uint16_t *__restrict__ codes,
+template <int VEC, int PARTS>
+__global__ __launch_bounds__(kBlock) void k_dequantize(const uint16_t *__restrict__ codes,
                                                        const float *__restrict__ codebooks,
                                                        const float *__restrict__ scales,
                                                        float *__restrict__ W_out, int64_t total,
@@ -131,56 +123,36 @@ __global__ __launch_bounds__(kDeqBlock) void k_dequantize(const uint16_t *__rest
     if constexpr (VEC == 4) {
         const int parts = PARTS > 0 ? PARTS : g / 4;
         const pv_f4 *cb4 = reinterpret_cast<const pv_f4 *>(codebooks);
-        const int64_t first = (int64_t)blockIdx.x * (kDeqBlock * kDeqAhead) + threadIdx.x;
+        const int64_t first = (int64_t)blockIdx.x * (kBlock * kDeqAhead) + threadIdx.x;
         int64_t at[kDeqAhead];
         int q[kDeqAhead];
-        unsigned code[kDeqAhead], code1[kDeqAhead];
+        unsigned code[kDeqAhead];
         float s[kDeqAhead];
         const uint16_t *cp[kDeqAhead];
 #pragma unroll
         for (int u = 0; u < kDeqAhead; ++u) {
-            const int64_t idx = first + (int64_t)u * kDeqBlock;
+            const int64_t idx = first + (int64_t)u * kBlock;
             at[u] = idx < total ? idx : total - 1;
             const int n = (int)(at[u] / parts);
             q[u] = (int)(at[u] - (int64_t)n * parts);
             cp[u] = codes + (int64_t)n * M;
-            if constexpr (MM == 2) {       // both codes of the group in one aligned 4-byte load
-                const unsigned both = *reinterpret_cast<const unsigned *>(cp[u]);
-                code[u] = both & mask;
-                code1[u] = (both >> 16) & mask;
-            } else {
-                code[u] = cp[u][0] & mask;
-                code1[u] = 0u;
-            }
+            code[u] = cp[u][0] & mask;
             s[u] = scales[pv_row_of((unsigned)n, inv_gpr)];
         }
         pv_f4 acc[kDeqAhead];
 #pragma unroll
         for (int u = 0; u < kDeqAhead; ++u) acc[u] = cb4[((int64_t)code[u] * g) / 4 + q[u]];
-        if constexpr (MM == 2) {
+        for (int m = 1; m < M; ++m) {
             pv_f4 c[kDeqAhead];
 #pragma unroll
-            for (int u = 0; u < kDeqAhead; ++u) c[u] = cb4[((csize + code1[u]) * g) / 4 + q[u]];
+            for (int u = 0; u < kDeqAhead; ++u)
+                c[u] = cb4[((m * csize + (cp[u][m] & mask)) * g) / 4 + q[u]];
 #pragma unroll
             for (int u = 0; u < kDeqAhead; ++u) {
                 acc[u].x = acc[u].x + c[u].x;
                 acc[u].y = acc[u].y + c[u].y;
                 acc[u].z = acc[u].z + c[u].z;
                 acc[u].w = acc[u].w + c[u].w;
-            }
-        } else if constexpr (MM == 0) {
-            for (int m = 1; m < M; ++m) {
-                pv_f4 c[kDeqAhead];
-#pragma unroll
-                for (int u = 0; u < kDeqAhead; ++u)
-                    c[u] = cb4[((m * csize + (cp[u][m] & mask)) * g) / 4 + q[u]];
-#pragma unroll
-                for (int u = 0; u < kDeqAhead; ++u) {
-                    acc[u].x = acc[u].x + c[u].x;
-                    acc[u].y = acc[u].y + c[u].y;
-                    acc[u].z = acc[u].z + c[u].z;
-                    acc[u].w = acc[u].w + c[u].w;
-                }
             }
         }
 #pragma unroll
@@ -190,16 +162,11 @@ __global__ __launch_bounds__(kDeqBlock) void k_dequantize(const uint16_t *__rest
             out.y = s[u] * acc[u].y;
             out.z = s[u] * acc[u].z;
             out.w = s[u] * acc[u].w;
-            if (first + (int64_t)u * kDeqBlock < total) {
-#if PV_DEQ_NT
+            if (first + (int64_t)u * kBlock < total)
                 __builtin_nontemporal_store(out, &reinterpret_cast<pv_f4 *>(W_out)[at[u]]);
-#else
-                reinterpret_cast<pv_f4 *>(W_out)[at[u]] = out;
-#endif
-            }
         }
     } else {
-        const int64_t idx = (int64_t)blockIdx.x * kDeqBlock + threadIdx.x;
+        const int64_t idx = (int64_t)blockIdx.x * kBlock + threadIdx.x;
         if (idx >= total) return;
         const int n = (int)(idx / g);
         const int q = (int)(idx - (int64_t)n * g);
@@ -339,32 +306,24 @@ pv_status pv_launch_dequantize(pv_ctx *ctx, const pv_layout *l, const uint16_t *
     const int g = l->group_size;
     const int64_t N = pv_num_groups(l);
     const int gpr = (int)(l->in_features / g);
-    const int M = l->num_codebooks;
     if (g % 4 == 0) {
         int64_t total = N * (g / 4);
-        int64_t blocks = (total + kDeqBlock * kDeqAhead - 1) / (kDeqBlock * kDeqAhead);
-#define PV_DEQ(P_, M_)                                                                           \
-    hipLaunchKernelGGL((k_dequantize<4, P_, M_>), dim3((unsigned)blocks), dim3(kDeqBlock), 0,     \
-                       ctx->stream, codes, codebooks, scales, W_out, total, g, M, l->nbits, gpr,  \
-                       1.0 / (double)gpr)
-#define PV_DEQ_M(P_)                                                                             \
-    do {                                                                                         \
-        if (M == 1) PV_DEQ(P_, 1);                                                               \
-        else if (M == 2 && (reinterpret_cast<uintptr_t>(codes) & 3u) == 0) PV_DEQ(P_, 2);       \
-        else PV_DEQ(P_, 0);                                                                      \
-    } while (0)
-        if (g == 8) PV_DEQ_M(2);
-        else if (g == 16) PV_DEQ_M(4);
-        else if (g == 4) PV_DEQ_M(1);
-        else PV_DEQ_M(0);
-#undef PV_DEQ_M
+        int64_t blocks = (total + kBlock * kDeqAhead - 1) / (kBlock * kDeqAhead);
+#define PV_DEQ(P_)                                                                               \
+    hipLaunchKernelGGL((k_dequantize<4, P_>), dim3((unsigned)blocks), dim3(kBlock), 0, ctx->stream, \
+                       codes, codebooks, scales, W_out, total, g, l->num_codebooks, l->nbits,   \
+                       gpr, 1.0 / (double)gpr)
+        if (g == 8) PV_DEQ(2);
+        else if (g == 16) PV_DEQ(4);
+        else if (g == 4) PV_DEQ(1);
+        else PV_DEQ(0);
 #undef PV_DEQ
     } else {
         int64_t total = N * g;
-        int64_t blocks = (total + kDeqBlock - 1) / kDeqBlock;
-        hipLaunchKernelGGL((k_dequantize<1, 0, 0>), dim3((unsigned)blocks), dim3(kDeqBlock), 0, ctx->stream,
-                           codes, codebooks, scales, W_out, total, g, M, l->nbits, gpr,
-                           1.0 / (double)gpr);
+        int64_t blocks = (total + kBlock - 1) / kBlock;
+        hipLaunchKernelGGL((k_dequantize<1, 0>), dim3((unsigned)blocks), dim3(kBlock), 0, ctx->stream,
+                           codes, codebooks, scales, W_out, total, g, l->num_codebooks, l->nbits,
+                           gpr, 1.0 / (double)gpr);
     }
     PV_HIP(ctx, hipGetLastError());
     return PV_OK;
