@@ -178,6 +178,53 @@ __global__ __launch_bounds__(kBlock) void k_dequantize(const uint16_t *__restric
     }
 }
 
+// One codebook, g = 8, whole chunks of 256 groups per wave: a lane loads four codes with one
+// 8-byte load (a wave's codes are 512 contiguous bytes instead of eight rounds of 2-byte
+// loads), the codes reach the lanes that need them through wave shuffles, and the eight
+// codeword gathers of a lane are in flight together.  Lane pairs share a group as above, so
+// every store instruction still writes 1 KiB of contiguous weights.
+#ifndef PV_DW_ROUNDS
+#define PV_DW_ROUNDS 8
+#endif
+__global__ __launch_bounds__(kBlock) void k_dequantize_g8_wide(const uint16_t *__restrict__ codes,
+                                                              const float *__restrict__ codebooks,
+                                                              const float *__restrict__ scales,
+                                                              float *__restrict__ W_out, int nbits,
+                                                              double inv_gpr)
+{
+    constexpr int kRounds = PV_DW_ROUNDS;               // 64 vectors (32 groups) of the wave each
+    constexpr int kGroups = 32 * kRounds;               // groups per wave
+    static_assert(kRounds == 8, "four codes a lane");
+    const unsigned mask = (1u << nbits) - 1u;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int64_t g0 = ((int64_t)blockIdx.x * (kBlock / 64) + wave) * kGroups;   // first group of the wave
+    const uint2 four = *reinterpret_cast<const uint2 *>(codes + g0 + 4 * lane);
+    const pv_f4 *cb4 = reinterpret_cast<const pv_f4 *>(codebooks);
+    pv_f4 *out4 = reinterpret_cast<pv_f4 *>(W_out) + g0 * 2;
+    const int half = lane & 1, gl = lane >> 1;          // vector of the group, group of the round
+    pv_f4 acc[kRounds];
+    float sc[kRounds];
+#pragma unroll
+    for (int k = 0; k < kRounds; ++k) {
+        // group 32 k + gl of the wave: code number (gl & 3) of lane 8 k + gl / 4
+        const int src = 8 * k + (gl >> 2);
+        const unsigned lo = (unsigned)__shfl((int)four.x, src), hi = (unsigned)__shfl((int)four.y, src);
+        const unsigned word = (gl & 2) ? hi : lo;
+        const unsigned code = ((gl & 1) ? word >> 16 : word) & 0xFFFFu & mask;
+        acc[k] = cb4[(int64_t)code * 2 + half];
+        sc[k] = scales[pv_row_of((unsigned)(g0 + 32 * k + gl), inv_gpr)];
+    }
+#pragma unroll
+    for (int k = 0; k < kRounds; ++k) {
+        pv_f4 o;
+        o.x = sc[k] * acc[k].x;
+        o.y = sc[k] * acc[k].y;
+        o.z = sc[k] * acc[k].z;
+        o.w = sc[k] * acc[k].w;
+        __builtin_nontemporal_store(o, &out4[64 * k + lane]);
+    }
+}
+
 // The same for a list of groups only (the groups a V step re-encoded): every other weight of
 // W_out keeps its value.  One thread per weight vector of a listed group.
 template <int VEC>
@@ -313,7 +360,12 @@ pv_status pv_launch_dequantize(pv_ctx *ctx, const pv_layout *l, const uint16_t *
     hipLaunchKernelGGL((k_dequantize<4, P_>), dim3((unsigned)blocks), dim3(kBlock), 0, ctx->stream, \
                        codes, codebooks, scales, W_out, total, g, l->num_codebooks, l->nbits,   \
                        gpr, 1.0 / (double)gpr)
-        if (g == 8) PV_DEQ(2);
+        constexpr int kWideGroups = (kBlock / 64) * 32 * PV_DW_ROUNDS;      // groups per block of the wide kernel
+        if (g == 8 && l->num_codebooks == 1 && N % kWideGroups == 0 && N < (INT64_C(1) << 31) &&
+            (reinterpret_cast<uintptr_t>(codes) & 7u) == 0)
+            hipLaunchKernelGGL(k_dequantize_g8_wide, dim3((unsigned)(N / kWideGroups)), dim3(kBlock), 0,
+                               ctx->stream, codes, codebooks, scales, W_out, l->nbits, 1.0 / (double)gpr);
+        else if (g == 8) PV_DEQ(2);
         else if (g == 16) PV_DEQ(4);
         else if (g == 4) PV_DEQ(1);
         else PV_DEQ(0);

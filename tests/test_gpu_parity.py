@@ -143,6 +143,26 @@ def test_dequantize_bit_exact(g, M, B):
     assert np.array_equal(W.view(np.uint32), ref.view(np.uint32))
 
 
+@pytest.mark.parametrize("shape,B", [((128, 512), 16), ((256, 11008), 16), ((64, 1024), 7)])
+def test_dequantize_whole_chunks_of_one_codebook_g8(shape, B):
+    """One codebook, g = 8 and a group count that is a multiple of 1024: the kernel that loads
+    four codes a lane.  Rows of 1376 groups put row boundaries inside a wave's chunk."""
+    wl = workloads.make(shape[0], shape[1], 8, 1, B, seed=29)
+    assert wl.layout.num_groups % 1024 == 0
+    run = GpuRun(wl)
+    W = run.dequantize(wl.codes)
+    ref = oracle.dequantize(wl.codes, wl.codebooks, wl.scales)
+    assert np.array_equal(W.view(np.uint32), ref.view(np.uint32))
+    # the same codes from an array that is not 8-byte aligned: the general kernel, same weights
+    flat = wl.codes.reshape(-1)
+    big = torch.zeros(flat.size + 8, dtype=torch.int16, device=DEV)
+    big[1:1 + flat.size] = torch.from_numpy(flat.view(np.int16)).to(DEV)
+    Wd = torch.empty(shape, dtype=torch.float32, device=DEV)
+    run.ctx.pv_dequantize(run.lay, big[1:1 + flat.size].view(torch.uint16), run.cb, run.sc, Wd)
+    torch.cuda.synchronize()
+    assert np.array_equal(Wd.cpu().numpy().view(np.uint32), ref.view(np.uint32))
+
+
 def test_dequantize_two_codebooks_with_codes_on_an_odd_halfword():
     """The codes of a two-codebook group are read with one 4-byte load when the array allows
     it; an array that starts on an odd 2-byte boundary takes the general kernel: same weights."""
