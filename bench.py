@@ -363,7 +363,9 @@ def main() -> int:
         # each, the gradients written
         nbytes = 2.0 * 4.0 * params + 2.0 * 2.0 * M * (params / g) + 4.0 * (M * (1 << B) * g + L.out_features)
         a = nbytes / (kern["pstep"]["avg_ms"] * 1e-3) / 1e9
-        roofline = {"kernel": "pv_codebook_grads (sort + segmented sums)", "bound": "hbm", "achieved": a,
+        small = g % 4 == 0 and M * (1 << B) * g * 8 <= 64 * 1024 and (params // g) // (1 << B) >= 64
+        route = "fixed-point LDS tables" if small else "sort + segmented sums"
+        roofline = {"kernel": f"pv_codebook_grads ({route})", "bound": "hbm", "achieved": a,
                     "peak": PEAK_HBM, "unit": "GB/s", "frac": a / PEAK_HBM, "traffic": None}
     elif dominant == "score_mfma":
         a = flops_contraction / (kern[dominant]["avg_ms"] * 1e-3) / 1e12
