@@ -539,9 +539,19 @@ __global__ __launch_bounds__(kBlock, 2) void k_beam_2x8_f16(
         changed += __shfl_xor(changed, off);
         fast += __shfl_xor(fast, off);
     }
+    // one atomic per block and counter: atomics on one device address are served one after the
+    // other, and all the waves finish at about the same time
+    __shared__ unsigned s_changed, s_fast;
+    if (threadIdx.x == 0) s_changed = s_fast = 0u;
+    __syncthreads();
     if (lane == 0) {
-        if (changed && num_changed) atomicAdd(num_changed, (unsigned long long)changed);
-        if (fast && stat_fast) atomicAdd(stat_fast, (unsigned long long)fast);
+        if (changed) atomicAdd(&s_changed, (unsigned)changed);
+        if (fast) atomicAdd(&s_fast, (unsigned)fast);
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        if (s_changed && num_changed) atomicAdd(num_changed, (unsigned long long)s_changed);
+        if (s_fast && stat_fast) atomicAdd(stat_fast, (unsigned long long)s_fast);
     }
 }
 

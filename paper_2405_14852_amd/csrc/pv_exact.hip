@@ -101,6 +101,9 @@ __global__ __launch_bounds__(kBlock) void k_exact_scan(
     const int64_t count = d_count ? (int64_t)*d_count : max_count;
     const int csize = 1 << nbits;
     const int64_t items = (count + GPB - 1) / GPB;
+    // thread 0 counts what the block decided and changed; one atomic per block and counter at
+    // the end (atomics on one device address are served one after the other)
+    unsigned blk_changed = 0u, blk_done = 0u;
     for (int64_t item = blockIdx.x; item < items; item += gridDim.x) {
         const int64_t base = item * GPB;
         const int c_begin = 0, c_end = csize;
@@ -219,11 +222,15 @@ __global__ __launch_bounds__(kBlock) void k_exact_scan(
                 if (o_prev == mine[q].obj || pick == 0x7fffffff) pick = prev;
                 if (pick != prev) {
                     codes[n] = (uint16_t)pick;
-                    if (num_changed) atomicAdd(num_changed, 1ull);
+                    ++blk_changed;
                 }
-                if (stat_counter) atomicAdd(stat_counter, 1ull);
+                ++blk_done;
             }
         }
+    }
+    if (threadIdx.x == 0) {
+        if (blk_changed && num_changed) atomicAdd(num_changed, (unsigned long long)blk_changed);
+        if (blk_done && stat_counter) atomicAdd(stat_counter, (unsigned long long)blk_done);
     }
 }
 
@@ -274,6 +281,7 @@ __global__ __launch_bounds__(kBlock) void k_beam(
     __shared__ int s_idx[kBlock / 64];
     __shared__ int s_pick;
     const int csize = 1 << nbits;
+    unsigned blk_changed = 0u, blk_done = 0u;   // thread 0's counts, one atomic each at the end
     for (int64_t j = blockIdx.x; j < k; j += gridDim.x) {
         const int n = group_idx[j];
         if (n < 0 || n >= N) continue;  // uniform over the block
@@ -351,10 +359,14 @@ __global__ __launch_bounds__(kBlock) void k_beam(
         if (threadIdx.x == 0) {
             if (ncur > 0 && s_beam_obj[cur][0] < o_prev) {
                 for (int p = 0; p < M; ++p) codes[(int64_t)n * M + p] = s_beam[cur][0][p];
-                if (num_changed) atomicAdd(num_changed, 1ull);
+                ++blk_changed;
             }
-            if (stat_counter) atomicAdd(stat_counter, 1ull);
+            ++blk_done;
         }
+    }
+    if (threadIdx.x == 0) {
+        if (blk_changed && num_changed) atomicAdd(num_changed, (unsigned long long)blk_changed);
+        if (blk_done && stat_counter) atomicAdd(stat_counter, (unsigned long long)blk_done);
     }
 }
 
@@ -537,9 +549,19 @@ __global__ __launch_bounds__(kBlock) void k_beam_2x8(
         changed += beam2_group_exact<G>(lane, n, T, s, cb0, second, beam_width, codes) ? 1u : 0u;
         ++done;
     }
+    // one atomic per block and counter: atomics on one device address are served one after the
+    // other (about 10 ns each), and a kernel lasts until the last of them has been served
+    __shared__ unsigned s_changed, s_done;
+    if (threadIdx.x == 0) s_changed = s_done = 0u;
+    __syncthreads();
     if (lane == 0) {
-        if (changed && num_changed) atomicAdd(num_changed, (unsigned long long)changed);
-        if (done && stat_counter) atomicAdd(stat_counter, (unsigned long long)done);
+        if (changed) atomicAdd(&s_changed, changed);
+        if (done) atomicAdd(&s_done, done);
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        if (s_changed && num_changed) atomicAdd(num_changed, (unsigned long long)s_changed);
+        if (s_done && stat_counter) atomicAdd(stat_counter, (unsigned long long)s_done);
     }
 }
 
@@ -918,10 +940,18 @@ __global__ __launch_bounds__(kBeamBlock, 4) void k_beam_2x8_mfma(
         // the next pair overwrites the per-wave staging: every lane is done reading it
         __builtin_amdgcn_wave_barrier();
     }
-    // lanes 0 and 32 hold the counters of their halves
+    // lanes 0 and 32 hold the counters of their halves; one atomic per block and counter
+    __shared__ unsigned s_changed, s_fast;
+    if (threadIdx.x == 0) s_changed = s_fast = 0u;
+    __syncthreads();
     if (hl == 0) {
-        if (changed && num_changed) atomicAdd(num_changed, (unsigned long long)changed);
-        if (fast && stat_fast) atomicAdd(stat_fast, (unsigned long long)fast);
+        if (changed) atomicAdd(&s_changed, (unsigned)changed);
+        if (fast) atomicAdd(&s_fast, (unsigned)fast);
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        if (s_changed && num_changed) atomicAdd(num_changed, (unsigned long long)s_changed);
+        if (s_fast && stat_fast) atomicAdd(stat_fast, (unsigned long long)s_fast);
     }
 }
 

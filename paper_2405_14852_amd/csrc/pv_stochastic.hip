@@ -92,6 +92,7 @@ __global__ __launch_bounds__(kBlock) void k_round_two_nearest(
     const int csize = 1 << nbits;
     const int64_t items = (count + GPB - 1) / GPB;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    unsigned blk_changed = 0u;    // per thread; added up once at the end (one atomic per block)
     for (int64_t item = blockIdx.x; item < items; item += gridDim.x) {
         const int64_t base = item * GPB;
         __syncthreads();
@@ -195,9 +196,15 @@ __global__ __launch_bounds__(kBlock) void k_round_two_nearest(
                 pick = pv_round_pick(b.o1, b.i1, b.o2, b.i2, power, seed, (unsigned long long)n);
             if (pick != prev) {
                 codes[n] = (uint16_t)pick;
-                if (num_changed) atomicAdd(num_changed, 1ull);
+                ++blk_changed;
             }
         }
+    }
+    // threads 0 .. GPB - 1 counted; they sit in the first wave
+    if (threadIdx.x < 64) {
+        for (int off = 32; off > 0; off >>= 1) blk_changed += __shfl_down(blk_changed, off);
+        if (threadIdx.x == 0 && blk_changed && num_changed)
+            atomicAdd(num_changed, (unsigned long long)blk_changed);
     }
 }
 
