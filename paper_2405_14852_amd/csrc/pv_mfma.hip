@@ -316,6 +316,10 @@ __global__ __launch_bounds__(kScanBlock) void k_cb_scan(const unsigned *__restri
 // and x_stage[j] = { the g target values, the row scale, the current code, the group id } is
 // what the re-rank kernel needs of the group, in one place (its loads then depend on nothing
 // but the list position).
+#ifndef PV_CB_PER
+#define PV_CB_PER 4
+#endif
+constexpr int kCbPer = PV_CB_PER;   // codeword positions a thread of the codebook part
 template <int G>
 __global__ __launch_bounds__(kBlock) void k_prep(const float *__restrict__ cb, int csize, int cpad,
                                                  int cb_blocks, unsigned *__restrict__ meta,
@@ -341,13 +345,24 @@ __global__ __launch_bounds__(kBlock) void k_prep(const float *__restrict__ cb, i
         for (int e = 0; e < 8; ++e) chunk[u][e] = (_Float16)0.0f;
 
     if ((int)blockIdx.x < cb_blocks) {
-        const int c = blockIdx.x * kBlock + threadIdx.x;
         float d2 = 0.0f;
+        // kCbPer codeword positions a thread: a quarter of the blocks, and of the atomics on the
+        // one address that takes the largest rounding error
+#pragma unroll 1
+        for (int rep = 0; rep < kCbPer; ++rep) {
+        const int c = (blockIdx.x * kCbPer + rep) * kBlock + threadIdx.x;
+        if (rep > 0) {
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) chunk[u][e] = (_Float16)0.0f;
+        }
         if (c < cpad) {
             int pos = c;
             if (c < csize) {
-                float hf[G], n2;
-                round_codeword<G>(cb + (int64_t)c * G, P, ok, hf, n2, d2);
+                float hf[G], n2, d2c;
+                round_codeword<G>(cb + (int64_t)c * G, P, ok, hf, n2, d2c);
+                d2 = fmaxf(d2, d2c);
 #pragma unroll
                 for (int i = 0; i < G; ++i) chunk[i >> 3][i & 7] = (_Float16)(2.0f * hf[i]);
                 if (G == 8) {
@@ -379,6 +394,7 @@ __global__ __launch_bounds__(kBlock) void k_prep(const float *__restrict__ cb, i
             const int row = 8 * (q >> 2) + 4 * hw + (q & 3);
 #pragma unroll
             for (int u = 0; u < 2; ++u) A[((int64_t)tile * 2 + u) * 32 + row] = chunk[u];
+        }
         }
         __shared__ float s_d[kBlock / 64];
         for (int off = 32; off > 0; off >>= 1) d2 = fmaxf(d2, __shfl_down(d2, off));
@@ -1772,8 +1788,10 @@ pv_status pv_launch_mfma_search(pv_ctx *ctx, const pv_layout *l, const float *T,
     {
         pv_timed t(ctx, PV_K_PREP);
         int blocks = (csize + kBlock - 1) / kBlock;
-        if (blocks > 128) blocks = 128;
-        const int cb_blocks = (p.cpad + kBlock - 1) / kBlock;
+        // every block ends with three atomics, each on one address: 64 blocks measured best (32
+        // are as good, 128 cost 1.6 us more, 256 another 4)
+        if (blocks > 64) blocks = 64;
+        const int cb_blocks = (p.cpad + kBlock * kCbPer - 1) / (kBlock * kCbPer);
         const int x_blocks = (p.k_pad + kBlock - 1) / kBlock;
         if (g == 8) {
             hipLaunchKernelGGL(k_cb_stats<8>, dim3(blocks), dim3(kBlock), 0, sm, codebooks, csize,

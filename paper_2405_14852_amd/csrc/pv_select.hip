@@ -41,9 +41,10 @@ constexpr int kItems = 8;                      // groups per thread in the compa
 constexpr int kChunk = kBlock * kItems;        // groups per chunk there
 static_assert(kChunk < 65536, "the compaction packs two per-chunk counts into 32 bits");
 #ifndef PV_SEL_BLOCKS
-#define PV_SEL_BLOCKS 1024
+#define PV_SEL_BLOCKS 512
 #endif
-constexpr int kMaxBlocks = PV_SEL_BLOCKS;      // persistent grid of the streaming kernels
+constexpr int kMaxBlocks = PV_SEL_BLOCKS;      // persistent grid of the streaming kernels: two blocks per compute unit (1024 cost 1 us on 2 M groups and 4 to 6 us on 3.7 to 5.6 M, 256 lose a sixth of the bandwidth)
+constexpr int kCompactBlocks = 1024;           // grid of the two compaction kernels
 
 __device__ __forceinline__ int digit_of(unsigned key, int pass)
 {
@@ -862,7 +863,7 @@ static pv_status select_run(pv_ctx *ctx, const pv_layout *l, const float *T, con
         pv_timed t(ctx, PV_K_SELECT);
         int64_t hb = ((int64_t)(N >> 2) + kHistBlock - 1) / kHistBlock;
         const unsigned hblocks = (unsigned)(hb < 512 ? (hb < 1 ? 1 : hb) : 512);
-        const unsigned cblocks = (unsigned)(nchunks < kMaxBlocks ? nchunks : kMaxBlocks);
+        const unsigned cblocks = (unsigned)(nchunks < kCompactBlocks ? nchunks : kCompactBlocks);
         hipLaunchKernelGGL(k_hist_next, dim3(hblocks), dim3(kHistBlock), 0, ctx->stream, scores, hist,
                            hist + kHist1, state, N, (unsigned)k, 1);
         hipLaunchKernelGGL(k_hist_next, dim3(hblocks), dim3(kHistBlock), 0, ctx->stream, scores, hist,
