@@ -24,7 +24,7 @@
 #endif
 
 #ifndef PV_LATE_VOTE_ROUNDS
-#define PV_LATE_VOTE_ROUNDS 0   // the same for the later digits: measured slower than plain LDS atomics, also on a one-bin distribution
+#define PV_LATE_VOTE_ROUNDS 0   // the same for the later digits: plain LDS atomics are faster on spread-out scores and on the narrow ones of an Adam step; only when EVERY score is equal would the merge win (5.6 M groups: 139 against 157 us for sweep + selection)
 #endif
 
 namespace {
