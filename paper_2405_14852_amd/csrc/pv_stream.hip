@@ -183,16 +183,14 @@ __global__ __launch_bounds__(kBlock) void k_dequantize(const uint16_t *__restric
 // loads), the codes reach the lanes that need them through wave shuffles, and the eight
 // codeword gathers of a lane are in flight together.  Lane pairs share a group as above, so
 // every store instruction still writes 1 KiB of contiguous weights.
-#ifndef PV_DW_ROUNDS
-#define PV_DW_ROUNDS 8
-#endif
+constexpr int kWideRounds = 8;   // rounds of 64 vectors a wave: four codes a lane
 __global__ __launch_bounds__(kBlock) void k_dequantize_g8_wide(const uint16_t *__restrict__ codes,
                                                               const float *__restrict__ codebooks,
                                                               const float *__restrict__ scales,
                                                               float *__restrict__ W_out, int nbits,
                                                               double inv_gpr)
 {
-    constexpr int kRounds = PV_DW_ROUNDS;               // 64 vectors (32 groups) of the wave each
+    constexpr int kRounds = kWideRounds;                // 64 vectors (32 groups) of the wave each
     constexpr int kGroups = 32 * kRounds;               // groups per wave
     static_assert(kRounds == 8, "four codes a lane");
     const unsigned mask = (1u << nbits) - 1u;
@@ -360,7 +358,7 @@ pv_status pv_launch_dequantize(pv_ctx *ctx, const pv_layout *l, const uint16_t *
     hipLaunchKernelGGL((k_dequantize<4, P_>), dim3((unsigned)blocks), dim3(kBlock), 0, ctx->stream, \
                        codes, codebooks, scales, W_out, total, g, l->num_codebooks, l->nbits,   \
                        gpr, 1.0 / (double)gpr)
-        constexpr int kWideGroups = (kBlock / 64) * 32 * PV_DW_ROUNDS;      // groups per block of the wide kernel
+        constexpr int kWideGroups = (kBlock / 64) * 32 * kWideRounds;      // groups per block of the wide kernel
         if (g == 8 && l->num_codebooks == 1 && N % kWideGroups == 0 && N < (INT64_C(1) << 31) &&
             (reinterpret_cast<uintptr_t>(codes) & 7u) == 0)
             hipLaunchKernelGGL(k_dequantize_g8_wide, dim3((unsigned)(N / kWideGroups)), dim3(kBlock), 0,
