@@ -184,3 +184,82 @@ def test_c2_full_trust_ratio():
         assert st[0] == pytest.approx(info["change_sq"], rel=1e-12)
         assert st[1] == pytest.approx(info["norm_sq"], rel=1e-12)
         assert np.array_equal(host_u16(codes), want)
+
+
+def _grads_on_gpu(wl):
+    run = GpuRun(wl)
+    gc = torch.full(tuple(wl.codebooks.shape), 7.0, dtype=torch.float32, device="cuda:0")
+    gs = torch.full((wl.layout.out_features,), 7.0, dtype=torch.float32, device="cuda:0")
+    run.ctx.pv_codebook_grads(run.lay, run.G, run.codes, run.cb, run.sc, gc, gs)
+    torch.cuda.synchronize()
+    first = (gc.cpu().numpy(), gs.cpu().numpy())
+    gc.fill_(-3.0)
+    gs.fill_(-3.0)
+    run.ctx.pv_codebook_grads(run.lay, run.G, run.codes, run.cb, run.sc, gc, gs)
+    torch.cuda.synchronize()
+    # a second call on the same context returns the same bits
+    assert np.array_equal(first[0].view(np.uint32), gc.cpu().numpy().view(np.uint32))
+    assert np.array_equal(first[1].view(np.uint32), gs.cpu().numpy().view(np.uint32))
+    return first
+
+
+def _close(got, want, mag):
+    tol = 2 * np.spacing(np.abs(want).astype(np.float32)) + 1e-12 * mag
+    return np.abs(got.astype(np.float64) - want.astype(np.float64)) <= tol
+
+
+@pytest.mark.parametrize("name", ["c2_4096x4096_1x16", "c3_11008x4096_2x8"])
+def test_pstep_gradients_full_size(name):
+    """Codebook and scale gradients of the P step at the benchmark sizes, every entry against
+    the oracle's sequential double sums: the sorted route (c2: segments of about 32 groups, the
+    same sum in the same order, so nearly every entry has the same bits) and the fixed-point
+    tables (c3: 22 000 terms per codeword)."""
+    wl = workloads.make_config(name, seed=0)
+    gc, gs = _grads_on_gpu(wl)
+    gc_ref, gs_ref = oracle.codebook_grads(wl.G, wl.codes, wl.codebooks, wl.scales)
+    mag = float(np.abs(wl.G).max() * np.abs(wl.scales).max()) * wl.layout.num_groups
+    assert _close(gc, gc_ref, mag * 1e-3).all()
+    same = (gc.view(np.uint32) == gc_ref.view(np.uint32)).mean()
+    assert same > 0.99, same
+    q = oracle.dequantize(wl.codes, wl.codebooks, np.ones_like(wl.scales))
+    assert _close(gs, gs_ref, np.abs(wl.G * q).sum(axis=1)).all()
+    # every weight of a group pulls on its codeword with the row's scale: the gradients of
+    # one codebook add up to the sum of s_o * G over the matrix, element by element
+    g = wl.layout.group_size
+    total = (wl.G.astype(np.float64) * wl.scales.astype(np.float64)[:, None]).reshape(-1, g).sum(axis=0)
+    for m in range(wl.layout.num_codebooks):
+        assert np.allclose(gc[m].astype(np.float64).sum(axis=0), total, rtol=0, atol=1e-6 * np.abs(total).max() + 1e-9)
+
+
+@pytest.mark.parametrize("name,sample", [("c2_4096x4096_1x16", 4096), ("c5a_14336x4096_1x16g16", 1024)])
+def test_stochastic_rounding_full_size_sampled(name, sample):
+    """pv_reencode_groups_stochastic at the benchmark sizes (power 5, as App. K's temperature
+    gives): all selected groups are rounded on the GPU, a seeded sample of them by the oracle."""
+    from gpu_util import dev_i32, dev_u16, lay_of
+    wl = workloads.make_config(name, seed=0)
+    M = wl.layout.num_codebooks
+    run = GpuRun(wl)
+    T = run.targets()
+    T_ref = oracle.encode_targets(wl.W, wl.G, wl.alpha)
+    idx = run.select(T, wl.k)
+    assert np.array_equal(idx, oracle.select_topk_groups(T_ref, wl.W, wl.layout.group_size, wl.k))
+    codes = dev_u16(wl.codes)
+    nch = torch.full((1,), -1, dtype=torch.int64, device="cuda:0")
+    seed = 20240528
+    run.ctx.pv_reencode_groups_stochastic(lay_of(wl), T, run.cb, run.sc, dev_i32(idx), len(idx), 5, seed,
+                                          codes, nch)
+    torch.cuda.synchronize()
+    got = host_u16(codes).reshape(-1)
+    rest = np.ones(wl.layout.num_groups, bool)
+    rest[idx] = False
+    assert np.array_equal(got[rest], wl.codes.reshape(-1)[rest])
+    assert int(nch.item()) == int((got[idx] != wl.codes.reshape(-1)[idx]).sum())
+    sub = np.sort(np.random.default_rng(321).choice(idx, size=sample, replace=False))
+    want, info = oracle.reencode_stochastic(T_ref, wl.codebooks, wl.scales, sub, wl.codes, power=5, seed=seed)
+    differ = np.nonzero(got[sub] != want.reshape(-1)[sub])[0]
+    assert info["near_tie"][differ].all(), (len(differ), differ[:5])
+    # the second nearest is taken in a noticeable share of the groups, never in most
+    second = (want.reshape(-1)[sub] == info["nearest_two"][:, 1]).mean()
+    assert 0.01 < second < 0.5, second
+    stats = run.ctx.pv_reencode_stats()
+    assert stats["filtered"] + stats["fallback"] == wl.k
