@@ -263,3 +263,61 @@ def test_stochastic_rounding_full_size_sampled(name, sample):
     assert 0.01 < second < 0.5, second
     stats = run.ctx.pv_reencode_stats()
     assert stats["filtered"] + stats["fallback"] == wl.k
+
+
+def test_c2_full_adam_direction_then_search():
+    """Sec. 3.4's Adam direction at the benchmark size: the fused sweep (moments, targets, scores,
+    selection) bit for bit against the oracle at step 3 with moments in flight, then the search on
+    the selected groups of those targets."""
+    from gpu_util import dev_i32
+    wl = workloads.make_config("c2_4096x4096_1x16", seed=0)
+    g = wl.layout.group_size
+    shape = wl.W.shape
+    rng = np.random.default_rng(91)
+    m = (rng.standard_normal(shape) * 1e-4).astype(np.float32)
+    v = (rng.random(shape) * 1e-8).astype(np.float32)
+    run = GpuRun(wl)
+    md, vd = dev_f32(m), dev_f32(v)
+    T = torch.empty_like(run.W)
+    idx = torch.empty(wl.k, dtype=torch.int32, device="cuda:0")
+    run.ctx.pv_encode_targets_adam_select(run.lay, run.W, run.G, md, vd, 3, 3e-3, 0.9, 0.95, 1e-8, T, wl.k, idx)
+    torch.cuda.synchronize()
+    T_ref, m_ref, v_ref = oracle.encode_targets_adam(wl.W, wl.G, m, v, 3, 3e-3, 0.9, 0.95, 1e-8)
+    assert np.array_equal(T.cpu().numpy().view(np.uint32), T_ref.view(np.uint32))
+    assert np.array_equal(md.cpu().numpy().view(np.uint32), m_ref.view(np.uint32))
+    assert np.array_equal(vd.cpu().numpy().view(np.uint32), v_ref.view(np.uint32))
+    idx_np = idx.cpu().numpy()
+    assert np.array_equal(idx_np, oracle.select_topk_groups(T_ref, wl.W, g, wl.k))
+    got, _ = run.reencode(T, idx_np)
+    sub = np.sort(np.random.default_rng(92).choice(idx_np, size=4096, replace=False))
+    want, info = oracle.reencode_groups(T_ref, wl.codebooks, wl.scales, sub, wl.codes)
+    check_codes_on(wl, T_ref, sub, got, want, info)
+
+
+def test_c2_full_straight_through_step():
+    """App. E at the benchmark size: the gradient step goes to the buffer (targets written over
+    W), the subspace is chosen from buffer against the dequantised codes, the codes follow the
+    buffer.  Buffer and subspace bit for bit, codes by the per-group rule."""
+    from gpu_util import dev_u16, lay_of
+    wl = workloads.make_config("c2_4096x4096_1x16", seed=0)
+    lay = lay_of(wl)
+    run = GpuRun(wl)
+    codes = dev_u16(wl.codes)
+    buf = torch.empty_like(run.W)
+    run.ctx.pv_dequantize(lay, codes, run.cb, run.sc, buf)
+    Wq = buf.clone()
+    idx = torch.empty(wl.k, dtype=torch.int32, device="cuda:0")
+    nch = torch.zeros(1, dtype=torch.int64, device="cuda:0")
+    alpha = 40.0                                          # updates of a fraction of the codeword spacing
+    run.ctx.pv_encode_targets(lay, buf, run.G, alpha, buf)
+    run.ctx.pv_select_topk_groups(lay, buf, Wq, wl.k, idx)
+    run.ctx.pv_reencode_groups(lay, buf, run.cb, run.sc, idx, wl.k, 1, codes, nch)
+    torch.cuda.synchronize()
+    buf0 = oracle.dequantize(wl.codes, wl.codebooks, wl.scales)
+    buf_ref, want, info = oracle.ste_step(buf0, wl.G, alpha, wl.codebooks, wl.scales, wl.codes.copy(), k=wl.k)
+    assert np.array_equal(buf.cpu().numpy().view(np.uint32), buf_ref.view(np.uint32))
+    assert np.array_equal(idx.cpu().numpy(), info["group_idx"])
+    got = host_u16(codes)
+    ndiff = check_codes_on(wl, buf_ref, info["group_idx"], got, want, info)
+    assert abs(int(nch.item()) - info["num_changed"]) <= ndiff
+    assert info["num_changed"] > 0
