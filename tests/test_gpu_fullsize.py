@@ -208,7 +208,7 @@ def _close(got, want, mag):
     return np.abs(got.astype(np.float64) - want.astype(np.float64)) <= tol
 
 
-@pytest.mark.parametrize("name", ["c2_4096x4096_1x16", "c3_11008x4096_2x8"])
+@pytest.mark.parametrize("name", ["c2_4096x4096_1x16", "c3_11008x4096_2x8", "c5a_14336x4096_1x16g16"])
 def test_pstep_gradients_full_size(name):
     """Codebook and scale gradients of the P step at the benchmark sizes, every entry against
     the oracle's sequential double sums: the sorted route (c2: segments of about 32 groups, the
