@@ -32,6 +32,12 @@
  *     first call of a shape, or a larger k), it waits for the stream, frees the old
  *     block and allocates a larger one before it enqueues anything; calls of a shape
  *     the context has seen before never wait, allocate or free.
+ *   - Graph capture: once a call of the same shape has sized the scratch, the calls of
+ *     a step (dequantize, targets, selection, re-encode and their variants) only launch
+ *     kernels on the context's stream, so a caller may capture them into a HIP graph and
+ *     replay it; the inputs may change in place between replays (a codebook rewritten by
+ *     the P step).  pv_reencode_stats, pv_timing_read and pv_destroy synchronise and do
+ *     not belong into a capture.
  *   - Errors are reported by the return code only; on an error nothing has been
  *     enqueued or written.  pv_last_error gives a short text for the last error
  *     of a context.

@@ -1784,6 +1784,17 @@ pv_status pv_launch_mfma_search(pv_ctx *ctx, const pv_layout *l, const float *T,
     unsigned *cb_meta_next = cb_meta + (ctx->meta_phase ? 0 : 8);
     cb_meta += ctx->meta_phase ? 8 : 0;
     ctx->meta_phase ^= 1;
+    {
+        // Under graph capture the slots do not alternate from replay to replay (the graph keeps
+        // the pointers of the captured call), so the slot this call accumulates into still holds
+        // what the last replay left: clear it first (a fill kernel, not a memset node).
+        hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
+        PV_HIP(ctx, hipStreamIsCapturing(sm, &capturing));
+        if (capturing != hipStreamCaptureStatusNone) {
+            pv_status fs = pv_launch_fill_f32(ctx, reinterpret_cast<float *>(cb_meta), 8, 0.0f);
+            if (fs != PV_OK) return fs;
+        }
+    }
     ctx->rr_blocks_last = rr_blocks;
     {
         pv_timed t(ctx, PV_K_PREP);
