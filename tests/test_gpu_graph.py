@@ -170,3 +170,101 @@ def test_captured_step_forgets_the_statistics_of_the_last_replay():
         differ = np.nonzero(g2[idx_ref] != want.reshape(-1)[idx_ref])[0]
         assert info["near_tie"][differ].all(), (len(differ), differ[:5])
         ctx.close()
+
+
+def _replays_equal_eager(side, run_once, outputs, scramble):
+    """Captures run_once on `side`, replays it three times (outputs scrambled before each, an eager
+    call in between) and compares the outputs with those of an eager call."""
+    run_once()
+    run_once()
+    side.synchronize()
+    want = [o.clone() for o in outputs]
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        run_once()
+    side.synchronize()
+    for rep in range(3):
+        scramble()
+        if rep == 1:
+            run_once()
+            scramble()
+        side.synchronize()
+        graph.replay()
+        side.synchronize()
+        for o, w in zip(outputs, want):
+            assert torch.equal(o.view(torch.uint8), w.view(torch.uint8)), rep
+
+
+def test_captured_trust_ratio_step_replays_like_the_eager_one():
+    wl = workloads.make(128, 1024, 8, 1, 12, tau=0.1, sigma_g=4e-3, seed=741)
+    lay = lay_of(wl)
+    k = wl.k
+    side = torch.cuda.Stream(device=DEV)
+    with torch.cuda.stream(side):
+        ctx = PVContext(0, stream=side)
+        G = dev_f32(wl.G)
+        cb, sc = dev_f32(wl.codebooks), dev_f32(wl.scales)
+        codes0 = torch.from_numpy(wl.codes.view(np.int16)).to(DEV)
+        codes = codes0.clone()
+        Wq = torch.empty(wl.W.shape, dtype=torch.float32, device=DEV)
+        T = torch.empty_like(Wq)
+        rank = torch.empty(k, dtype=torch.int32, device=DEV)
+        napp = torch.zeros(1, dtype=torch.int64, device=DEV)
+        sums = torch.zeros(2, dtype=torch.float64, device=DEV)
+
+        def run_once():
+            codes.copy_(codes0)
+            cu = codes.view(torch.uint16)
+            ctx.pv_dequantize(lay, cu, cb, sc, Wq)
+            ctx.pv_encode_targets(lay, Wq, G, 40.0, T)
+            ctx.pv_reencode_trust_ratio(lay, T, Wq, cb, sc, k, max(1, k // 10), 0.01, 1, cu, rank, napp, sums)
+
+        def scramble():
+            codes.fill_(0)
+            rank.zero_()
+            napp.fill_(-3)
+            sums.fill_(-1.0)
+
+        _replays_equal_eager(side, run_once, [codes, rank, napp, sums], scramble)
+        assert int(napp.item()) > 0
+        ctx.close()
+
+
+@pytest.mark.parametrize("g,M,B,shape", [(8, 1, 16, (128, 1024)), (8, 2, 8, (256, 2048)), (16, 1, 10, (64, 1024))])
+def test_captured_p_step_and_stochastic_rounding_replay_like_the_eager_ones(g, M, B, shape):
+    wl = workloads.make(shape[0], shape[1], g, M, B, tau=0.1, sigma_g=5e-3, seed=751 + B)
+    lay = lay_of(wl)
+    k = wl.k
+    side = torch.cuda.Stream(device=DEV)
+    with torch.cuda.stream(side):
+        ctx = PVContext(0, stream=side)
+        W, G = dev_f32(wl.W), dev_f32(wl.G)
+        cb, sc = dev_f32(wl.codebooks), dev_f32(wl.scales)
+        codes0 = torch.from_numpy(wl.codes.view(np.int16)).to(DEV)
+        codes = codes0.clone()
+        gcb, gsc = torch.empty_like(cb), torch.empty_like(sc)
+
+        def p_step():
+            ctx.pv_codebook_grads(lay, G, codes0.view(torch.uint16), cb, sc, gcb, gsc)
+
+        def scramble_p():
+            gcb.fill_(9.0)
+            gsc.fill_(9.0)
+
+        _replays_equal_eager(side, p_step, [gcb, gsc], scramble_p)
+        if M == 1:
+            T = torch.empty_like(W)
+            idx = torch.empty(k, dtype=torch.int32, device=DEV)
+            nch = torch.zeros(1, dtype=torch.int64, device=DEV)
+
+            def rounding():
+                codes.copy_(codes0)
+                ctx.pv_encode_targets_select(lay, W, G, wl.alpha, T, k, idx)
+                ctx.pv_reencode_groups_stochastic(lay, T, cb, sc, idx, k, 5, 99, codes.view(torch.uint16), nch)
+
+            def scramble_r():
+                codes.fill_(0)
+                nch.fill_(-1)
+
+            _replays_equal_eager(side, rounding, [codes, nch], scramble_r)
+        ctx.close()
