@@ -315,7 +315,7 @@ __global__ __launch_bounds__(kSmallBlock) void k_pg_small(
     __syncthreads();
     long long *out = partial + (int64_t)blockIdx.x * entries;
     for (int e = threadIdx.x; e < entries; e += kSmallBlock) {
-        const unsigned sw = (((unsigned)e / (unsigned)g) >> 2) & swm;
+        const unsigned sw = ((((unsigned)e / (unsigned)g) & mask) >> 2) & swm;   // the code within its codebook, as on the way in
         out[e] = (long long)tab[(unsigned)e ^ sw];
     }
 }

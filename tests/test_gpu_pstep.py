@@ -152,7 +152,11 @@ def test_codebook_grads_small_codebook_route_is_close_to_the_exact_sum_and_flags
 
 @pytest.mark.parametrize("g,M,B,shape", [(16, 1, 6, (128, 2048)), (16, 2, 8, (512, 4096)), (12, 1, 5, (96, 1536)),
                                          (8, 3, 5, (128, 1024)), (4, 2, 4, (64, 512)), (8, 1, 6, (100, 1000)),
-                                         (8, 2, 8, (1031, 1160))])
+                                         (8, 2, 8, (1031, 1160)),
+                                         # codebooks of fewer than 4 g codewords with several codebooks:
+                                         # the row permutation must use the code within its codebook
+                                         (8, 3, 4, (40, 840)), (16, 2, 4, (54, 1120)), (16, 3, 5, (64, 2048)),
+                                         (8, 2, 3, (64, 512)), (16, 2, 2, (32, 512)), (8, 4, 1, (32, 256))])
 def test_codebook_grads_small_codebook_route_shapes(g, M, B, shape):
     """The fixed-point route over the group sizes it has a kernel for (4, 8, 16 and the general
     one), more than two codebooks, and block ranges that start in the middle of a row."""
