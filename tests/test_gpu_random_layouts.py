@@ -15,6 +15,7 @@ import torch
 import oracle
 import workloads
 from gpu_util import DEV, GpuRun, check_codes_on, dev_f32, dev_i32, dev_u16, host_u16
+from paper_2405_14852_amd import Layout, PVContext
 
 pytestmark = pytest.mark.gpu
 
@@ -144,3 +145,44 @@ def test_random_layouts_match_the_oracle(seed):
             differ = np.nonzero(host_u16(codes).reshape(-1)[idx_ref] != w2.reshape(-1)[idx_ref])[0]
             assert i2["near_tie"][differ].all(), tag
         run.ctx.close()
+
+
+@pytest.mark.parametrize("seed", [201, 202])
+def test_random_scalar_grids_match_the_oracle(seed):
+    """The scalar uniform-grid representation (App. K): dequantise, targets and selection at group
+    size 1, round to the nearest grid value; every array bit for bit."""
+    rng = np.random.default_rng(seed)
+    for case in range(CASES_PER_SEED):
+        block = int(rng.choice([1, 3, 6, 8, 16, 32, 64, 128]))
+        blocks = int(rng.integers(1, 40))
+        o, i = int(rng.integers(1, 300)), block * blocks
+        nbits = int(rng.integers(1, 9))
+        n = o * i
+        k = max(1, int(float(rng.choice([0.01, 0.2, 1.0])) * n))
+        sw = float(10 ** rng.uniform(-3, 0))
+        W0, G, codes, sc, zp = workloads.make_scalar(o, i, block, nbits, seed=int(rng.integers(1 << 30)), sigma_w=sw,
+                                                     sigma_g=sw * float(10 ** rng.uniform(-2, 0)))
+        if rng.random() < 0.3:
+            sc = (sc * rng.choice([-1.0, 1.0], size=sc.shape)).astype(np.float32)
+        tag = (seed, case, o, i, block, nbits, k)
+        ctx = PVContext(0)
+        lay1 = Layout(o, i, 1, 1, 8)
+        cd = torch.from_numpy(codes).to(DEV)
+        sd, zd = dev_f32(sc), dev_f32(zp)
+        Wd = torch.empty(o, i, dtype=torch.float32, device=DEV)
+        ctx.pv_dequantize_scalar(o, i, block, nbits, cd, sd, zd, Wd)
+        W_ref = oracle.dequantize_scalar(codes, sc, zp, block, nbits)
+        assert np.array_equal(Wd.cpu().numpy().view(np.uint32), W_ref.view(np.uint32)), tag
+        Td = torch.empty_like(Wd)
+        idx = torch.empty(k, dtype=torch.int32, device=DEV)
+        ctx.pv_encode_targets_select(lay1, Wd, dev_f32(G), 3.0, Td, k, idx)
+        T_ref = oracle.encode_targets(W_ref, G, 3.0)
+        idx_ref = oracle.select_topk_groups(T_ref, W_ref, 1, k)
+        assert np.array_equal(idx.cpu().numpy(), idx_ref), tag
+        nch = torch.zeros(1, dtype=torch.int64, device=DEV)
+        ctx.pv_reencode_scalar(o, i, block, nbits, Td, sd, zd, idx, k, cd, nch)
+        torch.cuda.synchronize()
+        want, changed = oracle.reencode_scalar(T_ref, sc, zp, idx_ref, codes, block, nbits)
+        assert np.array_equal(cd.cpu().numpy(), want), tag
+        assert int(nch.item()) == changed, tag
+        ctx.close()
