@@ -186,3 +186,52 @@ def test_random_scalar_grids_match_the_oracle(seed):
         assert np.array_equal(cd.cpu().numpy(), want), tag
         assert int(nch.item()) == changed, tag
         ctx.close()
+
+
+@pytest.mark.parametrize("seed", [301, 302])
+def test_random_large_layouts_match_the_oracle(seed):
+    """Large odd shapes with thousands of selected groups: the matrix-core scoring and the beam
+    filter over many tiles and ragged tails, in both regimes of W (the configuration's dense
+    Gaussian, and the dequantised current codes as in a real step)."""
+    rng = np.random.default_rng(seed)
+    for case in range(6):
+        kind = int(rng.integers(0, 4))
+        if kind == 0:
+            g, M, B, beam = 8, 1, int(rng.integers(11, 17)), 1
+        elif kind == 1:
+            g, M, B, beam = 16, 1, int(rng.integers(11, 17)), 1
+        elif kind == 2:
+            g, M, B, beam = 8, 2, 8, int(rng.choice([4, 8, 16]))
+        else:
+            g, M, B, beam = int(rng.choice([4, 8, 16])), int(rng.choice([2, 3])), int(rng.choice([6, 8])), 8
+        out, gpr = int(rng.integers(500, 3000)), int(rng.integers(100, 1000))
+        N = out * gpr
+        budget = 2e9 if M == 1 else 3e8              # the oracle's search stays near a second
+        tau = max(min(float(rng.choice([0.01, 0.05, 0.3])), budget / (N * (1 << B) * beam * M)), 1.5 / N)
+        wl = workloads.make(out, gpr * g, g, M, B, seed=int(rng.integers(1 << 30)),
+                            sigma_g=float(10 ** rng.uniform(-4.5, -2)), sigma_w=0.02, tau=tau, beam_width=beam)
+        structured = rng.random() < 0.5
+        if structured:
+            wl.W = oracle.dequantize(wl.codes, wl.codebooks, wl.scales)
+        tag = (seed, case, out, gpr * g, g, M, B, beam, wl.k, structured)
+        run = GpuRun(wl)
+        T, idx = run.targets_select(wl.k)
+        T_ref = oracle.encode_targets(wl.W, wl.G, wl.alpha)
+        idx_ref = oracle.select_topk_groups(T_ref, wl.W, g, wl.k)
+        assert np.array_equal(T.cpu().numpy().view(np.uint32), T_ref.view(np.uint32)), tag
+        assert np.array_equal(idx, idx_ref), tag
+        got, nch = run.reencode(T, idx)
+        want, info = oracle.reencode_groups(T_ref, wl.codebooks, wl.scales, idx_ref, wl.codes, beam_width=beam)
+        ndiff = check_codes_on(wl, T_ref, idx_ref, got, want, info)
+        assert abs(nch - info["num_changed"]) <= ndiff, tag
+        assert np.array_equal(run.dequantize(got).view(np.uint32),
+                              oracle.dequantize(got, wl.codebooks, wl.scales).view(np.uint32)), tag
+        gc = torch.empty(tuple(wl.codebooks.shape), dtype=torch.float32, device=DEV)
+        gs = torch.empty((out,), dtype=torch.float32, device=DEV)
+        run.ctx.pv_codebook_grads(run.lay, run.G, run.codes, run.cb, run.sc, gc, gs)
+        torch.cuda.synchronize()
+        gc_ref, gs_ref = oracle.codebook_grads(wl.G, wl.codes, wl.codebooks, wl.scales)
+        assert close(gc.cpu().numpy(), gc_ref, np.abs(wl.G).sum() * np.abs(wl.scales).max()), tag
+        q = oracle.dequantize(wl.codes, wl.codebooks, np.ones_like(wl.scales))
+        assert close(gs.cpu().numpy(), gs_ref, np.abs(wl.G * q).sum(axis=1)), tag
+        run.ctx.close()
