@@ -357,7 +357,7 @@ __global__ __launch_bounds__(kBlock, 2) void k_beam_2x8_f16(
             const float s = w.s[gl];
             // operand column: y1 = P (x - C0[c0e]) as fp16, norms, shift
             float u[G], hf[G];
-            float yy = 0.0f, d2 = 0.0f, u2 = 0.0f;
+            float yy = 0.0f, u2 = 0.0f;
             bool fits = live;
 #pragma unroll
             for (int i = 0; i < G; ++i) {
@@ -365,10 +365,11 @@ __global__ __launch_bounds__(kBlock, 2) void k_beam_2x8_f16(
                 if (!(fabsf(u[i]) < 240.0f)) fits = false;
                 hf[i] = (float)to_half_flush(fits ? u[i] : 0.0f);
                 yy = fmaf(hf[i], hf[i], yy);
-                const float d = u[i] - hf[i];
-                d2 = fmaf(d, d, d2);
                 u2 = fmaf(u[i], u[i], u2);
             }
+            // || u - hf ||^2: an element moves by at most 2^-11 of itself when it is rounded to
+            // half precision and by less than 2^-14 when it is flushed to zero
+            const float d2 = fmaf(2.4e-7f, u2, 3.0e-8f);
             const float yn = sqrtf(yy) * 1.0001f;
             const float want = (yn + tb.cmin1) * (yn + tb.cmin1) * 1.0001f + 1.0e-3f;
             fits = fits && yy < 57000.0f && want < 60000.0f;
@@ -428,22 +429,20 @@ __global__ __launch_bounds__(kBlock, 2) void k_beam_2x8_f16(
             // the lane whose best key stands for the smallest distance (keys of different columns
             // are closenesses relative to different bases: the distances are what compares)
             const float dist = best == kNoKey ? __builtin_huge_valf() : fmaxf(base - key_upper(best), 0.0f);
-            unsigned long long bk = ((unsigned long long)__float_as_uint(dist) << 32) | (unsigned)lane;
+            // (which column is looked at first decides nothing but how much is left to evaluate
+            // afterwards, so the low six bits of the distance make room for the lane)
+            unsigned bk = (__float_as_uint(dist) & ~63u) | (unsigned)lane;
 #pragma unroll
-            for (int m = 1; m < 8; m <<= 1) {
-                const unsigned long long o = __shfl_xor(bk, m);
-                bk = o < bk ? o : bk;
-            }
-            {
-                const unsigned long long o = __shfl_xor(bk, 32);
-                bk = o < bk ? o : bk;
-            }
-            const int glane = (int)(bk & 63ull);
+            for (int m = 1; m < 8; m <<= 1) bk = min(bk, (unsigned)__shfl_xor(bk, m));
+            bk = min(bk, (unsigned)__shfl_xor(bk, 32));
+            const int glane = (int)(bk & 63u);
             const int gkey = __shfl(best, glane);
             unsigned gbad = colbad ? 1u : 0u;
+            if (__any(colbad)) {                         // rare: the exchange is skipped by the whole wave
 #pragma unroll
-            for (int m = 1; m < 8; m <<= 1) gbad |= __shfl_xor(gbad, m);
-            gbad |= __shfl_xor(gbad, 32);
+                for (int m = 1; m < 8; m <<= 1) gbad |= __shfl_xor(gbad, m);
+                gbad |= __shfl_xor(gbad, 32);
+            }
             bool open = gbad != 0u || gkey == kNoKey;   // filter left (or nothing to look at)
             // reference objective of the 16 pairs behind a key: lane (e, hw) takes codeword
             // e + 8 hw of the key's half tile
@@ -483,14 +482,17 @@ __global__ __launch_bounds__(kBlock, 2) void k_beam_2x8_f16(
                 }
             };
             if (!open) eval_key(gkey, glane);
-            double gobj = wobj;
-            int gidx = widx;
-            group_min(gobj, gidx);
             const double o_prev = w.o_prev[gl];
-            const double e_star = gobj < o_prev ? gobj : o_prev;
+            // E*: the smallest objective known for the group (rounded up; the exact minimum and
+            // its pair are taken once, after everything has been evaluated)
+            float e_star = __double2float_ru(wobj);
+#pragma unroll
+            for (int m = 1; m < 8; m <<= 1) e_star = fminf(e_star, __shfl_xor(e_star, m));
+            e_star = fminf(e_star, __shfl_xor(e_star, 32));
+            e_star = fminf(e_star, __double2float_ru(o_prev));
             // every pair that was not evaluated and could still reach E* sits behind a key whose
             // upper bound is at least kcut (fp32, every rounding covered)
-            const float rr = sqrtf(__double2float_ru(e_star)) * (P / fabsf(s)) * 1.000002f + tb.dC1 + dy;
+            const float rr = sqrtf(e_star) * (P / fabsf(s)) * 1.000002f + tb.dC1 + dy;
             float reach2 = rr * rr * 1.000002f;
             if (!(reach2 == reach2)) reach2 = __builtin_huge_valf();
             const float kcut = (base * 0.999999f - reach2 * 1.000001f) - e1 - 1.0e-6f * (base + reach2);
@@ -500,24 +502,28 @@ __global__ __launch_bounds__(kBlock, 2) void k_beam_2x8_f16(
             bool lopen = !open && live && fits && second != kNoKey && (no_bound || key_upper(second) >= kcut);
             // keys of the other lanes at or above their cut: evaluated by the group as well
             const unsigned long long gmask = (0xFFull << (lane & 24)) | (0xFFull << (32 + (lane & 24)));
-            for (;;) {
-                const unsigned long long pb = __ballot(pending) & gmask;
-                if (!__any(pb != 0ull)) break;
-                if (pb) {
-                    const int src = __ffsll((long long)pb) - 1;
-                    const int key = __shfl(best, src);
-                    eval_key(key, src);
-                    if (lane == src) pending = false;
+            if (__any(pending)) {
+                for (;;) {
+                    const unsigned long long pb = __ballot(pending) & gmask;
+                    if (!__any(pb != 0ull)) break;
+                    if (pb) {
+                        const int src = __ffsll((long long)pb) - 1;
+                        const int key = __shfl(best, src);
+                        eval_key(key, src);
+                        if (lane == src) pending = false;
+                    }
                 }
             }
-            gobj = wobj;
-            gidx = widx;
+            double gobj = wobj;
+            int gidx = widx;
             group_min(gobj, gidx);
-            unsigned go = lopen ? 1u : 0u;
+            if (__any(lopen)) {
+                unsigned go = lopen ? 1u : 0u;
 #pragma unroll
-            for (int m = 1; m < 8; m <<= 1) go |= __shfl_xor(go, m);
-            go |= __shfl_xor(go, 32);
-            open = open || go != 0u;
+                for (int m = 1; m < 8; m <<= 1) go |= __shfl_xor(go, m);
+                go |= __shfl_xor(go, 32);
+                open = open || go != 0u;
+            }
             if (head) {
                 const int n = w.n[gl];
                 if (!gok || open) {
