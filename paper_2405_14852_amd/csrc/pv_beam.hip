@@ -26,6 +26,7 @@
 // sends the group to the list.  The winner among the evaluated pairs (objective, then pair)
 // replaces the current pair if it is strictly better, as everywhere else.
 #include "pv_internal.h"
+#include <type_traits>
 
 namespace {
 
@@ -87,6 +88,26 @@ __device__ __forceinline__ float key_upper(int key)
 __device__ __forceinline__ bool better(double o1, int i1, double o2, int i2)
 {
     return o1 < o2 || (o1 == o2 && i1 < i2);
+}
+
+// Exchanges among the 16 lanes that work on one group in step 1 (8 consecutive lanes in each
+// half of the wave) go through the data-parallel-primitive paths of the vector unit, not through
+// LDS: lane ^ 1 and lane ^ 2 inside quads, then the mirror image inside 8 lanes (the quads are
+// uniform by then, so it brings the other quad's value), then the two halves of the wave.
+template <int CTRL>
+__device__ __forceinline__ int dpp_mov(int v)
+{
+    return __builtin_amdgcn_update_dpp(v, v, CTRL, 0xf, 0xf, false);
+}
+constexpr int kDppXor1 = 0xB1, kDppXor2 = 0x4E, kDppHalfMirror = 0x141;
+
+__device__ __forceinline__ unsigned group16_min_u32(unsigned v)
+{
+    v = min(v, (unsigned)dpp_mov<kDppXor1>((int)v));
+    v = min(v, (unsigned)dpp_mov<kDppXor2>((int)v));
+    v = min(v, (unsigned)dpp_mov<kDppHalfMirror>((int)v));
+    const auto r = __builtin_amdgcn_permlane32_swap(v, v, false, false);   // {lower half's, upper half's} in every lane
+    return min(r[0], r[1]);
 }
 
 // the reference chain for one pair
@@ -431,10 +452,7 @@ __global__ __launch_bounds__(kBlock, 2) void k_beam_2x8_f16(
             const float dist = best == kNoKey ? __builtin_huge_valf() : fmaxf(base - key_upper(best), 0.0f);
             // (which column is looked at first decides nothing but how much is left to evaluate
             // afterwards, so the low six bits of the distance make room for the lane)
-            unsigned bk = (__float_as_uint(dist) & ~63u) | (unsigned)lane;
-#pragma unroll
-            for (int m = 1; m < 8; m <<= 1) bk = min(bk, (unsigned)__shfl_xor(bk, m));
-            bk = min(bk, (unsigned)__shfl_xor(bk, 32));
+            const unsigned bk = group16_min_u32((__float_as_uint(dist) & ~63u) | (unsigned)lane);
             const int glane = (int)(bk & 63u);
             const int gkey = __shfl(best, glane);
             unsigned gbad = colbad ? 1u : 0u;
@@ -465,30 +483,36 @@ __global__ __launch_bounds__(kBlock, 2) void k_beam_2x8_f16(
                 }
             };
             auto group_min = [&](double &o, int &i) {
-#pragma unroll
-                for (int m = 1; m < 8; m <<= 1) {
-                    const double oo = __shfl_xor(o, m);
-                    const int ii = __shfl_xor(i, m);
+                auto stage = [&](auto ctrl) {
+                    constexpr int C = decltype(ctrl)::value;
+                    const int lo = dpp_mov<C>(__double2loint(o)), hi = dpp_mov<C>(__double2hiint(o));
+                    const int ii = dpp_mov<C>(i);
+                    const double oo = __hiloint2double(hi, lo);
                     if (better(oo, ii, o, i)) {
                         o = oo;
                         i = ii;
                     }
-                }
-                const double oo = __shfl_xor(o, 32);
-                const int ii = __shfl_xor(i, 32);
-                if (better(oo, ii, o, i)) {
-                    o = oo;
-                    i = ii;
-                }
+                };
+                stage(std::integral_constant<int, kDppXor1>{});
+                stage(std::integral_constant<int, kDppXor2>{});
+                stage(std::integral_constant<int, kDppHalfMirror>{});
+                const unsigned lo = (unsigned)__double2loint(o), hi = (unsigned)__double2hiint(o);
+                const auto rl = __builtin_amdgcn_permlane32_swap(lo, lo, false, false);
+                const auto rh = __builtin_amdgcn_permlane32_swap(hi, hi, false, false);
+                const auto ri = __builtin_amdgcn_permlane32_swap((unsigned)i, (unsigned)i, false, false);
+                const double oa = __hiloint2double((int)rh[0], (int)rl[0]);
+                const double ob = __hiloint2double((int)rh[1], (int)rl[1]);
+                const bool second = better(ob, (int)ri[1], oa, (int)ri[0]);
+                o = second ? ob : oa;
+                i = second ? (int)ri[1] : (int)ri[0];
             };
             if (!open) eval_key(gkey, glane);
             const double o_prev = w.o_prev[gl];
             // E*: the smallest objective known for the group (rounded up; the exact minimum and
             // its pair are taken once, after everything has been evaluated)
-            float e_star = __double2float_ru(wobj);
-#pragma unroll
-            for (int m = 1; m < 8; m <<= 1) e_star = fminf(e_star, __shfl_xor(e_star, m));
-            e_star = fminf(e_star, __shfl_xor(e_star, 32));
+            // (objectives are never negative, so their float bits order like integers; a NaN
+            // sorts above everything and is dropped by the fminf)
+            float e_star = __uint_as_float(group16_min_u32(__float_as_uint(__double2float_ru(wobj))));
             e_star = fminf(e_star, __double2float_ru(o_prev));
             // every pair that was not evaluated and could still reach E* sits behind a key whose
             // upper bound is at least kcut (fp32, every rounding covered)
