@@ -39,6 +39,7 @@
 // chosen code is the double-precision argmin with the tie rule of the definition, whatever the
 // fp16 rounding did.
 #include "pv_internal.h"
+#include "pv_dpp.h"
 
 // Launch shape of the contraction kernel (tunable at build time).
 #ifndef PV_STAGE
@@ -870,7 +871,7 @@ __global__ __launch_bounds__(kBlock, PV_RR_OCC) void k_rerank(
     constexpr int kTeam = rerank_team(G);          // lanes per group
     constexpr int kTeams = kBlock / kTeam;         // groups per block
     constexpr int kPer = 16 / kTeam;               // positions of a half tile per lane
-    static_assert(kTeam == 4 || kTeam == 8 || kTeam == 16, "a team is a power of two of at most 16 lanes");
+    static_assert(kTeam == 8 || kTeam == 16, "a team is 8 or 16 consecutive lanes");
     __shared__ unsigned s_cnt[4];   // groups decided by the teams, codes changed, candidates evaluated, groups scanned
     __shared__ open_rec_t s_open[kTeams];
     __shared__ unsigned s_nopen;
@@ -929,11 +930,7 @@ __global__ __launch_bounds__(kBlock, PV_RR_OCC) void k_rerank(
             long long v = ((long long)rec[u].x << 32) | (long long)(unsigned)(63 - p);
             bk = v > bk ? v : bk;
         }
-#pragma unroll
-        for (int m = kTeam / 2; m > 0; m >>= 1) {
-            long long o = __shfl_xor(bk, m, kTeam);
-            bk = o > bk ? o : bk;
-        }
+        bk = pv_team_max_i64<kTeam>(bk);
         const int best_key = (int)(bk >> 32);
         const int best_p = 63 - (int)(bk & 0xFFFFFFFFll);
 
@@ -992,15 +989,15 @@ __global__ __launch_bounds__(kBlock, PV_RR_OCC) void k_rerank(
             return r2 == r2 ? r2 : __builtin_huge_valf();   // NaN: nothing can be excluded
         };
         auto team_min = [&](cand_t c) {
-#pragma unroll
-            for (int m = kTeam / 2; m > 0; m >>= 1) {
-                double o = __shfl_xor(c.obj, m, kTeam);
-                int i = __shfl_xor(c.idx, m, kTeam);
+            pv_team_stages<kTeam>([&](auto ctrl) {
+                constexpr int C = decltype(ctrl)::value;
+                const double o = pv_dpp_f64<C>(c.obj);
+                const int i = pv_dpp<C>(c.idx);
                 if (cand_better(o, i, c.obj, c.idx)) {
                     c.obj = o;
                     c.idx = i;
                 }
-            }
+            });
             return c;
         };
 
@@ -1023,11 +1020,7 @@ __global__ __launch_bounds__(kBlock, PV_RR_OCC) void k_rerank(
                     wu = uu;
                 }
             unsigned long long pick = ((unsigned long long)__float_as_uint(dmin) << 32) | (unsigned)q;
-#pragma unroll
-            for (int m = kTeam / 2; m > 0; m >>= 1) {
-                unsigned long long o = __shfl_xor(pick, m, kTeam);
-                pick = o < pick ? o : pick;
-            }
+            pick = pv_team_min_u64<kTeam>(pick);
             const bool chosen = (int)(pick & 15u) == q && dmin < 3.0e38f;
             if (chosen) {
                 int pw = cwd[0];                   // cwd[wu] without dynamic register indexing
@@ -1068,8 +1061,7 @@ __global__ __launch_bounds__(kBlock, PV_RR_OCC) void k_rerank(
                     pending |= 1u << u;
             }
         }
-#pragma unroll
-        for (int m = kTeam / 2; m > 0; m >>= 1) open |= __shfl_xor(open, m, kTeam);
+        open = pv_team_or_u64<kTeam>(open);
         const int team_shift = (threadIdx.x & 63) & ~(kTeam - 1);
         // the best key of every other partition at or above kcut: its positions are evaluated here
         unsigned extra = 0;
@@ -1100,8 +1092,7 @@ __global__ __launch_bounds__(kBlock, PV_RR_OCC) void k_rerank(
             ++extra;
         }
         (void)extra;
-#pragma unroll
-        for (int m = kTeam / 2; m > 0; m >>= 1) exact_evals += __shfl_xor(exact_evals, m, kTeam);
+        exact_evals = pv_team_sum_u32<kTeam>(exact_evals);
         const cand_t win = team_min(mine);
         if (q == 0) {
             if (open) {
