@@ -59,6 +59,11 @@ __device__ __forceinline__ void split3(float v, _Float16 *p)
 
 __device__ __forceinline__ int imax3(int a, int b, int c) { return max(max(a, b), c); }
 
+// v_sqrt_f32 as it is (1 ulp; the library's sqrtf adds a dozen instructions to round correctly and
+// to scale denormal arguments).  Every use below multiplies the root by a margin far above one
+// ulp, or feeds a bound with that much slack.
+__device__ __forceinline__ float fast_sqrt(float v) { return __builtin_amdgcn_sqrtf(v); }
+
 __device__ __forceinline__ int and_or(int m, unsigned vmask, unsigned unit)
 {
     int r;
@@ -139,6 +144,7 @@ struct wave_t {
     float x[64][G];         // t / s of the wave's 64 groups
     float t[64][G];
     float s[64];
+    float p_over_s[64];     // P / |s|: objectives to distances of the scaled operands
     double o_prev[64];
     int n[64];
     unsigned char keep[64][kKeep];   // kept first codes
@@ -307,19 +313,25 @@ __global__ __launch_bounds__(kBlock, 2) void k_beam_2x8_f16(
             unsigned top[kKeep + 1];
 #pragma unroll
             for (int r = 0; r <= kKeep; ++r) top[r] = 0x7F800000u;          // +inf
+            float ym2[G];                                 // -2 y: the products come out of the chain as they are needed
+#pragma unroll
+            for (int i = 0; i < G; ++i) ym2[i] = -2.0f * y[i];
+            unsigned low8 = ~0xFFu;
+            asm volatile("" : "+v"(low8));                // in a register: the and-or takes no literal
             for (int c0 = 0; c0 < 256; ++c0) {
                 const pv_f4 r0 = *reinterpret_cast<const pv_f4 *>(&tb.c0[c0 * G]);
                 const pv_f4 r1 = *reinterpret_cast<const pv_f4 *>(&tb.c0[c0 * G + 4]);
-                float dot = r0.x * y[0];
-                dot = fmaf(r0.y, y[1], dot);
-                dot = fmaf(r0.z, y[2], dot);
-                dot = fmaf(r0.w, y[3], dot);
-                dot = fmaf(r1.x, y[4], dot);
-                dot = fmaf(r1.y, y[5], dot);
-                dot = fmaf(r1.z, y[6], dot);
-                dot = fmaf(r1.w, y[7], dot);
-                const float d = fmaf(-2.0f, dot, tb.n0[c0]) + lift;
-                unsigned carry = (__float_as_uint(d) & ~0xFFu) | (unsigned)c0;
+                // || c0 ||^2 + lift - 2 <c0, y>: every partial sum stays below span^2, nine roundings
+                float d = tb.n0[c0] + lift;
+                d = fmaf(r0.x, ym2[0], d);
+                d = fmaf(r0.y, ym2[1], d);
+                d = fmaf(r0.z, ym2[2], d);
+                d = fmaf(r0.w, ym2[3], d);
+                d = fmaf(r1.x, ym2[4], d);
+                d = fmaf(r1.y, ym2[5], d);
+                d = fmaf(r1.z, ym2[6], d);
+                d = fmaf(r1.w, ym2[7], d);
+                unsigned carry = (unsigned)and_or(__float_as_int(d), low8, (unsigned)c0);
                 // sorted insertion, two levels at a time
 #pragma unroll
                 for (int r = 0; r + 1 <= kKeep; r += 2) {
@@ -346,6 +358,7 @@ __global__ __launch_bounds__(kBlock, 2) void k_beam_2x8_f16(
             }
             w.n[lane] = valid ? n : -1;
             w.s[lane] = s;
+            w.p_over_s[lane] = P / fabsf(div);
             w.o_prev[lane] = o_prev;
             w.ok[lane] = ok ? 1 : 0;
             w.prev[lane][0] = (unsigned char)p0;
@@ -379,19 +392,24 @@ __global__ __launch_bounds__(kBlock, 2) void k_beam_2x8_f16(
             // operand column: y1 = P (x - C0[c0e]) as fp16, norms, shift
             float u[G], hf[G];
             float yy = 0.0f, u2 = 0.0f;
-            bool fits = live;
+#pragma unroll
+            for (int i = 0; i < G; ++i) u[i] = P * (w.x[gl][i] - tb.c0[c0e * G + i]);
+            // a column with an element of 240 or more does not fit and is dropped whole, so what the
+            // lines below make of its elements is never used (x and the codebook are finite for a
+            // live column, so u is a number or an infinity, never a NaN)
+            const float umax = fmaxf(fmaxf(fmaxf(fabsf(u[0]), fabsf(u[1])), fmaxf(fabsf(u[2]), fabsf(u[3]))),
+                                     fmaxf(fmaxf(fabsf(u[4]), fabsf(u[5])), fmaxf(fabsf(u[6]), fabsf(u[7]))));
+            bool fits = live && umax < 240.0f;
 #pragma unroll
             for (int i = 0; i < G; ++i) {
-                u[i] = P * (w.x[gl][i] - tb.c0[c0e * G + i]);
-                if (!(fabsf(u[i]) < 240.0f)) fits = false;
-                hf[i] = (float)to_half_flush(fits ? u[i] : 0.0f);
+                hf[i] = (float)to_half_flush(u[i]);
                 yy = fmaf(hf[i], hf[i], yy);
                 u2 = fmaf(u[i], u[i], u2);
             }
             // || u - hf ||^2: an element moves by at most 2^-11 of itself when it is rounded to
             // half precision and by less than 2^-14 when it is flushed to zero
             const float d2 = fmaf(2.4e-7f, u2, 3.0e-8f);
-            const float yn = sqrtf(yy) * 1.0001f;
+            const float yn = fast_sqrt(yy) * 1.0001f;
             const float want = (yn + tb.cmin1) * (yn + tb.cmin1) * 1.0001f + 1.0e-3f;
             fits = fits && yy < 57000.0f && want < 60000.0f;
             _Float16 sp[3];
@@ -400,7 +418,7 @@ __global__ __launch_bounds__(kBlock, 2) void k_beam_2x8_f16(
             const float base = shift + yy;
             const float e1 = 1.01f * (2.0f * kGamma * (tb.cmax1 + yn) * (tb.cmax1 + yn) * 1.01f + 5.0e-4f);
             // rounding of y1 to fp16, plus the fp32 division, subtraction and scaling
-            const float dy = sqrtf(d2) * 1.0001f + 2.4e-7f * (sqrtf(u2) + 2.0f * P * tb.cmax0) + 1.0e-30f;
+            const float dy = fast_sqrt(d2) * 1.0001f + 2.4e-7f * (fast_sqrt(u2) + 2.0f * P * tb.cmax0) + 1.0e-30f;
             h8 bop;
             if (hw == 0) {
 #pragma unroll
@@ -516,7 +534,7 @@ __global__ __launch_bounds__(kBlock, 2) void k_beam_2x8_f16(
             e_star = fminf(e_star, __double2float_ru(o_prev));
             // every pair that was not evaluated and could still reach E* sits behind a key whose
             // upper bound is at least kcut (fp32, every rounding covered)
-            const float rr = sqrtf(e_star) * (P / fabsf(s)) * 1.000002f + tb.dC1 + dy;
+            const float rr = fast_sqrt(fmaxf(e_star, 1.2e-38f)) * w.p_over_s[gl] * 1.000002f + tb.dC1 + dy;
             float reach2 = rr * rr * 1.000002f;
             if (!(reach2 == reach2)) reach2 = __builtin_huge_valf();
             const float kcut = (base * 0.999999f - reach2 * 1.000001f) - e1 - 1.0e-6f * (base + reach2);
