@@ -115,6 +115,30 @@ __device__ __forceinline__ unsigned group16_min_u32(unsigned v)
     return min(r[0], r[1]);
 }
 
+__device__ __forceinline__ unsigned long long group16_min_u64(unsigned long long v)
+{
+    auto stage = [&](auto ctrl) {
+        constexpr int C = decltype(ctrl)::value;
+        const unsigned lo = (unsigned)dpp_mov<C>((int)(unsigned)v), hi = (unsigned)dpp_mov<C>((int)(unsigned)(v >> 32));
+        const unsigned long long o = ((unsigned long long)hi << 32) | lo;
+        v = o < v ? o : v;
+    };
+    stage(std::integral_constant<int, kDppXor1>{});
+    stage(std::integral_constant<int, kDppXor2>{});
+    stage(std::integral_constant<int, kDppHalfMirror>{});
+    const unsigned lo = (unsigned)v, hi = (unsigned)(v >> 32);
+    const auto rl = __builtin_amdgcn_permlane32_swap(lo, lo, false, false);
+    const auto rh = __builtin_amdgcn_permlane32_swap(hi, hi, false, false);
+    const unsigned long long a = ((unsigned long long)rh[0] << 32) | rl[0];
+    const unsigned long long b = ((unsigned long long)rh[1] << 32) | rl[1];
+    return a < b ? a : b;
+}
+
+// an upper bound of a non-negative double as a float: rounding to nearest is off by at most
+// 2^-24 of the value, the factor makes up for that (an infinity stays one; below the smallest
+// normal float the caller's floor takes over)
+__device__ __forceinline__ float float_above(double v) { return (float)v * 1.0000002f; }
+
 // the reference chain for one pair
 __device__ __forceinline__ double pair_objective(const float *c0, const float *c1, double s,
                                                  const float *t)
@@ -146,6 +170,7 @@ struct wave_t {
     float s[64];
     float p_over_s[64];     // P / |s|: objectives to distances of the scaled operands
     double o_prev[64];
+    float e_prev[64];       // a float above o_prev
     int n[64];
     unsigned char keep[64][kKeep];   // kept first codes
     unsigned char prev[64][2];
@@ -360,6 +385,7 @@ __global__ __launch_bounds__(kBlock, 2) void k_beam_2x8_f16(
             w.s[lane] = s;
             w.p_over_s[lane] = P / fabsf(div);
             w.o_prev[lane] = o_prev;
+            w.e_prev[lane] = float_above(o_prev);
             w.ok[lane] = ok ? 1 : 0;
             w.prev[lane][0] = (unsigned char)p0;
             w.prev[lane][1] = (unsigned char)p1;
@@ -500,38 +526,23 @@ __global__ __launch_bounds__(kBlock, 2) void k_beam_2x8_f16(
                     widx = tie;
                 }
             };
+            // smallest objective of the group's 16 lanes, then the smallest pair index among the
+            // lanes that hold it (objectives are never negative and never NaN: their bits order
+            // like integers)
             auto group_min = [&](double &o, int &i) {
-                auto stage = [&](auto ctrl) {
-                    constexpr int C = decltype(ctrl)::value;
-                    const int lo = dpp_mov<C>(__double2loint(o)), hi = dpp_mov<C>(__double2hiint(o));
-                    const int ii = dpp_mov<C>(i);
-                    const double oo = __hiloint2double(hi, lo);
-                    if (better(oo, ii, o, i)) {
-                        o = oo;
-                        i = ii;
-                    }
-                };
-                stage(std::integral_constant<int, kDppXor1>{});
-                stage(std::integral_constant<int, kDppXor2>{});
-                stage(std::integral_constant<int, kDppHalfMirror>{});
-                const unsigned lo = (unsigned)__double2loint(o), hi = (unsigned)__double2hiint(o);
-                const auto rl = __builtin_amdgcn_permlane32_swap(lo, lo, false, false);
-                const auto rh = __builtin_amdgcn_permlane32_swap(hi, hi, false, false);
-                const auto ri = __builtin_amdgcn_permlane32_swap((unsigned)i, (unsigned)i, false, false);
-                const double oa = __hiloint2double((int)rh[0], (int)rl[0]);
-                const double ob = __hiloint2double((int)rh[1], (int)rl[1]);
-                const bool second = better(ob, (int)ri[1], oa, (int)ri[0]);
-                o = second ? ob : oa;
-                i = second ? (int)ri[1] : (int)ri[0];
+                const unsigned long long mine_bits = (unsigned long long)__double_as_longlong(o);
+                const unsigned long long m = group16_min_u64(mine_bits);
+                i = (int)group16_min_u32(mine_bits == m ? (unsigned)i : 0x7fffffffu);
+                o = __longlong_as_double((long long)m);
             };
             if (!open) eval_key(gkey, glane);
             const double o_prev = w.o_prev[gl];
-            // E*: the smallest objective known for the group (rounded up; the exact minimum and
+            // E*: the smallest objective known for the group (a float above it; the exact minimum and
             // its pair are taken once, after everything has been evaluated)
             // (objectives are never negative, so their float bits order like integers; a NaN
             // sorts above everything and is dropped by the fminf)
-            float e_star = __uint_as_float(group16_min_u32(__float_as_uint(__double2float_ru(wobj))));
-            e_star = fminf(e_star, __double2float_ru(o_prev));
+            float e_star = __uint_as_float(group16_min_u32(__float_as_uint(float_above(wobj))));
+            e_star = fminf(e_star, w.e_prev[gl]);
             // every pair that was not evaluated and could still reach E* sits behind a key whose
             // upper bound is at least kcut (fp32, every rounding covered)
             const float rr = fast_sqrt(fmaxf(e_star, 1.2e-38f)) * w.p_over_s[gl] * 1.000002f + tb.dC1 + dy;
