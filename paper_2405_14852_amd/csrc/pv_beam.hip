@@ -545,7 +545,7 @@ __global__ __launch_bounds__(kBlock, 2) void k_beam_2x8_f16(
             e_star = fminf(e_star, w.e_prev[gl]);
             // every pair that was not evaluated and could still reach E* sits behind a key whose
             // upper bound is at least kcut (fp32, every rounding covered)
-            const float rr = fast_sqrt(fmaxf(e_star, 1.2e-38f)) * w.p_over_s[gl] * 1.000002f + tb.dC1 + dy;
+            const float rr = fast_sqrt(e_star < 1.2e-38f ? 1.2e-38f : e_star) * w.p_over_s[gl] * 1.000002f + tb.dC1 + dy;
             float reach2 = rr * rr * 1.000002f;
             if (!(reach2 == reach2)) reach2 = __builtin_huge_valf();
             const float kcut = (base * 0.999999f - reach2 * 1.000001f) - e1 - 1.0e-6f * (base + reach2);

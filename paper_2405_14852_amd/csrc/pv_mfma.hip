@@ -858,6 +858,17 @@ struct open_rec_t {
 #ifndef PV_RR_OCC
 #define PV_RR_OCC 4   // blocks of the re-rank kernel per compute unit the register budget must allow (g = 16: 149 -> 128 registers, four waves per SIMD instead of three; five would spill)
 #endif
+// v_sqrt_f32 and v_rcp_f32 as they are (1 ulp each; the library's sqrtf and the division add a
+// dozen instructions apiece to round correctly and to scale denormal arguments).  Every use
+// multiplies the result by a margin far above the few ulps that leaves open; a vanishing or
+// denormal scale gives an infinite reciprocal, with which nothing is excluded.
+__device__ __forceinline__ float fast_sqrt(float v) { return __builtin_amdgcn_sqrtf(v); }
+__device__ __forceinline__ float fast_rcp(float v) { return __builtin_amdgcn_rcpf(v); }
+// an upper bound of a non-negative double as a float: rounding to nearest is off by at most
+// 2^-24 of the value, the factor makes up for that; below the smallest normal float the floor
+// applied before the root takes over
+__device__ __forceinline__ float float_above(double v) { return (float)v * 1.0000002f; }
+
 template <int G>
 __global__ __launch_bounds__(kBlock, PV_RR_OCC) void k_rerank(
     const float *__restrict__ x_stage, const float *__restrict__ codebook, int k, int k_pad,
@@ -944,11 +955,11 @@ __global__ __launch_bounds__(kBlock, PV_RR_OCC) void k_rerank(
         bool okP;
         const float Pscale = scale_from_maxabs(cb_meta[0], &okP);
         // what the cheap distance may be off by, at most (see approx_dd)
-        const float nsum = Pscale * sqrtf(__uint_as_float(cb_meta[5])) * 1.0001f + kNormMargin +
-                           sqrtf(meta.y) * 1.0001f;
+        const float nsum = Pscale * fast_sqrt(__uint_as_float(cb_meta[5])) * 1.0001f + kNormMargin +
+                           fast_sqrt(meta.y) * 1.0001f;
         const float dabs = kDdAbs * nsum * nsum;
-        const float dC = sqrtf(__uint_as_float(cb_meta[2])) * 1.0001f + 1e-30f;
-        const float p_over_s = Pscale / fabsf(s);     // inf for a vanishing scale: nothing is excluded then
+        const float dC = fast_sqrt(__uint_as_float(cb_meta[2])) * 1.0001f + 1e-30f;
+        const float p_over_s = Pscale * fast_rcp(fabsf(s));   // inf for a vanishing scale: nothing is excluded then
         // The 16 U positions behind a key (lane q takes positions q, q + kTeam, ... of each of the
         // U half tiles) are looked at in two levels: || c_hi - x_hi ||^2 from the fp16 operand rows (cheap,
         // consecutive rows), and the exact objective only for positions that can still reach
@@ -984,7 +995,9 @@ __global__ __launch_bounds__(kBlock, PV_RR_OCC) void k_rerank(
         };
         // upper bound, in fp32 with every rounding covered, of (P sqrt(E) / |s| + dC + dx)^2
         auto reach2_of = [&](double e_star) {
-            const float rr = sqrtf(__double2float_ru(e_star)) * p_over_s * 1.000002f + dC + meta.w;
+            const float ef = float_above(e_star);
+            // (a NaN passes the floor and the root, and is caught below)
+            const float rr = fast_sqrt(ef < 1.2e-38f ? 1.2e-38f : ef) * p_over_s * 1.000002f + dC + meta.w;
             const float r2 = rr * rr * 1.000002f;
             return r2 == r2 ? r2 : __builtin_huge_valf();   // NaN: nothing can be excluded
         };
@@ -1154,8 +1167,8 @@ __global__ __launch_bounds__(kBlock, PV_RR_OCC) void k_rerank(
         }
         const float xx = x_meta[(int64_t)rec.j * 4 + 1];
         bool okP2;
-        const float nsum = scale_from_maxabs(cb_meta[0], &okP2) * sqrtf(__uint_as_float(cb_meta[5])) * 1.0001f +
-                           kNormMargin + sqrtf(xx) * 1.0001f;
+        const float nsum = scale_from_maxabs(cb_meta[0], &okP2) * fast_sqrt(__uint_as_float(cb_meta[5])) * 1.0001f +
+                           kNormMargin + fast_sqrt(xx) * 1.0001f;
         const float dabs = kDdAbs * nsum * nsum;
         const bool test = rec.reach2 < 3.0e38f;
         const float r2f = rec.reach2;
