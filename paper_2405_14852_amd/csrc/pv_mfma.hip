@@ -1364,7 +1364,7 @@ __global__ __launch_bounds__(kBlock) void k_round_top2(
     if (!live) meta.w = -1.0f;
     bool okP;
     const float Pscale = scale_from_maxabs(cb_meta[0], &okP);
-    const float cmaxn = Pscale * sqrtf(__uint_as_float(cb_meta[5])) * 1.0001f + kNormMargin;
+    const float cmaxn = Pscale * fast_sqrt(__uint_as_float(cb_meta[5])) * 1.0001f + kNormMargin;
     auto decide = [&](const two_t &b, int group, int prev) {
         int pick = prev;                     // nothing could be evaluated (non-finite input): keep
         if (b.i1 != kPvNoCode) pick = pv_round_pick(b.o1, b.i1, b.o2, b.i2, power, seed, (unsigned long long)group);
@@ -1443,12 +1443,13 @@ __global__ __launch_bounds__(kBlock) void k_round_top2(
 #pragma unroll
             for (int h = 0; h < G / 8; ++h) xq[h] = X[((int64_t)gt * 2 + h) * 32 + col];
         }
-        const float nsum = cmaxn + sqrtf(meta.y) * 1.0001f;
+        const float nsum = cmaxn + fast_sqrt(meta.y) * 1.0001f;
         const float dabs = kDdAbs * nsum * nsum;
-        const float p_over_s = Pscale / fabsf(s);
-        const float dC = sqrtf(__uint_as_float(cb_meta[2])) * 1.0001f + 1e-30f;
+        const float p_over_s = Pscale * fast_rcp(fabsf(s));
+        const float dC = fast_sqrt(__uint_as_float(cb_meta[2])) * 1.0001f + 1e-30f;
         auto reach2_of = [&](double e) {
-            const float rr = sqrtf(__double2float_ru(e)) * p_over_s * 1.000002f + dC + meta.w;
+            const float ef = float_above(e);   // a NaN passes the floor and the root, and is caught below
+            const float rr = fast_sqrt(ef < 1.2e-38f ? 1.2e-38f : ef) * p_over_s * 1.000002f + dC + meta.w;
             const float r2 = rr * rr * 1.000002f;
             return r2 == r2 ? r2 : __builtin_huge_valf();
         };
@@ -1567,7 +1568,7 @@ __global__ __launch_bounds__(kBlock) void k_round_top2(
             for (int h = 0; h < G / 8; ++h) xq[h] = X[((int64_t)gt * 2 + h) * 32 + col];
         }
         const float xx = x_meta[(int64_t)rec.j * 4 + 1];
-        const float nsum = cmaxn + sqrtf(xx) * 1.0001f;
+        const float nsum = cmaxn + fast_sqrt(xx) * 1.0001f;
         const float dabs = kDdAbs * nsum * nsum;
         const bool test = rec.reach2 < 3.0e38f;
         const float r2f = rec.reach2;
