@@ -26,7 +26,7 @@
 // sends the group to the list.  The winner among the evaluated pairs (objective, then pair)
 // replaces the current pair if it is strictly better, as everywhere else.
 #include "pv_internal.h"
-#include <type_traits>
+#include "pv_dpp.h"
 
 namespace {
 
@@ -96,36 +96,17 @@ __device__ __forceinline__ bool better(double o1, int i1, double o2, int i2)
 }
 
 // Exchanges among the 16 lanes that work on one group in step 1 (8 consecutive lanes in each
-// half of the wave) go through the data-parallel-primitive paths of the vector unit, not through
-// LDS: lane ^ 1 and lane ^ 2 inside quads, then the mirror image inside 8 lanes (the quads are
-// uniform by then, so it brings the other quad's value), then the two halves of the wave.
-template <int CTRL>
-__device__ __forceinline__ int dpp_mov(int v)
-{
-    return __builtin_amdgcn_update_dpp(v, v, CTRL, 0xf, 0xf, false);
-}
-constexpr int kDppXor1 = 0xB1, kDppXor2 = 0x4E, kDppHalfMirror = 0x141;
-
+// half of the wave): the stages of a team of 8, then the two halves of the wave.
 __device__ __forceinline__ unsigned group16_min_u32(unsigned v)
 {
-    v = min(v, (unsigned)dpp_mov<kDppXor1>((int)v));
-    v = min(v, (unsigned)dpp_mov<kDppXor2>((int)v));
-    v = min(v, (unsigned)dpp_mov<kDppHalfMirror>((int)v));
+    v = pv_team_min_u32<8>(v);
     const auto r = __builtin_amdgcn_permlane32_swap(v, v, false, false);   // {lower half's, upper half's} in every lane
     return min(r[0], r[1]);
 }
 
 __device__ __forceinline__ unsigned long long group16_min_u64(unsigned long long v)
 {
-    auto stage = [&](auto ctrl) {
-        constexpr int C = decltype(ctrl)::value;
-        const unsigned lo = (unsigned)dpp_mov<C>((int)(unsigned)v), hi = (unsigned)dpp_mov<C>((int)(unsigned)(v >> 32));
-        const unsigned long long o = ((unsigned long long)hi << 32) | lo;
-        v = o < v ? o : v;
-    };
-    stage(std::integral_constant<int, kDppXor1>{});
-    stage(std::integral_constant<int, kDppXor2>{});
-    stage(std::integral_constant<int, kDppHalfMirror>{});
+    v = pv_team_min_u64<8>(v);
     const unsigned lo = (unsigned)v, hi = (unsigned)(v >> 32);
     const auto rl = __builtin_amdgcn_permlane32_swap(lo, lo, false, false);
     const auto rh = __builtin_amdgcn_permlane32_swap(hi, hi, false, false);

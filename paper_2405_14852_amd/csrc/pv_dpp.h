@@ -45,6 +45,13 @@ __device__ __forceinline__ void pv_team_stages(F &&f)
 }
 
 template <int TEAM>
+__device__ __forceinline__ unsigned pv_team_min_u32(unsigned v)
+{
+    pv_team_stages<TEAM>([&](auto c) { v = min(v, (unsigned)pv_dpp<decltype(c)::value>((int)v)); });
+    return v;
+}
+
+template <int TEAM>
 __device__ __forceinline__ unsigned long long pv_team_min_u64(unsigned long long v)
 {
     pv_team_stages<TEAM>([&](auto c) {
