@@ -124,12 +124,26 @@ pv_status pv_launch_dequantize(pv_ctx *ctx, const pv_layout *l, const uint16_t *
 pv_status pv_launch_dequantize_groups(pv_ctx *ctx, const pv_layout *l, const uint16_t *codes,
                                       const float *codebooks, const float *scales,
                                       const int32_t *group_idx, int64_t k, float *W_out);
+// A request to the scoring sweep to take, on its way, the squared norm of the dequantised
+// weights sum (scales[o] * codebooks[codes[n]][i])^2 (one codebook, g = 8 or 16): the gathers
+// from the L2-resident codebook ride under the sweep's memory traffic.  partial: device f64,
+// at least pv_select_norm_parts() entries; the sweep leaves `parts` partial sums there, to be
+// added in index order.  pv_select_norm_supported says whether a layout is covered.
+struct pv_norm_req {
+    const uint16_t *codes;
+    const float *codebooks;
+    const float *scales;
+    double *partial;
+    int parts;          // out
+};
+bool pv_select_norm_supported(const pv_layout *l);
+int pv_select_norm_parts();
 // G != nullptr: T is an output, formed in the scoring sweep as W - alpha * G, or, with adam and
 // the moments m, v given, as W minus one Adam update of G
 pv_status pv_launch_select(pv_ctx *ctx, const pv_layout *l, const float *T, const float *W,
                            int64_t k, int32_t *out_idx, float *scores, const float *G = nullptr,
                            float alpha = 0.0f, const pv_adam_t *adam = nullptr, float *m = nullptr,
-                           float *v = nullptr);
+                           float *v = nullptr, pv_norm_req *norm = nullptr);
 // selection with its scratch in the library's static device array (no allocation of any kind)
 pv_status pv_static_scratch_init(pv_ctx *ctx, int device);   // `device` must be current
 int64_t pv_static_max_groups();

@@ -230,14 +230,28 @@ __global__ __launch_bounds__(kBlock) void k_scores_hist0(const float *__restrict
 // the lane before it; the last lane of the group holds the score.
 constexpr int kVecUnroll = 4;
 
-template <int PARTS>
+// NORM: the sweep also adds up (scales[row] * codeword element)^2 over the dequantised weights
+// of the codes (one codebook; lane `part` of a group takes the same 16-byte piece of its
+// codeword as of its target), in double, every thread in the order of its loop, the block
+// in the fixed order of the reduction below: partial[block].
+struct norm_args {
+    const uint16_t *codes;
+    const pv_f4 *cb4;
+    const float *scales;
+    double *partial;
+    unsigned mask;
+    double inv_gpr;
+};
+
+template <int PARTS, bool NORM>
 __global__ __launch_bounds__(kBlock) void k_scores_hist0_vec(const float *__restrict__ T,
                                                              const float *__restrict__ W,
                                                              float *__restrict__ scores,
                                                              unsigned *__restrict__ hist0,
-                                                             int64_t nvec, int want_hist)
+                                                             int64_t nvec, int want_hist, norm_args na)
 {
     __shared__ unsigned lh[kFirstBins];
+    double nacc = 0.0;
     if (want_hist)
         for (int b = threadIdx.x; b < kFirstBins; b += kBlock) lh[b] = 0;
     __syncthreads();
@@ -259,9 +273,33 @@ __global__ __launch_bounds__(kBlock) void k_scores_hist0_vec(const float *__rest
                 b[u] = a[u];
             }
         }
+        // (requesting the codes a chunk ahead, so that the pieces go out with the chunk's targets
+        // and weights, measured 3 us slower on 2 M groups)
+        pv_f4 cw[kVecUnroll];
+        float sc[kVecUnroll];
+        if constexpr (NORM) {
+            unsigned code[kVecUnroll];
+#pragma unroll
+            for (int u = 0; u < kVecUnroll; ++u) {      // codes and scales first, all in flight ...
+                const int64_t i = base + (int64_t)u * kBlock;
+                const unsigned n = (unsigned)((i < nvec ? i : 0) / PARTS);
+                code[u] = na.codes[n] & na.mask;
+                sc[u] = i < nvec ? na.scales[pv_row_of(n, na.inv_gpr)] : 0.0f;
+            }
+#pragma unroll
+            for (int u = 0; u < kVecUnroll; ++u)        // ... then the codeword pieces
+                cw[u] = na.cb4[(int64_t)code[u] * PARTS + part];
+        }
 #pragma unroll
         for (int u = 0; u < kVecUnroll; ++u) {
             const int64_t i = base + (int64_t)u * kBlock;
+            if constexpr (NORM) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const double w = (double)(sc[u] * cw[u][e]);
+                    nacc = nacc + w * w;
+                }
+            }
             const float d0 = a[u].x - b[u].x, d1 = a[u].y - b[u].y;
             const float d2 = a[u].z - b[u].z, d3 = a[u].w - b[u].w;
             float s = 0.0f;
@@ -285,6 +323,18 @@ __global__ __launch_bounds__(kBlock) void k_scores_hist0_vec(const float *__rest
     }
     __syncthreads();
     if (want_hist) flush_hist(lh, hist0 + (blockIdx.x % kSub) * kBins, kFirstBins);
+    if constexpr (NORM) {
+        __shared__ double ntmp[kBlock / 64];
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) nacc = nacc + __shfl_down(nacc, off);
+        if ((threadIdx.x & 63) == 0) ntmp[threadIdx.x >> 6] = nacc;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            double t = 0.0;
+            for (int w = 0; w < kBlock / 64; ++w) t = t + ntmp[w];
+            na.partial[blockIdx.x] = t;
+        }
+    }
 }
 
 // Targets and pass 0 in one sweep (g = 4 * PARTS): T = W - alpha * G is formed and stored, and
@@ -683,6 +733,7 @@ __global__ __launch_bounds__(kBlock) void k_compact_write(const float *__restric
 struct sel_bufs {
     float *scores;
     unsigned *hist, *cc, *state;
+    pv_norm_req *norm = nullptr;
 };
 
 __global__ void k_sel_clear(unsigned *p, int n)
@@ -697,10 +748,12 @@ static pv_status select_run(pv_ctx *ctx, const pv_layout *l, const float *T, con
 // G != nullptr: T is an OUTPUT, formed here as W - alpha * G in the same pass that scores it.
 pv_status pv_launch_select(pv_ctx *ctx, const pv_layout *l, const float *T, const float *W,
                            int64_t k, int32_t *out_idx, float *scores, const float *G, float alpha,
-                           const pv_adam_t *adam, float *m, float *v)
+                           const pv_adam_t *adam, float *m, float *v, pv_norm_req *norm)
 {
     const int N = (int)pv_num_groups(l);
     pv_status st;
+    if (norm && (G || !pv_select_norm_supported(l)))
+        return pv_fail(ctx, PV_ERR_UNSUPPORTED, "norm request: scores-only sweep, one codebook, g = 8 or 16");
     if (!scores) {
         st = pv_ensure(ctx, ctx->sel_scores, (size_t)N * sizeof(float) + 16);
         if (st != PV_OK) return st;
@@ -718,8 +771,16 @@ pv_status pv_launch_select(pv_ctx *ctx, const pv_layout *l, const float *T, cons
     bufs.hist = static_cast<unsigned *>(ctx->sel_hist.ptr);
     bufs.cc = static_cast<unsigned *>(ctx->sel_blocks.ptr);
     bufs.state = static_cast<unsigned *>(ctx->sel_state.ptr);
+    bufs.norm = norm;
     return select_run(ctx, l, T, W, k, out_idx, bufs, G, alpha, adam, m, v);
 }
+
+bool pv_select_norm_supported(const pv_layout *l)
+{
+    return l->num_codebooks == 1 && (l->group_size == 8 || l->group_size == 16);
+}
+
+int pv_select_norm_parts() { return kMaxBlocks; }
 
 // ---------------------------------------------------------------- selection without allocation
 // For callers that cannot allocate device memory (code under HIP graph capture, tight serving
@@ -845,9 +906,25 @@ static pv_status select_run(pv_ctx *ctx, const pv_layout *l, const float *T, con
         const unsigned vblocks = (unsigned)(vb < kMaxBlocks ? vb : kMaxBlocks);
         int64_t sb = ((int64_t)N + kBlock - 1) / kBlock;
         const unsigned sblocks = (unsigned)(sb < kMaxBlocks ? sb : kMaxBlocks);
+        norm_args na{};
+        if (bufs.norm) {
+            na.codes = bufs.norm->codes;
+            na.cb4 = reinterpret_cast<const pv_f4 *>(bufs.norm->codebooks);
+            na.scales = bufs.norm->scales;
+            na.partial = bufs.norm->partial;
+            na.mask = (1u << l->nbits) - 1u;
+            na.inv_gpr = 1.0 / (double)(l->in_features / g);
+            bufs.norm->parts = (int)vblocks;
+        }
 #define PV_SCORES(PARTS_)                                                                          \
-    hipLaunchKernelGGL(k_scores_hist0_vec<PARTS_>, dim3(vblocks), dim3(kBlock), 0, ctx->stream, T, \
-                       W, scores, hist, nvec, want_hist)
+    do {                                                                                           \
+        if (bufs.norm)                                                                             \
+            hipLaunchKernelGGL((k_scores_hist0_vec<PARTS_, true>), dim3(vblocks), dim3(kBlock), 0, \
+                               ctx->stream, T, W, scores, hist, nvec, want_hist, na);              \
+        else                                                                                       \
+            hipLaunchKernelGGL((k_scores_hist0_vec<PARTS_, false>), dim3(vblocks), dim3(kBlock), 0, \
+                               ctx->stream, T, W, scores, hist, nvec, want_hist, na);              \
+    } while (0)
         if (g == 4) PV_SCORES(1);
         else if (g == 8) PV_SCORES(2);
         else if (g == 16) PV_SCORES(4);

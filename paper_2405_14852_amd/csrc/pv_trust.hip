@@ -627,7 +627,7 @@ pv_status pv_launch_trust_ratio(pv_ctx *ctx, const pv_layout *l, const float *T,
     size_t o_moved = o_prefix + align_up((kk + 1) * 8);
     size_t o_tiles = o_moved + align_up(kk);
     size_t o_norm = o_tiles + align_up((size_t)(tiles > 0 ? tiles : 1) * 8);
-    size_t o_keys3 = o_norm + align_up((size_t)norm_blocks * 8);
+    size_t o_keys3 = o_norm + align_up((size_t)(norm_blocks > pv_select_norm_parts() ? norm_blocks : pv_select_norm_parts()) * 8);
     size_t o_vals2 = o_keys3 + align_up(small_sort ? 0 : kk * 4);
     size_t o_hist = o_vals2 + align_up(small_sort ? 0 : kk * 4);
     size_t o_rowpre = o_hist + align_up(small_sort ? 0 : (size_t)sort_tiles * 256 * 4);
@@ -658,8 +658,11 @@ pv_status pv_launch_trust_ratio(pv_ctx *ctx, const pv_layout *l, const float *T,
     float *scores = static_cast<float *>(ctx->sel_scores.ptr);
     hipStream_t sm = ctx->stream;
 
-    // ||x^k||^2 of the codes as they are now (partial sums; the gather kernel adds them up)
-    {
+    // ||x^k||^2 of the codes as they are now (partial sums; the gather kernel adds them up).
+    // One codebook and g = 8 or 16: the scoring sweep of the selection takes it on its way.
+    pv_norm_req norm_req{codes, codebooks, scales, norm_partial, 0};
+    const bool fused_norm = pv_select_norm_supported(l);
+    if (!fused_norm) {
         pv_timed t(ctx, PV_K_TRUST_RATIO);
         if (M == 1 && g == 8)
             hipLaunchKernelGGL(k_tr_normsq_rows<2>, dim3(norm_blocks), dim3(kBlock), 0, sm, codes, codebooks,
@@ -675,8 +678,10 @@ pv_status pv_launch_trust_ratio(pv_ctx *ctx, const pv_layout *l, const float *T,
                                codebooks, scales, N, per_block, g, M, l->nbits, gpr, norm_partial);
     }
     // candidates: the k_max groups of the selection rule (ascending ids) and every score
-    st = pv_launch_select(ctx, l, T, W, k, idx, scores);
+    st = pv_launch_select(ctx, l, T, W, k, idx, scores, nullptr, 0.0f, nullptr, nullptr, nullptr,
+                          fused_norm ? &norm_req : nullptr);
     if (st != PV_OK) return st;
+    if (fused_norm) norm_blocks = norm_req.parts;
     const unsigned kblocks = (unsigned)((k + kBlock - 1) / kBlock);
     {
         pv_timed t(ctx, PV_K_TRUST_RATIO);
