@@ -139,23 +139,25 @@ struct tables_t {
     float c0[256 * G];      // first codebook
     float c1[256 * G];      // second codebook
     float n0[256];          // || c0 ||^2 (fp32 chain)
-    h8 a1[8 * 64];          // second codebook as matrix operand: tile, k-half, row
-    float red[kWaves][6];
-    float P, cmax0, cmax1, cmin1, dC1;
+    h8 a0[8 * 64];          // first codebook as matrix operand: tile, k-half, row
+    h8 a1[8 * 64];          // second codebook, the same
+    float red[kWaves][8];
+    float P, cmax0, cmaxu, cmax0h, cmax1, cmin1, dC0, dC1;
     int bad;
 };
 
+constexpr int kBatch = 32;  // groups a wave works on at a time: two lanes a group in step 0
 struct wave_t {
-    float x[64][G];         // t / s of the wave's 64 groups
-    float t[64][G];
-    float s[64];
-    float p_over_s[64];     // P / |s|: objectives to distances of the scaled operands
-    double o_prev[64];
-    float e_prev[64];       // a float above o_prev
-    int n[64];
-    unsigned char keep[64][kKeep];   // kept first codes
-    unsigned char prev[64][2];
-    unsigned char ok[64];   // the group is still with the filter
+    float x[kBatch][G];     // t / s of the wave's groups
+    float t[kBatch][G];
+    float s[kBatch];
+    float p_over_s[kBatch]; // P / |s|: objectives to distances of the scaled operands
+    double o_prev[kBatch];
+    float e_prev[kBatch];   // a float above o_prev
+    int n[kBatch];
+    unsigned char keep[kBatch][kKeep];   // kept first codes
+    unsigned char prev[kBatch][2];
+    unsigned char ok[kBatch];   // the group is still with the filter
 };
 
 __global__ __launch_bounds__(kBlock, 2) void k_beam_2x8_f16(
@@ -224,47 +226,68 @@ __global__ __launch_bounds__(kBlock, 2) void k_beam_2x8_f16(
             (void)frexpf(M, &ex);
             P = ldexpf(1.0f, 5 - ex);            // M * P in [16, 32)
         }
-        // operand row of codeword c of the second codebook: 2 c_hi | three pieces of ||c_hi||^2, 1, 1, 1
-        h8 ch0, ch1;
-        float nh = 0.0f, d2 = 0.0f;
+        // operand rows of codeword c of both codebooks: 2 c_hi | three pieces of ||c_hi||^2, 1, 1, 1
+        float dmax[2], nhmax0 = 0.0f;
+        auto rows_of = [&](const float *v8, h8 *table, float &d2out, float &nhout) {
+            h8 ch0, ch1;
+            float nh = 0.0f, d2 = 0.0f;
 #pragma unroll
-        for (int i = 0; i < G; ++i) {
-            const float v = ok ? P * b[i] : 0.0f;
-            const float hf = (float)to_half_flush(v);
-            nh = fmaf(hf, hf, nh);
-            const float d = v - hf;
-            d2 = fmaf(d, d, d2);
-            ch0[i] = (_Float16)(2.0f * hf);
-        }
-        _Float16 pieces[3];
-        split3(nh, pieces);
+            for (int i = 0; i < G; ++i) {
+                const float v = ok ? P * v8[i] : 0.0f;
+                const float hf = (float)to_half_flush(v);
+                nh = fmaf(hf, hf, nh);
+                const float d = v - hf;
+                d2 = fmaf(d, d, d2);
+                ch0[i] = (_Float16)(2.0f * hf);
+            }
+            _Float16 pieces[3];
+            split3(nh, pieces);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) ch1[i] = (_Float16)0.0f;
-        ch1[0] = pieces[0];
-        ch1[1] = pieces[1];
-        ch1[2] = pieces[2];
-        ch1[3] = (_Float16)1.0f;
-        ch1[4] = (_Float16)1.0f;
-        ch1[5] = (_Float16)1.0f;
-        {
+            for (int i = 0; i < 8; ++i) ch1[i] = (_Float16)0.0f;
+            ch1[0] = pieces[0];
+            ch1[1] = pieces[1];
+            ch1[2] = pieces[2];
+            ch1[3] = (_Float16)1.0f;
+            ch1[4] = (_Float16)1.0f;
+            ch1[5] = (_Float16)1.0f;
             const int tile = c >> 5, hw = (c >> 4) & 1, q = c & 15;
             const int row = 8 * (q >> 2) + 4 * hw + (q & 3);
-            tb.a1[(tile * 2 + 0) * 32 + row] = ch0;
-            tb.a1[(tile * 2 + 1) * 32 + row] = ch1;
+            table[(tile * 2 + 0) * 32 + row] = ch0;
+            table[(tile * 2 + 1) * 32 + row] = ch1;
+            d2out = d2;
+            nhout = nh;
+        };
+        float nh1;
+        rows_of(a, tb.a0, dmax[0], nhmax0);
+        rows_of(b, tb.a1, dmax[1], nh1);
+        for (int off = 32; off > 0; off >>= 1) {
+            dmax[0] = fmaxf(dmax[0], __shfl_xor(dmax[0], off));
+            dmax[1] = fmaxf(dmax[1], __shfl_xor(dmax[1], off));
+            nhmax0 = fmaxf(nhmax0, __shfl_xor(nhmax0, off));
         }
-        for (int off = 32; off > 0; off >>= 1) d2 = fmaxf(d2, __shfl_xor(d2, off));
         __syncthreads();
-        if (lane == 0) tb.red[wave][5] = d2;
+        if (lane == 0) {
+            tb.red[wave][5] = dmax[1];
+            tb.red[wave][6] = dmax[0];
+            tb.red[wave][7] = nhmax0;
+        }
         __syncthreads();
         if (threadIdx.x == 0) {
-            float D = 0.0f;
+            float D1 = 0.0f, D0 = 0.0f, H0 = 0.0f;
 #pragma unroll
-            for (int v = 0; v < kWaves; ++v) D = fmaxf(D, tb.red[v][5]);
+            for (int v = 0; v < kWaves; ++v) {
+                D1 = fmaxf(D1, tb.red[v][5]);
+                D0 = fmaxf(D0, tb.red[v][6]);
+                H0 = fmaxf(H0, tb.red[v][7]);
+            }
             tb.P = P;
             tb.cmax0 = sqrtf(X0) * 1.0001f;                        // unscaled
+            tb.cmaxu = sqrtf(fmaxf(X0, X1)) * 1.0001f;             // unscaled, both codebooks
+            tb.cmax0h = sqrtf(H0) * 1.0001f + kNormMargin;         // scaled, of the fp16 copy
             tb.cmax1 = P * sqrtf(X1) * 1.0001f + kNormMargin;      // scaled, of the fp16 copy
             tb.cmin1 = P * sqrtf(N1) * 1.0001f + kNormMargin;
-            tb.dC1 = sqrtf(D) * 1.0001f + 1.0e-30f;
+            tb.dC0 = sqrtf(D0) * 1.0001f + 1.0e-30f;
+            tb.dC1 = sqrtf(D1) * 1.0001f + 1.0e-30f;
             tb.bad = ok ? 0 : 1;
         }
         __syncthreads();
@@ -274,17 +297,25 @@ __global__ __launch_bounds__(kBlock, 2) void k_beam_2x8_f16(
     const int keep = beam_width < kKeep ? beam_width : kKeep;
     unsigned vmask = ~kKeyMask;
     asm volatile("" : "+v"(vmask));
-    // the eight operand tiles of the second codebook stay in registers
-    h8 a1[8];
-#pragma unroll
-    for (int tl = 0; tl < 8; ++tl) a1[tl] = tb.a1[tl * 64 + lane];
+    unsigned low8 = ~0xFFu;
+    asm volatile("" : "+v"(low8));                // in a register: the and-or takes no literal
+    const int col = lane & 31, hw = lane >> 5;
+    const f16v zacc = {0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0};
 
     unsigned changed = 0, fast = 0;
-    const int64_t batches = (k + 63) / 64;
+    const int64_t batches = (k + kBatch - 1) / kBatch;
     for (int64_t bi = (int64_t)blockIdx.x * kWaves + wave; bi < batches; bi += (int64_t)gridDim.x * kWaves) {
-        // ------------------------------------------------------------ step 0: lane = group
+        // ------------------------------------------------------------ step 0: two lanes a group
+        // Lanes col and col + 32 work on group col of the batch.  The matrix cores give the
+        // closeness of all 256 first codes to y0 (column col, the lane's half of every tile of
+        // 32 codes); the nine largest of the 16 (tile, half) maxima belong to nine different
+        // codes, so the (keep + 1)-th largest of them, K, bounds the (keep + 1)-th smallest
+        // distance from above, and by the triangle inequality a code can belong to the keep + 1
+        // nearest in the fp32 form only if its closeness reaches a cut below K.  Only those codes
+        // (a dozen) go through the fp32 form and the sorted insertion, each lane taking the ones
+        // of its halves; the two lanes then merge their lists.
         {
-            const int64_t j = bi * 64 + lane;
+            const int64_t j = bi * kBatch + col;
             int n = j < k ? group_idx[j] : -1;
             if (n >= N) n = -1;
             const bool valid = n >= 0;
@@ -316,15 +347,175 @@ __global__ __launch_bounds__(kBlock, 2) void k_beam_2x8_f16(
             const float span = tb.cmax0 + sqrtf(yy) + sqrtf(xx);
             const float e0 = 4.0e-6f * span * span;        // rounding bound of the form (4 * 2^-20)
             const float lift = yy * 1.00001f + e0;
+
+            // operand column: P y0 as fp16, norms, shift (all closenesses non-negative:
+            // SHIFT = (||y_hi|| + max ||c0_hi||)^2)
+            float u[G], hf[G];
+            float yyh = 0.0f, u2 = 0.0f;
+#pragma unroll
+            for (int i = 0; i < G; ++i) u[i] = P * y[i];
+            const float umax = fmaxf(fmaxf(fmaxf(fabsf(u[0]), fabsf(u[1])), fmaxf(fabsf(u[2]), fabsf(u[3]))),
+                                     fmaxf(fmaxf(fabsf(u[4]), fabsf(u[5])), fmaxf(fabsf(u[6]), fabsf(u[7]))));
+            bool fits = ok && umax < 240.0f;
+#pragma unroll
+            for (int i = 0; i < G; ++i) {
+                hf[i] = (float)to_half_flush(fits ? u[i] : 0.0f);
+                yyh = fmaf(hf[i], hf[i], yyh);
+                u2 = fmaf(u[i], u[i], u2);
+            }
+            const float d2 = fmaf(2.4e-7f, u2, 3.0e-8f);
+            const float yn = fast_sqrt(yyh) * 1.0001f;
+            const float want = (yn + tb.cmax0h) * (yn + tb.cmax0h) * 1.0001f + 1.0e-3f;
+            fits = fits && yyh < 57000.0f && want < 60000.0f;
+            _Float16 sp[3];
+            split3(fits ? want : 0.0f, sp);
+            const float shift = ((float)sp[0] + (float)sp[1]) + (float)sp[2];
+            const float base = shift + yyh;
+            const float e1 = 1.01f * (2.0f * kGamma * (tb.cmax0h + yn) * (tb.cmax0h + yn) * 1.01f + 5.0e-4f);
+            // rounding of P y0 to fp16, plus the fp32 division, subtraction and scaling; and of the codebook
+            const float delta = fast_sqrt(d2) * 1.0001f + 2.4e-7f * (fast_sqrt(u2) + 2.0f * P * tb.cmaxu) + 1.0e-30f +
+                                tb.dC0;
+            h8 bop;
+            if (hw == 0) {
+#pragma unroll
+                for (int i = 0; i < G; ++i) bop[i] = (_Float16)(fits ? hf[i] : 0.0f);
+            } else {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) bop[i] = (_Float16)0.0f;
+                if (fits) {
+                    bop[0] = (_Float16)-1.0f;
+                    bop[1] = (_Float16)-1.0f;
+                    bop[2] = (_Float16)-1.0f;
+                    bop[3] = sp[0];
+                    bop[4] = sp[1];
+                    bop[5] = sp[2];
+                }
+            }
+            // round 1: the largest closeness of each (tile, half); the operand tiles of the first
+            // codebook come from LDS as they are needed (held in registers they would cost a
+            // wave of occupancy)
+            auto aop = [&](int tl) { return tb.a0[tl * 64 + lane]; };
+            int pm[8];
+            {
+                f16v acc[2];
+                auto tile_max = [&](const f16v &a) {
+                    int m = imax3(__float_as_int(a[0]), __float_as_int(a[1]), __float_as_int(a[2]));
+                    m = imax3(m, __float_as_int(a[3]), __float_as_int(a[4]));
+                    m = imax3(m, __float_as_int(a[5]), __float_as_int(a[6]));
+                    m = imax3(m, __float_as_int(a[7]), __float_as_int(a[8]));
+                    m = imax3(m, __float_as_int(a[9]), __float_as_int(a[10]));
+                    m = imax3(m, __float_as_int(a[11]), __float_as_int(a[12]));
+                    m = imax3(m, __float_as_int(a[13]), __float_as_int(a[14]));
+                    return max(m, __float_as_int(a[15]));
+                };
+                acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(aop(0), bop, zacc, 0, 0, 0);
+#pragma unroll
+                for (int tl = 1; tl < 8; ++tl) {
+                    acc[tl & 1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(aop(tl), bop, zacc, 0, 0, 0);
+                    pm[tl - 1] = tile_max(acc[(tl - 1) & 1]);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                pm[7] = tile_max(acc[1]);
+            }
+            // K: the (keep + 1)-th largest of the group's 16 maxima (descending insertion of the
+            // lane's eight and the other lane's eight)
+            int K;
+            {
+                int big[kKeep + 1];
+#pragma unroll
+                for (int r = 0; r <= kKeep; ++r) big[r] = kNoKey;
+                auto put = [&](int v) {
+                    int carry = v;
+#pragma unroll
+                    for (int r = 0; r + 1 <= kKeep; r += 2) {
+                        const int hi = max(big[r], carry);
+                        const int mid = imed3(big[r], big[r + 1], carry);
+                        carry = min(big[r + 1], carry);
+                        big[r] = hi;
+                        big[r + 1] = mid;
+                    }
+                    big[kKeep] = max(big[kKeep], carry);
+                };
+#pragma unroll
+                for (int tl = 0; tl < 8; ++tl) put(pm[tl]);
+#pragma unroll
+                for (int tl = 0; tl < 8; ++tl) {
+                    const auto r = __builtin_amdgcn_permlane32_swap((unsigned)pm[tl], (unsigned)pm[tl], false, false);
+                    put((int)(hw ? r[0] : r[1]));
+                }
+                K = big[1];
+#pragma unroll
+                for (int r = 2; r <= kKeep; ++r)
+                    if (r <= keep) K = big[r];
+            }
+            // the cut: anchors (the codes behind the maxima down to K) lie within rho of y_hi; a
+            // code of the keep + 1 nearest in the fp32 form lies within
+            //     delta + sqrt((rho + delta)^2 + 2 e0 P^2)
+            // of it (delta: what the fp16 operands are off by; e0: what the form is off by)
+            fits = fits && K >= 0;
+            const float rho2 = fmaxf((base - __int_as_float(K < 0 ? 0 : K)) * 1.000001f + e1 + 1.0e-6f * base, 0.0f);
+            const float rho = fast_sqrt(rho2) * 1.000001f + delta;
+            const float reach = delta + fast_sqrt(rho * rho * 1.000001f + 2.000001f * e0 * P * P) * 1.000001f;
+            float reach2 = reach * reach * 1.000002f;
+            if (!(reach2 == reach2)) reach2 = __builtin_huge_valf();
+            const float kcut0 = (base * 0.999999f - reach2 * 1.000001f) - e1 - 1.0e-6f * (base + reach2);
+            // round 2: the codes at or above the cut, one bit each (bit 16 (tile & 1) + a of word
+            // tile / 2 for code 32 tile + 16 hw + a)
+            unsigned cand[4] = {0u, 0u, 0u, 0u};
+            asm volatile("" : "+v"(bop));   // a second round of its own: the 128 closenesses of round 1 are not kept
+            {
+                f16v acc[2];
+                auto mark = [&](const f16v &a, int tl) {
+                    unsigned bits = 0u;
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) bits |= (a[e] >= kcut0 ? 1u : 0u) << e;
+                    cand[tl >> 1] |= bits << (16 * (tl & 1));
+                };
+                acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(aop(0), bop, zacc, 0, 0, 0);
+#pragma unroll
+                for (int tl = 1; tl < 8; ++tl) {
+                    acc[tl & 1] = __builtin_amdgcn_mfma_f32_32x32x16_f16(aop(tl), bop, zacc, 0, 0, 0);
+                    mark(acc[(tl - 1) & 1], tl - 1);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                mark(acc[1], 7);
+            }
+            if (!fits) cand[0] = cand[1] = cand[2] = cand[3] = 0u;
+            // the fp32 form and the sorted insertion for the lane's candidates
             unsigned top[kKeep + 1];
 #pragma unroll
             for (int r = 0; r <= kKeep; ++r) top[r] = 0x7F800000u;          // +inf
             float ym2[G];                                 // -2 y: the products come out of the chain as they are needed
 #pragma unroll
             for (int i = 0; i < G; ++i) ym2[i] = -2.0f * y[i];
-            unsigned low8 = ~0xFFu;
-            asm volatile("" : "+v"(low8));                // in a register: the and-or takes no literal
-            for (int c0 = 0; c0 < 256; ++c0) {
+            auto insert = [&](unsigned carry) {
+#pragma unroll
+                for (int r = 0; r + 1 <= kKeep; r += 2) {
+                    const unsigned lo = min(top[r], carry);
+                    const unsigned mid = umed3(top[r], top[r + 1], carry);
+                    carry = max(top[r + 1], carry);
+                    top[r] = lo;
+                    top[r + 1] = mid;
+                }
+                top[kKeep] = min(top[kKeep], carry);
+            };
+            for (;;) {
+                int wsel = -1;
+                unsigned word = 0u;
+#pragma unroll
+                for (int q = 3; q >= 0; --q)
+                    if (cand[q]) {
+                        wsel = q;
+                        word = cand[q];
+                    }
+                if (!__any(wsel >= 0)) break;
+                const bool have = wsel >= 0;
+                const int bit = have ? __ffs((int)word) - 1 : 0;
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    if (q == wsel) cand[q] &= cand[q] - 1u;
+                const int tile = 2 * (have ? wsel : 0) + (bit >> 4);
+                const int c0 = tile * 32 + hw * 16 + (bit & 15);
                 const pv_f4 r0 = *reinterpret_cast<const pv_f4 *>(&tb.c0[c0 * G]);
                 const pv_f4 r1 = *reinterpret_cast<const pv_f4 *>(&tb.c0[c0 * G + 4]);
                 // || c0 ||^2 + lift - 2 <c0, y>: every partial sum stays below span^2, nine roundings
@@ -337,20 +528,23 @@ __global__ __launch_bounds__(kBlock, 2) void k_beam_2x8_f16(
                 d = fmaf(r1.y, ym2[5], d);
                 d = fmaf(r1.z, ym2[6], d);
                 d = fmaf(r1.w, ym2[7], d);
-                unsigned carry = (unsigned)and_or(__float_as_int(d), low8, (unsigned)c0);
-                // sorted insertion, two levels at a time
-#pragma unroll
-                for (int r = 0; r + 1 <= kKeep; r += 2) {
-                    const unsigned lo = min(top[r], carry);
-                    const unsigned mid = umed3(top[r], top[r + 1], carry);
-                    carry = max(top[r + 1], carry);
-                    top[r] = lo;
-                    top[r + 1] = mid;
-                }
-                top[kKeep] = min(top[kKeep], carry);
+                insert(have ? ((__float_as_uint(d) & low8) | (unsigned)c0) : 0x7F800000u);
             }
+            // the other lane's list
+            {
+                unsigned theirs[kKeep + 1];
+#pragma unroll
+                for (int r = 0; r <= kKeep; ++r) {
+                    const auto sw = __builtin_amdgcn_permlane32_swap(top[r], top[r], false, false);
+                    theirs[r] = hw ? sw[0] : sw[1];
+                }
+#pragma unroll
+                for (int r = 0; r <= kKeep; ++r) insert(theirs[r]);
+            }
+            ok = ok && fits;
             // the kept set is certain when the first dropped value clears the last kept one by
-            // twice the rounding bound plus the 8 bits given to the code
+            // twice the rounding bound plus the 8 bits given to the code (a code that was not a
+            // candidate lies above nine candidates, hence above the first dropped value)
             {
                 unsigned last = top[0], next = top[1];
 #pragma unroll
@@ -361,31 +555,36 @@ __global__ __launch_bounds__(kBlock, 2) void k_beam_2x8_f16(
                     }
                 const float vl = __uint_as_float(last | 0xFFu), vn = __uint_as_float(next & ~0xFFu);
                 ok = ok && (vn - vl > 2.0f * e0 + 1.0e-6f * vn);   // false for NaN
+                ok = ok && next != 0x7F800000u;                    // nine candidates were there
             }
-            w.n[lane] = valid ? n : -1;
-            w.s[lane] = s;
-            w.p_over_s[lane] = P / fabsf(div);
-            w.o_prev[lane] = o_prev;
-            w.e_prev[lane] = float_above(o_prev);
-            w.ok[lane] = ok ? 1 : 0;
-            w.prev[lane][0] = (unsigned char)p0;
-            w.prev[lane][1] = (unsigned char)p1;
+            if (hw == 0) {
+                w.n[col] = valid ? n : -1;
+                w.s[col] = s;
+                w.p_over_s[col] = P / fabsf(div);
+                w.o_prev[col] = o_prev;
+                w.e_prev[col] = float_above(o_prev);
+                w.ok[col] = ok ? 1 : 0;
+                w.prev[col][0] = (unsigned char)p0;
+                w.prev[col][1] = (unsigned char)p1;
 #pragma unroll
-            for (int i = 0; i < G; ++i) {
-                w.x[lane][i] = x[i];
-                w.t[lane][i] = t[i];
+                for (int i = 0; i < G; ++i) {
+                    w.x[col][i] = x[i];
+                    w.t[col][i] = t[i];
+                }
+#pragma unroll
+                for (int r = 0; r < kKeep; ++r) w.keep[col][r] = (unsigned char)(top[r] & 0xFFu);
             }
-#pragma unroll
-            for (int r = 0; r < kKeep; ++r) w.keep[lane][r] = (unsigned char)(top[r] & 0xFFu);
         }
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_s_waitcnt(0);
 
-        // ------------------------------------------------------------ step 1: 16 column tiles of 4 groups
-        const int col = lane & 31, hw = lane >> 5;
+        // ------------------------------------------------------------ step 1: 8 column tiles of 4 groups
         const int gq = col >> 3, e = col & 7;            // group of the tile, kept code
+        h8 a1[8];
+#pragma unroll
+        for (int tl = 0; tl < 8; ++tl) a1[tl] = tb.a1[tl * 64 + lane];
 #pragma unroll 1
-        for (int ct = 0; ct < 16; ++ct) {
+        for (int ct = 0; ct < kBatch / 4; ++ct) {
             const int gl = ct * 4 + gq;                  // the group's lane of step 0
             const bool gok = w.ok[gl] != 0;
             const bool head = e == 0 && hw == 0 && w.n[gl] >= 0;   // the lane that speaks for the group
@@ -603,7 +802,7 @@ pv_status pv_launch_beam_2x8_f16(pv_ctx *ctx, const float *T, const float *codeb
                                  unsigned long long *stat_fast, int32_t *redo_list,
                                  unsigned long long *redo_count, int gpr, int N)
 {
-    int64_t blocks = (k + 64 * kWaves - 1) / (64 * kWaves);
+    int64_t blocks = (k + kBatch * kWaves - 1) / (kBatch * kWaves);
     if (blocks > 768) blocks = 768;
     if (blocks < 1) blocks = 1;
     hipLaunchKernelGGL(k_beam_2x8_f16, dim3((unsigned)blocks), dim3(kBlock), 0, ctx->stream, T,
