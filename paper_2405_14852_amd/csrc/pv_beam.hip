@@ -85,6 +85,42 @@ __device__ __forceinline__ unsigned umed3(unsigned a, unsigned b, unsigned c)
     return r;
 }
 
+// Sorting networks (19 exchanges for eight values, 25 for nine): descending integers, ascending
+// unsigned keys.
+__device__ __forceinline__ void sort8_desc(int (&a)[8])
+{
+    auto ce = [&](int i, int j) {
+        const int hi = max(a[i], a[j]), lo = min(a[i], a[j]);
+        a[i] = hi;
+        a[j] = lo;
+    };
+    ce(0, 1); ce(2, 3); ce(4, 5); ce(6, 7);
+    ce(0, 2); ce(1, 3); ce(4, 6); ce(5, 7);
+    ce(1, 2); ce(5, 6); ce(0, 4); ce(3, 7);
+    ce(1, 5); ce(2, 6);
+    ce(1, 4); ce(3, 6);
+    ce(2, 4); ce(3, 5);
+    ce(3, 4);
+}
+
+__device__ __forceinline__ void sort9_asc(unsigned (&a)[9])
+{
+    auto ce = [&](int i, int j) {
+        const unsigned lo = min(a[i], a[j]), hi = max(a[i], a[j]);
+        a[i] = lo;
+        a[j] = hi;
+    };
+    ce(0, 1); ce(3, 4); ce(6, 7);
+    ce(1, 2); ce(4, 5); ce(7, 8);
+    ce(0, 1); ce(3, 4); ce(6, 7);
+    ce(0, 3); ce(3, 6); ce(0, 3);
+    ce(1, 4); ce(4, 7); ce(1, 4);
+    ce(2, 5); ce(5, 8); ce(2, 5);
+    ce(1, 3); ce(5, 7);
+    ce(2, 6); ce(4, 6); ce(2, 4);
+    ce(2, 3); ce(5, 6);
+}
+
 __device__ __forceinline__ float key_upper(int key)
 {
     return key < 0 ? 0.0f : __int_as_float(key | (int)kKeyMask);
@@ -417,36 +453,32 @@ __global__ __launch_bounds__(kBlock, 2) void k_beam_2x8_f16(
                 }
                 pm[7] = tile_max(acc[1]);
             }
-            // K: the (keep + 1)-th largest of the group's 16 maxima (descending insertion of the
-            // lane's eight and the other lane's eight)
+            // K: the (keep + 1)-th largest of the group's 16 maxima.  Both lanes sort their eight;
+            // max(a[i], b[7 - i]) are then the eight largest of the sixteen and the largest of the
+            // min(a[i], b[7 - i]) is the ninth.
             int K;
             {
-                int big[kKeep + 1];
-#pragma unroll
-                for (int r = 0; r <= kKeep; ++r) big[r] = kNoKey;
-                auto put = [&](int v) {
-                    int carry = v;
-#pragma unroll
-                    for (int r = 0; r + 1 <= kKeep; r += 2) {
-                        const int hi = max(big[r], carry);
-                        const int mid = imed3(big[r], big[r + 1], carry);
-                        carry = min(big[r + 1], carry);
-                        big[r] = hi;
-                        big[r + 1] = mid;
-                    }
-                    big[kKeep] = max(big[kKeep], carry);
-                };
-#pragma unroll
-                for (int tl = 0; tl < 8; ++tl) put(pm[tl]);
+                sort8_desc(pm);
+                int other[8];
 #pragma unroll
                 for (int tl = 0; tl < 8; ++tl) {
                     const auto r = __builtin_amdgcn_permlane32_swap((unsigned)pm[tl], (unsigned)pm[tl], false, false);
-                    put((int)(hw ? r[0] : r[1]));
+                    other[tl] = (int)(hw ? r[0] : r[1]);
                 }
-                K = big[1];
+                if (keep == kKeep) {                     // uniform
+                    K = min(pm[0], other[7]);
 #pragma unroll
-                for (int r = 2; r <= kKeep; ++r)
-                    if (r <= keep) K = big[r];
+                    for (int i = 1; i < 8; ++i) K = max(K, min(pm[i], other[7 - i]));
+                } else {
+                    int big[8];
+#pragma unroll
+                    for (int i = 0; i < 8; ++i) big[i] = max(pm[i], other[7 - i]);
+                    sort8_desc(big);
+                    K = big[0];
+#pragma unroll
+                    for (int r = 1; r < kKeep; ++r)
+                        if (r <= keep) K = big[r];
+                }
             }
             // the cut: anchors (the codes behind the maxima down to K) lie within rho of y_hi; a
             // code of the keep + 1 nearest in the fp32 form lies within
@@ -465,10 +497,15 @@ __global__ __launch_bounds__(kBlock, 2) void k_beam_2x8_f16(
             asm volatile("" : "+v"(bop));   // a second round of its own: the 128 closenesses of round 1 are not kept
             {
                 f16v acc[2];
+                // closenesses and the cut are non-negative floats, so acc >= cut is the sign of
+                // (cut - 1) - acc on their bits, shifted into the word from the right (a closeness
+                // that rounding made negative may or may not get a bit: it lies far below the cut)
+                const unsigned kc1 = __float_as_uint(kcut0) - 1u;
                 auto mark = [&](const f16v &a, int tl) {
                     unsigned bits = 0u;
 #pragma unroll
-                    for (int e = 0; e < 16; ++e) bits |= (a[e] >= kcut0 ? 1u : 0u) << e;
+                    for (int e = 15; e >= 0; --e)
+                        bits = __builtin_amdgcn_alignbit(bits, kc1 - __float_as_uint(a[e]), 31);
                     cand[tl >> 1] |= bits << (16 * (tl & 1));
                 };
                 acc[0] = __builtin_amdgcn_mfma_f32_32x32x16_f16(aop(0), bop, zacc, 0, 0, 0);
@@ -480,6 +517,7 @@ __global__ __launch_bounds__(kBlock, 2) void k_beam_2x8_f16(
                 }
                 mark(acc[1], 7);
             }
+            if (!(kcut0 > 0.0f)) cand[0] = cand[1] = cand[2] = cand[3] = ~0u;   // no bound: every code
             if (!fits) cand[0] = cand[1] = cand[2] = cand[3] = 0u;
             // the fp32 form and the sorted insertion for the lane's candidates
             unsigned top[kKeep + 1];
@@ -530,8 +568,9 @@ __global__ __launch_bounds__(kBlock, 2) void k_beam_2x8_f16(
                 d = fmaf(r1.w, ym2[7], d);
                 insert(have ? ((__float_as_uint(d) & low8) | (unsigned)c0) : 0x7F800000u);
             }
-            // the other lane's list
+            // the other lane's list: min(a[i], b[8 - i]) are the nine smallest of the eighteen
             {
+                static_assert(kKeep == 8, "the merge sorts nine values");
                 unsigned theirs[kKeep + 1];
 #pragma unroll
                 for (int r = 0; r <= kKeep; ++r) {
@@ -539,7 +578,8 @@ __global__ __launch_bounds__(kBlock, 2) void k_beam_2x8_f16(
                     theirs[r] = hw ? sw[0] : sw[1];
                 }
 #pragma unroll
-                for (int r = 0; r <= kKeep; ++r) insert(theirs[r]);
+                for (int r = 0; r <= kKeep; ++r) top[r] = min(top[r], theirs[kKeep - r]);
+                sort9_asc(top);
             }
             ok = ok && fits;
             // the kept set is certain when the first dropped value clears the last kept one by
