@@ -6,11 +6,20 @@
 //
 // With x = t / s the objective of a pair is  s^2 || c0 + c1 - x ||^2.
 //
-// Step 0 (256 first codes against the current second code), one group per LANE: the lane
-// forms y0 = x - C1[p1] and, for every first code, || c0 ||^2 - 2 <c0, y0> + || y0 ||^2 in
-// fp32 (the codebook rows are LDS broadcasts), keeping the nine smallest values sorted, the
-// code in the low 8 bits.  The kept set (the smallest beam_width) is accepted when the next
-// value lies above the last kept one by more than twice the rounding bound of that form.
+// Step 0 (256 first codes against the current second code), 32 groups a wave, two lanes a
+// group: with y0 = x - C1[p1] the matrix cores give the closeness of every first code to y0
+// (as in step 1 below; the shift makes every closeness non-negative).  Each lane sees the 16
+// codes of its half of each of the 8 tiles and keeps the largest closeness of each; the nine
+// largest of a group's 16 such maxima belong to nine different codes, so the (beam + 1)-th
+// largest of them bounds the (beam + 1)-th smallest distance from above, and a code can be among
+// the beam + 1 nearest in the fp32 form below only if its closeness reaches a cut under that
+// value (triangle inequality; the rounding of both operands, of the accumulation and of the form
+// are in the cut).  A second round of the same matrix instructions marks those codes, a dozen a
+// group, and only they go through
+//     || c0 ||^2 - 2 <c0, y0> + || y0 ||^2   in fp32
+// and the insertion into nine sorted values (the code in the low 8 bits); the two lanes merge
+// their lists.  The kept set (the smallest beam_width) is accepted when the next value lies above
+// the last kept one by more than twice the rounding bound of that form.
 //
 // Step 1 (256 second codes against each kept first code) is a dense contraction, done on
 // the fp16 matrix cores exactly like the one-codebook filter: columns are (group, kept
@@ -584,7 +593,7 @@ __global__ __launch_bounds__(kBlock, 2) void k_beam_2x8_f16(
             ok = ok && fits;
             // the kept set is certain when the first dropped value clears the last kept one by
             // twice the rounding bound plus the 8 bits given to the code (a code that was not a
-            // candidate lies above nine candidates, hence above the first dropped value)
+            // candidate lies above keep + 1 candidates, hence above the first dropped value)
             {
                 unsigned last = top[0], next = top[1];
 #pragma unroll
@@ -595,7 +604,7 @@ __global__ __launch_bounds__(kBlock, 2) void k_beam_2x8_f16(
                     }
                 const float vl = __uint_as_float(last | 0xFFu), vn = __uint_as_float(next & ~0xFFu);
                 ok = ok && (vn - vl > 2.0f * e0 + 1.0e-6f * vn);   // false for NaN
-                ok = ok && next != 0x7F800000u;                    // nine candidates were there
+                ok = ok && next != 0x7F800000u;                    // keep + 1 candidates were there
             }
             if (hw == 0) {
                 w.n[col] = valid ? n : -1;
