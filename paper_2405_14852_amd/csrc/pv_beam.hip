@@ -193,7 +193,7 @@ struct tables_t {
 
 constexpr int kBatch = 32;  // groups a wave works on at a time: two lanes a group in step 0
 struct wave_t {
-    float x[kBatch][G];     // t / s of the wave's groups
+    float x[kBatch][G];     // P t / s of the wave's groups (P: the power of two that scales the operands)
     float t[kBatch][G];
     float s[kBatch];
     float p_over_s[kBatch]; // P / |s|: objectives to distances of the scaled operands
@@ -617,7 +617,7 @@ __global__ __launch_bounds__(kBlock, 2) void k_beam_2x8_f16(
                 w.prev[col][1] = (unsigned char)p1;
 #pragma unroll
                 for (int i = 0; i < G; ++i) {
-                    w.x[col][i] = x[i];
+                    w.x[col][i] = P * x[i];
                     w.t[col][i] = t[i];
                 }
 #pragma unroll
@@ -648,7 +648,8 @@ __global__ __launch_bounds__(kBlock, 2) void k_beam_2x8_f16(
             float u[G], hf[G];
             float yy = 0.0f, u2 = 0.0f;
 #pragma unroll
-            for (int i = 0; i < G; ++i) u[i] = P * (w.x[gl][i] - tb.c0[c0e * G + i]);
+            // (one rounding, of P (x - c0): scaling by a power of two commutes with it)
+            for (int i = 0; i < G; ++i) u[i] = fmaf(-P, tb.c0[c0e * G + i], w.x[gl][i]);
             // a column with an element of 240 or more does not fit and is dropped whole, so what the
             // lines below make of its elements is never used (x and the codebook are finite for a
             // live column, so u is a number or an infinity, never a NaN)
@@ -657,7 +658,10 @@ __global__ __launch_bounds__(kBlock, 2) void k_beam_2x8_f16(
             bool fits = live && umax < 240.0f;
 #pragma unroll
             for (int i = 0; i < G; ++i) {
-                hf[i] = (float)to_half_flush(u[i]);
+                // (no flush of a denormal half here: whether the matrix core keeps it or flushes
+                // it, the operand stays within the bound below of u, and || hf ||^2 moves by less
+                // than 3e-8)
+                hf[i] = (float)(_Float16)u[i];
                 yy = fmaf(hf[i], hf[i], yy);
                 u2 = fmaf(u[i], u[i], u2);
             }
@@ -671,7 +675,7 @@ __global__ __launch_bounds__(kBlock, 2) void k_beam_2x8_f16(
             split3(fits ? want : 0.0f, sp);
             const float shift = ((float)sp[0] + (float)sp[1]) + (float)sp[2];
             const float base = shift + yy;
-            const float e1 = 1.01f * (2.0f * kGamma * (tb.cmax1 + yn) * (tb.cmax1 + yn) * 1.01f + 5.0e-4f);
+            const float e1 = 1.01f * (2.0f * kGamma * (tb.cmax1 + yn) * (tb.cmax1 + yn) * 1.01f + 5.01e-4f);
             // rounding of y1 to fp16, plus the fp32 division, subtraction and scaling
             const float dy = fast_sqrt(d2) * 1.0001f + 2.4e-7f * (fast_sqrt(u2) + 2.0f * P * tb.cmax0) + 1.0e-30f;
             h8 bop;
