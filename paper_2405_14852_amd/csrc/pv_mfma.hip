@@ -1345,7 +1345,6 @@ __global__ __launch_bounds__(kBlock) void k_round_top2(
     constexpr int kTeam = rerank_team(G);
     constexpr int kTeams = kBlock / kTeam;
     constexpr int kPer = 16 / kTeam;
-    constexpr int kMine = kU * kPer;               // positions of a key per lane
     __shared__ unsigned s_cnt[4];   // groups decided by the teams, codes changed, candidates evaluated, groups scanned
     __shared__ open2_t s_open[kTeams];
     __shared__ unsigned s_nopen;
@@ -1638,12 +1637,6 @@ __global__ __launch_bounds__(kBlock) void k_round_top2(
             if (total) atomicAdd(num_changed, total);
         }
     }
-}
-
-__global__ void k_fill_u32(unsigned *p, int n, unsigned v)
-{
-    int i = blockIdx.x * blockDim.x + threadIdx.x;
-    if (i < n) p[i] = v;
 }
 
 struct plan_t {
