@@ -4,13 +4,15 @@
 // index order, so that every implementation of this rule gives the same bits.
 // Scores are non-negative floats, so their bit patterns order like unsigned
 // integers.  The k-th largest key is found by a 3-digit radix select (11 + 12 +
-// 9 bits, most significant first); groups above the threshold are taken, groups
+// 8 bits below the sign, most significant first); groups above the threshold are taken, groups
 // equal to it are taken lowest id first, and the ids are written in ascending
 // order through a two-level prefix sum.  Nothing returns to the host.
 //
 // Launches: [scores + digit-0 histogram] [digit-1 histogram] [digit-2 histogram]
-// [per-chunk counts] [ordered write].  Digit 0 (sign, exponent, two mantissa
-// bits) is counted in an LDS histogram inside the streaming score kernel, whose
+// [per-chunk counts] [ordered write].  Digit 0 (exponent and three mantissa bits: an
+// eighth of an octave - the later passes pay one atomic on device memory for each key
+// that shares the chosen one, the sweep one for each populated bin of each block) is counted in an LDS histogram inside
+// the streaming score kernel, whose
 // blocks are persistent so that clearing and flushing it is paid once per block;
 // the later digits usually see only the few per cent of keys that share the
 // chosen digit 0, but a narrow score distribution (updates of one size, as an
@@ -30,13 +32,19 @@
 namespace {
 
 constexpr int kBlock = 256;
+#ifndef PV_REST_BITS
+#define PV_REST_BITS 20
+#endif
+constexpr int kRestBits = PV_REST_BITS;         // bits of a key below digit 0
 #ifndef PV_MID_BITS
-#define PV_MID_BITS 12
+#define PV_MID_BITS (PV_REST_BITS - 8)
 #endif
 constexpr int kMidBits = PV_MID_BITS;
-constexpr int kBins = 1 << kMidBits;            // digit 1: the next mantissa bits (also the slot count of every histogram, >= 2048)
-constexpr int kFirstBins = 2048;                // digit 0: sign, exponent, 2 mantissa bits
-constexpr int kLastBins = 1 << (21 - kMidBits); // digit 2: the remaining low mantissa bits
+constexpr int kSlots = 4096;                    // slots of every histogram in device memory
+constexpr int kFirstBins = 1 << (31 - kRestBits);      // digit 0: exponent and 3 mantissa bits (keys are clamped below 2^31)
+constexpr int kBins = 1 << kMidBits;                   // digit 1: the next mantissa bits
+constexpr int kLastBins = 1 << (kRestBits - kMidBits); // digit 2: the remaining low mantissa bits
+static_assert(kFirstBins <= kSlots && kBins <= kSlots && kLastBins <= kSlots, "a histogram fits its slots");
 constexpr int kItems = 8;                      // groups per thread in the compaction kernels
 constexpr int kChunk = kBlock * kItems;        // groups per chunk there
 static_assert(kChunk < 65536, "the compaction packs two per-chunk counts into 32 bits");
@@ -46,10 +54,15 @@ static_assert(kChunk < 65536, "the compaction packs two per-chunk counts into 32
 constexpr int kMaxBlocks = PV_SEL_BLOCKS;      // persistent grid of the streaming kernels: two blocks per compute unit (1024 cost 1 us on 2 M groups and 4 to 6 us on 3.7 to 5.6 M, 256 lose a sixth of the bandwidth)
 constexpr int kCompactBlocks = 1024;           // grid of the two compaction kernels
 
+// The key of a score: its bits, which order like the values because scores are sums of squares
+// (never negative); a pattern with the sign bit set can only be a NaN and is clamped to the
+// largest key, so that digit 0 needs no bit for the sign.
+__device__ __forceinline__ unsigned score_key(float s) { return min(__float_as_uint(s), 0x7FFFFFFFu); }
+
 __device__ __forceinline__ int digit_of(unsigned key, int pass)
 {
-    return pass == 0 ? (int)(key >> 21)
-                     : pass == 1 ? (int)((key >> (21 - kMidBits)) & (unsigned)(kBins - 1))
+    return pass == 0 ? (int)(key >> kRestBits)
+                     : pass == 1 ? (int)((key >> (kRestBits - kMidBits)) & (unsigned)(kBins - 1))
                                  : (int)(key & (unsigned)(kLastBins - 1));
 }
 
@@ -103,10 +116,10 @@ __device__ __forceinline__ unsigned block_excl_scan(unsigned v, unsigned *tmp, u
 
 // Global histograms are stored so that the scan below reads them coalesced:
 // digit d of a `bins`-digit histogram has rank r = bins - 1 - d from the top and
-// lives at slot (r % kPer) * 256 + r / kPer with kPer = kBins / 256 ranks per scan thread;
+// lives at slot (r % kPer) * 256 + r / kPer with kPer = kSlots / 256 ranks per scan thread;
 // thread t of the scan owns ranks [kPer t, kPer t + kPer), i.e. slots t, t + 256, ...
-// Every histogram occupies kBins slots.
-constexpr int kPer = kBins / kBlock;
+// Every histogram occupies kSlots slots.
+constexpr int kPer = kSlots / kBlock;
 // The first histogram is fed by every block of the scoring sweep at about the same moment, and
 // most of the counts fall on a dozen bins: its atomics would queue on a dozen addresses (5 to
 // 14 us on 2 M groups, depending on where the scores fall).  It is kept in kSub copies (two
@@ -116,9 +129,9 @@ constexpr int kPer = kBins / kBlock;
 #define PV_HIST_COPIES 2
 #endif
 constexpr int kSub = PV_HIST_COPIES;
-constexpr int kHist1 = kSub * kBins;          // offsets of the second and third histogram
-constexpr int kHist2 = kHist1 + kBins;
-constexpr int kHistTotal = kHist2 + kBins;
+constexpr int kHist1 = kSub * kSlots;         // offsets of the second and third histogram
+constexpr int kHist2 = kHist1 + kSlots;
+constexpr int kHistTotal = kHist2 + kSlots;
 __device__ __forceinline__ int hist_slot(int digit, int bins)
 {
     const int r = bins - 1 - digit;
@@ -142,7 +155,7 @@ __device__ void pick_digit(const unsigned *__restrict__ ghist, int bins, unsigne
         unsigned part[COPIES];     // all loads of the copies in flight together
 #pragma unroll
         for (int c = 0; c < COPIES; ++c)
-            part[c] = (tid * per + j) < bins ? ghist[c * kBins + j * kBlock + tid] : 0u;
+            part[c] = (tid * per + j) < bins ? ghist[c * kSlots + j * kBlock + tid] : 0u;
         cnt[j] = 0u;
 #pragma unroll
         for (int c = 0; c < COPIES; ++c) cnt[j] += part[c];
@@ -215,12 +228,12 @@ __global__ __launch_bounds__(kBlock) void k_scores_hist0(const float *__restrict
         if (valid) {
             float s = score_group(T + n * g, W + n * g, g);
             scores[n] = s;
-            key = __float_as_uint(s);
+            key = score_key(s);
         }
         if (want_hist) hist_add<PV_VOTE_ROUNDS>(lh, digit_of(key, 0), valid);
     }
     __syncthreads();
-    if (want_hist) flush_hist(lh, hist0 + (blockIdx.x % kSub) * kBins, kFirstBins);
+    if (want_hist) flush_hist(lh, hist0 + (blockIdx.x % kSub) * kSlots, kFirstBins);
 }
 
 // Pass 0 for g = 4 * PARTS (PARTS a power of two): every lane loads one 16-byte
@@ -318,11 +331,11 @@ __global__ __launch_bounds__(kBlock) void k_scores_hist0_vec(const float *__rest
             }
             const bool valid = i < nvec && part == PARTS - 1;
             if (valid) scores[i / PARTS] = s;
-            if (want_hist) hist_add<PV_VOTE_ROUNDS>(lh, digit_of(__float_as_uint(s), 0), valid);
+            if (want_hist) hist_add<PV_VOTE_ROUNDS>(lh, digit_of(score_key(s), 0), valid);
         }
     }
     __syncthreads();
-    if (want_hist) flush_hist(lh, hist0 + (blockIdx.x % kSub) * kBins, kFirstBins);
+    if (want_hist) flush_hist(lh, hist0 + (blockIdx.x % kSub) * kSlots, kFirstBins);
     if constexpr (NORM) {
         __shared__ double ntmp[kBlock / 64];
 #pragma unroll
@@ -425,7 +438,7 @@ __global__ __launch_bounds__(kBlock) void k_targets_scores_hist0_vec(const float
             }
             const bool valid = i < nvec && part == PARTS - 1;
             if (valid) scores[i / PARTS] = s;
-            if (want_hist) hist_add<PV_VOTE_ROUNDS>(lh, digit_of(__float_as_uint(s), 0), valid);
+            if (want_hist) hist_add<PV_VOTE_ROUNDS>(lh, digit_of(score_key(s), 0), valid);
         }
 #pragma unroll
         for (int u = 0; u < kVecUnroll; ++u) {
@@ -434,7 +447,7 @@ __global__ __launch_bounds__(kBlock) void k_targets_scores_hist0_vec(const float
         }
     }
     __syncthreads();
-    if (want_hist) flush_hist(lh, hist0 + (blockIdx.x % kSub) * kBins, kFirstBins);
+    if (want_hist) flush_hist(lh, hist0 + (blockIdx.x % kSub) * kSlots, kFirstBins);
 }
 
 // The same sweep for group sizes 1 and 2: a 16-byte vector holds 4 / GS whole groups and every
@@ -497,7 +510,7 @@ __global__ __launch_bounds__(kBlock) void k_targets_scores_hist0_sub(const float
             if (want_hist) {
 #pragma unroll
                 for (int q = 0; q < kPerVec; ++q)
-                    hist_add<PV_VOTE_ROUNDS>(lh, digit_of(__float_as_uint(sc[q]), 0), valid);
+                    hist_add<PV_VOTE_ROUNDS>(lh, digit_of(score_key(sc[q]), 0), valid);
             }
         }
     }
@@ -512,11 +525,11 @@ __global__ __launch_bounds__(kBlock) void k_targets_scores_hist0_sub(const float
                 s = fmaf(d, d, s);
             }
             scores[i / GS] = s;
-            if (want_hist) atomicAdd(&lh[digit_of(__float_as_uint(s), 0)], 1u);
+            if (want_hist) atomicAdd(&lh[digit_of(score_key(s), 0)], 1u);
         }
     }
     __syncthreads();
-    if (want_hist) flush_hist(lh, hist0 + (blockIdx.x % kSub) * kBins, kFirstBins);
+    if (want_hist) flush_hist(lh, hist0 + (blockIdx.x % kSub) * kSlots, kFirstBins);
 }
 
 // Passes 1 and 2: histogram of the next digit among keys that match the digits
@@ -573,14 +586,14 @@ __global__ __launch_bounds__(kHistBlock) void k_hist_next(const float *__restric
             const int64_t i = base + u * stride + threadIdx.x;
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
-                unsigned key = __float_as_uint(v[u][e]);
+                unsigned key = score_key(v[u][e]);
                 bool valid = i < n4 && digit_of(key, 0) == d0 && (pass == 1 || digit_of(key, 1) == d1);
                 hist_add<PV_LATE_VOTE_ROUNDS>(lh, digit_of(key, pass), valid);
             }
         }
     }
     if (blockIdx.x == 0 && (int)threadIdx.x < (N & 3)) {
-        unsigned key = __float_as_uint(scores[(n4 << 2) + threadIdx.x]);
+        unsigned key = score_key(scores[(n4 << 2) + threadIdx.x]);
         if (digit_of(key, 0) == d0 && (pass == 1 || digit_of(key, 1) == d1))
             atomicAdd(&lh[digit_of(key, pass)], 1u);
     }
@@ -615,7 +628,7 @@ __global__ __launch_bounds__(kBlock) void k_chunk_counts(const float *__restrict
     int d2;
     unsigned kk;
     pick_digit(hist_all + kHist2, kLastBins, state[7], tmp, &d2, &kk);
-    const unsigned thr = ((unsigned)d0 << 21) | ((unsigned)d1 << (21 - kMidBits)) | (unsigned)d2;
+    const unsigned thr = ((unsigned)d0 << kRestBits) | ((unsigned)d1 << (kRestBits - kMidBits)) | (unsigned)d2;
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         state[0] = thr;
         state[1] = kk;  // how many keys equal to thr are selected (lowest ids first)
@@ -630,7 +643,7 @@ __global__ __launch_bounds__(kBlock) void k_chunk_counts(const float *__restrict
                 pv_f4 x = s4[v];
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    unsigned key = __float_as_uint(x[e]);
+                    unsigned key = score_key(x[e]);
                     gt += key > thr;
                     eq += key == thr;
                 }
@@ -638,7 +651,7 @@ __global__ __launch_bounds__(kBlock) void k_chunk_counts(const float *__restrict
         } else {
             for (int j = 0; j < kItems; ++j)
                 if (base + j < N) {
-                    unsigned key = __float_as_uint(scores[base + j]);
+                    unsigned key = score_key(scores[base + j]);
                     gt += key > thr;
                     eq += key == thr;
                 }
@@ -688,11 +701,11 @@ __global__ __launch_bounds__(kBlock) void k_compact_write(const float *__restric
             for (int v = 0; v < kItems / 4; ++v) {
                 const pv_f4 x = s4[v];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) keys[v * 4 + e] = __float_as_uint(x[e]);
+                for (int e = 0; e < 4; ++e) keys[v * 4 + e] = score_key(x[e]);
             }
         } else {
 #pragma unroll
-            for (int j = 0; j < kItems; ++j) keys[j] = base + j < N ? __float_as_uint(scores[base + j]) : 0u;
+            for (int j = 0; j < kItems; ++j) keys[j] = base + j < N ? score_key(scores[base + j]) : 0u;
         }
 #pragma unroll
         for (int j = 0; j < kItems; ++j)
