@@ -43,7 +43,7 @@ constexpr int kMidBits = PV_MID_BITS;
 constexpr int kSlots = 4096;                    // slots of every histogram in device memory
 constexpr int kFirstBins = 1 << (31 - kRestBits);      // digit 0: exponent and 3 mantissa bits (keys are clamped below 2^31)
 constexpr int kBins = 1 << kMidBits;                   // digit 1: the next mantissa bits
-constexpr int kLastBins = 1 << (kRestBits - kMidBits); // digit 2: the remaining low mantissa bits
+constexpr int kLastBins = 1 << (kRestBits - kMidBits + 1); // digit 2: the remaining low mantissa bits (at most)
 static_assert(kFirstBins <= kSlots && kBins <= kSlots && kLastBins <= kSlots, "a histogram fits its slots");
 constexpr int kItems = 8;                      // groups per thread in the compaction kernels
 constexpr int kChunk = kBlock * kItems;        // groups per chunk there
@@ -59,11 +59,12 @@ constexpr int kCompactBlocks = 1024;           // grid of the two compaction ker
 // largest key, so that digit 0 needs no bit for the sign.
 __device__ __forceinline__ unsigned score_key(float s) { return min(__float_as_uint(s), 0x7FFFFFFFu); }
 
-__device__ __forceinline__ int digit_of(unsigned key, int pass)
+// `mid`: the width of digit 1, which every call fixes when digit 0 is known (see k_hist_next).
+__device__ __forceinline__ int digit_of(unsigned key, int pass, int mid = kMidBits)
 {
     return pass == 0 ? (int)(key >> kRestBits)
-                     : pass == 1 ? (int)((key >> (kRestBits - kMidBits)) & (unsigned)(kBins - 1))
-                                 : (int)(key & (unsigned)(kLastBins - 1));
+                     : pass == 1 ? (int)((key >> (kRestBits - mid)) & ((1u << mid) - 1u))
+                                 : (int)(key & ((1u << (kRestBits - mid)) - 1u));
 }
 
 // Add one count per valid lane to an LDS histogram.  Lanes of a wave that hit
@@ -141,10 +142,10 @@ __device__ __forceinline__ int hist_slot(int digit, int bins)
 // Given a histogram of `bins` digits and the rank `kk` (1-based, counted from the
 // largest digit), find the digit d with  count(> d) < kk <= count(>= d)  and
 // return kk - count(> d).  All threads of the block call this; the result goes
-// to all.  `tmp` is kBlock + 2 unsigneds of LDS.
+// to all, with the count of that digit if `count` is given.  `tmp` is kBlock + 3 unsigneds of LDS.
 template <int COPIES = 1>
 __device__ void pick_digit(const unsigned *__restrict__ ghist, int bins, unsigned kk,
-                           unsigned *tmp, int *digit, unsigned *kk_rem)
+                           unsigned *tmp, int *digit, unsigned *kk_rem, unsigned *count = nullptr)
 {
     constexpr int per = kPer;            // ranks per thread; thread 0 owns the TOP digits
     const int tid = threadIdx.x;
@@ -155,7 +156,7 @@ __device__ void pick_digit(const unsigned *__restrict__ ghist, int bins, unsigne
         unsigned part[COPIES];     // all loads of the copies in flight together
 #pragma unroll
         for (int c = 0; c < COPIES; ++c)
-            part[c] = (tid * per + j) < bins ? ghist[c * kSlots + j * kBlock + tid] : 0u;
+            part[c] = ghist[c * kSlots + j * kBlock + tid];   // ranks beyond `bins`: slots that stay zero
         cnt[j] = 0u;
 #pragma unroll
         for (int c = 0; c < COPIES; ++c) cnt[j] += part[c];
@@ -168,12 +169,14 @@ __device__ void pick_digit(const unsigned *__restrict__ ghist, int bins, unsigne
         if (above < kk && kk <= above + cnt[j]) {
             tmp[kBlock] = (unsigned)(bins - 1 - (tid * per + j));
             tmp[kBlock + 1] = kk - above;
+            tmp[kBlock + 2] = cnt[j];
         }
         above += cnt[j];
     }
     __syncthreads();
     *digit = (int)tmp[kBlock];
     *kk_rem = tmp[kBlock + 1];
+    if (count) *count = tmp[kBlock + 2];
     __syncthreads();
 }
 
@@ -536,7 +539,12 @@ __global__ __launch_bounds__(kBlock) void k_targets_scores_hist0_sub(const float
 // chosen so far.  Each launch resolves the digit of the previous histogram and
 // block 0 publishes it in `state` for the launches that follow:
 // state[4] = digit 0, state[5] = digit 1, state[6] = rank left after digit 0,
-// state[7] = rank left after digit 1.
+// state[7] = rank left after digit 1, state[2] = width of digit 1.
+// The width of digit 1 is fixed when digit 0 is known: kMidBits when few keys share digit 0 (a
+// spread-out distribution: every such key costs an atomic on device memory in the flush, and a
+// wide digit 1 leaves few for the last pass), one bit less when more than an eighth of all keys
+// do (a narrow one, as after a sign-like optimiser step: the keys then fall on half as many bins
+// of digit 1 and merge in the block histograms).
 constexpr int kHistBlock = 512;   // measured against 256 and 1024 threads on 2 M and 5.6 M groups
 __global__ __launch_bounds__(kHistBlock) void k_hist_next(const float *__restrict__ scores,
                                                       const unsigned *__restrict__ hist_all,
@@ -544,25 +552,29 @@ __global__ __launch_bounds__(kHistBlock) void k_hist_next(const float *__restric
                                                       unsigned *__restrict__ state, int N,
                                                       unsigned k, int pass)
 {
-    __shared__ unsigned tmp[kBlock + 2];
+    __shared__ unsigned tmp[kBlock + 3];
     __shared__ unsigned lh[kBins];
-    const int bins = pass == 1 ? kBins : kLastBins;
-    int d0, d1 = 0;
+    int d0, d1 = 0, mid;
     unsigned kk;
     if (pass == 1) {
-        pick_digit<kSub>(hist_all, kFirstBins, k, tmp, &d0, &kk);
+        unsigned share;
+        pick_digit<kSub>(hist_all, kFirstBins, k, tmp, &d0, &kk, &share);
+        mid = share > (unsigned)N / 8u ? kMidBits - 1 : kMidBits;
         if (blockIdx.x == 0 && threadIdx.x == 0) {
             state[4] = (unsigned)d0;
             state[6] = kk;
+            state[2] = (unsigned)mid;
         }
     } else {
         d0 = (int)state[4];
-        pick_digit(hist_all + kHist1, kBins, state[6], tmp, &d1, &kk);
+        mid = (int)state[2];
+        pick_digit(hist_all + kHist1, 1 << mid, state[6], tmp, &d1, &kk);
         if (blockIdx.x == 0 && threadIdx.x == 0) {
             state[5] = (unsigned)d1;
             state[7] = kk;
         }
     }
+    const int bins = pass == 1 ? (1 << mid) : (1 << (kRestBits - mid));
     // Per-block histogram in LDS, flushed once: a narrow score distribution (all updates of
     // one size, as after a sign-like optimiser step) puts most keys into a few bins, and that
     // many atomics on a few global addresses would serialise.
@@ -587,15 +599,15 @@ __global__ __launch_bounds__(kHistBlock) void k_hist_next(const float *__restric
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 unsigned key = score_key(v[u][e]);
-                bool valid = i < n4 && digit_of(key, 0) == d0 && (pass == 1 || digit_of(key, 1) == d1);
-                hist_add<PV_LATE_VOTE_ROUNDS>(lh, digit_of(key, pass), valid);
+                bool valid = i < n4 && digit_of(key, 0) == d0 && (pass == 1 || digit_of(key, 1, mid) == d1);
+                hist_add<PV_LATE_VOTE_ROUNDS>(lh, digit_of(key, pass, mid), valid);
             }
         }
     }
     if (blockIdx.x == 0 && (int)threadIdx.x < (N & 3)) {
         unsigned key = score_key(scores[(n4 << 2) + threadIdx.x]);
-        if (digit_of(key, 0) == d0 && (pass == 1 || digit_of(key, 1) == d1))
-            atomicAdd(&lh[digit_of(key, pass)], 1u);
+        if (digit_of(key, 0) == d0 && (pass == 1 || digit_of(key, 1, mid) == d1))
+            atomicAdd(&lh[digit_of(key, pass, mid)], 1u);
     }
     __syncthreads();
     for (int b = threadIdx.x; b < bins; b += kHistBlock) {
@@ -623,12 +635,12 @@ __global__ __launch_bounds__(kBlock) void k_chunk_counts(const float *__restrict
                                                          unsigned *__restrict__ chunk_counts, int N,
                                                          int nchunks)
 {
-    __shared__ unsigned tmp[kBlock + 2];
-    const int d0 = (int)state[4], d1 = (int)state[5];
+    __shared__ unsigned tmp[kBlock + 3];
+    const int d0 = (int)state[4], d1 = (int)state[5], mid = (int)state[2];
     int d2;
     unsigned kk;
-    pick_digit(hist_all + kHist2, kLastBins, state[7], tmp, &d2, &kk);
-    const unsigned thr = ((unsigned)d0 << kRestBits) | ((unsigned)d1 << (kRestBits - kMidBits)) | (unsigned)d2;
+    pick_digit(hist_all + kHist2, 1 << (kRestBits - mid), state[7], tmp, &d2, &kk);
+    const unsigned thr = ((unsigned)d0 << kRestBits) | ((unsigned)d1 << (kRestBits - mid)) | (unsigned)d2;
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         state[0] = thr;
         state[1] = kk;  // how many keys equal to thr are selected (lowest ids first)
@@ -675,7 +687,7 @@ __global__ __launch_bounds__(kBlock) void k_compact_write(const float *__restric
                                                           int32_t *__restrict__ out_idx, int N,
                                                           int nchunks)
 {
-    __shared__ unsigned tmp[kBlock + 2];
+    __shared__ unsigned tmp[kBlock + 3];
     const unsigned thr = state[0], need_eq = state[1];
     // counts of all earlier chunks: [0, done) is already in (pg, pe), a block that takes several
     // chunks only adds the ones in between
